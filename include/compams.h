@@ -1,0 +1,163 @@
+/* compams.h -- C ABI of the COMP-AMS optimizer step for MI355X (gfx950).
+ *
+ * One call of compams_step() is one iteration of the paper's Algorithm 2
+ * ("Distributed COMP-AMS with error feedback"): every one of n workers adds its
+ * error accumulator to its gradient, compresses the sum, keeps what the
+ * compressor dropped as the new error, and the server averages the n compressed
+ * gradients and applies an AMSGrad update (Algorithm 1's moment and parameter
+ * lines).  The n workers are the rows of an n x ld fp32 buffer in one GPU's
+ * memory; nothing is sent anywhere.
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers marked DEVICE are HIP device pointers on the device that was
+ *     current when compams_init() ran; pointers marked HOST are ordinary host
+ *     memory.  The library never allocates or frees device memory: all device
+ *     buffers, the workspace included, belong to the caller and are borrowed
+ *     until compams_destroy().
+ *   - Every function returns COMPAMS_OK (0) or a negative compams_status; it
+ *     never throws, aborts or prints.  Out-parameters are untouched on error.
+ *   - compams_step() only enqueues work on the given stream; it does not
+ *     synchronise with the host and takes no data-dependent decision on the
+ *     host.  One context may be driven by one host thread at a time.
+ */
+#ifndef COMPAMS_H
+#define COMPAMS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct compams_ctx compams_ctx; /* opaque; host memory owned by the library */
+
+/* The compressor C of Assumption 1. */
+enum {
+  COMPAMS_NONE = 0,     /* C(x) = x (q = 0): full-precision distributed AMSGrad; e is neither read nor written */
+  COMPAMS_TOPK = 1,     /* Definition 1: keep the k coordinates of largest magnitude per worker */
+  COMPAMS_BLOCKSIGN = 2 /* Definition 2: per block, sign(x) times the block's mean absolute value */
+};
+
+/* Where epsilon sits in the parameter line of Algorithms 1 and 2. */
+enum {
+  COMPAMS_EPS_IN_SQRT = 0, /* theta -= lr * m / sqrt(vhat + eps)   (as printed in the paper) */
+  COMPAMS_EPS_OUT_SQRT = 1 /* theta -= lr * m / (sqrt(vhat) + eps) */
+};
+
+enum {
+  COMPAMS_KEEP_STATE = 1 /* compams_init() leaves e, m, v, vhat as the caller filled them (resume) */
+};
+
+enum {
+  COMPAMS_OK = 0,
+  COMPAMS_INVALID_ARG = -1,         /* null pointer, size out of range, bad enum, offsets not ascending */
+  COMPAMS_BAD_ALIGNMENT = -2,       /* a device pointer is not 16-byte aligned, or ld is not a multiple of 4 */
+  COMPAMS_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < compams_workspace_size() */
+  COMPAMS_HIP_ERROR = -4,           /* a HIP runtime call failed */
+  COMPAMS_BAD_STATE = -5            /* query does not apply to this context's compressor */
+};
+
+typedef struct compams_config {
+  int32_t n;          /* number of workers (rows), >= 1 */
+  int64_t d;          /* coordinates per worker, 1 <= d < 2^31 */
+  int64_t ld;         /* row stride of g and e in elements: ld >= d and ld % 4 == 0 */
+  int32_t compressor; /* COMPAMS_NONE / COMPAMS_TOPK / COMPAMS_BLOCKSIGN */
+  int64_t k;          /* top-k: 1 <= k <= d, per worker over the whole flattened row; else ignored */
+  int64_t num_blocks; /* block-sign: number of blocks M >= 1; else ignored */
+  const int64_t* block_offsets; /* HOST, block-sign: M+1 strictly ascending offsets, [0] = 0, [M] = d; copied */
+  float beta1, beta2, eps;      /* the paper's defaults are 0.9, 0.999, 1e-8 (Section 5.1) */
+  int32_t eps_mode;             /* COMPAMS_EPS_* */
+  int32_t flags;                /* bit set of COMPAMS_KEEP_STATE */
+  /* DEVICE buffers, 16-byte aligned, borrowed for the life of the context */
+  float* theta; /* d: the parameter, theta_1 on entry to the first step */
+  float* m;     /* d: first moment  */
+  float* v;     /* d: second moment */
+  float* vhat;  /* d: running maximum of v */
+  float* e;     /* n * ld: error accumulators, row i = worker i; columns >= d are never touched */
+  void* workspace;        /* DEVICE scratch of at least compams_workspace_size() bytes, 256-byte aligned */
+  size_t workspace_bytes;
+} compams_config;
+
+/* Bytes of device workspace this configuration needs (0 on an invalid configuration).
+ * Host-only; reads n, d, compressor, k, num_blocks. */
+size_t compams_workspace_size(const compams_config* cfg);
+
+/* Validates cfg, copies it, lays out the workspace, uploads the block offsets and, unless
+ * COMPAMS_KEEP_STATE is set, zeroes e, m, v and vhat (the initialisation line of Algorithm 2).
+ * Blocks until that set-up work has finished.  *out receives the context. */
+int compams_init(const compams_config* cfg, compams_ctx** out);
+
+/* One iteration of Algorithm 2 with learning rate lr (eta_t).
+ *   g: DEVICE, n * ld floats, row i = worker i's stochastic gradient; read-only; may be reused by the
+ *      caller once the stream has passed the step.
+ *   hip_stream: a hipStream_t (NULL = the default stream).  All kernels of the step are enqueued there.
+ * Top-k ties are broken towards the larger |x| and then the lower index, with |x| ordered by the fp32
+ * bit pattern without its sign bit; the selected indices come out ascending per worker.  Block-sign
+ * uses sign(x) = -1 iff x < 0 and the exactly summed block L1 norm.  The average adds the workers'
+ * compressed gradients in the order 0..n-1 in fp32 and divides by n. */
+int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream);
+
+/* What compams_state() can hand out.  Counts are in elements of the listed type. */
+enum {
+  COMPAMS_STATE_THETA = 0,          /* float[d] */
+  COMPAMS_STATE_M = 1,              /* float[d] */
+  COMPAMS_STATE_V = 2,              /* float[d] */
+  COMPAMS_STATE_VHAT = 3,           /* float[d] */
+  COMPAMS_STATE_E = 4,              /* float[n*ld] */
+  COMPAMS_STATE_LAST_IDX = 5,       /* top-k: int32[n*k], worker i's selected coordinates, ascending */
+  COMPAMS_STATE_LAST_VAL = 6,       /* top-k: float[n*k], the corrected gradient at those coordinates */
+  COMPAMS_STATE_LAST_SIGNBITS = 7,  /* block-sign: uint32[n*ceil(d/32)], bit (j&31) of word j>>5 = (x_j < 0) */
+  COMPAMS_STATE_LAST_SCALES = 8,    /* block-sign: float[n*M], the block means of |x| */
+  COMPAMS_STATE_LAST_THRESHOLD = 9, /* top-k: uint32[n], magnitude key of the k-th largest entry */
+  COMPAMS_STATE_COUNTERS = 10       /* uint32[n*COMPAMS_COUNTERS_PER_ROW], see below */
+};
+
+/* Per-worker counters of the last step (top-k), for tests and profiling reports. */
+enum {
+  COMPAMS_CNT_DENSE_READS = 0, /* how many times the step read the whole row of corrected gradients back
+                                  (0: candidates came out of the first pass; 1: one re-read; 4: no candidate list) */
+  COMPAMS_CNT_CANDIDATES = 1,  /* entries in the candidate list, 0 if none was used */
+  COMPAMS_CNT_TIES = 2,        /* coordinates whose key equals the threshold key */
+  COMPAMS_CNT_TIES_TAKEN = 3,  /* how many of those were selected */
+  COMPAMS_COUNTERS_PER_ROW = 4
+};
+
+/* Borrowed DEVICE pointer to a state tensor or to what the workers "sent" in the last step, valid until
+ * the next compams_step() on the context changes it.  Reading it is the caller's business (ordered after
+ * the step on the step's stream). */
+int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* count);
+
+/* Knobs of the top-k selection.  None of them changes any result; they decide which route the
+ * selection takes and exist for tests of the rarely taken routes and for ablation measurements. */
+enum {
+  COMPAMS_OPT_CANDIDATE_CAP = 0, /* candidate-list capacity per worker, 0 .. the capacity the workspace was sized
+                                    for (min(d, 8k + 65536)); a list that would not fit is not built */
+  COMPAMS_OPT_PREDICT = 1,       /* 1 (default): the first pass of a step already writes the candidate list, using
+                                    the previous step's threshold bucket as a guess that is verified afterwards */
+  COMPAMS_OPT_FORCE_DENSE = 2    /* 1: never build a candidate list; every selection pass reads the whole row */
+};
+int compams_set_option(compams_ctx* ctx, int option, int64_t value);
+
+/* Optional per-kernel timing.  While enabled, compams_step() brackets each kernel with HIP events on the
+ * step's stream.  compams_profile_read() waits for the recorded events, then fills names[i] (static
+ * strings) and ms[i] (total milliseconds since the last reset) and launches[i] for up to cap kernels,
+ * returns how many kernels there are through *count, and resets the totals. */
+int compams_profile_enable(compams_ctx* ctx, int enable);
+int compams_profile_read(compams_ctx* ctx, int cap, const char** names, double* ms, int64_t* launches, int* count);
+
+/* Frees the context (host memory and HIP events only; device buffers stay the caller's). */
+int compams_destroy(compams_ctx* ctx);
+
+/* Static description of a status code. */
+const char* compams_strerror(int status);
+
+/* A plain streaming copy of `bytes` bytes (multiple of 16, both pointers DEVICE and 16-byte aligned) with
+ * the same launch style as the step's dense kernels: the measured bandwidth ceiling that reports set
+ * beside the step's figures, and the known-size kernel that hardware counters are calibrated against. */
+int compams_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMPAMS_H */

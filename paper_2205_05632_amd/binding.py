@@ -1,0 +1,229 @@
+"""Python binding of libcompams: argument marshalling only.
+
+Same names as the C ABI (include/compams.h).  PyTorch provides device memory and the current
+stream; every step of the optimizer runs in the library's HIP kernels.  There is no fallback: if
+the shared library has not been built, importing the functions raises.
+"""
+import ctypes
+import os
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcompams.so")
+
+NONE, TOPK, BLOCKSIGN = 0, 1, 2
+EPS_IN_SQRT, EPS_OUT_SQRT = 0, 1
+KEEP_STATE = 1
+OPT_CANDIDATE_CAP, OPT_PREDICT, OPT_FORCE_DENSE = 0, 1, 2
+COUNTERS_PER_ROW = 4
+
+STATE = {"theta": 0, "m": 1, "v": 2, "vhat": 3, "e": 4, "last_idx": 5, "last_val": 6, "last_signbits": 7,
+         "last_scales": 8, "last_threshold": 9, "counters": 10}
+_STATE_DTYPE = {"last_idx": torch.int32, "last_signbits": torch.int32, "last_threshold": torch.int32,
+                "counters": torch.int32}
+
+EXPORTS = ["compams_workspace_size", "compams_init", "compams_step", "compams_state", "compams_set_option",
+           "compams_profile_enable", "compams_profile_read", "compams_destroy", "compams_strerror", "compams_copy"]
+
+
+class compams_config(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int32), ("d", ctypes.c_int64), ("ld", ctypes.c_int64),
+                ("compressor", ctypes.c_int32), ("k", ctypes.c_int64), ("num_blocks", ctypes.c_int64),
+                ("block_offsets", ctypes.POINTER(ctypes.c_int64)),
+                ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("eps_mode", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("theta", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("vhat", ctypes.c_void_p), ("e", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+class CompamsError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise CompamsError(f"{LIB_PATH} is missing: build it with `python -m paper_2205_05632_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        cfgp = ctypes.POINTER(compams_config)
+        L.compams_workspace_size.restype = ctypes.c_size_t
+        L.compams_workspace_size.argtypes = [cfgp]
+        L.compams_init.argtypes = [cfgp, ctypes.POINTER(ctypes.c_void_p)]
+        L.compams_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p]
+        L.compams_state.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_void_p),
+                                    ctypes.POINTER(ctypes.c_int64)]
+        L.compams_set_option.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64]
+        L.compams_profile_enable.argtypes = [ctypes.c_void_p, ctypes.c_int]
+        L.compams_profile_read.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_char_p),
+                                           ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64),
+                                           ctypes.POINTER(ctypes.c_int)]
+        L.compams_destroy.argtypes = [ctypes.c_void_p]
+        L.compams_strerror.restype = ctypes.c_char_p
+        L.compams_strerror.argtypes = [ctypes.c_int]
+        L.compams_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise CompamsError(f"{what}: {lib().compams_strerror(status).decode()} ({status})")
+
+
+def compams_strerror(status: int) -> str:
+    return lib().compams_strerror(status).decode()
+
+
+def _current_stream_handle() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def padded_ld(d: int) -> int:
+    """Smallest legal row stride: d rounded up to a multiple of 4 elements (16-byte aligned rows)."""
+    return (int(d) + 3) // 4 * 4
+
+
+class Compams:
+    """One optimizer context: owns the torch tensors that the library borrows.
+
+    compams_init / compams_step / compams_state map one-to-one onto the C entry points.
+    """
+
+    def __init__(self, n: int, d: int, theta0: torch.Tensor, compressor: int = TOPK, k: int = 0,
+                 block_offsets=None, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                 eps_mode: int = EPS_IN_SQRT, ld: Optional[int] = None, device="cuda:0",
+                 state: Optional[Dict[str, torch.Tensor]] = None):
+        self.n, self.d, self.k, self.compressor = int(n), int(d), int(k), int(compressor)
+        self.ld = padded_ld(d) if ld is None else int(ld)
+        self.device = torch.device(device)
+        dev = self.device
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.theta = theta0.detach().to(**f32).clone().contiguous()
+        assert self.theta.numel() == self.d
+        self.m = torch.empty(self.d, **f32)
+        self.v = torch.empty(self.d, **f32)
+        self.vhat = torch.empty(self.d, **f32)
+        self.e = torch.zeros((self.n, self.ld), **f32) if compressor != NONE else None
+        flags = 0
+        if state is not None:
+            flags |= KEEP_STATE
+            self.m.copy_(state["m"]); self.v.copy_(state["v"]); self.vhat.copy_(state["vhat"])
+            if self.e is not None:
+                self.e.zero_()
+                self.e[:, : self.d].copy_(state["e"])
+        cfg = compams_config()
+        cfg.n, cfg.d, cfg.ld, cfg.compressor, cfg.k = self.n, self.d, self.ld, compressor, self.k
+        self._off = None
+        self.M = 0
+        if block_offsets is not None:
+            self._off = np.ascontiguousarray(block_offsets, dtype=np.int64)
+            self.M = self._off.size - 1
+            cfg.block_offsets = self._off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+        cfg.num_blocks = self.M
+        cfg.beta1, cfg.beta2, cfg.eps, cfg.eps_mode, cfg.flags = beta1, beta2, eps, eps_mode, flags
+        cfg.theta, cfg.m, cfg.v, cfg.vhat = (self.theta.data_ptr(), self.m.data_ptr(), self.v.data_ptr(),
+                                             self.vhat.data_ptr())
+        cfg.e = self.e.data_ptr() if self.e is not None else None
+        L = lib()
+        with torch.cuda.device(dev):
+            nbytes = L.compams_workspace_size(ctypes.byref(cfg))
+            if nbytes == 0:
+                raise CompamsError("compams_workspace_size: invalid configuration")
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            cfg.workspace, cfg.workspace_bytes = self.workspace.data_ptr(), nbytes
+            torch.cuda.synchronize(dev)
+            h = ctypes.c_void_p()
+            _check(L.compams_init(ctypes.byref(cfg), ctypes.byref(h)), "compams_init")
+        self._h = h
+        self._cfg = cfg
+
+    # -- the three calls of the boundary ---------------------------------------------------------
+    def compams_step(self, g: torch.Tensor, lr: float):
+        """g: n x ld fp32 tensor on the context's device (columns >= d ignored)."""
+        assert g.dtype == torch.float32 and g.is_cuda and g.is_contiguous()
+        assert g.shape == (self.n, self.ld), f"g must be {self.n} x {self.ld}, got {tuple(g.shape)}"
+        with torch.cuda.device(self.device):
+            _check(lib().compams_step(self._h, g.data_ptr(), lr, _current_stream_handle()), "compams_step")
+
+    def compams_state(self, name: str) -> torch.Tensor:
+        """A torch view (no copy) of a state tensor or of the last step's messages."""
+        p = ctypes.c_void_p()
+        cnt = ctypes.c_int64()
+        _check(lib().compams_state(self._h, STATE[name], ctypes.byref(p), ctypes.byref(cnt)), "compams_state")
+        dt = _STATE_DTYPE.get(name, torch.float32)
+        t = _tensor_from_ptr(p.value, cnt.value, dt, self.device, keepalive=self)
+        if name == "e":
+            return t.view(self.n, self.ld)[:, : self.d]
+        if name in ("last_idx", "last_val"):
+            return t.view(self.n, self.k)
+        if name in ("last_signbits",):
+            return t.view(self.n, -1)
+        if name == "last_scales":
+            return t.view(self.n, self.M)
+        if name == "counters":
+            return t.view(self.n, COUNTERS_PER_ROW)
+        return t
+
+    # -- extras ----------------------------------------------------------------------------------
+    def set_option(self, option: int, value: int):
+        _check(lib().compams_set_option(self._h, option, value), "compams_set_option")
+
+    def profile_enable(self, on: bool):
+        _check(lib().compams_profile_enable(self._h, 1 if on else 0), "compams_profile_enable")
+
+    def profile_read(self):
+        cap = 32
+        names = (ctypes.c_char_p * cap)()
+        ms = (ctypes.c_double * cap)()
+        launches = (ctypes.c_int64 * cap)()
+        cnt = ctypes.c_int()
+        _check(lib().compams_profile_read(self._h, cap, names, ms, launches, ctypes.byref(cnt)),
+               "compams_profile_read")
+        return {names[i].decode(): (ms[i], launches[i]) for i in range(min(cnt.value, cap))}
+
+    def close(self):
+        if getattr(self, "_h", None):
+            torch.cuda.synchronize(self.device)
+            lib().compams_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _tensor_from_ptr(ptr: int, count: int, dtype: torch.dtype, device, keepalive=None) -> torch.Tensor:
+    """Wrap borrowed device memory as a torch tensor through the CUDA array interface."""
+    itemsize = torch.empty(0, dtype=dtype).element_size()
+    typestr = {torch.float32: "<f4", torch.int32: "<i4", torch.uint8: "|u1"}[dtype]
+
+    class _Holder:
+        pass
+
+    hld = _Holder()
+    hld.__cuda_array_interface__ = {"shape": (int(count),), "typestr": typestr, "data": (int(ptr), False),
+                                    "version": 2, "strides": None}
+    hld._keepalive = keepalive
+    if count == 0:
+        return torch.empty(0, dtype=dtype, device=device)
+    t = torch.as_tensor(hld, device=device)
+    assert t.element_size() == itemsize
+    return t
+
+
+def compams_copy(dst: torch.Tensor, src: torch.Tensor):
+    """The library's plain streaming copy kernel (bandwidth ceiling / counter calibration)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().compams_copy(dst.data_ptr(), src.data_ptr(), nbytes, _current_stream_handle()), "compams_copy")

@@ -1,0 +1,393 @@
+// Host side of libcompams: the C ABI declared in include/compams.h.
+// Validates arguments, lays out the caller's workspace, and enqueues the kernels of one step.
+
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/compams.h"
+#include "compams_internal.h"
+
+namespace compams {
+
+struct Launcher {
+  struct Pair { hipEvent_t a, b; };
+  std::vector<Pair> pending[kNumSlots];
+  std::vector<Pair> pool;
+  double total_ms[kNumSlots];
+  int64_t launches[kNumSlots];
+  bool failed;
+  Launcher() : failed(false) {
+    for (int i = 0; i < kNumSlots; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+  }
+};
+
+void launcher_begin(Launcher* L, int slot, hipStream_t stream) {
+  Launcher::Pair p;
+  if (!L->pool.empty()) {
+    p = L->pool.back();
+    L->pool.pop_back();
+  } else if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) {
+    L->failed = true;
+    return;
+  }
+  if (hipEventRecord(p.a, stream) != hipSuccess) L->failed = true;
+  L->pending[slot].push_back(p);
+}
+
+void launcher_end(Launcher* L, int slot, hipStream_t stream) {
+  if (L->pending[slot].empty()) return;
+  if (hipEventRecord(L->pending[slot].back().b, stream) != hipSuccess) L->failed = true;
+}
+
+namespace {
+
+const char* const kSlotNames[kNumSlots] = {
+    "topk_pass_a", "topk_resolve0", "topk_pass_b", "topk_hist1", "topk_resolve1", "topk_hist2", "topk_resolve2",
+    "topk_count", "topk_scan", "topk_emit", "topk_amsgrad",
+    "bs_pass1", "bs_finalize", "bs_pass2", "bs_amsgrad", "none_amsgrad"};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Layout {
+  size_t total;
+  // top-k
+  size_t rows, counters, hist0, hist1, hist2, cnt_gt, cnt_eq, sel_off, eq_before, desc, cand, idx, val, tau;
+  // block-sign
+  size_t offsets, chunk_block, acc, special, scales, bits;
+  uint32_t cap_alloc, num_chunks, words;
+};
+
+bool basic_valid(const compams_config* c) {
+  if (!c) return false;
+  if (c->n < 1 || c->d < 1 || c->d >= (int64_t(1) << 31)) return false;
+  if (c->compressor != COMPAMS_NONE && c->compressor != COMPAMS_TOPK && c->compressor != COMPAMS_BLOCKSIGN)
+    return false;
+  if (c->compressor == COMPAMS_TOPK && (c->k < 1 || c->k > c->d)) return false;
+  if (c->compressor == COMPAMS_BLOCKSIGN && (c->num_blocks < 1 || c->num_blocks > c->d)) return false;
+  return true;
+}
+
+Layout make_layout(const compams_config* c) {
+  Layout L;
+  std::memset(&L, 0, sizeof L);
+  const size_t n = static_cast<size_t>(c->n), d = static_cast<size_t>(c->d);
+  L.num_chunks = static_cast<uint32_t>((d + kChunk - 1) / kChunk);
+  L.words = static_cast<uint32_t>((d + 31) / 32);
+  const size_t nc = L.num_chunks;
+  size_t at = 0;
+  auto take = [&](size_t bytes) { const size_t o = at; at = align_up(at + bytes, 256); return o; };
+  if (c->compressor == COMPAMS_TOPK) {
+    const size_t k = static_cast<size_t>(c->k);
+    size_t cap = 8 * k + 65536;
+    if (cap > d) cap = d;
+    L.cap_alloc = static_cast<uint32_t>(cap);
+    L.rows = take(n * sizeof(TopkRow));
+    L.counters = take(n * COMPAMS_COUNTERS_PER_ROW * 4);
+    L.hist0 = take(n * kNB0 * 4);
+    L.hist1 = take(n * kNB1 * 4);
+    L.hist2 = take(n * kNB2 * 4);
+    L.cnt_gt = take(n * nc * 4);
+    L.cnt_eq = take(n * nc * 4);
+    L.sel_off = take(n * (nc + 1) * 4);
+    L.eq_before = take(n * nc * 4);
+    L.desc = take(n * nc * 8);
+    L.cand = take(n * cap * 8);
+    L.idx = take(n * k * 4);
+    L.val = take(n * k * 4);
+    L.tau = take(n * 4);
+  } else if (c->compressor == COMPAMS_BLOCKSIGN) {
+    const size_t M = static_cast<size_t>(c->num_blocks);
+    L.offsets = take((M + 1) * 4);
+    L.chunk_block = take(nc * 4);
+    L.acc = take(n * M * kLimbs * 8);
+    L.special = take(n * M * 4);
+    L.scales = take(n * M * 4);
+    L.bits = take(n * static_cast<size_t>(L.words) * 4);
+  }
+  L.total = at ? at : 256;
+  return L;
+}
+
+}  // namespace
+}  // namespace compams
+
+using namespace compams;
+
+struct compams_ctx {
+  compams_config cfg;
+  Layout lay;
+  Geometry geo;
+  TopkWorkspace tk;
+  TopkOptions tkopt;
+  BlocksignWorkspace bs;
+  int device;
+  int64_t steps;
+  bool profiling;
+  Launcher launcher;
+};
+
+extern "C" {
+
+size_t compams_workspace_size(const compams_config* cfg) {
+  if (!basic_valid(cfg)) return 0;
+  return make_layout(cfg).total;
+}
+
+int compams_init(const compams_config* cfg, compams_ctx** out) {
+  if (!out || !basic_valid(cfg)) return COMPAMS_INVALID_ARG;
+  if (cfg->ld < cfg->d) return COMPAMS_INVALID_ARG;
+  if (cfg->ld % 4 != 0) return COMPAMS_BAD_ALIGNMENT;
+  if (cfg->eps_mode != COMPAMS_EPS_IN_SQRT && cfg->eps_mode != COMPAMS_EPS_OUT_SQRT) return COMPAMS_INVALID_ARG;
+  if (!cfg->theta || !cfg->m || !cfg->v || !cfg->vhat) return COMPAMS_INVALID_ARG;
+  if (cfg->compressor != COMPAMS_NONE && !cfg->e) return COMPAMS_INVALID_ARG;
+  if (!cfg->workspace) return COMPAMS_INVALID_ARG;
+  auto misaligned = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; };
+  if (misaligned(cfg->theta, 16) || misaligned(cfg->m, 16) || misaligned(cfg->v, 16) || misaligned(cfg->vhat, 16) ||
+      (cfg->e && misaligned(cfg->e, 16)) || misaligned(cfg->workspace, 256))
+    return COMPAMS_BAD_ALIGNMENT;
+  if (cfg->compressor == COMPAMS_BLOCKSIGN) {
+    const int64_t* o = cfg->block_offsets;
+    if (!o || o[0] != 0 || o[cfg->num_blocks] != cfg->d) return COMPAMS_INVALID_ARG;
+    for (int64_t b = 0; b < cfg->num_blocks; ++b)
+      if (o[b + 1] <= o[b]) return COMPAMS_INVALID_ARG;
+  }
+  const Layout lay = make_layout(cfg);
+  if (cfg->workspace_bytes < lay.total) return COMPAMS_WORKSPACE_TOO_SMALL;
+
+  compams_ctx* ctx = new (std::nothrow) compams_ctx();
+  if (!ctx) return COMPAMS_HIP_ERROR;
+  ctx->cfg = *cfg;
+  ctx->cfg.block_offsets = nullptr;  // the host array is the caller's; a device copy is made below
+  ctx->lay = lay;
+  ctx->steps = 0;
+  ctx->profiling = false;
+  if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return COMPAMS_HIP_ERROR; }
+  Geometry& geo = ctx->geo;
+  geo.n = static_cast<uint32_t>(cfg->n);
+  geo.d = static_cast<uint32_t>(cfg->d);
+  geo.ld = cfg->ld;
+  geo.num_chunks = lay.num_chunks;
+  geo.k = cfg->compressor == COMPAMS_TOPK ? static_cast<uint32_t>(cfg->k) : 0;
+  geo.num_blocks = cfg->compressor == COMPAMS_BLOCKSIGN ? static_cast<uint32_t>(cfg->num_blocks) : 0;
+  geo.words = lay.words;
+  char* w = static_cast<char*>(cfg->workspace);
+  hipStream_t s0 = nullptr;
+  hipError_t err = hipSuccess;
+  auto ok = [&](hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; };
+
+  if (cfg->compressor == COMPAMS_TOPK) {
+    TopkWorkspace& t = ctx->tk;
+    t.rows = reinterpret_cast<TopkRow*>(w + lay.rows);
+    t.counters = reinterpret_cast<uint32_t*>(w + lay.counters);
+    t.hist0 = reinterpret_cast<uint32_t*>(w + lay.hist0);
+    t.hist1 = reinterpret_cast<uint32_t*>(w + lay.hist1);
+    t.hist2 = reinterpret_cast<uint32_t*>(w + lay.hist2);
+    t.cnt_gt = reinterpret_cast<uint32_t*>(w + lay.cnt_gt);
+    t.cnt_eq = reinterpret_cast<uint32_t*>(w + lay.cnt_eq);
+    t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);
+    t.eq_before = reinterpret_cast<uint32_t*>(w + lay.eq_before);
+    t.desc = reinterpret_cast<uint2*>(w + lay.desc);
+    t.cand = reinterpret_cast<uint2*>(w + lay.cand);
+    t.idx = reinterpret_cast<int32_t*>(w + lay.idx);
+    t.val = reinterpret_cast<float*>(w + lay.val);
+    t.tau = reinterpret_cast<uint32_t*>(w + lay.tau);
+    ctx->tkopt.cap = lay.cap_alloc;
+    ctx->tkopt.predict = 1;
+    ctx->tkopt.force_dense = 0;
+    ctx->tkopt.first_pass_emits = 0;
+    // control blocks, counters, histograms and chunk tables start at zero; lists need no initial value
+    ok(fill_u32(reinterpret_cast<uint32_t*>(w), lay.cand / 4, 0u, s0));
+    ok(fill_u32(reinterpret_cast<uint32_t*>(w + lay.idx), (lay.total - lay.idx) / 4, 0u, s0));
+  } else if (cfg->compressor == COMPAMS_BLOCKSIGN) {
+    BlocksignWorkspace& b = ctx->bs;
+    b.offsets = reinterpret_cast<uint32_t*>(w + lay.offsets);
+    b.chunk_block = reinterpret_cast<uint32_t*>(w + lay.chunk_block);
+    b.acc = reinterpret_cast<uint64_t*>(w + lay.acc);
+    b.special = reinterpret_cast<uint32_t*>(w + lay.special);
+    b.scales = reinterpret_cast<float*>(w + lay.scales);
+    b.bits = reinterpret_cast<uint32_t*>(w + lay.bits);
+    std::vector<uint32_t> off32, cb;
+    try {
+      off32.resize(static_cast<size_t>(cfg->num_blocks) + 1);
+      cb.resize(lay.num_chunks);
+    } catch (...) { delete ctx; return COMPAMS_HIP_ERROR; }
+    for (int64_t i = 0; i <= cfg->num_blocks; ++i) off32[static_cast<size_t>(i)] = static_cast<uint32_t>(cfg->block_offsets[i]);
+    uint32_t blk = 0;
+    for (uint32_t c = 0; c < lay.num_chunks; ++c) {
+      const uint32_t j = c * static_cast<uint32_t>(kChunk);
+      while (off32[blk + 1] <= j) ++blk;
+      cb[c] = blk;
+    }
+    ok(fill_u32(reinterpret_cast<uint32_t*>(w), lay.total / 4, 0u, s0));
+    ok(hipStreamSynchronize(s0));
+    ok(hipMemcpy(b.offsets, off32.data(), off32.size() * 4, hipMemcpyHostToDevice));
+    ok(hipMemcpy(b.chunk_block, cb.data(), cb.size() * 4, hipMemcpyHostToDevice));
+  }
+  if (!(cfg->flags & COMPAMS_KEEP_STATE)) {
+    if (cfg->e) ok(fill_rows_f32(cfg->e, geo.n, geo.ld, geo.d, 0.0f, s0));
+    ok(fill_rows_f32(cfg->m, 1, 0, geo.d, 0.0f, s0));
+    ok(fill_rows_f32(cfg->v, 1, 0, geo.d, 0.0f, s0));
+    ok(fill_rows_f32(cfg->vhat, 1, 0, geo.d, 0.0f, s0));
+  }
+  ok(hipStreamSynchronize(s0));
+  if (err != hipSuccess) { delete ctx; return COMPAMS_HIP_ERROR; }
+  *out = ctx;
+  return COMPAMS_OK;
+}
+
+int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream) {
+  if (!ctx || !g) return COMPAMS_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(g) % 16 != 0) return COMPAMS_BAD_ALIGNMENT;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const compams_config& c = ctx->cfg;
+  AmsParams ap;
+  ap.beta1 = c.beta1;
+  ap.beta2 = c.beta2;
+  ap.one_minus_beta1 = 1.0f - c.beta1;
+  ap.one_minus_beta2 = 1.0f - c.beta2;
+  ap.eps = c.eps;
+  ap.lr = lr;
+  ap.nf = static_cast<float>(c.n);
+  ap.eps_out = c.eps_mode == COMPAMS_EPS_OUT_SQRT;
+  Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
+  hipError_t err;
+  try {
+    if (c.compressor == COMPAMS_TOPK) {
+      const bool may_predict = ctx->steps > 0 && ctx->tkopt.predict && !ctx->tkopt.force_dense;
+      err = topk_step(ctx->geo, ctx->tk, ctx->tkopt, ap, g, c.e, c.theta, c.m, c.v, c.vhat, may_predict, stream, L);
+    } else if (c.compressor == COMPAMS_BLOCKSIGN) {
+      err = blocksign_step(ctx->geo, ctx->bs, ap, g, c.e, c.theta, c.m, c.v, c.vhat, stream, L);
+    } else {
+      err = none_step(ctx->geo, ap, g, c.theta, c.m, c.v, c.vhat, stream, L);
+    }
+  } catch (...) {
+    return COMPAMS_HIP_ERROR;
+  }
+  if (err != hipSuccess || (L && L->failed)) return COMPAMS_HIP_ERROR;
+  ++ctx->steps;
+  return COMPAMS_OK;
+}
+
+int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* count) {
+  if (!ctx || !dev_ptr || !count) return COMPAMS_INVALID_ARG;
+  const compams_config& c = ctx->cfg;
+  const int64_t n = c.n, d = c.d;
+  const void* p = nullptr;
+  int64_t cnt = 0;
+  const bool tk = c.compressor == COMPAMS_TOPK, bs = c.compressor == COMPAMS_BLOCKSIGN;
+  switch (which) {
+    case COMPAMS_STATE_THETA: p = c.theta; cnt = d; break;
+    case COMPAMS_STATE_M: p = c.m; cnt = d; break;
+    case COMPAMS_STATE_V: p = c.v; cnt = d; break;
+    case COMPAMS_STATE_VHAT: p = c.vhat; cnt = d; break;
+    case COMPAMS_STATE_E:
+      if (!c.e) return COMPAMS_BAD_STATE;
+      p = c.e; cnt = n * c.ld; break;
+    case COMPAMS_STATE_LAST_IDX:
+      if (!tk) return COMPAMS_BAD_STATE;
+      p = ctx->tk.idx; cnt = n * c.k; break;
+    case COMPAMS_STATE_LAST_VAL:
+      if (!tk) return COMPAMS_BAD_STATE;
+      p = ctx->tk.val; cnt = n * c.k; break;
+    case COMPAMS_STATE_LAST_THRESHOLD:
+      if (!tk) return COMPAMS_BAD_STATE;
+      p = ctx->tk.tau; cnt = n; break;
+    case COMPAMS_STATE_COUNTERS:
+      if (!tk) return COMPAMS_BAD_STATE;
+      p = ctx->tk.counters; cnt = n * COMPAMS_COUNTERS_PER_ROW; break;
+    case COMPAMS_STATE_LAST_SIGNBITS:
+      if (!bs) return COMPAMS_BAD_STATE;
+      p = ctx->bs.bits; cnt = n * static_cast<int64_t>(ctx->geo.words); break;
+    case COMPAMS_STATE_LAST_SCALES:
+      if (!bs) return COMPAMS_BAD_STATE;
+      p = ctx->bs.scales; cnt = n * c.num_blocks; break;
+    default: return COMPAMS_INVALID_ARG;
+  }
+  *dev_ptr = p;
+  *count = cnt;
+  return COMPAMS_OK;
+}
+
+int compams_set_option(compams_ctx* ctx, int option, int64_t value) {
+  if (!ctx) return COMPAMS_INVALID_ARG;
+  if (ctx->cfg.compressor != COMPAMS_TOPK) return COMPAMS_BAD_STATE;
+  switch (option) {
+    case COMPAMS_OPT_CANDIDATE_CAP:
+      if (value < 0 || value > static_cast<int64_t>(ctx->lay.cap_alloc)) return COMPAMS_INVALID_ARG;
+      ctx->tkopt.cap = static_cast<uint32_t>(value);
+      return COMPAMS_OK;
+    case COMPAMS_OPT_PREDICT:
+      ctx->tkopt.predict = value ? 1u : 0u;
+      return COMPAMS_OK;
+    case COMPAMS_OPT_FORCE_DENSE:
+      ctx->tkopt.force_dense = value ? 1u : 0u;
+      return COMPAMS_OK;
+    default: return COMPAMS_INVALID_ARG;
+  }
+}
+
+int compams_profile_enable(compams_ctx* ctx, int enable) {
+  if (!ctx) return COMPAMS_INVALID_ARG;
+  ctx->profiling = enable != 0;
+  return COMPAMS_OK;
+}
+
+int compams_profile_read(compams_ctx* ctx, int cap, const char** names, double* ms, int64_t* launches, int* count) {
+  if (!ctx || !count || cap < 0 || (cap > 0 && (!names || !ms || !launches))) return COMPAMS_INVALID_ARG;
+  Launcher& L = ctx->launcher;
+  bool bad = false;
+  for (int s = 0; s < kNumSlots; ++s) {
+    for (const Launcher::Pair& p : L.pending[s]) {
+      float t = 0.0f;
+      if (hipEventSynchronize(p.b) != hipSuccess || hipEventElapsedTime(&t, p.a, p.b) != hipSuccess) bad = true;
+      else { L.total_ms[s] += t; ++L.launches[s]; }
+      try { L.pool.push_back(p); } catch (...) { bad = true; }
+    }
+    L.pending[s].clear();
+  }
+  int outn = 0;
+  for (int s = 0; s < kNumSlots; ++s) {
+    if (L.launches[s] == 0) continue;
+    if (outn < cap) { names[outn] = kSlotNames[s]; ms[outn] = L.total_ms[s]; launches[outn] = L.launches[s]; }
+    ++outn;
+  }
+  for (int s = 0; s < kNumSlots; ++s) { L.total_ms[s] = 0.0; L.launches[s] = 0; }
+  L.failed = false;
+  *count = outn;
+  return bad ? COMPAMS_HIP_ERROR : COMPAMS_OK;
+}
+
+int compams_destroy(compams_ctx* ctx) {
+  if (!ctx) return COMPAMS_INVALID_ARG;
+  Launcher& L = ctx->launcher;
+  for (int s = 0; s < kNumSlots; ++s)
+    for (const Launcher::Pair& p : L.pending[s]) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  for (const Launcher::Pair& p : L.pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  delete ctx;
+  return COMPAMS_OK;
+}
+
+const char* compams_strerror(int status) {
+  switch (status) {
+    case COMPAMS_OK: return "ok";
+    case COMPAMS_INVALID_ARG: return "invalid argument";
+    case COMPAMS_BAD_ALIGNMENT: return "pointer or row stride not aligned";
+    case COMPAMS_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case COMPAMS_HIP_ERROR: return "HIP runtime error";
+    case COMPAMS_BAD_STATE: return "query or option does not apply to this compressor";
+    default: return "unknown status";
+  }
+}
+
+int compams_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!dst || !src) return COMPAMS_INVALID_ARG;
+  if (bytes % 16 != 0 || reinterpret_cast<uintptr_t>(dst) % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0)
+    return COMPAMS_BAD_ALIGNMENT;
+  return stream_copy(dst, src, bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? COMPAMS_OK
+                                                                                            : COMPAMS_HIP_ERROR;
+}
+
+}  // extern "C"

@@ -1,0 +1,491 @@
+// Block-Sign with error feedback (Definition 2 inside the worker lines of Algorithm 2) for gfx950, and
+// the server lines for sign/scale messages.
+//
+// Per worker row and block B:  mu = ||x_B||_1 / d_B with x = e + g, message = (one sign bit per
+// coordinate, mu), residual e = x - sign(x) * mu, where sign(x) = -1 iff x < 0.
+//
+// The block L1 norm is accumulated EXACTLY, so that the scale does not depend on how the sum was
+// split over lanes, wavefronts and workgroups: every |x| is a 24-bit integer times a power of two;
+// it is added into a fixed-point number whose 32-bit digits are carried in 64-bit words (room for
+// 2^32 additions before a digit could overflow).  Integer addition commutes, so integer atomics leave
+// the result unique.  The sum is rounded once to double, divided by d_B in double and rounded to fp32.
+//
+// Pass 1 forms x (stored in place of e) and the sums, a small kernel turns sums into scales, pass 2
+// re-reads x and writes sign bits and residuals, and the server kernel adds the n workers' +-mu in
+// worker order before the AMSGrad update.
+
+#include "compams_device.h"
+#include "compams_internal.h"
+
+namespace compams {
+namespace {
+
+// |x| = mant * 2^(sh - 149), mant < 2^24, sh in [0, 253]; digit w = sh / 32 gets the low 32 bits of
+// mant << (sh % 32), digit w + 1 the rest.
+struct Fixed {
+  uint32_t w;
+  uint32_t lo;
+  uint32_t hi;
+  uint32_t special;  // 1: infinity, 2: NaN
+};
+
+__device__ __forceinline__ Fixed to_fixed(uint32_t bits) {
+  const uint32_t key = bits & 0x7fffffffu;
+  const uint32_t ex = key >> 23, frac = key & 0x7fffffu;
+  Fixed f;
+  if (ex == 255) {
+    f.w = 0; f.lo = 0; f.hi = 0;
+    f.special = frac ? 2u : 1u;
+    return f;
+  }
+  const uint32_t mant = ex ? (frac | 0x800000u) : frac;
+  const uint32_t sh = ex ? ex - 1 : 0;
+  const uint64_t val = static_cast<uint64_t>(mant) << (sh & 31u);
+  f.w = sh >> 5;
+  f.lo = static_cast<uint32_t>(val);
+  f.hi = static_cast<uint32_t>(val >> 32);
+  f.special = 0;
+  return f;
+}
+
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) {
+    const uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), s, 64);
+    const uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), s, 64);
+    v += (static_cast<uint64_t>(hi) << 32) | lo;
+  }
+  return v;
+}
+
+__device__ __forceinline__ void atomic_add_u64(uint64_t* p, uint64_t v) {
+  atomicAdd(reinterpret_cast<unsigned long long*>(p), static_cast<unsigned long long>(v));
+}
+
+// Three digits kept in registers per lane around a wave-uniform centre digit; everything else goes
+// straight to the global digits with atomics (rare: values more than 2^32 away from the centre).
+struct WaveAcc {
+  uint32_t centre;  // digit index of a1
+  uint64_t a0, a1, a2;
+  bool live;
+};
+
+__device__ __forceinline__ void acc_flush(WaveAcc& A, uint64_t* digits /* kLimbs of the (row, block) */) {
+  if (!A.live) return;
+  const uint64_t s0 = wave_sum_u64(A.a0), s1 = wave_sum_u64(A.a1), s2 = wave_sum_u64(A.a2);
+  if (lane_id() == 0) {
+    if (s0) atomic_add_u64(digits + A.centre - 1, s0);  // s0 != 0 implies centre >= 1
+    if (s1) atomic_add_u64(digits + A.centre, s1);
+    if (s2) atomic_add_u64(digits + A.centre + 1, s2);
+  }
+  A.a0 = A.a1 = A.a2 = 0;
+  A.live = false;
+}
+
+__device__ __forceinline__ void acc_add(WaveAcc& A, const Fixed& f, bool ok, uint64_t* digits, uint32_t* special) {
+  if (!ok) return;
+  if (f.special) { atomicOr(special, f.special); return; }
+  if ((f.lo | f.hi) == 0) return;
+  if (f.w == A.centre) { A.a1 += f.lo; A.a2 += f.hi; }
+  else if (f.w + 1 == A.centre) { A.a0 += f.lo; A.a1 += f.hi; }
+  else {
+    atomic_add_u64(digits + f.w, f.lo);
+    if (f.hi) atomic_add_u64(digits + f.w + 1, f.hi);
+  }
+}
+
+// Largest b with off[b] <= j, starting the walk at hint (off[hint] <= j must hold).
+__device__ __forceinline__ uint32_t block_of(const uint32_t* __restrict__ off, uint32_t hint, uint32_t j) {
+  uint32_t b = hint;
+  while (off[b + 1] <= j) ++b;
+  return b;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 1: x = e + g -> e and exact block sums.  Grid (groups_per_row, n), one wavefront per chunk.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
+                                                   BlocksignWorkspace ws) {
+  const uint32_t row = blockIdx.y;
+  const float* gr = g + static_cast<int64_t>(row) * geo.ld;
+  float* er = e + static_cast<int64_t>(row) * geo.ld;
+  const uint32_t* __restrict__ off = ws.offsets;
+  uint64_t* accr = ws.acc + static_cast<size_t>(row) * geo.num_blocks * kLimbs;
+  uint32_t* specr = ws.special + static_cast<size_t>(row) * geo.num_blocks;
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t stride = gridDim.x * kWaves;
+  const uint32_t d = geo.d;
+  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+    uint32_t b = ws.chunk_block[c];  // wave-uniform: block of the chunk's first coordinate
+    WaveAcc A;
+    A.a0 = A.a1 = A.a2 = 0; A.live = false; A.centre = 0;
+    for (int r = 0; r < kRounds; ++r) {
+      const uint32_t j0 = c * kChunk + r * 256;  // wave-uniform
+      if (j0 >= d) break;
+      const uint32_t j = j0 + lane * 4;
+      const bool in = j < d;
+      float4 gv = make_float4(0.f, 0.f, 0.f, 0.f), ev = gv;
+      if (in) {
+        gv = *reinterpret_cast<const float4*>(gr + j);
+        ev = *reinterpret_cast<const float4*>(er + j);
+      }
+      float4 x = make_float4(ev.x + gv.x, ev.y + gv.y, ev.z + gv.z, ev.w + gv.w);
+      const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
+      if (!ok[1]) x.y = ev.y;
+      if (!ok[2]) x.z = ev.z;
+      if (!ok[3]) x.w = ev.w;
+      if (in) *reinterpret_cast<float4*>(er + j) = x;
+      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
+                                __float_as_uint(x.w)};
+      // leave blocks that end at or before this round
+      while (off[b + 1] <= j0) {
+        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+        ++b;
+      }
+      const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
+      if (off[b + 1] >= j_end) {
+        // the whole round lies in block b
+        if (!A.live) {
+          // centre the register digits on the largest magnitude of this round
+          uint32_t kmax = 0;
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const uint32_t key = bits[s] & 0x7fffffffu;
+            if (ok[s] && key < 0x7f800000u && key > kmax) kmax = key;
+          }
+#pragma unroll
+          for (int s = 32; s >= 1; s >>= 1) {
+            const uint32_t o = __shfl_xor(kmax, s, 64);
+            kmax = o > kmax ? o : kmax;
+          }
+          const uint32_t ex = kmax >> 23;
+          A.centre = (ex ? ex - 1 : 0) >> 5;
+          A.live = true;
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          acc_add(A, to_fixed(bits[s]), ok[s], accr + static_cast<size_t>(b) * kLimbs, specr + b);
+      } else {
+        // the round straddles block boundaries: every coordinate goes to its own block's digits
+        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          if (!ok[s]) continue;
+          const uint32_t bb = block_of(off, b, j + s);
+          const Fixed f = to_fixed(bits[s]);
+          uint64_t* dg = accr + static_cast<size_t>(bb) * kLimbs;
+          if (f.special) atomicOr(specr + bb, f.special);
+          else {
+            if (f.lo) atomic_add_u64(dg + f.w, f.lo);
+            if (f.hi) atomic_add_u64(dg + f.w + 1, f.hi);
+          }
+        }
+      }
+    }
+    // b is wave-uniform; flush what is left for the block the chunk ended in
+    acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scales: one thread per (row, block).  Normalise the digits, round the sum to double (nearest, ties
+// to even), divide by the block length, round to fp32.  Clears the digits for the next step.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWorkspace ws) {
+  const size_t t = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x;
+  const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
+  if (t >= total) return;
+  const uint32_t b = static_cast<uint32_t>(t % geo.num_blocks);
+  uint64_t* dg = ws.acc + t * kLimbs;
+  uint32_t digit[kLimbs + 1];
+  uint64_t carry = 0;
+#pragma unroll
+  for (int i = 0; i < kLimbs; ++i) {
+    const uint64_t v = dg[i] + carry;
+    digit[i] = static_cast<uint32_t>(v);
+    carry = v >> 32;
+    dg[i] = 0;
+  }
+  digit[kLimbs] = static_cast<uint32_t>(carry);
+  const uint32_t sp = ws.special[t];
+  ws.special[t] = 0;
+  const double len = static_cast<double>(ws.offsets[b + 1] - ws.offsets[b]);
+  double sum;
+  int top = -1;
+  for (int i = kLimbs; i >= 0; --i)
+    if (digit[i]) { top = i * 32 + 31 - __clz(digit[i]); break; }
+  auto bit_at = [&](int p) -> uint32_t { return (digit[p >> 5] >> (p & 31)) & 1u; };
+  if (sp & 2u) sum = __longlong_as_double(0x7ff8000000000000ll);
+  else if (sp & 1u) sum = __longlong_as_double(0x7ff0000000000000ll);
+  else if (top < 0) sum = 0.0;
+  else if (top <= 52) {
+    const uint64_t v = (static_cast<uint64_t>(digit[1]) << 32) | digit[0];
+    sum = ldexp(static_cast<double>(v), -149);
+  } else {
+    const int low = top - 52;
+    uint64_t kept = 0;
+    for (int p = top; p >= low; --p) kept = (kept << 1) | bit_at(p);
+    const uint32_t guard = bit_at(low - 1);
+    bool sticky = false;
+    for (int p = low - 2; p >= 0; --p) sticky = sticky || bit_at(p);
+    if (guard && (sticky || (kept & 1))) ++kept;
+    sum = ldexp(static_cast<double>(kept), low - 149);
+  }
+  ws.scales[t] = static_cast<float>(sum / len);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 2: sign bits and residual  e = x - sign(x) * mu.  One wavefront per chunk.  Eight lanes
+// (32 coordinates) share one word of the bit map.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometry geo, BlocksignWorkspace ws) {
+  const uint32_t row = blockIdx.y;
+  float* er = e + static_cast<int64_t>(row) * geo.ld;
+  const uint32_t* __restrict__ off = ws.offsets;
+  const float* __restrict__ mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;
+  uint32_t* bitr = ws.bits + static_cast<size_t>(row) * geo.words;
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t stride = gridDim.x * kWaves;
+  const uint32_t d = geo.d;
+  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+    uint32_t b = ws.chunk_block[c];
+    for (int r = 0; r < kRounds; ++r) {
+      const uint32_t j0 = c * kChunk + r * 256;
+      if (j0 >= d) break;
+      const uint32_t j = j0 + lane * 4;
+      const bool in = j < d;
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (in) x = *reinterpret_cast<const float4*>(er + j);
+      const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
+      while (off[b + 1] <= j0) ++b;
+      const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
+      float mu[4];
+      if (off[b + 1] >= j_end) {
+        const float m0 = mur[b];
+        mu[0] = mu[1] = mu[2] = mu[3] = m0;
+      } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) mu[s] = ok[s] ? mur[block_of(off, b, j + s)] : 0.0f;
+      }
+      float xv[4] = {x.x, x.y, x.z, x.w};
+      uint32_t nib = 0;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const bool neg = ok[s] && xv[s] < 0.0f;
+        nib |= (neg ? 1u : 0u) << s;
+        if (ok[s]) xv[s] = xv[s] - (neg ? -mu[s] : mu[s]);
+      }
+      if (in) *reinterpret_cast<float4*>(er + j) = make_float4(xv[0], xv[1], xv[2], xv[3]);
+      uint32_t word = nib << ((lane & 7u) * 4u);
+      word |= __shfl_xor(word, 1, 64);
+      word |= __shfl_xor(word, 2, 64);
+      word |= __shfl_xor(word, 4, 64);
+      const uint32_t widx = (j0 >> 5) + (lane >> 3);
+      if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
+    }
+  }
+}
+
+__device__ __forceinline__ void ams_update(float gb, float& th, float& mm, float& vv, float& vh, const AmsParams& p) {
+  const float mj = p.beta1 * mm + p.one_minus_beta1 * gb;
+  const float vj = p.beta2 * vv + p.one_minus_beta2 * (gb * gb);
+  const float vhj = (vh < vj) ? vj : vh;
+  const float den = p.eps_out ? sqrtf(vhj) + p.eps : sqrtf(vhj + p.eps);
+  mm = mj;
+  vv = vj;
+  vh = vhj;
+  th = th - p.lr * (mj / den);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Server lines for sign/scale messages: gbar_j = (sum_i s_ij * mu_i,b(j)) / n in worker order, then
+// AMSGrad.  One wavefront per chunk of coordinates.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, float* __restrict__ m,
+                                                     float* __restrict__ v, float* __restrict__ vhat, Geometry geo,
+                                                     BlocksignWorkspace ws, AmsParams p) {
+  const uint32_t* __restrict__ off = ws.offsets;
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t d = geo.d;
+  const uint32_t c = blockIdx.x * kWaves + wave;
+  if (c >= geo.num_chunks) return;
+  uint32_t b = ws.chunk_block[c];
+  for (int r = 0; r < kRounds; ++r) {
+    const uint32_t j0 = c * kChunk + r * 256;
+    if (j0 >= d) break;
+    const uint32_t j = j0 + lane * 4;
+    const bool ok[4] = {j < d, j + 1 < d, j + 2 < d, j + 3 < d};
+    while (off[b + 1] <= j0) ++b;
+    const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
+    const bool uniform = off[b + 1] >= j_end;
+    uint32_t bb[4] = {b, b, b, b};
+    if (!uniform) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) bb[s] = ok[s] ? block_of(off, b, j + s) : b;
+    }
+    float sum[4] = {0.f, 0.f, 0.f, 0.f};
+    const uint32_t widx = j >> 5, sh = j & 31u;
+    for (uint32_t i = 0; i < geo.n; ++i) {
+      const uint32_t word = ok[0] ? ws.bits[static_cast<size_t>(i) * geo.words + widx] : 0u;
+      const float* mur = ws.scales + static_cast<size_t>(i) * geo.num_blocks;
+      const uint32_t nib = (word >> sh) & 15u;
+      if (uniform) {
+        const float mu = mur[b];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) sum[s] = sum[s] + (((nib >> s) & 1u) ? -mu : mu);
+      } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const float mu = mur[bb[s]];
+          sum[s] = sum[s] + (((nib >> s) & 1u) ? -mu : mu);
+        }
+      }
+    }
+    if (ok[3]) {
+      float4 th = *reinterpret_cast<float4*>(theta + j), mm = *reinterpret_cast<float4*>(m + j);
+      float4 vv = *reinterpret_cast<float4*>(v + j), vh = *reinterpret_cast<float4*>(vhat + j);
+      ams_update(sum[0] / p.nf, th.x, mm.x, vv.x, vh.x, p);
+      ams_update(sum[1] / p.nf, th.y, mm.y, vv.y, vh.y, p);
+      ams_update(sum[2] / p.nf, th.z, mm.z, vv.z, vh.z, p);
+      ams_update(sum[3] / p.nf, th.w, mm.w, vv.w, vh.w, p);
+      *reinterpret_cast<float4*>(theta + j) = th;
+      *reinterpret_cast<float4*>(m + j) = mm;
+      *reinterpret_cast<float4*>(v + j) = vv;
+      *reinterpret_cast<float4*>(vhat + j) = vh;
+    } else {
+      for (int s = 0; s < 4; ++s)
+        if (ok[s]) {
+          float th = theta[j + s], mm = m[j + s], vv = v[j + s], vh = vhat[j + s];
+          ams_update(sum[s] / p.nf, th, mm, vv, vh, p);
+          theta[j + s] = th; m[j + s] = mm; v[j + s] = vv; vhat[j + s] = vh;
+        }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// C = identity (full-precision distributed AMSGrad): gbar = mean of the n gradients in worker order.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWG) void k_none_amsgrad(const float* __restrict__ g, float* __restrict__ theta,
+                                                       float* __restrict__ m, float* __restrict__ v,
+                                                       float* __restrict__ vhat, Geometry geo, AmsParams p) {
+  const uint32_t j = (blockIdx.x * kWG + threadIdx.x) * 4;
+  if (j >= geo.d) return;
+  float sum[4] = {0.f, 0.f, 0.f, 0.f};
+  for (uint32_t i = 0; i < geo.n; ++i) {
+    // x = e + g with e identically zero
+    const float4 gv = *reinterpret_cast<const float4*>(g + static_cast<int64_t>(i) * geo.ld + j);
+    sum[0] = sum[0] + (0.0f + gv.x); sum[1] = sum[1] + (0.0f + gv.y);
+    sum[2] = sum[2] + (0.0f + gv.z); sum[3] = sum[3] + (0.0f + gv.w);
+  }
+  if (j + 3 < geo.d) {
+    float4 th = *reinterpret_cast<float4*>(theta + j), mm = *reinterpret_cast<float4*>(m + j);
+    float4 vv = *reinterpret_cast<float4*>(v + j), vh = *reinterpret_cast<float4*>(vhat + j);
+    ams_update(sum[0] / p.nf, th.x, mm.x, vv.x, vh.x, p);
+    ams_update(sum[1] / p.nf, th.y, mm.y, vv.y, vh.y, p);
+    ams_update(sum[2] / p.nf, th.z, mm.z, vv.z, vh.z, p);
+    ams_update(sum[3] / p.nf, th.w, mm.w, vv.w, vh.w, p);
+    *reinterpret_cast<float4*>(theta + j) = th;
+    *reinterpret_cast<float4*>(m + j) = mm;
+    *reinterpret_cast<float4*>(v + j) = vv;
+    *reinterpret_cast<float4*>(vhat + j) = vh;
+  } else {
+    for (uint32_t s = 0; s < 4 && j + s < geo.d; ++s) {
+      float th = theta[j + s], mm = m[j + s], vv = v[j + s], vh = vhat[j + s];
+      ams_update(sum[s] / p.nf, th, mm, vv, vh, p);
+      theta[j + s] = th; m[j + s] = mm; v[j + s] = vv; vhat[j + s] = vh;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Utility kernels.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWG) void k_fill_u32(uint32_t* p, size_t count, uint32_t value) {
+  const size_t step = static_cast<size_t>(gridDim.x) * kWG;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x; i < count; i += step) p[i] = value;
+}
+
+__global__ __launch_bounds__(kWG) void k_fill_rows(float* p, int64_t ld, uint32_t d, float value) {
+  float* r = p + static_cast<int64_t>(blockIdx.y) * ld;
+  const uint32_t step = gridDim.x * kWG;
+  for (uint32_t j = blockIdx.x * kWG + threadIdx.x; j < d; j += step) r[j] = value;
+}
+
+__global__ __launch_bounds__(kWG) void k_copy16(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t count) {
+  const size_t step = static_cast<size_t>(gridDim.x) * kWG;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x; i < count; i += step) dst[i] = src[i];
+}
+
+}  // namespace
+
+#define COMPAMS_CHECK_LAUNCH()                    \
+  do {                                            \
+    hipError_t err__ = hipGetLastError();         \
+    if (err__ != hipSuccess) return err__;        \
+  } while (0)
+
+hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, const float* g,
+                          float* e, float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
+  const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
+  const dim3 grid_rows(G, geo.n), wg(kWG);
+  {
+    ScopedSlot s(L, kSlotBsPass1, stream);
+    hipLaunchKernelGGL(k_bs_pass1, grid_rows, wg, 0, stream, g, e, geo, ws);
+  }
+  COMPAMS_CHECK_LAUNCH();
+  {
+    ScopedSlot s(L, kSlotBsFinal, stream);
+    const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
+    hipLaunchKernelGGL(k_bs_finalize, dim3(static_cast<uint32_t>((total + kWG - 1) / kWG)), wg, 0, stream, geo, ws);
+  }
+  COMPAMS_CHECK_LAUNCH();
+  {
+    ScopedSlot s(L, kSlotBsPass2, stream);
+    hipLaunchKernelGGL(k_bs_pass2, grid_rows, wg, 0, stream, e, geo, ws);
+  }
+  COMPAMS_CHECK_LAUNCH();
+  {
+    ScopedSlot s(L, kSlotBsAms, stream);
+    hipLaunchKernelGGL(k_bs_amsgrad, dim3((geo.num_chunks + kWaves - 1) / kWaves), wg, 0, stream, theta, m, v, vhat,
+                       geo, ws, ap);
+  }
+  COMPAMS_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, float* theta, float* m, float* v,
+                     float* vhat, hipStream_t stream, Launcher* L) {
+  ScopedSlot s(L, kSlotNoneAms, stream);
+  const uint32_t quads = (geo.d + 3) / 4;
+  hipLaunchKernelGGL(k_none_amsgrad, dim3((quads + kWG - 1) / kWG), dim3(kWG), 0, stream, g, theta, m, v, vhat, geo,
+                     ap);
+  return hipGetLastError();
+}
+
+hipError_t fill_u32(uint32_t* p, size_t count, uint32_t value, hipStream_t stream) {
+  if (!count) return hipSuccess;
+  size_t blocks = (count + kWG - 1) / kWG;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(k_fill_u32, dim3(static_cast<uint32_t>(blocks)), dim3(kWG), 0, stream, p, count, value);
+  return hipGetLastError();
+}
+
+hipError_t fill_rows_f32(float* p, uint32_t n, int64_t ld, uint32_t d, float value, hipStream_t stream) {
+  uint32_t blocks = (d + kWG - 1) / kWG;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(k_fill_rows, dim3(blocks, n), dim3(kWG), 0, stream, p, ld, d, value);
+  return hipGetLastError();
+}
+
+hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+  const size_t count = bytes / 16;
+  if (!count) return hipSuccess;
+  size_t blocks = (count + kWG - 1) / kWG;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(k_copy16, dim3(static_cast<uint32_t>(blocks)), dim3(kWG), 0, stream,
+                     static_cast<uint4*>(dst), static_cast<const uint4*>(src), count);
+  return hipGetLastError();
+}
+
+}  // namespace compams

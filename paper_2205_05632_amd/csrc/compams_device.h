@@ -1,0 +1,59 @@
+// Device-side helpers for the gfx950 kernels of libcompams (wave64 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace compams {
+
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+
+// 64-bit mask of the lanes of this wavefront for which p holds.
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p ? 1 : 0); }
+
+// Number of set bits of mask that belong to lanes below the calling lane.
+__device__ __forceinline__ uint32_t count_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                   __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+}
+
+__device__ __forceinline__ uint32_t popc64(uint64_t m) { return static_cast<uint32_t>(__popcll(m)); }
+
+// Value of lane 0 made wave-uniform.
+__device__ __forceinline__ uint32_t first_lane(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Magnitude key of Definition 1's ordering: the fp32 pattern without its sign bit.
+__device__ __forceinline__ uint32_t key_of_bits(uint32_t bits) { return bits & 0x7fffffffu; }
+
+// Inclusive wave prefix sum (64 lanes).
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+#pragma unroll
+  for (int s = 1; s < 64; s <<= 1) {
+    const uint32_t o = __shfl_up(v, s, 64);
+    if (lane_id() >= static_cast<uint32_t>(s)) v += o;
+  }
+  return v;
+}
+
+// Exclusive prefix sum over a workgroup of NT threads (NT a multiple of 64, at most 1024).
+// scratch must hold NT/64 + 1 words.  Returns the exclusive prefix; *total gets the workgroup sum.
+template <int NT>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
+  constexpr int NW = NT / 64;
+  const uint32_t incl = wave_incl_scan(v);
+  const uint32_t w = threadIdx.x >> 6;
+  __syncthreads();  // scratch may still be read from a previous call
+  if (lane_id() == 63) scratch[w] = incl;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) {
+    const uint32_t t = scratch[i];
+    if (static_cast<uint32_t>(i) < w) before += t;
+    all += t;
+  }
+  *total = all;
+  return before + incl - v;
+}
+
+}  // namespace compams

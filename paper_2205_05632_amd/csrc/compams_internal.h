@@ -1,0 +1,148 @@
+// Internal declarations shared by the kernel files and the C-ABI host code of libcompams.
+// Nothing here is part of the public interface (include/compams.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace compams {
+
+// ---------------------------------------------------------------------------------------------
+// Geometry shared by all kernels.
+//
+// A row (one worker's d coordinates) is cut into chunks of kChunk consecutive coordinates.  One
+// wavefront (64 lanes) owns a chunk at a time and walks it in kRounds rounds; in a round lane l
+// holds the four coordinates base + 256*round + 4*l + {0,1,2,3}, so that a wave's 128-bit accesses
+// cover 1 KiB of contiguous memory and (round, lane, slot) order is ascending coordinate order.
+// ---------------------------------------------------------------------------------------------
+constexpr int kWG = 256;                 // threads per workgroup = 4 wavefronts
+constexpr int kWaves = kWG / 64;
+constexpr int kChunk = 4096;             // coordinates per chunk
+constexpr int kRounds = kChunk / 256;    // rounds per chunk and wavefront
+
+// Radix levels over the 31-bit magnitude key (fp32 bit pattern without the sign):
+// level 0 = bits 30..19 (the exponent and 4 mantissa bits), level 1 = bits 18..9, level 2 = bits 8..0.
+constexpr int kL0Shift = 19;
+constexpr int kNB0 = 1 << 12;
+constexpr int kL1Shift = 9;
+constexpr int kNB1 = 1 << 10;
+constexpr int kNB2 = 1 << 9;
+
+// Where a row's selection reads its elements from after the first pass.
+enum : uint32_t {
+  kModeCand = 0,   // candidate list written by the first pass (threshold bucket was predicted)
+  kModeNeedB = 1,  // candidate list written by a second dense pass that knows the exact level-0 bucket
+  kModeDense = 2   // no candidate list (it would not fit): every later pass reads the whole row
+};
+
+// Per-row control block of the top-k selection (device memory, written by single workgroups).
+struct TopkRow {
+  uint32_t pred_valid;  // the next first pass may emit candidates with level-0 bucket >= b_guess
+  uint32_t b_guess;
+  uint32_t cursor;      // candidate entries allocated so far in this step
+  uint32_t mode;        // kMode*
+  uint32_t n_src;       // entries in the candidate list (kModeCand / kModeNeedB)
+  uint32_t bstar;       // level-0 bucket that holds the k-th largest key
+  uint32_t need;        // keys still to be taken inside the current prefix
+  uint32_t prefix1;     // bits 30..9 of the k-th largest key (after level 1)
+  uint32_t tau;         // the k-th largest key
+  uint32_t r;           // how many keys equal to tau are selected
+  uint32_t ties;        // how many keys equal tau
+  uint32_t take_all_ties;  // r == ties: no tie ranking needed
+  uint32_t pad[4];
+};
+static_assert(sizeof(TopkRow) == 64, "TopkRow layout");
+
+struct TopkOptions {
+  uint32_t cap;            // candidate entries per row
+  uint32_t predict;        // 1: carry the threshold bucket over to the next step's first pass
+  uint32_t force_dense;    // 1: never build a candidate list (test / ablation)
+  uint32_t first_pass_emits;  // set per step by the host: this step's first pass was the emitting variant
+};
+
+struct TopkWorkspace {
+  TopkRow* rows;        // n
+  uint32_t* counters;   // n * COMPAMS_COUNTERS_PER_ROW
+  uint32_t* hist0;      // n * kNB0
+  uint32_t* hist1;      // n * kNB1
+  uint32_t* hist2;      // n * kNB2
+  uint32_t* cnt_gt;     // n * num_chunks : keys above tau per chunk
+  uint32_t* cnt_eq;     // n * num_chunks : keys equal to tau per chunk
+  uint32_t* sel_off;    // n * (num_chunks + 1) : exclusive prefix of selected entries per chunk
+  uint32_t* eq_before;  // n * num_chunks : ties in earlier chunks
+  uint2* desc;          // n * num_chunks : (offset, count) of the chunk's segment in the candidate list
+  uint2* cand;          // n * cap_alloc  : (coordinate, fp32 bits)
+  int32_t* idx;         // n * k
+  float* val;           // n * k
+  uint32_t* tau;        // n
+};
+
+struct BlocksignWorkspace {
+  uint32_t* offsets;    // M + 1 block offsets
+  uint32_t* chunk_block; // num_chunks : index of the block that holds the chunk's first coordinate
+  uint64_t* acc;        // n * M * kLimbs : exact sums of |x| (32-bit digits carried in 64-bit words)
+  uint32_t* special;    // n * M : bit 0 = an infinity was seen, bit 1 = a NaN was seen
+  float* scales;        // n * M
+  uint32_t* bits;       // n * words
+};
+constexpr int kLimbs = 10;  // 10 digits of 32 bits cover 2^-149 .. 2^171
+
+struct AmsParams {
+  float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, lr, nf;
+  int eps_out;  // 1: epsilon outside the square root
+};
+
+struct Geometry {
+  uint32_t n;
+  uint32_t d;
+  int64_t ld;
+  uint32_t num_chunks;
+  uint32_t k;
+  uint32_t num_blocks;
+  uint32_t words;  // ceil(d / 32)
+};
+
+// Kernel slots for optional timing.
+enum KernelSlot {
+  kSlotPassA = 0, kSlotResolve0, kSlotPassB, kSlotHist1, kSlotResolve1, kSlotHist2, kSlotResolve2,
+  kSlotCount, kSlotScan, kSlotEmit, kSlotTopkAms,
+  kSlotBsPass1, kSlotBsFinal, kSlotBsPass2, kSlotBsAms,
+  kSlotNoneAms, kNumSlots
+};
+
+struct Launcher;  // host-side helper that brackets launches with events (compams_api.hip)
+
+// Host-side launch entry points, one per compressor (defined next to their kernels).
+hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
+                     const float* g, float* e, float* theta, float* m, float* v, float* vhat,
+                     bool first_pass_may_predict, hipStream_t stream, Launcher* L);
+hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, const float* g,
+                          float* e, float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L);
+hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, float* theta, float* m, float* v,
+                     float* vhat, hipStream_t stream, Launcher* L);
+hipError_t fill_u32(uint32_t* p, size_t count, uint32_t value, hipStream_t stream);
+hipError_t fill_rows_f32(float* p, uint32_t n, int64_t ld, uint32_t d, float value, hipStream_t stream);
+hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
+// Event bracketing used by the *_step functions.
+void launcher_begin(Launcher* L, int slot, hipStream_t stream);
+void launcher_end(Launcher* L, int slot, hipStream_t stream);
+
+struct ScopedSlot {
+  Launcher* L; int slot; hipStream_t s;
+  ScopedSlot(Launcher* l, int sl, hipStream_t st) : L(l), slot(sl), s(st) { if (L) launcher_begin(L, slot, s); }
+  ~ScopedSlot() { if (L) launcher_end(L, slot, s); }
+};
+
+// How many workgroups per row the streaming kernels use: enough to keep 256 compute units busy
+// with several workgroups each, whatever n is.
+inline uint32_t groups_per_row(uint32_t n, uint32_t num_chunks) {
+  const uint32_t target = 256 * 8;  // workgroups in flight over the whole grid
+  uint32_t g = (target + n - 1) / n;
+  const uint32_t max_g = (num_chunks + kWaves - 1) / kWaves;  // one chunk per wavefront at least
+  if (g > max_g) g = max_g;
+  if (g < 1) g = 1;
+  return g;
+}
+
+}  // namespace compams

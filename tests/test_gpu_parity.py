@@ -1,0 +1,308 @@
+"""GPU parity tests: the HIP library, called through its C ABI, against the CPU oracle.
+
+Bar: selected index sets, selected values, sign patterns and block scales bit-exact; theta, m, v, vhat and
+the residuals e within |a - b| <= 1e-5 |b| + 1e-5 max|b| after every step (10 steps in the basic cases).
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2205_05632_amd import binding as B
+from paper_2205_05632_amd import workloads as W
+
+from parity import Pair
+
+pytestmark = pytest.mark.gpu
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def run_pair(p, gs, lr=1e-3, label=""):
+    for t, g in enumerate(gs):
+        p.step(g, lr, label=f"{label} step {t}")
+
+
+def rand_grads(seed, n, d, steps, scale=1.0):
+    rng = np.random.default_rng(seed)
+    return [(rng.standard_normal((n, d)) * scale).astype(np.float32) for _ in range(steps)]
+
+
+# ------------------------------------------------------------------------------------------- top-k
+@pytest.mark.parametrize("eps_mode", [B.EPS_IN_SQRT, B.EPS_OUT_SQRT])
+def test_topk_tiny_config_10_steps(eps_mode):
+    w = W.get("tiny")
+    p = Pair(w.n, w.d, W.theta0(w).numpy(), B.TOPK, k=w.k, eps_mode=eps_mode)
+    run_pair(p, [W.gradients(w, t).numpy() for t in range(10)], lr=w.lr, label="tiny")
+    # every operation is element-wise IEEE fp32 in a fixed order on both sides
+    assert all(p.exact.values()), p.exact
+    c = p.gpu.compams_state("counters").cpu().numpy()
+    assert (c[:, 0] == 0).all(), f"steady-state steps should take candidates from the first pass: {c}"
+    p.close()
+
+
+@pytest.mark.parametrize("n,d,k,ld", [(3, 100003, 1000, None), (2, 4097, 5, 4100), (1, 1, 1, None), (5, 8191, 8191, 8200),
+                                      (2, 12288, 1, None), (4, 300001, 150000, None), (17, 20000, 200, None)])
+def test_topk_ragged_shapes(n, d, k, ld):
+    rng = np.random.default_rng(d + k)
+    p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, B.TOPK, k=k, ld=ld)
+    run_pair(p, rand_grads(d, n, d, 4), label=f"ragged d={d} k={k}")
+    # columns >= d of e are never touched
+    if p.gpu.ld > d:
+        assert not p.gpu.e[:, d:].any()
+    p.close()
+
+
+def test_topk_padding_columns_keep_their_contents():
+    n, d, ld, k = 2, 1001, 1008, 10
+    p = Pair(n, d, np.zeros(d, np.float32), B.TOPK, k=k, ld=ld)
+    p.gpu.e[:, d:] = 7.0
+    g = np.random.default_rng(0).standard_normal((n, d)).astype(np.float32)
+    gp = torch.full((n, ld), 3.0)
+    gp[:, :d] = torch.from_numpy(g)
+    p.gpu.compams_step(gp.cuda(), 1e-3)
+    p.cpu.step(g, 1e-3)
+    p.compare("padding")
+    assert (p.gpu.e[:, d:] == 7.0).all()
+    p.close()
+
+
+def adversarial_rows(d, rng):
+    rows = []
+    rows.append(np.full(d, 1.5, np.float32))                               # all equal
+    rows.append(np.zeros(d, np.float32))                                   # all zero
+    r = np.zeros(d, np.float32); r[::7] = -0.0; r[5::11] = 1e-40; r[3] = 2.0   # +-0, denormals, one large
+    rows.append(r)
+    rows.append(rng.integers(-3, 4, d).astype(np.float32))                 # few magnitudes: ties at the threshold
+    r = rng.standard_normal(d).astype(np.float32); r[10] = np.inf; r[20] = -np.inf
+    rows.append(r)
+    r = (rng.standard_normal(d) * 1e-42).astype(np.float32)                # all denormal
+    rows.append(r)
+    r = rng.standard_normal(d).astype(np.float32); r[d // 2:] = r[: d - d // 2]  # every magnitude twice
+    rows.append(r)
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("k", [1, 2, 97, 5000, 20000])
+@pytest.mark.parametrize("route", ["default", "dense", "small_cap", "no_predict"])
+def test_topk_adversarial_rows_every_route(k, route):
+    d = 20000
+    rng = np.random.default_rng(k)
+    g0 = adversarial_rows(d, rng)
+    n = g0.shape[0]
+    p = Pair(n, d, np.zeros(d, np.float32), B.TOPK, k=k)
+    if route == "dense":
+        p.gpu.set_option(B.OPT_FORCE_DENSE, 1)
+    elif route == "small_cap":
+        p.gpu.set_option(B.OPT_CANDIDATE_CAP, min(d, max(k + 50, 300)))
+    elif route == "no_predict":
+        p.gpu.set_option(B.OPT_PREDICT, 0)
+    # state tensors may hold Inf/NaN here; index sets and values are the point
+    for t in range(3):
+        g = g0 if t != 1 else g0[::-1].copy()
+        p.step(g, 1e-3, label=f"adversarial k={k} {route} step {t}")
+    c = p.gpu.compams_state("counters").cpu().numpy()
+    if route == "dense":
+        assert (c[:, 0] == 4).all()
+    if route == "no_predict":
+        assert (c[:, 0] >= 1).all()
+    p.close()
+
+
+def test_topk_routes_agree_and_are_counted():
+    """Guessed candidates, re-read candidates and no candidates must give identical bytes."""
+    n, d, k = 3, 150000, 1500
+    gs = rand_grads(5, n, d, 6)
+    outs = []
+    for route in ("default", "no_predict", "dense", "small_cap"):
+        p = Pair(n, d, np.zeros(d, np.float32), B.TOPK, k=k)
+        if route == "no_predict":
+            p.gpu.set_option(B.OPT_PREDICT, 0)
+        if route == "dense":
+            p.gpu.set_option(B.OPT_FORCE_DENSE, 1)
+        if route == "small_cap":
+            p.gpu.set_option(B.OPT_CANDIDATE_CAP, k // 2)   # no list can fit
+        reads = []
+        for t, g in enumerate(gs):
+            p.step(g, 1e-3, label=f"{route} step {t}")
+            reads.append(p.gpu.compams_state("counters").cpu().numpy()[:, 0].copy())
+        outs.append([p.gpu.compams_state(s).cpu().numpy().copy() for s in ("theta", "e", "last_idx", "last_val")])
+        reads = np.array(reads)
+        if route == "default":
+            assert (reads[0] == 1).all() and (reads[2:] == 0).all(), reads
+        elif route == "no_predict":
+            assert (reads == 1).all(), reads
+        else:
+            assert (reads == 4).all(), reads
+        p.close()
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def test_topk_guess_that_is_too_high_falls_back():
+    """Gradients that shrink by 100x make the carried-over bucket too high: the step must notice and re-read."""
+    n, d, k = 2, 100000, 1000
+    rng = np.random.default_rng(3)
+    p = Pair(n, d, np.zeros(d, np.float32), B.TOPK, k=k)
+    reads = []
+    for t in range(6):
+        scale = 1.0 if t < 3 else 1e-4
+        g = (rng.standard_normal((n, d)) * scale).astype(np.float32)
+        if t == 3:
+            p.gpu.e.zero_()                 # drop the residuals so that the threshold really falls
+            p.cpu.set_state(e=np.zeros((n, d), np.float32))
+        p.step(g, 1e-3, label=f"shrink step {t}")
+        reads.append(p.gpu.compams_state("counters").cpu().numpy()[:, 0].copy())
+    reads = np.array(reads)
+    assert (reads[2] == 0).all() and (reads[3] >= 1).all() and (reads[5] == 0).all(), reads
+    p.close()
+
+
+def test_topk_is_deterministic():
+    n, d, k = 4, 200000, 2000
+    gs = rand_grads(9, n, d, 5)
+    res = []
+    for rep in range(2):
+        gpu = B.Compams(n, d, torch.zeros(d), compressor=B.TOPK, k=k)
+        for g in gs:
+            gp = torch.zeros((n, gpu.ld)); gp[:, :d] = torch.from_numpy(g)
+            gpu.compams_step(gp.cuda(), 1e-3)
+        torch.cuda.synchronize()
+        res.append([gpu.compams_state(s).cpu().numpy().copy() for s in ("theta", "m", "v", "vhat", "e", "last_idx", "last_val")])
+        gpu.close()
+    for a, b in zip(*res):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------------------- block-sign
+@pytest.mark.parametrize("eps_mode", [B.EPS_IN_SQRT, B.EPS_OUT_SQRT])
+def test_blocksign_tiny_config_10_steps(eps_mode):
+    w = W.get("tiny_blocksign")
+    p = Pair(w.n, w.d, W.theta0(w).numpy(), B.BLOCKSIGN, block_offsets=w.block_offsets(), eps_mode=eps_mode)
+    run_pair(p, [W.gradients(w, t).numpy() for t in range(10)], lr=w.lr, label="tiny_blocksign")
+    assert all(p.exact.values()), p.exact
+    p.close()
+
+
+def ragged_offsets(d, rng, m):
+    cuts = np.sort(rng.choice(np.arange(1, d), size=m - 1, replace=False))
+    return np.concatenate([[0], cuts, [d]]).astype(np.int64)
+
+
+@pytest.mark.parametrize("n,d,offsets", [
+    (3, 5000, [0, 1, 11, 500, 2548, 5000]),
+    (2, 100003, "ragged40"),
+    (2, 9000, "unit"),
+    (4, 70000, "fixed4096"),
+    (2, 50000, "one"),
+    (3, 33000, "ragged2000"),
+])
+def test_blocksign_block_layouts(n, d, offsets):
+    rng = np.random.default_rng(d)
+    if offsets == "ragged40":
+        off = ragged_offsets(d, rng, 40)
+    elif offsets == "ragged2000":
+        off = ragged_offsets(d, rng, 2000)
+    elif offsets == "unit":
+        off = np.arange(d + 1, dtype=np.int64)
+    elif offsets == "fixed4096":
+        off = np.concatenate([np.arange(0, d, 4096), [d]]).astype(np.int64)
+    elif offsets == "one":
+        off = np.array([0, d], dtype=np.int64)
+    else:
+        off = np.array(offsets, dtype=np.int64)
+    p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, B.BLOCKSIGN, block_offsets=off)
+    gs = []
+    for t in range(5):
+        g = (rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-4, 1, (1, d))).astype(np.float32)
+        g[:, ::13] = 0.0
+        gs.append(g)
+    run_pair(p, gs, label=f"blocksign {offsets}")
+    if offsets == "unit":
+        assert not p.gpu.compams_state("e").any()     # d_i = 1: the compressor is the identity
+    p.close()
+
+
+def test_blocksign_wide_dynamic_range_is_summed_exactly():
+    """Magnitudes from denormal to 1e30 in one block: any accumulation that is not exact gets the scale wrong."""
+    n, d = 2, 40000
+    rng = np.random.default_rng(1)
+    off = np.array([0, 10000, 10001, 30000, d], dtype=np.int64)
+    p = Pair(n, d, np.zeros(d, np.float32), B.BLOCKSIGN, block_offsets=off)
+    for t in range(3):
+        g = (rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-44, 30, (n, d))).astype(np.float32)
+        g[0, :10000] = 0.0                    # an all-zero block: scale 0, stays zero
+        p.step(g, 1e-3, label=f"wide range step {t}")
+    assert not p.gpu.compams_state("e")[0, :10000].any()
+    p.close()
+
+
+def test_blocksign_is_deterministic():
+    n, d = 3, 120000
+    off = np.concatenate([np.arange(0, d, 30011), [d]]).astype(np.int64)
+    gs = rand_grads(4, n, d, 4)
+    res = []
+    for rep in range(2):
+        gpu = B.Compams(n, d, torch.zeros(d), compressor=B.BLOCKSIGN, block_offsets=off)
+        for g in gs:
+            gp = torch.zeros((n, gpu.ld)); gp[:, :d] = torch.from_numpy(g)
+            gpu.compams_step(gp.cuda(), 1e-3)
+        torch.cuda.synchronize()
+        res.append([gpu.compams_state(s).cpu().numpy().copy()
+                    for s in ("theta", "m", "v", "vhat", "e", "last_signbits", "last_scales")])
+        gpu.close()
+    for a, b in zip(*res):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------------------- identity
+@pytest.mark.parametrize("n,d", [(4, 65536), (3, 10001), (16, 5)])
+def test_identity_compressor(n, d):
+    rng = np.random.default_rng(d)
+    p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, B.NONE)
+    run_pair(p, rand_grads(d, n, d, 10, scale=0.3), label="none")
+    assert all(p.exact[s] for s in ("theta", "m", "v", "vhat"))
+    p.close()
+
+
+# ------------------------------------------------------------------------------------------- hand-derived case
+@pytest.mark.parametrize("eps_mode,key", [(B.EPS_IN_SQRT, "theta_eps_in"), (B.EPS_OUT_SQRT, "theta_eps_out")])
+def test_worked_example_on_gpu(eps_mode, key):
+    with open(os.path.join(HERE, "golden", "worked_example_d8.json")) as f:
+        G = json.load(f)
+    for comp, part in ((B.TOPK, G["topk"]), (B.BLOCKSIGN, G["blocksign"])):
+        kw = dict(k=part["k"]) if comp == B.TOPK else dict(block_offsets=part["block_offsets"])
+        gpu = B.Compams(G["n"], G["d"], torch.tensor(G["theta1"], dtype=torch.float32), compressor=comp,
+                        eps_mode=eps_mode, **kw)
+        for t in range(2):
+            gpu.compams_step(torch.tensor(G["g"][t], dtype=torch.float32).cuda(), G["lr"])
+            torch.cuda.synchronize()
+            assert np.array_equal(gpu.compams_state("e").cpu().numpy(), np.array(part["e"][t], np.float32))
+            np.testing.assert_allclose(gpu.compams_state("theta").cpu().numpy(), part[key][t], rtol=2e-6, atol=0)
+            if comp == B.TOPK:
+                assert gpu.compams_state("last_idx").cpu().tolist() == part["idx"][t]
+            else:
+                assert np.array_equal(gpu.compams_state("last_scales").cpu().numpy(), np.array(part["mu"][t], np.float32))
+                bits = gpu.compams_state("last_signbits").cpu().numpy()[:, 0]
+                assert [[(int(bits[i]) >> j) & 1 for j in range(8)] for i in range(2)] == part["neg"][t]
+        gpu.close()
+
+
+# ------------------------------------------------------------------------------------------- resume
+def test_keep_state_resumes_bit_exactly():
+    n, d, k = 2, 30000, 300
+    gs = rand_grads(21, n, d, 6)
+    a = B.Compams(n, d, torch.zeros(d), compressor=B.TOPK, k=k)
+    for g in gs[:3]:
+        gp = torch.zeros((n, a.ld)); gp[:, :d] = torch.from_numpy(g); a.compams_step(gp.cuda(), 1e-3)
+    st = {s: a.compams_state(s).clone() for s in ("m", "v", "vhat", "e")}
+    b = B.Compams(n, d, a.compams_state("theta").clone(), compressor=B.TOPK, k=k, state=st)
+    for g in gs[3:]:
+        gp = torch.zeros((n, a.ld)); gp[:, :d] = torch.from_numpy(g)
+        a.compams_step(gp.cuda(), 1e-3); b.compams_step(gp.cuda(), 1e-3)
+    torch.cuda.synchronize()
+    for s in ("theta", "m", "v", "vhat", "e", "last_idx"):
+        assert torch.equal(a.compams_state(s), b.compams_state(s)), s
+    a.close(); b.close()
