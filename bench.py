@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the COMP-AMS optimizer step on one MI355X.
+
+A "step" is one call of compams_step(): all n workers' error-feedback compression, the worker-ordered
+average and the AMSGrad update, on gradients that already sit in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+The default workload is the one the headline metric is quoted on: n = 16 workers, d = 11 181 642
+(ResNet-18-shaped), top-k with k/d = 1 %.  Gradients are seeded synthetic data (a distinct pre-generated
+buffer per step, so the residuals evolve as they would in training).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(w, comp):
+    """Minimum bytes one step must move (fp32): per worker-coordinate read g, read e, write e; per coordinate
+    read+write theta, m, v, vhat; plus writing and reading the compressed messages."""
+    n, d = w.n, w.d
+    dense = 12 * n * d + 32 * d
+    if comp == "topk":
+        return dense + 16 * n * w.k
+    if comp == "blocksign":
+        M = len(w.block_offsets()) - 1
+        return dense + 2 * n * (d // 8 + 4 * M)
+    return 4 * n * d + 32 * d  # identity: g is read once, e does not exist
+
+
+def dominant_kernel(comp):
+    """(kernel slot name, algorithmic bytes per launch as a function of n, d)."""
+    if comp == "topk":
+        return "topk_pass_a", lambda n, d: 12 * n * d      # read g, read e, write x in place of e
+    if comp == "blocksign":
+        return "bs_pass1", lambda n, d: 12 * n * d
+    return "none_amsgrad", lambda n, d: 4 * n * d + 32 * d
+
+
+def load_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 3 and parts[0] == "hbm_bytes_per_launch" and parts[1] == kernel:
+            return float(parts[2])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="r18_topk1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for the cpu_baseline leg")
+    ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--no-predict", action="store_true", help="ablation: re-read the row instead of guessing")
+    ap.add_argument("--force-dense", action="store_true", help="ablation: no candidate lists at all")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the n workers are rows of one buffer); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2205_05632_amd import binding as B
+    from paper_2205_05632_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = W.get(args.workload)
+    comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE}[w.compressor]
+    ctx = B.Compams(w.n, w.d, W.theta0(w, dev), compressor=comp, k=w.k, block_offsets=w.block_offsets(), device=dev)
+    if args.no_predict:
+        ctx.set_option(B.OPT_PREDICT, 0)
+    if args.force_dense:
+        ctx.set_option(B.OPT_FORCE_DENSE, 1)
+
+    total = args.warmup + args.steps
+    scale = W.coordinate_scale(w, dev)
+    grads = [W.gradients(w, t, device=dev, ld=ctx.ld, scale=scale) for t in range(total)]
+    torch.cuda.synchronize()
+
+    for t in range(args.warmup):
+        ctx.compams_step(grads[t], w.lr)
+    # timed region: per-kernel HIP events ride along on the step's stream (their cost is part of the time)
+    ctx.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.warmup, total):
+        ctx.compams_step(grads[t], w.lr)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    sec = t1 - t0
+    ms_per_step = sec / args.steps * 1e3
+    steps_per_s = args.steps / sec
+
+    bmin = algorithmic_bytes(w, w.compressor)
+    kname, kbytes = dominant_kernel(w.compressor)
+    k_ms, k_launches = prof[kname]
+    k_avg_s = k_ms / k_launches * 1e-3
+    k_gbps = kbytes(w.n, w.d) / k_avg_s / 1e9
+    traffic = load_traffic(w.name, kname)
+    kernel_sum_ms = sum(ms for ms, _ in prof.values()) / args.steps
+
+    counters = None
+    if comp == B.TOPK:
+        c = ctx.compams_state("counters").cpu()
+        counters = {"dense_rereads_per_row_last_step": c[:, 0].tolist(),
+                    "candidates_per_row_last_step": c[:, 1].tolist()}
+    if args.kernels:
+        for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+            print(f"  {name:16s} {ms / cnt * 1e3:9.1f} us/launch  x{cnt}", file=sys.stderr)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import compams_oracle as O
+        ocomp = {"topk": O.TOPK, "blocksign": O.BLOCKSIGN, "none": O.NONE}[w.compressor]
+        orc = O.Oracle(w.n, w.d, W.theta0(w, dev).cpu().numpy(), compressor=ocomp, k=w.k,
+                       block_offsets=w.block_offsets())
+        host = [grads[t][:, : w.d].cpu().contiguous().numpy() for t in range(args.cpu_steps)]
+        c0 = time.perf_counter()
+        for g in host:
+            orc.step(g, w.lr)
+        c1 = time.perf_counter()
+        cpu = {"value": args.cpu_steps / (c1 - c0), "unit": "steps/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {args.cpu_steps} steps of the same workload and inputs, single thread"}
+        orc.close()
+
+    out = {
+        "metric": "compressed-AMSGrad steps/sec and HBM GB/s (% of peak), n=16, d=11.2M, top-k 1%",
+        "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "d": w.d, "compressor": w.compressor, "k": w.k,
+                   "num_blocks": (len(w.block_offsets()) - 1) if w.compressor == "blocksign" else 0,
+                   "predict": not args.no_predict, "force_dense": args.force_dense},
+        "hbm_gbps": bmin / (sec / args.steps) / 1e9,
+        "hbm_frac_of_peak": bmin / (sec / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "algorithmic_bytes_per_step": bmin,
+        "kernel_ms_per_step": kernel_sum_ms,
+        "roofline": {"bound": "hbm", "kernel": kname, "achieved": k_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": k_gbps / HBM_PEAK_GBPS, "traffic": traffic,
+                     "avg_launch_us": k_avg_s * 1e6, "algorithmic_bytes_per_launch": kbytes(w.n, w.d)},
+        "kernels_us_per_step": {k_: v_[0] / args.steps * 1e3 for k_, v_ in prof.items()},
+        "topk_counters": counters,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -198,6 +198,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     ctx->tkopt.predict = 1;
     ctx->tkopt.force_dense = 0;
     ctx->tkopt.first_pass_emits = 0;
+    ctx->tkopt.dbg = 0;
     // control blocks, counters, histograms and chunk tables start at zero; lists need no initial value
     ok(fill_u32(reinterpret_cast<uint32_t*>(w), lay.cand / 4, 0u, s0));
     ok(fill_u32(reinterpret_cast<uint32_t*>(w + lay.idx), (lay.total - lay.idx) / 4, 0u, s0));

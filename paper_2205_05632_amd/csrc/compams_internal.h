@@ -58,6 +58,7 @@ struct TopkOptions {
   uint32_t predict;        // 1: carry the threshold bucket over to the next step's first pass
   uint32_t force_dense;    // 1: never build a candidate list (test / ablation)
   uint32_t first_pass_emits;  // set per step by the host: this step's first pass was the emitting variant
+  uint32_t dbg;
 };
 
 struct TopkWorkspace {

@@ -18,6 +18,7 @@
 // order; segments are placed by an integer atomic cursor, so their physical order varies from run to
 // run, but nothing that is output depends on it.  No floating-point atomics are used anywhere.
 
+#include <cstdlib>
 #include "compams_device.h"
 #include "compams_internal.h"
 
@@ -46,85 +47,148 @@ __device__ __forceinline__ void hist4(uint32_t* lh, const Quad& q, uint32_t& zer
   zeros += z;
 }
 
-// Emit the flagged entries of one round in (lane, slot) order starting at position `at`; returns how many.
-__device__ __forceinline__ uint32_t emit_round(uint2* out, uint32_t at, uint32_t j, const uint32_t bits[4],
-                                               const bool flag[4]) {
+// Number of flagged entries of one round, and this lane's position among them in (lane, slot) order.
+struct RoundRank {
+  uint32_t total;
+  uint32_t below;
+};
+__device__ __forceinline__ RoundRank rank_round(const bool flag[4]) {
   const uint64_t b0 = ballot64(flag[0]), b1 = ballot64(flag[1]), b2 = ballot64(flag[2]), b3 = ballot64(flag[3]);
-  const uint32_t total = popc64(b0) + popc64(b1) + popc64(b2) + popc64(b3);
-  if (total == 0) return 0;
-  uint32_t pos = at + count_below(b0) + count_below(b1) + count_below(b2) + count_below(b3);
-#pragma unroll
-  for (int s = 0; s < 4; ++s)
-    if (flag[s]) out[pos++] = make_uint2(j + s, bits[s]);
-  return total;
+  RoundRank rr;
+  rr.total = popc64(b0) + popc64(b1) + popc64(b2) + popc64(b3);
+  rr.below = rr.total ? count_below(b0) + count_below(b1) + count_below(b2) + count_below(b3) : 0;
+  return rr;
 }
 
-template <bool PRED, bool FULL>
-__device__ __forceinline__ void pass_a_chunk(const float* __restrict__ gr, float* __restrict__ er, uint32_t d,
-                                             uint32_t c, uint32_t* lh, uint32_t& zeros, bool pred, uint32_t bg,
-                                             TopkRow* rowp, uint2* candr, uint32_t cap, uint2* descr) {
+// Candidate entries of the chunk a wavefront is walking are first staged in LDS (kStage entries per
+// wavefront) so that the chunk's segment can be allocated with one atomic once its size is known and
+// then written with coalesced stores.  A chunk with more candidates than that is re-read instead.
+constexpr int kStage = 512;
+
+__device__ __forceinline__ void stage_round(uint2* stage, uint32_t& n, uint32_t j, const uint32_t bits[4],
+                                            const bool flag[4]) {
+  const RoundRank rr = rank_round(flag);
+  if (rr.total == 0) return;
+  uint32_t pos = n + rr.below;
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+    if (flag[s]) {
+      if (pos < static_cast<uint32_t>(kStage)) stage[pos] = make_uint2(j + s, bits[s]);
+      ++pos;
+    }
+  n += rr.total;
+}
+
+// Allocate the chunk's segment and write it: from the staging area if everything fitted there, else by
+// reading the chunk's (already stored) corrected gradients again.
+__device__ __forceinline__ void flush_chunk(const uint2* stage, uint32_t cnt, const float* __restrict__ er, uint32_t d,
+                                            uint32_t c, uint32_t thr_bucket, TopkRow* rowp, uint2* candr,
+                                            uint32_t cap, uint2* descr) {
   const uint32_t lane = lane_id();
-  const uint32_t base = c * kChunk + lane * 4;
-  float4 xs[PRED ? kRounds : 1];
-  uint32_t cnt = 0;
-#pragma unroll
-  for (int r = 0; r < kRounds; ++r) {
-    const uint32_t j = base + r * 256;
-    const bool in = FULL || j < d;
-    float4 gv = make_float4(0.f, 0.f, 0.f, 0.f), ev = gv;
-    if (in) {
-      gv = *reinterpret_cast<const float4*>(gr + j);
-      ev = *reinterpret_cast<const float4*>(er + j);
-    }
-    float4 x = make_float4(ev.x + gv.x, ev.y + gv.y, ev.z + gv.z, ev.w + gv.w);
-    Quad q;
-    q.ok[0] = in; q.ok[1] = FULL || j + 1 < d; q.ok[2] = FULL || j + 2 < d; q.ok[3] = FULL || j + 3 < d;
-    if (!FULL) {  // columns >= d keep what they held
-      if (!q.ok[1]) x.y = ev.y;
-      if (!q.ok[2]) x.z = ev.z;
-      if (!q.ok[3]) x.w = ev.w;
-    }
-    if (in) *reinterpret_cast<float4*>(er + j) = x;
-    q.key[0] = key_of_bits(__float_as_uint(x.x)); q.key[1] = key_of_bits(__float_as_uint(x.y));
-    q.key[2] = key_of_bits(__float_as_uint(x.z)); q.key[3] = key_of_bits(__float_as_uint(x.w));
-    hist4(lh, q, zeros);
-    if constexpr (PRED) {
-      xs[r] = x;
-      if (pred) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) cnt += popc64(ballot64(q.ok[s] && (q.key[s] >> kL0Shift) >= bg));
-      }
-    }
-  }
-  if constexpr (PRED) if (pred) {
-    uint32_t off = 0;
-    if (cnt) {
-      if (lane == 0) off = atomicAdd(&rowp->cursor, cnt);
-      off = first_lane(off);
-      if (off + cnt <= cap) {
+  uint32_t off = 0;
+  if (cnt) {
+    if (lane == 0) off = atomicAdd(&rowp->cursor, cnt);
+    off = first_lane(off);
+    if (off + cnt <= cap) {  // otherwise the row's list has overflowed and will not be used
+      if (cnt <= static_cast<uint32_t>(kStage)) {
+        for (uint32_t q = lane; q < cnt; q += 64) candr[off + q] = stage[q];
+      } else {
         uint32_t at = off;
-#pragma unroll
         for (int r = 0; r < kRounds; ++r) {
-          const uint32_t j = base + r * 256;
-          const float4 x = xs[r];
+          const uint32_t j = c * kChunk + r * 256 + lane * 4;
+          float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (j < d) x = *reinterpret_cast<const float4*>(er + j);
           const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
                                     __float_as_uint(x.w)};
           bool flag[4];
 #pragma unroll
+          for (int s = 0; s < 4; ++s) flag[s] = j + s < d && (key_of_bits(bits[s]) >> kL0Shift) >= thr_bucket;
+          const RoundRank rr = rank_round(flag);
+          uint32_t pos = at + rr.below;
+#pragma unroll
           for (int s = 0; s < 4; ++s)
-            flag[s] = (FULL || j + s < d) && (key_of_bits(bits[s]) >> kL0Shift) >= bg;
-          at += emit_round(candr, at, j, bits, flag);
+            if (flag[s]) {
+              if (pos < off + cnt) candr[pos] = make_uint2(j + s, bits[s]);
+              ++pos;
+            }
+          at += rr.total;
         }
       }
     }
-    if (lane == 0) descr[c] = make_uint2(off, cnt);
   }
+  if (lane == 0) descr[c] = make_uint2(off, cnt);
+}
+
+typedef float f4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream(const float* p) {
+  const f4v v = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream(float* p, const float4& x) {
+  f4v v;
+  v.x = x.x; v.y = x.y; v.z = x.z; v.w = x.w;
+  __builtin_nontemporal_store(v, reinterpret_cast<f4v*>(p));
+}
+
+constexpr int kBatch = 4;  // rounds whose loads are issued together
+
+template <bool PRED, bool FULL>
+__device__ __forceinline__ void pass_a_chunk(const float* __restrict__ gr, float* __restrict__ er, uint32_t d,
+                                             uint32_t c, uint32_t* lh, uint32_t& zeros, bool pred, uint32_t bg,
+                                             TopkRow* rowp, uint2* candr, uint32_t cap, uint2* descr, uint2* stage, uint32_t dbg) {
+  const uint32_t lane = lane_id();
+  const uint32_t base = c * kChunk + lane * 4;
+  uint32_t cnt = 0;
+#pragma unroll 1
+  for (int r0 = 0; r0 < kRounds; r0 += kBatch) {
+    float4 gv[kBatch], ev[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const uint32_t j = base + (r0 + u) * 256;
+      gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      ev[u] = gv[u];
+      if (FULL || j < d) {
+        gv[u] = load_stream(gr + j);
+        ev[u] = load_stream(er + j);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const uint32_t j = base + (r0 + u) * 256;
+      const bool in = FULL || j < d;
+      float4 x = make_float4(ev[u].x + gv[u].x, ev[u].y + gv[u].y, ev[u].z + gv[u].z, ev[u].w + gv[u].w);
+      Quad q;
+      q.ok[0] = in; q.ok[1] = FULL || j + 1 < d; q.ok[2] = FULL || j + 2 < d; q.ok[3] = FULL || j + 3 < d;
+      if (!FULL) {  // columns >= d keep what they held
+        if (!q.ok[1]) x.y = ev[u].y;
+        if (!q.ok[2]) x.z = ev[u].z;
+        if (!q.ok[3]) x.w = ev[u].w;
+      }
+      if (in) store_stream(er + j, x);
+      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
+                                __float_as_uint(x.w)};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) q.key[s] = key_of_bits(bits[s]);
+      if (!(dbg & 1)) hist4(lh, q, zeros);
+      if constexpr (PRED) {
+        if (pred && !(dbg & 2)) {
+          bool flag[4];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) flag[s] = q.ok[s] && (q.key[s] >> kL0Shift) >= bg;
+          stage_round(stage, cnt, j, bits, flag);
+        }
+      }
+    }
+  }
+  if constexpr (PRED)
+    if (pred) flush_chunk(stage, cnt, er, d, c, bg, rowp, candr, cap, descr);
 }
 
 template <bool PRED>
 __global__ __launch_bounds__(kWG) void k_topk_pass_a(const float* __restrict__ g, float* __restrict__ e,
                                                       Geometry geo, TopkWorkspace ws, TopkOptions opt) {
   __shared__ uint32_t lh[kNB0];
+  __shared__ uint2 stage_all[PRED ? kWaves * kStage : 1];
   const uint32_t row = blockIdx.y;
   for (int b = threadIdx.x; b < kNB0; b += kWG) lh[b] = 0;
   __syncthreads();
@@ -140,13 +204,14 @@ __global__ __launch_bounds__(kWG) void k_topk_pass_a(const float* __restrict__ g
   uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
   uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
   const uint32_t wave = threadIdx.x >> 6;
+  uint2* stage = stage_all + (PRED ? wave * kStage : 0);
   const uint32_t stride = gridDim.x * kWaves;
   uint32_t zeros = 0;
   for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
     if ((c + 1) * static_cast<uint64_t>(kChunk) <= geo.d)
-      pass_a_chunk<PRED, true>(gr, er, geo.d, c, lh, zeros, pred, bg, rowp, candr, opt.cap, descr);
+      pass_a_chunk<PRED, true>(gr, er, geo.d, c, lh, zeros, pred, bg, rowp, candr, opt.cap, descr, stage, opt.dbg);
     else
-      pass_a_chunk<PRED, false>(gr, er, geo.d, c, lh, zeros, pred, bg, rowp, candr, opt.cap, descr);
+      pass_a_chunk<PRED, false>(gr, er, geo.d, c, lh, zeros, pred, bg, rowp, candr, opt.cap, descr, stage, opt.dbg);
   }
   if (zeros && lane_id() == 0) atomicAdd(&lh[0], zeros);
   __syncthreads();
@@ -242,6 +307,7 @@ __global__ __launch_bounds__(kWG) void k_topk_resolve0(Geometry geo, TopkWorkspa
 // Second dense pass (rows in kModeNeedB only): candidate list = entries with level-0 bucket >= bstar.
 __global__ __launch_bounds__(kWG) void k_topk_pass_b(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                       TopkOptions opt) {
+  __shared__ uint2 stage_all[kWaves * kStage];
   const uint32_t row = blockIdx.y;
   TopkRow* rowp = ws.rows + row;
   if (rowp->mode != kModeNeedB) return;
@@ -250,44 +316,25 @@ __global__ __launch_bounds__(kWG) void k_topk_pass_b(const float* __restrict__ e
   uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
   uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  uint2* stage = stage_all + wave * kStage;
   const uint32_t stride = gridDim.x * kWaves;
   for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
     const uint32_t base = c * kChunk + lane * 4;
-    float4 xs[kRounds];
     uint32_t cnt = 0;
-#pragma unroll
+#pragma unroll 4
     for (int r = 0; r < kRounds; ++r) {
       const uint32_t j = base + r * 256;
       float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
       if (j < geo.d) x = *reinterpret_cast<const float4*>(er + j);
-      xs[r] = x;
       const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
                                 __float_as_uint(x.w)};
+      bool flag[4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
-        cnt += popc64(ballot64(j + s < geo.d && (key_of_bits(bits[s]) >> kL0Shift) >= bstar));
+      for (int s = 0; s < 4; ++s) flag[s] = j + s < geo.d && (key_of_bits(bits[s]) >> kL0Shift) >= bstar;
+      stage_round(stage, cnt, j, bits, flag);
     }
-    uint32_t off = 0;
-    if (cnt) {
-      if (lane == 0) off = atomicAdd(&rowp->cursor, cnt);
-      off = first_lane(off);
-      uint32_t at = off;
-      // fits by construction (the histogram counted exactly these entries); the test only keeps a logic error
-      // elsewhere from turning into a write outside the list
-      if (off + cnt <= opt.cap)
-#pragma unroll
-      for (int r = 0; r < kRounds; ++r) {
-        const uint32_t j = base + r * 256;
-        const float4 x = xs[r];
-        const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
-                                  __float_as_uint(x.w)};
-        bool flag[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) flag[s] = j + s < geo.d && (key_of_bits(bits[s]) >> kL0Shift) >= bstar;
-        at += emit_round(candr, at, j, bits, flag);
-      }
-    }
-    if (lane == 0) descr[c] = make_uint2(off, cnt);
+    // fits by construction: the level-0 histogram counted exactly these entries
+    flush_chunk(stage, cnt, er, geo.d, c, bstar, rowp, candr, opt.cap, descr);
   }
 }
 
@@ -541,7 +588,7 @@ __global__ __launch_bounds__(kWG) void k_topk_emit(float* __restrict__ e, Geomet
           if (pos < geo.k && en.j[s] < geo.d) {  // always true when the counts are consistent
             idx[pos] = static_cast<int32_t>(en.j[s]);
             val[pos] = __uint_as_float(en.bits[s]);
-            er[en.j[s]] = 0.0f;
+            if (!(opt.dbg & 8)) er[en.j[s]] = 0.0f;
           }
           ++pos;
         }
@@ -627,13 +674,16 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   TopkOptions opt = opt_in;
   opt.first_pass_emits = first_pass_may_predict ? 1u : 0u;
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
-  const dim3 grid_rows(G, geo.n), wg(kWG);
+  uint32_t GA = G;
+  if (getenv("COMPAMS_TUNE_GA")) GA = atoi(getenv("COMPAMS_TUNE_GA"));
+  if (getenv("COMPAMS_TUNE_DBG")) opt.dbg = atoi(getenv("COMPAMS_TUNE_DBG"));
+  const dim3 grid_rows(G, geo.n), wg(kWG), grid_a(GA, geo.n);
   {
     ScopedSlot s(L, kSlotPassA, stream);
     if (first_pass_may_predict)
-      hipLaunchKernelGGL(k_topk_pass_a<true>, grid_rows, wg, 0, stream, g, e, geo, ws, opt);
+      hipLaunchKernelGGL(k_topk_pass_a<true>, grid_a, wg, 0, stream, g, e, geo, ws, opt);
     else
-      hipLaunchKernelGGL(k_topk_pass_a<false>, grid_rows, wg, 0, stream, g, e, geo, ws, opt);
+      hipLaunchKernelGGL(k_topk_pass_a<false>, grid_a, wg, 0, stream, g, e, geo, ws, opt);
   }
   COMPAMS_CHECK_LAUNCH();
   {
