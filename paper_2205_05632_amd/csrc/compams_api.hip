@@ -45,8 +45,7 @@ void launcher_end(Launcher* L, int slot, hipStream_t stream) {
 namespace {
 
 const char* const kSlotNames[kNumSlots] = {
-    "topk_pass_a", "topk_resolve0", "topk_pass_b", "topk_hist1", "topk_resolve1", "topk_hist2", "topk_resolve2",
-    "topk_count", "topk_scan", "topk_emit", "topk_amsgrad",
+    "topk_pass_a", "topk_level1", "topk_level2", "topk_count", "topk_final",
     "bs_pass1", "bs_finalize", "bs_pass2", "bs_amsgrad", "none_amsgrad"};
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -54,7 +53,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t total;
   // top-k
-  size_t rows, counters, hist0, hist1, hist2, cnt_gt, cnt_eq, sel_off, eq_before, desc, cand, idx, val, tau;
+  size_t rows, counters, hist0, hist1, hist1x, hist2, cnt_gt, cnt_eq, sel_off, eq_before, desc, cand, idx, val, tau;
   // block-sign
   size_t offsets, chunk_block, acc, special, scales, bits;
   uint32_t cap_alloc, num_chunks, words;
@@ -88,6 +87,7 @@ Layout make_layout(const compams_config* c) {
     L.counters = take(n * COMPAMS_COUNTERS_PER_ROW * 4);
     L.hist0 = take(n * kNB0 * 4);
     L.hist1 = take(n * kNB1 * 4);
+    L.hist1x = take(n * 2 * kNB1 * 4);
     L.hist2 = take(n * kNB2 * 4);
     L.cnt_gt = take(n * nc * 4);
     L.cnt_eq = take(n * nc * 4);
@@ -125,9 +125,20 @@ struct compams_ctx {
   BlocksignWorkspace bs;
   int device;
   int64_t steps;
+  bool clear_pending;      // top-k: e still holds x at the coordinates selected by the last step
+  hipStream_t last_stream; // stream of the last step
   bool profiling;
   Launcher launcher;
 };
+
+// Top-k leaves the zeroing of the residual at the selected coordinates to the next step's first pass.
+// Before anybody else looks at e, the zeros are written for real (on the stream of the last step).
+static hipError_t settle_residuals(compams_ctx* ctx) {
+  if (ctx->cfg.compressor != COMPAMS_TOPK || !ctx->clear_pending) return hipSuccess;
+  const hipError_t err = topk_apply_clear(ctx->geo, ctx->tk, ctx->cfg.e, ctx->last_stream);
+  if (err == hipSuccess) ctx->clear_pending = false;
+  return err;
+}
 
 extern "C" {
 
@@ -163,6 +174,8 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
   ctx->cfg.block_offsets = nullptr;  // the host array is the caller's; a device copy is made below
   ctx->lay = lay;
   ctx->steps = 0;
+  ctx->clear_pending = false;
+  ctx->last_stream = nullptr;
   ctx->profiling = false;
   if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return COMPAMS_HIP_ERROR; }
   Geometry& geo = ctx->geo;
@@ -184,6 +197,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     t.counters = reinterpret_cast<uint32_t*>(w + lay.counters);
     t.hist0 = reinterpret_cast<uint32_t*>(w + lay.hist0);
     t.hist1 = reinterpret_cast<uint32_t*>(w + lay.hist1);
+    t.hist1x = reinterpret_cast<uint32_t*>(w + lay.hist1x);
     t.hist2 = reinterpret_cast<uint32_t*>(w + lay.hist2);
     t.cnt_gt = reinterpret_cast<uint32_t*>(w + lay.cnt_gt);
     t.cnt_eq = reinterpret_cast<uint32_t*>(w + lay.cnt_eq);
@@ -197,8 +211,6 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     ctx->tkopt.cap = lay.cap_alloc;
     ctx->tkopt.predict = 1;
     ctx->tkopt.force_dense = 0;
-    ctx->tkopt.first_pass_emits = 0;
-    ctx->tkopt.dbg = 0;
     // control blocks, counters, histograms and chunk tables start at zero; lists need no initial value
     ok(fill_u32(reinterpret_cast<uint32_t*>(w), lay.cand / 4, 0u, s0));
     ok(fill_u32(reinterpret_cast<uint32_t*>(w + lay.idx), (lay.total - lay.idx) / 4, 0u, s0));
@@ -258,7 +270,9 @@ int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream) {
   try {
     if (c.compressor == COMPAMS_TOPK) {
       const bool may_predict = ctx->steps > 0 && ctx->tkopt.predict && !ctx->tkopt.force_dense;
-      err = topk_step(ctx->geo, ctx->tk, ctx->tkopt, ap, g, c.e, c.theta, c.m, c.v, c.vhat, may_predict, stream, L);
+      err = topk_step(ctx->geo, ctx->tk, ctx->tkopt, ap, g, c.e, c.theta, c.m, c.v, c.vhat, may_predict,
+                      ctx->clear_pending, stream, L);
+      ctx->clear_pending = true;
     } else if (c.compressor == COMPAMS_BLOCKSIGN) {
       err = blocksign_step(ctx->geo, ctx->bs, ap, g, c.e, c.theta, c.m, c.v, c.vhat, stream, L);
     } else {
@@ -267,6 +281,7 @@ int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream) {
   } catch (...) {
     return COMPAMS_HIP_ERROR;
   }
+  ctx->last_stream = stream;
   if (err != hipSuccess || (L && L->failed)) return COMPAMS_HIP_ERROR;
   ++ctx->steps;
   return COMPAMS_OK;
@@ -286,6 +301,7 @@ int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* co
     case COMPAMS_STATE_VHAT: p = c.vhat; cnt = d; break;
     case COMPAMS_STATE_E:
       if (!c.e) return COMPAMS_BAD_STATE;
+      if (settle_residuals(ctx) != hipSuccess) return COMPAMS_HIP_ERROR;
       p = c.e; cnt = n * c.ld; break;
     case COMPAMS_STATE_LAST_IDX:
       if (!tk) return COMPAMS_BAD_STATE;
@@ -363,12 +379,17 @@ int compams_profile_read(compams_ctx* ctx, int cap, const char** names, double* 
 
 int compams_destroy(compams_ctx* ctx) {
   if (!ctx) return COMPAMS_INVALID_ARG;
+  int status = COMPAMS_OK;
+  if (ctx->clear_pending) {  // hand e back to the caller in its settled form
+    if (settle_residuals(ctx) != hipSuccess || hipStreamSynchronize(ctx->last_stream) != hipSuccess)
+      status = COMPAMS_HIP_ERROR;
+  }
   Launcher& L = ctx->launcher;
   for (int s = 0; s < kNumSlots; ++s)
     for (const Launcher::Pair& p : L.pending[s]) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   for (const Launcher::Pair& p : L.pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
   delete ctx;
-  return COMPAMS_OK;
+  return status;
 }
 
 const char* compams_strerror(int status) {

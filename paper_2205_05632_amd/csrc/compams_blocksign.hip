@@ -286,17 +286,6 @@ __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometr
   }
 }
 
-__device__ __forceinline__ void ams_update(float gb, float& th, float& mm, float& vv, float& vh, const AmsParams& p) {
-  const float mj = p.beta1 * mm + p.one_minus_beta1 * gb;
-  const float vj = p.beta2 * vv + p.one_minus_beta2 * (gb * gb);
-  const float vhj = (vh < vj) ? vj : vh;
-  const float den = p.eps_out ? sqrtf(vhj) + p.eps : sqrtf(vhj + p.eps);
-  mm = mj;
-  vv = vj;
-  vh = vhj;
-  th = th - p.lr * (mj / den);
-}
-
 // ---------------------------------------------------------------------------------------------
 // Server lines for sign/scale messages: gbar_j = (sum_i s_ij * mu_i,b(j)) / n in worker order, then
 // AMSGrad.  One wavefront per chunk of coordinates.

@@ -56,4 +56,16 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* scratc
   return before + incl - v;
 }
 
+// 128-bit streaming (non-temporal) access for data that is touched once per step.
+typedef float f4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream4(const float* p) {
+  const f4v v = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream4(float* p, const float4& x) {
+  f4v v;
+  v.x = x.x; v.y = x.y; v.z = x.z; v.w = x.w;
+  __builtin_nontemporal_store(v, reinterpret_cast<f4v*>(p));
+}
+
 }  // namespace compams

@@ -49,16 +49,16 @@ struct TopkRow {
   uint32_t r;           // how many keys equal to tau are selected
   uint32_t ties;        // how many keys equal tau
   uint32_t take_all_ties;  // r == ties: no tie ranking needed
-  uint32_t pad[4];
+  uint32_t level1_done;    // bits 30..9 of the threshold key are known (prefix1 / need are valid)
+  uint32_t ticket[4];      // "last workgroup of the row" counters of kernels 1..4; zero between launches
+  uint32_t pad[15];
 };
-static_assert(sizeof(TopkRow) == 64, "TopkRow layout");
+static_assert(sizeof(TopkRow) == 128, "TopkRow layout");
 
 struct TopkOptions {
   uint32_t cap;            // candidate entries per row
   uint32_t predict;        // 1: carry the threshold bucket over to the next step's first pass
   uint32_t force_dense;    // 1: never build a candidate list (test / ablation)
-  uint32_t first_pass_emits;  // set per step by the host: this step's first pass was the emitting variant
-  uint32_t dbg;
 };
 
 struct TopkWorkspace {
@@ -66,6 +66,7 @@ struct TopkWorkspace {
   uint32_t* counters;   // n * COMPAMS_COUNTERS_PER_ROW
   uint32_t* hist0;      // n * kNB0
   uint32_t* hist1;      // n * kNB1
+  uint32_t* hist1x;     // n * 2 * kNB1 : level-1 histograms of the two buckets tracked by the first pass
   uint32_t* hist2;      // n * kNB2
   uint32_t* cnt_gt;     // n * num_chunks : keys above tau per chunk
   uint32_t* cnt_eq;     // n * num_chunks : keys equal to tau per chunk
@@ -93,6 +94,19 @@ struct AmsParams {
   int eps_out;  // 1: epsilon outside the square root
 };
 
+// Moment and parameter lines of Algorithm 2 for one coordinate: every product, sum, square root and
+// quotient is a separately rounded fp32 operation (the library is built without contraction).
+__device__ __forceinline__ void ams_update(float gb, float& th, float& mm, float& vv, float& vh, const AmsParams& p) {
+  const float mj = p.beta1 * mm + p.one_minus_beta1 * gb;
+  const float vj = p.beta2 * vv + p.one_minus_beta2 * (gb * gb);
+  const float vhj = (vh < vj) ? vj : vh;
+  const float den = p.eps_out ? sqrtf(vhj) + p.eps : sqrtf(vhj + p.eps);
+  mm = mj;
+  vv = vj;
+  vh = vhj;
+  th = th - p.lr * (mj / den);
+}
+
 struct Geometry {
   uint32_t n;
   uint32_t d;
@@ -105,8 +119,7 @@ struct Geometry {
 
 // Kernel slots for optional timing.
 enum KernelSlot {
-  kSlotPassA = 0, kSlotResolve0, kSlotPassB, kSlotHist1, kSlotResolve1, kSlotHist2, kSlotResolve2,
-  kSlotCount, kSlotScan, kSlotEmit, kSlotTopkAms,
+  kSlotPassA = 0, kSlotLevel1, kSlotLevel2, kSlotCount, kSlotTopkFinal,
   kSlotBsPass1, kSlotBsFinal, kSlotBsPass2, kSlotBsAms,
   kSlotNoneAms, kNumSlots
 };
@@ -116,7 +129,8 @@ struct Launcher;  // host-side helper that brackets launches with events (compam
 // Host-side launch entry points, one per compressor (defined next to their kernels).
 hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
                      const float* g, float* e, float* theta, float* m, float* v, float* vhat,
-                     bool first_pass_may_predict, hipStream_t stream, Launcher* L);
+                     bool first_pass_may_predict, bool clear_pending, hipStream_t stream, Launcher* L);
+hipError_t topk_apply_clear(const Geometry& geo, const TopkWorkspace& ws, float* e, hipStream_t stream);
 hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, const float* g,
                           float* e, float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L);
 hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, float* theta, float* m, float* v,
@@ -141,6 +155,16 @@ inline uint32_t groups_per_row(uint32_t n, uint32_t num_chunks) {
   const uint32_t target = 256 * 8;  // workgroups in flight over the whole grid
   uint32_t g = (target + n - 1) / n;
   const uint32_t max_g = (num_chunks + kWaves - 1) / kWaves;  // one chunk per wavefront at least
+  if (g > max_g) g = max_g;
+  if (g < 1) g = 1;
+  return g;
+}
+
+// The first pass streams best with about one workgroup per compute unit (fewer concurrent address
+// streams keep DRAM pages open longer); measured on MI355X.
+inline uint32_t groups_first_pass(uint32_t n, uint32_t num_chunks) {
+  uint32_t g = (256 + n - 1) / n;
+  const uint32_t max_g = (num_chunks + kWaves - 1) / kWaves;
   if (g > max_g) g = max_g;
   if (g < 1) g = 1;
   return g;

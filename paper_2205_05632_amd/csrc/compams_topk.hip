@@ -1,34 +1,42 @@
-// Top-k with error feedback (Definition 1 inside the worker lines of Algorithm 2) for gfx950.
+// Top-k with error feedback (Definition 1 inside the worker lines of Algorithm 2) and the server
+// lines for sparse messages, for gfx950.
 //
 // Per worker row:  x = e + g is stored in place of e, the k coordinates of largest magnitude key
 // (fp32 pattern without the sign; ties to the lower coordinate) are written out as ascending
-// (coordinate, value) lists and their residual entries are set to zero.
+// (coordinate, value) lists, and the residual at those coordinates becomes zero.
 //
-// The k-th largest key is found by a three-level radix select (12 + 10 + 9 key bits).  The level-0
-// histogram is built by the same pass that forms x.  Everything after it works on a candidate list
-// (all entries whose level-0 bucket is at least the threshold bucket), which is written
-//   * by the first pass itself when the previous step's threshold bucket is carried over as a guess
-//     and turns out to be low enough (no second read of the row), or
-//   * by one more read of the row once the exact bucket is known, or
-//   * not at all when it would not fit (rows dominated by equal keys): then every later pass reads
-//     the row itself.
-// All three routes give the same result; the guess only decides how many bytes move.
+// Five kernels per step:
+//   1 first pass   x = e + g -> e, level-0 histogram of the keys (12 bits); when the previous step's
+//                  threshold bucket is carried over as a guess, the same pass also writes the candidate
+//                  list (entries at or above the guessed bucket) and the level-1 histograms of the two
+//                  buckets the threshold is expected in.  The last workgroup of a row to finish finds
+//                  the threshold bucket, checks the guess, and resolves level 1 if it can.
+//   2 level 1      only for rows whose guess failed (or had none): one more read of the row that writes
+//                  the candidate list with the exact bucket and builds the level-1 histogram (10 bits);
+//                  rows that would not fit a list are histogrammed from the row itself.
+//   3 level 2      histogram of the last 9 key bits over the matching candidates; yields the k-th largest
+//                  key tau and how many keys equal to tau are taken.
+//   4 count        per chunk: keys above tau and keys equal to tau; the row's last workgroup turns them
+//                  into exclusive prefixes (positions of every chunk's entries in the output lists).
+//   5 final        per chunk of coordinates: each worker's selected entries are written to its list, then
+//                  added in worker order into an LDS tile of the averaged gradient, then AMSGrad.
+// Zeroing the residual at the selected coordinates is not done by scattered stores: the next step's
+// first pass treats the coordinates in the previous lists as zero while it forms x (and a small kernel
+// applies the zeros when the caller asks for e).
 //
-// Ordering: a candidate list is a set of per-chunk segments.  Each segment is in ascending coordinate
-// order; segments are placed by an integer atomic cursor, so their physical order varies from run to
-// run, but nothing that is output depends on it.  No floating-point atomics are used anywhere.
+// All routes give the same result; the guess only decides how many bytes move.  A candidate list is a
+// set of per-chunk segments, each in ascending coordinate order, placed by an integer atomic cursor:
+// their physical order varies from run to run but nothing that is output depends on it.  No
+// floating-point atomics are used anywhere.
 
 #include <cstdlib>
+
 #include "compams_device.h"
 #include "compams_internal.h"
 
 namespace compams {
 namespace {
 
-// ---------------------------------------------------------------------------------------------
-// First pass: x = e + g -> e, level-0 histogram, optional candidate emission with a guessed bucket.
-// Grid (groups_per_row, n); each wavefront walks chunks wave, wave + stride, ...
-// ---------------------------------------------------------------------------------------------
 struct Quad {
   uint32_t key[4];
   bool ok[4];
@@ -119,113 +127,41 @@ __device__ __forceinline__ void flush_chunk(const uint2* stage, uint32_t cnt, co
   if (lane == 0) descr[c] = make_uint2(off, cnt);
 }
 
-typedef float f4v __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 load_stream(const float* p) {
-  const f4v v = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void store_stream(float* p, const float4& x) {
-  f4v v;
-  v.x = x.x; v.y = x.y; v.z = x.z; v.w = x.w;
-  __builtin_nontemporal_store(v, reinterpret_cast<f4v*>(p));
-}
-
-constexpr int kBatch = 4;  // rounds whose loads are issued together
-
-template <bool PRED, bool FULL>
-__device__ __forceinline__ void pass_a_chunk(const float* __restrict__ gr, float* __restrict__ er, uint32_t d,
-                                             uint32_t c, uint32_t* lh, uint32_t& zeros, bool pred, uint32_t bg,
-                                             TopkRow* rowp, uint2* candr, uint32_t cap, uint2* descr, uint2* stage, uint32_t dbg) {
-  const uint32_t lane = lane_id();
-  const uint32_t base = c * kChunk + lane * 4;
-  uint32_t cnt = 0;
-#pragma unroll 1
-  for (int r0 = 0; r0 < kRounds; r0 += kBatch) {
-    float4 gv[kBatch], ev[kBatch];
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const uint32_t j = base + (r0 + u) * 256;
-      gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-      ev[u] = gv[u];
-      if (FULL || j < d) {
-        gv[u] = load_stream(gr + j);
-        ev[u] = load_stream(er + j);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const uint32_t j = base + (r0 + u) * 256;
-      const bool in = FULL || j < d;
-      float4 x = make_float4(ev[u].x + gv[u].x, ev[u].y + gv[u].y, ev[u].z + gv[u].z, ev[u].w + gv[u].w);
-      Quad q;
-      q.ok[0] = in; q.ok[1] = FULL || j + 1 < d; q.ok[2] = FULL || j + 2 < d; q.ok[3] = FULL || j + 3 < d;
-      if (!FULL) {  // columns >= d keep what they held
-        if (!q.ok[1]) x.y = ev[u].y;
-        if (!q.ok[2]) x.z = ev[u].z;
-        if (!q.ok[3]) x.w = ev[u].w;
-      }
-      if (in) store_stream(er + j, x);
-      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
-                                __float_as_uint(x.w)};
-#pragma unroll
-      for (int s = 0; s < 4; ++s) q.key[s] = key_of_bits(bits[s]);
-      if (!(dbg & 1)) hist4(lh, q, zeros);
-      if constexpr (PRED) {
-        if (pred && !(dbg & 2)) {
-          bool flag[4];
-#pragma unroll
-          for (int s = 0; s < 4; ++s) flag[s] = q.ok[s] && (q.key[s] >> kL0Shift) >= bg;
-          stage_round(stage, cnt, j, bits, flag);
-        }
-      }
-    }
-  }
-  if constexpr (PRED)
-    if (pred) flush_chunk(stage, cnt, er, d, c, bg, rowp, candr, cap, descr);
-}
-
-template <bool PRED>
-__global__ __launch_bounds__(kWG) void k_topk_pass_a(const float* __restrict__ g, float* __restrict__ e,
-                                                      Geometry geo, TopkWorkspace ws, TopkOptions opt) {
-  __shared__ uint32_t lh[kNB0];
-  __shared__ uint2 stage_all[PRED ? kWaves * kStage : 1];
-  const uint32_t row = blockIdx.y;
-  for (int b = threadIdx.x; b < kNB0; b += kWG) lh[b] = 0;
+// ---------------------------------------------------------------------------------------------
+// "Last workgroup of the row": every workgroup of a row takes a ticket when it has finished; the one
+// that draws the last ticket continues with the row-wide step.  No workgroup ever waits for another.
+//
+// Everything the last workgroup reads from the others travels through device-scope atomics (adds,
+// stores) and is read back with device-scope atomic loads: those are performed at the level of the
+// memory hierarchy that all compute units share, so no cache write-back or invalidation is needed
+// (a full device-scope fence would write back and invalidate the whole L2 of the die at every call).
+// Ordering: each wavefront waits until its own atomics have been acknowledged, the workgroup barrier
+// collects all wavefronts, and only then is the ticket drawn.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool last_group_of_row(uint32_t* ticket, uint32_t groups, uint32_t* sh_flag) {
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // this wavefront's atomics have been performed
   __syncthreads();
-  const float* gr = g + static_cast<int64_t>(row) * geo.ld;
-  float* er = e + static_cast<int64_t>(row) * geo.ld;
-  TopkRow* rowp = ws.rows + row;
-  bool pred = false;
-  uint32_t bg = 0;
-  if (PRED) {
-    pred = rowp->pred_valid != 0;
-    bg = rowp->b_guess;
+  if (threadIdx.x == 0) {
+    const uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = (t + 1 == groups);
+    if (last) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next launch
+    *sh_flag = last ? 1u : 0u;
   }
-  uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
-  uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
-  const uint32_t wave = threadIdx.x >> 6;
-  uint2* stage = stage_all + (PRED ? wave * kStage : 0);
-  const uint32_t stride = gridDim.x * kWaves;
-  uint32_t zeros = 0;
-  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
-    if ((c + 1) * static_cast<uint64_t>(kChunk) <= geo.d)
-      pass_a_chunk<PRED, true>(gr, er, geo.d, c, lh, zeros, pred, bg, rowp, candr, opt.cap, descr, stage, opt.dbg);
-    else
-      pass_a_chunk<PRED, false>(gr, er, geo.d, c, lh, zeros, pred, bg, rowp, candr, opt.cap, descr, stage, opt.dbg);
-  }
-  if (zeros && lane_id() == 0) atomicAdd(&lh[0], zeros);
   __syncthreads();
-  uint32_t* gh = ws.hist0 + static_cast<size_t>(row) * kNB0;
-  for (int b = threadIdx.x; b < kNB0; b += kWG) {
-    const uint32_t h = lh[b];
-    if (h) atomicAdd(&gh[b], h);
-  }
+  return *sh_flag != 0;
+}
+
+__device__ __forceinline__ uint32_t load_agent(const uint32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_agent(uint32_t* p, uint32_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Finding the bucket in which a suffix count crosses `need`, by one workgroup of kWG threads.
-// h: NB bucket counts in LDS.  Returns (wave-uniformly, through LDS) the largest s with
-// sum_{b >= s} h[b] >= need, and the count strictly above it.  Requires 1 <= need <= sum h.
+// h: NB bucket counts in LDS.  Returns through out2 the largest s with sum_{b >= s} h[b] >= need and the
+// count strictly above it.  Requires 1 <= need <= sum h.
 // ---------------------------------------------------------------------------------------------
 template <int NB>
 __device__ void find_crossing(const uint32_t* h, uint32_t need, uint32_t* suf /* kWG + 1 */, uint32_t* out2) {
@@ -235,11 +171,11 @@ __device__ void find_crossing(const uint32_t* h, uint32_t need, uint32_t* suf /*
   uint32_t part = 0;
 #pragma unroll
   for (int i = 0; i < PER; ++i) part += h[t * PER + i];
+  __syncthreads();
   suf[t] = part;
   if (t == 0) { suf[kWG] = 0; out2[0] = 0; out2[1] = 0; }
   __syncthreads();
-  // inclusive suffix sums by doubling
-  for (int s = 1; s < kWG; s <<= 1) {
+  for (int s = 1; s < kWG; s <<= 1) {  // inclusive suffix sums by doubling
     const uint32_t add = (t + s < kWG) ? suf[t + s] : 0;
     __syncthreads();
     suf[t] += add;
@@ -260,107 +196,322 @@ __device__ void find_crossing(const uint32_t* h, uint32_t need, uint32_t* suf /*
   __syncthreads();
 }
 
-// Level 0: one workgroup per row.
-__global__ __launch_bounds__(kWG) void k_topk_resolve0(Geometry geo, TopkWorkspace ws, TopkOptions opt) {
-  __shared__ uint32_t h[kNB0];
-  __shared__ uint32_t suf[kWG + 1];
-  __shared__ uint32_t out2[2];
-  const uint32_t row = blockIdx.x;
-  uint32_t* gh = ws.hist0 + static_cast<size_t>(row) * kNB0;
-  for (int b = threadIdx.x; b < kNB0; b += kWG) {
-    h[b] = gh[b];
-    gh[b] = 0;  // ready for the next step
+// Copy a row's global histogram into LDS and clear it for the next step.
+template <int NB>
+__device__ __forceinline__ void take_hist(uint32_t* gh, uint32_t* h) {
+  for (int b = threadIdx.x; b < NB; b += kWG) {
+    h[b] = load_agent(gh + b);
+    gh[b] = 0;
   }
   __syncthreads();
-  find_crossing<kNB0>(h, geo.k, suf, out2);
+}
+
+// bstar and need are passed in (not re-read from the control block): the caller may have written them a
+// moment ago, and a line of the control block read earlier by this compute unit may still sit in its L1.
+__device__ __forceinline__ void resolve_level1(TopkRow* rp, uint32_t bstar, uint32_t need, const uint32_t* h,
+                                               uint32_t* suf, uint32_t* out2) {
+  find_crossing<kNB1>(h, need, suf, out2);
   if (threadIdx.x == 0) {
-    TopkRow* rp = ws.rows + row;
+    rp->prefix1 = (bstar << (kL0Shift - kL1Shift)) | out2[0];
+    rp->need = need - out2[1];
+    rp->level1_done = 1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Kernel 1: first pass.  Grid (groups, n); each wavefront walks chunks wave, wave + stride, ...
+//   PRED: rows with a valid guess also emit candidates and level-1 histograms of buckets guess, guess+1.
+//   PEND: coordinates selected in the previous step still hold their old value in e and count as zero.
+// ---------------------------------------------------------------------------------------------
+constexpr int kBatch = 4;  // rounds whose loads are in flight together
+
+struct Batch {
+  float4 g[kBatch], e[kBatch];
+};
+
+template <bool FULL>
+__device__ __forceinline__ void load_batch(Batch& b, const float* __restrict__ gr, const float* __restrict__ er,
+                                           uint32_t base, int r0, uint32_t d) {
+#pragma unroll
+  for (int u = 0; u < kBatch; ++u) {
+    const uint32_t j = base + (r0 + u) * 256;
+    b.g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    b.e[u] = b.g[u];
+    if (FULL || j < d) {
+      b.g[u] = load_stream4(gr + j);
+      b.e[u] = load_stream4(er + j);
+    }
+  }
+}
+
+template <bool PRED, bool PEND, bool FULL>
+__device__ __forceinline__ void pass_a_chunk(const float* __restrict__ gr, float* __restrict__ er, uint32_t d,
+                                             uint32_t c, uint32_t* lh, uint32_t* lh1, uint32_t& zeros, bool pred,
+                                             uint32_t bg, TopkRow* rowp, uint2* candr, uint32_t cap, uint2* descr,
+                                             uint2* stage, uint32_t* bm, const uint32_t* __restrict__ prev_off,
+                                             const int32_t* __restrict__ prev_idx, uint32_t k) {
+  const uint32_t lane = lane_id();
+  const uint32_t base = c * kChunk + lane * 4;
+  uint32_t cnt = 0;
+  Batch cur;
+  load_batch<FULL>(cur, gr, er, base, 0, d);
+  if constexpr (PEND) {
+    // bit map of the chunk's coordinates that were selected in the previous step (their residual is zero)
+    bm[lane] = 0;
+    bm[lane + 64] = 0;
+    const uint32_t lo = prev_off[c], hi = prev_off[c + 1];
+    for (uint32_t q = lo + lane; q < hi && q < k; q += 64) {
+      const uint32_t jl = static_cast<uint32_t>(prev_idx[q]) - c * kChunk;
+      if (jl < static_cast<uint32_t>(kChunk)) atomicOr(&bm[jl >> 5], 1u << (jl & 31u));
+    }
+  }
+#pragma unroll 1
+  for (int r0 = 0; r0 < kRounds; r0 += kBatch) {
+    Batch nxt;
+    if (r0 + kBatch < kRounds) load_batch<FULL>(nxt, gr, er, base, r0 + kBatch, d);
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int r = r0 + u;
+      const uint32_t j = base + r * 256;
+      const bool in = FULL || j < d;
+      float4 ev = cur.e[u];
+      const float4 gv = cur.g[u];
+      if constexpr (PEND) {
+        const uint32_t nib = (bm[r * 8 + (lane >> 3)] >> ((lane & 7u) * 4u)) & 15u;
+        if (nib & 1u) ev.x = 0.0f;
+        if (nib & 2u) ev.y = 0.0f;
+        if (nib & 4u) ev.z = 0.0f;
+        if (nib & 8u) ev.w = 0.0f;
+      }
+      float4 x = make_float4(ev.x + gv.x, ev.y + gv.y, ev.z + gv.z, ev.w + gv.w);
+      Quad q;
+      q.ok[0] = in; q.ok[1] = FULL || j + 1 < d; q.ok[2] = FULL || j + 2 < d; q.ok[3] = FULL || j + 3 < d;
+      if (!FULL) {  // columns >= d keep what they held
+        if (!q.ok[1]) x.y = cur.e[u].y;
+        if (!q.ok[2]) x.z = cur.e[u].z;
+        if (!q.ok[3]) x.w = cur.e[u].w;
+      }
+      if (in) store_stream4(er + j, x);
+      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
+                                __float_as_uint(x.w)};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) q.key[s] = key_of_bits(bits[s]);
+      hist4(lh, q, zeros);
+      if constexpr (PRED) {
+        if (pred) {
+          bool flag[4];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const uint32_t rel = (q.key[s] >> kL0Shift) - bg;  // wraps to a huge value below the guess
+            flag[s] = q.ok[s] && (q.key[s] >> kL0Shift) >= bg;
+            if (flag[s] && rel < 2u) atomicAdd(&lh1[rel * kNB1 + ((q.key[s] >> kL1Shift) & (kNB1 - 1))], 1u);
+          }
+          stage_round(stage, cnt, j, bits, flag);
+        }
+      }
+    }
+    cur = nxt;
+  }
+  if constexpr (PRED)
+    if (pred) flush_chunk(stage, cnt, er, d, c, bg, rowp, candr, cap, descr);
+}
+
+template <bool PRED, bool PEND>
+__global__ __launch_bounds__(kWG) void k_topk_pass_a(const float* __restrict__ g, float* __restrict__ e,
+                                                      Geometry geo, TopkWorkspace ws, TopkOptions opt) {
+  __shared__ uint32_t lh[kNB0];
+  __shared__ uint32_t lh1[PRED ? 2 * kNB1 : 1];
+  __shared__ uint2 stage_all[PRED ? kWaves * kStage : 1];
+  __shared__ uint32_t bm_all[PEND ? kWaves * 128 : 1];
+  __shared__ uint32_t suf[kWG + 1];
+  __shared__ uint32_t out2[2];
+  __shared__ uint32_t sh_flag, sh_l1, sh_bstar, sh_need;
+  const uint32_t row = blockIdx.y;
+  for (int b = threadIdx.x; b < kNB0; b += kWG) lh[b] = 0;
+  if (PRED)
+    for (int b = threadIdx.x; b < 2 * kNB1; b += kWG) lh1[b] = 0;
+  __syncthreads();
+  const float* gr = g + static_cast<int64_t>(row) * geo.ld;
+  float* er = e + static_cast<int64_t>(row) * geo.ld;
+  TopkRow* rowp = ws.rows + row;
+  bool pred = false;
+  uint32_t bg = 0;
+  if (PRED) {
+    pred = rowp->pred_valid != 0;
+    bg = rowp->b_guess;
+  }
+  uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
+  uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
+  const uint32_t* prev_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
+  const int32_t* prev_idx = ws.idx + static_cast<size_t>(row) * geo.k;
+  const uint32_t wave = threadIdx.x >> 6;
+  uint2* stage = stage_all + (PRED ? wave * kStage : 0);
+  uint32_t* bm = bm_all + (PEND ? wave * 128 : 0);
+  const uint32_t stride = gridDim.x * kWaves;
+  uint32_t zeros = 0;
+  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+    if ((c + 1) * static_cast<uint64_t>(kChunk) <= geo.d)
+      pass_a_chunk<PRED, PEND, true>(gr, er, geo.d, c, lh, lh1, zeros, pred, bg, rowp, candr, opt.cap, descr, stage,
+                                     bm, prev_off, prev_idx, geo.k);
+    else
+      pass_a_chunk<PRED, PEND, false>(gr, er, geo.d, c, lh, lh1, zeros, pred, bg, rowp, candr, opt.cap, descr, stage,
+                                      bm, prev_off, prev_idx, geo.k);
+  }
+  if (zeros && lane_id() == 0) atomicAdd(&lh[0], zeros);
+  __syncthreads();
+  uint32_t* gh = ws.hist0 + static_cast<size_t>(row) * kNB0;
+  for (int b = threadIdx.x; b < kNB0; b += kWG) {
+    const uint32_t h = lh[b];
+    if (h) atomicAdd(&gh[b], h);
+  }
+  uint32_t* gh1 = ws.hist1x + static_cast<size_t>(row) * 2 * kNB1;
+  if (PRED && pred)
+    for (int b = threadIdx.x; b < 2 * kNB1; b += kWG) {
+      const uint32_t h = lh1[b];
+      if (h) atomicAdd(&gh1[b], h);
+    }
+
+  // ---- row-wide part, by whichever workgroup of the row finishes last ----
+  if (!last_group_of_row(&rowp->ticket[0], gridDim.x, &sh_flag)) return;
+  take_hist<kNB0>(gh, lh);
+  find_crossing<kNB0>(lh, geo.k, suf, out2);
+  if (threadIdx.x == 0) {
     const uint32_t bstar = out2[0], above = out2[1];
-    const uint32_t total = above + h[bstar];  // entries with bucket >= bstar
-    const bool pred_ok = opt.first_pass_emits && rp->pred_valid && bstar >= rp->b_guess && rp->cursor <= opt.cap &&
-                         !opt.force_dense;
+    const uint32_t total = above + lh[bstar];  // entries with bucket >= bstar
+    const uint32_t cursor = load_agent(&rowp->cursor);
+    const bool pred_ok = PRED && pred && bstar >= bg && cursor <= opt.cap && !opt.force_dense;
     uint32_t mode, n_src, reads;
-    if (pred_ok) { mode = kModeCand; n_src = rp->cursor; reads = 0; }
+    if (pred_ok) { mode = kModeCand; n_src = cursor; reads = 0; }
     else if (total <= opt.cap && !opt.force_dense) { mode = kModeNeedB; n_src = total; reads = 1; }
     else { mode = kModeDense; n_src = 0; reads = 4; }
-    rp->mode = mode;
-    rp->n_src = n_src;
-    rp->cursor = 0;
-    rp->bstar = bstar;
-    rp->need = geo.k - above;
+    rowp->mode = mode;
+    rowp->n_src = n_src;
+    rowp->cursor = 0;
+    rowp->bstar = bstar;
+    rowp->need = geo.k - above;
+    rowp->level1_done = 0;
     // Guess for the next step: one bucket below this step's threshold bucket if the list that guess would
     // have produced now fits with room to spare, else the bucket itself, else no guess.
     uint32_t valid = 0, guess = 0;
     if (opt.predict && !opt.force_dense) {
-      const uint32_t below = bstar ? h[bstar - 1] : 0;
+      const uint32_t below = bstar ? lh[bstar - 1] : 0;
       if (bstar && total + below <= opt.cap / 2) { valid = 1; guess = bstar - 1; }
       else if (total <= opt.cap / 2) { valid = 1; guess = bstar; }
     }
-    rp->pred_valid = valid;
-    rp->b_guess = guess;
+    rowp->pred_valid = valid;
+    rowp->b_guess = guess;
     uint32_t* cn = ws.counters + row * 4;
     cn[0] = reads;
     cn[1] = n_src;
+    sh_l1 = (pred_ok && bstar - bg < 2u) ? 1u + (bstar - bg) : 0u;
+    sh_bstar = bstar;
+    sh_need = geo.k - above;
+  }
+  __syncthreads();
+  if (PRED && pred) {
+    const uint32_t which = sh_l1;  // 0: level 1 not available; 1, 2: histogram of bucket guess, guess + 1
+    if (which) {
+      for (int b = threadIdx.x; b < kNB1; b += kWG) lh[b] = load_agent(gh1 + (which - 1) * kNB1 + b);
+    }
+    for (int b = threadIdx.x; b < 2 * kNB1; b += kWG) gh1[b] = 0;
+    __syncthreads();
+    if (which) resolve_level1(rowp, sh_bstar, sh_need, lh, suf, out2);
   }
 }
 
-// Second dense pass (rows in kModeNeedB only): candidate list = entries with level-0 bucket >= bstar.
-__global__ __launch_bounds__(kWG) void k_topk_pass_b(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
+// ---------------------------------------------------------------------------------------------
+// Kernel 2: level 1 for rows that could not resolve it in the first pass.
+//   kModeNeedB: one more read of the row; writes the candidate list (bucket >= bstar) and the histogram.
+//   kModeCand : the list exists (the threshold bucket was above the two tracked ones): sweep it.
+//   kModeDense: no list: histogram from the row itself.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                       TopkOptions opt) {
+  __shared__ uint32_t lh[kNB1];
   __shared__ uint2 stage_all[kWaves * kStage];
+  __shared__ uint32_t suf[kWG + 1];
+  __shared__ uint32_t out2[2];
+  __shared__ uint32_t sh_flag;
   const uint32_t row = blockIdx.y;
   TopkRow* rowp = ws.rows + row;
-  if (rowp->mode != kModeNeedB) return;
-  const uint32_t bstar = rowp->bstar;
+  if (rowp->level1_done) return;
+  const uint32_t mode = rowp->mode, bstar = rowp->bstar, need = rowp->need;
+  for (int b = threadIdx.x; b < kNB1; b += kWG) lh[b] = 0;
+  __syncthreads();
   const float* er = e + static_cast<int64_t>(row) * geo.ld;
   uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
-  uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  uint2* stage = stage_all + wave * kStage;
-  const uint32_t stride = gridDim.x * kWaves;
-  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
-    const uint32_t base = c * kChunk + lane * 4;
-    uint32_t cnt = 0;
+  auto visit = [&](uint32_t bits, bool ok) {
+    const uint32_t key = key_of_bits(bits);
+    if (ok && (key >> kL0Shift) == bstar) atomicAdd(&lh[(key >> kL1Shift) & (kNB1 - 1)], 1u);
+  };
+  if (mode == kModeNeedB) {
+    uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
+    const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+    uint2* stage = stage_all + wave * kStage;
+    const uint32_t stride = gridDim.x * kWaves;
+    for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+      const uint32_t base = c * kChunk + lane * 4;
+      uint32_t cnt = 0;
 #pragma unroll 4
-    for (int r = 0; r < kRounds; ++r) {
-      const uint32_t j = base + r * 256;
-      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (j < geo.d) x = *reinterpret_cast<const float4*>(er + j);
-      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
-                                __float_as_uint(x.w)};
-      bool flag[4];
+      for (int r = 0; r < kRounds; ++r) {
+        const uint32_t j = base + r * 256;
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j < geo.d) x = *reinterpret_cast<const float4*>(er + j);
+        const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
+                                  __float_as_uint(x.w)};
+        bool flag[4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) flag[s] = j + s < geo.d && (key_of_bits(bits[s]) >> kL0Shift) >= bstar;
-      stage_round(stage, cnt, j, bits, flag);
+        for (int s = 0; s < 4; ++s) {
+          flag[s] = j + s < geo.d && (key_of_bits(bits[s]) >> kL0Shift) >= bstar;
+          visit(bits[s], j + s < geo.d);
+        }
+        stage_round(stage, cnt, j, bits, flag);
+      }
+      // fits by construction: the level-0 histogram counted exactly these entries
+      flush_chunk(stage, cnt, er, geo.d, c, bstar, rowp, candr, opt.cap, descr);
     }
-    // fits by construction: the level-0 histogram counted exactly these entries
-    flush_chunk(stage, cnt, er, geo.d, c, bstar, rowp, candr, opt.cap, descr);
+  } else if (mode == kModeCand) {
+    const uint32_t n_src = rowp->n_src;
+    const uint32_t step = gridDim.x * kWG;
+    for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < n_src; q += step) visit(candr[q].y, true);
+  } else {
+    const uint32_t step = gridDim.x * kWG * 4;
+    for (uint32_t j = (blockIdx.x * kWG + threadIdx.x) * 4; j < geo.d; j += step) {
+      const float4 x = *reinterpret_cast<const float4*>(er + j);
+      visit(__float_as_uint(x.x), true);
+      visit(__float_as_uint(x.y), j + 1 < geo.d);
+      visit(__float_as_uint(x.z), j + 2 < geo.d);
+      visit(__float_as_uint(x.w), j + 3 < geo.d);
+    }
   }
+  __syncthreads();
+  uint32_t* gh = ws.hist1 + static_cast<size_t>(row) * kNB1;
+  for (int b = threadIdx.x; b < kNB1; b += kWG) {
+    const uint32_t h = lh[b];
+    if (h) atomicAdd(&gh[b], h);
+  }
+  if (!last_group_of_row(&rowp->ticket[1], gridDim.x, &sh_flag)) return;
+  take_hist<kNB1>(gh, lh);
+  resolve_level1(rowp, bstar, need, lh, suf, out2);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Levels 1 and 2: histogram of the next key bits over the entries that match the prefix so far.
-// LEVEL 1: match (key >> 19) == bstar, bin = (key >> 9) & 1023.  LEVEL 2: match (key >> 9) == prefix1,
-// bin = key & 511.  Source: the candidate list (linear sweep) or the row itself.
+// Kernel 3: level 2 (last 9 key bits) over the entries that match bits 30..9 of the threshold key.
 // ---------------------------------------------------------------------------------------------
-template <int LEVEL>
-__global__ __launch_bounds__(kWG) void k_topk_hist(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
-                                                    TopkOptions opt) {
-  constexpr int NB = LEVEL == 1 ? kNB1 : kNB2;
-  __shared__ uint32_t lh[NB];
+__global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
+                                                      TopkOptions opt) {
+  __shared__ uint32_t lh[kNB2];
+  __shared__ uint32_t suf[kWG + 1];
+  __shared__ uint32_t out2[2];
+  __shared__ uint32_t sh_flag;
   const uint32_t row = blockIdx.y;
-  const TopkRow* rowp = ws.rows + row;
-  const uint32_t mode = rowp->mode;
-  const uint32_t want = LEVEL == 1 ? rowp->bstar : rowp->prefix1;
-  for (int b = threadIdx.x; b < NB; b += kWG) lh[b] = 0;
+  TopkRow* rowp = ws.rows + row;
+  const uint32_t mode = rowp->mode, want = rowp->prefix1, need = rowp->need;
+  for (int b = threadIdx.x; b < kNB2; b += kWG) lh[b] = 0;
   __syncthreads();
   auto visit = [&](uint32_t bits, bool ok) {
     const uint32_t key = key_of_bits(bits);
-    if (LEVEL == 1) {
-      if (ok && (key >> kL0Shift) == want) atomicAdd(&lh[(key >> kL1Shift) & (kNB1 - 1)], 1u);
-    } else {
-      if (ok && (key >> kL1Shift) == want) atomicAdd(&lh[key & (kNB2 - 1)], 1u);
-    }
+    if (ok && (key >> kL1Shift) == want) atomicAdd(&lh[key & (kNB2 - 1)], 1u);
   };
   if (mode == kModeDense) {
     const float* er = e + static_cast<int64_t>(row) * geo.ld;
@@ -379,46 +530,26 @@ __global__ __launch_bounds__(kWG) void k_topk_hist(const float* __restrict__ e, 
     for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < n_src; q += step) visit(candr[q].y, true);
   }
   __syncthreads();
-  uint32_t* gh = (LEVEL == 1 ? ws.hist1 : ws.hist2) + static_cast<size_t>(row) * NB;
-  for (int b = threadIdx.x; b < NB; b += kWG) {
+  uint32_t* gh = ws.hist2 + static_cast<size_t>(row) * kNB2;
+  for (int b = threadIdx.x; b < kNB2; b += kWG) {
     const uint32_t h = lh[b];
     if (h) atomicAdd(&gh[b], h);
   }
-}
-
-template <int LEVEL>
-__global__ __launch_bounds__(kWG) void k_topk_resolve(Geometry geo, TopkWorkspace ws) {
-  constexpr int NB = LEVEL == 1 ? kNB1 : kNB2;
-  __shared__ uint32_t h[NB];
-  __shared__ uint32_t suf[kWG + 1];
-  __shared__ uint32_t out2[2];
-  const uint32_t row = blockIdx.x;
-  TopkRow* rp = ws.rows + row;
-  uint32_t* gh = (LEVEL == 1 ? ws.hist1 : ws.hist2) + static_cast<size_t>(row) * NB;
-  for (int b = threadIdx.x; b < NB; b += kWG) {
-    h[b] = gh[b];
-    gh[b] = 0;
-  }
-  __syncthreads();
-  const uint32_t need = rp->need;
-  find_crossing<NB>(h, need, suf, out2);
+  if (!last_group_of_row(&rowp->ticket[2], gridDim.x, &sh_flag)) return;
+  take_hist<kNB2>(gh, lh);
+  find_crossing<kNB2>(lh, need, suf, out2);
   if (threadIdx.x == 0) {
     const uint32_t s = out2[0], above = out2[1];
-    if (LEVEL == 1) {
-      rp->prefix1 = (rp->bstar << (kL0Shift - kL1Shift)) | s;
-      rp->need = need - above;
-    } else {
-      const uint32_t tau = (rp->prefix1 << kL1Shift) | s;
-      const uint32_t r = need - above, ties = h[s];
-      rp->tau = tau;
-      rp->r = r;
-      rp->ties = ties;
-      rp->take_all_ties = (r == ties);
-      ws.tau[row] = tau;
-      uint32_t* cn = ws.counters + row * 4;
-      cn[2] = ties;
-      cn[3] = r;
-    }
+    const uint32_t tau = (want << kL1Shift) | s;
+    const uint32_t r = need - above, ties = lh[s];
+    rowp->tau = tau;
+    rowp->r = r;
+    rowp->ties = ties;
+    rowp->take_all_ties = (r == ties);
+    ws.tau[row] = tau;
+    uint32_t* cn = ws.counters + row * 4;
+    cn[2] = ties;
+    cn[3] = r;
   }
 }
 
@@ -472,15 +603,23 @@ __device__ __forceinline__ void for_each_round(uint32_t mode, const float* __res
   }
 }
 
-// Per chunk: how many keys lie above tau and how many equal it.
+// ---------------------------------------------------------------------------------------------
+// Kernel 4: per chunk, how many keys lie above tau and how many equal it; then, by the row's last
+// workgroup, the exclusive prefixes over chunks (ties are taken in coordinate order until r are in).
+// ---------------------------------------------------------------------------------------------
+constexpr int kScanItems = 16;  // chunks per thread in the row scan
+
 __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                      TopkOptions opt) {
+  __shared__ uint32_t scratch[kWG / 64 + 1];
+  __shared__ uint32_t sh_flag;
   const uint32_t row = blockIdx.y;
-  const TopkRow* rowp = ws.rows + row;
+  TopkRow* rowp = ws.rows + row;
   const uint32_t mode = rowp->mode, tau = rowp->tau;
   const float* er = e + static_cast<int64_t>(row) * geo.ld;
   const uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
   const uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
+  const size_t rb = static_cast<size_t>(row) * geo.num_chunks;
   const uint32_t wave = threadIdx.x >> 6;
   const uint32_t stride = gridDim.x * kWaves;
   for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
@@ -492,68 +631,90 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
         eq += popc64(ballot64(en.ok[s] && key == tau));
       }
     });
-    if (lane_id() == 0) {
-      ws.cnt_gt[static_cast<size_t>(row) * geo.num_chunks + c] = gt;
-      ws.cnt_eq[static_cast<size_t>(row) * geo.num_chunks + c] = eq;
+    if (lane_id() == 0) {  // read back by the row's last workgroup in this same launch
+      store_agent(ws.cnt_gt + rb + c, gt);
+      store_agent(ws.cnt_eq + rb + c, eq);
     }
   }
-}
-
-// Per row: exclusive prefix over chunks of the selected counts, and of the tie counts.
-constexpr int kScanWG = 1024;
-__global__ __launch_bounds__(kScanWG) void k_topk_scan(Geometry geo, TopkWorkspace ws) {
-  __shared__ uint32_t scratch[kScanWG / 64 + 1];
-  const uint32_t row = blockIdx.x;
-  TopkRow* rp = ws.rows + row;
-  const uint32_t r = rp->r;
-  const size_t rb = static_cast<size_t>(row) * geo.num_chunks;
+  if (!last_group_of_row(&rowp->ticket[3], gridDim.x, &sh_flag)) return;
+  const uint32_t r = rowp->r;
   uint32_t* sel_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
   uint32_t eq_carry = 0, sel_carry = 0;
-  for (uint32_t c0 = 0; c0 < geo.num_chunks; c0 += kScanWG) {
-    const uint32_t c = c0 + threadIdx.x;
-    const bool in = c < geo.num_chunks;
-    const uint32_t eq = in ? ws.cnt_eq[rb + c] : 0;
-    const uint32_t gt = in ? ws.cnt_gt[rb + c] : 0;
+  for (uint32_t c0 = 0; c0 < geo.num_chunks; c0 += kWG * kScanItems) {
+    const uint32_t first = c0 + threadIdx.x * kScanItems;
+    uint32_t eq[kScanItems], gt[kScanItems];
+    uint32_t eq_sum = 0;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+      const uint32_t c = first + i;
+      const bool in = c < geo.num_chunks;
+      eq[i] = in ? load_agent(ws.cnt_eq + rb + c) : 0;
+      gt[i] = in ? load_agent(ws.cnt_gt + rb + c) : 0;
+      eq_sum += eq[i];
+    }
     uint32_t eq_total, sel_total;
-    const uint32_t eq_before = eq_carry + block_excl_scan<kScanWG>(eq, scratch, &eq_total);
-    // ties are taken in coordinate order until r of them are in
-    const uint32_t room = r > eq_before ? r - eq_before : 0;
-    const uint32_t take = eq < room ? eq : room;
-    const uint32_t sel_before = sel_carry + block_excl_scan<kScanWG>(gt + take, scratch, &sel_total);
-    if (in) {
-      ws.eq_before[rb + c] = eq_before;
-      sel_off[c] = sel_before;
+    uint32_t eq_before = eq_carry + block_excl_scan<kWG>(eq_sum, scratch, &eq_total);
+    uint32_t take[kScanItems], eqb[kScanItems];
+    uint32_t sel_sum = 0;
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+      eqb[i] = eq_before;
+      const uint32_t room = r > eq_before ? r - eq_before : 0;
+      take[i] = eq[i] < room ? eq[i] : room;
+      sel_sum += gt[i] + take[i];
+      eq_before += eq[i];
+    }
+    uint32_t sel_before = sel_carry + block_excl_scan<kWG>(sel_sum, scratch, &sel_total);
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+      const uint32_t c = first + i;
+      if (c < geo.num_chunks) {
+        ws.eq_before[rb + c] = eqb[i];
+        sel_off[c] = sel_before;
+      }
+      sel_before += gt[i] + take[i];
     }
     eq_carry += eq_total;
     sel_carry += sel_total;
   }
   if (threadIdx.x == 0) {
     sel_off[geo.num_chunks] = sel_carry;  // == k
-    rp->cursor = 0;                       // the list has been counted; the next first pass allocates from 0
+    rowp->cursor = 0;                     // the next step's first pass allocates its list from the start
   }
 }
 
-// Per chunk: write the selected (coordinate, value) pairs at their final ascending positions and clear
-// their residual entries (the worker's error update of Algorithm 2 for the kept coordinates).
-__global__ __launch_bounds__(kWG) void k_topk_emit(float* __restrict__ e, Geometry geo, TopkWorkspace ws,
-                                                    TopkOptions opt) {
-  const uint32_t row = blockIdx.y;
-  const TopkRow* rowp = ws.rows + row;
-  const uint32_t mode = rowp->mode, tau = rowp->tau, r = rowp->r;
-  const bool all_ties = rowp->take_all_ties != 0;
-  float* er = e + static_cast<int64_t>(row) * geo.ld;
-  const uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
-  const uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
-  int32_t* idx = ws.idx + static_cast<size_t>(row) * geo.k;
-  float* val = ws.val + static_cast<size_t>(row) * geo.k;
-  const size_t rb = static_cast<size_t>(row) * geo.num_chunks;
-  const uint32_t* sel_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
+// ---------------------------------------------------------------------------------------------
+// Kernel 5: per chunk of coordinates.
+//   Phase 1: wavefront w writes the selected entries of workers w, w+4, ... that fall in this chunk to
+//            their final positions in the workers' (coordinate, value) lists.
+//   Phase 2: the chunk's entries are added into an LDS tile of the summed gradient, one worker after
+//            the other (a barrier between them): the fp32 sum has exactly the order i = 0 .. n-1, and
+//            one worker's coordinates are distinct, so no atomics are needed.
+//   Phase 3: gbar = sum / n and the AMSGrad moment and parameter update (server lines of Algorithm 2).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWG) void k_topk_final(float* __restrict__ theta, float* __restrict__ m,
+                                                     float* __restrict__ v, float* __restrict__ vhat,
+                                                     const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
+                                                     TopkOptions opt, AmsParams p) {
+  __shared__ float gs[kChunk];
+  const uint32_t c = blockIdx.x;
+  const uint32_t base = c * kChunk;
   const uint32_t wave = threadIdx.x >> 6;
-  const uint32_t stride = gridDim.x * kWaves;
-  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
-    uint32_t at = sel_off[c];
-    if (sel_off[c + 1] == at) continue;  // nothing selected in this chunk (wave-uniform)
-    uint32_t eq_seen = ws.eq_before[rb + c];
+  for (int t = threadIdx.x; t < kChunk; t += kWG) gs[t] = 0.0f;
+
+  for (uint32_t i = wave; i < geo.n; i += kWaves) {
+    const uint32_t* so = ws.sel_off + static_cast<size_t>(i) * (geo.num_chunks + 1) + c;
+    uint32_t at = so[0];
+    if (so[1] == at) continue;  // nothing of this worker in the chunk (wave-uniform)
+    const TopkRow* rowp = ws.rows + i;
+    const uint32_t mode = rowp->mode, tau = rowp->tau, r = rowp->r;
+    const bool all_ties = rowp->take_all_ties != 0;
+    const float* er = e + static_cast<int64_t>(i) * geo.ld;
+    const uint2* candr = ws.cand + static_cast<size_t>(i) * opt.cap;
+    const uint2* descr = ws.desc + static_cast<size_t>(i) * geo.num_chunks;
+    int32_t* idx = ws.idx + static_cast<size_t>(i) * geo.k;
+    float* val = ws.val + static_cast<size_t>(i) * geo.k;
+    uint32_t eq_seen = ws.eq_before[static_cast<size_t>(i) * geo.num_chunks + c];
     for_each_round(mode, er, geo.d, c, candr, descr, opt.cap, [&](const Entry4& en, int slots) {
       bool sel[4] = {false, false, false, false};
       if (all_ties) {
@@ -585,44 +746,17 @@ __global__ __launch_bounds__(kWG) void k_topk_emit(float* __restrict__ e, Geomet
       uint32_t pos = at + below;
       for (int s = 0; s < slots; ++s)
         if (sel[s]) {
-          if (pos < geo.k && en.j[s] < geo.d) {  // always true when the counts are consistent
+          if (pos < geo.k) {  // always true when the counts are consistent
             idx[pos] = static_cast<int32_t>(en.j[s]);
             val[pos] = __uint_as_float(en.bits[s]);
-            if (!(opt.dbg & 8)) er[en.j[s]] = 0.0f;
           }
           ++pos;
         }
       at += total;
     });
   }
-}
+  __syncthreads();  // the chunk's list entries are visible to the whole workgroup
 
-// ---------------------------------------------------------------------------------------------
-// Server lines of Algorithm 2 for sparse messages: worker-ordered sum of the selected values, divided
-// by n, then the AMSGrad moment and parameter update.  One workgroup per chunk of coordinates; the
-// chunk's averaged gradient lives in LDS.  Workers are added one after the other (a barrier between
-// them), and one worker's coordinates are distinct, so no atomics are needed and the fp32 sum has
-// exactly the order i = 0 .. n-1.
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void ams_update(float gb, float& th, float& mm, float& vv, float& vh, const AmsParams& p) {
-  const float mj = p.beta1 * mm + p.one_minus_beta1 * gb;
-  const float vj = p.beta2 * vv + p.one_minus_beta2 * (gb * gb);
-  const float vhj = (vh < vj) ? vj : vh;
-  const float den = p.eps_out ? sqrtf(vhj) + p.eps : sqrtf(vhj + p.eps);
-  mm = mj;
-  vv = vj;
-  vh = vhj;
-  th = th - p.lr * (mj / den);
-}
-
-__global__ __launch_bounds__(kWG) void k_topk_amsgrad(float* __restrict__ theta, float* __restrict__ m,
-                                                       float* __restrict__ v, float* __restrict__ vhat, Geometry geo,
-                                                       TopkWorkspace ws, AmsParams p) {
-  __shared__ float gs[kChunk];
-  const uint32_t c = blockIdx.x;
-  const uint32_t base = c * kChunk;
-  for (int t = threadIdx.x; t < kChunk; t += kWG) gs[t] = 0.0f;
-  __syncthreads();
   for (uint32_t i = 0; i < geo.n; ++i) {
     const uint32_t* so = ws.sel_off + static_cast<size_t>(i) * (geo.num_chunks + 1) + c;
     const uint32_t lo = so[0], hi = so[1];
@@ -634,6 +768,7 @@ __global__ __launch_bounds__(kWG) void k_topk_amsgrad(float* __restrict__ theta,
     }
     __syncthreads();
   }
+
 #pragma unroll
   for (int r = 0; r < kChunk / (kWG * 4); ++r) {
     const uint32_t t = r * kWG * 4 + threadIdx.x * 4;
@@ -660,6 +795,19 @@ __global__ __launch_bounds__(kWG) void k_topk_amsgrad(float* __restrict__ theta,
   }
 }
 
+// The residual at the coordinates selected in the last step becomes zero (the worker's error update of
+// Algorithm 2 for the kept coordinates), applied on request.
+__global__ __launch_bounds__(kWG) void k_topk_apply_clear(float* __restrict__ e, Geometry geo, TopkWorkspace ws) {
+  const uint32_t row = blockIdx.y;
+  float* er = e + static_cast<int64_t>(row) * geo.ld;
+  const int32_t* idx = ws.idx + static_cast<size_t>(row) * geo.k;
+  const uint32_t step = gridDim.x * kWG;
+  for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < geo.k; q += step) {
+    const uint32_t j = static_cast<uint32_t>(idx[q]);
+    if (j < geo.d) er[j] = 0.0f;
+  }
+}
+
 }  // namespace
 
 #define COMPAMS_CHECK_LAUNCH()                    \
@@ -668,54 +816,32 @@ __global__ __launch_bounds__(kWG) void k_topk_amsgrad(float* __restrict__ theta,
     if (err__ != hipSuccess) return err__;        \
   } while (0)
 
-hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt_in, const AmsParams& ap,
+hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
                      const float* g, float* e, float* theta, float* m, float* v, float* vhat,
-                     bool first_pass_may_predict, hipStream_t stream, Launcher* L) {
-  TopkOptions opt = opt_in;
-  opt.first_pass_emits = first_pass_may_predict ? 1u : 0u;
+                     bool first_pass_may_predict, bool clear_pending, hipStream_t stream, Launcher* L) {
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
-  uint32_t GA = G;
+  uint32_t GA = groups_first_pass(geo.n, geo.num_chunks);
   if (getenv("COMPAMS_TUNE_GA")) GA = atoi(getenv("COMPAMS_TUNE_GA"));
-  if (getenv("COMPAMS_TUNE_DBG")) opt.dbg = atoi(getenv("COMPAMS_TUNE_DBG"));
   const dim3 grid_rows(G, geo.n), wg(kWG), grid_a(GA, geo.n);
   {
     ScopedSlot s(L, kSlotPassA, stream);
-    if (first_pass_may_predict)
-      hipLaunchKernelGGL(k_topk_pass_a<true>, grid_a, wg, 0, stream, g, e, geo, ws, opt);
-    else
-      hipLaunchKernelGGL(k_topk_pass_a<false>, grid_a, wg, 0, stream, g, e, geo, ws, opt);
+    if (first_pass_may_predict) {
+      if (clear_pending) hipLaunchKernelGGL((k_topk_pass_a<true, true>), grid_a, wg, 0, stream, g, e, geo, ws, opt);
+      else hipLaunchKernelGGL((k_topk_pass_a<true, false>), grid_a, wg, 0, stream, g, e, geo, ws, opt);
+    } else {
+      if (clear_pending) hipLaunchKernelGGL((k_topk_pass_a<false, true>), grid_a, wg, 0, stream, g, e, geo, ws, opt);
+      else hipLaunchKernelGGL((k_topk_pass_a<false, false>), grid_a, wg, 0, stream, g, e, geo, ws, opt);
+    }
   }
   COMPAMS_CHECK_LAUNCH();
   {
-    ScopedSlot s(L, kSlotResolve0, stream);
-    hipLaunchKernelGGL(k_topk_resolve0, dim3(geo.n), wg, 0, stream, geo, ws, opt);
+    ScopedSlot s(L, kSlotLevel1, stream);
+    hipLaunchKernelGGL(k_topk_level1, grid_rows, wg, 0, stream, e, geo, ws, opt);
   }
   COMPAMS_CHECK_LAUNCH();
   {
-    ScopedSlot s(L, kSlotPassB, stream);
-    hipLaunchKernelGGL(k_topk_pass_b, grid_rows, wg, 0, stream, e, geo, ws, opt);
-  }
-  COMPAMS_CHECK_LAUNCH();
-  // sweeps over the (short) candidate lists use fewer, fully occupied workgroups per row
-  const dim3 grid_hist(G, geo.n);
-  {
-    ScopedSlot s(L, kSlotHist1, stream);
-    hipLaunchKernelGGL(k_topk_hist<1>, grid_hist, wg, 0, stream, e, geo, ws, opt);
-  }
-  COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotResolve1, stream);
-    hipLaunchKernelGGL(k_topk_resolve<1>, dim3(geo.n), wg, 0, stream, geo, ws);
-  }
-  COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotHist2, stream);
-    hipLaunchKernelGGL(k_topk_hist<2>, grid_hist, wg, 0, stream, e, geo, ws, opt);
-  }
-  COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotResolve2, stream);
-    hipLaunchKernelGGL(k_topk_resolve<2>, dim3(geo.n), wg, 0, stream, geo, ws);
+    ScopedSlot s(L, kSlotLevel2, stream);
+    hipLaunchKernelGGL(k_topk_level2, grid_rows, wg, 0, stream, e, geo, ws, opt);
   }
   COMPAMS_CHECK_LAUNCH();
   {
@@ -724,21 +850,18 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   }
   COMPAMS_CHECK_LAUNCH();
   {
-    ScopedSlot s(L, kSlotScan, stream);
-    hipLaunchKernelGGL(k_topk_scan, dim3(geo.n), dim3(kScanWG), 0, stream, geo, ws);
-  }
-  COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotEmit, stream);
-    hipLaunchKernelGGL(k_topk_emit, grid_rows, wg, 0, stream, e, geo, ws, opt);
-  }
-  COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotTopkAms, stream);
-    hipLaunchKernelGGL(k_topk_amsgrad, dim3(geo.num_chunks), wg, 0, stream, theta, m, v, vhat, geo, ws, ap);
+    ScopedSlot s(L, kSlotTopkFinal, stream);
+    hipLaunchKernelGGL(k_topk_final, dim3(geo.num_chunks), wg, 0, stream, theta, m, v, vhat, e, geo, ws, opt, ap);
   }
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
+}
+
+hipError_t topk_apply_clear(const Geometry& geo, const TopkWorkspace& ws, float* e, hipStream_t stream) {
+  uint32_t blocks = (geo.k + kWG - 1) / kWG;
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(k_topk_apply_clear, dim3(blocks, geo.n), dim3(kWG), 0, stream, e, geo, ws);
+  return hipGetLastError();
 }
 
 }  // namespace compams

@@ -160,6 +160,21 @@ def test_topk_guess_that_is_too_high_falls_back():
     p.close()
 
 
+@pytest.mark.parametrize("n,d,k", [(4, 65536, 655), (3, 100003, 50000), (2, 8191, 8191), (2, 20000, 1)])
+def test_topk_deferred_residual_clearing(n, d, k):
+    """Between steps the zeroing of the selected residuals is pending; the next first pass must honour it.
+    Index sets and parameters are compared after every step, the residuals only at the end."""
+    rng = np.random.default_rng(d)
+    p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, B.TOPK, k=k)
+    gs = rand_grads(d + 1, n, d, 7)
+    for t, g in enumerate(gs):
+        p.step(g, 1e-3, label=f"deferred step {t}", with_e=(t == len(gs) - 1))
+    assert all(p.exact.values()), p.exact
+    # the caller's own view of e is settled by the query above
+    assert np.array_equal(p.gpu.e[:, :d].cpu().numpy().view(np.uint32), p.cpu.get("e").view(np.uint32))
+    p.close()
+
+
 def test_topk_is_deterministic():
     n, d, k = 4, 200000, 2000
     gs = rand_grads(9, n, d, 5)
