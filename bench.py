@@ -68,6 +68,12 @@ def main():
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
     ap.add_argument("--no-predict", action="store_true", help="ablation: re-read the row instead of guessing")
     ap.add_argument("--force-dense", action="store_true", help="ablation: no candidate lists at all")
+    ap.add_argument("--grad-buffers", type=int, default=0,
+                    help="how many distinct gradient buffers to cycle through (0: one per step)")
+    ap.add_argument("--settle-each-step", action="store_true",
+                    help="ablation: ask for e after every step, so that the residual zeroing is never deferred")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="time the steps without per-kernel events (the roofline object is then left out)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the n workers are rows of one buffer); --gpus must be 1",
@@ -90,17 +96,21 @@ def main():
 
     total = args.warmup + args.steps
     scale = W.coordinate_scale(w, dev)
-    grads = [W.gradients(w, t, device=dev, ld=ctx.ld, scale=scale) for t in range(total)]
+    nbuf = total if args.grad_buffers <= 0 else min(total, args.grad_buffers)
+    pool = [W.gradients(w, t, device=dev, ld=ctx.ld, scale=scale) for t in range(nbuf)]
+    grads = [pool[t % nbuf] for t in range(total)]
     torch.cuda.synchronize()
 
     for t in range(args.warmup):
         ctx.compams_step(grads[t], w.lr)
     # timed region: per-kernel HIP events ride along on the step's stream (their cost is part of the time)
-    ctx.profile_enable(True)
+    ctx.profile_enable(not args.no_kernel_events)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(args.warmup, total):
         ctx.compams_step(grads[t], w.lr)
+        if args.settle_each_step:
+            ctx.compams_state("e")
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = ctx.profile_read()
@@ -111,11 +121,16 @@ def main():
 
     bmin = algorithmic_bytes(w, w.compressor)
     kname, kbytes = dominant_kernel(w.compressor)
-    k_ms, k_launches = prof[kname]
-    k_avg_s = k_ms / k_launches * 1e-3
-    k_gbps = kbytes(w.n, w.d) / k_avg_s / 1e9
-    traffic = load_traffic(w.name, kname)
-    kernel_sum_ms = sum(ms for ms, _ in prof.values()) / args.steps
+    roofline = None
+    kernel_sum_ms = None
+    if prof:
+        k_ms, k_launches = prof[kname]
+        k_avg_s = k_ms / k_launches * 1e-3
+        k_gbps = kbytes(w.n, w.d) / k_avg_s / 1e9
+        kernel_sum_ms = sum(ms for ms, _ in prof.values()) / args.steps
+        roofline = {"bound": "hbm", "kernel": kname, "achieved": k_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": k_gbps / HBM_PEAK_GBPS, "traffic": load_traffic(w.name, kname),
+                    "avg_launch_us": k_avg_s * 1e6, "algorithmic_bytes_per_launch": kbytes(w.n, w.d)}
 
     counters = None
     if comp == B.TOPK:
@@ -153,9 +168,7 @@ def main():
         "hbm_frac_of_peak": bmin / (sec / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_step": bmin,
         "kernel_ms_per_step": kernel_sum_ms,
-        "roofline": {"bound": "hbm", "kernel": kname, "achieved": k_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": k_gbps / HBM_PEAK_GBPS, "traffic": traffic,
-                     "avg_launch_us": k_avg_s * 1e6, "algorithmic_bytes_per_launch": kbytes(w.n, w.d)},
+        "roofline": roofline,
         "kernels_us_per_step": {k_: v_[0] / args.steps * 1e3 for k_, v_ in prof.items()},
         "topk_counters": counters,
         "cpu_baseline": cpu,

@@ -9,7 +9,7 @@ namespace compams {
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 
 // 64-bit mask of the lanes of this wavefront for which p holds.
-__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p ? 1 : 0); }
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 
 // Number of set bits of mask that belong to lanes below the calling lane.
 __device__ __forceinline__ uint32_t count_below(uint64_t mask) {

@@ -34,6 +34,10 @@
 #include "compams_device.h"
 #include "compams_internal.h"
 
+#ifndef COMPAMS_DBG
+#define COMPAMS_DBG 0
+#endif
+
 namespace compams {
 namespace {
 
@@ -42,7 +46,17 @@ struct Quad {
   bool ok[4];
 };
 
+template <bool FULL>
 __device__ __forceinline__ void hist4(uint32_t* lh, const Quad& q, uint32_t& zeros) {
+  if (FULL) {
+    // common case: no zero key in the whole round -> four unconditional LDS adds
+    const uint32_t kmin = min(min(q.key[0], q.key[1]), min(q.key[2], q.key[3]));
+    if (ballot64(kmin == 0) == 0) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) atomicAdd(&lh[q.key[s] >> kL0Shift], 1u);
+      return;
+    }
+  }
   // Zero keys (frequent in sparse gradients) would serialise on one LDS word: count them by ballot.
   uint32_t z = 0;
 #pragma unroll
@@ -71,7 +85,7 @@ __device__ __forceinline__ RoundRank rank_round(const bool flag[4]) {
 // Candidate entries of the chunk a wavefront is walking are first staged in LDS (kStage entries per
 // wavefront) so that the chunk's segment can be allocated with one atomic once its size is known and
 // then written with coalesced stores.  A chunk with more candidates than that is re-read instead.
-constexpr int kStage = 512;
+constexpr int kStage = 256;
 
 __device__ __forceinline__ void stage_round(uint2* stage, uint32_t& n, uint32_t j, const uint32_t bits[4],
                                             const bool flag[4]) {
@@ -238,8 +252,13 @@ __device__ __forceinline__ void load_batch(Batch& b, const float* __restrict__ g
     b.g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
     b.e[u] = b.g[u];
     if (FULL || j < d) {
-      b.g[u] = load_stream4(gr + j);
-      b.e[u] = load_stream4(er + j);
+      if constexpr (COMPAMS_DBG & 16) {
+        b.g[u] = *reinterpret_cast<const float4*>(gr + j);
+        b.e[u] = *reinterpret_cast<const float4*>(er + j);
+      } else {
+        b.g[u] = load_stream4(gr + j);
+        b.e[u] = load_stream4(er + j);
+      }
     }
   }
 }
@@ -268,7 +287,11 @@ __device__ __forceinline__ void pass_a_chunk(const float* __restrict__ gr, float
 #pragma unroll 1
   for (int r0 = 0; r0 < kRounds; r0 += kBatch) {
     Batch nxt;
-    if (r0 + kBatch < kRounds) load_batch<FULL>(nxt, gr, er, base, r0 + kBatch, d);
+    if constexpr (COMPAMS_DBG & 128) {
+      if (r0) load_batch<FULL>(cur, gr, er, base, r0, d);
+    } else {
+      if (r0 + kBatch < kRounds) load_batch<FULL>(nxt, gr, er, base, r0 + kBatch, d);
+    }
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
       const int r = r0 + u;
@@ -276,7 +299,7 @@ __device__ __forceinline__ void pass_a_chunk(const float* __restrict__ gr, float
       const bool in = FULL || j < d;
       float4 ev = cur.e[u];
       const float4 gv = cur.g[u];
-      if constexpr (PEND) {
+      if constexpr (PEND && !(COMPAMS_DBG & 4)) {
         const uint32_t nib = (bm[r * 8 + (lane >> 3)] >> ((lane & 7u) * 4u)) & 15u;
         if (nib & 1u) ev.x = 0.0f;
         if (nib & 2u) ev.y = 0.0f;
@@ -291,28 +314,43 @@ __device__ __forceinline__ void pass_a_chunk(const float* __restrict__ gr, float
         if (!q.ok[2]) x.z = cur.e[u].z;
         if (!q.ok[3]) x.w = cur.e[u].w;
       }
-      if (in) store_stream4(er + j, x);
+      if (in) { if constexpr (COMPAMS_DBG & 32) *reinterpret_cast<float4*>(er + j) = x; else store_stream4(er + j, x); }
       const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
                                 __float_as_uint(x.w)};
 #pragma unroll
       for (int s = 0; s < 4; ++s) q.key[s] = key_of_bits(bits[s]);
-      hist4(lh, q, zeros);
-      if constexpr (PRED) {
+      if constexpr (!(COMPAMS_DBG & 1)) hist4<FULL>(lh, q, zeros);
+      if constexpr (PRED && !(COMPAMS_DBG & 2)) {
         if (pred) {
+          // candidates (bucket >= guess): staged in coordinate order; those in the two tracked buckets
+          // also go into the level-1 histograms
           bool flag[4];
+          uint64_t mk[4];
+          uint32_t total = 0;
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
-            const uint32_t rel = (q.key[s] >> kL0Shift) - bg;  // wraps to a huge value below the guess
             flag[s] = q.ok[s] && (q.key[s] >> kL0Shift) >= bg;
-            if (flag[s] && rel < 2u) atomicAdd(&lh1[rel * kNB1 + ((q.key[s] >> kL1Shift) & (kNB1 - 1))], 1u);
+            mk[s] = ballot64(flag[s]);
+            total += popc64(mk[s]);
           }
-          stage_round(stage, cnt, j, bits, flag);
+          if (total) {
+            uint32_t pos = cnt + count_below(mk[0]) + count_below(mk[1]) + count_below(mk[2]) + count_below(mk[3]);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+              if (flag[s]) {
+                if (pos < static_cast<uint32_t>(kStage)) stage[pos] = make_uint2(j + s, bits[s]);
+                ++pos;
+                const uint32_t rel = (q.key[s] >> kL0Shift) - bg;
+                if (rel < 2u) atomicAdd(&lh1[rel * kNB1 + ((q.key[s] >> kL1Shift) & (kNB1 - 1))], 1u);
+              }
+            cnt += total;
+          }
         }
       }
     }
-    cur = nxt;
+    if constexpr (!(COMPAMS_DBG & 128)) cur = nxt;
   }
-  if constexpr (PRED)
+  if constexpr (PRED && !(COMPAMS_DBG & 8))
     if (pred) flush_chunk(stage, cnt, er, d, c, bg, rowp, candr, cap, descr);
 }
 
@@ -372,6 +410,7 @@ __global__ __launch_bounds__(kWG) void k_topk_pass_a(const float* __restrict__ g
     }
 
   // ---- row-wide part, by whichever workgroup of the row finishes last ----
+  if constexpr (COMPAMS_DBG & 64) return;
   if (!last_group_of_row(&rowp->ticket[0], gridDim.x, &sh_flag)) return;
   take_hist<kNB0>(gh, lh);
   find_crossing<kNB0>(lh, geo.k, suf, out2);
