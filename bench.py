@@ -65,7 +65,8 @@ def main():
     ap.add_argument("--workload", default="r18_topk1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for the cpu_baseline leg")
-    ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--kernels", action="store_true",
+                    help="bracket every kernel with events and print the per-kernel table to stderr")
     ap.add_argument("--no-predict", action="store_true", help="ablation: re-read the row instead of guessing")
     ap.add_argument("--force-dense", action="store_true", help="ablation: no candidate lists at all")
     ap.add_argument("--grad-buffers", type=int, default=0,
@@ -103,8 +104,9 @@ def main():
 
     for t in range(args.warmup):
         ctx.compams_step(grads[t], w.lr)
-    # timed region: per-kernel HIP events ride along on the step's stream (their cost is part of the time)
-    ctx.profile_enable(not args.no_kernel_events)
+    # timed region: the dominant kernel is bracketed by HIP events on the step's stream (their cost is part of
+    # the measured time); --kernels brackets every kernel instead, which costs a few microseconds per kernel
+    ctx.profile_enable(0 if args.no_kernel_events else (1 if args.kernels else 2))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(args.warmup, total):
@@ -114,7 +116,7 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = ctx.profile_read()
-    ctx.profile_enable(False)
+    ctx.profile_enable(0)
     sec = t1 - t0
     ms_per_step = sec / args.steps * 1e3
     steps_per_s = args.steps / sec

@@ -180,8 +180,9 @@ class Compams:
     def set_option(self, option: int, value: int):
         _check(lib().compams_set_option(self._h, option, value), "compams_set_option")
 
-    def profile_enable(self, on: bool):
-        _check(lib().compams_profile_enable(self._h, 1 if on else 0), "compams_profile_enable")
+    def profile_enable(self, mode: int):
+        """0 off, 1 every kernel, 2 only the kernel that moves most of the bytes."""
+        _check(lib().compams_profile_enable(self._h, int(mode)), "compams_profile_enable")
 
     def profile_read(self):
         cap = 32

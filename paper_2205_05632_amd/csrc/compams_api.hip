@@ -18,13 +18,15 @@ struct Launcher {
   std::vector<Pair> pool;
   double total_ms[kNumSlots];
   int64_t launches[kNumSlots];
+  uint32_t mask;  // slots that are bracketed
   bool failed;
-  Launcher() : failed(false) {
+  Launcher() : mask(0), failed(false) {
     for (int i = 0; i < kNumSlots; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
   }
 };
 
 void launcher_begin(Launcher* L, int slot, hipStream_t stream) {
+  if (!(L->mask & (1u << slot))) return;
   Launcher::Pair p;
   if (!L->pool.empty()) {
     p = L->pool.back();
@@ -38,7 +40,7 @@ void launcher_begin(Launcher* L, int slot, hipStream_t stream) {
 }
 
 void launcher_end(Launcher* L, int slot, hipStream_t stream) {
-  if (L->pending[slot].empty()) return;
+  if (!(L->mask & (1u << slot)) || L->pending[slot].empty()) return;
   if (hipEventRecord(L->pending[slot].back().b, stream) != hipSuccess) L->failed = true;
 }
 
@@ -348,7 +350,11 @@ int compams_set_option(compams_ctx* ctx, int option, int64_t value) {
 
 int compams_profile_enable(compams_ctx* ctx, int enable) {
   if (!ctx) return COMPAMS_INVALID_ARG;
+  if (enable < 0 || enable > 2) return COMPAMS_INVALID_ARG;
   ctx->profiling = enable != 0;
+  // 1: every kernel; 2: only the kernel that moves most of the bytes (the first pass of each compressor)
+  ctx->launcher.mask = enable == 1 ? 0xffffffffu
+                                   : (1u << kSlotPassA) | (1u << kSlotBsPass1) | (1u << kSlotNoneAms);
   return COMPAMS_OK;
 }
 

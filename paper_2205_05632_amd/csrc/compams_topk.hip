@@ -796,16 +796,42 @@ __global__ __launch_bounds__(kWG) void k_topk_final(float* __restrict__ theta, f
   }
   __syncthreads();  // the chunk's list entries are visible to the whole workgroup
 
-  for (uint32_t i = 0; i < geo.n; ++i) {
-    const uint32_t* so = ws.sel_off + static_cast<size_t>(i) * (geo.num_chunks + 1) + c;
-    const uint32_t lo = so[0], hi = so[1];
-    const int32_t* idx = ws.idx + static_cast<size_t>(i) * geo.k;
-    const float* val = ws.val + static_cast<size_t>(i) * geo.k;
-    for (uint32_t q = lo + threadIdx.x; q < hi && q < geo.k; q += kWG) {
-      const uint32_t j = static_cast<uint32_t>(idx[q]) - base;
-      if (j < static_cast<uint32_t>(kChunk)) gs[j] = gs[j] + val[q];
+  // Workers are taken in groups of kGroup: every thread first requests its entry of each worker's chunk
+  // segment (independent loads, one round trip for the whole group), then the entries are added one worker
+  // after the other.
+  constexpr int kGroup = 8;
+  for (uint32_t i0 = 0; i0 < geo.n; i0 += kGroup) {
+    uint32_t lo[kGroup], hi[kGroup], jl[kGroup];
+    float vl[kGroup];
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+      const uint32_t i = i0 + u;
+      lo[u] = hi[u] = 0;
+      jl[u] = 0xffffffffu;
+      vl[u] = 0.0f;
+      if (i < geo.n) {
+        const uint32_t* so = ws.sel_off + static_cast<size_t>(i) * (geo.num_chunks + 1) + c;
+        lo[u] = so[0];
+        hi[u] = so[1] < geo.k ? so[1] : geo.k;
+        const uint32_t q = lo[u] + threadIdx.x;
+        if (q < hi[u]) {
+          jl[u] = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + q]) - base;
+          vl[u] = ws.val[static_cast<size_t>(i) * geo.k + q];
+        }
+      }
     }
-    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+      const uint32_t i = i0 + u;
+      if (i < geo.n) {  // uniform
+        if (jl[u] < static_cast<uint32_t>(kChunk)) gs[jl[u]] = gs[jl[u]] + vl[u];
+        for (uint32_t q = lo[u] + kWG + threadIdx.x; q < hi[u]; q += kWG) {  // segments longer than a workgroup
+          const uint32_t j = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + q]) - base;
+          if (j < static_cast<uint32_t>(kChunk)) gs[j] = gs[j] + ws.val[static_cast<size_t>(i) * geo.k + q];
+        }
+        __syncthreads();
+      }
+    }
   }
 
 #pragma unroll
