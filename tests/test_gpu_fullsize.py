@@ -1,0 +1,77 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times (default row stride,
+default options, gradients generated on the GPU by the workload module and copied to the host for the oracle).
+
+The oracle finishes a step of the ResNet-18-shaped workload in a few seconds, so everything is compared
+element by element; for the 124M-coordinate workload two steps are compared the same way."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import compams_oracle as O
+from paper_2205_05632_amd import binding as B
+from paper_2205_05632_amd import workloads as W
+
+from parity import close, bits_equal
+
+pytestmark = pytest.mark.gpu
+
+
+def run_full(name, steps, check_every_step=True):
+    w = W.get(name)
+    dev = torch.device("cuda:0")
+    comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE}[w.compressor]
+    th0 = W.theta0(w, dev)
+    gpu = B.Compams(w.n, w.d, th0, compressor=comp, k=w.k, block_offsets=w.block_offsets())
+    cpu = O.Oracle(w.n, w.d, th0.cpu().numpy(), compressor=comp, k=w.k, block_offsets=w.block_offsets())
+    scale = W.coordinate_scale(w, dev)
+    for t in range(steps):
+        g = W.gradients(w, t, device=dev, ld=gpu.ld, scale=scale)
+        gpu.compams_step(g, w.lr)
+        cpu.step(g[:, : w.d].cpu().contiguous().numpy(), w.lr)
+        del g
+        last = t == steps - 1
+        torch.cuda.synchronize()
+        if comp == B.TOPK:
+            assert np.array_equal(gpu.compams_state("last_idx").cpu().numpy(), cpu.get("idx")), f"{name} step {t}: index sets"
+            assert bits_equal(gpu.compams_state("last_val").cpu().numpy(), cpu.get("val")), f"{name} step {t}: values"
+        elif comp == B.BLOCKSIGN:
+            assert np.array_equal(gpu.compams_state("last_signbits").cpu().numpy().view(np.uint32), cpu.get("bits")), \
+                f"{name} step {t}: sign patterns"
+            assert bits_equal(gpu.compams_state("last_scales").cpu().numpy(), cpu.get("mu")), f"{name} step {t}: scales"
+        for s in ("theta", "m", "v", "vhat") + (("e",) if last and comp != B.NONE else ()):
+            a = gpu.compams_state(s).cpu().numpy()
+            b = cpu.get(s)
+            close(a, b, f"{name} step {t}: {s}")
+            assert bits_equal(np.ascontiguousarray(a), b), f"{name} step {t}: {s} is within tolerance but not bit-identical"
+    counters = gpu.compams_state("counters").cpu().numpy() if comp == B.TOPK else None
+    gpu.close(); cpu.close()
+    return counters
+
+
+def test_full_size_resnet18_topk_1_percent():
+    c = run_full("r18_topk1", 4)
+    assert (c[:, 0] == 0).all()          # by the 4th step every row took its candidates from the first pass
+
+
+def test_full_size_resnet18_topk_01_percent():
+    run_full("r18_topk01", 3)
+
+
+def test_full_size_resnet18_blocksign_layers():
+    run_full("r18_blocksign", 3)
+
+
+def test_full_size_resnet18_identity():
+    run_full("r18_none", 2)
+
+
+def test_full_size_resnet50_heavy_tailed_topk():
+    run_full("r50_topk1", 3)
+
+
+def test_full_size_gpt2_small_topk_with_zero_rows():
+    run_full("gpt2s_topk01", 2)
+
+
+def test_full_size_gpt2_small_blocksign_4096():
+    run_full("gpt2s_blocksign", 2)
