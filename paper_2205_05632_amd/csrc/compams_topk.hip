@@ -101,16 +101,23 @@ __device__ __forceinline__ void stage_round(uint2* stage, uint32_t& n, uint32_t 
   n += rr.total;
 }
 
-// Allocate the chunk's segment and write it: from the staging area if everything fitted there, else by
-// reading the chunk's (already stored) corrected gradients again.
-__device__ __forceinline__ void flush_chunk(const uint2* stage, uint32_t cnt, const float* __restrict__ er, uint32_t d,
-                                            uint32_t c, uint32_t thr_bucket, TopkRow* rowp, uint2* candr,
-                                            uint32_t cap, uint2* descr) {
+// Allocating a chunk's segment of the candidate list takes an atomic with return.  It is split in two so
+// that a caller can put other work between the request and the first use of its result.
+__device__ __forceinline__ uint32_t segment_request(TopkRow* rowp, uint32_t cnt) {
+  uint32_t raw = 0;
+  if (cnt && lane_id() == 0) raw = atomicAdd(&rowp->cursor, cnt);
+  return raw;  // meaningful in lane 0 only; nobody has looked at it yet
+}
+
+// Write the chunk's segment: from the staging area if everything fitted there, else by reading the chunk's
+// (already stored) corrected gradients again.
+__device__ __forceinline__ void segment_write(uint32_t raw, const uint2* stage, uint32_t cnt,
+                                              const float* __restrict__ er, uint32_t d, uint32_t c,
+                                              uint32_t thr_bucket, uint2* candr, uint32_t cap, uint2* descr) {
   const uint32_t lane = lane_id();
   uint32_t off = 0;
   if (cnt) {
-    if (lane == 0) off = atomicAdd(&rowp->cursor, cnt);
-    off = first_lane(off);
+    off = first_lane(raw);
     if (off + cnt <= cap) {  // otherwise the row's list has overflowed and will not be used
       if (cnt <= static_cast<uint32_t>(kStage)) {
         for (uint32_t q = lane; q < cnt; q += 64) candr[off + q] = stage[q];
@@ -139,6 +146,13 @@ __device__ __forceinline__ void flush_chunk(const uint2* stage, uint32_t cnt, co
     }
   }
   if (lane == 0) descr[c] = make_uint2(off, cnt);
+}
+
+__device__ __forceinline__ void flush_chunk(const uint2* stage, uint32_t cnt, const float* __restrict__ er, uint32_t d,
+                                            uint32_t c, uint32_t thr_bucket, TopkRow* rowp, uint2* candr,
+                                            uint32_t cap, uint2* descr) {
+  const uint32_t raw = segment_request(rowp, cnt);
+  segment_write(raw, stage, cnt, er, d, c, thr_bucket, candr, cap, descr);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -177,20 +191,20 @@ __device__ __forceinline__ void store_agent(uint32_t* p, uint32_t v) {
 // h: NB bucket counts in LDS.  Returns through out2 the largest s with sum_{b >= s} h[b] >= need and the
 // count strictly above it.  Requires 1 <= need <= sum h.
 // ---------------------------------------------------------------------------------------------
-template <int NB>
-__device__ void find_crossing(const uint32_t* h, uint32_t need, uint32_t* suf /* kWG + 1 */, uint32_t* out2) {
-  constexpr int PER = NB / kWG;
-  static_assert(NB % kWG == 0, "buckets per thread");
+template <int NB, int NT = kWG>
+__device__ void find_crossing(const uint32_t* h, uint32_t need, uint32_t* suf /* NT + 1 */, uint32_t* out2) {
+  constexpr int PER = NB / NT;
+  static_assert(NB % NT == 0, "buckets per thread");
   const int t = threadIdx.x;
   uint32_t part = 0;
 #pragma unroll
   for (int i = 0; i < PER; ++i) part += h[t * PER + i];
   __syncthreads();
   suf[t] = part;
-  if (t == 0) { suf[kWG] = 0; out2[0] = 0; out2[1] = 0; }
+  if (t == 0) { suf[NT] = 0; out2[0] = 0; out2[1] = 0; }
   __syncthreads();
-  for (int s = 1; s < kWG; s <<= 1) {  // inclusive suffix sums by doubling
-    const uint32_t add = (t + s < kWG) ? suf[t + s] : 0;
+  for (int s = 1; s < NT; s <<= 1) {  // inclusive suffix sums by doubling
+    const uint32_t add = (t + s < NT) ? suf[t + s] : 0;
     __syncthreads();
     suf[t] += add;
     __syncthreads();
@@ -211,9 +225,9 @@ __device__ void find_crossing(const uint32_t* h, uint32_t need, uint32_t* suf /*
 }
 
 // Copy a row's global histogram into LDS and clear it for the next step.
-template <int NB>
+template <int NB, int NT = kWG>
 __device__ __forceinline__ void take_hist(uint32_t* gh, uint32_t* h) {
-  for (int b = threadIdx.x; b < NB; b += kWG) {
+  for (int b = threadIdx.x; b < NB; b += NT) {
     h[b] = load_agent(gh + b);
     gh[b] = 0;
   }
@@ -222,9 +236,10 @@ __device__ __forceinline__ void take_hist(uint32_t* gh, uint32_t* h) {
 
 // bstar and need are passed in (not re-read from the control block): the caller may have written them a
 // moment ago, and a line of the control block read earlier by this compute unit may still sit in its L1.
+template <int NT = kWG>
 __device__ __forceinline__ void resolve_level1(TopkRow* rp, uint32_t bstar, uint32_t need, const uint32_t* h,
                                                uint32_t* suf, uint32_t* out2) {
-  find_crossing<kNB1>(h, need, suf, out2);
+  find_crossing<kNB1, NT>(h, need, suf, out2);
   if (threadIdx.x == 0) {
     rp->prefix1 = (bstar << (kL0Shift - kL1Shift)) | out2[0];
     rp->need = need - out2[1];
@@ -238,6 +253,11 @@ __device__ __forceinline__ void resolve_level1(TopkRow* rp, uint32_t bstar, uint
 //   PEND: coordinates selected in the previous step still hold their old value in e and count as zero.
 // ---------------------------------------------------------------------------------------------
 constexpr int kBatch = 4;  // rounds whose loads are in flight together
+#ifndef COMPAMS_WGA
+#define COMPAMS_WGA 256
+#endif
+constexpr int kWGA = COMPAMS_WGA;  // threads per workgroup of the first pass
+constexpr int kWavesA = kWGA / 64;
 
 struct Batch {
   float4 g[kBatch], e[kBatch];
@@ -263,111 +283,199 @@ __device__ __forceinline__ void load_batch(Batch& b, const float* __restrict__ g
   }
 }
 
-template <bool PRED, bool PEND, bool FULL>
-__device__ __forceinline__ void pass_a_chunk(const float* __restrict__ gr, float* __restrict__ er, uint32_t d,
-                                             uint32_t c, uint32_t* lh, uint32_t* lh1, uint32_t& zeros, bool pred,
-                                             uint32_t bg, TopkRow* rowp, uint2* candr, uint32_t cap, uint2* descr,
-                                             uint2* stage, uint32_t* bm, const uint32_t* __restrict__ prev_off,
-                                             const int32_t* __restrict__ prev_idx, uint32_t k) {
+// What one wavefront carries through its walk over chunks.
+struct PassA {
+  const float* gr;
+  float* er;
+  uint32_t d;
+  uint32_t* lh;          // level-0 histogram of the workgroup (LDS)
+  uint32_t* lh1;         // level-1 histograms of the two tracked buckets (LDS)
+  uint2* stage;          // this wavefront's staging area (LDS)
+  uint32_t* bm;          // this wavefront's bit map of pending zeros (LDS, 128 words)
+  bool pred;
+  uint32_t bg;
+  TopkRow* rowp;
+  uint2* candr;
+  uint32_t cap;
+  uint2* descr;
+  const uint32_t* prev_off;
+  const int32_t* prev_idx;
+  uint32_t k;
+  uint32_t zeros;        // zero keys seen (added to bin 0 at the end)
+};
+
+// The first 128 entries of a chunk's slice of the previous step's list, requested ahead of time.
+struct PendAhead {
+  uint32_t lo, hi;
+  uint32_t j0, j1;
+};
+
+__device__ __forceinline__ void pend_request(PendAhead& pa, const PassA& A, uint32_t c) {
   const uint32_t lane = lane_id();
-  const uint32_t base = c * kChunk + lane * 4;
-  uint32_t cnt = 0;
-  Batch cur;
-  load_batch<FULL>(cur, gr, er, base, 0, d);
+  pa.lo = A.prev_off[c];
+  pa.hi = A.prev_off[c + 1] < A.k ? A.prev_off[c + 1] : A.k;
+  pa.j0 = pa.lo + lane < pa.hi ? static_cast<uint32_t>(A.prev_idx[pa.lo + lane]) : 0xffffffffu;
+  pa.j1 = pa.lo + 64 + lane < pa.hi ? static_cast<uint32_t>(A.prev_idx[pa.lo + 64 + lane]) : 0xffffffffu;
+}
+
+// Bit map of the chunk's coordinates that were selected in the previous step (their residual is zero).
+__device__ __forceinline__ void pend_build(const PendAhead& pa, const PassA& A, uint32_t c) {
+  const uint32_t lane = lane_id();
+  A.bm[lane] = 0;
+  A.bm[lane + 64] = 0;
+  const uint32_t a = pa.j0 - c * kChunk, b = pa.j1 - c * kChunk;
+  if (a < static_cast<uint32_t>(kChunk)) atomicOr(&A.bm[a >> 5], 1u << (a & 31u));
+  if (b < static_cast<uint32_t>(kChunk)) atomicOr(&A.bm[b >> 5], 1u << (b & 31u));
+  for (uint32_t q = pa.lo + 128 + lane; q < pa.hi; q += 64) {  // dense chunks only
+    const uint32_t jl = static_cast<uint32_t>(A.prev_idx[q]) - c * kChunk;
+    if (jl < static_cast<uint32_t>(kChunk)) atomicOr(&A.bm[jl >> 5], 1u << (jl & 31u));
+  }
+}
+
+// One round (256 coordinates) of the first pass: x = e + g (pending zeros honoured), store, histogram,
+// candidate staging.  cnt is the running number of staged candidates of the chunk.
+template <bool PRED, bool PEND, bool FULL>
+__device__ __forceinline__ void pass_a_round(PassA& A, uint32_t j, int r, const float4& gv, const float4& e_in,
+                                             uint32_t& cnt) {
+  const uint32_t lane = lane_id();
+  const bool in = FULL || j < A.d;
+  float4 ev = e_in;
   if constexpr (PEND) {
-    // bit map of the chunk's coordinates that were selected in the previous step (their residual is zero)
-    bm[lane] = 0;
-    bm[lane + 64] = 0;
-    const uint32_t lo = prev_off[c], hi = prev_off[c + 1];
-    for (uint32_t q = lo + lane; q < hi && q < k; q += 64) {
-      const uint32_t jl = static_cast<uint32_t>(prev_idx[q]) - c * kChunk;
-      if (jl < static_cast<uint32_t>(kChunk)) atomicOr(&bm[jl >> 5], 1u << (jl & 31u));
+    const uint32_t nib = (A.bm[r * 8 + (lane >> 3)] >> ((lane & 7u) * 4u)) & 15u;
+    if (nib & 1u) ev.x = 0.0f;
+    if (nib & 2u) ev.y = 0.0f;
+    if (nib & 4u) ev.z = 0.0f;
+    if (nib & 8u) ev.w = 0.0f;
+  }
+  float4 x = make_float4(ev.x + gv.x, ev.y + gv.y, ev.z + gv.z, ev.w + gv.w);
+  Quad q;
+  q.ok[0] = in; q.ok[1] = FULL || j + 1 < A.d; q.ok[2] = FULL || j + 2 < A.d; q.ok[3] = FULL || j + 3 < A.d;
+  if (!FULL) {  // columns >= d keep what they held
+    if (!q.ok[1]) x.y = e_in.y;
+    if (!q.ok[2]) x.z = e_in.z;
+    if (!q.ok[3]) x.w = e_in.w;
+  }
+  if (in) store_stream4(A.er + j, x);
+  const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)};
+#pragma unroll
+  for (int s = 0; s < 4; ++s) q.key[s] = key_of_bits(bits[s]);
+  hist4<FULL>(A.lh, q, A.zeros);
+  if constexpr (PRED) {
+    if (A.pred) {
+      // candidates (bucket >= guess): staged in coordinate order; those in the two tracked buckets also go
+      // into the level-1 histograms
+      bool flag[4];
+      uint64_t mk[4];
+      uint32_t total = 0;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        flag[s] = q.ok[s] && (q.key[s] >> kL0Shift) >= A.bg;
+        mk[s] = ballot64(flag[s]);
+        total += popc64(mk[s]);
+      }
+      if (total) {
+        uint32_t pos = cnt + count_below(mk[0]) + count_below(mk[1]) + count_below(mk[2]) + count_below(mk[3]);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          if (flag[s]) {
+            if (pos < static_cast<uint32_t>(kStage)) A.stage[pos] = make_uint2(j + s, bits[s]);
+            ++pos;
+            const uint32_t rel = (q.key[s] >> kL0Shift) - A.bg;
+            if (rel < 2u) atomicAdd(&A.lh1[rel * kNB1 + ((q.key[s] >> kL1Shift) & (kNB1 - 1))], 1u);
+          }
+        cnt += total;
+      }
     }
   }
+}
+
+// A wavefront's walk over its chunks (c = first, first + stride, ...).  Loads run one batch of kBatch
+// rounds ahead of the arithmetic, across chunk boundaries too, so that the round trip of a chunk's
+// segment allocation (an atomic with return) and of the look-up of pending zeros never leaves the
+// wavefront without loads in flight.
+template <bool PRED, bool PEND>
+__device__ __forceinline__ void pass_a_walk(PassA& A, uint32_t first, uint32_t stride, uint32_t num_chunks) {
+  const uint32_t lane = lane_id();
+  const uint32_t nfull = A.d / kChunk;  // whole chunks
+  uint32_t c = first;
+  Batch cur;
+  PendAhead pa;
+  // the previous chunk's segment: requested, not yet written (its staging buffer is the other one)
+  bool p_have = false;
+  uint32_t p_raw = 0, p_cnt = 0, p_c = 0;
+  uint2* const stage0 = A.stage;
+  uint32_t buf = 0;
+  if (c < nfull) {
+    load_batch<true>(cur, A.gr, A.er, c * kChunk + lane * 4, 0, A.d);
+    if constexpr (PEND) pend_request(pa, A, c);
+  }
+  while (c < nfull) {
+    const uint32_t cn = c + stride;
+    const bool more = cn < nfull;
+    const uint32_t base = c * kChunk + lane * 4;
+    if constexpr (PEND) pend_build(pa, A, c);
+    A.stage = stage0 + buf * kStage;
+    uint32_t cnt = 0;
 #pragma unroll 1
-  for (int r0 = 0; r0 < kRounds; r0 += kBatch) {
-    Batch nxt;
-    if constexpr (COMPAMS_DBG & 128) {
-      if (r0) load_batch<FULL>(cur, gr, er, base, r0, d);
-    } else {
-      if (r0 + kBatch < kRounds) load_batch<FULL>(nxt, gr, er, base, r0 + kBatch, d);
+    for (int r0 = 0; r0 < kRounds; r0 += kBatch) {
+      Batch nxt;
+      if (r0 + kBatch < kRounds) load_batch<true>(nxt, A.gr, A.er, base, r0 + kBatch, A.d);
+      else if (more) load_batch<true>(nxt, A.gr, A.er, cn * kChunk + lane * 4, 0, A.d);
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        pass_a_round<PRED, PEND, true>(A, base + (r0 + u) * 256, r0 + u, cur.g[u], cur.e[u], cnt);
+      cur = nxt;
     }
-#pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      const int r = r0 + u;
-      const uint32_t j = base + r * 256;
-      const bool in = FULL || j < d;
-      float4 ev = cur.e[u];
-      const float4 gv = cur.g[u];
-      if constexpr (PEND && !(COMPAMS_DBG & 4)) {
-        const uint32_t nib = (bm[r * 8 + (lane >> 3)] >> ((lane & 7u) * 4u)) & 15u;
-        if (nib & 1u) ev.x = 0.0f;
-        if (nib & 2u) ev.y = 0.0f;
-        if (nib & 4u) ev.z = 0.0f;
-        if (nib & 8u) ev.w = 0.0f;
-      }
-      float4 x = make_float4(ev.x + gv.x, ev.y + gv.y, ev.z + gv.z, ev.w + gv.w);
-      Quad q;
-      q.ok[0] = in; q.ok[1] = FULL || j + 1 < d; q.ok[2] = FULL || j + 2 < d; q.ok[3] = FULL || j + 3 < d;
-      if (!FULL) {  // columns >= d keep what they held
-        if (!q.ok[1]) x.y = cur.e[u].y;
-        if (!q.ok[2]) x.z = cur.e[u].z;
-        if (!q.ok[3]) x.w = cur.e[u].w;
-      }
-      if (in) { if constexpr (COMPAMS_DBG & 32) *reinterpret_cast<float4*>(er + j) = x; else store_stream4(er + j, x); }
-      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
-                                __float_as_uint(x.w)};
-#pragma unroll
-      for (int s = 0; s < 4; ++s) q.key[s] = key_of_bits(bits[s]);
-      if constexpr (!(COMPAMS_DBG & 1)) hist4<FULL>(lh, q, zeros);
-      if constexpr (PRED && !(COMPAMS_DBG & 2)) {
-        if (pred) {
-          // candidates (bucket >= guess): staged in coordinate order; those in the two tracked buckets
-          // also go into the level-1 histograms
-          bool flag[4];
-          uint64_t mk[4];
-          uint32_t total = 0;
-#pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            flag[s] = q.ok[s] && (q.key[s] >> kL0Shift) >= bg;
-            mk[s] = ballot64(flag[s]);
-            total += popc64(mk[s]);
-          }
-          if (total) {
-            uint32_t pos = cnt + count_below(mk[0]) + count_below(mk[1]) + count_below(mk[2]) + count_below(mk[3]);
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-              if (flag[s]) {
-                if (pos < static_cast<uint32_t>(kStage)) stage[pos] = make_uint2(j + s, bits[s]);
-                ++pos;
-                const uint32_t rel = (q.key[s] >> kL0Shift) - bg;
-                if (rel < 2u) atomicAdd(&lh1[rel * kNB1 + ((q.key[s] >> kL1Shift) & (kNB1 - 1))], 1u);
-              }
-            cnt += total;
-          }
-        }
+    if constexpr (PEND)
+      if (more) pend_request(pa, A, cn);
+    if constexpr (PRED && !(COMPAMS_DBG & 8)) {
+      if (A.pred) {
+        // request this chunk's segment now, write the previous chunk's (whose request returned long ago)
+        const uint32_t raw = segment_request(A.rowp, cnt);
+        if (p_have)
+          segment_write(p_raw, stage0 + (buf ^ 1u) * kStage, p_cnt, A.er, A.d, p_c, A.bg, A.candr, A.cap, A.descr);
+        p_have = true; p_raw = raw; p_cnt = cnt; p_c = c;
+        buf ^= 1u;
       }
     }
-    if constexpr (!(COMPAMS_DBG & 128)) cur = nxt;
+    c = cn;
   }
-  if constexpr (PRED && !(COMPAMS_DBG & 8))
-    if (pred) flush_chunk(stage, cnt, er, d, c, bg, rowp, candr, cap, descr);
+  if constexpr (PRED)
+    if (p_have) segment_write(p_raw, stage0 + (buf ^ 1u) * kStage, p_cnt, A.er, A.d, p_c, A.bg, A.candr, A.cap, A.descr);
+  A.stage = stage0;
+  if (c == nfull && nfull < num_chunks) {  // the row's last, partial chunk
+    const uint32_t base = c * kChunk + lane * 4;
+    if constexpr (PEND) {
+      pend_request(pa, A, c);
+      pend_build(pa, A, c);
+    }
+    uint32_t cnt = 0;
+#pragma unroll 1
+    for (int r0 = 0; r0 < kRounds; r0 += kBatch) {
+      load_batch<false>(cur, A.gr, A.er, base, r0, A.d);
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u)
+        pass_a_round<PRED, PEND, false>(A, base + (r0 + u) * 256, r0 + u, cur.g[u], cur.e[u], cnt);
+    }
+    if constexpr (PRED)
+      if (A.pred) flush_chunk(A.stage, cnt, A.er, A.d, c, A.bg, A.rowp, A.candr, A.cap, A.descr);
+  }
 }
 
 template <bool PRED, bool PEND>
-__global__ __launch_bounds__(kWG) void k_topk_pass_a(const float* __restrict__ g, float* __restrict__ e,
+__global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ g, float* __restrict__ e,
                                                       Geometry geo, TopkWorkspace ws, TopkOptions opt) {
   __shared__ uint32_t lh[kNB0];
   __shared__ uint32_t lh1[PRED ? 2 * kNB1 : 1];
-  __shared__ uint2 stage_all[PRED ? kWaves * kStage : 1];
-  __shared__ uint32_t bm_all[PEND ? kWaves * 128 : 1];
-  __shared__ uint32_t suf[kWG + 1];
+  __shared__ uint2 stage_all[PRED ? kWavesA * 2 * kStage : 1];
+  __shared__ uint32_t bm_all[PEND ? kWavesA * 128 : 1];
+  __shared__ uint32_t suf[kWGA + 1];
   __shared__ uint32_t out2[2];
   __shared__ uint32_t sh_flag, sh_l1, sh_bstar, sh_need;
   const uint32_t row = blockIdx.y;
-  for (int b = threadIdx.x; b < kNB0; b += kWG) lh[b] = 0;
+  for (int b = threadIdx.x; b < kNB0; b += kWGA) lh[b] = 0;
   if (PRED)
-    for (int b = threadIdx.x; b < 2 * kNB1; b += kWG) lh1[b] = 0;
+    for (int b = threadIdx.x; b < 2 * kNB1; b += kWGA) lh1[b] = 0;
   __syncthreads();
   const float* gr = g + static_cast<int64_t>(row) * geo.ld;
   float* er = e + static_cast<int64_t>(row) * geo.ld;
@@ -383,28 +491,24 @@ __global__ __launch_bounds__(kWG) void k_topk_pass_a(const float* __restrict__ g
   const uint32_t* prev_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
   const int32_t* prev_idx = ws.idx + static_cast<size_t>(row) * geo.k;
   const uint32_t wave = threadIdx.x >> 6;
-  uint2* stage = stage_all + (PRED ? wave * kStage : 0);
+  uint2* stage = stage_all + (PRED ? wave * 2 * kStage : 0);
   uint32_t* bm = bm_all + (PEND ? wave * 128 : 0);
-  const uint32_t stride = gridDim.x * kWaves;
-  uint32_t zeros = 0;
-  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
-    if ((c + 1) * static_cast<uint64_t>(kChunk) <= geo.d)
-      pass_a_chunk<PRED, PEND, true>(gr, er, geo.d, c, lh, lh1, zeros, pred, bg, rowp, candr, opt.cap, descr, stage,
-                                     bm, prev_off, prev_idx, geo.k);
-    else
-      pass_a_chunk<PRED, PEND, false>(gr, er, geo.d, c, lh, lh1, zeros, pred, bg, rowp, candr, opt.cap, descr, stage,
-                                      bm, prev_off, prev_idx, geo.k);
-  }
+  PassA A;
+  A.gr = gr; A.er = er; A.d = geo.d; A.lh = lh; A.lh1 = lh1; A.stage = stage; A.bm = bm; A.pred = pred; A.bg = bg;
+  A.rowp = rowp; A.candr = candr; A.cap = opt.cap; A.descr = descr; A.prev_off = prev_off; A.prev_idx = prev_idx;
+  A.k = geo.k; A.zeros = 0;
+  pass_a_walk<PRED, PEND>(A, blockIdx.x * kWavesA + wave, gridDim.x * kWavesA, geo.num_chunks);
+  const uint32_t zeros = A.zeros;
   if (zeros && lane_id() == 0) atomicAdd(&lh[0], zeros);
   __syncthreads();
   uint32_t* gh = ws.hist0 + static_cast<size_t>(row) * kNB0;
-  for (int b = threadIdx.x; b < kNB0; b += kWG) {
+  for (int b = threadIdx.x; b < kNB0; b += kWGA) {
     const uint32_t h = lh[b];
     if (h) atomicAdd(&gh[b], h);
   }
   uint32_t* gh1 = ws.hist1x + static_cast<size_t>(row) * 2 * kNB1;
   if (PRED && pred)
-    for (int b = threadIdx.x; b < 2 * kNB1; b += kWG) {
+    for (int b = threadIdx.x; b < 2 * kNB1; b += kWGA) {
       const uint32_t h = lh1[b];
       if (h) atomicAdd(&gh1[b], h);
     }
@@ -412,8 +516,8 @@ __global__ __launch_bounds__(kWG) void k_topk_pass_a(const float* __restrict__ g
   // ---- row-wide part, by whichever workgroup of the row finishes last ----
   if constexpr (COMPAMS_DBG & 64) return;
   if (!last_group_of_row(&rowp->ticket[0], gridDim.x, &sh_flag)) return;
-  take_hist<kNB0>(gh, lh);
-  find_crossing<kNB0>(lh, geo.k, suf, out2);
+  take_hist<kNB0, kWGA>(gh, lh);
+  find_crossing<kNB0, kWGA>(lh, geo.k, suf, out2);
   if (threadIdx.x == 0) {
     const uint32_t bstar = out2[0], above = out2[1];
     const uint32_t total = above + lh[bstar];  // entries with bucket >= bstar
@@ -450,11 +554,11 @@ __global__ __launch_bounds__(kWG) void k_topk_pass_a(const float* __restrict__ g
   if (PRED && pred) {
     const uint32_t which = sh_l1;  // 0: level 1 not available; 1, 2: histogram of bucket guess, guess + 1
     if (which) {
-      for (int b = threadIdx.x; b < kNB1; b += kWG) lh[b] = load_agent(gh1 + (which - 1) * kNB1 + b);
+      for (int b = threadIdx.x; b < kNB1; b += kWGA) lh[b] = load_agent(gh1 + (which - 1) * kNB1 + b);
     }
-    for (int b = threadIdx.x; b < 2 * kNB1; b += kWG) gh1[b] = 0;
+    for (int b = threadIdx.x; b < 2 * kNB1; b += kWGA) gh1[b] = 0;
     __syncthreads();
-    if (which) resolve_level1(rowp, sh_bstar, sh_need, lh, suf, out2);
+    if (which) resolve_level1<kWGA>(rowp, sh_bstar, sh_need, lh, suf, out2);
   }
 }
 
@@ -885,17 +989,17 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
                      const float* g, float* e, float* theta, float* m, float* v, float* vhat,
                      bool first_pass_may_predict, bool clear_pending, hipStream_t stream, Launcher* L) {
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
-  uint32_t GA = groups_first_pass(geo.n, geo.num_chunks);
+  uint32_t GA = groups_first_pass(geo.n, geo.num_chunks, kWavesA);
   if (getenv("COMPAMS_TUNE_GA")) GA = atoi(getenv("COMPAMS_TUNE_GA"));
-  const dim3 grid_rows(G, geo.n), wg(kWG), grid_a(GA, geo.n);
+  const dim3 grid_rows(G, geo.n), wg(kWG), grid_a(GA, geo.n), wga(kWGA);
   {
     ScopedSlot s(L, kSlotPassA, stream);
     if (first_pass_may_predict) {
-      if (clear_pending) hipLaunchKernelGGL((k_topk_pass_a<true, true>), grid_a, wg, 0, stream, g, e, geo, ws, opt);
-      else hipLaunchKernelGGL((k_topk_pass_a<true, false>), grid_a, wg, 0, stream, g, e, geo, ws, opt);
+      if (clear_pending) hipLaunchKernelGGL((k_topk_pass_a<true, true>), grid_a, wga, 0, stream, g, e, geo, ws, opt);
+      else hipLaunchKernelGGL((k_topk_pass_a<true, false>), grid_a, wga, 0, stream, g, e, geo, ws, opt);
     } else {
-      if (clear_pending) hipLaunchKernelGGL((k_topk_pass_a<false, true>), grid_a, wg, 0, stream, g, e, geo, ws, opt);
-      else hipLaunchKernelGGL((k_topk_pass_a<false, false>), grid_a, wg, 0, stream, g, e, geo, ws, opt);
+      if (clear_pending) hipLaunchKernelGGL((k_topk_pass_a<false, true>), grid_a, wga, 0, stream, g, e, geo, ws, opt);
+      else hipLaunchKernelGGL((k_topk_pass_a<false, false>), grid_a, wga, 0, stream, g, e, geo, ws, opt);
     }
   }
   COMPAMS_CHECK_LAUNCH();
