@@ -763,23 +763,65 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
   const uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
   const uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
   const size_t rb = static_cast<size_t>(row) * geo.num_chunks;
-  const uint32_t wave = threadIdx.x >> 6;
-  const uint32_t stride = gridDim.x * kWaves;
-  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
-    uint32_t gt = 0, eq = 0;
-    for_each_round(mode, er, geo.d, c, candr, descr, opt.cap, [&](const Entry4& en, int slots) {
-      for (int s = 0; s < slots; ++s) {
-        const uint32_t key = key_of_bits(en.bits[s]);
-        gt += popc64(ballot64(en.ok[s] && key > tau));
-        eq += popc64(ballot64(en.ok[s] && key == tau));
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  if (mode == kModeDense) {
+    const uint32_t stride = gridDim.x * kWaves;
+    for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+      uint32_t gt = 0, eq = 0;
+      for_each_round(mode, er, geo.d, c, candr, descr, opt.cap, [&](const Entry4& en, int slots) {
+        for (int s = 0; s < slots; ++s) {
+          const uint32_t key = key_of_bits(en.bits[s]);
+          gt += popc64(ballot64(en.ok[s] && key > tau));
+          eq += popc64(ballot64(en.ok[s] && key == tau));
+        }
+      });
+      if (lane == 0) {  // read back by the row's last workgroup in this same launch
+        store_agent(ws.cnt_gt + rb + c, gt);
+        store_agent(ws.cnt_eq + rb + c, eq);
       }
-    });
-    if (lane_id() == 0) {  // read back by the row's last workgroup in this same launch
-      store_agent(ws.cnt_gt + rb + c, gt);
-      store_agent(ws.cnt_eq + rb + c, eq);
+    }
+  } else {
+    // A wavefront takes kGroup consecutive chunks at a time: their descriptors come with one load, the first
+    // 128 entries of every segment with independent loads (two round trips for the whole group).
+    constexpr int kGroup = 8;
+    const uint32_t stride = gridDim.x * kWaves * kGroup;
+    for (uint32_t c0 = (blockIdx.x * kWaves + wave) * kGroup; c0 < geo.num_chunks; c0 += stride) {
+      uint2 ds = make_uint2(0, 0);
+      if (lane < kGroup && c0 + lane < geo.num_chunks) ds = descr[c0 + lane];
+      if (ds.x > opt.cap) ds.y = 0;  // segments always lie inside the list; never read outside it
+      else if (ds.y > opt.cap - ds.x) ds.y = opt.cap - ds.x;
+      uint32_t off[kGroup], cnt[kGroup];
+      uint2 a[kGroup], b[kGroup];
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        off[u] = __builtin_amdgcn_readlane(ds.x, u);
+        cnt[u] = __builtin_amdgcn_readlane(ds.y, u);
+        a[u] = lane < cnt[u] ? candr[off[u] + lane] : make_uint2(0, 0);
+        b[u] = lane + 64 < cnt[u] ? candr[off[u] + lane + 64] : make_uint2(0, 0);
+      }
+      uint32_t my_gt = 0, my_eq = 0;
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        const uint32_t ka = key_of_bits(a[u].y), kb = key_of_bits(b[u].y);
+        uint32_t gt = popc64(ballot64(lane < cnt[u] && ka > tau)) + popc64(ballot64(lane + 64 < cnt[u] && kb > tau));
+        uint32_t eq = popc64(ballot64(lane < cnt[u] && ka == tau)) + popc64(ballot64(lane + 64 < cnt[u] && kb == tau));
+        for (uint32_t t = 128; t < cnt[u]; t += 64) {  // long segments
+          const bool ok = t + lane < cnt[u];
+          const uint32_t key = ok ? key_of_bits(candr[off[u] + t + lane].y) : 0;
+          gt += popc64(ballot64(ok && key > tau));
+          eq += popc64(ballot64(ok && key == tau));
+        }
+        if (lane == static_cast<uint32_t>(u)) { my_gt = gt; my_eq = eq; }
+      }
+      if (lane < kGroup && c0 + lane < geo.num_chunks) {  // read back by the row's last workgroup in this launch
+        store_agent(ws.cnt_gt + rb + c0 + lane, my_gt);
+        store_agent(ws.cnt_eq + rb + c0 + lane, my_eq);
+      }
     }
   }
+  if constexpr (COMPAMS_DBG & 256) return;
   if (!last_group_of_row(&rowp->ticket[3], gridDim.x, &sh_flag)) return;
+  if constexpr (COMPAMS_DBG & 512) return;
   const uint32_t r = rowp->r;
   uint32_t* sel_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
   uint32_t eq_carry = 0, sel_carry = 0;
@@ -1010,7 +1052,9 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   COMPAMS_CHECK_LAUNCH();
   {
     ScopedSlot s(L, kSlotLevel2, stream);
-    hipLaunchKernelGGL(k_topk_level2, grid_rows, wg, 0, stream, e, geo, ws, opt);
+    uint32_t G2 = G;
+    if (getenv("COMPAMS_TUNE_G2")) G2 = atoi(getenv("COMPAMS_TUNE_G2"));
+    hipLaunchKernelGGL(k_topk_level2, dim3(G2, geo.n), wg, 0, stream, e, geo, ws, opt);
   }
   COMPAMS_CHECK_LAUNCH();
   {
