@@ -57,7 +57,7 @@ struct Layout {
   // top-k
   size_t rows, counters, hist0, hist1, hist1x, hist2, cnt_gt, cnt_eq, sel_off, eq_before, desc, cand, idx, val, tau;
   // block-sign
-  size_t offsets, chunk_block, acc, special, scales, bits;
+  size_t offsets, chunk_block, acc, special, done, scales, bits;
   uint32_t cap_alloc, num_chunks, words;
 };
 
@@ -106,6 +106,7 @@ Layout make_layout(const compams_config* c) {
     L.chunk_block = take(nc * 4);
     L.acc = take(n * M * kLimbs * 8);
     L.special = take(n * M * 4);
+    L.done = take(n * M * 4);
     L.scales = take(n * M * 4);
     L.bits = take(n * static_cast<size_t>(L.words) * 4);
   }
@@ -222,6 +223,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     b.chunk_block = reinterpret_cast<uint32_t*>(w + lay.chunk_block);
     b.acc = reinterpret_cast<uint64_t*>(w + lay.acc);
     b.special = reinterpret_cast<uint32_t*>(w + lay.special);
+    b.done = reinterpret_cast<uint32_t*>(w + lay.done);
     b.scales = reinterpret_cast<float*>(w + lay.scales);
     b.bits = reinterpret_cast<uint32_t*>(w + lay.bits);
     std::vector<uint32_t> off32, cb;
@@ -230,6 +232,9 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
       cb.resize(lay.num_chunks);
     } catch (...) { delete ctx; return COMPAMS_HIP_ERROR; }
     for (int64_t i = 0; i <= cfg->num_blocks; ++i) off32[static_cast<size_t>(i)] = static_cast<uint32_t>(cfg->block_offsets[i]);
+    bool uniform = static_cast<uint32_t>(cfg->num_blocks) == lay.num_chunks;
+    for (int64_t i = 0; uniform && i < cfg->num_blocks; ++i) uniform = cfg->block_offsets[i] == i * kChunk;
+    b.uniform4096 = uniform ? 1u : 0u;
     uint32_t blk = 0;
     for (uint32_t c = 0; c < lay.num_chunks; ++c) {
       const uint32_t j = c * static_cast<uint32_t>(kChunk);

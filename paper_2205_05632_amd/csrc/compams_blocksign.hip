@@ -14,6 +14,8 @@
 // re-reads x and writes sign bits and residuals, and the server kernel adds the n workers' +-mu in
 // worker order before the AMSGrad update.
 
+#include <cstdlib>
+
 #include "compams_device.h"
 #include "compams_internal.h"
 
@@ -102,8 +104,61 @@ __device__ __forceinline__ uint32_t block_of(const uint32_t* __restrict__ off, u
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pass 1: x = e + g -> e and exact block sums.  Grid (groups_per_row, n), one wavefront per chunk.
+// Exact rounding of a fixed-point sum to double (nearest, ties to even).
+// The value is (w2:w1:w0 as a 192-bit integer) * 2^lsb_exp; extra_sticky says that non-zero bits exist
+// below bit 0 (they can only matter as a sticky bit).
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ double fixed192_to_double(uint64_t w0, uint64_t w1, uint64_t w2, int lsb_exp,
+                                                     bool extra_sticky) {
+  int top;
+  if (w2) top = 128 + 63 - __clzll(static_cast<long long>(w2));
+  else if (w1) top = 64 + 63 - __clzll(static_cast<long long>(w1));
+  else if (w0) top = 63 - __clzll(static_cast<long long>(w0));
+  else return 0.0;
+  if (top <= 52) return ldexp(static_cast<double>(w0), lsb_exp);  // fits a double exactly (extra_sticky is then false)
+  const int sh = top - 52;  // bits dropped: 1 .. 139
+  auto word = [&](int i) -> uint64_t { return i == 0 ? w0 : (i == 1 ? w1 : (i == 2 ? w2 : 0ull)); };
+  const int wi = sh >> 6, bi = sh & 63;
+  uint64_t kept = bi ? ((word(wi) >> bi) | (word(wi + 1) << (64 - bi))) : word(wi);
+  const int gp = sh - 1, gw = gp >> 6, gb = gp & 63;
+  const bool guard = ((word(gw) >> gb) & 1ull) != 0;
+  bool sticky = extra_sticky || (word(gw) & ((1ull << gb) - 1ull)) != 0;
+  if (gw >= 1) sticky = sticky || w0 != 0;
+  if (gw >= 2) sticky = sticky || w1 != 0;
+  if (guard && (sticky || (kept & 1ull))) ++kept;  // may reach 2^53: still exact
+  return ldexp(static_cast<double>(kept), lsb_exp + sh);
+}
+
+// Sum of three 64-bit digit accumulators that sit 32 bits apart (s0 lowest) as a 192-bit integer.
+__device__ __forceinline__ void digits3_to_192(uint64_t s0, uint64_t s1, uint64_t s2, uint64_t& w0, uint64_t& w1,
+                                               uint64_t& w2) {
+  // value = s0 + s1 * 2^32 + s2 * 2^64
+  w0 = s0;
+  w1 = 0;
+  w2 = 0;
+  const uint64_t a = s1 << 32, ah = s1 >> 32;
+  w0 += a;
+  uint64_t c = w0 < a ? 1ull : 0ull;
+  w1 = ah + c;  // ah < 2^32: no wrap
+  const uint64_t t = w1 + s2;
+  w2 = t < s2 ? 1ull : 0ull;
+  w1 = t;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 1: x = e + g -> e and exact block sums.  Grid (groups, n), one wavefront per chunk, loads one
+// batch of rounds ahead.
+// ---------------------------------------------------------------------------------------------
+constexpr int kBsBatch = 4;
+
+__device__ __forceinline__ void bs_add_direct(uint64_t* dg, uint32_t* special, const Fixed& f) {
+  if (f.special) atomicOr(special, f.special);
+  else {
+    if (f.lo) atomic_add_u64(dg + f.w, f.lo);
+    if (f.hi) atomic_add_u64(dg + f.w + 1, f.hi);
+  }
+}
+
 __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
                                                    BlocksignWorkspace ws) {
   const uint32_t row = blockIdx.y;
@@ -119,65 +174,70 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
     uint32_t b = ws.chunk_block[c];  // wave-uniform: block of the chunk's first coordinate
     WaveAcc A;
     A.a0 = A.a1 = A.a2 = 0; A.live = false; A.centre = 0;
-    for (int r = 0; r < kRounds; ++r) {
-      const uint32_t j0 = c * kChunk + r * 256;  // wave-uniform
-      if (j0 >= d) break;
-      const uint32_t j = j0 + lane * 4;
-      const bool in = j < d;
-      float4 gv = make_float4(0.f, 0.f, 0.f, 0.f), ev = gv;
-      if (in) {
-        gv = *reinterpret_cast<const float4*>(gr + j);
-        ev = *reinterpret_cast<const float4*>(er + j);
+#pragma unroll 1
+    for (int r0 = 0; r0 < kRounds; r0 += kBsBatch) {
+      if (c * kChunk + r0 * 256 >= d) break;  // wave-uniform
+      float4 gv[kBsBatch], ev[kBsBatch];
+#pragma unroll
+      for (int u = 0; u < kBsBatch; ++u) {
+        const uint32_t j = c * kChunk + (r0 + u) * 256 + lane * 4;
+        gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        ev[u] = gv[u];
+        if (j < d) {
+          gv[u] = load_stream4(gr + j);
+          ev[u] = load_stream4(er + j);
+        }
       }
-      float4 x = make_float4(ev.x + gv.x, ev.y + gv.y, ev.z + gv.z, ev.w + gv.w);
-      const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
-      if (!ok[1]) x.y = ev.y;
-      if (!ok[2]) x.z = ev.z;
-      if (!ok[3]) x.w = ev.w;
-      if (in) *reinterpret_cast<float4*>(er + j) = x;
-      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
-                                __float_as_uint(x.w)};
-      // leave blocks that end at or before this round
-      while (off[b + 1] <= j0) {
-        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
-        ++b;
-      }
-      const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
-      if (off[b + 1] >= j_end) {
-        // the whole round lies in block b
-        if (!A.live) {
-          // centre the register digits on the largest magnitude of this round
-          uint32_t kmax = 0;
+#pragma unroll
+      for (int u = 0; u < kBsBatch; ++u) {
+        const uint32_t j0 = c * kChunk + (r0 + u) * 256;  // wave-uniform
+        if (j0 >= d) break;
+        const uint32_t j = j0 + lane * 4;
+        const bool in = j < d;
+        float4 x = make_float4(ev[u].x + gv[u].x, ev[u].y + gv[u].y, ev[u].z + gv[u].z, ev[u].w + gv[u].w);
+        const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
+        if (!ok[1]) x.y = ev[u].y;
+        if (!ok[2]) x.z = ev[u].z;
+        if (!ok[3]) x.w = ev[u].w;
+        if (in) store_stream4(er + j, x);
+        const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
+                                  __float_as_uint(x.w)};
+        // leave blocks that end at or before this round
+        while (off[b + 1] <= j0) {
+          acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+          ++b;
+        }
+        const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
+        if (off[b + 1] >= j_end) {
+          // the whole round lies in block b
+          if (!A.live) {
+            // centre the register digits on the largest magnitude of this round
+            uint32_t kmax = 0;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+              const uint32_t key = bits[s] & 0x7fffffffu;
+              if (ok[s] && key < 0x7f800000u && key > kmax) kmax = key;
+            }
+#pragma unroll
+            for (int s = 32; s >= 1; s >>= 1) {
+              const uint32_t o = __shfl_xor(kmax, s, 64);
+              kmax = o > kmax ? o : kmax;
+            }
+            const uint32_t ex = kmax >> 23;
+            A.centre = (ex ? ex - 1 : 0) >> 5;
+            A.live = true;
+          }
+#pragma unroll
+          for (int s = 0; s < 4; ++s)
+            acc_add(A, to_fixed(bits[s]), ok[s], accr + static_cast<size_t>(b) * kLimbs, specr + b);
+        } else {
+          // the round straddles block boundaries: every coordinate goes to its own block's digits
+          acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
-            const uint32_t key = bits[s] & 0x7fffffffu;
-            if (ok[s] && key < 0x7f800000u && key > kmax) kmax = key;
-          }
-#pragma unroll
-          for (int s = 32; s >= 1; s >>= 1) {
-            const uint32_t o = __shfl_xor(kmax, s, 64);
-            kmax = o > kmax ? o : kmax;
-          }
-          const uint32_t ex = kmax >> 23;
-          A.centre = (ex ? ex - 1 : 0) >> 5;
-          A.live = true;
-        }
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-          acc_add(A, to_fixed(bits[s]), ok[s], accr + static_cast<size_t>(b) * kLimbs, specr + b);
-      } else {
-        // the round straddles block boundaries: every coordinate goes to its own block's digits
-        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          if (!ok[s]) continue;
-          const uint32_t bb = block_of(off, b, j + s);
-          const Fixed f = to_fixed(bits[s]);
-          uint64_t* dg = accr + static_cast<size_t>(bb) * kLimbs;
-          if (f.special) atomicOr(specr + bb, f.special);
-          else {
-            if (f.lo) atomic_add_u64(dg + f.w, f.lo);
-            if (f.hi) atomic_add_u64(dg + f.w + 1, f.hi);
+            if (!ok[s]) continue;
+            const uint32_t bb = block_of(off, b, j + s);
+            bs_add_direct(accr + static_cast<size_t>(bb) * kLimbs, specr + bb, to_fixed(bits[s]));
           }
         }
       }
@@ -188,13 +248,151 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
 }
 
 // ---------------------------------------------------------------------------------------------
+// Fused single pass for the layout "block b = coordinates [4096 b, 4096 (b+1))" (block = chunk): the
+// wavefront keeps the chunk's x in registers, sums it exactly, derives the scale itself and writes sign
+// bits and residuals: 12 bytes per coordinate instead of 20.  A block with an entry more than 2^32 below
+// its largest one, or with a non-finite entry, takes the general route instead (x is stored, the digits
+// go to memory, done = 0) and is finished by the kernels below.
+// ---------------------------------------------------------------------------------------------
+// Store the entries of a lane's quad that lie below d (columns >= d are never written).
+__device__ __forceinline__ void store_valid4(float* er, uint32_t j, uint32_t d, const float xv[4]) {
+  if (j + 3 < d) store_stream4(er + j, make_float4(xv[0], xv[1], xv[2], xv[3]));
+  else {
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (j + s < d) er[j + s] = xv[s];
+  }
+}
+
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_bs_fused4096(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
+                                                       BlocksignWorkspace ws) {
+  const uint32_t row = blockIdx.y;
+  const float* gr = g + static_cast<int64_t>(row) * geo.ld;
+  float* er = e + static_cast<int64_t>(row) * geo.ld;
+  uint64_t* accr = ws.acc + static_cast<size_t>(row) * geo.num_blocks * kLimbs;
+  uint32_t* specr = ws.special + static_cast<size_t>(row) * geo.num_blocks;
+  float* mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;
+  uint32_t* doner = ws.done + static_cast<size_t>(row) * geo.num_blocks;
+  uint32_t* bitr = ws.bits + static_cast<size_t>(row) * geo.words;
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t stride = gridDim.x * kWaves;
+  const uint32_t d = geo.d;
+  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+    const uint32_t base = c * kChunk + lane * 4;
+    const uint32_t len = (c + 1) * static_cast<uint64_t>(kChunk) <= d ? kChunk : d - c * kChunk;
+    float4 x[kRounds];
+    uint32_t kmax = 0;
+    bool odd = false;  // a non-finite entry
+#pragma unroll
+    for (int r0 = 0; r0 < kRounds; r0 += kBsBatch) {
+      float4 gv[kBsBatch], ev[kBsBatch];
+#pragma unroll
+      for (int u = 0; u < kBsBatch; ++u) {
+        const uint32_t j = base + (r0 + u) * 256;
+        gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        ev[u] = gv[u];
+        if (j < d) {
+          gv[u] = load_stream4(gr + j);
+          ev[u] = load_stream4(er + j);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kBsBatch; ++u) {
+        const int r = r0 + u;
+        const uint32_t j = base + r * 256;
+        x[r] = make_float4(ev[u].x + gv[u].x, ev[u].y + gv[u].y, ev[u].z + gv[u].z, ev[u].w + gv[u].w);
+        const float xv[4] = {x[r].x, x[r].y, x[r].z, x[r].w};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const uint32_t key = __float_as_uint(xv[s]) & 0x7fffffffu;
+          if (j + s < d) {
+            if (key >= 0x7f800000u) odd = true;
+            else if (key > kmax) kmax = key;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) {
+      const uint32_t o = __shfl_xor(kmax, s, 64);
+      kmax = o > kmax ? o : kmax;
+    }
+    const uint32_t exm = kmax >> 23;
+    const uint32_t centre = (exm ? exm - 1 : 0) >> 5;  // digit of the largest entry: nothing lies above it
+    uint64_t a0 = 0, a1 = 0, a2 = 0;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      const uint32_t j = base + r * 256;
+      const float xv[4] = {x[r].x, x[r].y, x[r].z, x[r].w};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (j + s >= d) continue;
+        const Fixed f = to_fixed(__float_as_uint(xv[s]));
+        if (f.special || (f.lo | f.hi) == 0) continue;
+        if (f.w == centre) { a1 += f.lo; a2 += f.hi; }
+        else if (f.w + 1 == centre) { a0 += f.lo; a1 += f.hi; }
+        else odd = true;  // more than 2^32 below the largest entry
+      }
+    }
+    if (ballot64(odd) == 0) {
+      const uint64_t s0 = wave_sum_u64(a0), s1 = wave_sum_u64(a1), s2 = wave_sum_u64(a2);
+      uint64_t w0, w1, w2;
+      // lowest digit held: centre - 1 (or 0 when the centre is digit 0; a0 is then empty)
+      const uint32_t low = centre ? centre - 1 : 0;
+      if (centre) digits3_to_192(s0, s1, s2, w0, w1, w2);
+      else digits3_to_192(s1, s2, 0, w0, w1, w2);
+      const double sum = fixed192_to_double(w0, w1, w2, 32 * static_cast<int>(low) - 149, false);
+      const float mu = static_cast<float>(sum / static_cast<double>(len));
+      if (lane == 0) {
+        mur[c] = mu;
+        doner[c] = 1;
+      }
+#pragma unroll
+      for (int r = 0; r < kRounds; ++r) {
+        const uint32_t j0 = c * kChunk + r * 256;
+        if (j0 >= d) break;  // wave-uniform
+        const uint32_t j = j0 + lane * 4;
+        float xv[4] = {x[r].x, x[r].y, x[r].z, x[r].w};
+        uint32_t nib = 0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bool neg = j + s < d && xv[s] < 0.0f;
+          nib |= (neg ? 1u : 0u) << s;
+          xv[s] = xv[s] - (neg ? -mu : mu);
+        }
+        store_valid4(er, j, d, xv);
+        uint32_t word = nib << ((lane & 7u) * 4u);
+        word |= __shfl_xor(word, 1, 64);
+        word |= __shfl_xor(word, 2, 64);
+        word |= __shfl_xor(word, 4, 64);
+        const uint32_t widx = (j0 >> 5) + (lane >> 3);
+        if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
+      }
+    } else {
+      if (lane == 0) doner[c] = 0;
+      uint64_t* dg = accr + static_cast<size_t>(c) * kLimbs;
+#pragma unroll
+      for (int r = 0; r < kRounds; ++r) {
+        const uint32_t j = base + r * 256;
+        const float xv[4] = {x[r].x, x[r].y, x[r].z, x[r].w};
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          if (j + s < d) bs_add_direct(dg, specr + c, to_fixed(__float_as_uint(xv[s])));
+        store_valid4(er, j, d, xv);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Scales: one thread per (row, block).  Normalise the digits, round the sum to double (nearest, ties
 // to even), divide by the block length, round to fp32.  Clears the digits for the next step.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWorkspace ws) {
+__global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWorkspace ws, int skip_done) {
   const size_t t = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x;
   const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
   if (t >= total) return;
+  if (skip_done && ws.done[t]) return;
   const uint32_t b = static_cast<uint32_t>(t % geo.num_blocks);
   uint64_t* dg = ws.acc + t * kLimbs;
   uint32_t digit[kLimbs + 1];
@@ -211,25 +409,24 @@ __global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWork
   ws.special[t] = 0;
   const double len = static_cast<double>(ws.offsets[b + 1] - ws.offsets[b]);
   double sum;
-  int top = -1;
-  for (int i = kLimbs; i >= 0; --i)
-    if (digit[i]) { top = i * 32 + 31 - __clz(digit[i]); break; }
-  auto bit_at = [&](int p) -> uint32_t { return (digit[p >> 5] >> (p & 31)) & 1u; };
   if (sp & 2u) sum = __longlong_as_double(0x7ff8000000000000ll);
   else if (sp & 1u) sum = __longlong_as_double(0x7ff0000000000000ll);
-  else if (top < 0) sum = 0.0;
-  else if (top <= 52) {
-    const uint64_t v = (static_cast<uint64_t>(digit[1]) << 32) | digit[0];
-    sum = ldexp(static_cast<double>(v), -149);
-  } else {
-    const int low = top - 52;
-    uint64_t kept = 0;
-    for (int p = top; p >= low; --p) kept = (kept << 1) | bit_at(p);
-    const uint32_t guard = bit_at(low - 1);
-    bool sticky = false;
-    for (int p = low - 2; p >= 0; --p) sticky = sticky || bit_at(p);
-    if (guard && (sticky || (kept & 1))) ++kept;
-    sum = ldexp(static_cast<double>(kept), low - 149);
+  else {
+    // the four highest non-zero digits carry every bit a double can hold; the rest is a sticky bit
+    int top = 0;
+#pragma unroll
+    for (int i = 1; i <= kLimbs; ++i)
+      if (digit[i]) top = i;
+    const int low = top >= 3 ? top - 3 : 0;
+    uint32_t q[4] = {0, 0, 0, 0};
+    bool below = false;
+#pragma unroll
+    for (int i = 0; i <= kLimbs; ++i) {
+      if (i >= low && i < low + 4) q[i - low] = digit[i];
+      else if (i < low && digit[i]) below = true;
+    }
+    const uint64_t w0 = (static_cast<uint64_t>(q[1]) << 32) | q[0], w1 = (static_cast<uint64_t>(q[3]) << 32) | q[2];
+    sum = fixed192_to_double(w0, w1, 0, 32 * low - 149, below);
   }
   ws.scales[t] = static_cast<float>(sum / len);
 }
@@ -238,50 +435,63 @@ __global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWork
 // Pass 2: sign bits and residual  e = x - sign(x) * mu.  One wavefront per chunk.  Eight lanes
 // (32 coordinates) share one word of the bit map.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometry geo, BlocksignWorkspace ws) {
+__global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometry geo, BlocksignWorkspace ws,
+                                                   int skip_done) {
   const uint32_t row = blockIdx.y;
   float* er = e + static_cast<int64_t>(row) * geo.ld;
   const uint32_t* __restrict__ off = ws.offsets;
   const float* __restrict__ mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;
+  const uint32_t* doner = ws.done + static_cast<size_t>(row) * geo.num_blocks;
   uint32_t* bitr = ws.bits + static_cast<size_t>(row) * geo.words;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const uint32_t stride = gridDim.x * kWaves;
   const uint32_t d = geo.d;
   for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+    if (skip_done && doner[c]) continue;  // block = chunk, finished by the fused pass (wave-uniform)
     uint32_t b = ws.chunk_block[c];
-    for (int r = 0; r < kRounds; ++r) {
-      const uint32_t j0 = c * kChunk + r * 256;
-      if (j0 >= d) break;
-      const uint32_t j = j0 + lane * 4;
-      const bool in = j < d;
-      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (in) x = *reinterpret_cast<const float4*>(er + j);
-      const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
-      while (off[b + 1] <= j0) ++b;
-      const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
-      float mu[4];
-      if (off[b + 1] >= j_end) {
-        const float m0 = mur[b];
-        mu[0] = mu[1] = mu[2] = mu[3] = m0;
-      } else {
+#pragma unroll 1
+    for (int r0 = 0; r0 < kRounds; r0 += kBsBatch) {
+      if (c * kChunk + r0 * 256 >= d) break;  // wave-uniform
+      float4 xb[kBsBatch];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) mu[s] = ok[s] ? mur[block_of(off, b, j + s)] : 0.0f;
+      for (int u = 0; u < kBsBatch; ++u) {
+        const uint32_t j = c * kChunk + (r0 + u) * 256 + lane * 4;
+        xb[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j < d) xb[u] = load_stream4(er + j);
       }
-      float xv[4] = {x.x, x.y, x.z, x.w};
-      uint32_t nib = 0;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const bool neg = ok[s] && xv[s] < 0.0f;
-        nib |= (neg ? 1u : 0u) << s;
-        if (ok[s]) xv[s] = xv[s] - (neg ? -mu[s] : mu[s]);
+      for (int u = 0; u < kBsBatch; ++u) {
+        const uint32_t j0 = c * kChunk + (r0 + u) * 256;
+        if (j0 >= d) break;
+        const uint32_t j = j0 + lane * 4;
+        const bool in = j < d;
+        const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
+        while (off[b + 1] <= j0) ++b;
+        const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
+        float mu[4];
+        if (off[b + 1] >= j_end) {
+          const float m0 = mur[b];
+          mu[0] = mu[1] = mu[2] = mu[3] = m0;
+        } else {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) mu[s] = ok[s] ? mur[block_of(off, b, j + s)] : 0.0f;
+        }
+        float xv[4] = {xb[u].x, xb[u].y, xb[u].z, xb[u].w};
+        uint32_t nib = 0;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const bool neg = ok[s] && xv[s] < 0.0f;
+          nib |= (neg ? 1u : 0u) << s;
+          if (ok[s]) xv[s] = xv[s] - (neg ? -mu[s] : mu[s]);
+        }
+        if (in) store_stream4(er + j, make_float4(xv[0], xv[1], xv[2], xv[3]));
+        uint32_t word = nib << ((lane & 7u) * 4u);
+        word |= __shfl_xor(word, 1, 64);
+        word |= __shfl_xor(word, 2, 64);
+        word |= __shfl_xor(word, 4, 64);
+        const uint32_t widx = (j0 >> 5) + (lane >> 3);
+        if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
       }
-      if (in) *reinterpret_cast<float4*>(er + j) = make_float4(xv[0], xv[1], xv[2], xv[3]);
-      uint32_t word = nib << ((lane & 7u) * 4u);
-      word |= __shfl_xor(word, 1, 64);
-      word |= __shfl_xor(word, 2, 64);
-      word |= __shfl_xor(word, 4, 64);
-      const uint32_t widx = (j0 >> 5) + (lane >> 3);
-      if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
     }
   }
 }
@@ -290,6 +500,8 @@ __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometr
 // Server lines for sign/scale messages: gbar_j = (sum_i s_ij * mu_i,b(j)) / n in worker order, then
 // AMSGrad.  One wavefront per chunk of coordinates.
 // ---------------------------------------------------------------------------------------------
+constexpr int kBsWorkers = 8;  // workers whose sign words and scales are requested together
+
 __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, float* __restrict__ m,
                                                      float* __restrict__ v, float* __restrict__ vhat, Geometry geo,
                                                      BlocksignWorkspace ws, AmsParams p) {
@@ -304,6 +516,14 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
     if (j0 >= d) break;
     const uint32_t j = j0 + lane * 4;
     const bool ok[4] = {j < d, j + 1 < d, j + 2 < d, j + 3 < d};
+    // the optimizer state of this round is requested first; the sign/scale loop runs while it travels
+    float4 th = make_float4(0.f, 0.f, 0.f, 0.f), mm = th, vv = th, vh = th;
+    if (ok[3]) {
+      th = *reinterpret_cast<const float4*>(theta + j);
+      mm = *reinterpret_cast<const float4*>(m + j);
+      vv = *reinterpret_cast<const float4*>(v + j);
+      vh = *reinterpret_cast<const float4*>(vhat + j);
+    }
     while (off[b + 1] <= j0) ++b;
     const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
     const bool uniform = off[b + 1] >= j_end;
@@ -314,15 +534,34 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
     }
     float sum[4] = {0.f, 0.f, 0.f, 0.f};
     const uint32_t widx = j >> 5, sh = j & 31u;
-    for (uint32_t i = 0; i < geo.n; ++i) {
-      const uint32_t word = ok[0] ? ws.bits[static_cast<size_t>(i) * geo.words + widx] : 0u;
-      const float* mur = ws.scales + static_cast<size_t>(i) * geo.num_blocks;
-      const uint32_t nib = (word >> sh) & 15u;
-      if (uniform) {
-        const float mu = mur[b];
+    if (uniform) {
+      for (uint32_t i0 = 0; i0 < geo.n; i0 += kBsWorkers) {
+        uint32_t word[kBsWorkers];
+        float mu[kBsWorkers];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) sum[s] = sum[s] + (((nib >> s) & 1u) ? -mu : mu);
-      } else {
+        for (int u = 0; u < kBsWorkers; ++u) {
+          const uint32_t i = i0 + u;
+          word[u] = 0;
+          mu[u] = 0.0f;
+          if (i < geo.n) {
+            if (ok[0]) word[u] = ws.bits[static_cast<size_t>(i) * geo.words + widx];
+            mu[u] = ws.scales[static_cast<size_t>(i) * geo.num_blocks + b];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < kBsWorkers; ++u) {
+          if (i0 + u < geo.n) {  // wave-uniform
+            const uint32_t nib = (word[u] >> sh) & 15u;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) sum[s] = sum[s] + (((nib >> s) & 1u) ? -mu[u] : mu[u]);
+          }
+        }
+      }
+    } else {
+      for (uint32_t i = 0; i < geo.n; ++i) {
+        const uint32_t word = ok[0] ? ws.bits[static_cast<size_t>(i) * geo.words + widx] : 0u;
+        const float* mur = ws.scales + static_cast<size_t>(i) * geo.num_blocks;
+        const uint32_t nib = (word >> sh) & 15u;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
           const float mu = mur[bb[s]];
@@ -331,8 +570,6 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
       }
     }
     if (ok[3]) {
-      float4 th = *reinterpret_cast<float4*>(theta + j), mm = *reinterpret_cast<float4*>(m + j);
-      float4 vv = *reinterpret_cast<float4*>(v + j), vh = *reinterpret_cast<float4*>(vhat + j);
       ams_update(sum[0] / p.nf, th.x, mm.x, vv.x, vh.x, p);
       ams_update(sum[1] / p.nf, th.y, mm.y, vv.y, vh.y, p);
       ams_update(sum[2] / p.nf, th.z, mm.z, vv.z, vh.z, p);
@@ -344,9 +581,9 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
     } else {
       for (int s = 0; s < 4; ++s)
         if (ok[s]) {
-          float th = theta[j + s], mm = m[j + s], vv = v[j + s], vh = vhat[j + s];
-          ams_update(sum[s] / p.nf, th, mm, vv, vh, p);
-          theta[j + s] = th; m[j + s] = mm; v[j + s] = vv; vhat[j + s] = vh;
+          float t1 = theta[j + s], m1 = m[j + s], v1 = v[j + s], h1 = vhat[j + s];
+          ams_update(sum[s] / p.nf, t1, m1, v1, h1, p);
+          theta[j + s] = t1; m[j + s] = m1; v[j + s] = v1; vhat[j + s] = h1;
         }
     }
   }
@@ -417,21 +654,29 @@ __global__ __launch_bounds__(kWG) void k_copy16(uint4* __restrict__ dst, const u
 hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, const float* g,
                           float* e, float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
-  const dim3 grid_rows(G, geo.n), wg(kWG);
+  // these passes hide their latencies through occupancy: many workgroups per row
+  uint32_t GA = G * 2;
+  uint32_t G2 = G * 2;
+  if (getenv("COMPAMS_TUNE_GB1")) GA = atoi(getenv("COMPAMS_TUNE_GB1"));
+  if (getenv("COMPAMS_TUNE_GB2")) G2 = atoi(getenv("COMPAMS_TUNE_GB2"));
+  const dim3 grid_rows(G, geo.n), grid_a(GA, geo.n), grid_2(G2, geo.n), wg(kWG);
+  const int fused = ws.uniform4096 ? 1 : 0;
   {
     ScopedSlot s(L, kSlotBsPass1, stream);
-    hipLaunchKernelGGL(k_bs_pass1, grid_rows, wg, 0, stream, g, e, geo, ws);
+    if (fused) hipLaunchKernelGGL(k_bs_fused4096, grid_a, wg, 0, stream, g, e, geo, ws);
+    else hipLaunchKernelGGL(k_bs_pass1, grid_a, wg, 0, stream, g, e, geo, ws);
   }
   COMPAMS_CHECK_LAUNCH();
   {
     ScopedSlot s(L, kSlotBsFinal, stream);
     const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
-    hipLaunchKernelGGL(k_bs_finalize, dim3(static_cast<uint32_t>((total + kWG - 1) / kWG)), wg, 0, stream, geo, ws);
+    hipLaunchKernelGGL(k_bs_finalize, dim3(static_cast<uint32_t>((total + kWG - 1) / kWG)), wg, 0, stream, geo, ws,
+                       fused);
   }
   COMPAMS_CHECK_LAUNCH();
   {
     ScopedSlot s(L, kSlotBsPass2, stream);
-    hipLaunchKernelGGL(k_bs_pass2, grid_rows, wg, 0, stream, e, geo, ws);
+    hipLaunchKernelGGL(k_bs_pass2, fused ? grid_rows : grid_2, wg, 0, stream, e, geo, ws, fused);
   }
   COMPAMS_CHECK_LAUNCH();
   {

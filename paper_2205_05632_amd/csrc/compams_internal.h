@@ -84,6 +84,8 @@ struct BlocksignWorkspace {
   uint32_t* chunk_block; // num_chunks : index of the block that holds the chunk's first coordinate
   uint64_t* acc;        // n * M * kLimbs : exact sums of |x| (32-bit digits carried in 64-bit words)
   uint32_t* special;    // n * M : bit 0 = an infinity was seen, bit 1 = a NaN was seen
+  uint32_t* done;       // n * M : the fused single pass has finished this block (block = chunk layouts only)
+  uint32_t uniform4096; // block b is exactly coordinates [4096 b, 4096 (b + 1))
   float* scales;        // n * M
   uint32_t* bits;       // n * words
 };

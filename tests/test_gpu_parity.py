@@ -254,6 +254,24 @@ def test_blocksign_wide_dynamic_range_is_summed_exactly():
     p.close()
 
 
+def test_blocksign_4096_blocks_take_the_general_route_when_a_block_is_too_wide():
+    """Blocks of exactly 4096 coordinates are normally finished in one pass; a block whose entries span more than
+    2^32 (or hold an infinity) is handed to the general kernels.  Both kinds in one run."""
+    n, d = 3, 10 * 4096 + 1000
+    rng = np.random.default_rng(6)
+    off = np.concatenate([np.arange(0, d, 4096), [d]]).astype(np.int64)
+    p = Pair(n, d, np.zeros(d, np.float32), B.BLOCKSIGN, block_offsets=off)
+    for t in range(4):
+        g = rng.standard_normal((n, d)).astype(np.float32)
+        g[:, 4096:2 * 4096] *= (10.0 ** rng.uniform(-44, 30, (n, 4096))).astype(np.float32)   # wide block
+        g[:, 3 * 4096:4 * 4096] = 0.0                                                            # empty block
+        g[:, 5 * 4096 + 7] = 1e-30                                                               # one tiny entry
+        g[1, 8 * 4096:9 * 4096] *= 1e-38                                                         # denormal block
+        p.step(g, 1e-3, label=f"4096 mixed step {t}")
+    assert all(p.exact.values()), p.exact
+    p.close()
+
+
 def test_blocksign_is_deterministic():
     n, d = 3, 120000
     off = np.concatenate([np.arange(0, d, 30011), [d]]).astype(np.int64)
