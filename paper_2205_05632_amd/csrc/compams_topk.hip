@@ -85,7 +85,10 @@ __device__ __forceinline__ RoundRank rank_round(const bool flag[4]) {
 // Candidate entries of the chunk a wavefront is walking are first staged in LDS (kStage entries per
 // wavefront) so that the chunk's segment can be allocated with one atomic once its size is known and
 // then written with coalesced stores.  A chunk with more candidates than that is re-read instead.
-constexpr int kStage = 256;
+#ifndef COMPAMS_STAGE
+#define COMPAMS_STAGE 512
+#endif
+constexpr int kStage = COMPAMS_STAGE;
 
 __device__ __forceinline__ void stage_round(uint2* stage, uint32_t& n, uint32_t j, const uint32_t bits[4],
                                             const bool flag[4]) {
@@ -186,6 +189,22 @@ __device__ __forceinline__ void store_agent(uint32_t* p, uint32_t v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Many device-scope loads in flight at once.  The compiler waits for each atomic load before it issues the
+// next, which turns a row-wide step of a few thousand words into a chain of memory round trips; buffer loads
+// with the same cache policy (served by the level all compute units share) are ordinary loads to it and
+// overlap.  A view covers `words` 32-bit words from p; reads beyond it return 0.
+struct AgentView {
+  __amdgpu_buffer_rsrc_t rsrc;
+};
+__device__ __forceinline__ AgentView agent_view(const uint32_t* p, uint32_t words) {
+  AgentView v;
+  v.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(p), 0, words * 4u, 0x00020000);
+  return v;
+}
+__device__ __forceinline__ uint32_t load_agent(const AgentView& v, uint32_t word) {
+  return __builtin_amdgcn_raw_buffer_load_b32(v.rsrc, word * 4u, 0, /*device-scope policy*/ 16);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Finding the bucket in which a suffix count crosses `need`, by one workgroup of kWG threads.
 // h: NB bucket counts in LDS.  Returns through out2 the largest s with sum_{b >= s} h[b] >= need and the
@@ -227,9 +246,16 @@ __device__ void find_crossing(const uint32_t* h, uint32_t need, uint32_t* suf /*
 // Copy a row's global histogram into LDS and clear it for the next step.
 template <int NB, int NT = kWG>
 __device__ __forceinline__ void take_hist(uint32_t* gh, uint32_t* h) {
-  for (int b = threadIdx.x; b < NB; b += NT) {
-    h[b] = load_agent(gh + b);
-    gh[b] = 0;
+  static_assert(NB % NT == 0, "buckets per thread");
+  constexpr int PER = NB / NT;
+  const AgentView view = agent_view(gh, NB);
+  uint32_t x[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) x[i] = load_agent(view, i * NT + threadIdx.x);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    h[i * NT + threadIdx.x] = x[i];
+    gh[i * NT + threadIdx.x] = 0;
   }
   __syncthreads();
 }
@@ -554,7 +580,12 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
   if (PRED && pred) {
     const uint32_t which = sh_l1;  // 0: level 1 not available; 1, 2: histogram of bucket guess, guess + 1
     if (which) {
-      for (int b = threadIdx.x; b < kNB1; b += kWGA) lh[b] = load_agent(gh1 + (which - 1) * kNB1 + b);
+      const AgentView view = agent_view(gh1 + (which - 1) * kNB1, kNB1);
+      uint32_t x[kNB1 / kWGA];
+#pragma unroll
+      for (int i = 0; i < kNB1 / kWGA; ++i) x[i] = load_agent(view, i * kWGA + threadIdx.x);
+#pragma unroll
+      for (int i = 0; i < kNB1 / kWGA; ++i) lh[i * kWGA + threadIdx.x] = x[i];
     }
     for (int b = threadIdx.x; b < 2 * kNB1; b += kWGA) gh1[b] = 0;
     __syncthreads();
@@ -756,6 +787,7 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
                                                      TopkOptions opt) {
   __shared__ uint32_t scratch[kWG / 64 + 1];
   __shared__ uint32_t sh_flag;
+  __shared__ uint32_t t_eq[kWG * kScanItems], t_gt[kWG * kScanItems];
   const uint32_t row = blockIdx.y;
   TopkRow* rowp = ws.rows + row;
   const uint32_t mode = rowp->mode, tau = rowp->tau;
@@ -805,11 +837,19 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
         const uint32_t ka = key_of_bits(a[u].y), kb = key_of_bits(b[u].y);
         uint32_t gt = popc64(ballot64(lane < cnt[u] && ka > tau)) + popc64(ballot64(lane + 64 < cnt[u] && kb > tau));
         uint32_t eq = popc64(ballot64(lane < cnt[u] && ka == tau)) + popc64(ballot64(lane + 64 < cnt[u] && kb == tau));
-        for (uint32_t t = 128; t < cnt[u]; t += 64) {  // long segments
-          const bool ok = t + lane < cnt[u];
-          const uint32_t key = ok ? key_of_bits(candr[off[u] + t + lane].y) : 0;
-          gt += popc64(ballot64(ok && key > tau));
-          eq += popc64(ballot64(ok && key == tau));
+        for (uint32_t t = 128; t < cnt[u]; t += 256) {  // long segments: four independent loads per trip
+          uint32_t kk[4];
+          bool okk[4];
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            okk[w] = t + w * 64 + lane < cnt[u];
+            kk[w] = okk[w] ? key_of_bits(candr[off[u] + t + w * 64 + lane].y) : 0;
+          }
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            gt += popc64(ballot64(okk[w] && kk[w] > tau));
+            eq += popc64(ballot64(okk[w] && kk[w] == tau));
+          }
         }
         if (lane == static_cast<uint32_t>(u)) { my_gt = gt; my_eq = eq; }
       }
@@ -825,39 +865,57 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
   const uint32_t r = rowp->r;
   uint32_t* sel_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
   uint32_t eq_carry = 0, sel_carry = 0;
-  for (uint32_t c0 = 0; c0 < geo.num_chunks; c0 += kWG * kScanItems) {
-    const uint32_t first = c0 + threadIdx.x * kScanItems;
+  // Tiles of kWG * kScanItems chunks.  Global accesses are coalesced (thread t touches chunk tile + i * kWG + t);
+  // the tile passes through LDS so that each thread can scan kScanItems consecutive chunks.
+  constexpr int kTile = kWG * kScanItems;
+  const AgentView eq_view = agent_view(ws.cnt_eq + rb, geo.num_chunks);
+  const AgentView gt_view = agent_view(ws.cnt_gt + rb, geo.num_chunks);
+  for (uint32_t c0 = 0; c0 < geo.num_chunks; c0 += kTile) {
+    __syncthreads();  // the previous tile has been written out
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+      const uint32_t t = i * kWG + threadIdx.x;
+      const uint32_t c = c0 + t;
+      t_eq[t] = load_agent(eq_view, c);  // 0 beyond the row's last chunk
+      t_gt[t] = load_agent(gt_view, c);
+    }
+    __syncthreads();
+    const uint32_t first = threadIdx.x * kScanItems;
     uint32_t eq[kScanItems], gt[kScanItems];
     uint32_t eq_sum = 0;
 #pragma unroll
     for (int i = 0; i < kScanItems; ++i) {
-      const uint32_t c = first + i;
-      const bool in = c < geo.num_chunks;
-      eq[i] = in ? load_agent(ws.cnt_eq + rb + c) : 0;
-      gt[i] = in ? load_agent(ws.cnt_gt + rb + c) : 0;
+      eq[i] = t_eq[first + i];
+      gt[i] = t_gt[first + i];
       eq_sum += eq[i];
     }
     uint32_t eq_total, sel_total;
     uint32_t eq_before = eq_carry + block_excl_scan<kWG>(eq_sum, scratch, &eq_total);
-    uint32_t take[kScanItems], eqb[kScanItems];
     uint32_t sel_sum = 0;
 #pragma unroll
     for (int i = 0; i < kScanItems; ++i) {
-      eqb[i] = eq_before;
       const uint32_t room = r > eq_before ? r - eq_before : 0;
-      take[i] = eq[i] < room ? eq[i] : room;
-      sel_sum += gt[i] + take[i];
+      const uint32_t take = eq[i] < room ? eq[i] : room;
+      t_eq[first + i] = eq_before;  // ties in earlier chunks
+      gt[i] += take;                // selected in this chunk
+      sel_sum += gt[i];
       eq_before += eq[i];
     }
     uint32_t sel_before = sel_carry + block_excl_scan<kWG>(sel_sum, scratch, &sel_total);
 #pragma unroll
     for (int i = 0; i < kScanItems; ++i) {
-      const uint32_t c = first + i;
+      t_gt[first + i] = sel_before;
+      sel_before += gt[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+      const uint32_t t = i * kWG + threadIdx.x;
+      const uint32_t c = c0 + t;
       if (c < geo.num_chunks) {
-        ws.eq_before[rb + c] = eqb[i];
-        sel_off[c] = sel_before;
+        ws.eq_before[rb + c] = t_eq[t];
+        sel_off[c] = t_gt[t];
       }
-      sel_before += gt[i] + take[i];
     }
     eq_carry += eq_total;
     sel_carry += sel_total;
