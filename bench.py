@@ -75,6 +75,9 @@ def main():
                     help="ablation: ask for e after every step, so that the residual zeroing is never deferred")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="time the steps without per-kernel events (the roofline object is then left out)")
+    ap.add_argument("--event-stride", type=int, default=4,
+                    help="bracket the dominant kernel with events on every this-many-th timed step (each bracketed "
+                         "launch adds a few microseconds to its step)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the n workers are rows of one buffer); --gpus must be 1",
@@ -106,10 +109,16 @@ def main():
         ctx.compams_step(grads[t], w.lr)
     # timed region: the dominant kernel is bracketed by HIP events on the step's stream (their cost is part of
     # the measured time); --kernels brackets every kernel instead, which costs a few microseconds per kernel
-    ctx.profile_enable(0 if args.no_kernel_events else (1 if args.kernels else 2))
+    event_mode = 0 if args.no_kernel_events else (1 if args.kernels else 2)
+    stride = 1 if args.kernels else max(1, args.event_stride)
+    ctx.profile_enable(0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(args.warmup, total):
+        if event_mode and stride > 1:
+            ctx.profile_enable(event_mode if (t - args.warmup) % stride == 0 else 0)  # host-side switch only
+        elif t == args.warmup:
+            ctx.profile_enable(event_mode)
         ctx.compams_step(grads[t], w.lr)
         if args.settle_each_step:
             ctx.compams_state("e")
@@ -129,10 +138,11 @@ def main():
         k_ms, k_launches = prof[kname]
         k_avg_s = k_ms / k_launches * 1e-3
         k_gbps = kbytes(w.n, w.d) / k_avg_s / 1e9
-        kernel_sum_ms = sum(ms for ms, _ in prof.values()) / args.steps
+        kernel_sum_ms = sum(ms / cnt for ms, cnt in prof.values())
         roofline = {"bound": "hbm", "kernel": kname, "achieved": k_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": k_gbps / HBM_PEAK_GBPS, "traffic": load_traffic(w.name, kname),
-                    "avg_launch_us": k_avg_s * 1e6, "algorithmic_bytes_per_launch": kbytes(w.n, w.d)}
+                    "avg_launch_us": k_avg_s * 1e6, "launches_timed": k_launches,
+                    "algorithmic_bytes_per_launch": kbytes(w.n, w.d)}
 
     counters = None
     if comp == B.TOPK:
@@ -171,7 +181,7 @@ def main():
         "algorithmic_bytes_per_step": bmin,
         "kernel_ms_per_step": kernel_sum_ms,
         "roofline": roofline,
-        "kernels_us_per_step": {k_: v_[0] / args.steps * 1e3 for k_, v_ in prof.items()},
+        "kernels_us_per_launch": {k_: v_[0] / v_[1] * 1e3 for k_, v_ in prof.items()},
         "topk_counters": counters,
         "cpu_baseline": cpu,
     }

@@ -89,7 +89,7 @@ Layout make_layout(const compams_config* c) {
     L.counters = take(n * COMPAMS_COUNTERS_PER_ROW * 4);
     L.hist0 = take(n * kNB0 * 4);
     L.hist1 = take(n * kNB1 * 4);
-    L.hist1x = take(n * 2 * kNB1 * 4);
+    L.hist1x = take(n * kTracked * kNB1 * 4);
     L.hist2 = take(n * kNB2 * 4);
     L.cnt_gt = take(n * nc * 4);
     L.cnt_eq = take(n * nc * 4);

@@ -655,45 +655,28 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
                           float* e, float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
   // these passes hide their latencies through occupancy: many workgroups per row
-  uint32_t GA = G * 2;
-  uint32_t G2 = G * 2;
-  if (getenv("COMPAMS_TUNE_GB1")) GA = atoi(getenv("COMPAMS_TUNE_GB1"));
-  if (getenv("COMPAMS_TUNE_GB2")) G2 = atoi(getenv("COMPAMS_TUNE_GB2"));
-  const dim3 grid_rows(G, geo.n), grid_a(GA, geo.n), grid_2(G2, geo.n), wg(kWG);
+  const dim3 grid_rows(G, geo.n), grid_2(G * 2, geo.n), wg(kWG);
   const int fused = ws.uniform4096 ? 1 : 0;
-  {
-    ScopedSlot s(L, kSlotBsPass1, stream);
-    if (fused) hipLaunchKernelGGL(k_bs_fused4096, grid_a, wg, 0, stream, g, e, geo, ws);
-    else hipLaunchKernelGGL(k_bs_pass1, grid_a, wg, 0, stream, g, e, geo, ws);
-  }
+  if (fused) launch(L, kSlotBsPass1, k_bs_fused4096, grid_2, wg, stream, g, e, geo, ws);
+  else launch(L, kSlotBsPass1, k_bs_pass1, grid_2, wg, stream, g, e, geo, ws);
   COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotBsFinal, stream);
-    const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
-    hipLaunchKernelGGL(k_bs_finalize, dim3(static_cast<uint32_t>((total + kWG - 1) / kWG)), wg, 0, stream, geo, ws,
-                       fused);
-  }
+  const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
+  launch(L, kSlotBsFinal, k_bs_finalize, dim3(static_cast<uint32_t>((total + kWG - 1) / kWG)), wg, stream, geo, ws,
+         fused);
   COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotBsPass2, stream);
-    hipLaunchKernelGGL(k_bs_pass2, fused ? grid_rows : grid_2, wg, 0, stream, e, geo, ws, fused);
-  }
+  launch(L, kSlotBsPass2, k_bs_pass2, fused ? grid_rows : grid_2, wg, stream, e, geo, ws, fused);
   COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotBsAms, stream);
-    hipLaunchKernelGGL(k_bs_amsgrad, dim3((geo.num_chunks + kWaves - 1) / kWaves), wg, 0, stream, theta, m, v, vhat,
-                       geo, ws, ap);
-  }
+  launch(L, kSlotBsAms, k_bs_amsgrad, dim3((geo.num_chunks + kWaves - 1) / kWaves), wg, stream, theta, m, v, vhat, geo,
+         ws, ap);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
 
 hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, float* theta, float* m, float* v,
                      float* vhat, hipStream_t stream, Launcher* L) {
-  ScopedSlot s(L, kSlotNoneAms, stream);
   const uint32_t quads = (geo.d + 3) / 4;
-  hipLaunchKernelGGL(k_none_amsgrad, dim3((quads + kWG - 1) / kWG), dim3(kWG), 0, stream, g, theta, m, v, vhat, geo,
-                     ap);
+  launch(L, kSlotNoneAms, k_none_amsgrad, dim3((quads + kWG - 1) / kWG), dim3(kWG), stream, g, theta, m, v, vhat, geo,
+         ap);
   return hipGetLastError();
 }
 

@@ -27,6 +27,9 @@ constexpr int kNB0 = 1 << 12;
 constexpr int kL1Shift = 9;
 constexpr int kNB1 = 1 << 10;
 constexpr int kNB2 = 1 << 9;
+// The first pass keeps level-1 histograms of this many buckets, starting at the guessed one: the guess is one
+// below the last threshold bucket, so a threshold that moved by one bucket either way still resolves there.
+constexpr uint32_t kTracked = 3;
 
 // Where a row's selection reads its elements from after the first pass.
 enum : uint32_t {
@@ -66,7 +69,7 @@ struct TopkWorkspace {
   uint32_t* counters;   // n * COMPAMS_COUNTERS_PER_ROW
   uint32_t* hist0;      // n * kNB0
   uint32_t* hist1;      // n * kNB1
-  uint32_t* hist1x;     // n * 2 * kNB1 : level-1 histograms of the two buckets tracked by the first pass
+  uint32_t* hist1x;     // n * kTracked * kNB1 : level-1 histograms of the buckets tracked by the first pass
   uint32_t* hist2;      // n * kNB2
   uint32_t* cnt_gt;     // n * num_chunks : keys above tau per chunk
   uint32_t* cnt_eq;     // n * num_chunks : keys equal to tau per chunk
@@ -141,15 +144,19 @@ hipError_t fill_u32(uint32_t* p, size_t count, uint32_t value, hipStream_t strea
 hipError_t fill_rows_f32(float* p, uint32_t n, int64_t ld, uint32_t d, float value, hipStream_t stream);
 hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 
-// Event bracketing used by the *_step functions.
+// Launch with optional timing: when the slot is being timed, the launch is bracketed by a pair of events on
+// the same stream.  (Events attached to the dispatch itself give the same durations but slow the step down
+// by more than the bracketing does; measured on MI355X.)
 void launcher_begin(Launcher* L, int slot, hipStream_t stream);
 void launcher_end(Launcher* L, int slot, hipStream_t stream);
 
-struct ScopedSlot {
-  Launcher* L; int slot; hipStream_t s;
-  ScopedSlot(Launcher* l, int sl, hipStream_t st) : L(l), slot(sl), s(st) { if (L) launcher_begin(L, slot, s); }
-  ~ScopedSlot() { if (L) launcher_end(L, slot, s); }
-};
+template <typename... KArgs, typename... Args>
+inline void launch(Launcher* L, int slot, void (*kernel)(KArgs...), const dim3& grid, const dim3& block,
+                   hipStream_t stream, Args... args) {
+  if (L) launcher_begin(L, slot, stream);
+  hipLaunchKernelGGL(kernel, grid, block, 0, stream, static_cast<KArgs>(args)...);
+  if (L) launcher_end(L, slot, stream);
+}
 
 // How many workgroups per row the streaming kernels use: enough to keep 256 compute units busy
 // with several workgroups each, whatever n is.

@@ -315,7 +315,7 @@ struct PassA {
   float* er;
   uint32_t d;
   uint32_t* lh;          // level-0 histogram of the workgroup (LDS)
-  uint32_t* lh1;         // level-1 histograms of the two tracked buckets (LDS)
+  uint32_t* lh1;         // level-1 histograms of the tracked buckets (LDS)
   uint2* stage;          // this wavefront's staging area (LDS)
   uint32_t* bm;          // this wavefront's bit map of pending zeros (LDS, 128 words)
   bool pred;
@@ -388,7 +388,7 @@ __device__ __forceinline__ void pass_a_round(PassA& A, uint32_t j, int r, const 
   hist4<FULL>(A.lh, q, A.zeros);
   if constexpr (PRED) {
     if (A.pred) {
-      // candidates (bucket >= guess): staged in coordinate order; those in the two tracked buckets also go
+      // candidates (bucket >= guess): staged in coordinate order; those in the tracked buckets also go
       // into the level-1 histograms
       bool flag[4];
       uint64_t mk[4];
@@ -407,7 +407,7 @@ __device__ __forceinline__ void pass_a_round(PassA& A, uint32_t j, int r, const 
             if (pos < static_cast<uint32_t>(kStage)) A.stage[pos] = make_uint2(j + s, bits[s]);
             ++pos;
             const uint32_t rel = (q.key[s] >> kL0Shift) - A.bg;
-            if (rel < 2u) atomicAdd(&A.lh1[rel * kNB1 + ((q.key[s] >> kL1Shift) & (kNB1 - 1))], 1u);
+            if (rel < kTracked) atomicAdd(&A.lh1[rel * kNB1 + ((q.key[s] >> kL1Shift) & (kNB1 - 1))], 1u);
           }
         cnt += total;
       }
@@ -492,7 +492,7 @@ template <bool PRED, bool PEND>
 __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ g, float* __restrict__ e,
                                                       Geometry geo, TopkWorkspace ws, TopkOptions opt) {
   __shared__ uint32_t lh[kNB0];
-  __shared__ uint32_t lh1[PRED ? 2 * kNB1 : 1];
+  __shared__ uint32_t lh1[PRED ? kTracked * kNB1 : 1];
   __shared__ uint2 stage_all[PRED ? kWavesA * 2 * kStage : 1];
   __shared__ uint32_t bm_all[PEND ? kWavesA * 128 : 1];
   __shared__ uint32_t suf[kWGA + 1];
@@ -501,7 +501,7 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
   const uint32_t row = blockIdx.y;
   for (int b = threadIdx.x; b < kNB0; b += kWGA) lh[b] = 0;
   if (PRED)
-    for (int b = threadIdx.x; b < 2 * kNB1; b += kWGA) lh1[b] = 0;
+    for (int b = threadIdx.x; b < kTracked * kNB1; b += kWGA) lh1[b] = 0;
   __syncthreads();
   const float* gr = g + static_cast<int64_t>(row) * geo.ld;
   float* er = e + static_cast<int64_t>(row) * geo.ld;
@@ -532,9 +532,9 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
     const uint32_t h = lh[b];
     if (h) atomicAdd(&gh[b], h);
   }
-  uint32_t* gh1 = ws.hist1x + static_cast<size_t>(row) * 2 * kNB1;
+  uint32_t* gh1 = ws.hist1x + static_cast<size_t>(row) * kTracked * kNB1;
   if (PRED && pred)
-    for (int b = threadIdx.x; b < 2 * kNB1; b += kWGA) {
+    for (int b = threadIdx.x; b < kTracked * kNB1; b += kWGA) {
       const uint32_t h = lh1[b];
       if (h) atomicAdd(&gh1[b], h);
     }
@@ -572,13 +572,13 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
     uint32_t* cn = ws.counters + row * 4;
     cn[0] = reads;
     cn[1] = n_src;
-    sh_l1 = (pred_ok && bstar - bg < 2u) ? 1u + (bstar - bg) : 0u;
+    sh_l1 = (pred_ok && bstar - bg < kTracked) ? 1u + (bstar - bg) : 0u;
     sh_bstar = bstar;
     sh_need = geo.k - above;
   }
   __syncthreads();
   if (PRED && pred) {
-    const uint32_t which = sh_l1;  // 0: level 1 not available; 1, 2: histogram of bucket guess, guess + 1
+    const uint32_t which = sh_l1;  // 0: level 1 not available; 1 + t: histogram of bucket guess + t
     if (which) {
       const AgentView view = agent_view(gh1 + (which - 1) * kNB1, kNB1);
       uint32_t x[kNB1 / kWGA];
@@ -587,7 +587,7 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
 #pragma unroll
       for (int i = 0; i < kNB1 / kWGA; ++i) lh[i * kWGA + threadIdx.x] = x[i];
     }
-    for (int b = threadIdx.x; b < 2 * kNB1; b += kWGA) gh1[b] = 0;
+    for (int b = threadIdx.x; b < kTracked * kNB1; b += kWGA) gh1[b] = 0;
     __syncthreads();
     if (which) resolve_level1<kWGA>(rowp, sh_bstar, sh_need, lh, suf, out2);
   }
@@ -596,7 +596,7 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 // Kernel 2: level 1 for rows that could not resolve it in the first pass.
 //   kModeNeedB: one more read of the row; writes the candidate list (bucket >= bstar) and the histogram.
-//   kModeCand : the list exists (the threshold bucket was above the two tracked ones): sweep it.
+//   kModeCand : the list exists (the threshold bucket was above the tracked ones): sweep it.
 //   kModeDense: no list: histogram from the row itself.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
@@ -1089,41 +1089,23 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
                      const float* g, float* e, float* theta, float* m, float* v, float* vhat,
                      bool first_pass_may_predict, bool clear_pending, hipStream_t stream, Launcher* L) {
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
-  uint32_t GA = groups_first_pass(geo.n, geo.num_chunks, kWavesA);
-  if (getenv("COMPAMS_TUNE_GA")) GA = atoi(getenv("COMPAMS_TUNE_GA"));
+  const uint32_t GA = groups_first_pass(geo.n, geo.num_chunks, kWavesA);
   const dim3 grid_rows(G, geo.n), wg(kWG), grid_a(GA, geo.n), wga(kWGA);
-  {
-    ScopedSlot s(L, kSlotPassA, stream);
-    if (first_pass_may_predict) {
-      if (clear_pending) hipLaunchKernelGGL((k_topk_pass_a<true, true>), grid_a, wga, 0, stream, g, e, geo, ws, opt);
-      else hipLaunchKernelGGL((k_topk_pass_a<true, false>), grid_a, wga, 0, stream, g, e, geo, ws, opt);
-    } else {
-      if (clear_pending) hipLaunchKernelGGL((k_topk_pass_a<false, true>), grid_a, wga, 0, stream, g, e, geo, ws, opt);
-      else hipLaunchKernelGGL((k_topk_pass_a<false, false>), grid_a, wga, 0, stream, g, e, geo, ws, opt);
-    }
+  if (first_pass_may_predict) {
+    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<true, true>, grid_a, wga, stream, g, e, geo, ws, opt);
+    else launch(L, kSlotPassA, k_topk_pass_a<true, false>, grid_a, wga, stream, g, e, geo, ws, opt);
+  } else {
+    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<false, true>, grid_a, wga, stream, g, e, geo, ws, opt);
+    else launch(L, kSlotPassA, k_topk_pass_a<false, false>, grid_a, wga, stream, g, e, geo, ws, opt);
   }
   COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotLevel1, stream);
-    hipLaunchKernelGGL(k_topk_level1, grid_rows, wg, 0, stream, e, geo, ws, opt);
-  }
+  launch(L, kSlotLevel1, k_topk_level1, grid_rows, wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotLevel2, stream);
-    uint32_t G2 = G;
-    if (getenv("COMPAMS_TUNE_G2")) G2 = atoi(getenv("COMPAMS_TUNE_G2"));
-    hipLaunchKernelGGL(k_topk_level2, dim3(G2, geo.n), wg, 0, stream, e, geo, ws, opt);
-  }
+  launch(L, kSlotLevel2, k_topk_level2, grid_rows, wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotCount, stream);
-    hipLaunchKernelGGL(k_topk_count, grid_rows, wg, 0, stream, e, geo, ws, opt);
-  }
+  launch(L, kSlotCount, k_topk_count, grid_rows, wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
-  {
-    ScopedSlot s(L, kSlotTopkFinal, stream);
-    hipLaunchKernelGGL(k_topk_final, dim3(geo.num_chunks), wg, 0, stream, theta, m, v, vhat, e, geo, ws, opt, ap);
-  }
+  launch(L, kSlotTopkFinal, k_topk_final, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws, opt, ap);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
