@@ -55,7 +55,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t total;
   // top-k
-  size_t rows, counters, hist0, hist1, hist1x, hist2, cnt_gt, cnt_eq, sel_off, eq_before, desc, cand, idx, val, tau;
+  size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau;
   // block-sign
   size_t offsets, chunk_block, acc, special, done, scales, bits;
   uint32_t cap_alloc, num_chunks, words;
@@ -91,10 +91,9 @@ Layout make_layout(const compams_config* c) {
     L.hist1 = take(n * kNB1 * 4);
     L.hist1x = take(n * kTracked * kNB1 * 4);
     L.hist2 = take(n * kNB2 * 4);
-    L.cnt_gt = take(n * nc * 4);
-    L.cnt_eq = take(n * nc * 4);
+    L.chunk_rec = take(n * nc * 16);
+    L.blk = take(n * kMaxCountBlocks * 8);
     L.sel_off = take(n * (nc + 1) * 4);
-    L.eq_before = take(n * nc * 4);
     L.desc = take(n * nc * 8);
     L.cand = take(n * cap * 8);
     L.idx = take(n * k * 4);
@@ -189,6 +188,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
   geo.k = cfg->compressor == COMPAMS_TOPK ? static_cast<uint32_t>(cfg->k) : 0;
   geo.num_blocks = cfg->compressor == COMPAMS_BLOCKSIGN ? static_cast<uint32_t>(cfg->num_blocks) : 0;
   geo.words = lay.words;
+  geo.count_cpw = count_chunks_per_block(lay.num_chunks);
   char* w = static_cast<char*>(cfg->workspace);
   hipStream_t s0 = nullptr;
   hipError_t err = hipSuccess;
@@ -202,10 +202,9 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     t.hist1 = reinterpret_cast<uint32_t*>(w + lay.hist1);
     t.hist1x = reinterpret_cast<uint32_t*>(w + lay.hist1x);
     t.hist2 = reinterpret_cast<uint32_t*>(w + lay.hist2);
-    t.cnt_gt = reinterpret_cast<uint32_t*>(w + lay.cnt_gt);
-    t.cnt_eq = reinterpret_cast<uint32_t*>(w + lay.cnt_eq);
+    t.chunk_rec = reinterpret_cast<uint4*>(w + lay.chunk_rec);
+    t.blk = reinterpret_cast<uint2*>(w + lay.blk);
     t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);
-    t.eq_before = reinterpret_cast<uint32_t*>(w + lay.eq_before);
     t.desc = reinterpret_cast<uint2*>(w + lay.desc);
     t.cand = reinterpret_cast<uint2*>(w + lay.cand);
     t.idx = reinterpret_cast<int32_t*>(w + lay.idx);

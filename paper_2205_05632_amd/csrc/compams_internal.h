@@ -31,6 +31,15 @@ constexpr int kNB2 = 1 << 9;
 // below the last threshold bucket, so a threshold that moved by one bucket either way still resolves there.
 constexpr uint32_t kTracked = 3;
 
+// The counting kernel splits a row's chunks into at most kMaxCountBlocks contiguous blocks of count_cpw chunks
+// (a multiple of 32: four wavefronts, eight chunks at a time).  d < 2^31 gives at most 2^19 chunks.
+constexpr uint32_t kMaxCountBlocks = 256;
+constexpr uint32_t kMaxCountCpw = 2048;
+inline uint32_t count_chunks_per_block(uint32_t num_chunks) {
+  const uint32_t m = (num_chunks + 32 * kMaxCountBlocks - 1) / (32 * kMaxCountBlocks);
+  return 32 * (m ? m : 1);
+}
+
 // Where a row's selection reads its elements from after the first pass.
 enum : uint32_t {
   kModeCand = 0,   // candidate list written by the first pass (threshold bucket was predicted)
@@ -71,10 +80,10 @@ struct TopkWorkspace {
   uint32_t* hist1;      // n * kNB1
   uint32_t* hist1x;     // n * kTracked * kNB1 : level-1 histograms of the buckets tracked by the first pass
   uint32_t* hist2;      // n * kNB2
-  uint32_t* cnt_gt;     // n * num_chunks : keys above tau per chunk
-  uint32_t* cnt_eq;     // n * num_chunks : keys equal to tau per chunk
-  uint32_t* sel_off;    // n * (num_chunks + 1) : exclusive prefix of selected entries per chunk
-  uint32_t* eq_before;  // n * num_chunks : ties in earlier chunks
+  uint4* chunk_rec;     // n * num_chunks : keys above tau, keys equal to tau, and the exclusive prefixes of both
+                        //                  within the chunk's count block
+  uint2* blk;           // n * kMaxCountBlocks : the two totals of every count block
+  uint32_t* sel_off;    // n * (num_chunks + 1) : where each chunk's slice of the worker's list starts
   uint2* desc;          // n * num_chunks : (offset, count) of the chunk's segment in the candidate list
   uint2* cand;          // n * cap_alloc  : (coordinate, fp32 bits)
   int32_t* idx;         // n * k
@@ -120,6 +129,7 @@ struct Geometry {
   uint32_t k;
   uint32_t num_blocks;
   uint32_t words;  // ceil(d / 32)
+  uint32_t count_cpw;  // top-k: chunks per block of the counting kernel
 };
 
 // Kernel slots for optional timing.

@@ -778,27 +778,28 @@ __device__ __forceinline__ void for_each_round(uint32_t mode, const float* __res
 }
 
 // ---------------------------------------------------------------------------------------------
-// Kernel 4: per chunk, how many keys lie above tau and how many equal it; then, by the row's last
-// workgroup, the exclusive prefixes over chunks (ties are taken in coordinate order until r are in).
+// Kernel 4: per chunk, how many keys lie above tau and how many equal it.  A workgroup owns a contiguous
+// block of geo.count_cpw chunks; it leaves, per chunk, the two counts and their exclusive prefixes within
+// the block, and per block the two totals.  The last kernel turns these into positions in the worker's
+// list (a sum over at most kMaxCountBlocks block totals), so no workgroup waits for or follows another.
 // ---------------------------------------------------------------------------------------------
-constexpr int kScanItems = 16;  // chunks per thread in the row scan
-
 __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                      TopkOptions opt) {
+  __shared__ uint32_t l_gt[kMaxCountCpw], l_eq[kMaxCountCpw];
   __shared__ uint32_t scratch[kWG / 64 + 1];
-  __shared__ uint32_t sh_flag;
-  __shared__ uint32_t t_eq[kWG * kScanItems], t_gt[kWG * kScanItems];
   const uint32_t row = blockIdx.y;
-  TopkRow* rowp = ws.rows + row;
+  const uint32_t cpw = geo.count_cpw;
+  const uint32_t start = blockIdx.x * cpw;
+  if (start >= geo.num_chunks) return;  // uniform; the grid has exactly the blocks that exist
+  const uint32_t end = start + cpw < geo.num_chunks ? start + cpw : geo.num_chunks;
+  const TopkRow* rowp = ws.rows + row;
   const uint32_t mode = rowp->mode, tau = rowp->tau;
   const float* er = e + static_cast<int64_t>(row) * geo.ld;
   const uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
   const uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
-  const size_t rb = static_cast<size_t>(row) * geo.num_chunks;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   if (mode == kModeDense) {
-    const uint32_t stride = gridDim.x * kWaves;
-    for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+    for (uint32_t c = start + wave; c < end; c += kWaves) {
       uint32_t gt = 0, eq = 0;
       for_each_round(mode, er, geo.d, c, candr, descr, opt.cap, [&](const Entry4& en, int slots) {
         for (int s = 0; s < slots; ++s) {
@@ -807,19 +808,15 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
           eq += popc64(ballot64(en.ok[s] && key == tau));
         }
       });
-      if (lane == 0) {  // read back by the row's last workgroup in this same launch
-        store_agent(ws.cnt_gt + rb + c, gt);
-        store_agent(ws.cnt_eq + rb + c, eq);
-      }
+      if (lane == 0) { l_gt[c - start] = gt; l_eq[c - start] = eq; }
     }
   } else {
     // A wavefront takes kGroup consecutive chunks at a time: their descriptors come with one load, the first
     // 128 entries of every segment with independent loads (two round trips for the whole group).
     constexpr int kGroup = 8;
-    const uint32_t stride = gridDim.x * kWaves * kGroup;
-    for (uint32_t c0 = (blockIdx.x * kWaves + wave) * kGroup; c0 < geo.num_chunks; c0 += stride) {
+    for (uint32_t c0 = start + wave * kGroup; c0 < end; c0 += kWaves * kGroup) {
       uint2 ds = make_uint2(0, 0);
-      if (lane < kGroup && c0 + lane < geo.num_chunks) ds = descr[c0 + lane];
+      if (lane < kGroup && c0 + lane < end) ds = descr[c0 + lane];
       if (ds.x > opt.cap) ds.y = 0;  // segments always lie inside the list; never read outside it
       else if (ds.y > opt.cap - ds.x) ds.y = opt.cap - ds.x;
       uint32_t off[kGroup], cnt[kGroup];
@@ -853,187 +850,202 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
         }
         if (lane == static_cast<uint32_t>(u)) { my_gt = gt; my_eq = eq; }
       }
-      if (lane < kGroup && c0 + lane < geo.num_chunks) {  // read back by the row's last workgroup in this launch
-        store_agent(ws.cnt_gt + rb + c0 + lane, my_gt);
-        store_agent(ws.cnt_eq + rb + c0 + lane, my_eq);
-      }
+      if (lane < kGroup && c0 + lane < end) { l_gt[c0 - start + lane] = my_gt; l_eq[c0 - start + lane] = my_eq; }
     }
   }
-  if constexpr (COMPAMS_DBG & 256) return;
-  if (!last_group_of_row(&rowp->ticket[3], gridDim.x, &sh_flag)) return;
-  if constexpr (COMPAMS_DBG & 512) return;
-  const uint32_t r = rowp->r;
-  uint32_t* sel_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
-  uint32_t eq_carry = 0, sel_carry = 0;
-  // Tiles of kWG * kScanItems chunks.  Global accesses are coalesced (thread t touches chunk tile + i * kWG + t);
-  // the tile passes through LDS so that each thread can scan kScanItems consecutive chunks.
-  constexpr int kTile = kWG * kScanItems;
-  const AgentView eq_view = agent_view(ws.cnt_eq + rb, geo.num_chunks);
-  const AgentView gt_view = agent_view(ws.cnt_gt + rb, geo.num_chunks);
-  for (uint32_t c0 = 0; c0 < geo.num_chunks; c0 += kTile) {
-    __syncthreads();  // the previous tile has been written out
-#pragma unroll
-    for (int i = 0; i < kScanItems; ++i) {
-      const uint32_t t = i * kWG + threadIdx.x;
-      const uint32_t c = c0 + t;
-      t_eq[t] = load_agent(eq_view, c);  // 0 beyond the row's last chunk
-      t_gt[t] = load_agent(gt_view, c);
+  __syncthreads();
+  // exclusive prefixes within the block: thread t takes `per` consecutive chunks
+  const uint32_t len = end - start;
+  const uint32_t per = (cpw + kWG - 1) / kWG;  // <= kMaxCountCpw / kWG
+  const uint32_t first = threadIdx.x * per;
+  uint32_t sum_gt = 0, sum_eq = 0;
+  for (uint32_t i = 0; i < per; ++i)
+    if (first + i < len) { sum_gt += l_gt[first + i]; sum_eq += l_eq[first + i]; }
+  uint32_t tot_gt, tot_eq;
+  uint32_t pre_gt = block_excl_scan<kWG>(sum_gt, scratch, &tot_gt);
+  uint32_t pre_eq = block_excl_scan<kWG>(sum_eq, scratch, &tot_eq);
+  uint4* rec = ws.chunk_rec + static_cast<size_t>(row) * geo.num_chunks + start;
+  for (uint32_t i = 0; i < per; ++i)
+    if (first + i < len) {
+      const uint32_t gt = l_gt[first + i], eq = l_eq[first + i];
+      rec[first + i] = make_uint4(gt, eq, pre_gt, pre_eq);
+      pre_gt += gt;
+      pre_eq += eq;
     }
-    __syncthreads();
-    const uint32_t first = threadIdx.x * kScanItems;
-    uint32_t eq[kScanItems], gt[kScanItems];
-    uint32_t eq_sum = 0;
-#pragma unroll
-    for (int i = 0; i < kScanItems; ++i) {
-      eq[i] = t_eq[first + i];
-      gt[i] = t_gt[first + i];
-      eq_sum += eq[i];
-    }
-    uint32_t eq_total, sel_total;
-    uint32_t eq_before = eq_carry + block_excl_scan<kWG>(eq_sum, scratch, &eq_total);
-    uint32_t sel_sum = 0;
-#pragma unroll
-    for (int i = 0; i < kScanItems; ++i) {
-      const uint32_t room = r > eq_before ? r - eq_before : 0;
-      const uint32_t take = eq[i] < room ? eq[i] : room;
-      t_eq[first + i] = eq_before;  // ties in earlier chunks
-      gt[i] += take;                // selected in this chunk
-      sel_sum += gt[i];
-      eq_before += eq[i];
-    }
-    uint32_t sel_before = sel_carry + block_excl_scan<kWG>(sel_sum, scratch, &sel_total);
-#pragma unroll
-    for (int i = 0; i < kScanItems; ++i) {
-      t_gt[first + i] = sel_before;
-      sel_before += gt[i];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kScanItems; ++i) {
-      const uint32_t t = i * kWG + threadIdx.x;
-      const uint32_t c = c0 + t;
-      if (c < geo.num_chunks) {
-        ws.eq_before[rb + c] = t_eq[t];
-        sel_off[c] = t_gt[t];
-      }
-    }
-    eq_carry += eq_total;
-    sel_carry += sel_total;
-  }
-  if (threadIdx.x == 0) {
-    sel_off[geo.num_chunks] = sel_carry;  // == k
-    rowp->cursor = 0;                     // the next step's first pass allocates its list from the start
-  }
+  if (threadIdx.x == 0) ws.blk[static_cast<size_t>(row) * kMaxCountBlocks + blockIdx.x] = make_uint2(tot_gt, tot_eq);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Kernel 5: per chunk of coordinates.
-//   Phase 1: wavefront w writes the selected entries of workers w, w+4, ... that fall in this chunk to
-//            their final positions in the workers' (coordinate, value) lists.
+// Kernel 5: per chunk of coordinates.  Workers are taken in tiles of kTileWorkers.
+//   Phase 1: a wavefront finds where its workers' entries of this chunk go in the workers' lists (entries
+//            above the threshold in earlier chunks, plus the ties taken there: in coordinate order until r
+//            are in) and writes the selected (coordinate, value) pairs there.
 //   Phase 2: the chunk's entries are added into an LDS tile of the summed gradient, one worker after
 //            the other (a barrier between them): the fp32 sum has exactly the order i = 0 .. n-1, and
 //            one worker's coordinates are distinct, so no atomics are needed.
 //   Phase 3: gbar = sum / n and the AMSGrad moment and parameter update (server lines of Algorithm 2).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kWG) void k_topk_final(float* __restrict__ theta, float* __restrict__ m,
-                                                     float* __restrict__ v, float* __restrict__ vhat,
-                                                     const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
-                                                     TopkOptions opt, AmsParams p) {
+constexpr int kPerWave = 4;                       // workers per wavefront and tile
+constexpr int kTileWorkers = kWaves * kPerWave;
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+  return v;
+}
+
+// (eight wavefronts per SIMD: the streaming phase needs the occupancy more than phase 1 needs registers)
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_topk_final(
+    float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v, float* __restrict__ vhat,
+    const float* __restrict__ e, Geometry geo, TopkWorkspace ws, TopkOptions opt, AmsParams p) {
   __shared__ float gs[kChunk];
+  __shared__ uint32_t sh_lo[kTileWorkers], sh_hi[kTileWorkers], sh_eqb[kTileWorkers];
   const uint32_t c = blockIdx.x;
   const uint32_t base = c * kChunk;
-  const uint32_t wave = threadIdx.x >> 6;
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   for (int t = threadIdx.x; t < kChunk; t += kWG) gs[t] = 0.0f;
+  if (c == 0)  // the next step's first pass allocates its candidate lists from the start
+    for (uint32_t i = threadIdx.x; i < geo.n; i += kWG) ws.rows[i].cursor = 0;
+  const uint32_t my_block = c / geo.count_cpw;  // count blocks before this chunk's
 
-  for (uint32_t i = wave; i < geo.n; i += kWaves) {
-    const uint32_t* so = ws.sel_off + static_cast<size_t>(i) * (geo.num_chunks + 1) + c;
-    uint32_t at = so[0];
-    if (so[1] == at) continue;  // nothing of this worker in the chunk (wave-uniform)
-    const TopkRow* rowp = ws.rows + i;
-    const uint32_t mode = rowp->mode, tau = rowp->tau, r = rowp->r;
-    const bool all_ties = rowp->take_all_ties != 0;
-    const float* er = e + static_cast<int64_t>(i) * geo.ld;
-    const uint2* candr = ws.cand + static_cast<size_t>(i) * opt.cap;
-    const uint2* descr = ws.desc + static_cast<size_t>(i) * geo.num_chunks;
-    int32_t* idx = ws.idx + static_cast<size_t>(i) * geo.k;
-    float* val = ws.val + static_cast<size_t>(i) * geo.k;
-    uint32_t eq_seen = ws.eq_before[static_cast<size_t>(i) * geo.num_chunks + c];
-    for_each_round(mode, er, geo.d, c, candr, descr, opt.cap, [&](const Entry4& en, int slots) {
-      bool sel[4] = {false, false, false, false};
-      if (all_ties) {
-        for (int s = 0; s < slots; ++s) sel[s] = en.ok[s] && key_of_bits(en.bits[s]) >= tau;
-      } else {
-        uint64_t be[4];
-        uint32_t below = 0, total = 0;
-        for (int s = 0; s < slots; ++s) {
-          be[s] = ballot64(en.ok[s] && key_of_bits(en.bits[s]) == tau);
-          below += count_below(be[s]);
-          total += popc64(be[s]);
-        }
-        uint32_t rank = eq_seen + below;  // ties before this lane's first slot, in coordinate order
-        for (int s = 0; s < slots; ++s) {
-          const uint32_t key = key_of_bits(en.bits[s]);
-          const bool is_eq = en.ok[s] && key == tau;
-          sel[s] = en.ok[s] && (key > tau || (is_eq && rank < r));
-          rank += is_eq;
-        }
-        eq_seen += total;
-      }
-      uint64_t bs[4];
-      uint32_t below = 0, total = 0;
-      for (int s = 0; s < slots; ++s) {
-        bs[s] = ballot64(sel[s]);
-        below += count_below(bs[s]);
-        total += popc64(bs[s]);
-      }
-      uint32_t pos = at + below;
-      for (int s = 0; s < slots; ++s)
-        if (sel[s]) {
-          if (pos < geo.k) {  // always true when the counts are consistent
-            idx[pos] = static_cast<int32_t>(en.j[s]);
-            val[pos] = __uint_as_float(en.bits[s]);
-          }
-          ++pos;
-        }
-      at += total;
-    });
-  }
-  __syncthreads();  // the chunk's list entries are visible to the whole workgroup
-
-  // Workers are taken in groups of kGroup: every thread first requests its entry of each worker's chunk
-  // segment (independent loads, one round trip for the whole group), then the entries are added one worker
-  // after the other.
-  constexpr int kGroup = 8;
-  for (uint32_t i0 = 0; i0 < geo.n; i0 += kGroup) {
-    uint32_t lo[kGroup], hi[kGroup], jl[kGroup];
-    float vl[kGroup];
+  for (uint32_t i0 = 0; i0 < geo.n; i0 += kTileWorkers) {
+    // ---- phase 1a: positions, for this wavefront's workers of the tile (all loads issued together) ----
+    {
+      uint4 rec[kPerWave];
+      uint2 part[kPerWave];
+      uint32_t r_[kPerWave];
 #pragma unroll
-    for (int u = 0; u < kGroup; ++u) {
-      const uint32_t i = i0 + u;
-      lo[u] = hi[u] = 0;
-      jl[u] = 0xffffffffu;
-      vl[u] = 0.0f;
-      if (i < geo.n) {
-        const uint32_t* so = ws.sel_off + static_cast<size_t>(i) * (geo.num_chunks + 1) + c;
-        lo[u] = so[0];
-        hi[u] = so[1] < geo.k ? so[1] : geo.k;
-        const uint32_t q = lo[u] + threadIdx.x;
-        if (q < hi[u]) {
-          jl[u] = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + q]) - base;
-          vl[u] = ws.val[static_cast<size_t>(i) * geo.k + q];
+      for (int u = 0; u < kPerWave; ++u) {
+        const uint32_t i = i0 + wave + u * kWaves;
+        rec[u] = make_uint4(0, 0, 0, 0);
+        part[u] = make_uint2(0, 0);
+        r_[u] = 0;
+        if (i < geo.n) {  // wave-uniform
+          rec[u] = ws.chunk_rec[static_cast<size_t>(i) * geo.num_chunks + c];
+          const uint2* blk = ws.blk + static_cast<size_t>(i) * kMaxCountBlocks;
+          for (uint32_t b = lane; b < my_block; b += 64) {
+            const uint2 t = blk[b];
+            part[u].x += t.x;
+            part[u].y += t.y;
+          }
+          r_[u] = ws.rows[i].r;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kPerWave; ++u) {
+        const uint32_t i = i0 + wave + u * kWaves;
+        if (i >= geo.n) continue;  // wave-uniform
+        const uint32_t gt_before = wave_sum(part[u].x) + rec[u].z;
+        const uint32_t eq_before = wave_sum(part[u].y) + rec[u].w;
+        const uint32_t r = r_[u];
+        const uint32_t taken_before = eq_before < r ? eq_before : r;  // ties go in coordinate order until r are in
+        const uint32_t quota = r - taken_before;
+        const uint32_t take_here = rec[u].y < quota ? rec[u].y : quota;
+        const uint32_t at = gt_before + taken_before;
+        const uint32_t hi = at + rec[u].x + take_here;
+        if (lane == 0) {
+          uint32_t* so = ws.sel_off + static_cast<size_t>(i) * (geo.num_chunks + 1);
+          so[c] = at;  // the next step's first pass finds this chunk's slice of the list here
+          if (c + 1 == geo.num_chunks) so[c + 1] = hi;
+          sh_lo[i - i0] = at;
+          sh_hi[i - i0] = hi;
+          sh_eqb[i - i0] = eq_before;
         }
       }
     }
-#pragma unroll
-    for (int u = 0; u < kGroup; ++u) {
-      const uint32_t i = i0 + u;
-      if (i < geo.n) {  // uniform
-        if (jl[u] < static_cast<uint32_t>(kChunk)) gs[jl[u]] = gs[jl[u]] + vl[u];
-        for (uint32_t q = lo[u] + kWG + threadIdx.x; q < hi[u]; q += kWG) {  // segments longer than a workgroup
-          const uint32_t j = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + q]) - base;
-          if (j < static_cast<uint32_t>(kChunk)) gs[j] = gs[j] + ws.val[static_cast<size_t>(i) * geo.k + q];
+    // ---- phase 1b: write the selected entries (positions come back from LDS: written by this wavefront) ----
+#pragma unroll 1
+    for (uint32_t i = i0 + wave; i < geo.n && i < i0 + kTileWorkers; i += kWaves) {
+      uint32_t at = sh_lo[i - i0];
+      const uint32_t hi = sh_hi[i - i0];
+      if (hi == at) continue;  // nothing of this worker in the chunk (wave-uniform)
+      const float* er = e + static_cast<int64_t>(i) * geo.ld;
+      const uint2* candr = ws.cand + static_cast<size_t>(i) * opt.cap;
+      const uint2* descr = ws.desc + static_cast<size_t>(i) * geo.num_chunks;
+      int32_t* idx = ws.idx + static_cast<size_t>(i) * geo.k;
+      float* val = ws.val + static_cast<size_t>(i) * geo.k;
+      const TopkRow* rowp = ws.rows + i;
+      const uint32_t mode = rowp->mode, tau = rowp->tau, r = rowp->r;
+      const bool all_ties = rowp->take_all_ties != 0;
+      uint32_t eq_seen = sh_eqb[i - i0];
+      for_each_round(mode, er, geo.d, c, candr, descr, opt.cap, [&](const Entry4& en, int slots) {
+        bool sel[4] = {false, false, false, false};
+        if (all_ties) {
+          for (int s = 0; s < slots; ++s) sel[s] = en.ok[s] && key_of_bits(en.bits[s]) >= tau;
+        } else {
+          uint64_t be[4];
+          uint32_t below = 0, total = 0;
+          for (int s = 0; s < slots; ++s) {
+            be[s] = ballot64(en.ok[s] && key_of_bits(en.bits[s]) == tau);
+            below += count_below(be[s]);
+            total += popc64(be[s]);
+          }
+          uint32_t rank = eq_seen + below;  // ties before this lane's first slot, in coordinate order
+          for (int s = 0; s < slots; ++s) {
+            const uint32_t key = key_of_bits(en.bits[s]);
+            const bool is_eq = en.ok[s] && key == tau;
+            sel[s] = en.ok[s] && (key > tau || (is_eq && rank < r));
+            rank += is_eq;
+          }
+          eq_seen += total;
         }
-        __syncthreads();
+        uint64_t bs[4];
+        uint32_t below = 0, total = 0;
+        for (int s = 0; s < slots; ++s) {
+          bs[s] = ballot64(sel[s]);
+          below += count_below(bs[s]);
+          total += popc64(bs[s]);
+        }
+        uint32_t pos = at + below;
+        for (int s = 0; s < slots; ++s)
+          if (sel[s]) {
+            if (pos < geo.k) {  // always true when the counts are consistent
+              idx[pos] = static_cast<int32_t>(en.j[s]);
+              val[pos] = __uint_as_float(en.bits[s]);
+            }
+            ++pos;
+          }
+        at += total;
+      });
+    }
+    __syncthreads();  // the chunk's list entries and their positions are visible to the whole workgroup
+
+    // ---- phase 2 ----
+    // Workers are taken in groups of kGroup: every thread first requests its entry of each worker's chunk
+    // segment (independent loads, one round trip for the whole group), then the entries are added one worker
+    // after the other.
+    constexpr int kGroup = 8;
+    const uint32_t i_end = i0 + kTileWorkers < geo.n ? i0 + kTileWorkers : geo.n;
+    for (uint32_t g0 = i0; g0 < i_end; g0 += kGroup) {
+      uint32_t lo[kGroup], hi[kGroup], jl[kGroup];
+      float vl[kGroup];
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        const uint32_t i = g0 + u;
+        lo[u] = hi[u] = 0;
+        jl[u] = 0xffffffffu;
+        vl[u] = 0.0f;
+        if (i < i_end) {
+          lo[u] = sh_lo[i - i0];
+          hi[u] = sh_hi[i - i0] < geo.k ? sh_hi[i - i0] : geo.k;
+          const uint32_t q = lo[u] + threadIdx.x;
+          if (q < hi[u]) {
+            jl[u] = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + q]) - base;
+            vl[u] = ws.val[static_cast<size_t>(i) * geo.k + q];
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        const uint32_t i = g0 + u;
+        if (i < i_end) {  // uniform
+          if (jl[u] < static_cast<uint32_t>(kChunk)) gs[jl[u]] = gs[jl[u]] + vl[u];
+          for (uint32_t q = lo[u] + kWG + threadIdx.x; q < hi[u]; q += kWG) {  // segments longer than a workgroup
+            const uint32_t j = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + q]) - base;
+            if (j < static_cast<uint32_t>(kChunk)) gs[j] = gs[j] + ws.val[static_cast<size_t>(i) * geo.k + q];
+          }
+          __syncthreads();
+        }
       }
     }
   }
@@ -1103,7 +1115,8 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   COMPAMS_CHECK_LAUNCH();
   launch(L, kSlotLevel2, k_topk_level2, grid_rows, wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotCount, k_topk_count, grid_rows, wg, stream, e, geo, ws, opt);
+  const uint32_t count_blocks = (geo.num_chunks + geo.count_cpw - 1) / geo.count_cpw;  // <= kMaxCountBlocks
+  launch(L, kSlotCount, k_topk_count, dim3(count_blocks, geo.n), wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
   launch(L, kSlotTopkFinal, k_topk_final, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws, opt, ap);
   COMPAMS_CHECK_LAUNCH();
