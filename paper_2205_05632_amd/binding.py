@@ -12,7 +12,7 @@ import numpy as np
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("COMPAMS_LIB", os.path.join(HERE, "libcompams.so"))
+LIB_PATH = os.path.join(HERE, "libcompams.so")
 
 NONE, TOPK, BLOCKSIGN = 0, 1, 2
 EPS_IN_SQRT, EPS_OUT_SQRT = 0, 1

@@ -14,8 +14,6 @@
 // re-reads x and writes sign bits and residuals, and the server kernel adds the n workers' +-mu in
 // worker order before the AMSGrad update.
 
-#include <cstdlib>
-
 #include "compams_device.h"
 #include "compams_internal.h"
 

@@ -8,18 +8,19 @@
 // Five kernels per step:
 //   1 first pass   x = e + g -> e, level-0 histogram of the keys (12 bits); when the previous step's
 //                  threshold bucket is carried over as a guess, the same pass also writes the candidate
-//                  list (entries at or above the guessed bucket) and the level-1 histograms of the two
-//                  buckets the threshold is expected in.  The last workgroup of a row to finish finds
+//                  list (entries at or above the guessed bucket) and the level-1 histograms of the three
+//                  buckets from the guess upwards, among which the threshold is expected.  The last workgroup of a row to finish finds
 //                  the threshold bucket, checks the guess, and resolves level 1 if it can.
 //   2 level 1      only for rows whose guess failed (or had none): one more read of the row that writes
 //                  the candidate list with the exact bucket and builds the level-1 histogram (10 bits);
 //                  rows that would not fit a list are histogrammed from the row itself.
 //   3 level 2      histogram of the last 9 key bits over the matching candidates; yields the k-th largest
 //                  key tau and how many keys equal to tau are taken.
-//   4 count        per chunk: keys above tau and keys equal to tau; the row's last workgroup turns them
-//                  into exclusive prefixes (positions of every chunk's entries in the output lists).
-//   5 final        per chunk of coordinates: each worker's selected entries are written to its list, then
-//                  added in worker order into an LDS tile of the averaged gradient, then AMSGrad.
+//   4 count        per chunk: keys above tau and keys equal to tau, with prefixes inside contiguous blocks of
+//                  chunks and the totals of every block.
+//   5 final        per chunk of coordinates: the position of each worker's entries in its list follows from
+//                  the block totals and prefixes; the selected entries are written there, then added in
+//                  worker order into an LDS tile of the averaged gradient, then AMSGrad.
 // Zeroing the residual at the selected coordinates is not done by scattered stores: the next step's
 // first pass treats the coordinates in the previous lists as zero while it forms x (and a small kernel
 // applies the zeros when the caller asks for e).
@@ -29,14 +30,8 @@
 // their physical order varies from run to run but nothing that is output depends on it.  No
 // floating-point atomics are used anywhere.
 
-#include <cstdlib>
-
 #include "compams_device.h"
 #include "compams_internal.h"
-
-#ifndef COMPAMS_DBG
-#define COMPAMS_DBG 0
-#endif
 
 namespace compams {
 namespace {
@@ -85,10 +80,7 @@ __device__ __forceinline__ RoundRank rank_round(const bool flag[4]) {
 // Candidate entries of the chunk a wavefront is walking are first staged in LDS (kStage entries per
 // wavefront) so that the chunk's segment can be allocated with one atomic once its size is known and
 // then written with coalesced stores.  A chunk with more candidates than that is re-read instead.
-#ifndef COMPAMS_STAGE
-#define COMPAMS_STAGE 512
-#endif
-constexpr int kStage = COMPAMS_STAGE;
+constexpr int kStage = 512;
 
 __device__ __forceinline__ void stage_round(uint2* stage, uint32_t& n, uint32_t j, const uint32_t bits[4],
                                             const bool flag[4]) {
@@ -279,10 +271,7 @@ __device__ __forceinline__ void resolve_level1(TopkRow* rp, uint32_t bstar, uint
 //   PEND: coordinates selected in the previous step still hold their old value in e and count as zero.
 // ---------------------------------------------------------------------------------------------
 constexpr int kBatch = 4;  // rounds whose loads are in flight together
-#ifndef COMPAMS_WGA
-#define COMPAMS_WGA 256
-#endif
-constexpr int kWGA = COMPAMS_WGA;  // threads per workgroup of the first pass
+constexpr int kWGA = 256;  // threads per workgroup of the first pass
 constexpr int kWavesA = kWGA / 64;
 
 struct Batch {
@@ -298,13 +287,8 @@ __device__ __forceinline__ void load_batch(Batch& b, const float* __restrict__ g
     b.g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
     b.e[u] = b.g[u];
     if (FULL || j < d) {
-      if constexpr (COMPAMS_DBG & 16) {
-        b.g[u] = *reinterpret_cast<const float4*>(gr + j);
-        b.e[u] = *reinterpret_cast<const float4*>(er + j);
-      } else {
-        b.g[u] = load_stream4(gr + j);
-        b.e[u] = load_stream4(er + j);
-      }
+      b.g[u] = load_stream4(gr + j);
+      b.e[u] = load_stream4(er + j);
     }
   }
 }
@@ -454,7 +438,7 @@ __device__ __forceinline__ void pass_a_walk(PassA& A, uint32_t first, uint32_t s
     }
     if constexpr (PEND)
       if (more) pend_request(pa, A, cn);
-    if constexpr (PRED && !(COMPAMS_DBG & 8)) {
+    if constexpr (PRED) {
       if (A.pred) {
         // request this chunk's segment now, write the previous chunk's (whose request returned long ago)
         const uint32_t raw = segment_request(A.rowp, cnt);
@@ -540,7 +524,6 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
     }
 
   // ---- row-wide part, by whichever workgroup of the row finishes last ----
-  if constexpr (COMPAMS_DBG & 64) return;
   if (!last_group_of_row(&rowp->ticket[0], gridDim.x, &sh_flag)) return;
   take_hist<kNB0, kWGA>(gh, lh);
   find_crossing<kNB0, kWGA>(lh, geo.k, suf, out2);
@@ -763,16 +746,24 @@ __device__ __forceinline__ void for_each_round(uint32_t mode, const float* __res
     uint32_t cnt = first_lane(ds.y);
     if (off > cap) cnt = 0;                      // segments always lie inside the list; never read outside it
     else if (cnt > cap - off) cnt = cap - off;
-    for (uint32_t t = 0; t < cnt; t += 64) {
-      Entry4 en;
-      const uint32_t q = t + lane;
-      en.ok[0] = q < cnt;
-      uint2 cv = make_uint2(0, 0);
-      if (en.ok[0]) cv = candr[off + q];
-      en.j[0] = cv.x; en.bits[0] = cv.y;
+    constexpr int kAhead = 4;  // loads in flight per trip (long segments would otherwise be a chain of round trips)
+    for (uint32_t t = 0; t < cnt; t += 64 * kAhead) {
+      uint2 cv[kAhead];
 #pragma unroll
-      for (int s = 1; s < 4; ++s) { en.j[s] = 0; en.bits[s] = 0; en.ok[s] = false; }
-      f(en, 1);
+      for (int w = 0; w < kAhead; ++w) {
+        const uint32_t q = t + w * 64 + lane;
+        cv[w] = q < cnt ? candr[off + q] : make_uint2(0, 0);
+      }
+#pragma unroll
+      for (int w = 0; w < kAhead; ++w) {
+        if (t + w * 64 >= cnt) break;  // wave-uniform
+        Entry4 en;
+        en.ok[0] = t + w * 64 + lane < cnt;
+        en.j[0] = cv[w].x; en.bits[0] = cv[w].y;
+#pragma unroll
+        for (int s = 1; s < 4; ++s) { en.j[s] = 0; en.bits[s] = 0; en.ok[s] = false; }
+        f(en, 1);
+      }
     }
   }
 }
@@ -1040,9 +1031,23 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         const uint32_t i = g0 + u;
         if (i < i_end) {  // uniform
           if (jl[u] < static_cast<uint32_t>(kChunk)) gs[jl[u]] = gs[jl[u]] + vl[u];
-          for (uint32_t q = lo[u] + kWG + threadIdx.x; q < hi[u]; q += kWG) {  // segments longer than a workgroup
-            const uint32_t j = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + q]) - base;
-            if (j < static_cast<uint32_t>(kChunk)) gs[j] = gs[j] + ws.val[static_cast<size_t>(i) * geo.k + q];
+          // segments longer than a workgroup: four entries per thread and trip, loads in flight together
+          for (uint32_t q = lo[u] + kWG + threadIdx.x; q < hi[u]; q += 4 * kWG) {
+            uint32_t jj[4];
+            float vv[4];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+              const uint32_t qq = q + w * kWG;
+              jj[w] = 0xffffffffu;
+              vv[w] = 0.0f;
+              if (qq < hi[u]) {
+                jj[w] = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + qq]) - base;
+                vv[w] = ws.val[static_cast<size_t>(i) * geo.k + qq];
+              }
+            }
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+              if (jj[w] < static_cast<uint32_t>(kChunk)) gs[jj[w]] = gs[jj[w]] + vv[w];
           }
           __syncthreads();
         }
