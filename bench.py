@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="r18_topk1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=2, help="oracle steps timed for the cpu_baseline leg")
+    ap.add_argument("--cpu-steps", type=int, default=10, help="oracle steps timed for the cpu_baseline leg")
     ap.add_argument("--kernels", action="store_true",
                     help="bracket every kernel with events and print the per-kernel table to stderr")
     ap.add_argument("--no-predict", action="store_true", help="ablation: re-read the row instead of guessing")

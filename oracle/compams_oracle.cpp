@@ -24,6 +24,9 @@
 //   * epsilon sits inside the square root as in Algorithms 1 and 2; the outside
 //     form is available as a switch.
 //
+//   * the wire format of a message is this library's own (the paper only fixes 32 bits per transmitted
+//     float); it is stated at the encode functions below and in the public header.
+//
 // Parity pins: every exported function is pinned by tests/test_oracle_*.py
 // (brute-force sort, math.fsum, closed forms, Lemma 5 telescoping, the identity
 // special cases that reduce Algorithm 2 to Algorithm 1, a hand-derived d=8 case).
@@ -333,6 +336,87 @@ double oracle_exact_abs_sum(const float* x, int64_t len) {
   ExactSum s;
   for (int64_t j = 0; j < len; ++j) s.add_abs(x[j]);
   return s.to_double();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Wire format of one worker's message (what "send the compressed gradient to the server" in the worker
+// lines of Algorithm 2 puts on the wire), as a sequence of 32-bit words.  The paper fixes only the
+// accounting (32 bits per transmitted float, experiments section); the layout is this library's own and
+// is stated in full in the public header.  Written here bit by bit, straight from that statement.
+//
+//   top-k      [1, k, b,  gap stream of ceil(k*b/32) words,  k value words]
+//              gap_0 = idx_0, gap_q = idx_q - idx_{q-1} - 1; b = number of bits of the largest gap (at least 1);
+//              gap q occupies stream bits q*b .. q*b+b-1, least significant bit first; stream bit t is
+//              bit (t mod 32) of stream word t div 32; unused bits of the last stream word are 0.
+//   block-sign [2, d, M,  ceil(d/32) sign words,  M scale words]
+// ---------------------------------------------------------------------------------------------
+int64_t oracle_wire_encode_topk(int64_t k, const int32_t* idx, const float* val, uint32_t* out) {
+  uint32_t widest = 0;
+  std::vector<uint32_t> gap(static_cast<size_t>(k));
+  for (int64_t q = 0; q < k; ++q) {
+    gap[q] = q == 0 ? static_cast<uint32_t>(idx[0])
+                    : static_cast<uint32_t>(idx[q]) - static_cast<uint32_t>(idx[q - 1]) - 1u;
+    if (gap[q] > widest) widest = gap[q];
+  }
+  uint32_t b = 1;
+  while (b < 32 && (widest >> b) != 0) ++b;
+  const int64_t stream_words = (k * b + 31) / 32;
+  out[0] = 1u; out[1] = static_cast<uint32_t>(k); out[2] = b;
+  uint32_t* stream = out + 3;
+  for (int64_t w = 0; w < stream_words; ++w) stream[w] = 0;
+  for (int64_t q = 0; q < k; ++q)
+    for (uint32_t t = 0; t < b; ++t)
+      if ((gap[q] >> t) & 1u) {
+        const int64_t pos = q * b + t;
+        stream[pos / 32] |= 1u << (pos % 32);
+      }
+  uint32_t* values = stream + stream_words;
+  for (int64_t q = 0; q < k; ++q) std::memcpy(&values[q], &val[q], 4);
+  return 3 + stream_words + k;
+}
+
+// Returns 0, or a negative number if the words are not a top-k message of k entries below d.
+int64_t oracle_wire_decode_topk(const uint32_t* msg, int64_t nwords, int64_t k, int64_t d, int32_t* idx, float* val) {
+  if (nwords < 3 || msg[0] != 1u || msg[1] != static_cast<uint32_t>(k)) return -1;
+  const uint32_t b = msg[2];
+  if (b < 1 || b > 31) return -2;
+  const int64_t stream_words = (k * b + 31) / 32;
+  if (nwords != 3 + stream_words + k) return -3;
+  const uint32_t* stream = msg + 3;
+  int64_t prev = -1;
+  for (int64_t q = 0; q < k; ++q) {
+    uint32_t gap = 0;
+    for (uint32_t t = 0; t < b; ++t) {
+      const int64_t pos = q * b + t;
+      gap |= ((stream[pos / 32] >> (pos % 32)) & 1u) << t;
+    }
+    const int64_t j = prev + 1 + static_cast<int64_t>(gap);
+    if (j >= d) return -4;
+    idx[q] = static_cast<int32_t>(j);
+    prev = j;
+  }
+  const uint32_t* values = stream + stream_words;
+  for (int64_t q = 0; q < k; ++q) std::memcpy(&val[q], &values[q], 4);
+  return 0;
+}
+
+int64_t oracle_wire_encode_blocksign(int64_t d, int64_t M, const uint32_t* bits, const float* mu, uint32_t* out) {
+  const int64_t words = (d + 31) / 32;
+  out[0] = 2u; out[1] = static_cast<uint32_t>(d); out[2] = static_cast<uint32_t>(M);
+  for (int64_t w = 0; w < words; ++w) out[3 + w] = bits[w];
+  for (int64_t b = 0; b < M; ++b) std::memcpy(&out[3 + words + b], &mu[b], 4);
+  return 3 + words + M;
+}
+
+int64_t oracle_wire_decode_blocksign(const uint32_t* msg, int64_t nwords, int64_t d, int64_t M, uint32_t* bits,
+                                     float* mu) {
+  const int64_t words = (d + 31) / 32;
+  if (nwords != 3 + words + M || msg[0] != 2u || msg[1] != static_cast<uint32_t>(d) ||
+      msg[2] != static_cast<uint32_t>(M))
+    return -1;
+  for (int64_t w = 0; w < words; ++w) bits[w] = msg[3 + w];
+  for (int64_t b = 0; b < M; ++b) std::memcpy(&mu[b], &msg[3 + words + b], 4);
+  return 0;
 }
 
 }  // extern "C"

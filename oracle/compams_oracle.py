@@ -43,6 +43,15 @@ def lib():
         L.oracle_block_l1_mean.argtypes = [f32p, ctypes.c_int64]
         L.oracle_exact_abs_sum.restype = ctypes.c_double
         L.oracle_exact_abs_sum.argtypes = [f32p, ctypes.c_int64]
+        u32p = ctypes.POINTER(ctypes.c_uint32)
+        L.oracle_wire_encode_topk.restype = ctypes.c_int64
+        L.oracle_wire_encode_topk.argtypes = [ctypes.c_int64, i32p, f32p, u32p]
+        L.oracle_wire_decode_topk.restype = ctypes.c_int64
+        L.oracle_wire_decode_topk.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, i32p, f32p]
+        L.oracle_wire_encode_blocksign.restype = ctypes.c_int64
+        L.oracle_wire_encode_blocksign.argtypes = [ctypes.c_int64, ctypes.c_int64, u32p, f32p, u32p]
+        L.oracle_wire_decode_blocksign.restype = ctypes.c_int64
+        L.oracle_wire_decode_blocksign.argtypes = [u32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, u32p, f32p]
         _lib = L
     return _lib
 
@@ -68,6 +77,51 @@ def block_l1_mean(x):
 def exact_abs_sum(x):
     x, px = _f32(x)
     return float(lib().oracle_exact_abs_sum(px, x.size))
+
+
+def _u32p(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32))
+
+
+def wire_encode_topk(idx, val):
+    """One worker's top-k message as uint32 words."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    val, pv = _f32(val)
+    k = idx.size
+    out = np.zeros(3 + 2 * k, dtype=np.uint32)
+    n = lib().oracle_wire_encode_topk(k, idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), pv, _u32p(out))
+    return out[:n].copy()
+
+
+def wire_decode_topk(msg, k, d):
+    """(idx, val) of a top-k message, or raises ValueError if the words are not one for (k, d)."""
+    msg = np.ascontiguousarray(msg, dtype=np.uint32)
+    idx = np.empty(k, dtype=np.int32)
+    val = np.empty(k, dtype=np.float32)
+    rc = lib().oracle_wire_decode_topk(_u32p(msg), msg.size, k, d, idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                       val.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if rc != 0:
+        raise ValueError(f"not a top-k message (code {rc})")
+    return idx, val
+
+
+def wire_encode_blocksign(d, bits, mu):
+    bits = np.ascontiguousarray(bits, dtype=np.uint32)
+    mu, pm = _f32(mu)
+    out = np.zeros(3 + bits.size + mu.size, dtype=np.uint32)
+    n = lib().oracle_wire_encode_blocksign(d, mu.size, _u32p(bits), pm, _u32p(out))
+    return out[:n].copy()
+
+
+def wire_decode_blocksign(msg, d, M):
+    msg = np.ascontiguousarray(msg, dtype=np.uint32)
+    bits = np.empty((d + 31) // 32, dtype=np.uint32)
+    mu = np.empty(M, dtype=np.float32)
+    rc = lib().oracle_wire_decode_blocksign(_u32p(msg), msg.size, d, M, _u32p(bits),
+                                            mu.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if rc != 0:
+        raise ValueError(f"not a block-sign message (code {rc})")
+    return bits, mu
 
 
 class Oracle:

@@ -300,6 +300,36 @@ def test_identity_compressor(n, d):
     p.close()
 
 
+def test_degenerate_compressors_are_the_identity():
+    """Top-k with k = d and block-sign with one coordinate per block keep everything (the compressors with q = 0
+    of Remark 1): the step then is distributed AMSGrad without compression, bit for bit, and e stays zero."""
+    n, d, steps = 3, 20003, 5
+    rng = np.random.default_rng(77)
+    theta0 = torch.from_numpy(rng.standard_normal(d).astype(np.float32) * 0.1)
+    gs = rand_grads(78, n, d, steps, scale=0.5)
+    for g in gs:
+        g[:, ::7] = 0.0
+    ctxs = {
+        "none": B.Compams(n, d, theta0.clone(), compressor=B.NONE),
+        "topk": B.Compams(n, d, theta0.clone(), compressor=B.TOPK, k=d),
+        "blocksign": B.Compams(n, d, theta0.clone(), compressor=B.BLOCKSIGN,
+                               block_offsets=np.arange(d + 1, dtype=np.int64)),
+    }
+    for g in gs:
+        for c in ctxs.values():
+            gp = torch.zeros((n, c.ld), dtype=torch.float32)
+            gp[:, :d] = torch.from_numpy(g)
+            c.compams_step(gp.to(c.device), 1e-3)
+    ref = {s: ctxs["none"].compams_state(s).cpu().numpy() for s in ("theta", "m", "v", "vhat")}
+    for name in ("topk", "blocksign"):
+        for s, want in ref.items():
+            got = ctxs[name].compams_state(s).cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), (name, s)
+        assert not ctxs[name].compams_state("e")[:, :d].any(), name
+    for c in ctxs.values():
+        c.close()
+
+
 # ------------------------------------------------------------------------------------------- hand-derived case
 @pytest.mark.parametrize("eps_mode,key", [(B.EPS_IN_SQRT, "theta_eps_in"), (B.EPS_OUT_SQRT, "theta_eps_out")])
 def test_worked_example_on_gpu(eps_mode, key):
