@@ -153,6 +153,31 @@ def main():
         for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
             print(f"  {name:16s} {ms / cnt * 1e3:9.1f} us/launch  x{cnt}", file=sys.stderr)
 
+    # the last step's messages on the wire: sizes (32 bits per word, the accounting of the paper's experiments
+    # section) and the time to pack and unpack them; not part of `value`
+    wire = None
+    if comp != B.NONE:
+        reps = 20
+        msgs, words = ctx.compams_encode()      # warm-up: first launches load the kernels
+        ctx.compams_decode(msgs, words)
+        torch.cuda.synchronize()
+        w0 = time.perf_counter()
+        for _ in range(reps):
+            msgs, words = ctx.compams_encode()
+        torch.cuda.synchronize()
+        w1 = time.perf_counter()
+        for _ in range(reps):
+            ctx.compams_decode(msgs, words)
+        torch.cuda.synchronize()
+        w2 = time.perf_counter()
+        bits = 32.0 * float(words.float().mean().item())
+        wire = {"bits_per_worker": bits, "full_gradient_bits": 32.0 * w.d, "reduction": 32.0 * w.d / bits,
+                "encode_us": (w1 - w0) / reps * 1e6, "decode_us": (w2 - w1) / reps * 1e6}
+        if comp == B.TOPK:
+            wire["gap_bits"] = msgs[:, 2].tolist()
+            wire["reduction_values_only"] = w.d / w.k
+        del msgs, words
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import compams_oracle as O
@@ -183,6 +208,7 @@ def main():
         "roofline": roofline,
         "kernels_us_per_launch": {k_: v_[0] / v_[1] * 1e3 for k_, v_ in prof.items()},
         "topk_counters": counters,
+        "wire": wire,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

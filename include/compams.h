@@ -154,6 +154,44 @@ int compams_destroy(compams_ctx* ctx);
 /* Static description of a status code. */
 const char* compams_strerror(int status);
 
+/* ---- The workers' messages on the wire ------------------------------------------------------------------
+ * What a worker sends to the server in its "send" line of Algorithm 2, as one contiguous sequence of 32-bit
+ * little-endian words per worker.  The paper fixes only the accounting (experiments section: 32 bits per
+ * transmitted float); the layout below is this library's.
+ *
+ *   top-k (Definition 1)       [1, k, b,  gap stream: ceil(k*b/32) words,  k value words]
+ *       The kept coordinates are ascending; gap_0 = idx_0 and gap_q = idx_q - idx_{q-1} - 1.  b (1..31) is the
+ *       number of bits of the largest gap of the message (1 if all gaps are 0).  Gap q occupies bits q*b ..
+ *       q*b+b-1 of the stream, least significant bit first; stream bit t is bit (t mod 32) of stream word
+ *       t div 32; the unused high bits of the last stream word are 0.  The values are the fp32 patterns of
+ *       the corrected gradient at the kept coordinates, in the same order.
+ *   block-sign (Definition 2)  [2, d, M,  ceil(d/32) sign words,  M scale words]
+ *       Bit (j mod 32) of sign word j div 32 is 1 iff x_j < 0 (unused bits 0); scale b is the fp32 mean of
+ *       |x| over block b.
+ *
+ * Bits per worker and step: 32 * (message length in words).  For comparison the paper counts 32*d bits for an
+ * uncompressed gradient; a top-k message is between 32*k (its values alone) and 64*k + 96 bits.
+ *
+ * compams_wire_capacity: the largest message (in words) a worker of this configuration can produce; pure,
+ *   host only; 0 for an invalid configuration or COMPAMS_NONE (nothing is compressed: the message would be
+ *   the gradient row itself).
+ * compams_encode: packs the n messages of the last step.  messages: DEVICE, n * stride_words words, worker
+ *   i's message starts at messages + i * stride_words (stride_words >= capacity); words_out: DEVICE, n
+ *   words, receives each message's length.  Enqueued on hip_stream (the step's stream, or one ordered after
+ *   it).  COMPAMS_BAD_STATE before the first step or for COMPAMS_NONE.
+ * compams_decode: the inverse, for n messages laid out the same way.  words: DEVICE, the n lengths, or NULL
+ *   (then lengths are not checked).  top-k: out_a = int32[n*k] coordinates, out_b = float[n*k] values;
+ *   block-sign: out_a = uint32[n*ceil(d/32)] sign words, out_b = float[n*M] scales (all DEVICE, caller-owned).
+ *   status_out: DEVICE, n words: 0 if message i was well formed, else bit 0 = not a message of this kind and
+ *   size, bit 1 = length differs from `words`, bit 2 = a coordinate at or beyond d.  Malformed input never
+ *   makes the library read outside [message, message + stride_words); the outputs for such a message are
+ *   unspecified.  Uses the context's workspace: not concurrent with compams_step or another decode on the
+ *   same context. */
+size_t compams_wire_capacity(const compams_config* cfg);
+int compams_encode(compams_ctx* ctx, uint32_t* messages, int64_t stride_words, uint32_t* words_out, void* hip_stream);
+int compams_decode(compams_ctx* ctx, const uint32_t* messages, int64_t stride_words, const uint32_t* words,
+                   void* out_a, void* out_b, uint32_t* status_out, void* hip_stream);
+
 /* A plain streaming copy of `bytes` bytes (multiple of 16, both pointers DEVICE and 16-byte aligned) with
  * the same launch style as the step's dense kernels: the measured bandwidth ceiling that reports set
  * beside the step's figures, and the known-size kernel that hardware counters are calibrated against. */

@@ -26,7 +26,8 @@ _STATE_DTYPE = {"last_idx": torch.int32, "last_signbits": torch.int32, "last_thr
                 "counters": torch.int32}
 
 EXPORTS = ["compams_workspace_size", "compams_init", "compams_step", "compams_state", "compams_set_option",
-           "compams_profile_enable", "compams_profile_read", "compams_destroy", "compams_strerror", "compams_copy"]
+           "compams_profile_enable", "compams_profile_read", "compams_destroy", "compams_strerror", "compams_copy",
+           "compams_wire_capacity", "compams_encode", "compams_decode"]
 
 
 class compams_config(ctypes.Structure):
@@ -70,6 +71,11 @@ def lib():
         L.compams_strerror.restype = ctypes.c_char_p
         L.compams_strerror.argtypes = [ctypes.c_int]
         L.compams_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.compams_wire_capacity.restype = ctypes.c_size_t
+        L.compams_wire_capacity.argtypes = [cfgp]
+        L.compams_encode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        L.compams_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -175,6 +181,39 @@ class Compams:
         if name == "counters":
             return t.view(self.n, COUNTERS_PER_ROW)
         return t
+
+    # -- the messages on the wire ----------------------------------------------------------------
+    def compams_wire_capacity(self) -> int:
+        """Largest message of one worker, in 32-bit words."""
+        return int(lib().compams_wire_capacity(ctypes.byref(self._cfg)))
+
+    def compams_encode(self, stride_words=None):
+        """Packs the last step's messages: (messages int32[n, stride] viewed as raw words, words int32[n])."""
+        stride = self.compams_wire_capacity() if stride_words is None else int(stride_words)
+        messages = torch.empty((self.n, stride), dtype=torch.int32, device=self.device)
+        words = torch.empty(self.n, dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(lib().compams_encode(self._h, messages.data_ptr(), stride, words.data_ptr(),
+                                        _current_stream_handle()), "compams_encode")
+        return messages, words
+
+    def compams_decode(self, messages: torch.Tensor, words=None):
+        """Unpacks n messages: (idx int32[n, k], val float[n, k]) or (sign words int32[n, W], scales float[n, M]),
+        and the per-message status words."""
+        assert messages.dtype == torch.int32 and messages.is_cuda and messages.is_contiguous()
+        assert messages.shape[0] == self.n
+        if self.compressor == TOPK:
+            a = torch.empty((self.n, self.k), dtype=torch.int32, device=self.device)
+            b = torch.empty((self.n, self.k), dtype=torch.float32, device=self.device)
+        else:
+            a = torch.empty((self.n, (self.d + 31) // 32), dtype=torch.int32, device=self.device)
+            b = torch.empty((self.n, self.M), dtype=torch.float32, device=self.device)
+        status = torch.empty(self.n, dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(lib().compams_decode(self._h, messages.data_ptr(), messages.shape[1],
+                                        None if words is None else words.data_ptr(), a.data_ptr(), b.data_ptr(),
+                                        status.data_ptr(), _current_stream_handle()), "compams_decode")
+        return a, b, status
 
     # -- extras ----------------------------------------------------------------------------------
     def set_option(self, option: int, value: int):

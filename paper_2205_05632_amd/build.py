@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcompams.so")
-SOURCES = ["compams_api.hip", "compams_topk.hip", "compams_blocksign.hip"]
+SOURCES = ["compams_api.hip", "compams_topk.hip", "compams_blocksign.hip", "compams_wire.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",

@@ -48,14 +48,15 @@ namespace {
 
 const char* const kSlotNames[kNumSlots] = {
     "topk_pass_a", "topk_level1", "topk_level2", "topk_count", "topk_final",
-    "bs_pass1", "bs_finalize", "bs_pass2", "bs_amsgrad", "none_amsgrad"};
+    "bs_pass1", "bs_finalize", "bs_pass2", "bs_amsgrad", "none_amsgrad", "wire_encode", "wire_decode"};
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
   size_t total;
   // top-k
-  size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau;
+  size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, wire_max,
+      wire_tiles;
   // block-sign
   size_t offsets, chunk_block, acc, special, done, scales, bits;
   uint32_t cap_alloc, num_chunks, words;
@@ -99,6 +100,8 @@ Layout make_layout(const compams_config* c) {
     L.idx = take(n * k * 4);
     L.val = take(n * k * 4);
     L.tau = take(n * 4);
+    L.wire_max = take(n * 4);
+    L.wire_tiles = take(n * ((k + kWireTile - 1) / kWireTile) * 4);
   } else if (c->compressor == COMPAMS_BLOCKSIGN) {
     const size_t M = static_cast<size_t>(c->num_blocks);
     L.offsets = take((M + 1) * 4);
@@ -205,6 +208,8 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     t.chunk_rec = reinterpret_cast<uint4*>(w + lay.chunk_rec);
     t.blk = reinterpret_cast<uint2*>(w + lay.blk);
     t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);
+    t.wire_max = reinterpret_cast<uint32_t*>(w + lay.wire_max);
+    t.wire_tiles = reinterpret_cast<uint32_t*>(w + lay.wire_tiles);
     t.desc = reinterpret_cast<uint2*>(w + lay.desc);
     t.cand = reinterpret_cast<uint2*>(w + lay.cand);
     t.idx = reinterpret_cast<int32_t*>(w + lay.idx);
@@ -412,6 +417,59 @@ const char* compams_strerror(int status) {
     case COMPAMS_BAD_STATE: return "query or option does not apply to this compressor";
     default: return "unknown status";
   }
+}
+
+size_t compams_wire_capacity(const compams_config* cfg) {
+  if (!basic_valid(cfg)) return 0;
+  if (cfg->compressor == COMPAMS_TOPK) return 3 + 2 * static_cast<size_t>(cfg->k);  // gaps never need 32 bits
+  if (cfg->compressor == COMPAMS_BLOCKSIGN)
+    return 3 + (static_cast<size_t>(cfg->d) + 31) / 32 + static_cast<size_t>(cfg->num_blocks);
+  return 0;
+}
+
+int compams_encode(compams_ctx* ctx, uint32_t* messages, int64_t stride_words, uint32_t* words_out, void* hip_stream) {
+  if (!ctx || !messages || !words_out) return COMPAMS_INVALID_ARG;
+  const compams_config& c = ctx->cfg;
+  if (c.compressor == COMPAMS_NONE || ctx->steps == 0) return COMPAMS_BAD_STATE;
+  if (stride_words < static_cast<int64_t>(compams_wire_capacity(&c))) return COMPAMS_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(messages) % 4 != 0 || reinterpret_cast<uintptr_t>(words_out) % 4 != 0)
+    return COMPAMS_BAD_ALIGNMENT;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
+  hipError_t err;
+  try {
+    err = c.compressor == COMPAMS_TOPK
+              ? wire_encode_topk(ctx->geo, ctx->tk, messages, stride_words, words_out, stream, L)
+              : wire_encode_blocksign(ctx->geo, ctx->bs, messages, stride_words, words_out, stream, L);
+  } catch (...) {
+    return COMPAMS_HIP_ERROR;
+  }
+  return err == hipSuccess && !(L && L->failed) ? COMPAMS_OK : COMPAMS_HIP_ERROR;
+}
+
+int compams_decode(compams_ctx* ctx, const uint32_t* messages, int64_t stride_words, const uint32_t* words,
+                   void* out_a, void* out_b, uint32_t* status_out, void* hip_stream) {
+  if (!ctx || !messages || !out_a || !out_b || !status_out) return COMPAMS_INVALID_ARG;
+  const compams_config& c = ctx->cfg;
+  if (c.compressor == COMPAMS_NONE) return COMPAMS_BAD_STATE;
+  if (stride_words < static_cast<int64_t>(compams_wire_capacity(&c))) return COMPAMS_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(messages) % 4 != 0 || reinterpret_cast<uintptr_t>(out_a) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(out_b) % 4 != 0 || reinterpret_cast<uintptr_t>(status_out) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(words) % 4 != 0)
+    return COMPAMS_BAD_ALIGNMENT;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
+  hipError_t err;
+  try {
+    err = c.compressor == COMPAMS_TOPK
+              ? wire_decode_topk(ctx->geo, ctx->tk, messages, stride_words, words, static_cast<int32_t*>(out_a),
+                                 static_cast<float*>(out_b), status_out, stream, L)
+              : wire_decode_blocksign(ctx->geo, messages, stride_words, words, static_cast<uint32_t*>(out_a),
+                                      static_cast<float*>(out_b), status_out, stream, L);
+  } catch (...) {
+    return COMPAMS_HIP_ERROR;
+  }
+  return err == hipSuccess && !(L && L->failed) ? COMPAMS_OK : COMPAMS_HIP_ERROR;
 }
 
 int compams_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {

@@ -40,6 +40,8 @@ inline uint32_t count_chunks_per_block(uint32_t num_chunks) {
   return 32 * (m ? m : 1);
 }
 
+constexpr int kWireTile = 4096;  // entries per tile when a top-k message is unpacked
+
 // Where a row's selection reads its elements from after the first pass.
 enum : uint32_t {
   kModeCand = 0,   // candidate list written by the first pass (threshold bucket was predicted)
@@ -84,6 +86,8 @@ struct TopkWorkspace {
                         //                  within the chunk's count block
   uint2* blk;           // n * kMaxCountBlocks : the two totals of every count block
   uint32_t* sel_off;    // n * (num_chunks + 1) : where each chunk's slice of the worker's list starts
+  uint32_t* wire_max;   // n : largest coordinate gap of the message being packed
+  uint32_t* wire_tiles; // n * ceil(k / kWireTile) : coordinates before each tile of a message being unpacked
   uint2* desc;          // n * num_chunks : (offset, count) of the chunk's segment in the candidate list
   uint2* cand;          // n * cap_alloc  : (coordinate, fp32 bits)
   int32_t* idx;         // n * k
@@ -136,7 +140,7 @@ struct Geometry {
 enum KernelSlot {
   kSlotPassA = 0, kSlotLevel1, kSlotLevel2, kSlotCount, kSlotTopkFinal,
   kSlotBsPass1, kSlotBsFinal, kSlotBsPass2, kSlotBsAms,
-  kSlotNoneAms, kNumSlots
+  kSlotNoneAms, kSlotWireEncode, kSlotWireDecode, kNumSlots
 };
 
 struct Launcher;  // host-side helper that brackets launches with events (compams_api.hip)
@@ -150,6 +154,16 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
                           float* e, float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L);
 hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, float* theta, float* m, float* v,
                      float* vhat, hipStream_t stream, Launcher* L);
+hipError_t wire_encode_topk(const Geometry& geo, const TopkWorkspace& ws, uint32_t* messages, int64_t stride,
+                            uint32_t* words_out, hipStream_t stream, Launcher* L);
+hipError_t wire_decode_topk(const Geometry& geo, const TopkWorkspace& ws, const uint32_t* messages, int64_t stride,
+                            const uint32_t* words, int32_t* idx_out, float* val_out, uint32_t* status,
+                            hipStream_t stream, Launcher* L);
+hipError_t wire_encode_blocksign(const Geometry& geo, const BlocksignWorkspace& ws, uint32_t* messages, int64_t stride,
+                                 uint32_t* words_out, hipStream_t stream, Launcher* L);
+hipError_t wire_decode_blocksign(const Geometry& geo, const uint32_t* messages, int64_t stride, const uint32_t* words,
+                                 uint32_t* bits_out, float* scales_out, uint32_t* status, hipStream_t stream,
+                                 Launcher* L);
 hipError_t fill_u32(uint32_t* p, size_t count, uint32_t value, hipStream_t stream);
 hipError_t fill_rows_f32(float* p, uint32_t n, int64_t ld, uint32_t d, float value, hipStream_t stream);
 hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);

@@ -43,9 +43,34 @@ def run_full(name, steps, check_every_step=True):
             b = cpu.get(s)
             close(a, b, f"{name} step {t}: {s}")
             assert bits_equal(np.ascontiguousarray(a), b), f"{name} step {t}: {s} is within tolerance but not bit-identical"
+    if comp != B.NONE:
+        check_wire(name, w, comp, gpu, cpu)
     counters = gpu.compams_state("counters").cpu().numpy() if comp == B.TOPK else None
     gpu.close(); cpu.close()
     return counters
+
+
+def check_wire(name, w, comp, gpu, cpu):
+    """The last step's messages, packed on the GPU, against the oracle's packing of its own messages, word for word;
+    then unpacked on the GPU again."""
+    msgs, words = gpu.compams_encode()
+    a, b, status = gpu.compams_decode(msgs, words)
+    torch.cuda.synchronize()
+    m = msgs.cpu().numpy().view(np.uint32)
+    wn = words.cpu().numpy()
+    assert not status.cpu().numpy().any(), f"{name}: decode status"
+    if comp == B.TOPK:
+        idx, val = cpu.get("idx"), cpu.get("val")
+        for i in range(w.n):
+            want = O.wire_encode_topk(idx[i], val[i])
+            assert wn[i] == want.size and np.array_equal(m[i, : wn[i]], want), f"{name}: message of worker {i}"
+        assert np.array_equal(a.cpu().numpy(), idx) and bits_equal(b.cpu().numpy(), val), f"{name}: decoded lists"
+    else:
+        bits, mu = cpu.get("bits"), cpu.get("mu")
+        for i in range(w.n):
+            want = O.wire_encode_blocksign(w.d, bits[i], mu[i])
+            assert wn[i] == want.size and np.array_equal(m[i, : wn[i]], want), f"{name}: message of worker {i}"
+        assert np.array_equal(a.cpu().numpy().view(np.uint32), bits) and bits_equal(b.cpu().numpy(), mu)
 
 
 def test_full_size_resnet18_topk_1_percent():
