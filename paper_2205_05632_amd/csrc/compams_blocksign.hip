@@ -33,18 +33,14 @@ __device__ __forceinline__ Fixed to_fixed(uint32_t bits) {
   const uint32_t key = bits & 0x7fffffffu;
   const uint32_t ex = key >> 23, frac = key & 0x7fffffu;
   Fixed f;
-  if (ex == 255) {
-    f.w = 0; f.lo = 0; f.hi = 0;
-    f.special = frac ? 2u : 1u;
-    return f;
-  }
-  const uint32_t mant = ex ? (frac | 0x800000u) : frac;
+  const bool nonfinite = ex == 255u;
+  const uint32_t mant = nonfinite ? 0u : (ex ? (frac | 0x800000u) : frac);
   const uint32_t sh = ex ? ex - 1 : 0;
   const uint64_t val = static_cast<uint64_t>(mant) << (sh & 31u);
-  f.w = sh >> 5;
+  f.w = nonfinite ? 0u : sh >> 5;
   f.lo = static_cast<uint32_t>(val);
   f.hi = static_cast<uint32_t>(val >> 32);
-  f.special = 0;
+  f.special = nonfinite ? (frac ? 2u : 1u) : 0u;
   return f;
 }
 
@@ -82,15 +78,22 @@ __device__ __forceinline__ void acc_flush(WaveAcc& A, uint64_t* digits /* kLimbs
   A.live = false;
 }
 
+// Branch-free for values whose digits lie in the register window (selects and three additions); the
+// rest (special values, values far from the centre) leave through one wave-uniform branch.
 __device__ __forceinline__ void acc_add(WaveAcc& A, const Fixed& f, bool ok, uint64_t* digits, uint32_t* special) {
-  if (!ok) return;
-  if (f.special) { atomicOr(special, f.special); return; }
-  if ((f.lo | f.hi) == 0) return;
-  if (f.w == A.centre) { A.a1 += f.lo; A.a2 += f.hi; }
-  else if (f.w + 1 == A.centre) { A.a0 += f.lo; A.a1 += f.hi; }
-  else {
-    atomic_add_u64(digits + f.w, f.lo);
-    if (f.hi) atomic_add_u64(digits + f.w + 1, f.hi);
+  const uint32_t rel = f.w + 1u - A.centre;  // 0: low digit one below the centre, 1: at the centre
+  const bool nz = ok && !f.special && (f.lo | f.hi) != 0;
+  const bool in0 = nz && rel == 0u, in1 = nz && rel == 1u;
+  A.a0 += in0 ? f.lo : 0u;
+  A.a1 += in0 ? f.hi : (in1 ? f.lo : 0u);
+  A.a2 += in1 ? f.hi : 0u;
+  const bool rare = ok && (f.special || (nz && rel > 1u));
+  if (ballot64(rare) != 0 && rare) {
+    if (f.special) atomicOr(special, f.special);
+    else {
+      atomic_add_u64(digits + f.w, f.lo);
+      if (f.hi) atomic_add_u64(digits + f.w + 1, f.hi);
+    }
   }
 }
 
@@ -157,6 +160,27 @@ __device__ __forceinline__ void bs_add_direct(uint64_t* dg, uint32_t* special, c
   }
 }
 
+struct BsBatch {
+  float4 g[kBsBatch], e[kBsBatch];
+};
+
+__device__ __forceinline__ void bs_load_batch(BsBatch& B, const float* __restrict__ gr, const float* __restrict__ er,
+                                              uint32_t c, int r0, uint32_t d) {
+  const uint32_t lane = lane_id();
+#pragma unroll
+  for (int u = 0; u < kBsBatch; ++u) {
+    const uint32_t j = c * kChunk + (r0 + u) * 256 + lane * 4;
+    B.g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    B.e[u] = B.g[u];
+    if (j < d) {
+      B.g[u] = load_stream4(gr + j);
+      B.e[u] = load_stream4(er + j);
+    }
+  }
+}
+
+// A wavefront walks chunks c, c + stride, ... in batches of kBsBatch rounds; the loads of the next batch
+// (of the same or of the next chunk) are in flight while the current one is summed.
 __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
                                                    BlocksignWorkspace ws) {
   const uint32_t row = blockIdx.y;
@@ -168,80 +192,97 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const uint32_t stride = gridDim.x * kWaves;
   const uint32_t d = geo.d;
-  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
-    uint32_t b = ws.chunk_block[c];  // wave-uniform: block of the chunk's first coordinate
-    WaveAcc A;
-    A.a0 = A.a1 = A.a2 = 0; A.live = false; A.centre = 0;
-#pragma unroll 1
-    for (int r0 = 0; r0 < kRounds; r0 += kBsBatch) {
-      if (c * kChunk + r0 * 256 >= d) break;  // wave-uniform
-      float4 gv[kBsBatch], ev[kBsBatch];
+  uint32_t c = blockIdx.x * kWaves + wave;
+  if (c >= geo.num_chunks) return;
+  int r0 = 0;
+  BsBatch cur, nxt;
+  bs_load_batch(cur, gr, er, c, 0, d);
+  // b: block of the round being summed; blk_end = off[b + 1] is kept in a register (the table is only read
+  // when the walk enters another block); b_next: block of the next chunk's first coordinate, requested
+  // together with that chunk's first batch.
+  uint32_t b = ws.chunk_block[c], b_next = b;
+  uint32_t blk_end = off[b + 1];
+  WaveAcc A;
+  A.a0 = A.a1 = A.a2 = 0; A.live = false; A.centre = 0;
+  for (;;) {
+    // where the walk goes next (wave-uniform)
+    uint32_t cn = c;
+    int rn = r0 + kBsBatch;
+    if (rn >= kRounds || c * kChunk + rn * 256 >= d) { cn = c + stride; rn = 0; }
+    const bool more = cn < geo.num_chunks;
+    if (more) {
+      bs_load_batch(nxt, gr, er, cn, rn, d);
+      if (rn == 0) b_next = ws.chunk_block[cn];
+    }
 #pragma unroll
-      for (int u = 0; u < kBsBatch; ++u) {
-        const uint32_t j = c * kChunk + (r0 + u) * 256 + lane * 4;
-        gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        ev[u] = gv[u];
-        if (j < d) {
-          gv[u] = load_stream4(gr + j);
-          ev[u] = load_stream4(er + j);
-        }
+    for (int u = 0; u < kBsBatch; ++u) {
+      const uint32_t j0 = c * kChunk + (r0 + u) * 256;  // wave-uniform
+      if (j0 >= d) break;
+      const uint32_t j = j0 + lane * 4;
+      const bool in = j < d;
+      float4 x = make_float4(cur.e[u].x + cur.g[u].x, cur.e[u].y + cur.g[u].y, cur.e[u].z + cur.g[u].z,
+                             cur.e[u].w + cur.g[u].w);
+      const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
+      if (!ok[1]) x.y = cur.e[u].y;
+      if (!ok[2]) x.z = cur.e[u].z;
+      if (!ok[3]) x.w = cur.e[u].w;
+      if (in) store_stream4(er + j, x);
+      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
+                                __float_as_uint(x.w)};
+      // leave blocks that end at or before this round
+      while (blk_end <= j0) {
+        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+        ++b;
+        blk_end = off[b + 1];
       }
-#pragma unroll
-      for (int u = 0; u < kBsBatch; ++u) {
-        const uint32_t j0 = c * kChunk + (r0 + u) * 256;  // wave-uniform
-        if (j0 >= d) break;
-        const uint32_t j = j0 + lane * 4;
-        const bool in = j < d;
-        float4 x = make_float4(ev[u].x + gv[u].x, ev[u].y + gv[u].y, ev[u].z + gv[u].z, ev[u].w + gv[u].w);
-        const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
-        if (!ok[1]) x.y = ev[u].y;
-        if (!ok[2]) x.z = ev[u].z;
-        if (!ok[3]) x.w = ev[u].w;
-        if (in) store_stream4(er + j, x);
-        const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
-                                  __float_as_uint(x.w)};
-        // leave blocks that end at or before this round
-        while (off[b + 1] <= j0) {
-          acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
-          ++b;
-        }
-        const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
-        if (off[b + 1] >= j_end) {
-          // the whole round lies in block b
-          if (!A.live) {
-            // centre the register digits on the largest magnitude of this round
-            uint32_t kmax = 0;
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-              const uint32_t key = bits[s] & 0x7fffffffu;
-              if (ok[s] && key < 0x7f800000u && key > kmax) kmax = key;
-            }
-#pragma unroll
-            for (int s = 32; s >= 1; s >>= 1) {
-              const uint32_t o = __shfl_xor(kmax, s, 64);
-              kmax = o > kmax ? o : kmax;
-            }
-            const uint32_t ex = kmax >> 23;
-            A.centre = (ex ? ex - 1 : 0) >> 5;
-            A.live = true;
-          }
-#pragma unroll
-          for (int s = 0; s < 4; ++s)
-            acc_add(A, to_fixed(bits[s]), ok[s], accr + static_cast<size_t>(b) * kLimbs, specr + b);
-        } else {
-          // the round straddles block boundaries: every coordinate goes to its own block's digits
-          acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+      const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
+      if (blk_end >= j_end) {
+        // the whole round lies in block b
+        if (!A.live) {
+          // centre the register digits on the largest magnitude of this round
+          uint32_t kmax = 0;
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
-            if (!ok[s]) continue;
-            const uint32_t bb = block_of(off, b, j + s);
-            bs_add_direct(accr + static_cast<size_t>(bb) * kLimbs, specr + bb, to_fixed(bits[s]));
+            const uint32_t key = bits[s] & 0x7fffffffu;
+            if (ok[s] && key < 0x7f800000u && key > kmax) kmax = key;
           }
+#pragma unroll
+          for (int s = 32; s >= 1; s >>= 1) {
+            const uint32_t o = __shfl_xor(kmax, s, 64);
+            kmax = o > kmax ? o : kmax;
+          }
+          const uint32_t ex = kmax >> 23;
+          A.centre = (ex ? ex - 1 : 0) >> 5;
+          A.live = true;
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          acc_add(A, to_fixed(bits[s]), ok[s], accr + static_cast<size_t>(b) * kLimbs, specr + b);
+      } else {
+        // the round straddles block boundaries: every coordinate goes to its own block's digits
+        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          if (!ok[s]) continue;
+          const uint32_t bb = block_of(off, b, j + s);
+          bs_add_direct(accr + static_cast<size_t>(bb) * kLimbs, specr + bb, to_fixed(bits[s]));
         }
       }
     }
-    // b is wave-uniform; flush what is left for the block the chunk ended in
-    acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+    // b is wave-uniform.  The register digits stay live across the wavefront's chunks as long as these lie in
+    // one block; they are flushed when the walk moves to another block and at the end.
+    if (!more) {
+      acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+      break;
+    }
+    if (rn == 0 && b_next != b) {
+      acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+      b = b_next;
+      blk_end = off[b + 1];
+    }
+    cur = nxt;
+    c = cn;
+    r0 = rn;
   }
 }
 
@@ -656,7 +697,7 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
   const dim3 grid_rows(G, geo.n), grid_2(G * 2, geo.n), wg(kWG);
   const int fused = ws.uniform4096 ? 1 : 0;
   if (fused) launch(L, kSlotBsPass1, k_bs_fused4096, grid_2, wg, stream, g, e, geo, ws);
-  else launch(L, kSlotBsPass1, k_bs_pass1, grid_2, wg, stream, g, e, geo, ws);
+  else launch(L, kSlotBsPass1, k_bs_pass1, dim3(G * 4, geo.n), wg, stream, g, e, geo, ws);
   COMPAMS_CHECK_LAUNCH();
   const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
   launch(L, kSlotBsFinal, k_bs_finalize, dim3(static_cast<uint32_t>((total + kWG - 1) / kWG)), wg, stream, geo, ws,
