@@ -130,7 +130,8 @@ struct compams_ctx {
   BlocksignWorkspace bs;
   int device;
   int64_t steps;
-  bool clear_pending;      // top-k: e still holds x at the coordinates selected by the last step
+  bool clear_pending;      // the last step's residual update is still to be applied: top-k: e holds x at the
+                           // selected coordinates; block-sign (general layouts): e holds x everywhere
   hipStream_t last_stream; // stream of the last step
   bool profiling;
   Launcher launcher;
@@ -139,8 +140,11 @@ struct compams_ctx {
 // Top-k leaves the zeroing of the residual at the selected coordinates to the next step's first pass.
 // Before anybody else looks at e, the zeros are written for real (on the stream of the last step).
 static hipError_t settle_residuals(compams_ctx* ctx) {
-  if (ctx->cfg.compressor != COMPAMS_TOPK || !ctx->clear_pending) return hipSuccess;
-  const hipError_t err = topk_apply_clear(ctx->geo, ctx->tk, ctx->cfg.e, ctx->last_stream);
+  if (!ctx->clear_pending) return hipSuccess;
+  hipError_t err = hipSuccess;
+  if (ctx->cfg.compressor == COMPAMS_TOPK) err = topk_apply_clear(ctx->geo, ctx->tk, ctx->cfg.e, ctx->last_stream);
+  else if (ctx->cfg.compressor == COMPAMS_BLOCKSIGN)
+    err = blocksign_apply_residual(ctx->geo, ctx->bs, ctx->cfg.e, ctx->last_stream);
   if (err == hipSuccess) ctx->clear_pending = false;
   return err;
 }
@@ -285,7 +289,8 @@ int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream) {
                       ctx->clear_pending, stream, L);
       ctx->clear_pending = true;
     } else if (c.compressor == COMPAMS_BLOCKSIGN) {
-      err = blocksign_step(ctx->geo, ctx->bs, ap, g, c.e, c.theta, c.m, c.v, c.vhat, stream, L);
+      err = blocksign_step(ctx->geo, ctx->bs, ap, g, c.e, c.theta, c.m, c.v, c.vhat, ctx->clear_pending, stream, L);
+      ctx->clear_pending = ctx->bs.uniform4096 == 0;  // the single-pass layout writes its residuals itself
     } else {
       err = none_step(ctx->geo, ap, g, c.theta, c.m, c.v, c.vhat, stream, L);
     }

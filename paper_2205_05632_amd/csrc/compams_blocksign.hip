@@ -181,12 +181,22 @@ __device__ __forceinline__ void bs_load_batch(BsBatch& B, const float* __restric
 
 // A wavefront walks chunks c, c + stride, ... in batches of kBsBatch rounds; the loads of the next batch
 // (of the same or of the next chunk) are in flight while the current one is summed.
+//
+// PEND: the residual update of the previous step has not been applied yet: e still holds that step's x,
+// and ws.scales that step's block means.  The pass then forms e = x_prev - sign(x_prev) * mu_prev on the
+// fly (the very expression, in fp32, that the stand-alone residual kernel applies) before it adds g.  In
+// this way a step with layer-sized blocks reads g and e once and writes e once; the mean of a block is
+// needed before its residual can be written, but not before the *next* step reads it.
+// The pass also writes the sign words of x (eight lanes, 32 coordinates, share a word).
+template <bool PEND>
 __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
                                                    BlocksignWorkspace ws) {
   const uint32_t row = blockIdx.y;
   const float* gr = g + static_cast<int64_t>(row) * geo.ld;
   float* er = e + static_cast<int64_t>(row) * geo.ld;
   const uint32_t* __restrict__ off = ws.offsets;
+  const float* mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;  // previous step's means (PEND)
+  uint32_t* bitr = ws.bits + static_cast<size_t>(row) * geo.words;
   uint64_t* accr = ws.acc + static_cast<size_t>(row) * geo.num_blocks * kLimbs;
   uint32_t* specr = ws.special + static_cast<size_t>(row) * geo.num_blocks;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
@@ -197,11 +207,12 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
   int r0 = 0;
   BsBatch cur, nxt;
   bs_load_batch(cur, gr, er, c, 0, d);
-  // b: block of the round being summed; blk_end = off[b + 1] is kept in a register (the table is only read
-  // when the walk enters another block); b_next: block of the next chunk's first coordinate, requested
-  // together with that chunk's first batch.
+  // b: block of the round being summed; blk_end = off[b + 1] and mu_b = the block's previous mean are kept in
+  // registers (the tables are only read when the walk enters another block); b_next: block of the next
+  // chunk's first coordinate, requested together with that chunk's first batch.
   uint32_t b = ws.chunk_block[c], b_next = b;
   uint32_t blk_end = off[b + 1];
+  float mu_b = PEND ? mur[b] : 0.0f;
   WaveAcc A;
   A.a0 = A.a1 = A.a2 = 0; A.live = false; A.centre = 0;
   for (;;) {
@@ -220,24 +231,47 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
       if (j0 >= d) break;
       const uint32_t j = j0 + lane * 4;
       const bool in = j < d;
-      float4 x = make_float4(cur.e[u].x + cur.g[u].x, cur.e[u].y + cur.g[u].y, cur.e[u].z + cur.g[u].z,
-                             cur.e[u].w + cur.g[u].w);
       const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
-      if (!ok[1]) x.y = cur.e[u].y;
-      if (!ok[2]) x.z = cur.e[u].z;
-      if (!ok[3]) x.w = cur.e[u].w;
-      if (in) store_stream4(er + j, x);
-      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z),
-                                __float_as_uint(x.w)};
       // leave blocks that end at or before this round
       while (blk_end <= j0) {
         acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
         ++b;
         blk_end = off[b + 1];
+        if (PEND) mu_b = mur[b];
       }
       const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
-      if (blk_end >= j_end) {
-        // the whole round lies in block b
+      const bool whole = blk_end >= j_end;  // the whole round lies in block b (wave-uniform)
+      uint32_t bb[4] = {b, b, b, b};
+      if (!whole) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) bb[s] = ok[s] ? block_of(off, b, j + s) : b;
+      }
+      float ev[4] = {cur.e[u].x, cur.e[u].y, cur.e[u].z, cur.e[u].w};
+      const float gv[4] = {cur.g[u].x, cur.g[u].y, cur.g[u].z, cur.g[u].w};
+      if (PEND) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const float mu = whole ? mu_b : (ok[s] ? mur[bb[s]] : 0.0f);
+          if (ok[s]) ev[s] = ev[s] - (ev[s] < 0.0f ? -mu : mu);
+        }
+      }
+      float xv[4];
+      uint32_t nib = 0;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        xv[s] = ok[s] ? ev[s] + gv[s] : ev[s];  // columns at and beyond d keep their contents
+        nib |= (ok[s] && xv[s] < 0.0f ? 1u : 0u) << s;
+      }
+      if (in) store_stream4(er + j, make_float4(xv[0], xv[1], xv[2], xv[3]));
+      uint32_t word = nib << ((lane & 7u) * 4u);
+      word |= __shfl_xor(word, 1, 64);
+      word |= __shfl_xor(word, 2, 64);
+      word |= __shfl_xor(word, 4, 64);
+      const uint32_t widx = (j0 >> 5) + (lane >> 3);
+      if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
+      const uint32_t bits[4] = {__float_as_uint(xv[0]), __float_as_uint(xv[1]), __float_as_uint(xv[2]),
+                                __float_as_uint(xv[3])};
+      if (whole) {
         if (!A.live) {
           // centre the register digits on the largest magnitude of this round
           uint32_t kmax = 0;
@@ -264,8 +298,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
           if (!ok[s]) continue;
-          const uint32_t bb = block_of(off, b, j + s);
-          bs_add_direct(accr + static_cast<size_t>(bb) * kLimbs, specr + bb, to_fixed(bits[s]));
+          bs_add_direct(accr + static_cast<size_t>(bb[s]) * kLimbs, specr + bb[s], to_fixed(bits[s]));
         }
       }
     }
@@ -279,6 +312,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
       acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
       b = b_next;
       blk_end = off[b + 1];
+      if (PEND) mu_b = mur[b];
     }
     cur = nxt;
     c = cn;
@@ -691,24 +725,37 @@ __global__ __launch_bounds__(kWG) void k_copy16(uint4* __restrict__ dst, const u
   } while (0)
 
 hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, const float* g,
-                          float* e, float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
+                          float* e, float* theta, float* m, float* v, float* vhat, bool residual_pending,
+                          hipStream_t stream, Launcher* L) {
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
   // these passes hide their latencies through occupancy: many workgroups per row
-  const dim3 grid_rows(G, geo.n), grid_2(G * 2, geo.n), wg(kWG);
+  const dim3 grid_rows(G, geo.n), grid_2(G * 2, geo.n), grid_4(G * 4, geo.n), wg(kWG);
   const int fused = ws.uniform4096 ? 1 : 0;
   if (fused) launch(L, kSlotBsPass1, k_bs_fused4096, grid_2, wg, stream, g, e, geo, ws);
-  else launch(L, kSlotBsPass1, k_bs_pass1, dim3(G * 4, geo.n), wg, stream, g, e, geo, ws);
+  else if (residual_pending) launch(L, kSlotBsPass1, k_bs_pass1<true>, grid_4, wg, stream, g, e, geo, ws);
+  else launch(L, kSlotBsPass1, k_bs_pass1<false>, grid_4, wg, stream, g, e, geo, ws);
   COMPAMS_CHECK_LAUNCH();
   const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
   launch(L, kSlotBsFinal, k_bs_finalize, dim3(static_cast<uint32_t>((total + kWG - 1) / kWG)), wg, stream, geo, ws,
          fused);
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotBsPass2, k_bs_pass2, fused ? grid_rows : grid_2, wg, stream, e, geo, ws, fused);
-  COMPAMS_CHECK_LAUNCH();
+  // General layouts: the residual e = x - sign(x) * mu is left to the next step's first pass (or to
+  // blocksign_apply_residual when e is asked for).  Block = chunk layout: only the blocks that the single pass
+  // could not finish are completed here.
+  if (fused) {
+    launch(L, kSlotBsPass2, k_bs_pass2, grid_rows, wg, stream, e, geo, ws, 1);
+    COMPAMS_CHECK_LAUNCH();
+  }
   launch(L, kSlotBsAms, k_bs_amsgrad, dim3((geo.num_chunks + kWaves - 1) / kWaves), wg, stream, theta, m, v, vhat, geo,
          ws, ap);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
+}
+
+hipError_t blocksign_apply_residual(const Geometry& geo, const BlocksignWorkspace& ws, float* e, hipStream_t stream) {
+  const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
+  hipLaunchKernelGGL(k_bs_pass2, dim3(G * 2, geo.n), dim3(kWG), 0, stream, e, geo, ws, 0);
+  return hipGetLastError();
 }
 
 hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, float* theta, float* m, float* v,

@@ -151,7 +151,9 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
                      bool first_pass_may_predict, bool clear_pending, hipStream_t stream, Launcher* L);
 hipError_t topk_apply_clear(const Geometry& geo, const TopkWorkspace& ws, float* e, hipStream_t stream);
 hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, const float* g,
-                          float* e, float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L);
+                          float* e, float* theta, float* m, float* v, float* vhat, bool residual_pending,
+                          hipStream_t stream, Launcher* L);
+hipError_t blocksign_apply_residual(const Geometry& geo, const BlocksignWorkspace& ws, float* e, hipStream_t stream);
 hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, float* theta, float* m, float* v,
                      float* vhat, hipStream_t stream, Launcher* L);
 hipError_t wire_encode_topk(const Geometry& geo, const TopkWorkspace& ws, uint32_t* messages, int64_t stride,

@@ -240,6 +240,57 @@ def test_blocksign_block_layouts(n, d, offsets):
     p.close()
 
 
+@pytest.mark.parametrize("n,d,offsets", [
+    (3, 5000, [0, 1, 11, 500, 2548, 5000]),
+    (2, 100003, "ragged40"),
+    (2, 9000, "unit"),
+    (2, 50000, "one"),
+    (3, 33000, "ragged2000"),
+    (2, 4101, [0, 4094, 4099, 4101]),
+])
+def test_blocksign_deferred_residual(n, d, offsets):
+    """For layouts other than block = chunk the residual e = x - sign(x) mu of a step is applied by the next
+    step's first pass (or when e is asked for).  Sign words, scales and parameters are compared after every
+    step, the residuals after the 4th step (which settles them: the 5th step then takes the other variant of
+    the first pass) and at the end."""
+    rng = np.random.default_rng(d + 1)
+    if offsets == "ragged40":
+        off = ragged_offsets(d, rng, 40)
+    elif offsets == "ragged2000":
+        off = ragged_offsets(d, rng, 2000)
+    elif offsets == "unit":
+        off = np.arange(d + 1, dtype=np.int64)
+    elif offsets == "one":
+        off = np.array([0, d], dtype=np.int64)
+    else:
+        off = np.array(offsets, dtype=np.int64)
+    p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, B.BLOCKSIGN, block_offsets=off)
+    steps = 8
+    for t in range(steps):
+        g = (rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-3, 1, (1, d))).astype(np.float32)
+        g[:, ::11] = 0.0
+        p.step(g, 1e-3, label=f"deferred block-sign {offsets} step {t}", with_e=(t == 3 or t == steps - 1))
+    assert all(p.exact.values()), p.exact
+    assert np.array_equal(p.gpu.e[:, :d].cpu().numpy().view(np.uint32), p.cpu.get("e").view(np.uint32))
+    p.close()
+
+
+def test_blocksign_deferred_residual_with_a_block_that_is_not_finite():
+    """An infinite entry makes its block's mean infinite; the residual of that block (x - sign(x) * inf) is then
+    -inf, +inf or NaN, and the deferred form must produce the same pattern as the oracle's immediate one."""
+    n, d = 2, 30000
+    rng = np.random.default_rng(4)
+    off = np.array([0, 100, 9000, 9001, 20000, d], dtype=np.int64)
+    p = Pair(n, d, np.zeros(d, np.float32), B.BLOCKSIGN, block_offsets=off)
+    for t in range(4):
+        g = rng.standard_normal((n, d)).astype(np.float32)
+        if t == 1:
+            g[0, 12345] = np.inf
+            g[1, 50] = -np.inf
+        p.step(g, 1e-3, label=f"non-finite block step {t}", with_e=(t == 3))
+    p.close()
+
+
 def test_blocksign_wide_dynamic_range_is_summed_exactly():
     """Magnitudes from denormal to 1e30 in one block: any accumulation that is not exact gets the scale wrong."""
     n, d = 2, 40000
