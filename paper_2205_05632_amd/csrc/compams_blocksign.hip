@@ -8,11 +8,15 @@
 // split over lanes, wavefronts and workgroups: every |x| is a 24-bit integer times a power of two;
 // it is added into a fixed-point number whose 32-bit digits are carried in 64-bit words (room for
 // 2^32 additions before a digit could overflow).  Integer addition commutes, so integer atomics leave
-// the result unique.  The sum is rounded once to double, divided by d_B in double and rounded to fp32.
+// the result unique.  Inside a lane the additions run in fp64 over windows of exponents narrow enough that
+// no addition rounds.  The sum is rounded once to double, divided by d_B in double and rounded to fp32.
 //
-// Pass 1 forms x (stored in place of e) and the sums, a small kernel turns sums into scales, pass 2
-// re-reads x and writes sign bits and residuals, and the server kernel adds the n workers' +-mu in
-// worker order before the AMSGrad update.
+// Pass 1 forms x (stored in place of e), its sign words and the sums, a small kernel turns sums into
+// scales, and the server kernel adds the n workers' +-mu in worker order before the AMSGrad update.  The
+// residual e = x - sign(x) * mu is applied by the next step's pass 1 as it reads e (or by the stand-alone
+// residual kernel when e is asked for).  Layouts with block = 4096-coordinate chunk do all of it in one pass.
+
+#include <type_traits>
 
 #include "compams_device.h"
 #include "compams_internal.h"
@@ -58,47 +62,118 @@ __device__ __forceinline__ void atomic_add_u64(uint64_t* p, uint64_t v) {
   atomicAdd(reinterpret_cast<unsigned long long*>(p), static_cast<unsigned long long>(v));
 }
 
-// Three digits kept in registers per lane around a wave-uniform centre digit; everything else goes
-// straight to the global digits with atomics (rare: values more than 2^32 away from the centre).
+// Register accumulators of a lane: two fp64 sums, one per window of kWinSpan binary exponents, placed by the
+// wavefront (wave-uniform) where the magnitudes are expected.  Every |x| in a window is an integer below
+// 2^(24 + kWinSpan - 1) = 2^40 times the window's quantum 2^(lowest exponent - 150), so the fp64 sum of up to
+// kWinAdds = 2^13 of them is below 2^53 quanta: every addition is exact and their order does not matter.  At a
+// flush the sums become integers again, are added over the wavefront and go to the global digits.  Entries
+// outside both windows (rare) and non-finite ones go straight to the global digits and flags.
+// "Exponent" here is the effective one: max(biased exponent, 1), so that subnormals share the quantum of
+// the smallest normal numbers; |x| = mantissa * 2^(exponent - 150).
+constexpr uint32_t kWinSpan = 17;
+constexpr uint32_t kWinAdds = 8192;
+
 struct WaveAcc {
-  uint32_t centre;  // digit index of a1
-  uint64_t a0, a1, a2;
+  double hi, lo;    // sums of the upper and the lower window
+  uint32_t eh;      // upper window: exponents eh .. eh + kWinSpan - 1
+  uint32_t el;      // lower window: exponents el .. eh - 1 (empty when el == eh)
+  uint32_t adds;    // additions per lane since the last flush (wave-uniform)
   bool live;
 };
 
-__device__ __forceinline__ void acc_flush(WaveAcc& A, uint64_t* digits /* kLimbs of the (row, block) */) {
-  if (!A.live) return;
-  const uint64_t s0 = wave_sum_u64(A.a0), s1 = wave_sum_u64(A.a1), s2 = wave_sum_u64(A.a2);
-  if (lane_id() == 0) {
-    if (s0) atomic_add_u64(digits + A.centre - 1, s0);  // s0 != 0 implies centre >= 1
-    if (s1) atomic_add_u64(digits + A.centre, s1);
-    if (s2) atomic_add_u64(digits + A.centre + 1, s2);
-  }
-  A.a0 = A.a1 = A.a2 = 0;
-  A.live = false;
+__device__ __forceinline__ void acc_reset(WaveAcc& A) {
+  A.hi = 0.0; A.lo = 0.0; A.eh = 1; A.el = 1; A.adds = 0; A.live = false;
 }
 
-// Branch-free for values whose digits lie in the register window (selects and three additions); the
-// rest (special values, values far from the centre) leave through one wave-uniform branch.
-__device__ __forceinline__ void acc_add(WaveAcc& A, const Fixed& f, bool ok, uint64_t* digits, uint32_t* special) {
-  const uint32_t rel = f.w + 1u - A.centre;  // 0: low digit one below the centre, 1: at the centre
-  const bool nz = ok && !f.special && (f.lo | f.hi) != 0;
-  const bool in0 = nz && rel == 0u, in1 = nz && rel == 1u;
-  A.a0 += in0 ? f.lo : 0u;
-  A.a1 += in0 ? f.hi : (in1 ? f.lo : 0u);
-  A.a2 += in1 ? f.hi : 0u;
-  const bool rare = ok && (f.special || (nz && rel > 1u));
-  if (ballot64(rare) != 0 && rare) {
-    if (f.special) atomicOr(special, f.special);
-    else {
-      atomic_add_u64(digits + f.w, f.lo);
-      if (f.hi) atomic_add_u64(digits + f.w + 1, f.hi);
-    }
+// Places the windows so that the upper one ends `headroom` exponents above the largest finite magnitude key
+// kmax_key seen so far (wave-uniform).
+__device__ __forceinline__ void acc_place(WaveAcc& A, uint32_t kmax_key, uint32_t headroom) {
+  uint32_t top = kmax_key >> 23;
+  top = top ? top : 1u;
+  top = top + headroom > 254u ? 254u : top + headroom;
+  A.eh = top >= kWinSpan ? top - (kWinSpan - 1u) : 1u;
+  A.el = A.eh > kWinSpan ? A.eh - kWinSpan : 1u;
+  A.live = true;
+}
+
+// One window's sum as an integer number of quanta 2^(e_low - 150), added over the wavefront and then, by
+// lane 0, into the digits: bit position e_low - 1 above 2^-149, i.e. digit (e_low - 1) / 32 and up.
+__device__ __forceinline__ void window_to_digits(double sum, uint32_t e_low, uint64_t* digits) {
+  const uint64_t mine = static_cast<uint64_t>(ldexp(sum, 150 - static_cast<int>(e_low)));  // exact, below 2^53
+  const uint64_t all = wave_sum_u64(mine);                                                 // below 2^59
+  if (lane_id() == 0 && all) {
+    const uint32_t sh = e_low - 1u, w = sh >> 5, s = sh & 31u;
+    const uint64_t low = all << s, high = s ? all >> (64u - s) : 0ull;
+    const uint64_t d0 = low & 0xffffffffull, d1 = low >> 32;
+    if (d0) atomic_add_u64(digits + w, d0);
+    if (d1) atomic_add_u64(digits + w + 1, d1);
+    if (high) atomic_add_u64(digits + w + 2, high);  // w <= 7: still inside the kLimbs digits
+  }
+}
+
+// Out of line: flushes are rare (a wavefront leaves a block, or a window has taken kWinAdds additions), and the
+// streaming loops stay small enough for the instruction cache.
+__device__ __noinline__ void flush_windows(double hi, double lo, uint32_t eh, uint32_t el, uint64_t* digits) {
+  window_to_digits(hi, eh, digits);
+  if (el != eh) window_to_digits(lo, el, digits);
+}
+
+__device__ __forceinline__ void acc_flush(WaveAcc& A, uint64_t* digits /* kLimbs of the (row, block) */) {
+  if (!A.live) return;
+  flush_windows(A.hi, A.lo, A.eh, A.el, digits);
+  acc_reset(A);
+}
+
+// One entry straight into the global digits (or the flags for non-finite values).  Out of line: rare.
+__device__ __noinline__ void add_direct(uint32_t bits, uint64_t* digits, uint32_t* special) {
+  const Fixed f = to_fixed(bits);
+  if (f.special) atomicOr(special, f.special);
+  else {
+    if (f.lo) atomic_add_u64(digits + f.w, f.lo);
+    if (f.hi) atomic_add_u64(digits + f.w + 1, f.hi);
+  }
+}
+
+// Which window an entry with magnitude key `key` belongs to.
+struct WinClass {
+  bool in_hi, in_lo, finite;
+};
+__device__ __forceinline__ WinClass classify(const WaveAcc& A, uint32_t key) {
+  const uint32_t ex = key >> 23;
+  const uint32_t ee = ex ? ex : 1u;
+  WinClass c;
+  c.finite = ex != 255u;
+  c.in_hi = c.finite && ee - A.eh < kWinSpan;            // unsigned: false below the window
+  c.in_lo = c.finite && ee - A.el < A.eh - A.el;         // el <= ee < eh
+  return c;
+}
+
+// Adds the four entries of a lane's quad.  Branch-free for entries inside the windows; everything else
+// leaves through one wave-uniform branch.
+__device__ __forceinline__ void acc_add4(WaveAcc& A, const uint32_t bits[4], const bool ok[4], uint64_t* digits,
+                                         uint32_t* special) {
+  bool rare[4];
+  bool any = false;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const uint32_t key = bits[s] & 0x7fffffffu;
+    const WinClass c = classify(A, key);
+    const double v = static_cast<double>(__uint_as_float(key));  // |x|, exactly
+    A.hi += (ok[s] && c.in_hi) ? v : 0.0;
+    A.lo += (ok[s] && c.in_lo) ? v : 0.0;
+    rare[s] = ok[s] && (!c.finite || (key != 0u && !c.in_hi && !c.in_lo));
+    any |= rare[s];
+  }
+  A.adds += 4;
+  if (ballot64(any) != 0) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (rare[s]) add_direct(bits[s], digits, special);
   }
 }
 
 // Largest b with off[b] <= j, starting the walk at hint (off[hint] <= j must hold).
-__device__ __forceinline__ uint32_t block_of(const uint32_t* __restrict__ off, uint32_t hint, uint32_t j) {
+__device__ __noinline__ uint32_t block_of(const uint32_t* __restrict__ off, uint32_t hint, uint32_t j) {
   uint32_t b = hint;
   while (off[b + 1] <= j) ++b;
   return b;
@@ -151,14 +226,6 @@ __device__ __forceinline__ void digits3_to_192(uint64_t s0, uint64_t s1, uint64_
 // batch of rounds ahead.
 // ---------------------------------------------------------------------------------------------
 constexpr int kBsBatch = 4;
-
-__device__ __forceinline__ void bs_add_direct(uint64_t* dg, uint32_t* special, const Fixed& f) {
-  if (f.special) atomicOr(special, f.special);
-  else {
-    if (f.lo) atomic_add_u64(dg + f.w, f.lo);
-    if (f.hi) atomic_add_u64(dg + f.w + 1, f.hi);
-  }
-}
 
 struct BsBatch {
   float4 g[kBsBatch], e[kBsBatch];
@@ -214,7 +281,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
   uint32_t blk_end = off[b + 1];
   float mu_b = PEND ? mur[b] : 0.0f;
   WaveAcc A;
-  A.a0 = A.a1 = A.a2 = 0; A.live = false; A.centre = 0;
+  acc_reset(A);
   for (;;) {
     // where the walk goes next (wave-uniform)
     uint32_t cn = c;
@@ -225,13 +292,17 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
       bs_load_batch(nxt, gr, er, cn, rn, d);
       if (rn == 0) b_next = ws.chunk_block[cn];
     }
+    // One batch of rounds.  FULL: the chunk lies entirely below d (every chunk of a row but the last): no
+    // per-coordinate bounds predicates are needed.
+    auto batch = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
     for (int u = 0; u < kBsBatch; ++u) {
       const uint32_t j0 = c * kChunk + (r0 + u) * 256;  // wave-uniform
-      if (j0 >= d) break;
+      if (!FULL && j0 >= d) break;
       const uint32_t j = j0 + lane * 4;
-      const bool in = j < d;
-      const bool ok[4] = {in, j + 1 < d, j + 2 < d, j + 3 < d};
+      const bool in = FULL || j < d;
+      const bool ok[4] = {in, FULL || j + 1 < d, FULL || j + 2 < d, FULL || j + 3 < d};
       // leave blocks that end at or before this round
       while (blk_end <= j0) {
         acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
@@ -239,7 +310,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
         blk_end = off[b + 1];
         if (PEND) mu_b = mur[b];
       }
-      const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
+      const uint32_t j_end = (FULL || j0 + 256 < d) ? j0 + 256 : d;
       const bool whole = blk_end >= j_end;  // the whole round lies in block b (wave-uniform)
       uint32_t bb[4] = {b, b, b, b};
       if (!whole) {
@@ -263,17 +334,15 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
         nib |= (ok[s] && xv[s] < 0.0f ? 1u : 0u) << s;
       }
       if (in) store_stream4(er + j, make_float4(xv[0], xv[1], xv[2], xv[3]));
-      uint32_t word = nib << ((lane & 7u) * 4u);
-      word |= __shfl_xor(word, 1, 64);
-      word |= __shfl_xor(word, 2, 64);
-      word |= __shfl_xor(word, 4, 64);
+      const uint32_t word = or_over_8_lanes(nib << ((lane & 7u) * 4u));
       const uint32_t widx = (j0 >> 5) + (lane >> 3);
-      if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
+      if ((lane & 7u) == 0 && (FULL || widx < geo.words)) bitr[widx] = word;
       const uint32_t bits[4] = {__float_as_uint(xv[0]), __float_as_uint(xv[1]), __float_as_uint(xv[2]),
                                 __float_as_uint(xv[3])};
       if (whole) {
+        if (A.adds + 4 > kWinAdds) acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
         if (!A.live) {
-          // centre the register digits on the largest magnitude of this round
+          // place the windows by the largest magnitude of this round, with room for entries 4 times larger
           uint32_t kmax = 0;
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
@@ -285,23 +354,22 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
             const uint32_t o = __shfl_xor(kmax, s, 64);
             kmax = o > kmax ? o : kmax;
           }
-          const uint32_t ex = kmax >> 23;
-          A.centre = (ex ? ex - 1 : 0) >> 5;
-          A.live = true;
+          acc_place(A, kmax, 2);
         }
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-          acc_add(A, to_fixed(bits[s]), ok[s], accr + static_cast<size_t>(b) * kLimbs, specr + b);
+        acc_add4(A, bits, ok, accr + static_cast<size_t>(b) * kLimbs, specr + b);
       } else {
         // the round straddles block boundaries: every coordinate goes to its own block's digits
         acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
           if (!ok[s]) continue;
-          bs_add_direct(accr + static_cast<size_t>(bb[s]) * kLimbs, specr + bb[s], to_fixed(bits[s]));
+          add_direct(bits[s], accr + static_cast<size_t>(bb[s]) * kLimbs, specr + bb[s]);
         }
       }
     }
+    };
+    if ((c + 1) * static_cast<uint64_t>(kChunk) <= d) batch(std::true_type{});
+    else batch(std::false_type{});
     // b is wave-uniform.  The register digits stay live across the wavefront's chunks as long as these lie in
     // one block; they are flushed when the walk moves to another block and at the end.
     if (!more) {
@@ -434,10 +502,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
           xv[s] = xv[s] - (neg ? -mu : mu);
         }
         store_valid4(er, j, d, xv);
-        uint32_t word = nib << ((lane & 7u) * 4u);
-        word |= __shfl_xor(word, 1, 64);
-        word |= __shfl_xor(word, 2, 64);
-        word |= __shfl_xor(word, 4, 64);
+        const uint32_t word = or_over_8_lanes(nib << ((lane & 7u) * 4u));
         const uint32_t widx = (j0 >> 5) + (lane >> 3);
         if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
       }
@@ -450,7 +515,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         const float xv[4] = {x[r].x, x[r].y, x[r].z, x[r].w};
 #pragma unroll
         for (int s = 0; s < 4; ++s)
-          if (j + s < d) bs_add_direct(dg, specr + c, to_fixed(__float_as_uint(xv[s])));
+          if (j + s < d) add_direct(__float_as_uint(xv[s]), dg, specr + c);
         store_valid4(er, j, d, xv);
       }
     }
@@ -558,10 +623,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometr
           if (ok[s]) xv[s] = xv[s] - (neg ? -mu[s] : mu[s]);
         }
         if (in) store_stream4(er + j, make_float4(xv[0], xv[1], xv[2], xv[3]));
-        uint32_t word = nib << ((lane & 7u) * 4u);
-        word |= __shfl_xor(word, 1, 64);
-        word |= __shfl_xor(word, 2, 64);
-        word |= __shfl_xor(word, 4, 64);
+        const uint32_t word = or_over_8_lanes(nib << ((lane & 7u) * 4u));
         const uint32_t widx = (j0 >> 5) + (lane >> 3);
         if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
       }
@@ -574,6 +636,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometr
 // AMSGrad.  One wavefront per chunk of coordinates.
 // ---------------------------------------------------------------------------------------------
 constexpr int kBsWorkers = 8;  // workers whose sign words and scales are requested together
+constexpr int kBsSplit = 4;    // wavefronts per chunk in the server kernel
 
 __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, float* __restrict__ m,
                                                      float* __restrict__ v, float* __restrict__ vhat, Geometry geo,
@@ -581,10 +644,13 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
   const uint32_t* __restrict__ off = ws.offsets;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const uint32_t d = geo.d;
-  const uint32_t c = blockIdx.x * kWaves + wave;
+  // a wavefront takes a quarter of a chunk: four times as many wavefronts hide the latency of the per-round
+  // chain (state, sign words, scales -> update -> store) better than one wavefront per chunk does
+  const uint32_t gw = blockIdx.x * kWaves + wave;
+  const uint32_t c = gw / kBsSplit, part = gw % kBsSplit;
   if (c >= geo.num_chunks) return;
   uint32_t b = ws.chunk_block[c];
-  for (int r = 0; r < kRounds; ++r) {
+  for (int r = part * (kRounds / kBsSplit); r < static_cast<int>(part + 1) * (kRounds / kBsSplit); ++r) {
     const uint32_t j0 = c * kChunk + r * 256;
     if (j0 >= d) break;
     const uint32_t j = j0 + lane * 4;
@@ -746,8 +812,8 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
     launch(L, kSlotBsPass2, k_bs_pass2, grid_rows, wg, stream, e, geo, ws, 1);
     COMPAMS_CHECK_LAUNCH();
   }
-  launch(L, kSlotBsAms, k_bs_amsgrad, dim3((geo.num_chunks + kWaves - 1) / kWaves), wg, stream, theta, m, v, vhat, geo,
-         ws, ap);
+  launch(L, kSlotBsAms, k_bs_amsgrad, dim3((geo.num_chunks * kBsSplit + kWaves - 1) / kWaves), wg, stream, theta, m, v,
+         vhat, geo, ws, ap);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }

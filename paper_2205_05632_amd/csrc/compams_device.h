@@ -56,6 +56,16 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* scratc
   return before + incl - v;
 }
 
+// Bitwise OR over each aligned group of 8 lanes, left in all 8 of them.  Data-parallel-primitive moves
+// (quad permutes, then the mirror of each half row) instead of LDS-routed shuffles: three VALU
+// instructions, no memory-counter waits.
+__device__ __forceinline__ uint32_t or_over_8_lanes(uint32_t w) {
+  w |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(w), 0xB1, 0xF, 0xF, true));   // lanes ^ 1
+  w |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(w), 0x4E, 0xF, 0xF, true));   // lanes ^ 2
+  w |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(w), 0x141, 0xF, 0xF, true));  // 7 - lane
+  return w;
+}
+
 // 128-bit streaming (non-temporal) access for data that is touched once per step.
 typedef float f4v __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float4 load_stream4(const float* p) {
