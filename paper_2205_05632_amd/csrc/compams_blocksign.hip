@@ -65,13 +65,15 @@ __device__ __forceinline__ void atomic_add_u64(uint64_t* p, uint64_t v) {
 // Register accumulators of a lane: two fp64 sums, one per window of kWinSpan binary exponents, placed by the
 // wavefront (wave-uniform) where the magnitudes are expected.  Every |x| in a window is an integer below
 // 2^(24 + kWinSpan - 1) = 2^40 times the window's quantum 2^(lowest exponent - 150), so the fp64 sum of up to
-// kWinAdds = 2^13 of them is below 2^53 quanta: every addition is exact and their order does not matter.  At a
-// flush the sums become integers again, are added over the wavefront and go to the global digits.  Entries
+// 2^13 of them is below 2^53 quanta: every addition is exact and their order does not matter.  A lane flushes
+// after kWinAdds additions, far inside that bound (a wavefront rarely stays in one block for longer, and the
+// longest rows of the tests then reach the limit).  At a flush the sums become integers again, are added over
+// the wavefront and go to the global digits.  Entries
 // outside both windows (rare) and non-finite ones go straight to the global digits and flags.
 // "Exponent" here is the effective one: max(biased exponent, 1), so that subnormals share the quantum of
 // the smallest normal numbers; |x| = mantissa * 2^(exponent - 150).
 constexpr uint32_t kWinSpan = 17;
-constexpr uint32_t kWinAdds = 8192;
+constexpr uint32_t kWinAdds = 256;
 
 struct WaveAcc {
   double hi, lo;    // sums of the upper and the lower window
