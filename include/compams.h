@@ -75,7 +75,8 @@ typedef struct compams_config {
   float* m;     /* d: first moment  */
   float* v;     /* d: second moment */
   float* vhat;  /* d: running maximum of v */
-  float* e;     /* n * ld: error accumulators, row i = worker i; columns >= d are never touched */
+  float* e;     /* n * ld: error accumulators, row i = worker i; columns >= d are never touched.  Between steps
+                   the contents are the library's: see compams_step() */
   void* workspace;        /* DEVICE scratch of at least compams_workspace_size() bytes, 256-byte aligned */
   size_t workspace_bytes;
 } compams_config;
@@ -96,7 +97,13 @@ int compams_init(const compams_config* cfg, compams_ctx** out);
  * Top-k ties are broken towards the larger |x| and then the lower index, with |x| ordered by the fp32
  * bit pattern without its sign bit; the selected indices come out ascending per worker.  Block-sign
  * uses sign(x) = -1 iff x < 0 and the exactly summed block L1 norm.  The average adds the workers'
- * compressed gradients in the order 0..n-1 in fp32 and divides by n. */
+ * compressed gradients in the order 0..n-1 in fp32 and divides by n. *
+ * The error line of Algorithm 2 (e <- x - C(x)) may be left pending when the step returns: e then still
+ * holds the corrected gradient x where the update has not been applied (top-k: at the selected
+ * coordinates; block-sign with blocks other than aligned 4096-coordinate chunks: everywhere), and the next
+ * step applies it while it reads e.  compams_state(COMPAMS_STATE_E) and compams_destroy() apply what is
+ * pending first (one kernel on the last step's stream); do not read or write the e buffer between steps by
+ * any other route.  Every other result of the step is final when the stream has passed it. */
 int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream);
 
 /* What compams_state() can hand out.  Counts are in elements of the listed type. */
@@ -105,7 +112,7 @@ enum {
   COMPAMS_STATE_M = 1,              /* float[d] */
   COMPAMS_STATE_V = 2,              /* float[d] */
   COMPAMS_STATE_VHAT = 3,           /* float[d] */
-  COMPAMS_STATE_E = 4,              /* float[n*ld] */
+  COMPAMS_STATE_E = 4,              /* float[n*ld]; asking for it applies a pending residual update first */
   COMPAMS_STATE_LAST_IDX = 5,       /* top-k: int32[n*k], worker i's selected coordinates, ascending */
   COMPAMS_STATE_LAST_VAL = 6,       /* top-k: float[n*k], the corrected gradient at those coordinates */
   COMPAMS_STATE_LAST_SIGNBITS = 7,  /* block-sign: uint32[n*ceil(d/32)], bit (j&31) of word j>>5 = (x_j < 0) */

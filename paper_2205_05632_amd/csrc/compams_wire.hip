@@ -50,7 +50,14 @@ __global__ __launch_bounds__(kWG) void k_wire_gap_max(const int32_t* __restrict_
     const uint32_t o = __shfl_xor(mx, s, 64);
     mx = o > mx ? o : mx;
   }
-  if (lane_id() == 0 && mx) atomicMax(&wmax[row], mx);
+  // one atomic per workgroup: atomics on one word are served one after the other
+  __shared__ uint32_t part[kWG / 64];
+  if (lane_id() == 0) part[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < kWG / 64; ++w) mx = part[w] > mx ? part[w] : mx;
+    if (mx) atomicMax(&wmax[row], mx);
+  }
 }
 
 __global__ __launch_bounds__(kWG) void k_wire_pack_topk(const int32_t* __restrict__ idx_all,
