@@ -305,6 +305,33 @@ def test_blocksign_wide_dynamic_range_is_summed_exactly():
     p.close()
 
 
+@pytest.mark.parametrize("late_exp", [-3, 0, 2, 3, 9, 40])
+def test_blocksign_sums_around_the_register_windows(late_exp):
+    """The exact block sum runs, inside a lane, over two windows of binary exponents placed by the first entries
+    a wavefront meets.  Here the first 256 coordinates of each block are about 1.0 and later ones sit on, just
+    inside and far outside the window edges (powers of two from 2^-45 up to 2^late_exp, denormals, zeros, a few
+    entries that share mantissa bits across the whole 24-bit width): every route into the sum must agree with the
+    oracle to the last bit of the scale."""
+    n, d = 2, 3 * 4096 + 123
+    rng = np.random.default_rng(100 + late_exp)
+    off = np.array([0, 4096 + 17, d], dtype=np.int64)
+    p = Pair(n, d, np.zeros(d, np.float32), B.BLOCKSIGN, block_offsets=off)
+    for t in range(3):
+        g = np.empty((n, d), np.float32)
+        exps = rng.integers(-45, late_exp + 1, size=(n, d))
+        mant = 1.0 + rng.integers(0, 1 << 23, size=(n, d)) / float(1 << 23)         # full-width mantissas
+        g[:] = (np.ldexp(mant, exps) * rng.choice([-1.0, 1.0], size=(n, d))).astype(np.float32)
+        for lo in off[:-1]:
+            g[:, lo:lo + 256] = (1.0 + rng.random((n, 256))).astype(np.float32)       # what places the windows
+        g[:, 700::97] = 0.0
+        g[:, 701::193] = np.float32(1e-45)                                            # the smallest denormal
+        g[:, 702::389] = np.float32(2.0 ** -126)
+        g[0, 5000] = np.float32(2.0 ** (late_exp + 1)) * np.float32(1.9999999)        # above everything else
+        p.step(g, 1e-3, label=f"windows late_exp={late_exp} step {t}", with_e=(t == 2))
+    assert all(p.exact.values()), p.exact
+    p.close()
+
+
 def test_blocksign_4096_blocks_take_the_general_route_when_a_block_is_too_wide():
     """Blocks of exactly 4096 coordinates are normally finished in one pass; a block whose entries span more than
     2^32 (or hold an infinity) is handed to the general kernels.  Both kinds in one run."""
