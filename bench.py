@@ -153,6 +153,31 @@ def main():
         for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
             print(f"  {name:16s} {ms / cnt * 1e3:9.1f} us/launch  x{cnt}", file=sys.stderr)
 
+    # a second look at the same steps, one pair of events per step: median and minimum (each figure includes
+    # the cost of its events; `value` above does not)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i, (a, b) in enumerate(ev):
+        a.record()
+        ctx.compams_step(grads[args.warmup + i], w.lr)
+        b.record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in ev)
+    step_ms_median, step_ms_min = per_step[len(per_step) // 2], per_step[0]
+
+    # what the box gives a plain copy (1 GiB read + 1 GiB written per launch): the practical ceiling beside the
+    # published peak
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        B.compams_copy(dst, src)
+    torch.cuda.synchronize()
+    c0 = time.perf_counter()
+    for _ in range(10):
+        B.compams_copy(dst, src)
+    torch.cuda.synchronize()
+    copy_gbps = 2.0 * (1 << 30) / ((time.perf_counter() - c0) / 10) / 1e9
+    del src, dst
+
     # the last step's messages on the wire: sizes (32 bits per word, the accounting of the paper's experiments
     # section) and the time to pack and unpack them; not part of `value`
     wire = None
@@ -204,6 +229,8 @@ def main():
         "hbm_gbps": bmin / (sec / args.steps) / 1e9,
         "hbm_frac_of_peak": bmin / (sec / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_step": bmin,
+        "step_ms_median": step_ms_median, "step_ms_min": step_ms_min,
+        "copy_kernel_gbps": copy_gbps, "hbm_frac_of_copy_kernel": bmin / (sec / args.steps) / 1e9 / copy_gbps,
         "kernel_ms_per_step": kernel_sum_ms,
         "roofline": roofline,
         "kernels_us_per_launch": {k_: v_[0] / v_[1] * 1e3 for k_, v_ in prof.items()},

@@ -118,7 +118,9 @@ enum {
   COMPAMS_STATE_LAST_SIGNBITS = 7,  /* block-sign: uint32[n*ceil(d/32)], bit (j&31) of word j>>5 = (x_j < 0) */
   COMPAMS_STATE_LAST_SCALES = 8,    /* block-sign: float[n*M], the block means of |x| */
   COMPAMS_STATE_LAST_THRESHOLD = 9, /* top-k: uint32[n], magnitude key of the k-th largest entry */
-  COMPAMS_STATE_COUNTERS = 10       /* uint32[n*COMPAMS_COUNTERS_PER_ROW], see below */
+  COMPAMS_STATE_COUNTERS = 10,      /* uint32[n*COMPAMS_COUNTERS_PER_ROW], see below */
+  COMPAMS_STATE_LAST_COUNT_GT = 11  /* top-k: uint32[n], selected entries strictly above the threshold key (the
+                                       other k - that many are ties, taken in coordinate order) */
 };
 
 /* Per-worker counters of the last step (top-k), for tests and profiling reports. */

@@ -21,9 +21,9 @@ OPT_CANDIDATE_CAP, OPT_PREDICT, OPT_FORCE_DENSE = 0, 1, 2
 COUNTERS_PER_ROW = 4
 
 STATE = {"theta": 0, "m": 1, "v": 2, "vhat": 3, "e": 4, "last_idx": 5, "last_val": 6, "last_signbits": 7,
-         "last_scales": 8, "last_threshold": 9, "counters": 10}
+         "last_scales": 8, "last_threshold": 9, "counters": 10, "last_count_gt": 11}
 _STATE_DTYPE = {"last_idx": torch.int32, "last_signbits": torch.int32, "last_threshold": torch.int32,
-                "counters": torch.int32}
+                "counters": torch.int32, "last_count_gt": torch.int32}
 
 EXPORTS = ["compams_workspace_size", "compams_init", "compams_step", "compams_state", "compams_set_option",
            "compams_profile_enable", "compams_profile_read", "compams_destroy", "compams_strerror", "compams_copy",

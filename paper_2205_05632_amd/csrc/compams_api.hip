@@ -55,7 +55,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t total;
   // top-k
-  size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, wire_max,
+  size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_max,
       wire_tiles;
   // block-sign
   size_t offsets, chunk_block, acc, special, done, scales, bits;
@@ -100,6 +100,7 @@ Layout make_layout(const compams_config* c) {
     L.idx = take(n * k * 4);
     L.val = take(n * k * 4);
     L.tau = take(n * 4);
+    L.count_gt = take(n * 4);
     L.wire_max = take(n * 4);
     L.wire_tiles = take(n * ((k + kWireTile - 1) / kWireTile) * 4);
   } else if (c->compressor == COMPAMS_BLOCKSIGN) {
@@ -212,6 +213,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     t.chunk_rec = reinterpret_cast<uint4*>(w + lay.chunk_rec);
     t.blk = reinterpret_cast<uint2*>(w + lay.blk);
     t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);
+    t.count_gt = reinterpret_cast<uint32_t*>(w + lay.count_gt);
     t.wire_max = reinterpret_cast<uint32_t*>(w + lay.wire_max);
     t.wire_tiles = reinterpret_cast<uint32_t*>(w + lay.wire_tiles);
     t.desc = reinterpret_cast<uint2*>(w + lay.desc);
@@ -328,6 +330,9 @@ int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* co
     case COMPAMS_STATE_LAST_THRESHOLD:
       if (!tk) return COMPAMS_BAD_STATE;
       p = ctx->tk.tau; cnt = n; break;
+    case COMPAMS_STATE_LAST_COUNT_GT:
+      if (!tk) return COMPAMS_BAD_STATE;
+      p = ctx->tk.count_gt; cnt = n; break;
     case COMPAMS_STATE_COUNTERS:
       if (!tk) return COMPAMS_BAD_STATE;
       p = ctx->tk.counters; cnt = n * COMPAMS_COUNTERS_PER_ROW; break;

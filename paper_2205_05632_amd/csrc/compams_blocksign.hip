@@ -779,9 +779,11 @@ __global__ __launch_bounds__(kWG) void k_fill_rows(float* p, int64_t ld, uint32_
   for (uint32_t j = blockIdx.x * kWG + threadIdx.x; j < d; j += step) r[j] = value;
 }
 
-__global__ __launch_bounds__(kWG) void k_copy16(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t count) {
+// Streaming (non-temporal) accesses, as in the step's dense kernels.
+__global__ __launch_bounds__(kWG) void k_copy16(float* __restrict__ dst, const float* __restrict__ src, size_t count) {
   const size_t step = static_cast<size_t>(gridDim.x) * kWG;
-  for (size_t i = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x; i < count; i += step) dst[i] = src[i];
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x; i < count; i += step)
+    store_stream4(dst + 4 * i, load_stream4(src + 4 * i));
 }
 
 }  // namespace
@@ -855,7 +857,7 @@ hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t str
   size_t blocks = (count + kWG - 1) / kWG;
   if (blocks > 256 * 16) blocks = 256 * 16;
   hipLaunchKernelGGL(k_copy16, dim3(static_cast<uint32_t>(blocks)), dim3(kWG), 0, stream,
-                     static_cast<uint4*>(dst), static_cast<const uint4*>(src), count);
+                     static_cast<float*>(dst), static_cast<const float*>(src), count);
   return hipGetLastError();
 }
 

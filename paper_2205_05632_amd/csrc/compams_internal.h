@@ -86,6 +86,7 @@ struct TopkWorkspace {
                         //                  within the chunk's count block
   uint2* blk;           // n * kMaxCountBlocks : the two totals of every count block
   uint32_t* sel_off;    // n * (num_chunks + 1) : where each chunk's slice of the worker's list starts
+  uint32_t* count_gt;   // n : selected entries whose key lies strictly above the threshold key
   uint32_t* wire_max;   // n : largest coordinate gap of the message being packed
   uint32_t* wire_tiles; // n * ceil(k / kWireTile) : coordinates before each tile of a message being unpacked
   uint2* desc;          // n * num_chunks : (offset, count) of the chunk's segment in the candidate list

@@ -704,6 +704,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
     rowp->ties = ties;
     rowp->take_all_ties = (r == ties);
     ws.tau[row] = tau;
+    ws.count_gt[row] = geo.k - r;
     uint32_t* cn = ws.counters + row * 4;
     cn[2] = ties;
     cn[3] = r;

@@ -74,6 +74,13 @@ class Pair:
                 raise AssertionError(f"{label}: selected index sets differ in rows {rows}; row {i} first differs at "
                                      f"position {q}: gpu {idx[i][q:q+4]} oracle {want_idx[i][q:q+4]}")
             assert bits_equal(val, cpu.get("val")), f"{label}: selected values differ"
+            # threshold key and the number of entries strictly above it, from the oracle's own selection
+            keys = cpu.get("val").view(np.uint32) & 0x7FFFFFFF
+            tau = keys.min(axis=1)
+            assert np.array_equal(gpu.compams_state("last_threshold").cpu().numpy().view(np.uint32), tau), \
+                f"{label}: threshold keys differ"
+            assert np.array_equal(gpu.compams_state("last_count_gt").cpu().numpy(), (keys > tau[:, None]).sum(axis=1)), \
+                f"{label}: counts above the threshold differ"
         elif self.compressor == B.BLOCKSIGN:
             bits = gpu.compams_state("last_signbits").cpu().numpy().view(np.uint32)
             assert np.array_equal(bits, cpu.get("bits")), f"{label}: sign patterns differ"
