@@ -224,8 +224,8 @@ __device__ __forceinline__ void digits3_to_192(uint64_t s0, uint64_t s1, uint64_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pass 1: x = e + g -> e and exact block sums.  Grid (groups, n), one wavefront per chunk, loads one
-// batch of rounds ahead.
+// Pass 1: x = e + g -> e, the sign words of x and the exact block sums.  Grid (groups, n); a wavefront
+// takes a chunk at a time and loads one batch of rounds ahead.
 // ---------------------------------------------------------------------------------------------
 constexpr int kBsBatch = 4;
 
@@ -572,7 +572,9 @@ __global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWork
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pass 2: sign bits and residual  e = x - sign(x) * mu.  One wavefront per chunk.  Eight lanes
+// The residual  e = x - sign(x) * mu  on its own (and the sign words once more): for blocks that the
+// single-pass kernel left unfinished, and when the caller asks for e while the update of a general
+// layout is still pending.  One wavefront per chunk.  Eight lanes
 // (32 coordinates) share one word of the bit map.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometry geo, BlocksignWorkspace ws,
