@@ -199,7 +199,8 @@ def main():
         wire = {"bits_per_worker": bits, "full_gradient_bits": 32.0 * w.d, "reduction": 32.0 * w.d / bits,
                 "encode_us": (w1 - w0) / reps * 1e6, "decode_us": (w2 - w1) / reps * 1e6}
         if comp == B.TOPK:
-            wire["gap_bits"] = msgs[:, 2].tolist()
+            tiles = (w.k + 255) // 256
+            wire["gap_bits_mean"] = (bits / 32.0 - 3 - (tiles + 3) // 4 - w.k) * 32.0 / w.k
             wire["reduction_values_only"] = w.d / w.k
         del msgs, words
 

@@ -168,18 +168,21 @@ const char* compams_strerror(int status);
  * little-endian words per worker.  The paper fixes only the accounting (experiments section: 32 bits per
  * transmitted float); the layout below is this library's.
  *
- *   top-k (Definition 1)       [1, k, b,  gap stream: ceil(k*b/32) words,  k value words]
- *       The kept coordinates are ascending; gap_0 = idx_0 and gap_q = idx_q - idx_{q-1} - 1.  b (1..31) is the
- *       number of bits of the largest gap of the message (1 if all gaps are 0).  Gap q occupies bits q*b ..
- *       q*b+b-1 of the stream, least significant bit first; stream bit t is bit (t mod 32) of stream word
- *       t div 32; the unused high bits of the last stream word are 0.  The values are the fp32 patterns of
- *       the corrected gradient at the kept coordinates, in the same order.
+ *   top-k (Definition 1)       [1, k, 256,  width words,  gap stream,  k value words]
+ *       The kept coordinates are ascending; gap_0 = idx_0 and gap_q = idx_q - idx_{q-1} - 1.  The gaps are
+ *       taken in tiles of 256 (the last tile may be shorter).  Tile t has its own width b_t (1..31), the number
+ *       of bits of its largest gap (1 if all its gaps are 0), kept as byte (t mod 4) of width word t div 4;
+ *       there are ceil(ceil(k/256)/4) width words and their unused bytes are 0.  In the stream the tiles follow
+ *       one another, each starting on a word boundary and taking ceil(count_t * b_t / 32) words: gap i of a
+ *       tile occupies the tile's bits i*b_t .. i*b_t+b_t-1, least significant bit first; bit u of a tile is bit
+ *       (u mod 32) of its word u div 32; the unused high bits of a tile's last word are 0.  The values are the
+ *       fp32 patterns of the corrected gradient at the kept coordinates, in the same order.
  *   block-sign (Definition 2)  [2, d, M,  ceil(d/32) sign words,  M scale words]
  *       Bit (j mod 32) of sign word j div 32 is 1 iff x_j < 0 (unused bits 0); scale b is the fp32 mean of
  *       |x| over block b.
  *
  * Bits per worker and step: 32 * (message length in words).  For comparison the paper counts 32*d bits for an
- * uncompressed gradient; a top-k message is between 32*k (its values alone) and 64*k + 96 bits.
+ * uncompressed gradient; a top-k message is between 32*k (its values alone) and about 64*k bits.
  *
  * compams_wire_capacity: the largest message (in words) a worker of this configuration can produce; pure,
  *   host only; 0 for an invalid configuration or COMPAMS_NONE (nothing is compressed: the message would be
@@ -192,8 +195,9 @@ const char* compams_strerror(int status);
  *   (then lengths are not checked).  top-k: out_a = int32[n*k] coordinates, out_b = float[n*k] values;
  *   block-sign: out_a = uint32[n*ceil(d/32)] sign words, out_b = float[n*M] scales (all DEVICE, caller-owned).
  *   status_out: DEVICE, n words: 0 if message i was well formed, else bit 0 = not a message of this kind and
- *   size, bit 1 = length differs from `words`, bit 2 = a coordinate at or beyond d.  Malformed input never
- *   makes the library read outside [message, message + stride_words); the outputs for such a message are
+ *   size or a tile width outside 1..31, bit 1 = length differs from `words`, bit 2 = a coordinate at or
+ *   beyond d.  Malformed input never makes the library read outside [message, message + stride_words); the
+ *   outputs for such a message are
  *   unspecified.  Uses the context's workspace: not concurrent with compams_step or another decode on the
  *   same context. */
 size_t compams_wire_capacity(const compams_config* cfg);

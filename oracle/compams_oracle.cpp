@@ -344,58 +344,89 @@ double oracle_exact_abs_sum(const float* x, int64_t len) {
 // accounting (32 bits per transmitted float, experiments section); the layout is this library's own and
 // is stated in full in the public header.  Written here bit by bit, straight from that statement.
 //
-//   top-k      [1, k, b,  gap stream of ceil(k*b/32) words,  k value words]
-//              gap_0 = idx_0, gap_q = idx_q - idx_{q-1} - 1; b = number of bits of the largest gap (at least 1);
-//              gap q occupies stream bits q*b .. q*b+b-1, least significant bit first; stream bit t is
-//              bit (t mod 32) of stream word t div 32; unused bits of the last stream word are 0.
+//   top-k      [1, k, 256,  width words,  gap stream,  k value words]
+//              gap_0 = idx_0, gap_q = idx_q - idx_{q-1} - 1.  The gaps are taken in tiles of 256 (the last one
+//              may be shorter); tile t has its own width b_t = number of bits of its largest gap (at least 1),
+//              kept as byte (t mod 4) of width word t div 4 (unused bytes 0).  In the stream the tiles follow
+//              one another, each starting on a word boundary: gap i of a tile occupies the tile's bits
+//              i*b_t .. i*b_t + b_t - 1, least significant bit first; bit u of a tile is bit (u mod 32) of its
+//              word u div 32; unused bits of a tile's last word are 0.
 //   block-sign [2, d, M,  ceil(d/32) sign words,  M scale words]
 // ---------------------------------------------------------------------------------------------
+constexpr int64_t kWireTileGaps = 256;
+
 int64_t oracle_wire_encode_topk(int64_t k, const int32_t* idx, const float* val, uint32_t* out) {
-  uint32_t widest = 0;
   std::vector<uint32_t> gap(static_cast<size_t>(k));
-  for (int64_t q = 0; q < k; ++q) {
+  for (int64_t q = 0; q < k; ++q)
     gap[q] = q == 0 ? static_cast<uint32_t>(idx[0])
                     : static_cast<uint32_t>(idx[q]) - static_cast<uint32_t>(idx[q - 1]) - 1u;
-    if (gap[q] > widest) widest = gap[q];
+  const int64_t tiles = (k + kWireTileGaps - 1) / kWireTileGaps;
+  const int64_t width_words = (tiles + 3) / 4;
+  out[0] = 1u; out[1] = static_cast<uint32_t>(k); out[2] = static_cast<uint32_t>(kWireTileGaps);
+  uint32_t* widths = out + 3;
+  for (int64_t w = 0; w < width_words; ++w) widths[w] = 0;
+  uint32_t* stream = widths + width_words;
+  int64_t at = 0;  // words of the stream written so far
+  for (int64_t t = 0; t < tiles; ++t) {
+    const int64_t first = t * kWireTileGaps;
+    const int64_t cnt = std::min<int64_t>(kWireTileGaps, k - first);
+    uint32_t widest = 0;
+    for (int64_t i = 0; i < cnt; ++i) widest = std::max(widest, gap[first + i]);
+    uint32_t b = 1;
+    while (b < 32 && (widest >> b) != 0) ++b;
+    widths[t / 4] |= b << (8 * (t % 4));
+    const int64_t tile_words = (cnt * b + 31) / 32;
+    for (int64_t w = 0; w < tile_words; ++w) stream[at + w] = 0;
+    for (int64_t i = 0; i < cnt; ++i)
+      for (uint32_t u = 0; u < b; ++u)
+        if ((gap[first + i] >> u) & 1u) {
+          const int64_t pos = i * b + u;
+          stream[at + pos / 32] |= 1u << (pos % 32);
+        }
+    at += tile_words;
   }
-  uint32_t b = 1;
-  while (b < 32 && (widest >> b) != 0) ++b;
-  const int64_t stream_words = (k * b + 31) / 32;
-  out[0] = 1u; out[1] = static_cast<uint32_t>(k); out[2] = b;
-  uint32_t* stream = out + 3;
-  for (int64_t w = 0; w < stream_words; ++w) stream[w] = 0;
-  for (int64_t q = 0; q < k; ++q)
-    for (uint32_t t = 0; t < b; ++t)
-      if ((gap[q] >> t) & 1u) {
-        const int64_t pos = q * b + t;
-        stream[pos / 32] |= 1u << (pos % 32);
-      }
-  uint32_t* values = stream + stream_words;
+  uint32_t* values = stream + at;
   for (int64_t q = 0; q < k; ++q) std::memcpy(&values[q], &val[q], 4);
-  return 3 + stream_words + k;
+  return 3 + width_words + at + k;
 }
 
 // Returns 0, or a negative number if the words are not a top-k message of k entries below d.
 int64_t oracle_wire_decode_topk(const uint32_t* msg, int64_t nwords, int64_t k, int64_t d, int32_t* idx, float* val) {
-  if (nwords < 3 || msg[0] != 1u || msg[1] != static_cast<uint32_t>(k)) return -1;
-  const uint32_t b = msg[2];
-  if (b < 1 || b > 31) return -2;
-  const int64_t stream_words = (k * b + 31) / 32;
-  if (nwords != 3 + stream_words + k) return -3;
-  const uint32_t* stream = msg + 3;
-  int64_t prev = -1;
-  for (int64_t q = 0; q < k; ++q) {
-    uint32_t gap = 0;
-    for (uint32_t t = 0; t < b; ++t) {
-      const int64_t pos = q * b + t;
-      gap |= ((stream[pos / 32] >> (pos % 32)) & 1u) << t;
-    }
-    const int64_t j = prev + 1 + static_cast<int64_t>(gap);
-    if (j >= d) return -4;
-    idx[q] = static_cast<int32_t>(j);
-    prev = j;
+  if (nwords < 3 || msg[0] != 1u || msg[1] != static_cast<uint32_t>(k) ||
+      msg[2] != static_cast<uint32_t>(kWireTileGaps))
+    return -1;
+  const int64_t tiles = (k + kWireTileGaps - 1) / kWireTileGaps;
+  const int64_t width_words = (tiles + 3) / 4;
+  if (nwords < 3 + width_words) return -3;
+  const uint32_t* widths = msg + 3;
+  int64_t stream_words = 0;
+  for (int64_t t = 0; t < tiles; ++t) {
+    const uint32_t b = (widths[t / 4] >> (8 * (t % 4))) & 0xffu;
+    if (b < 1 || b > 31) return -2;
+    const int64_t cnt = std::min<int64_t>(kWireTileGaps, k - t * kWireTileGaps);
+    stream_words += (cnt * b + 31) / 32;
   }
-  const uint32_t* values = stream + stream_words;
+  if (nwords != 3 + width_words + stream_words + k) return -3;
+  const uint32_t* stream = widths + width_words;
+  int64_t at = 0, prev = -1;
+  for (int64_t t = 0; t < tiles; ++t) {
+    const uint32_t b = (widths[t / 4] >> (8 * (t % 4))) & 0xffu;
+    const int64_t first = t * kWireTileGaps;
+    const int64_t cnt = std::min<int64_t>(kWireTileGaps, k - first);
+    for (int64_t i = 0; i < cnt; ++i) {
+      uint32_t gap = 0;
+      for (uint32_t u = 0; u < b; ++u) {
+        const int64_t pos = i * b + u;
+        gap |= ((stream[at + pos / 32] >> (pos % 32)) & 1u) << u;
+      }
+      const int64_t j = prev + 1 + static_cast<int64_t>(gap);
+      if (j >= d) return -4;
+      idx[first + i] = static_cast<int32_t>(j);
+      prev = j;
+    }
+    at += (cnt * b + 31) / 32;
+  }
+  const uint32_t* values = stream + at;
   for (int64_t q = 0; q < k; ++q) std::memcpy(&val[q], &values[q], 4);
   return 0;
 }

@@ -88,7 +88,7 @@ def wire_encode_topk(idx, val):
     idx = np.ascontiguousarray(idx, dtype=np.int32)
     val, pv = _f32(val)
     k = idx.size
-    out = np.zeros(3 + 2 * k, dtype=np.uint32)
+    out = np.zeros(4 + (k + 1023) // 1024 + 2 * k, dtype=np.uint32)
     n = lib().oracle_wire_encode_topk(k, idx.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), pv, _u32p(out))
     return out[:n].copy()
 

@@ -55,8 +55,8 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t total;
   // top-k
-  size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_max,
-      wire_tiles;
+  size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_total,
+      wire_tile_off, wire_tile_sum;
   // block-sign
   size_t offsets, chunk_block, acc, special, done, scales, bits;
   uint32_t cap_alloc, num_chunks, words;
@@ -101,8 +101,9 @@ Layout make_layout(const compams_config* c) {
     L.val = take(n * k * 4);
     L.tau = take(n * 4);
     L.count_gt = take(n * 4);
-    L.wire_max = take(n * 4);
-    L.wire_tiles = take(n * ((k + kWireTile - 1) / kWireTile) * 4);
+    L.wire_total = take(n * 4);
+    L.wire_tile_off = take(n * ((k + kWireTile - 1) / kWireTile) * 4);
+    L.wire_tile_sum = take(n * ((k + kWireTile - 1) / kWireTile) * 4);
   } else if (c->compressor == COMPAMS_BLOCKSIGN) {
     const size_t M = static_cast<size_t>(c->num_blocks);
     L.offsets = take((M + 1) * 4);
@@ -214,8 +215,9 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     t.blk = reinterpret_cast<uint2*>(w + lay.blk);
     t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);
     t.count_gt = reinterpret_cast<uint32_t*>(w + lay.count_gt);
-    t.wire_max = reinterpret_cast<uint32_t*>(w + lay.wire_max);
-    t.wire_tiles = reinterpret_cast<uint32_t*>(w + lay.wire_tiles);
+    t.wire_total = reinterpret_cast<uint32_t*>(w + lay.wire_total);
+    t.wire_tile_off = reinterpret_cast<uint32_t*>(w + lay.wire_tile_off);
+    t.wire_tile_sum = reinterpret_cast<uint32_t*>(w + lay.wire_tile_sum);
     t.desc = reinterpret_cast<uint2*>(w + lay.desc);
     t.cand = reinterpret_cast<uint2*>(w + lay.cand);
     t.idx = reinterpret_cast<int32_t*>(w + lay.idx);
@@ -431,7 +433,10 @@ const char* compams_strerror(int status) {
 
 size_t compams_wire_capacity(const compams_config* cfg) {
   if (!basic_valid(cfg)) return 0;
-  if (cfg->compressor == COMPAMS_TOPK) return 3 + 2 * static_cast<size_t>(cfg->k);  // gaps never need 32 bits
+  if (cfg->compressor == COMPAMS_TOPK) {  // header, a width byte per tile of 256 gaps, at most 31 bits per gap
+    const size_t k = static_cast<size_t>(cfg->k), tiles = (k + kWireTile - 1) / kWireTile;
+    return 3 + (tiles + 3) / 4 + 2 * k;
+  }
   if (cfg->compressor == COMPAMS_BLOCKSIGN)
     return 3 + (static_cast<size_t>(cfg->d) + 31) / 32 + static_cast<size_t>(cfg->num_blocks);
   return 0;

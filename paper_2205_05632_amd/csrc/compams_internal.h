@@ -40,7 +40,7 @@ inline uint32_t count_chunks_per_block(uint32_t num_chunks) {
   return 32 * (m ? m : 1);
 }
 
-constexpr int kWireTile = 4096;  // entries per tile when a top-k message is unpacked
+constexpr int kWireTile = 256;  // coordinate gaps per tile of a top-k message (one width per tile)
 
 // Where a row's selection reads its elements from after the first pass.
 enum : uint32_t {
@@ -87,8 +87,9 @@ struct TopkWorkspace {
   uint2* blk;           // n * kMaxCountBlocks : the two totals of every count block
   uint32_t* sel_off;    // n * (num_chunks + 1) : where each chunk's slice of the worker's list starts
   uint32_t* count_gt;   // n : selected entries whose key lies strictly above the threshold key
-  uint32_t* wire_max;   // n : largest coordinate gap of the message being packed
-  uint32_t* wire_tiles; // n * ceil(k / kWireTile) : coordinates before each tile of a message being unpacked
+  uint32_t* wire_total;    // n : words of the gap stream of the message being packed or unpacked
+  uint32_t* wire_tile_off; // n * ceil(k / kWireTile) : where each tile of gaps starts in its stream
+  uint32_t* wire_tile_sum; // n * ceil(k / kWireTile) : coordinates before each tile, while unpacking
   uint2* desc;          // n * num_chunks : (offset, count) of the chunk's segment in the candidate list
   uint2* cand;          // n * cap_alloc  : (coordinate, fp32 bits)
   int32_t* idx;         // n * k

@@ -1,16 +1,20 @@
 // The workers' messages as they would go on the wire ("send the compressed gradient to the server" in the
 // worker lines of Algorithm 2), and back.  One message per worker, a sequence of 32-bit words:
 //
-//   top-k      [1, k, b,  gap stream of ceil(k*b/32) words,  k value words]
-//              gap_0 = idx_0, gap_q = idx_q - idx_{q-1} - 1; b = number of bits of the largest gap (at least 1);
-//              gap q occupies stream bits q*b .. q*b+b-1, least significant bit first; stream bit t is
-//              bit (t mod 32) of stream word t div 32; unused bits of the last stream word are 0.
+//   top-k      [1, k, 256,  width words,  gap stream,  k value words]
+//              gap_0 = idx_0, gap_q = idx_q - idx_{q-1} - 1.  The gaps are taken in tiles of 256 (the last one
+//              may be shorter); tile t has its own width b_t = number of bits of its largest gap (at least 1),
+//              kept as byte (t mod 4) of width word t div 4 (unused bytes 0).  In the stream the tiles follow
+//              one another, each starting on a word boundary: gap i of a tile occupies the tile's bits
+//              i*b_t .. i*b_t + b_t - 1, least significant bit first; bit u of a tile is bit (u mod 32) of its
+//              word u div 32; unused bits of a tile's last word are 0.
 //   block-sign [2, d, M,  ceil(d/32) sign words,  M scale words]
 //
-// Packing: every stream word is owned by one thread, which gathers the (at most 32) gaps that overlap it, so
-// no atomics touch the message.  Unpacking turns gaps back into coordinates with a two-level prefix sum over
-// tiles of 4096 entries.  A message that is not well formed never makes a kernel read outside
-// [message, message + stride): the entry count and the sizes come from the configuration, not from the words.
+// A wavefront owns a tile.  Packing: the tile's gaps are staged in LDS and every stream word is written by one
+// lane, which gathers the (at most 32) gaps that overlap it: no atomics touch the message.  Where a tile starts
+// in the stream, and the coordinate before its first entry when unpacking, come from prefix sums over the
+// tiles of a row (one workgroup per row).  A message that is not well formed never makes a kernel read outside
+// [message, message + stride): counts come from the configuration and widths are clamped to 1 .. 31.
 
 #include "compams_device.h"
 #include "compams_internal.h"
@@ -18,7 +22,7 @@
 namespace compams {
 namespace {
 
-constexpr int kWirePer = kWireTile / kWG;  // entries per thread in a tile
+static_assert(kWireTile == 256, "a wavefront takes a tile as four gaps per lane");
 
 __device__ __forceinline__ uint32_t gap_of(const int32_t* idx, uint32_t q) {
   const uint32_t cur = static_cast<uint32_t>(idx[q]);
@@ -31,115 +35,59 @@ __device__ __forceinline__ uint32_t width_of(uint32_t widest) {  // coordinates 
 
 __device__ __forceinline__ uint32_t clamp_width(uint32_t b) { return b < 1u ? 1u : (b > 31u ? 31u : b); }
 
-__device__ __forceinline__ uint32_t stream_words(uint32_t k, uint32_t b) {
-  return static_cast<uint32_t>((static_cast<uint64_t>(k) * b + 31u) >> 5);
+__device__ __forceinline__ uint32_t tile_count(uint32_t k, uint32_t t) {
+  const uint32_t left = k - t * kWireTile;
+  return left < kWireTile ? left : kWireTile;
 }
 
-__global__ __launch_bounds__(kWG) void k_wire_gap_max(const int32_t* __restrict__ idx_all, uint32_t k,
-                                                       uint32_t* __restrict__ wmax) {
-  const uint32_t row = blockIdx.y;
-  const int32_t* idx = idx_all + static_cast<size_t>(row) * k;
-  uint32_t mx = 0;
-  const uint32_t step = gridDim.x * kWG;
-  for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < k; q += step) {
-    const uint32_t g = gap_of(idx, q);
-    mx = g > mx ? g : mx;
-  }
+__device__ __forceinline__ uint32_t tile_words(uint32_t cnt, uint32_t b) { return (cnt * b + 31u) >> 5; }
+
+__device__ __forceinline__ uint32_t width_byte(const uint32_t* msg, uint32_t t) {
+  return (msg[3 + (t >> 2)] >> (8u * (t & 3u))) & 0xffu;
+}
+
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
 #pragma unroll
   for (int s = 32; s >= 1; s >>= 1) {
-    const uint32_t o = __shfl_xor(mx, s, 64);
-    mx = o > mx ? o : mx;
+    const uint32_t o = __shfl_xor(v, s, 64);
+    v = o > v ? o : v;
   }
-  // one atomic per workgroup: atomics on one word are served one after the other
-  __shared__ uint32_t part[kWG / 64];
-  if (lane_id() == 0) part[threadIdx.x >> 6] = mx;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    for (int w = 1; w < kWG / 64; ++w) mx = part[w] > mx ? part[w] : mx;
-    if (mx) atomicMax(&wmax[row], mx);
-  }
+  return v;
 }
 
-__global__ __launch_bounds__(kWG) void k_wire_pack_topk(const int32_t* __restrict__ idx_all,
-                                                         const float* __restrict__ val_all, uint32_t k,
-                                                         const uint32_t* __restrict__ wmax,
-                                                         uint32_t* __restrict__ messages, int64_t stride,
-                                                         uint32_t* __restrict__ words_out) {
-  const uint32_t row = blockIdx.y;
+// Widths of the tiles (into the message) and the words each tile will take (into tile_off, to be scanned).
+__global__ __launch_bounds__(kWG) void k_wire_tile_width(const int32_t* __restrict__ idx_all, uint32_t k,
+                                                          uint32_t tiles, uint32_t* __restrict__ messages,
+                                                          int64_t stride, uint32_t* __restrict__ tile_off) {
+  __shared__ uint32_t sb[kWaves];
+  const uint32_t row = blockIdx.y, wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t t = blockIdx.x * kWaves + wave;
   const int32_t* idx = idx_all + static_cast<size_t>(row) * k;
-  const float* val = val_all + static_cast<size_t>(row) * k;
-  const uint32_t b = width_of(wmax[row]);
-  const uint32_t P = stream_words(k, b);
-  uint32_t* msg = messages + static_cast<int64_t>(row) * stride;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
-    msg[0] = 1u;
-    msg[1] = k;
-    msg[2] = b;
-    words_out[row] = 3u + P + k;
-  }
-  uint32_t* stream = msg + 3;
-  const uint32_t step = gridDim.x * kWG;
-  for (uint32_t w = blockIdx.x * kWG + threadIdx.x; w < P; w += step) {
-    const uint64_t lo = static_cast<uint64_t>(w) * 32u;
-    const uint32_t q0 = static_cast<uint32_t>(lo / b);
-    uint64_t q1 = (lo + 31u) / b;
-    if (q1 > k - 1u) q1 = k - 1u;
-    uint32_t word = 0;
-    for (uint32_t q = q0; q <= static_cast<uint32_t>(q1); ++q) {
-      const uint32_t g = gap_of(idx, q);
-      const int64_t sh = static_cast<int64_t>(static_cast<uint64_t>(q) * b) - static_cast<int64_t>(lo);
-      word |= sh >= 0 ? (g << sh) : (g >> (-sh));  // |sh| <= 31
-    }
-    stream[w] = word;
-  }
-  uint32_t* values = stream + P;
-  for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < k; q += step) values[q] = __float_as_uint(val[q]);
-}
-
-// Gap q of a stream of P words (q < k, so the field lies inside the stream).
-__device__ __forceinline__ uint32_t field_of(const uint32_t* __restrict__ stream, uint32_t P, uint32_t q, uint32_t b) {
-  const uint64_t pos = static_cast<uint64_t>(q) * b;
-  const uint32_t w = static_cast<uint32_t>(pos >> 5), sh = static_cast<uint32_t>(pos & 31u);
-  uint64_t two = stream[w];
-  if (w + 1 < P) two |= static_cast<uint64_t>(stream[w + 1]) << 32;
-  return static_cast<uint32_t>(two >> sh) & ((1u << b) - 1u);
-}
-
-// status[row]: 0 well formed; bit 0: not a message of this kind and size; bit 1: length differs; bit 2 (set
-// while unpacking): a coordinate at or beyond d.
-__global__ void k_wire_check_topk(const uint32_t* __restrict__ messages, int64_t stride,
-                                  const uint32_t* __restrict__ words, uint32_t n, uint32_t k,
-                                  uint32_t* __restrict__ status) {
-  const uint32_t row = blockIdx.x * blockDim.x + threadIdx.x;
-  if (row >= n) return;
-  const uint32_t* msg = messages + static_cast<int64_t>(row) * stride;
-  uint32_t st = 0;
-  const uint32_t b = msg[2];
-  if (msg[0] != 1u || msg[1] != k || b < 1u || b > 31u) st |= 1u;
-  else if (words && words[row] != 3u + stream_words(k, b) + k) st |= 2u;
-  status[row] = st;
-}
-
-__global__ __launch_bounds__(kWG) void k_wire_tile_sums(const uint32_t* __restrict__ messages, int64_t stride,
-                                                         uint32_t k, uint32_t tiles_per_row,
-                                                         uint32_t* __restrict__ tiles) {
-  __shared__ uint32_t scratch[kWG / 64 + 1];
-  const uint32_t row = blockIdx.y, t = blockIdx.x;
-  const uint32_t* msg = messages + static_cast<int64_t>(row) * stride;
-  const uint32_t b = clamp_width(msg[2]);
-  const uint32_t P = stream_words(k, b);
-  const uint32_t first = t * kWireTile + threadIdx.x * kWirePer;
-  uint32_t sum = 0;
+  uint32_t b = 0;  // tiles beyond the last one leave a zero byte
+  if (t < tiles) {
+    const uint32_t cnt = tile_count(k, t);
+    uint32_t mx = 0;
 #pragma unroll
-  for (int i = 0; i < kWirePer; ++i)
-    if (first + i < k) sum += field_of(msg + 3, P, first + i, b) + 1u;
-  uint32_t total;
-  (void)block_excl_scan<kWG>(sum, scratch, &total);
-  if (threadIdx.x == 0) tiles[static_cast<size_t>(row) * tiles_per_row + t] = total;
+    for (int s = 0; s < 4; ++s) {
+      const uint32_t i = lane + 64u * s;
+      if (i < cnt) {
+        const uint32_t g = gap_of(idx, t * kWireTile + i);
+        mx = g > mx ? g : mx;
+      }
+    }
+    b = width_of(wave_max(mx));
+    if (lane == 0) tile_off[static_cast<size_t>(row) * tiles + t] = tile_words(cnt, b);
+  }
+  if (lane == 0) sb[wave] = b;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    messages[static_cast<int64_t>(row) * stride + 3 + blockIdx.x] = sb[0] | (sb[1] << 8) | (sb[2] << 16) | (sb[3] << 24);
 }
 
-// In place: tile totals -> what lies before each tile.  One workgroup per row.
-__global__ __launch_bounds__(kWG) void k_wire_tile_scan(uint32_t* __restrict__ tiles, uint32_t tiles_per_row) {
+// In place: per-tile amounts -> what lies before each tile; totals[row] (if given) gets the row's sum.
+// One workgroup per row.
+__global__ __launch_bounds__(kWG) void k_wire_tile_scan(uint32_t* __restrict__ tiles, uint32_t tiles_per_row,
+                                                         uint32_t* __restrict__ totals) {
   __shared__ uint32_t scratch[kWG / 64 + 1];
   uint32_t* t = tiles + static_cast<size_t>(blockIdx.x) * tiles_per_row;
   uint32_t carry = 0;
@@ -151,46 +99,179 @@ __global__ __launch_bounds__(kWG) void k_wire_tile_scan(uint32_t* __restrict__ t
     if (i < tiles_per_row) t[i] = carry + before;
     carry += total;
   }
+  if (totals && threadIdx.x == 0) totals[blockIdx.x] = carry;
+}
+
+__global__ __launch_bounds__(kWG) void k_wire_pack_topk(const int32_t* __restrict__ idx_all,
+                                                         const float* __restrict__ val_all, uint32_t k,
+                                                         uint32_t tiles, const uint32_t* __restrict__ tile_off,
+                                                         const uint32_t* __restrict__ totals,
+                                                         uint32_t* __restrict__ messages, int64_t stride,
+                                                         uint32_t* __restrict__ words_out) {
+  __shared__ uint32_t sg[kWaves][kWireTile];
+  const uint32_t row = blockIdx.y, wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t t = blockIdx.x * kWaves + wave;
+  const int32_t* idx = idx_all + static_cast<size_t>(row) * k;
+  const float* val = val_all + static_cast<size_t>(row) * k;
+  uint32_t* msg = messages + static_cast<int64_t>(row) * stride;
+  const uint32_t width_words = (tiles + 3u) >> 2;
+  const uint32_t stream_total = totals[row];
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    msg[0] = 1u;
+    msg[1] = k;
+    msg[2] = kWireTile;
+    words_out[row] = 3u + width_words + stream_total + k;
+  }
+  const bool live = t < tiles;
+  const uint32_t cnt = live ? tile_count(k, t) : 0u;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const uint32_t i = lane + 64u * s;
+    sg[wave][i] = i < cnt ? gap_of(idx, t * kWireTile + i) : 0u;
+  }
+  __syncthreads();
+  if (live) {
+    const uint32_t b = width_byte(msg, t);  // written by the width kernel: 1 .. 31
+    uint32_t* stream = msg + 3 + width_words + tile_off[static_cast<size_t>(row) * tiles + t];
+    const uint32_t nw = tile_words(cnt, b);
+    for (uint32_t w = lane; w < nw; w += 64) {
+      const uint32_t lo = w * 32u;
+      const uint32_t q0 = lo / b;
+      uint32_t q1 = (lo + 31u) / b;
+      if (q1 > cnt - 1u) q1 = cnt - 1u;
+      uint32_t word = 0;
+      for (uint32_t q = q0; q <= q1; ++q) {
+        const uint32_t g = sg[wave][q];
+        const int32_t sh = static_cast<int32_t>(q * b) - static_cast<int32_t>(lo);
+        word |= sh >= 0 ? (g << sh) : (g >> (-sh));  // |sh| <= 31
+      }
+      stream[w] = word;
+    }
+  }
+  uint32_t* values = msg + 3 + width_words + stream_total;
+  const uint32_t step = gridDim.x * kWG;
+  for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < k; q += step) values[q] = __float_as_uint(val[q]);
+}
+
+// Gap i of a tile whose stream starts at `tile` and has nw words (i < cnt, so the field lies inside them).
+__device__ __forceinline__ uint32_t field_of(const uint32_t* __restrict__ tile, uint32_t nw, uint32_t i, uint32_t b) {
+  const uint32_t pos = i * b;
+  const uint32_t w = pos >> 5, sh = pos & 31u;
+  uint64_t two = tile[w];
+  if (w + 1 < nw) two |= static_cast<uint64_t>(tile[w + 1]) << 32;
+  return static_cast<uint32_t>(two >> sh) & ((1u << b) - 1u);
+}
+
+// status[row]: 0 well formed; bit 0: not a message of this kind and size, or a width outside 1 .. 31; bit 1 (set
+// while unpacking): length differs; bit 2 (set while unpacking): a coordinate at or beyond d.
+// Also leaves the words each tile takes (from the clamped widths) in tile_off, to be scanned.
+__global__ __launch_bounds__(kWG) void k_wire_check_topk(const uint32_t* __restrict__ messages, int64_t stride,
+                                                          uint32_t k, uint32_t tiles,
+                                                          uint32_t* __restrict__ tile_off,
+                                                          uint32_t* __restrict__ status) {
+  __shared__ uint32_t st;
+  const uint32_t row = blockIdx.x;
+  const uint32_t* msg = messages + static_cast<int64_t>(row) * stride;
+  if (threadIdx.x == 0) st = (msg[0] != 1u || msg[1] != k || msg[2] != kWireTile) ? 1u : 0u;
+  __syncthreads();
+  bool bad = false;
+  for (uint32_t t = threadIdx.x; t < tiles; t += kWG) {
+    const uint32_t b = width_byte(msg, t);
+    bad |= b < 1u || b > 31u;
+    tile_off[static_cast<size_t>(row) * tiles + t] = tile_words(tile_count(k, t), clamp_width(b));
+  }
+  if (bad) atomicOr(&st, 1u);
+  __syncthreads();
+  if (threadIdx.x == 0) status[row] = st;
+}
+
+// The gaps of a lane's four consecutive entries of tile t (zero beyond the tile) and their number.
+struct LaneGaps {
+  uint32_t gap[4];
+  uint32_t n;
+};
+__device__ __forceinline__ LaneGaps lane_gaps(const uint32_t* __restrict__ msg, uint32_t k, uint32_t tiles, uint32_t t,
+                                              const uint32_t* __restrict__ tile_off_row) {
+  const uint32_t lane = lane_id();
+  const uint32_t cnt = tile_count(k, t);
+  const uint32_t b = clamp_width(width_byte(msg, t));
+  const uint32_t* tile = msg + 3 + ((tiles + 3u) >> 2) + tile_off_row[t];
+  const uint32_t nw = tile_words(cnt, b);
+  LaneGaps g;
+  g.n = 0;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const uint32_t i = lane * 4u + s;
+    g.gap[s] = 0;
+    if (i < cnt) {
+      g.gap[s] = field_of(tile, nw, i, b);
+      g.n = s + 1;
+    }
+  }
+  return g;
+}
+
+__device__ __forceinline__ uint32_t wave_total(uint32_t v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+  return v;
+}
+
+// Coordinates covered by each tile (sum of gap + 1), to be scanned into the coordinate before each tile.
+__global__ __launch_bounds__(kWG) void k_wire_tile_sums(const uint32_t* __restrict__ messages, int64_t stride,
+                                                         uint32_t k, uint32_t tiles,
+                                                         const uint32_t* __restrict__ tile_off,
+                                                         uint32_t* __restrict__ tile_sum) {
+  const uint32_t row = blockIdx.y, wave = threadIdx.x >> 6;
+  const uint32_t t = blockIdx.x * kWaves + wave;
+  if (t >= tiles) return;  // wave-uniform; no barrier below
+  const uint32_t* msg = messages + static_cast<int64_t>(row) * stride;
+  const LaneGaps g = lane_gaps(msg, k, tiles, t, tile_off + static_cast<size_t>(row) * tiles);
+  uint32_t sum = g.n;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) sum += g.gap[s];
+  sum = wave_total(sum);
+  if (lane_id() == 0) tile_sum[static_cast<size_t>(row) * tiles + t] = sum;
 }
 
 __global__ __launch_bounds__(kWG) void k_wire_unpack_topk(const uint32_t* __restrict__ messages, int64_t stride,
-                                                           uint32_t k, uint32_t d, uint32_t tiles_per_row,
-                                                           const uint32_t* __restrict__ tiles,
+                                                           const uint32_t* __restrict__ words, uint32_t k,
+                                                           uint32_t d, uint32_t tiles,
+                                                           const uint32_t* __restrict__ tile_off,
+                                                           const uint32_t* __restrict__ totals,
+                                                           const uint32_t* __restrict__ tile_sum,
                                                            int32_t* __restrict__ idx_out, float* __restrict__ val_out,
                                                            uint32_t* __restrict__ status) {
-  __shared__ uint32_t scratch[kWG / 64 + 1];
-  const uint32_t row = blockIdx.y, t = blockIdx.x;
+  const uint32_t row = blockIdx.y, wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t t = blockIdx.x * kWaves + wave;
   const uint32_t* msg = messages + static_cast<int64_t>(row) * stride;
-  const uint32_t b = clamp_width(msg[2]);
-  const uint32_t P = stream_words(k, b);
-  const uint32_t first = t * kWireTile + threadIdx.x * kWirePer;
-  uint32_t gap[kWirePer];
-  uint32_t sum = 0;
+  const uint32_t width_words = (tiles + 3u) >> 2;
+  const uint32_t stream_total = totals[row];
+  if (blockIdx.x == 0 && threadIdx.x == 0 && words && words[row] != 3u + width_words + stream_total + k)
+    atomicOr(&status[row], 2u);
+  if (t < tiles) {  // wave-uniform
+    const LaneGaps g = lane_gaps(msg, k, tiles, t, tile_off + static_cast<size_t>(row) * tiles);
+    uint32_t mine = g.n;
 #pragma unroll
-  for (int i = 0; i < kWirePer; ++i) {
-    gap[i] = 0;
-    if (first + i < k) {
-      gap[i] = field_of(msg + 3, P, first + i, b);
-      sum += gap[i] + 1u;
-    }
+    for (int s = 0; s < 4; ++s) mine += g.gap[s];
+    // coordinates before this lane's first entry: those before the tile + those of the lanes below
+    uint32_t pos = tile_sum[static_cast<size_t>(row) * tiles + t] + wave_incl_scan(mine) - mine;
+    int32_t* idx = idx_out + static_cast<size_t>(row) * k + t * kWireTile + lane * 4u;
+    bool beyond = false;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (static_cast<uint32_t>(s) < g.n) {
+        const uint32_t j = pos + g.gap[s];
+        beyond |= j >= d;
+        idx[s] = static_cast<int32_t>(j);
+        pos = j + 1u;
+      }
+    if (beyond) atomicOr(&status[row], 4u);
   }
-  uint32_t total;
-  uint32_t pos = tiles[static_cast<size_t>(row) * tiles_per_row + t] + block_excl_scan<kWG>(sum, scratch, &total);
-  int32_t* idx = idx_out + static_cast<size_t>(row) * k;
-  bool beyond = false;
-#pragma unroll
-  for (int i = 0; i < kWirePer; ++i)
-    if (first + i < k) {
-      const uint32_t j = pos + gap[i];  // coordinates before this entry + its gap
-      beyond |= j >= d;
-      idx[first + i] = static_cast<int32_t>(j);
-      pos = j + 1u;
-    }
-  if (beyond) atomicOr(&status[row], 4u);
-  const uint32_t* values = msg + 3 + P;
+  const uint32_t* values = msg + 3 + width_words + stream_total;
   float* val = val_out + static_cast<size_t>(row) * k;
-  for (uint32_t q = t * kWireTile + threadIdx.x; q < (t + 1) * kWireTile && q < k; q += kWG)
-    val[q] = __uint_as_float(values[q]);
+  const uint32_t step = gridDim.x * kWG;
+  for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < k; q += step) val[q] = __uint_as_float(values[q]);
 }
 
 __global__ __launch_bounds__(kWG) void k_wire_pack_blocksign(const uint32_t* __restrict__ bits_all,
@@ -251,13 +332,15 @@ uint32_t copy_groups(uint32_t n, uint64_t items) {
 
 hipError_t wire_encode_topk(const Geometry& geo, const TopkWorkspace& ws, uint32_t* messages, int64_t stride,
                             uint32_t* words_out, hipStream_t stream, Launcher* L) {
-  hipError_t err = fill_u32(ws.wire_max, geo.n, 0u, stream);
-  if (err != hipSuccess) return err;
-  const dim3 grid(copy_groups(geo.n, geo.k), geo.n), wg(kWG);
-  launch(L, kSlotWireEncode, k_wire_gap_max, grid, wg, stream, ws.idx, geo.k, ws.wire_max);
+  const uint32_t tiles = (geo.k + kWireTile - 1) / kWireTile;
+  const dim3 grid((tiles + kWaves - 1) / kWaves, geo.n), wg(kWG);
+  launch(L, kSlotWireEncode, k_wire_tile_width, grid, wg, stream, ws.idx, geo.k, tiles, messages, stride,
+         ws.wire_tile_off);
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotWireEncode, k_wire_pack_topk, grid, wg, stream, ws.idx, ws.val, geo.k, ws.wire_max, messages, stride,
-         words_out);
+  launch(L, kSlotWireEncode, k_wire_tile_scan, dim3(geo.n), wg, stream, ws.wire_tile_off, tiles, ws.wire_total);
+  COMPAMS_CHECK_LAUNCH();
+  launch(L, kSlotWireEncode, k_wire_pack_topk, grid, wg, stream, ws.idx, ws.val, geo.k, tiles, ws.wire_tile_off,
+         ws.wire_total, messages, stride, words_out);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -266,16 +349,20 @@ hipError_t wire_decode_topk(const Geometry& geo, const TopkWorkspace& ws, const 
                             const uint32_t* words, int32_t* idx_out, float* val_out, uint32_t* status,
                             hipStream_t stream, Launcher* L) {
   const uint32_t tiles = (geo.k + kWireTile - 1) / kWireTile;
-  const dim3 wg(kWG), grid(tiles, geo.n);
-  launch(L, kSlotWireDecode, k_wire_check_topk, dim3((geo.n + kWG - 1) / kWG), wg, stream, messages, stride, words,
-         geo.n, geo.k, status);
+  const dim3 grid((tiles + kWaves - 1) / kWaves, geo.n), wg(kWG);
+  uint32_t* none = nullptr;
+  launch(L, kSlotWireDecode, k_wire_check_topk, dim3(geo.n), wg, stream, messages, stride, geo.k, tiles,
+         ws.wire_tile_off, status);
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotWireDecode, k_wire_tile_sums, grid, wg, stream, messages, stride, geo.k, tiles, ws.wire_tiles);
+  launch(L, kSlotWireDecode, k_wire_tile_scan, dim3(geo.n), wg, stream, ws.wire_tile_off, tiles, ws.wire_total);
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotWireDecode, k_wire_tile_scan, dim3(geo.n), wg, stream, ws.wire_tiles, tiles);
+  launch(L, kSlotWireDecode, k_wire_tile_sums, grid, wg, stream, messages, stride, geo.k, tiles, ws.wire_tile_off,
+         ws.wire_tile_sum);
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotWireDecode, k_wire_unpack_topk, grid, wg, stream, messages, stride, geo.k, geo.d, tiles,
-         ws.wire_tiles, idx_out, val_out, status);
+  launch(L, kSlotWireDecode, k_wire_tile_scan, dim3(geo.n), wg, stream, ws.wire_tile_sum, tiles, none);
+  COMPAMS_CHECK_LAUNCH();
+  launch(L, kSlotWireDecode, k_wire_unpack_topk, grid, wg, stream, messages, stride, words, geo.k, geo.d, tiles,
+         ws.wire_tile_off, ws.wire_total, ws.wire_tile_sum, idx_out, val_out, status);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }

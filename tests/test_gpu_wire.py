@@ -71,7 +71,8 @@ def test_topk_message_with_the_widest_gaps():
     g[1, 1], g[1, d - 2] = -3.0, 2.0
     p.step(g, 1e-3, label="wide gaps")
     m, wn = check_topk_messages(p, "wide gaps")
-    assert m[0, 2] == 22 and wn[0] == 3 + 2 + 2      # gap d - 2 = 2 999 998 needs 22 bits; 44 bits = 2 words
+    # gap d - 2 = 2 999 998 needs 22 bits; one tile of 2 gaps: 44 bits = 2 words after the one width word
+    assert m[0, 2] == 256 and m[0, 3] == 22 and wn[0] == 3 + 1 + 2 + 2
     p.close()
 
 
@@ -101,14 +102,14 @@ def test_decode_flags_malformed_messages_and_stays_in_bounds():
     torch.cuda.synchronize()
     bad = msgs.clone()
     bad[0, 0] = 7                       # not a top-k message
-    bad[1, 2] = 0                       # impossible gap width
-    bad[2, 3:10] = -1                   # gaps of all ones: coordinates run past d
+    bad[1, 3] = 0x2000                  # first tile: width 0, second tile: width 32
+    bad[2, 4:12] = -1                   # gaps of all ones in the first tile: coordinates run past d
     wrong_words = words.clone()
     wrong_words[3] += 1                 # a length that does not fit the header
     a, b, status = p.gpu.compams_decode(bad, wrong_words)
     torch.cuda.synchronize()
     st = status.cpu().numpy()
-    assert st[0] & 1 and st[1] & 1 and st[2] & 4 and st[3] == 2, st
+    assert st[0] & 1 and st[1] & 1 and st[2] == 4 and st[3] == 2, st
     # the untouched message still decodes to what was sent
     assert np.array_equal(a[3].cpu().numpy(), p.cpu.get("idx")[3])
     p.close()

@@ -17,34 +17,49 @@ def f32_words(values):
 
 
 def test_topk_message_worked_out_by_hand():
-    # coordinates 5, 6, 100, 101: gaps 5, 0, 93, 0; the widest gap 93 needs 7 bits;
+    # coordinates 5, 6, 100, 101: gaps 5, 0, 93, 0; one tile; its widest gap 93 needs 7 bits (width word 0x07);
     # stream = 5 + 0 * 2^7 + 93 * 2^14 + 0 * 2^21 = 1 523 717 = 0x174005, one word
     msg = O.wire_encode_topk([5, 6, 100, 101], [1.0, 2.0, 3.0, 4.0])
-    assert msg.tolist() == [1, 4, 7, 0x174005] + f32_words([1.0, 2.0, 3.0, 4.0])
+    assert msg.tolist() == [1, 4, 256, 0x07, 0x174005] + f32_words([1.0, 2.0, 3.0, 4.0])
+
+
+def test_topk_message_of_two_tiles_worked_out_by_hand():
+    # 258 coordinates: 0 .. 255 (a full tile of zero gaps: width 1, 256 bits = 8 zero words), then 1255 and 1258
+    # (gaps 999 and 2: width 10; stream word 999 + 2 * 2^10 = 3047).  Width word: 0x0a01.
+    idx = list(range(256)) + [1255, 1258]
+    msg = O.wire_encode_topk(idx, np.ones(258))
+    assert msg[:4].tolist() == [1, 258, 256, 0x0A01]
+    assert msg[4:13].tolist() == [0] * 8 + [3047]
+    assert msg.size == 4 + 9 + 258
 
 
 def test_topk_message_of_consecutive_coordinates_uses_one_bit_per_gap():
     # gaps are all zero: width 1 (never 0), stream of ceil(40 / 32) = 2 zero words
     msg = O.wire_encode_topk(np.arange(40), np.ones(40))
-    assert msg[:5].tolist() == [1, 40, 1, 0, 0] and msg.size == 3 + 2 + 40
+    assert msg[:6].tolist() == [1, 40, 256, 1, 0, 0] and msg.size == 3 + 1 + 2 + 40
 
 
-def test_topk_gap_stream_is_the_little_endian_big_integer():
+def test_topk_gap_stream_is_the_little_endian_big_integer_of_each_tile():
     rng = np.random.default_rng(5)
-    for d, k in [(1000, 37), (1 << 20, 5000), (70000, 70000), (50, 1), ((1 << 31) - 1, 300)]:
-        idx = np.sort(rng.choice(d, size=k, replace=False)) if d < (1 << 22) else \
+    for d, k in [(1000, 37), (1 << 20, 5000), (70000, 70000), (50, 1), ((1 << 31) - 1, 300), (1 << 22, 1025)]:
+        idx = np.sort(rng.choice(d, size=k, replace=False)) if d <= (1 << 22) else \
             np.unique(rng.integers(0, d, size=2 * k))[:k]
         if k == 300:
             idx[-1] = d - 1  # the largest coordinate the library admits
         val = rng.standard_normal(k).astype(np.float32)
         msg = O.wire_encode_topk(idx, val)
         gaps = [int(idx[0])] + [int(idx[q]) - int(idx[q - 1]) - 1 for q in range(1, k)]
-        b = max(1, max(gaps).bit_length())
-        big = 0
-        for q, gap in enumerate(gaps):
-            big |= gap << (q * b)
-        nw = (k * b + 31) // 32
-        want = [1, k, b] + [(big >> (32 * w)) & 0xFFFFFFFF for w in range(nw)] + f32_words(val)
+        tiles = [gaps[i:i + 256] for i in range(0, k, 256)]
+        width_words = [0] * ((len(tiles) + 3) // 4)
+        stream = []
+        for t, tile in enumerate(tiles):
+            b = max(1, max(tile).bit_length())
+            width_words[t // 4] |= b << (8 * (t % 4))
+            big = 0
+            for i, gap in enumerate(tile):
+                big |= gap << (i * b)
+            stream += [(big >> (32 * w)) & 0xFFFFFFFF for w in range((len(tile) * b + 31) // 32)]
+        want = [1, k, 256] + width_words + stream + f32_words(val)
         assert msg.tolist() == want
         i2, v2 = O.wire_decode_topk(msg, k, d)
         assert np.array_equal(i2, idx) and np.array_equal(v2.view(np.uint32), val.view(np.uint32))
@@ -62,7 +77,13 @@ def test_topk_decode_rejects_what_is_not_a_message():
     bad = msg.copy(); bad[0] = 2
     with pytest.raises(ValueError):
         O.wire_decode_topk(bad, 4, 102)
-    bad = msg.copy(); bad[2] = 0
+    bad = msg.copy(); bad[2] = 128      # another tile size
+    with pytest.raises(ValueError):
+        O.wire_decode_topk(bad, 4, 102)
+    bad = msg.copy(); bad[3] = 0        # a width of zero bits
+    with pytest.raises(ValueError):
+        O.wire_decode_topk(bad, 4, 102)
+    bad = msg.copy(); bad[3] = 32       # a width no coordinate gap can need
     with pytest.raises(ValueError):
         O.wire_decode_topk(bad, 4, 102)
 
@@ -94,7 +115,7 @@ def test_messages_of_a_step_round_trip_and_match_the_papers_accounting():
         msg = O.wire_encode_topk(idx[i], val[i])
         i2, v2 = O.wire_decode_topk(msg, w.k, w.d)
         assert np.array_equal(i2, idx[i]) and np.array_equal(v2.view(np.uint32), val[i].view(np.uint32))
-        assert 32 * w.k < 32 * msg.size < 64 * w.k + 96
+        assert 32 * w.k < 32 * msg.size < 64 * w.k + 128
     o.close()
     assert 32 * w.d / (32 * w.k) == pytest.approx(100.0, rel=0.01)
 
