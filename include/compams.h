@@ -205,6 +205,26 @@ int compams_encode(compams_ctx* ctx, uint32_t* messages, int64_t stride_words, u
 int compams_decode(compams_ctx* ctx, const uint32_t* messages, int64_t stride_words, const uint32_t* words,
                    void* out_a, void* out_b, uint32_t* status_out, void* hip_stream);
 
+/* ---- The two halves of a step ---------------------------------------------------------------------------
+ * Algorithm 2 as printed has the workers and the server on different machines.  compams_step() runs both
+ * halves on one device; these two calls run them apart, with the packed messages in between.
+ *
+ * compams_worker_step: the workers' lines for the context's n rows: x = e + g, the compressor, the error
+ *   update (possibly left pending, see compams_step).  Leaves the messages in the workspace (compams_state
+ *   LAST_*, compams_encode).  Neither reads nor writes theta, m, v, vhat.  COMPAMS_BAD_STATE for COMPAMS_NONE
+ *   (nothing is compressed: the message is the gradient row itself).
+ * compams_server_step: the server's lines from n packed messages (laid out as for compams_decode; message i
+ *   is worker i in the fixed order of the average): unpacks them into the workspace, adds them in that order,
+ *   divides by n and applies the AMSGrad lines with learning rate lr.  Reads no gradient; touches e only to
+ *   apply a residual update of this same context that is still pending.  status_out: as for compams_decode; a
+ *   message that is not well formed still contributes whatever it unpacks to (never read out of bounds), so
+ *   check status_out.
+ * compams_worker_step + compams_encode on one context followed by compams_server_step on a context of the
+ * same configuration gives, bit for bit, the state that compams_step gives. */
+int compams_worker_step(compams_ctx* ctx, const float* g, void* hip_stream);
+int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stride_words, const uint32_t* words,
+                        float lr, uint32_t* status_out, void* hip_stream);
+
 /* A plain streaming copy of `bytes` bytes (multiple of 16, both pointers DEVICE and 16-byte aligned) with
  * the same launch style as the step's dense kernels: the measured bandwidth ceiling that reports set
  * beside the step's figures, and the known-size kernel that hardware counters are calibrated against. */

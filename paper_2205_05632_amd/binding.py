@@ -27,7 +27,7 @@ _STATE_DTYPE = {"last_idx": torch.int32, "last_signbits": torch.int32, "last_thr
 
 EXPORTS = ["compams_workspace_size", "compams_init", "compams_step", "compams_state", "compams_set_option",
            "compams_profile_enable", "compams_profile_read", "compams_destroy", "compams_strerror", "compams_copy",
-           "compams_wire_capacity", "compams_encode", "compams_decode"]
+           "compams_wire_capacity", "compams_encode", "compams_decode", "compams_worker_step", "compams_server_step"]
 
 
 class compams_config(ctypes.Structure):
@@ -76,6 +76,9 @@ def lib():
         L.compams_encode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
         L.compams_decode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.compams_worker_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.compams_server_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                          ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -214,6 +217,25 @@ class Compams:
                                         None if words is None else words.data_ptr(), a.data_ptr(), b.data_ptr(),
                                         status.data_ptr(), _current_stream_handle()), "compams_decode")
         return a, b, status
+
+    # -- the two halves of a step ----------------------------------------------------------------
+    def compams_worker_step(self, g: torch.Tensor):
+        """The workers' lines only: compresses, updates e, leaves the messages for compams_encode."""
+        assert g.dtype == torch.float32 and g.is_cuda and g.is_contiguous()
+        assert g.shape == (self.n, self.ld), f"g must be {self.n} x {self.ld}, got {tuple(g.shape)}"
+        with torch.cuda.device(self.device):
+            _check(lib().compams_worker_step(self._h, g.data_ptr(), _current_stream_handle()), "compams_worker_step")
+
+    def compams_server_step(self, messages: torch.Tensor, words, lr: float) -> torch.Tensor:
+        """The server's lines from n packed messages; returns the per-message status words."""
+        assert messages.dtype == torch.int32 and messages.is_cuda and messages.is_contiguous()
+        assert messages.shape[0] == self.n
+        status = torch.empty(self.n, dtype=torch.int32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(lib().compams_server_step(self._h, messages.data_ptr(), messages.shape[1],
+                                             None if words is None else words.data_ptr(), lr, status.data_ptr(),
+                                             _current_stream_handle()), "compams_server_step")
+        return status
 
     # -- extras ----------------------------------------------------------------------------------
     def set_option(self, option: int, value: int):

@@ -270,11 +270,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
   return COMPAMS_OK;
 }
 
-int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream) {
-  if (!ctx || !g) return COMPAMS_INVALID_ARG;
-  if (reinterpret_cast<uintptr_t>(g) % 16 != 0) return COMPAMS_BAD_ALIGNMENT;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const compams_config& c = ctx->cfg;
+static AmsParams ams_params(const compams_config& c, float lr) {
   AmsParams ap;
   ap.beta1 = c.beta1;
   ap.beta2 = c.beta2;
@@ -284,16 +280,28 @@ int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream) {
   ap.lr = lr;
   ap.nf = static_cast<float>(c.n);
   ap.eps_out = c.eps_mode == COMPAMS_EPS_OUT_SQRT;
+  return ap;
+}
+
+// The whole step, or only the workers' lines of it.
+static int step_impl(compams_ctx* ctx, const float* g, float lr, bool workers_only, void* hip_stream) {
+  if (!ctx || !g) return COMPAMS_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(g) % 16 != 0) return COMPAMS_BAD_ALIGNMENT;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const compams_config& c = ctx->cfg;
+  if (workers_only && c.compressor == COMPAMS_NONE) return COMPAMS_BAD_STATE;  // the message is g itself
+  const AmsParams ap = ams_params(c, lr);
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
   try {
     if (c.compressor == COMPAMS_TOPK) {
       const bool may_predict = ctx->steps > 0 && ctx->tkopt.predict && !ctx->tkopt.force_dense;
       err = topk_step(ctx->geo, ctx->tk, ctx->tkopt, ap, g, c.e, c.theta, c.m, c.v, c.vhat, may_predict,
-                      ctx->clear_pending, stream, L);
+                      ctx->clear_pending, workers_only, stream, L);
       ctx->clear_pending = true;
     } else if (c.compressor == COMPAMS_BLOCKSIGN) {
-      err = blocksign_step(ctx->geo, ctx->bs, ap, g, c.e, c.theta, c.m, c.v, c.vhat, ctx->clear_pending, stream, L);
+      err = blocksign_step(ctx->geo, ctx->bs, ap, g, c.e, c.theta, c.m, c.v, c.vhat, ctx->clear_pending, workers_only,
+                           stream, L);
       ctx->clear_pending = ctx->bs.uniform4096 == 0;  // the single-pass layout writes its residuals itself
     } else {
       err = none_step(ctx->geo, ap, g, c.theta, c.m, c.v, c.vhat, stream, L);
@@ -305,6 +313,52 @@ int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream) {
   if (err != hipSuccess || (L && L->failed)) return COMPAMS_HIP_ERROR;
   ++ctx->steps;
   return COMPAMS_OK;
+}
+
+int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream) {
+  return step_impl(ctx, g, lr, false, hip_stream);
+}
+
+int compams_worker_step(compams_ctx* ctx, const float* g, void* hip_stream) {
+  return step_impl(ctx, g, 0.0f, true, hip_stream);
+}
+
+int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stride_words, const uint32_t* words,
+                        float lr, uint32_t* status_out, void* hip_stream) {
+  if (!ctx || !messages || !status_out) return COMPAMS_INVALID_ARG;
+  const compams_config& c = ctx->cfg;
+  if (c.compressor == COMPAMS_NONE) return COMPAMS_BAD_STATE;
+  if (stride_words < static_cast<int64_t>(compams_wire_capacity(&c))) return COMPAMS_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(messages) % 4 != 0 || reinterpret_cast<uintptr_t>(status_out) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(words) % 4 != 0)
+    return COMPAMS_BAD_ALIGNMENT;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // The messages are unpacked into the workspace arrays that a pending residual update of this context still
+  // needs (the last lists, the last scales): apply it first.
+  if (ctx->clear_pending) {
+    if (ctx->last_stream != stream && hipStreamSynchronize(ctx->last_stream) != hipSuccess) return COMPAMS_HIP_ERROR;
+    ctx->last_stream = stream;
+    if (settle_residuals(ctx) != hipSuccess) return COMPAMS_HIP_ERROR;
+  }
+  const AmsParams ap = ams_params(c, lr);
+  Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
+  hipError_t err;
+  try {
+    if (c.compressor == COMPAMS_TOPK) {
+      err = wire_decode_topk(ctx->geo, ctx->tk, messages, stride_words, words, ctx->tk.idx, ctx->tk.val, status_out,
+                             stream, L);
+      if (err == hipSuccess)
+        err = topk_server_step(ctx->geo, ctx->tk, ctx->tkopt, ap, c.theta, c.m, c.v, c.vhat, stream, L);
+    } else {
+      err = wire_decode_blocksign(ctx->geo, messages, stride_words, words, ctx->bs.bits, ctx->bs.scales, status_out,
+                                  stream, L);
+      if (err == hipSuccess) err = blocksign_server_step(ctx->geo, ctx->bs, ap, c.theta, c.m, c.v, c.vhat, stream, L);
+    }
+  } catch (...) {
+    return COMPAMS_HIP_ERROR;
+  }
+  ctx->last_stream = stream;
+  return err == hipSuccess && !(L && L->failed) ? COMPAMS_OK : COMPAMS_HIP_ERROR;
 }
 
 int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* count) {

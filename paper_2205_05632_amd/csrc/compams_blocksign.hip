@@ -798,7 +798,7 @@ __global__ __launch_bounds__(kWG) void k_copy16(float* __restrict__ dst, const f
 
 hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, const float* g,
                           float* e, float* theta, float* m, float* v, float* vhat, bool residual_pending,
-                          hipStream_t stream, Launcher* L) {
+                          bool workers_only, hipStream_t stream, Launcher* L) {
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
   // these passes hide their latencies through occupancy: many workgroups per row
   const dim3 grid_rows(G, geo.n), grid_2(G * 2, geo.n), grid_4(G * 4, geo.n), wg(kWG);
@@ -818,8 +818,15 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
     launch(L, kSlotBsPass2, k_bs_pass2, grid_rows, wg, stream, e, geo, ws, 1);
     COMPAMS_CHECK_LAUNCH();
   }
-  launch(L, kSlotBsAms, k_bs_amsgrad, dim3((geo.num_chunks * kBsSplit + kWaves - 1) / kWaves), wg, stream, theta, m, v,
-         vhat, geo, ws, ap);
+  if (workers_only) return hipSuccess;
+  return blocksign_server_step(geo, ws, ap, theta, m, v, vhat, stream, L);
+}
+
+// The server's lines from the sign words and scales that sit in the workspace.
+hipError_t blocksign_server_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, float* theta,
+                                 float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
+  launch(L, kSlotBsAms, k_bs_amsgrad, dim3((geo.num_chunks * kBsSplit + kWaves - 1) / kWaves), dim3(kWG), stream, theta,
+         m, v, vhat, geo, ws, ap);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }

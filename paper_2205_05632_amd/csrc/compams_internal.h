@@ -150,11 +150,16 @@ struct Launcher;  // host-side helper that brackets launches with events (compam
 // Host-side launch entry points, one per compressor (defined next to their kernels).
 hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
                      const float* g, float* e, float* theta, float* m, float* v, float* vhat,
-                     bool first_pass_may_predict, bool clear_pending, hipStream_t stream, Launcher* L);
+                     bool first_pass_may_predict, bool clear_pending, bool workers_only, hipStream_t stream,
+                     Launcher* L);
+hipError_t topk_server_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
+                            float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L);
 hipError_t topk_apply_clear(const Geometry& geo, const TopkWorkspace& ws, float* e, hipStream_t stream);
 hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, const float* g,
                           float* e, float* theta, float* m, float* v, float* vhat, bool residual_pending,
-                          hipStream_t stream, Launcher* L);
+                          bool workers_only, hipStream_t stream, Launcher* L);
+hipError_t blocksign_server_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, float* theta,
+                                 float* m, float* v, float* vhat, hipStream_t stream, Launcher* L);
 hipError_t blocksign_apply_residual(const Geometry& geo, const BlocksignWorkspace& ws, float* e, hipStream_t stream);
 hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, float* theta, float* m, float* v,
                      float* vhat, hipStream_t stream, Launcher* L);

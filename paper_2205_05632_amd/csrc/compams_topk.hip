@@ -886,7 +886,13 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
   return v;
 }
 
+// ROLE: kWholeStep runs all phases; kWorkerHalf stops after phase 1 (the workers' lines of Algorithm 2: the
+// lists are the messages); kServerHalf starts at phase 2 from lists that were put into the workspace (the
+// server's lines; where a chunk's slice of each list starts was found by k_topk_list_offsets).
 // (eight wavefronts per SIMD: the streaming phase needs the occupancy more than phase 1 needs registers)
+enum : int { kWholeStep = 0, kWorkerHalf = 1, kServerHalf = 2 };
+
+template <int ROLE>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_topk_final(
     float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v, float* __restrict__ vhat,
     const float* __restrict__ e, Geometry geo, TopkWorkspace ws, TopkOptions opt, AmsParams p) {
@@ -895,12 +901,20 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   const uint32_t c = blockIdx.x;
   const uint32_t base = c * kChunk;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  for (int t = threadIdx.x; t < kChunk; t += kWG) gs[t] = 0.0f;
-  if (c == 0)  // the next step's first pass allocates its candidate lists from the start
+  if (ROLE != kWorkerHalf)
+    for (int t = threadIdx.x; t < kChunk; t += kWG) gs[t] = 0.0f;
+  if (ROLE != kServerHalf && c == 0)  // the next step's first pass allocates its candidate lists from the start
     for (uint32_t i = threadIdx.x; i < geo.n; i += kWG) ws.rows[i].cursor = 0;
   const uint32_t my_block = c / geo.count_cpw;  // count blocks before this chunk's
 
   for (uint32_t i0 = 0; i0 < geo.n; i0 += kTileWorkers) {
+    if (ROLE == kServerHalf) {
+      if (threadIdx.x < kTileWorkers && i0 + threadIdx.x < geo.n) {
+        const uint32_t* so = ws.sel_off + static_cast<size_t>(i0 + threadIdx.x) * (geo.num_chunks + 1) + c;
+        sh_lo[threadIdx.x] = so[0];
+        sh_hi[threadIdx.x] = so[1];
+      }
+    } else {
     // ---- phase 1a: positions, for this wavefront's workers of the tile (all loads issued together) ----
     {
       uint4 rec[kPerWave];
@@ -1000,6 +1014,8 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         at += total;
       });
     }
+    }  // ROLE != kServerHalf
+    if (ROLE == kWorkerHalf) continue;
     __syncthreads();  // the chunk's list entries and their positions are visible to the whole workgroup
 
     // ---- phase 2 ----
@@ -1056,6 +1072,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     }
   }
 
+  if (ROLE == kWorkerHalf) return;
 #pragma unroll
   for (int r = 0; r < kChunk / (kWG * 4); ++r) {
     const uint32_t t = r * kWG * 4 + threadIdx.x * 4;
@@ -1082,6 +1099,29 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   }
 }
 
+// Where each chunk's slice of a worker's ascending coordinate list starts: sel_off[c] = number of listed
+// coordinates below c * kChunk, for c = 0 .. num_chunks.  The thread of entry q fills the chunks between its
+// predecessor's chunk (exclusive) and its own (inclusive); the last entry also fills the rest up to num_chunks.
+__global__ __launch_bounds__(kWG) void k_topk_list_offsets(Geometry geo, TopkWorkspace ws) {
+  const uint32_t row = blockIdx.y;
+  const int32_t* idx = ws.idx + static_cast<size_t>(row) * geo.k;
+  uint32_t* so = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
+  const uint32_t step = gridDim.x * kWG;
+  for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < geo.k; q += step) {
+    uint32_t cur = static_cast<uint32_t>(idx[q]) / kChunk;
+    if (cur >= geo.num_chunks) cur = geo.num_chunks - 1;  // a coordinate beyond d (flagged by the unpacking)
+    uint32_t from = 0;
+    if (q) {
+      uint32_t prev = static_cast<uint32_t>(idx[q - 1]) / kChunk;
+      if (prev >= geo.num_chunks) prev = geo.num_chunks - 1;
+      from = prev + 1;
+    }
+    for (uint32_t c = from; c <= cur; ++c) so[c] = q;
+    if (q + 1 == geo.k)
+      for (uint32_t c = cur + 1; c <= geo.num_chunks; ++c) so[c] = geo.k;
+  }
+}
+
 // The residual at the coordinates selected in the last step becomes zero (the worker's error update of
 // Algorithm 2 for the kept coordinates), applied on request.
 __global__ __launch_bounds__(kWG) void k_topk_apply_clear(float* __restrict__ e, Geometry geo, TopkWorkspace ws) {
@@ -1105,7 +1145,9 @@ __global__ __launch_bounds__(kWG) void k_topk_apply_clear(float* __restrict__ e,
 
 hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
                      const float* g, float* e, float* theta, float* m, float* v, float* vhat,
-                     bool first_pass_may_predict, bool clear_pending, hipStream_t stream, Launcher* L) {
+                     bool first_pass_may_predict, bool clear_pending, bool workers_only, hipStream_t stream,
+                     Launcher* L) {
+  const int role = workers_only ? kWorkerHalf : kWholeStep;
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
   const uint32_t GA = groups_first_pass(geo.n, geo.num_chunks, kWavesA);
   const dim3 grid_rows(G, geo.n), wg(kWG), grid_a(GA, geo.n), wga(kWGA);
@@ -1124,7 +1166,26 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   const uint32_t count_blocks = (geo.num_chunks + geo.count_cpw - 1) / geo.count_cpw;  // <= kMaxCountBlocks
   launch(L, kSlotCount, k_topk_count, dim3(count_blocks, geo.n), wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotTopkFinal, k_topk_final, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws, opt, ap);
+  if (role == kWorkerHalf)
+    launch(L, kSlotTopkFinal, k_topk_final<kWorkerHalf>, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws,
+           opt, ap);
+  else
+    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep>, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws,
+           opt, ap);
+  COMPAMS_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+// The server's lines from lists that sit in the workspace (idx, val: n ascending lists of k entries).
+hipError_t topk_server_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
+                            float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
+  uint32_t groups = (geo.k + kWG * 4 - 1) / (kWG * 4);
+  if (groups > 256) groups = 256;
+  launch(L, kSlotTopkFinal, k_topk_list_offsets, dim3(groups, geo.n), dim3(kWG), stream, geo, ws);
+  COMPAMS_CHECK_LAUNCH();
+  const float* no_e = nullptr;
+  launch(L, kSlotTopkFinal, k_topk_final<kServerHalf>, dim3(geo.num_chunks), dim3(kWG), stream, theta, m, v, vhat, no_e,
+         geo, ws, opt, ap);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
