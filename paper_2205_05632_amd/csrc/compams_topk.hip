@@ -177,9 +177,6 @@ __device__ __forceinline__ bool last_group_of_row(uint32_t* ticket, uint32_t gro
 __device__ __forceinline__ uint32_t load_agent(const uint32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void store_agent(uint32_t* p, uint32_t v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // Many device-scope loads in flight at once.  The compiler waits for each atomic load before it issues the
 // next, which turns a row-wide step of a few thousand words into a chain of memory round trips; buffer loads
@@ -485,7 +482,7 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
   const uint32_t row = blockIdx.y;
   for (int b = threadIdx.x; b < kNB0; b += kWGA) lh[b] = 0;
   if (PRED)
-    for (int b = threadIdx.x; b < kTracked * kNB1; b += kWGA) lh1[b] = 0;
+    for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWGA) lh1[b] = 0;
   __syncthreads();
   const float* gr = g + static_cast<int64_t>(row) * geo.ld;
   float* er = e + static_cast<int64_t>(row) * geo.ld;
@@ -518,7 +515,7 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
   }
   uint32_t* gh1 = ws.hist1x + static_cast<size_t>(row) * kTracked * kNB1;
   if (PRED && pred)
-    for (int b = threadIdx.x; b < kTracked * kNB1; b += kWGA) {
+    for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWGA) {
       const uint32_t h = lh1[b];
       if (h) atomicAdd(&gh1[b], h);
     }
@@ -570,7 +567,7 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
 #pragma unroll
       for (int i = 0; i < kNB1 / kWGA; ++i) lh[i * kWGA + threadIdx.x] = x[i];
     }
-    for (int b = threadIdx.x; b < kTracked * kNB1; b += kWGA) gh1[b] = 0;
+    for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWGA) gh1[b] = 0;
     __syncthreads();
     if (which) resolve_level1<kWGA>(rowp, sh_bstar, sh_need, lh, suf, out2);
   }
