@@ -28,7 +28,7 @@ def algorithmic_bytes(w, comp):
     read+write theta, m, v, vhat; plus writing and reading the compressed messages."""
     n, d = w.n, w.d
     dense = 12 * n * d + 32 * d
-    if comp == "topk":
+    if comp in ("topk", "topk_blocks"):
         return dense + 16 * n * w.k
     if comp == "blocksign":
         M = len(w.block_offsets()) - 1
@@ -91,11 +91,18 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     w = W.get(args.workload)
-    comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE}[w.compressor]
-    ctx = B.Compams(w.n, w.d, W.theta0(w, dev), compressor=comp, k=w.k, block_offsets=w.block_offsets(), device=dev)
-    if args.no_predict:
+    per_block = w.compressor == "topk_blocks"   # one context per layer tensor: no per-kernel events, no codec
+    if per_block:
+        comp = None
+        ctx = B.CompamsBlockTopk(w.n, w.d, W.theta0(w, dev), w.block_offsets(), w.block_k(), device=dev)
+        args.no_kernel_events = True
+    else:
+        comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE}[w.compressor]
+        ctx = B.Compams(w.n, w.d, W.theta0(w, dev), compressor=comp, k=w.k, block_offsets=w.block_offsets(),
+                        device=dev)
+    if args.no_predict and not per_block:
         ctx.set_option(B.OPT_PREDICT, 0)
-    if args.force_dense:
+    if args.force_dense and not per_block:
         ctx.set_option(B.OPT_FORCE_DENSE, 1)
 
     total = args.warmup + args.steps
@@ -111,27 +118,29 @@ def main():
     # the measured time); --kernels brackets every kernel instead, which costs a few microseconds per kernel
     event_mode = 0 if args.no_kernel_events else (1 if args.kernels else 2)
     stride = 1 if args.kernels else max(1, args.event_stride)
-    ctx.profile_enable(0)
+    if not per_block:
+        ctx.profile_enable(0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(args.warmup, total):
         if event_mode and stride > 1:
             ctx.profile_enable(event_mode if (t - args.warmup) % stride == 0 else 0)  # host-side switch only
-        elif t == args.warmup:
+        elif t == args.warmup and not per_block:
             ctx.profile_enable(event_mode)
         ctx.compams_step(grads[t], w.lr)
         if args.settle_each_step:
             ctx.compams_state("e")
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    prof = ctx.profile_read()
-    ctx.profile_enable(0)
+    prof = {} if per_block else ctx.profile_read()
+    if not per_block:
+        ctx.profile_enable(0)
     sec = t1 - t0
     ms_per_step = sec / args.steps * 1e3
     steps_per_s = args.steps / sec
 
     bmin = algorithmic_bytes(w, w.compressor)
-    kname, kbytes = dominant_kernel(w.compressor)
+    kname, kbytes = dominant_kernel("topk" if per_block else w.compressor)
     roofline = None
     kernel_sum_ms = None
     if prof:
@@ -181,7 +190,7 @@ def main():
     # the last step's messages on the wire: sizes (32 bits per word, the accounting of the paper's experiments
     # section) and the time to pack and unpack them; not part of `value`
     wire = None
-    if comp != B.NONE:
+    if comp is not None and comp != B.NONE:
         reps = 20
         msgs, words = ctx.compams_encode()      # warm-up: first launches load the kernels
         ctx.compams_decode(msgs, words)
@@ -207,9 +216,9 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import compams_oracle as O
-        ocomp = {"topk": O.TOPK, "blocksign": O.BLOCKSIGN, "none": O.NONE}[w.compressor]
+        ocomp = {"topk": O.TOPK, "blocksign": O.BLOCKSIGN, "none": O.NONE, "topk_blocks": O.TOPK_BLOCKS}[w.compressor]
         orc = O.Oracle(w.n, w.d, W.theta0(w, dev).cpu().numpy(), compressor=ocomp, k=w.k,
-                       block_offsets=w.block_offsets())
+                       block_offsets=w.block_offsets(), block_k=w.block_k() if per_block else None)
         host = [grads[t][:, : w.d].cpu().contiguous().numpy() for t in range(args.cpu_steps)]
         c0 = time.perf_counter()
         for g in host:

@@ -41,7 +41,7 @@
 
 namespace {
 
-enum { C_NONE = 0, C_TOPK = 1, C_BLOCKSIGN = 2 };
+enum { C_NONE = 0, C_TOPK = 1, C_BLOCKSIGN = 2, C_TOPK_BLOCKS = 3 };
 enum { EPS_IN_SQRT = 0, EPS_OUT_SQRT = 1 };
 
 inline uint32_t bits_of(float x) {
@@ -161,6 +161,7 @@ struct Oracle {
   int64_t k;
   int64_t M;
   std::vector<int64_t> off;  // M+1 block offsets
+  std::vector<int64_t> kb;   // top-k per block: how many coordinates each block keeps
   float beta1, beta2, eps;
   int eps_mode;
   int64_t t;  // iterations done
@@ -190,6 +191,30 @@ void worker_topk(Oracle& o, int i) {
     val[q] = o.x[j];
     c[j] = o.x[j];
     e[j] = 0.0f;
+  }
+}
+
+// Definition 1 applied to every block on its own: block b keeps its kb[b] largest magnitudes.  The worker's list
+// holds the kept coordinates of block 0, then of block 1, ...: ascending over the whole row.
+void worker_topk_blocks(Oracle& o, int i) {
+  const int64_t d = o.d, k = o.k;
+  float* e = &o.e[static_cast<size_t>(i) * d];
+  float* c = &o.ctil[static_cast<size_t>(i) * d];
+  int32_t* idx = &o.last_idx[static_cast<size_t>(i) * k];
+  float* val = &o.last_val[static_cast<size_t>(i) * k];
+  for (int64_t j = 0; j < d; ++j) { c[j] = 0.0f; e[j] = o.x[j]; }
+  int64_t at = 0;
+  for (int64_t b = 0; b < o.M; ++b) {
+    const int64_t lo = o.off[b], len = o.off[b + 1] - lo;
+    topk_select(o.x.data() + lo, len, o.kb[b], idx + at);
+    for (int64_t q = 0; q < o.kb[b]; ++q) {
+      const int32_t j = static_cast<int32_t>(lo) + idx[at + q];
+      idx[at + q] = j;
+      val[at + q] = o.x[j];
+      c[j] = o.x[j];
+      e[j] = 0.0f;
+    }
+    at += o.kb[b];
   }
 }
 
@@ -227,6 +252,7 @@ void step(Oracle& o, const float* g, float lr) {
     const float* ei = &o.e[static_cast<size_t>(i) * d];
     for (int64_t j = 0; j < d; ++j) o.x[j] = ei[j] + gi[j];  // corrected gradient
     if (o.compressor == C_TOPK) worker_topk(o, i);
+    else if (o.compressor == C_TOPK_BLOCKS) worker_topk_blocks(o, i);
     else if (o.compressor == C_BLOCKSIGN) worker_blocksign(o, i);
     else worker_identity(o, i);
   }
@@ -285,6 +311,31 @@ void* oracle_compams_create(int n, int64_t d, int compressor, int64_t k, int64_t
     o->last_bits.assign(sn * static_cast<size_t>((d + 31) / 32), 0u);
     o->last_mu.assign(sn * static_cast<size_t>(o->M), 0.0f);
   }
+  return o;
+}
+
+// Top-k per block: block b = [block_offsets[b], block_offsets[b+1]) keeps block_k[b] coordinates (1 .. its size).
+void* oracle_compams_create_topk_blocks(int n, int64_t d, int64_t num_blocks, const int64_t* block_offsets,
+                                        const int64_t* block_k, float beta1, float beta2, float eps, int eps_mode,
+                                        const float* theta0) {
+  if (num_blocks < 1 || !block_offsets || !block_k) return nullptr;
+  int64_t total = 0;
+  for (int64_t b = 0; b < num_blocks; ++b) {
+    const int64_t len = block_offsets[b + 1] - block_offsets[b];
+    if (len < 1 || block_k[b] < 1 || block_k[b] > len) return nullptr;
+    total += block_k[b];
+  }
+  // created as a block layout (validates the offsets), then turned into the per-block top-k
+  Oracle* o = static_cast<Oracle*>(oracle_compams_create(n, d, C_BLOCKSIGN, 0, num_blocks, block_offsets, beta1, beta2,
+                                                          eps, eps_mode, theta0));
+  if (!o) return nullptr;
+  o->compressor = C_TOPK_BLOCKS;
+  o->k = total;
+  o->kb.assign(block_k, block_k + num_blocks);
+  o->last_idx.assign(static_cast<size_t>(n) * static_cast<size_t>(total), 0);
+  o->last_val.assign(static_cast<size_t>(n) * static_cast<size_t>(total), 0.0f);
+  o->last_bits.clear();
+  o->last_mu.clear();
   return o;
 }
 

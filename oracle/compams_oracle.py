@@ -10,7 +10,7 @@ import numpy as np
 
 from . import build_oracle
 
-NONE, TOPK, BLOCKSIGN = 0, 1, 2
+NONE, TOPK, BLOCKSIGN, TOPK_BLOCKS = 0, 1, 2, 3
 EPS_IN_SQRT, EPS_OUT_SQRT = 0, 1
 
 _Q = {"theta": 0, "m": 1, "v": 2, "vhat": 3, "e": 4, "idx": 5, "val": 6, "bits": 7, "mu": 8,
@@ -43,6 +43,10 @@ def lib():
         L.oracle_block_l1_mean.argtypes = [f32p, ctypes.c_int64]
         L.oracle_exact_abs_sum.restype = ctypes.c_double
         L.oracle_exact_abs_sum.argtypes = [f32p, ctypes.c_int64]
+        L.oracle_compams_create_topk_blocks.restype = ctypes.c_void_p
+        L.oracle_compams_create_topk_blocks.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, i64p, i64p,
+                                                        ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int,
+                                                        f32p]
         u32p = ctypes.POINTER(ctypes.c_uint32)
         L.oracle_wire_encode_topk.restype = ctypes.c_int64
         L.oracle_wire_encode_topk.argtypes = [ctypes.c_int64, i32p, f32p, u32p]
@@ -128,8 +132,22 @@ class Oracle:
     """One COMP-AMS optimizer: n workers, d coordinates, state on the host."""
 
     def __init__(self, n, d, theta0, compressor=TOPK, k=0, block_offsets=None,
-                 beta1=0.9, beta2=0.999, eps=1e-8, eps_mode=EPS_IN_SQRT):
+                 beta1=0.9, beta2=0.999, eps=1e-8, eps_mode=EPS_IN_SQRT, block_k=None):
+        """compressor TOPK_BLOCKS: Definition 1 per block, block b keeping block_k[b] coordinates."""
         self.n, self.d, self.k, self.compressor = int(n), int(d), int(k), compressor
+        if compressor == TOPK_BLOCKS:
+            off = np.ascontiguousarray(block_offsets, dtype=np.int64)
+            kb = np.ascontiguousarray(block_k, dtype=np.int64)
+            assert kb.size == off.size - 1
+            self.M, self.k = kb.size, int(kb.sum())
+            th, pth = _f32(theta0)
+            assert th.size == d
+            i64 = ctypes.POINTER(ctypes.c_int64)
+            self._h = lib().oracle_compams_create_topk_blocks(self.n, self.d, self.M, off.ctypes.data_as(i64),
+                                                              kb.ctypes.data_as(i64), beta1, beta2, eps, eps_mode, pth)
+            if not self._h:
+                raise ValueError("oracle_compams_create_topk_blocks rejected the configuration")
+            return
         off = None
         M = 0
         if block_offsets is not None:

@@ -113,18 +113,29 @@ class Compams:
     def __init__(self, n: int, d: int, theta0: torch.Tensor, compressor: int = TOPK, k: int = 0,
                  block_offsets=None, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
                  eps_mode: int = EPS_IN_SQRT, ld: Optional[int] = None, device="cuda:0",
-                 state: Optional[Dict[str, torch.Tensor]] = None):
+                 state: Optional[Dict[str, torch.Tensor]] = None,
+                 views: Optional[Dict[str, torch.Tensor]] = None):
+        """views: instead of allocating, borrow the caller's tensors (theta, m, v, vhat: d floats each; e: a view
+        whose first element is row 0, column 0 of this context's residuals and whose row stride is ld) -- how a
+        context is laid over a slice of larger buffers; theta0 is then ignored."""
         self.n, self.d, self.k, self.compressor = int(n), int(d), int(k), int(compressor)
         self.ld = padded_ld(d) if ld is None else int(ld)
         self.device = torch.device(device)
         dev = self.device
         f32 = dict(dtype=torch.float32, device=dev)
-        self.theta = theta0.detach().to(**f32).clone().contiguous()
-        assert self.theta.numel() == self.d
-        self.m = torch.empty(self.d, **f32)
-        self.v = torch.empty(self.d, **f32)
-        self.vhat = torch.empty(self.d, **f32)
-        self.e = torch.zeros((self.n, self.ld), **f32) if compressor != NONE else None
+        if views is not None:
+            self.theta, self.m, self.v, self.vhat = views["theta"], views["m"], views["v"], views["vhat"]
+            self.e = views.get("e")
+            for t in (self.theta, self.m, self.v, self.vhat):
+                assert t.is_cuda and t.dtype == torch.float32 and t.numel() == self.d and t.is_contiguous()
+            assert self.e is None or (self.e.stride(0) == self.ld and self.e.stride(1) == 1)
+        else:
+            self.theta = theta0.detach().to(**f32).clone().contiguous()
+            assert self.theta.numel() == self.d
+            self.m = torch.empty(self.d, **f32)
+            self.v = torch.empty(self.d, **f32)
+            self.vhat = torch.empty(self.d, **f32)
+            self.e = torch.zeros((self.n, self.ld), **f32) if compressor != NONE else None
         flags = 0
         if state is not None:
             flags |= KEEP_STATE
@@ -260,6 +271,75 @@ class Compams:
             torch.cuda.synchronize(self.device)
             lib().compams_destroy(self._h)
             self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class CompamsBlockTopk:
+    """Top-k applied to every block (layer tensor) on its own: block b keeps block_k[b] coordinates per worker.
+
+    The average and the AMSGrad lines act coordinate by coordinate, so the step falls apart into one
+    independent top-k step per block on the block's slice of g, e, theta, m, v, vhat.  This class lays one
+    context over every slice of shared buffers and steps them one after the other on the same stream (five
+    launches per block: not fused across blocks).  Block offsets must be multiples of 4 (16-byte aligned
+    slices)."""
+
+    def __init__(self, n: int, d: int, theta0: torch.Tensor, block_offsets, block_k, beta1: float = 0.9,
+                 beta2: float = 0.999, eps: float = 1e-8, eps_mode: int = EPS_IN_SQRT, ld: Optional[int] = None,
+                 device="cuda:0"):
+        self.n, self.d = int(n), int(d)
+        self.off = np.ascontiguousarray(block_offsets, dtype=np.int64)
+        self.kb = np.ascontiguousarray(block_k, dtype=np.int64)
+        if self.off[0] != 0 or self.off[-1] != d or self.kb.size != self.off.size - 1:
+            raise CompamsError("block offsets must run from 0 to d, with one count per block")
+        if (self.off[:-1] % 4).any():
+            raise CompamsError("block offsets must be multiples of 4 (16-byte aligned slices)")
+        self.k = int(self.kb.sum())
+        self.ld = padded_ld(d) if ld is None else int(ld)
+        self.device = torch.device(device)
+        f32 = dict(dtype=torch.float32, device=self.device)
+        self.theta = theta0.detach().to(**f32).clone().contiguous()
+        self.m = torch.empty(self.d, **f32)
+        self.v = torch.empty(self.d, **f32)
+        self.vhat = torch.empty(self.d, **f32)
+        self.e = torch.zeros((self.n, self.ld), **f32)
+        self.blocks = []
+        for b in range(self.kb.size):
+            lo, hi = int(self.off[b]), int(self.off[b + 1])
+            views = {"theta": self.theta[lo:hi], "m": self.m[lo:hi], "v": self.v[lo:hi], "vhat": self.vhat[lo:hi],
+                     "e": self.e[:, lo:hi]}
+            self.blocks.append(Compams(n, hi - lo, None, compressor=TOPK, k=int(self.kb[b]), beta1=beta1, beta2=beta2,
+                                       eps=eps, eps_mode=eps_mode, ld=self.ld, device=device, views=views))
+
+    def compams_step(self, g: torch.Tensor, lr: float):
+        assert g.dtype == torch.float32 and g.is_cuda and g.is_contiguous() and g.shape == (self.n, self.ld)
+        with torch.cuda.device(self.device):
+            stream = _current_stream_handle()
+            for b, c in enumerate(self.blocks):
+                _check(lib().compams_step(c._h, g.data_ptr() + 4 * int(self.off[b]), lr, stream), "compams_step")
+
+    def compams_state(self, name: str) -> torch.Tensor:
+        if name in ("theta", "m", "v", "vhat"):
+            return getattr(self, name)
+        if name == "e":
+            for c in self.blocks:     # asking a block for its residuals applies what is pending there
+                p, cnt = ctypes.c_void_p(), ctypes.c_int64()
+                _check(lib().compams_state(c._h, STATE["e"], ctypes.byref(p), ctypes.byref(cnt)), "compams_state")
+            return self.e[:, : self.d]
+        if name == "last_idx":
+            return torch.cat([c.compams_state("last_idx") + int(self.off[b]) for b, c in enumerate(self.blocks)], dim=1)
+        if name == "last_val":
+            return torch.cat([c.compams_state("last_val") for c in self.blocks], dim=1)
+        raise CompamsError(f"no such state for per-block top-k: {name}")
+
+    def close(self):
+        for c in self.blocks:
+            c.close()
+        self.blocks = []
 
     def __del__(self):
         try:

@@ -63,7 +63,7 @@ class Workload:
     n: int                      # workers
     sizes: List[int]            # layer tensor sizes, flattened in this order
     dist: str                   # "normal" | "student_t3"
-    compressor: str             # "topk" | "blocksign" | "none"
+    compressor: str             # "topk" | "blocksign" | "none" | "topk_blocks" (top-k inside every layer tensor)
     k: int = 0
     block: str = "layer"        # blocksign: "layer" or an integer block length as string
     steps: int = 10
@@ -75,11 +75,20 @@ class Workload:
 
     def __post_init__(self):
         self.d = int(sum(self.sizes))
+        if self.compressor == "topk_blocks":
+            self.k = int(self.block_k().sum())
 
     def layer_offsets(self) -> np.ndarray:
         return np.concatenate([[0], np.cumsum(np.asarray(self.sizes, dtype=np.int64))])
 
+    def block_k(self, num: int = 1, den: int = 100) -> np.ndarray:
+        """Top-k per layer tensor: floor(size * num / den) coordinates, at least one."""
+        sizes = np.asarray(self.sizes, dtype=np.int64)
+        return np.maximum(1, (sizes * num) // den)
+
     def block_offsets(self) -> Optional[np.ndarray]:
+        if self.compressor == "topk_blocks":
+            return self.layer_offsets()
         if self.compressor != "blocksign":
             return None
         if self.block == "layer":
@@ -113,6 +122,7 @@ def get(name: str) -> Workload:
         "r18_topk01": lambda: Workload("r18_topk01", 16, r18, "normal", "topk",
                                        k=_ratio_k(d18, 1, 1000), steps=20),
         "r18_none": lambda: Workload("r18_none", 16, r18, "normal", "none", steps=20),
+        "r18_topk1_layers": lambda: Workload("r18_topk1_layers", 16, r18, "normal", "topk_blocks", steps=20),
         "r50_topk1": lambda: Workload("r50_topk1", 8, r50, "student_t3", "topk",
                                       k=_ratio_k(d50, 1, 100), steps=20),
         "gpt2s_topk01": lambda: Workload("gpt2s_topk01", 8, g2, "normal", "topk",

@@ -86,6 +86,29 @@ def test_full_size_resnet18_blocksign_layers():
     run_full("r18_blocksign", 3)
 
 
+def test_full_size_resnet18_topk_per_layer():
+    """Top-k inside every layer tensor (62 contexts over slices of shared buffers) against the oracle's per-block
+    compressor, ResNet-18 shape, 1 % of every tensor."""
+    w = W.get("r18_topk1_layers")
+    dev = torch.device("cuda:0")
+    th0 = W.theta0(w, dev)
+    gpu = B.CompamsBlockTopk(w.n, w.d, th0, w.block_offsets(), w.block_k())
+    cpu = O.Oracle(w.n, w.d, th0.cpu().numpy(), compressor=O.TOPK_BLOCKS, block_offsets=w.block_offsets(),
+                   block_k=w.block_k())
+    scale = W.coordinate_scale(w, dev)
+    for t in range(3):
+        g = W.gradients(w, t, device=dev, ld=gpu.ld, scale=scale)
+        gpu.compams_step(g, w.lr)
+        cpu.step(g[:, : w.d].cpu().contiguous().numpy(), w.lr)
+        del g
+        torch.cuda.synchronize()
+        assert np.array_equal(gpu.compams_state("last_idx").cpu().numpy(), cpu.get("idx")), f"step {t}: index sets"
+        assert bits_equal(gpu.compams_state("last_val").cpu().numpy(), cpu.get("val")), f"step {t}: values"
+        for s in ("theta", "m", "v", "vhat") + (("e",) if t == 2 else ()):
+            assert bits_equal(np.ascontiguousarray(gpu.compams_state(s).cpu().numpy()), cpu.get(s)), f"step {t}: {s}"
+    gpu.close(); cpu.close()
+
+
 def test_full_size_resnet18_identity():
     run_full("r18_none", 2)
 

@@ -10,6 +10,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import compams_oracle as O
 from paper_2205_05632_amd import binding as B
 from paper_2205_05632_amd import workloads as W
 
@@ -369,6 +370,39 @@ def test_blocksign_is_deterministic():
         gpu.close()
     for a, b in zip(*res):
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------------------- top-k per block
+@pytest.mark.parametrize("n,d,blocks", [(3, 40000, 7), (2, 100000, 30), (5, 8192, 2), (2, 4 * 4096, 4096)])
+def test_topk_per_block_composition(n, d, blocks):
+    """Top-k inside every block, as one context per block laid over slices of shared buffers, against the oracle's
+    per-block compressor: lists, values, parameters, moments and residuals bit for bit."""
+    rng = np.random.default_rng(d + blocks)
+    cuts = np.sort(rng.choice(np.arange(1, d // 4), size=blocks - 1, replace=False)) * 4
+    off = np.concatenate([[0], cuts, [d]]).astype(np.int64)
+    kb = np.maximum(1, ((off[1:] - off[:-1]) * 0.03).astype(np.int64))
+    theta0 = rng.standard_normal(d).astype(np.float32) * 0.1
+    gpu = B.CompamsBlockTopk(n, d, torch.from_numpy(theta0), off, kb)
+    cpu = O.Oracle(n, d, theta0, compressor=O.TOPK_BLOCKS, block_offsets=off, block_k=kb)
+    for t in range(5):
+        g = (rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-3, 0, (1, d))).astype(np.float32)
+        g[:, ::6] = 0.0
+        gp = torch.zeros((n, gpu.ld), dtype=torch.float32)
+        gp[:, :d] = torch.from_numpy(g)
+        gpu.compams_step(gp.to(gpu.device), 1e-3)
+        cpu.step(g, 1e-3)
+        torch.cuda.synchronize()
+        assert np.array_equal(gpu.compams_state("last_idx").cpu().numpy(), cpu.get("idx")), f"step {t}: lists"
+        assert np.array_equal(gpu.compams_state("last_val").cpu().numpy().view(np.uint32), cpu.get("val").view(np.uint32))
+        for name in ("theta", "m", "v", "vhat") + (("e",) if t == 4 else ()):
+            got = np.ascontiguousarray(gpu.compams_state(name).cpu().numpy())
+            assert np.array_equal(got.view(np.uint32), cpu.get(name).view(np.uint32)), f"step {t}: {name}"
+    gpu.close(); cpu.close()
+
+
+def test_topk_per_block_needs_aligned_blocks():
+    with pytest.raises(B.CompamsError):
+        B.CompamsBlockTopk(2, 100, torch.zeros(100), [0, 50, 100], [1, 1])     # 50 is not a multiple of 4
 
 
 # ------------------------------------------------------------------------------------------- identity

@@ -370,3 +370,74 @@ def test_create_rejects_bad_configs():
         O.Oracle(2, 8, z, compressor=O.BLOCKSIGN, block_offsets=[0, 4, 4, 8])
     with pytest.raises(ValueError):
         O.Oracle(2, 8, z, compressor=O.BLOCKSIGN, block_offsets=[0, 4, 7])
+
+
+# ------------------------------------------------------------------------------------- top-k per block
+def _block_layout(rng, d, m):
+    cuts = np.sort(rng.choice(np.arange(1, d // 4), size=m - 1, replace=False)) * 4
+    off = np.concatenate([[0], cuts, [d]]).astype(np.int64)
+    kb = np.maximum(1, ((off[1:] - off[:-1]) * 0.05).astype(np.int64))
+    return off, kb
+
+
+def test_topk_per_block_with_one_block_is_plain_topk():
+    n, d, k = 3, 5000, 77
+    rng = np.random.default_rng(11)
+    th = rng.standard_normal(d).astype(np.float32)
+    a = O.Oracle(n, d, th, compressor=O.TOPK, k=k)
+    b = O.Oracle(n, d, th, compressor=O.TOPK_BLOCKS, block_offsets=[0, d], block_k=[k])
+    for _ in range(4):
+        g = rng.standard_normal((n, d)).astype(np.float32)
+        a.step(g, 1e-3); b.step(g, 1e-3)
+        for name in ("idx", "val", "theta", "m", "v", "vhat", "e"):
+            assert np.array_equal(a.get(name).view(np.uint32), b.get(name).view(np.uint32)), name
+    a.close(); b.close()
+
+
+def test_topk_per_block_selects_by_brute_force_inside_every_block():
+    n, d = 2, 3000
+    rng = np.random.default_rng(12)
+    off, kb = _block_layout(rng, d, 9)
+    o = O.Oracle(n, d, np.zeros(d, np.float32), compressor=O.TOPK_BLOCKS, block_offsets=off, block_k=kb)
+    g = rng.standard_normal((n, d)).astype(np.float32)
+    g[:, ::5] = np.float32(0.25)                                 # ties inside and across blocks
+    o.step(g, 1e-3)
+    idx, val, e = o.get("idx"), o.get("val"), o.get("e")
+    for i in range(n):
+        want = []
+        for b in range(kb.size):
+            lo, hi = off[b], off[b + 1]
+            key = g[i, lo:hi].view(np.uint32) & 0x7FFFFFFF
+            order = np.lexsort((np.arange(hi - lo), -key.astype(np.int64)))   # larger |x| first, then lower index
+            want.append(np.sort(order[: kb[b]]) + lo)
+        want = np.concatenate(want)
+        assert np.array_equal(idx[i], want) and np.all(np.diff(idx[i]) > 0)
+        assert np.array_equal(val[i], g[i, want])
+        c = np.zeros(d, np.float32); c[want] = g[i, want]
+        assert np.array_equal((c + e[i]).view(np.uint32), g[i].view(np.uint32))  # C(x) + e_new = e_old + g exactly
+    o.close()
+
+
+def test_topk_per_block_is_one_independent_topk_step_per_block():
+    """The server's lines act coordinate by coordinate: the per-block compressor equals one plain top-k oracle per
+    block on the block's slice of everything."""
+    n, d = 3, 4000
+    rng = np.random.default_rng(13)
+    off, kb = _block_layout(rng, d, 6)
+    th = rng.standard_normal(d).astype(np.float32) * 0.1
+    whole = O.Oracle(n, d, th, compressor=O.TOPK_BLOCKS, block_offsets=off, block_k=kb)
+    parts = [O.Oracle(n, int(off[b + 1] - off[b]), th[off[b]:off[b + 1]], compressor=O.TOPK, k=int(kb[b]))
+             for b in range(kb.size)]
+    for _ in range(5):
+        g = rng.standard_normal((n, d)).astype(np.float32)
+        whole.step(g, 2e-3)
+        for b, p in enumerate(parts):
+            p.step(np.ascontiguousarray(g[:, off[b]:off[b + 1]]), 2e-3)
+        for name in ("theta", "m", "v", "vhat"):
+            got = whole.get(name)
+            for b, p in enumerate(parts):
+                assert np.array_equal(got[off[b]:off[b + 1]].view(np.uint32), p.get(name).view(np.uint32)), name
+        assert np.array_equal(whole.get("idx"), np.concatenate([p.get("idx") + off[b] for b, p in enumerate(parts)], 1))
+    whole.close()
+    for p in parts:
+        p.close()
