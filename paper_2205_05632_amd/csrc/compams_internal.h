@@ -69,6 +69,29 @@ struct TopkRow {
 };
 static_assert(sizeof(TopkRow) == 128, "TopkRow layout");
 
+// One selection problem: a worker's whole row (top-k over the flattened gradient) or one block of a worker's
+// row (top-k inside every block).  Index fields count entries of the respective workspace tables.
+struct Seg {
+  int64_t elem_off;      // first element, relative to the start of g and of e
+  uint64_t chunk_base;   // first entry in the per-chunk tables (segment descriptors, count records)
+  uint64_t seloff_base;  // first entry in sel_off (a segment has one entry more than it has chunks)
+  uint64_t cand_base;    // first entry of the segment's candidate list
+  uint64_t list_base;    // first entry of the segment's slice of the worker's (coordinate, value) list
+  uint32_t d, k;         // length, and how many coordinates are kept
+  uint32_t num_chunks;
+  uint32_t cap;          // capacity of the candidate list
+  uint32_t coord_base;   // coordinate of the first element within the worker's row
+  uint32_t count_cpw;    // chunks per block of the counting kernel
+  uint32_t groups_first, groups_sweep, count_blocks;  // workgroups the three kernel classes give this segment
+  uint32_t pad[3];
+};
+static_assert(sizeof(Seg) == 88 || sizeof(Seg) == 96, "Seg layout");
+
+// Which segment, and which of its workgroups, a workgroup of a flat launch is.
+struct WgSlot {
+  uint32_t seg, group;
+};
+
 struct TopkOptions {
   uint32_t cap;            // candidate entries per row
   uint32_t predict;        // 1: carry the threshold bucket over to the next step's first pass
@@ -95,6 +118,14 @@ struct TopkWorkspace {
   int32_t* idx;         // n * k
   float* val;           // n * k
   uint32_t* tau;        // n
+  // top-k inside every block only: the segments and, per kernel class, the workgroups of a flat launch
+  const Seg* segs;
+  const WgSlot* map_first;
+  const WgSlot* map_sweep;
+  const WgSlot* map_count;
+  const WgSlot* map_emit;   // .group = first chunk of the four that the workgroup's wavefronts take
+  uint32_t* sel_off_srv;    // n * (chunks of a whole row + 1) : list offsets per chunk of coordinates, for the
+                            //                                   server's lines run from lists
 };
 
 struct BlocksignWorkspace {

@@ -306,7 +306,8 @@ struct PassA {
   uint32_t cap;
   uint2* descr;
   const uint32_t* prev_off;
-  const int32_t* prev_idx;
+  const int32_t* prev_idx;  // coordinates within the worker's row
+  uint32_t coord_base;      // the row coordinate of this problem's first element
   uint32_t k;
   uint32_t zeros;        // zero keys seen (added to bin 0 at the end)
 };
@@ -330,11 +331,11 @@ __device__ __forceinline__ void pend_build(const PendAhead& pa, const PassA& A, 
   const uint32_t lane = lane_id();
   A.bm[lane] = 0;
   A.bm[lane + 64] = 0;
-  const uint32_t a = pa.j0 - c * kChunk, b = pa.j1 - c * kChunk;
+  const uint32_t a = pa.j0 - A.coord_base - c * kChunk, b = pa.j1 - A.coord_base - c * kChunk;
   if (a < static_cast<uint32_t>(kChunk)) atomicOr(&A.bm[a >> 5], 1u << (a & 31u));
   if (b < static_cast<uint32_t>(kChunk)) atomicOr(&A.bm[b >> 5], 1u << (b & 31u));
   for (uint32_t q = pa.lo + 128 + lane; q < pa.hi; q += 64) {  // dense chunks only
-    const uint32_t jl = static_cast<uint32_t>(A.prev_idx[q]) - c * kChunk;
+    const uint32_t jl = static_cast<uint32_t>(A.prev_idx[q]) - A.coord_base - c * kChunk;
     if (jl < static_cast<uint32_t>(kChunk)) atomicOr(&A.bm[jl >> 5], 1u << (jl & 31u));
   }
 }
@@ -469,7 +470,58 @@ __device__ __forceinline__ void pass_a_walk(PassA& A, uint32_t first, uint32_t s
   }
 }
 
-template <bool PRED, bool PEND>
+// ---------------------------------------------------------------------------------------------
+// Which selection problem a workgroup works on.  UNI: one problem per worker row, all of one shape, grid
+// (groups, rows): everything follows from the block indices.  Otherwise the launch is flat and tables say
+// which segment (a block of a worker's row) and which of its workgroups this is; geo and opt are then
+// narrowed to the segment's own shape.
+// ---------------------------------------------------------------------------------------------
+enum : int { kClassFirst = 0, kClassSweep = 1, kClassCount = 2 };
+
+struct SegCtx {
+  uint32_t seg;     // index into the per-problem tables (control blocks, histograms, thresholds)
+  uint32_t group;   // this workgroup's index among the `groups` that share the problem
+  uint32_t groups;
+  int64_t elem_off;
+  uint32_t coord_base;
+  size_t chunk_base, seloff_base, cand_base, list_base;
+};
+
+template <bool UNI, int CLASS>
+__device__ __forceinline__ SegCtx seg_ctx(Geometry& geo, TopkOptions& opt, const TopkWorkspace& ws) {
+  SegCtx c;
+  if (UNI) {
+    c.seg = blockIdx.y;
+    c.group = blockIdx.x;
+    c.groups = gridDim.x;
+    c.elem_off = static_cast<int64_t>(c.seg) * geo.ld;
+    c.coord_base = 0;
+    c.chunk_base = static_cast<size_t>(c.seg) * geo.num_chunks;
+    c.seloff_base = static_cast<size_t>(c.seg) * (geo.num_chunks + 1);
+    c.cand_base = static_cast<size_t>(c.seg) * opt.cap;
+    c.list_base = static_cast<size_t>(c.seg) * geo.k;
+  } else {
+    const WgSlot slot = (CLASS == kClassFirst ? ws.map_first : (CLASS == kClassSweep ? ws.map_sweep : ws.map_count))[blockIdx.x];
+    const Seg sg = ws.segs[slot.seg];
+    c.seg = slot.seg;
+    c.group = slot.group;
+    c.groups = CLASS == kClassFirst ? sg.groups_first : (CLASS == kClassSweep ? sg.groups_sweep : sg.count_blocks);
+    c.elem_off = sg.elem_off;
+    c.coord_base = sg.coord_base;
+    c.chunk_base = sg.chunk_base;
+    c.seloff_base = sg.seloff_base;
+    c.cand_base = sg.cand_base;
+    c.list_base = sg.list_base;
+    geo.d = sg.d;
+    geo.k = sg.k;
+    geo.num_chunks = sg.num_chunks;
+    geo.count_cpw = sg.count_cpw;
+    opt.cap = opt.cap < sg.cap ? opt.cap : sg.cap;
+  }
+  return c;
+}
+
+template <bool PRED, bool PEND, bool UNI>
 __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ g, float* __restrict__ e,
                                                       Geometry geo, TopkWorkspace ws, TopkOptions opt) {
   __shared__ uint32_t lh[kNB0];
@@ -479,13 +531,14 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
   __shared__ uint32_t suf[kWGA + 1];
   __shared__ uint32_t out2[2];
   __shared__ uint32_t sh_flag, sh_l1, sh_bstar, sh_need;
-  const uint32_t row = blockIdx.y;
+  const SegCtx sc = seg_ctx<UNI, kClassFirst>(geo, opt, ws);
+  const uint32_t row = sc.seg;
   for (int b = threadIdx.x; b < kNB0; b += kWGA) lh[b] = 0;
   if (PRED)
     for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWGA) lh1[b] = 0;
   __syncthreads();
-  const float* gr = g + static_cast<int64_t>(row) * geo.ld;
-  float* er = e + static_cast<int64_t>(row) * geo.ld;
+  const float* gr = g + sc.elem_off;
+  float* er = e + sc.elem_off;
   TopkRow* rowp = ws.rows + row;
   bool pred = false;
   uint32_t bg = 0;
@@ -493,18 +546,18 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
     pred = rowp->pred_valid != 0;
     bg = rowp->b_guess;
   }
-  uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
-  uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
-  const uint32_t* prev_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
-  const int32_t* prev_idx = ws.idx + static_cast<size_t>(row) * geo.k;
+  uint2* candr = ws.cand + sc.cand_base;
+  uint2* descr = ws.desc + sc.chunk_base;
+  const uint32_t* prev_off = ws.sel_off + sc.seloff_base;
+  const int32_t* prev_idx = ws.idx + sc.list_base;
   const uint32_t wave = threadIdx.x >> 6;
   uint2* stage = stage_all + (PRED ? wave * 2 * kStage : 0);
   uint32_t* bm = bm_all + (PEND ? wave * 128 : 0);
   PassA A;
   A.gr = gr; A.er = er; A.d = geo.d; A.lh = lh; A.lh1 = lh1; A.stage = stage; A.bm = bm; A.pred = pred; A.bg = bg;
   A.rowp = rowp; A.candr = candr; A.cap = opt.cap; A.descr = descr; A.prev_off = prev_off; A.prev_idx = prev_idx;
-  A.k = geo.k; A.zeros = 0;
-  pass_a_walk<PRED, PEND>(A, blockIdx.x * kWavesA + wave, gridDim.x * kWavesA, geo.num_chunks);
+  A.k = geo.k; A.zeros = 0; A.coord_base = sc.coord_base;
+  pass_a_walk<PRED, PEND>(A, sc.group * kWavesA + wave, sc.groups * kWavesA, geo.num_chunks);
   const uint32_t zeros = A.zeros;
   if (zeros && lane_id() == 0) atomicAdd(&lh[0], zeros);
   __syncthreads();
@@ -521,7 +574,7 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
     }
 
   // ---- row-wide part, by whichever workgroup of the row finishes last ----
-  if (!last_group_of_row(&rowp->ticket[0], gridDim.x, &sh_flag)) return;
+  if (!last_group_of_row(&rowp->ticket[0], sc.groups, &sh_flag)) return;
   take_hist<kNB0, kWGA>(gh, lh);
   find_crossing<kNB0, kWGA>(lh, geo.k, suf, out2);
   if (threadIdx.x == 0) {
@@ -579,6 +632,7 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
 //   kModeCand : the list exists (the threshold bucket was above the tracked ones): sweep it.
 //   kModeDense: no list: histogram from the row itself.
 // ---------------------------------------------------------------------------------------------
+template <bool UNI>
 __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                       TopkOptions opt) {
   __shared__ uint32_t lh[kNB1];
@@ -586,24 +640,25 @@ __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e
   __shared__ uint32_t suf[kWG + 1];
   __shared__ uint32_t out2[2];
   __shared__ uint32_t sh_flag;
-  const uint32_t row = blockIdx.y;
+  const SegCtx sc = seg_ctx<UNI, kClassSweep>(geo, opt, ws);
+  const uint32_t row = sc.seg;
   TopkRow* rowp = ws.rows + row;
   if (rowp->level1_done) return;
   const uint32_t mode = rowp->mode, bstar = rowp->bstar, need = rowp->need;
   for (int b = threadIdx.x; b < kNB1; b += kWG) lh[b] = 0;
   __syncthreads();
-  const float* er = e + static_cast<int64_t>(row) * geo.ld;
-  uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
+  const float* er = e + sc.elem_off;
+  uint2* candr = ws.cand + sc.cand_base;
   auto visit = [&](uint32_t bits, bool ok) {
     const uint32_t key = key_of_bits(bits);
     if (ok && (key >> kL0Shift) == bstar) atomicAdd(&lh[(key >> kL1Shift) & (kNB1 - 1)], 1u);
   };
   if (mode == kModeNeedB) {
-    uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
+    uint2* descr = ws.desc + sc.chunk_base;
     const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
     uint2* stage = stage_all + wave * kStage;
-    const uint32_t stride = gridDim.x * kWaves;
-    for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+    const uint32_t stride = sc.groups * kWaves;
+    for (uint32_t c = sc.group * kWaves + wave; c < geo.num_chunks; c += stride) {
       const uint32_t base = c * kChunk + lane * 4;
       uint32_t cnt = 0;
 #pragma unroll 4
@@ -626,11 +681,11 @@ __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e
     }
   } else if (mode == kModeCand) {
     const uint32_t n_src = rowp->n_src;
-    const uint32_t step = gridDim.x * kWG;
-    for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < n_src; q += step) visit(candr[q].y, true);
+    const uint32_t step = sc.groups * kWG;
+    for (uint32_t q = sc.group * kWG + threadIdx.x; q < n_src; q += step) visit(candr[q].y, true);
   } else {
-    const uint32_t step = gridDim.x * kWG * 4;
-    for (uint32_t j = (blockIdx.x * kWG + threadIdx.x) * 4; j < geo.d; j += step) {
+    const uint32_t step = sc.groups * kWG * 4;
+    for (uint32_t j = (sc.group * kWG + threadIdx.x) * 4; j < geo.d; j += step) {
       const float4 x = *reinterpret_cast<const float4*>(er + j);
       visit(__float_as_uint(x.x), true);
       visit(__float_as_uint(x.y), j + 1 < geo.d);
@@ -644,7 +699,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e
     const uint32_t h = lh[b];
     if (h) atomicAdd(&gh[b], h);
   }
-  if (!last_group_of_row(&rowp->ticket[1], gridDim.x, &sh_flag)) return;
+  if (!last_group_of_row(&rowp->ticket[1], sc.groups, &sh_flag)) return;
   take_hist<kNB1>(gh, lh);
   resolve_level1(rowp, bstar, need, lh, suf, out2);
 }
@@ -652,13 +707,15 @@ __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e
 // ---------------------------------------------------------------------------------------------
 // Kernel 3: level 2 (last 9 key bits) over the entries that match bits 30..9 of the threshold key.
 // ---------------------------------------------------------------------------------------------
+template <bool UNI>
 __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                       TopkOptions opt) {
   __shared__ uint32_t lh[kNB2];
   __shared__ uint32_t suf[kWG + 1];
   __shared__ uint32_t out2[2];
   __shared__ uint32_t sh_flag;
-  const uint32_t row = blockIdx.y;
+  const SegCtx sc = seg_ctx<UNI, kClassSweep>(geo, opt, ws);
+  const uint32_t row = sc.seg;
   TopkRow* rowp = ws.rows + row;
   const uint32_t mode = rowp->mode, want = rowp->prefix1, need = rowp->need;
   for (int b = threadIdx.x; b < kNB2; b += kWG) lh[b] = 0;
@@ -668,9 +725,9 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
     if (ok && (key >> kL1Shift) == want) atomicAdd(&lh[key & (kNB2 - 1)], 1u);
   };
   if (mode == kModeDense) {
-    const float* er = e + static_cast<int64_t>(row) * geo.ld;
-    const uint32_t step = gridDim.x * kWG * 4;
-    for (uint32_t j = (blockIdx.x * kWG + threadIdx.x) * 4; j < geo.d; j += step) {
+    const float* er = e + sc.elem_off;
+    const uint32_t step = sc.groups * kWG * 4;
+    for (uint32_t j = (sc.group * kWG + threadIdx.x) * 4; j < geo.d; j += step) {
       const float4 x = *reinterpret_cast<const float4*>(er + j);
       visit(__float_as_uint(x.x), true);
       visit(__float_as_uint(x.y), j + 1 < geo.d);
@@ -678,10 +735,10 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
       visit(__float_as_uint(x.w), j + 3 < geo.d);
     }
   } else {
-    const uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
+    const uint2* candr = ws.cand + sc.cand_base;
     const uint32_t n_src = rowp->n_src;
-    const uint32_t step = gridDim.x * kWG;
-    for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < n_src; q += step) visit(candr[q].y, true);
+    const uint32_t step = sc.groups * kWG;
+    for (uint32_t q = sc.group * kWG + threadIdx.x; q < n_src; q += step) visit(candr[q].y, true);
   }
   __syncthreads();
   uint32_t* gh = ws.hist2 + static_cast<size_t>(row) * kNB2;
@@ -689,7 +746,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
     const uint32_t h = lh[b];
     if (h) atomicAdd(&gh[b], h);
   }
-  if (!last_group_of_row(&rowp->ticket[2], gridDim.x, &sh_flag)) return;
+  if (!last_group_of_row(&rowp->ticket[2], sc.groups, &sh_flag)) return;
   take_hist<kNB2>(gh, lh);
   find_crossing<kNB2>(lh, need, suf, out2);
   if (threadIdx.x == 0) {
@@ -772,20 +829,22 @@ __device__ __forceinline__ void for_each_round(uint32_t mode, const float* __res
 // the block, and per block the two totals.  The last kernel turns these into positions in the worker's
 // list (a sum over at most kMaxCountBlocks block totals), so no workgroup waits for or follows another.
 // ---------------------------------------------------------------------------------------------
+template <bool UNI>
 __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                      TopkOptions opt) {
   __shared__ uint32_t l_gt[kMaxCountCpw], l_eq[kMaxCountCpw];
   __shared__ uint32_t scratch[kWG / 64 + 1];
-  const uint32_t row = blockIdx.y;
+  const SegCtx sc = seg_ctx<UNI, kClassCount>(geo, opt, ws);
+  const uint32_t row = sc.seg;
   const uint32_t cpw = geo.count_cpw;
-  const uint32_t start = blockIdx.x * cpw;
+  const uint32_t start = sc.group * cpw;
   if (start >= geo.num_chunks) return;  // uniform; the grid has exactly the blocks that exist
   const uint32_t end = start + cpw < geo.num_chunks ? start + cpw : geo.num_chunks;
   const TopkRow* rowp = ws.rows + row;
   const uint32_t mode = rowp->mode, tau = rowp->tau;
-  const float* er = e + static_cast<int64_t>(row) * geo.ld;
-  const uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
-  const uint2* descr = ws.desc + static_cast<size_t>(row) * geo.num_chunks;
+  const float* er = e + sc.elem_off;
+  const uint2* candr = ws.cand + sc.cand_base;
+  const uint2* descr = ws.desc + sc.chunk_base;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   if (mode == kModeDense) {
     for (uint32_t c = start + wave; c < end; c += kWaves) {
@@ -853,7 +912,7 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
   uint32_t tot_gt, tot_eq;
   uint32_t pre_gt = block_excl_scan<kWG>(sum_gt, scratch, &tot_gt);
   uint32_t pre_eq = block_excl_scan<kWG>(sum_eq, scratch, &tot_eq);
-  uint4* rec = ws.chunk_rec + static_cast<size_t>(row) * geo.num_chunks + start;
+  uint4* rec = ws.chunk_rec + sc.chunk_base + start;
   for (uint32_t i = 0; i < per; ++i)
     if (first + i < len) {
       const uint32_t gt = l_gt[first + i], eq = l_eq[first + i];
@@ -861,7 +920,7 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
       pre_gt += gt;
       pre_eq += eq;
     }
-  if (threadIdx.x == 0) ws.blk[static_cast<size_t>(row) * kMaxCountBlocks + blockIdx.x] = make_uint2(tot_gt, tot_eq);
+  if (threadIdx.x == 0) ws.blk[static_cast<size_t>(row) * kMaxCountBlocks + sc.group] = make_uint2(tot_gt, tot_eq);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1149,19 +1208,19 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   const uint32_t GA = groups_first_pass(geo.n, geo.num_chunks, kWavesA);
   const dim3 grid_rows(G, geo.n), wg(kWG), grid_a(GA, geo.n), wga(kWGA);
   if (first_pass_may_predict) {
-    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<true, true>, grid_a, wga, stream, g, e, geo, ws, opt);
-    else launch(L, kSlotPassA, k_topk_pass_a<true, false>, grid_a, wga, stream, g, e, geo, ws, opt);
+    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<true, true, true>, grid_a, wga, stream, g, e, geo, ws, opt);
+    else launch(L, kSlotPassA, k_topk_pass_a<true, false, true>, grid_a, wga, stream, g, e, geo, ws, opt);
   } else {
-    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<false, true>, grid_a, wga, stream, g, e, geo, ws, opt);
-    else launch(L, kSlotPassA, k_topk_pass_a<false, false>, grid_a, wga, stream, g, e, geo, ws, opt);
+    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<false, true, true>, grid_a, wga, stream, g, e, geo, ws, opt);
+    else launch(L, kSlotPassA, k_topk_pass_a<false, false, true>, grid_a, wga, stream, g, e, geo, ws, opt);
   }
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotLevel1, k_topk_level1, grid_rows, wg, stream, e, geo, ws, opt);
+  launch(L, kSlotLevel1, k_topk_level1<true>, grid_rows, wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotLevel2, k_topk_level2, grid_rows, wg, stream, e, geo, ws, opt);
+  launch(L, kSlotLevel2, k_topk_level2<true>, grid_rows, wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
   const uint32_t count_blocks = (geo.num_chunks + geo.count_cpw - 1) / geo.count_cpw;  // <= kMaxCountBlocks
-  launch(L, kSlotCount, k_topk_count, dim3(count_blocks, geo.n), wg, stream, e, geo, ws, opt);
+  launch(L, kSlotCount, k_topk_count<true>, dim3(count_blocks, geo.n), wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
   if (role == kWorkerHalf)
     launch(L, kSlotTopkFinal, k_topk_final<kWorkerHalf>, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws,
