@@ -69,6 +69,8 @@ def main():
                     help="bracket every kernel with events and print the per-kernel table to stderr")
     ap.add_argument("--no-predict", action="store_true", help="ablation: re-read the row instead of guessing")
     ap.add_argument("--force-dense", action="store_true", help="ablation: no candidate lists at all")
+    ap.add_argument("--compose-blocks", action="store_true",
+                    help="top-k per layer tensor as one context per tensor, stepped one after the other")
     ap.add_argument("--grad-buffers", type=int, default=0,
                     help="how many distinct gradient buffers to cycle through (0: one per step)")
     ap.add_argument("--settle-each-step", action="store_true",
@@ -91,15 +93,17 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     w = W.get(args.workload)
-    per_block = w.compressor == "topk_blocks"   # one context per layer tensor: no per-kernel events, no codec
+    blocks_topk = w.compressor == "topk_blocks"
+    # --compose-blocks: one context per layer tensor stepped one after the other (no per-kernel events, no codec)
+    per_block = blocks_topk and args.compose_blocks
     if per_block:
         comp = None
         ctx = B.CompamsBlockTopk(w.n, w.d, W.theta0(w, dev), w.block_offsets(), w.block_k(), device=dev)
         args.no_kernel_events = True
     else:
-        comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE}[w.compressor]
+        comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE, "topk_blocks": B.TOPK_BLOCKS}[w.compressor]
         ctx = B.Compams(w.n, w.d, W.theta0(w, dev), compressor=comp, k=w.k, block_offsets=w.block_offsets(),
-                        device=dev)
+                        block_k=w.block_k() if blocks_topk else None, device=dev)
     if args.no_predict and not per_block:
         ctx.set_option(B.OPT_PREDICT, 0)
     if args.force_dense and not per_block:
@@ -140,7 +144,7 @@ def main():
     steps_per_s = args.steps / sec
 
     bmin = algorithmic_bytes(w, w.compressor)
-    kname, kbytes = dominant_kernel("topk" if per_block else w.compressor)
+    kname, kbytes = dominant_kernel("topk" if blocks_topk else w.compressor)
     roofline = None
     kernel_sum_ms = None
     if prof:
@@ -154,10 +158,15 @@ def main():
                     "algorithmic_bytes_per_launch": kbytes(w.n, w.d)}
 
     counters = None
-    if comp == B.TOPK:
+    if comp in (B.TOPK, B.TOPK_BLOCKS):
         c = ctx.compams_state("counters").cpu()
-        counters = {"dense_rereads_per_row_last_step": c[:, 0].tolist(),
-                    "candidates_per_row_last_step": c[:, 1].tolist()}
+        if comp == B.TOPK:
+            counters = {"dense_rereads_per_row_last_step": c[:, 0].tolist(),
+                        "candidates_per_row_last_step": c[:, 1].tolist()}
+        else:   # one selection problem per (worker, block): totals
+            counters = {"selection_problems": int(c.shape[0]),
+                        "problems_with_dense_rereads_last_step": int((c[:, 0] > 0).sum()),
+                        "candidates_last_step": int(c[:, 1].sum())}
     if args.kernels:
         for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
             print(f"  {name:16s} {ms / cnt * 1e3:9.1f} us/launch  x{cnt}", file=sys.stderr)
@@ -207,7 +216,7 @@ def main():
         bits = 32.0 * float(words.float().mean().item())
         wire = {"bits_per_worker": bits, "full_gradient_bits": 32.0 * w.d, "reduction": 32.0 * w.d / bits,
                 "encode_us": (w1 - w0) / reps * 1e6, "decode_us": (w2 - w1) / reps * 1e6}
-        if comp == B.TOPK:
+        if comp in (B.TOPK, B.TOPK_BLOCKS):
             tiles = (w.k + 255) // 256
             wire["gap_bits_mean"] = (bits / 32.0 - 3 - (tiles + 3) // 4 - w.k) * 32.0 / w.k
             wire["reduction_values_only"] = w.d / w.k
@@ -218,7 +227,7 @@ def main():
         from oracle import compams_oracle as O
         ocomp = {"topk": O.TOPK, "blocksign": O.BLOCKSIGN, "none": O.NONE, "topk_blocks": O.TOPK_BLOCKS}[w.compressor]
         orc = O.Oracle(w.n, w.d, W.theta0(w, dev).cpu().numpy(), compressor=ocomp, k=w.k,
-                       block_offsets=w.block_offsets(), block_k=w.block_k() if per_block else None)
+                       block_offsets=w.block_offsets(), block_k=w.block_k() if blocks_topk else None)
         host = [grads[t][:, : w.d].cpu().contiguous().numpy() for t in range(args.cpu_steps)]
         c0 = time.perf_counter()
         for g in host:

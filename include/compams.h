@@ -36,7 +36,11 @@ typedef struct compams_ctx compams_ctx; /* opaque; host memory owned by the libr
 enum {
   COMPAMS_NONE = 0,     /* C(x) = x (q = 0): full-precision distributed AMSGrad; e is neither read nor written */
   COMPAMS_TOPK = 1,     /* Definition 1: keep the k coordinates of largest magnitude per worker */
-  COMPAMS_BLOCKSIGN = 2 /* Definition 2: per block, sign(x) times the block's mean absolute value */
+  COMPAMS_BLOCKSIGN = 2, /* Definition 2: per block, sign(x) times the block's mean absolute value */
+  COMPAMS_TOPK_BLOCKS = 3 /* Definition 1 applied to every block on its own: block b keeps its block_k[b] coordinates
+                             of largest magnitude per worker (the usual per-layer top-k).  Block offsets must be
+                             multiples of 4.  Workspace grows with n * num_blocks (about 35 KB each): meant for
+                             layer-sized blocks */
 };
 
 /* Where epsilon sits in the parameter line of Algorithms 1 and 2. */
@@ -63,10 +67,11 @@ typedef struct compams_config {
   int64_t d;          /* coordinates per worker, 1 <= d < 2^31 */
   int64_t ld;         /* row stride of g and e in elements: ld >= d and ld % 4 == 0; a multiple of 1024 (rows that
                          start on 4 KiB boundaries) streams about 8 % faster than an odd stride */
-  int32_t compressor; /* COMPAMS_NONE / COMPAMS_TOPK / COMPAMS_BLOCKSIGN */
+  int32_t compressor; /* COMPAMS_NONE / COMPAMS_TOPK / COMPAMS_BLOCKSIGN / COMPAMS_TOPK_BLOCKS */
   int64_t k;          /* top-k: 1 <= k <= d, per worker over the whole flattened row; else ignored */
-  int64_t num_blocks; /* block-sign: number of blocks M >= 1; else ignored */
-  const int64_t* block_offsets; /* HOST, block-sign: M+1 strictly ascending offsets, [0] = 0, [M] = d; copied */
+  int64_t num_blocks; /* block-sign, top-k per block: number of blocks M >= 1; else ignored */
+  const int64_t* block_offsets; /* HOST, block-sign, top-k per block: M+1 strictly ascending offsets, [0] = 0,
+                                   [M] = d; copied */
   float beta1, beta2, eps;      /* the paper's defaults are 0.9, 0.999, 1e-8 (Section 5.1) */
   int32_t eps_mode;             /* COMPAMS_EPS_* */
   int32_t flags;                /* bit set of COMPAMS_KEEP_STATE */
@@ -79,10 +84,13 @@ typedef struct compams_config {
                    the contents are the library's: see compams_step() */
   void* workspace;        /* DEVICE scratch of at least compams_workspace_size() bytes, 256-byte aligned */
   size_t workspace_bytes;
+  const int64_t* block_k; /* HOST, top-k per block: M counts, 1 <= block_k[b] <= size of block b; copied; else
+                             ignored (may be NULL).  The workers' lists then hold sum(block_k) entries: the kept
+                             coordinates of block 0, of block 1, ...: ascending over the whole row */
 } compams_config;
 
 /* Bytes of device workspace this configuration needs (0 on an invalid configuration).
- * Host-only; reads n, d, compressor, k, num_blocks. */
+ * Host-only; reads n, d, compressor, k, num_blocks (and block_offsets, block_k for top-k per block). */
 size_t compams_workspace_size(const compams_config* cfg);
 
 /* Validates cfg, copies it, lays out the workspace, uploads the block offsets and, unless
@@ -117,7 +125,8 @@ enum {
   COMPAMS_STATE_LAST_VAL = 6,       /* top-k: float[n*k], the corrected gradient at those coordinates */
   COMPAMS_STATE_LAST_SIGNBITS = 7,  /* block-sign: uint32[n*ceil(d/32)], bit (j&31) of word j>>5 = (x_j < 0) */
   COMPAMS_STATE_LAST_SCALES = 8,    /* block-sign: float[n*M], the block means of |x| */
-  COMPAMS_STATE_LAST_THRESHOLD = 9, /* top-k: uint32[n], magnitude key of the k-th largest entry */
+  COMPAMS_STATE_LAST_THRESHOLD = 9, /* top-k: uint32[n], magnitude key of the k-th largest entry (top-k per block:
+                                       uint32[n*M], worker-major; likewise the count and the counters below) */
   COMPAMS_STATE_COUNTERS = 10,      /* uint32[n*COMPAMS_COUNTERS_PER_ROW], see below */
   COMPAMS_STATE_LAST_COUNT_GT = 11  /* top-k: uint32[n], selected entries strictly above the threshold key (the
                                        other k - that many are ties, taken in coordinate order) */

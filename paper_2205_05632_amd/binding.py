@@ -14,7 +14,7 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libcompams.so")
 
-NONE, TOPK, BLOCKSIGN = 0, 1, 2
+NONE, TOPK, BLOCKSIGN, TOPK_BLOCKS = 0, 1, 2, 3
 EPS_IN_SQRT, EPS_OUT_SQRT = 0, 1
 KEEP_STATE = 1
 OPT_CANDIDATE_CAP, OPT_PREDICT, OPT_FORCE_DENSE = 0, 1, 2
@@ -38,7 +38,8 @@ class compams_config(ctypes.Structure):
                 ("eps_mode", ctypes.c_int32), ("flags", ctypes.c_int32),
                 ("theta", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p),
                 ("vhat", ctypes.c_void_p), ("e", ctypes.c_void_p),
-                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("block_k", ctypes.POINTER(ctypes.c_int64))]
 
 
 class CompamsError(RuntimeError):
@@ -114,11 +115,17 @@ class Compams:
                  block_offsets=None, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
                  eps_mode: int = EPS_IN_SQRT, ld: Optional[int] = None, device="cuda:0",
                  state: Optional[Dict[str, torch.Tensor]] = None,
-                 views: Optional[Dict[str, torch.Tensor]] = None):
-        """views: instead of allocating, borrow the caller's tensors (theta, m, v, vhat: d floats each; e: a view
+                 views: Optional[Dict[str, torch.Tensor]] = None, block_k=None):
+        """block_k (TOPK_BLOCKS): coordinates kept in every block; a worker's list then has sum(block_k) entries,
+        block after block, and k is ignored.
+        views: instead of allocating, borrow the caller's tensors (theta, m, v, vhat: d floats each; e: a view
         whose first element is row 0, column 0 of this context's residuals and whose row stride is ld) -- how a
         context is laid over a slice of larger buffers; theta0 is then ignored."""
         self.n, self.d, self.k, self.compressor = int(n), int(d), int(k), int(compressor)
+        self._kb = None
+        if block_k is not None:
+            self._kb = np.ascontiguousarray(block_k, dtype=np.int64)
+            self.k = int(self._kb.sum())
         self.ld = padded_ld(d) if ld is None else int(ld)
         self.device = torch.device(device)
         dev = self.device
@@ -152,6 +159,8 @@ class Compams:
             self.M = self._off.size - 1
             cfg.block_offsets = self._off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
         cfg.num_blocks = self.M
+        if self._kb is not None:
+            cfg.block_k = self._kb.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
         cfg.beta1, cfg.beta2, cfg.eps, cfg.eps_mode, cfg.flags = beta1, beta2, eps, eps_mode, flags
         cfg.theta, cfg.m, cfg.v, cfg.vhat = (self.theta.data_ptr(), self.m.data_ptr(), self.v.data_ptr(),
                                              self.vhat.data_ptr())
@@ -193,7 +202,7 @@ class Compams:
         if name == "last_scales":
             return t.view(self.n, self.M)
         if name == "counters":
-            return t.view(self.n, COUNTERS_PER_ROW)
+            return t.view(-1, COUNTERS_PER_ROW)
         return t
 
     # -- the messages on the wire ----------------------------------------------------------------
@@ -216,7 +225,7 @@ class Compams:
         and the per-message status words."""
         assert messages.dtype == torch.int32 and messages.is_cuda and messages.is_contiguous()
         assert messages.shape[0] == self.n
-        if self.compressor == TOPK:
+        if self.compressor in (TOPK, TOPK_BLOCKS):
             a = torch.empty((self.n, self.k), dtype=torch.int32, device=self.device)
             b = torch.empty((self.n, self.k), dtype=torch.float32, device=self.device)
         else:

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -47,7 +48,7 @@ void launcher_end(Launcher* L, int slot, hipStream_t stream) {
 namespace {
 
 const char* const kSlotNames[kNumSlots] = {
-    "topk_pass_a", "topk_level1", "topk_level2", "topk_count", "topk_final",
+    "topk_pass_a", "topk_level1", "topk_level2", "topk_count", "topk_final", "topk_emit", "topk_offsets",
     "bs_pass1", "bs_finalize", "bs_pass2", "bs_amsgrad", "none_amsgrad", "wire_encode", "wire_decode"};
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -56,20 +57,73 @@ struct Layout {
   size_t total;
   // top-k
   size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_total,
-      wire_tile_off, wire_tile_sum;
+      wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_sweep, map_count, map_emit, map_final;
   // block-sign
   size_t offsets, chunk_block, acc, special, done, scales, bits;
   uint32_t cap_alloc, num_chunks, words;
+  // top-k inside every block
+  uint64_t k_total;
+  TopkFlat flat;
 };
+
+bool blocks_valid(const compams_config* c) {
+  const int64_t* o = c->block_offsets;
+  if (c->num_blocks < 1 || c->num_blocks > c->d || !o || o[0] != 0 || o[c->num_blocks] != c->d) return false;
+  for (int64_t b = 0; b < c->num_blocks; ++b)
+    if (o[b + 1] <= o[b]) return false;
+  return true;
+}
 
 bool basic_valid(const compams_config* c) {
   if (!c) return false;
   if (c->n < 1 || c->d < 1 || c->d >= (int64_t(1) << 31)) return false;
-  if (c->compressor != COMPAMS_NONE && c->compressor != COMPAMS_TOPK && c->compressor != COMPAMS_BLOCKSIGN)
+  if (c->compressor != COMPAMS_NONE && c->compressor != COMPAMS_TOPK && c->compressor != COMPAMS_BLOCKSIGN &&
+      c->compressor != COMPAMS_TOPK_BLOCKS)
     return false;
   if (c->compressor == COMPAMS_TOPK && (c->k < 1 || c->k > c->d)) return false;
   if (c->compressor == COMPAMS_BLOCKSIGN && (c->num_blocks < 1 || c->num_blocks > c->d)) return false;
+  if (c->compressor == COMPAMS_TOPK_BLOCKS) {  // its workspace depends on the blocks: they are checked here already
+    if (!blocks_valid(c) || !c->block_k) return false;
+    for (int64_t b = 0; b < c->num_blocks; ++b)
+      if (c->block_k[b] < 1 || c->block_k[b] > c->block_offsets[b + 1] - c->block_offsets[b]) return false;
+  }
   return true;
+}
+
+// Top-k inside every block: the shape of one block's selection problem and how many workgroups it gets.
+struct BlockShape {
+  uint32_t off, d, k, nc, cap, cpw, groups_first, groups_sweep, count_blocks, emit_slots;
+};
+
+std::vector<BlockShape> block_shapes(const compams_config* c) {
+  const size_t M = static_cast<size_t>(c->num_blocks);
+  std::vector<BlockShape> v(M);
+  uint64_t chunks_per_worker = 0;
+  for (size_t b = 0; b < M; ++b) {
+    BlockShape& s = v[b];
+    s.off = static_cast<uint32_t>(c->block_offsets[b]);
+    s.d = static_cast<uint32_t>(c->block_offsets[b + 1] - c->block_offsets[b]);
+    s.k = static_cast<uint32_t>(c->block_k[b]);
+    s.nc = (s.d + kChunk - 1) / kChunk;
+    const uint64_t cap = 8ull * s.k + 8192;
+    s.cap = cap > s.d ? s.d : static_cast<uint32_t>(cap);
+    s.cpw = count_chunks_per_block(s.nc);
+    s.count_blocks = (s.nc + s.cpw - 1) / s.cpw;
+    s.emit_slots = (s.nc + kWaves - 1) / kWaves;
+    chunks_per_worker += s.nc;
+  }
+  // about 2048 workgroups in the first pass (blocks differ in size by orders of magnitude: small pieces, handed
+  // out largest first, are what keeps the compute units evenly busy; measured on MI355X) and in the sweeps over
+  // all workers, at least one per problem
+  const uint64_t all = chunks_per_worker * static_cast<uint64_t>(c->n);
+  const uint32_t per_first = static_cast<uint32_t>(std::max<uint64_t>(8, (all + 2047) / 2048));
+  const uint32_t per_sweep = static_cast<uint32_t>(std::max<uint64_t>(4, (all + 2047) / 2048));
+  for (BlockShape& s : v) {
+    const uint32_t most = (s.nc + kWaves - 1) / kWaves;  // one chunk per wavefront at least
+    s.groups_first = std::max<uint32_t>(1, std::min<uint32_t>(most, (s.nc + per_first / 2) / per_first));
+    s.groups_sweep = std::max<uint32_t>(1, std::min<uint32_t>(most, (s.nc + per_sweep / 2) / per_sweep));
+  }
+  return v;
 }
 
 Layout make_layout(const compams_config* c) {
@@ -104,6 +158,52 @@ Layout make_layout(const compams_config* c) {
     L.wire_total = take(n * 4);
     L.wire_tile_off = take(n * ((k + kWireTile - 1) / kWireTile) * 4);
     L.wire_tile_sum = take(n * ((k + kWireTile - 1) / kWireTile) * 4);
+    L.sel_off_srv = take(n * (nc + 1) * 4);
+  } else if (c->compressor == COMPAMS_TOPK_BLOCKS) {
+    const std::vector<BlockShape> shapes = block_shapes(c);
+    const size_t M = shapes.size(), S = n * M;
+    size_t k = 0, chunks = 0, caps = 0, wg_first = 0, wg_sweep = 0, wg_count = 0, wg_emit = 0;
+    uint32_t cap_max = 0;
+    for (const BlockShape& b : shapes) {
+      k += b.k; chunks += b.nc; caps += b.cap; cap_max = std::max(cap_max, b.cap);
+      wg_first += b.groups_first; wg_sweep += b.groups_sweep; wg_count += b.count_blocks; wg_emit += b.emit_slots;
+    }
+    L.k_total = k;
+    L.cap_alloc = cap_max;
+    L.flat.wg_first = static_cast<uint32_t>(n * wg_first);
+    L.flat.wg_sweep = static_cast<uint32_t>(n * wg_sweep);
+    L.flat.wg_count = static_cast<uint32_t>(n * wg_count);
+    L.flat.wg_emit = static_cast<uint32_t>(n * wg_emit);
+    L.flat.wg_final = static_cast<uint32_t>(chunks);
+    L.flat.blocks = static_cast<uint32_t>(M);
+    L.flat.chunk_stride = static_cast<uint32_t>(chunks);
+    L.flat.seloff_stride = static_cast<uint32_t>(chunks + M);
+    L.flat.cand_stride = caps;
+    L.rows = take(S * sizeof(TopkRow));
+    L.counters = take(S * COMPAMS_COUNTERS_PER_ROW * 4);
+    L.hist0 = take(S * kNB0 * 4);
+    L.hist1 = take(S * kNB1 * 4);
+    L.hist1x = take(S * kTracked * kNB1 * 4);
+    L.hist2 = take(S * kNB2 * 4);
+    L.chunk_rec = take(n * chunks * 16);
+    L.blk = take(S * kMaxCountBlocks * 8);
+    L.sel_off = take(n * (chunks + M) * 4);
+    L.desc = take(n * chunks * 8);
+    L.cand = take(n * caps * 8);
+    L.idx = take(n * k * 4);
+    L.val = take(n * k * 4);
+    L.tau = take(S * 4);
+    L.count_gt = take(S * 4);
+    L.wire_total = take(n * 4);
+    L.wire_tile_off = take(n * ((k + kWireTile - 1) / kWireTile) * 4);
+    L.wire_tile_sum = take(n * ((k + kWireTile - 1) / kWireTile) * 4);
+    L.sel_off_srv = take(n * (nc + 1) * 4);
+    L.segs = take(S * sizeof(Seg));
+    L.map_first = take(L.flat.wg_first * sizeof(WgSlot));
+    L.map_sweep = take(L.flat.wg_sweep * sizeof(WgSlot));
+    L.map_count = take(L.flat.wg_count * sizeof(WgSlot));
+    L.map_emit = take(L.flat.wg_emit * sizeof(WgSlot));
+    L.map_final = take(L.flat.wg_final * sizeof(WgSlot));
   } else if (c->compressor == COMPAMS_BLOCKSIGN) {
     const size_t M = static_cast<size_t>(c->num_blocks);
     L.offsets = take((M + 1) * 4);
@@ -122,6 +222,23 @@ Layout make_layout(const compams_config* c) {
 }  // namespace compams
 
 using namespace compams;
+
+// Largest message of one worker in 32-bit words (k: entries of a worker's list).
+static size_t wire_capacity_words(int compressor, size_t k, size_t d, size_t num_blocks) {
+  if (compressor == COMPAMS_TOPK || compressor == COMPAMS_TOPK_BLOCKS) {
+    const size_t tiles = (k + kWireTile - 1) / kWireTile;  // header, a width byte per tile, at most 31 bits per gap
+    return 3 + (tiles + 3) / 4 + 2 * k;
+  }
+  if (compressor == COMPAMS_BLOCKSIGN) return 3 + (d + 31) / 32 + num_blocks;
+  return 0;
+}
+
+static size_t ctx_wire_capacity(const compams_config& c) {  // a context's configuration holds the list length in k
+  return wire_capacity_words(c.compressor, static_cast<size_t>(c.k), static_cast<size_t>(c.d),
+                             static_cast<size_t>(c.num_blocks));
+}
+
+static bool is_topk(int compressor) { return compressor == COMPAMS_TOPK || compressor == COMPAMS_TOPK_BLOCKS; }
 
 struct compams_ctx {
   compams_config cfg;
@@ -144,7 +261,7 @@ struct compams_ctx {
 static hipError_t settle_residuals(compams_ctx* ctx) {
   if (!ctx->clear_pending) return hipSuccess;
   hipError_t err = hipSuccess;
-  if (ctx->cfg.compressor == COMPAMS_TOPK) err = topk_apply_clear(ctx->geo, ctx->tk, ctx->cfg.e, ctx->last_stream);
+  if (is_topk(ctx->cfg.compressor)) err = topk_apply_clear(ctx->geo, ctx->tk, ctx->cfg.e, ctx->last_stream);
   else if (ctx->cfg.compressor == COMPAMS_BLOCKSIGN)
     err = blocksign_apply_residual(ctx->geo, ctx->bs, ctx->cfg.e, ctx->last_stream);
   if (err == hipSuccess) ctx->clear_pending = false;
@@ -155,7 +272,11 @@ extern "C" {
 
 size_t compams_workspace_size(const compams_config* cfg) {
   if (!basic_valid(cfg)) return 0;
-  return make_layout(cfg).total;
+  try {
+    return make_layout(cfg).total;
+  } catch (...) {
+    return 0;
+  }
 }
 
 int compams_init(const compams_config* cfg, compams_ctx** out) {
@@ -170,19 +291,24 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
   if (misaligned(cfg->theta, 16) || misaligned(cfg->m, 16) || misaligned(cfg->v, 16) || misaligned(cfg->vhat, 16) ||
       (cfg->e && misaligned(cfg->e, 16)) || misaligned(cfg->workspace, 256))
     return COMPAMS_BAD_ALIGNMENT;
-  if (cfg->compressor == COMPAMS_BLOCKSIGN) {
-    const int64_t* o = cfg->block_offsets;
-    if (!o || o[0] != 0 || o[cfg->num_blocks] != cfg->d) return COMPAMS_INVALID_ARG;
+  if (cfg->compressor == COMPAMS_BLOCKSIGN && !blocks_valid(cfg)) return COMPAMS_INVALID_ARG;
+  if (cfg->compressor == COMPAMS_TOPK_BLOCKS)
     for (int64_t b = 0; b < cfg->num_blocks; ++b)
-      if (o[b + 1] <= o[b]) return COMPAMS_INVALID_ARG;
+      if (cfg->block_offsets[b] % 4 != 0) return COMPAMS_BAD_ALIGNMENT;  // every block starts on 16 bytes
+  Layout lay;
+  try {
+    lay = make_layout(cfg);
+  } catch (...) {
+    return COMPAMS_HIP_ERROR;
   }
-  const Layout lay = make_layout(cfg);
   if (cfg->workspace_bytes < lay.total) return COMPAMS_WORKSPACE_TOO_SMALL;
 
   compams_ctx* ctx = new (std::nothrow) compams_ctx();
   if (!ctx) return COMPAMS_HIP_ERROR;
   ctx->cfg = *cfg;
-  ctx->cfg.block_offsets = nullptr;  // the host array is the caller's; a device copy is made below
+  ctx->cfg.block_offsets = nullptr;  // the host arrays are the caller's; device copies are made below
+  ctx->cfg.block_k = nullptr;
+  if (cfg->compressor == COMPAMS_TOPK_BLOCKS) ctx->cfg.k = static_cast<int64_t>(lay.k_total);
   ctx->lay = lay;
   ctx->steps = 0;
   ctx->clear_pending = false;
@@ -194,7 +320,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
   geo.d = static_cast<uint32_t>(cfg->d);
   geo.ld = cfg->ld;
   geo.num_chunks = lay.num_chunks;
-  geo.k = cfg->compressor == COMPAMS_TOPK ? static_cast<uint32_t>(cfg->k) : 0;
+  geo.k = is_topk(cfg->compressor) ? static_cast<uint32_t>(ctx->cfg.k) : 0;
   geo.num_blocks = cfg->compressor == COMPAMS_BLOCKSIGN ? static_cast<uint32_t>(cfg->num_blocks) : 0;
   geo.words = lay.words;
   geo.count_cpw = count_chunks_per_block(lay.num_chunks);
@@ -203,7 +329,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
   hipError_t err = hipSuccess;
   auto ok = [&](hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; };
 
-  if (cfg->compressor == COMPAMS_TOPK) {
+  if (is_topk(cfg->compressor)) {
     TopkWorkspace& t = ctx->tk;
     t.rows = reinterpret_cast<TopkRow*>(w + lay.rows);
     t.counters = reinterpret_cast<uint32_t*>(w + lay.counters);
@@ -226,9 +352,65 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     ctx->tkopt.cap = lay.cap_alloc;
     ctx->tkopt.predict = 1;
     ctx->tkopt.force_dense = 0;
+    t.sel_off_srv = reinterpret_cast<uint32_t*>(w + lay.sel_off_srv);
+    t.segs = nullptr; t.map_first = t.map_sweep = t.map_count = t.map_emit = t.map_final = nullptr;
     // control blocks, counters, histograms and chunk tables start at zero; lists need no initial value
     ok(fill_u32(reinterpret_cast<uint32_t*>(w), lay.cand / 4, 0u, s0));
     ok(fill_u32(reinterpret_cast<uint32_t*>(w + lay.idx), (lay.total - lay.idx) / 4, 0u, s0));
+    if (cfg->compressor == COMPAMS_TOPK_BLOCKS) {
+      // the segments (worker-major: worker i, block b is segment i * M + b) and the workgroups of the flat launches
+      std::vector<Seg> segs;
+      std::vector<WgSlot> m_first, m_sweep, m_count, m_emit, m_final;
+      try {
+        const std::vector<BlockShape> shapes = block_shapes(cfg);
+        const size_t M = shapes.size();
+        uint64_t chunks = 0, caps = 0;
+        for (const BlockShape& b : shapes) { chunks += b.nc; caps += b.cap; }
+        segs.resize(static_cast<size_t>(cfg->n) * M);
+        for (int64_t i = 0; i < cfg->n; ++i) {
+          uint64_t c_at = 0, cap_at = 0, k_at = 0;
+          for (size_t b = 0; b < M; ++b) {
+            const BlockShape& sh = shapes[b];
+            const uint32_t si = static_cast<uint32_t>(static_cast<size_t>(i) * M + b);
+            Seg& sg = segs[si];
+            std::memset(&sg, 0, sizeof sg);
+            sg.elem_off = i * cfg->ld + sh.off;
+            sg.chunk_base = static_cast<uint64_t>(i) * chunks + c_at;
+            sg.seloff_base = static_cast<uint64_t>(i) * (chunks + M) + c_at + b;
+            sg.cand_base = static_cast<uint64_t>(i) * caps + cap_at;
+            sg.list_base = static_cast<uint64_t>(i) * lay.k_total + k_at;
+            sg.d = sh.d; sg.k = sh.k; sg.num_chunks = sh.nc; sg.cap = sh.cap; sg.coord_base = sh.off;
+            sg.count_cpw = sh.cpw;
+            sg.groups_first = sh.groups_first; sg.groups_sweep = sh.groups_sweep; sg.count_blocks = sh.count_blocks;
+            for (uint32_t q = 0; q < sh.groups_first; ++q) m_first.push_back(WgSlot{si, q});
+            for (uint32_t q = 0; q < sh.groups_sweep; ++q) m_sweep.push_back(WgSlot{si, q});
+            for (uint32_t q = 0; q < sh.count_blocks; ++q) m_count.push_back(WgSlot{si, q});
+            for (uint32_t q = 0; q < sh.emit_slots; ++q) m_emit.push_back(WgSlot{si, q * static_cast<uint32_t>(kWaves)});
+            if (i == 0)
+              for (uint32_t q = 0; q < sh.nc; ++q) m_final.push_back(WgSlot{si, q});
+            c_at += sh.nc; cap_at += sh.cap; k_at += sh.k;
+          }
+        }
+        // the first pass hands out its workgroups in launch order: the longest ones first
+        auto work = [&](const WgSlot& a) {
+          return (segs[a.seg].num_chunks + segs[a.seg].groups_first - 1) / segs[a.seg].groups_first;
+        };
+        std::stable_sort(m_first.begin(), m_first.end(), [&](const WgSlot& a, const WgSlot& b) { return work(a) > work(b); });
+      } catch (...) { delete ctx; return COMPAMS_HIP_ERROR; }
+      ok(hipStreamSynchronize(s0));
+      ok(hipMemcpy(w + lay.segs, segs.data(), segs.size() * sizeof(Seg), hipMemcpyHostToDevice));
+      ok(hipMemcpy(w + lay.map_first, m_first.data(), m_first.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
+      ok(hipMemcpy(w + lay.map_sweep, m_sweep.data(), m_sweep.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
+      ok(hipMemcpy(w + lay.map_count, m_count.data(), m_count.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
+      ok(hipMemcpy(w + lay.map_emit, m_emit.data(), m_emit.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
+      ok(hipMemcpy(w + lay.map_final, m_final.data(), m_final.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
+      t.segs = reinterpret_cast<const Seg*>(w + lay.segs);
+      t.map_first = reinterpret_cast<const WgSlot*>(w + lay.map_first);
+      t.map_sweep = reinterpret_cast<const WgSlot*>(w + lay.map_sweep);
+      t.map_count = reinterpret_cast<const WgSlot*>(w + lay.map_count);
+      t.map_emit = reinterpret_cast<const WgSlot*>(w + lay.map_emit);
+      t.map_final = reinterpret_cast<const WgSlot*>(w + lay.map_final);
+    }
   } else if (cfg->compressor == COMPAMS_BLOCKSIGN) {
     BlocksignWorkspace& b = ctx->bs;
     b.offsets = reinterpret_cast<uint32_t*>(w + lay.offsets);
@@ -294,10 +476,14 @@ static int step_impl(compams_ctx* ctx, const float* g, float lr, bool workers_on
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
   try {
-    if (c.compressor == COMPAMS_TOPK) {
+    if (is_topk(c.compressor)) {
       const bool may_predict = ctx->steps > 0 && ctx->tkopt.predict && !ctx->tkopt.force_dense;
-      err = topk_step(ctx->geo, ctx->tk, ctx->tkopt, ap, g, c.e, c.theta, c.m, c.v, c.vhat, may_predict,
-                      ctx->clear_pending, workers_only, stream, L);
+      if (c.compressor == COMPAMS_TOPK)
+        err = topk_step(ctx->geo, ctx->tk, ctx->tkopt, ap, g, c.e, c.theta, c.m, c.v, c.vhat, may_predict,
+                        ctx->clear_pending, workers_only, stream, L);
+      else
+        err = topk_blocks_step(ctx->geo, ctx->tk, ctx->tkopt, ap, ctx->lay.flat, g, c.e, c.theta, c.m, c.v, c.vhat,
+                               may_predict, ctx->clear_pending, workers_only, stream, L);
       ctx->clear_pending = true;
     } else if (c.compressor == COMPAMS_BLOCKSIGN) {
       err = blocksign_step(ctx->geo, ctx->bs, ap, g, c.e, c.theta, c.m, c.v, c.vhat, ctx->clear_pending, workers_only,
@@ -328,7 +514,7 @@ int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stri
   if (!ctx || !messages || !status_out) return COMPAMS_INVALID_ARG;
   const compams_config& c = ctx->cfg;
   if (c.compressor == COMPAMS_NONE) return COMPAMS_BAD_STATE;
-  if (stride_words < static_cast<int64_t>(compams_wire_capacity(&c))) return COMPAMS_INVALID_ARG;
+  if (stride_words < static_cast<int64_t>(ctx_wire_capacity(c))) return COMPAMS_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(messages) % 4 != 0 || reinterpret_cast<uintptr_t>(status_out) % 4 != 0 ||
       reinterpret_cast<uintptr_t>(words) % 4 != 0)
     return COMPAMS_BAD_ALIGNMENT;
@@ -344,7 +530,7 @@ int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stri
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
   try {
-    if (c.compressor == COMPAMS_TOPK) {
+    if (is_topk(c.compressor)) {
       err = wire_decode_topk(ctx->geo, ctx->tk, messages, stride_words, words, ctx->tk.idx, ctx->tk.val, status_out,
                              stream, L);
       if (err == hipSuccess)
@@ -367,7 +553,8 @@ int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* co
   const int64_t n = c.n, d = c.d;
   const void* p = nullptr;
   int64_t cnt = 0;
-  const bool tk = c.compressor == COMPAMS_TOPK, bs = c.compressor == COMPAMS_BLOCKSIGN;
+  const bool tk = is_topk(c.compressor), bs = c.compressor == COMPAMS_BLOCKSIGN;
+  const int64_t problems = c.compressor == COMPAMS_TOPK_BLOCKS ? n * c.num_blocks : n;  // selection problems
   switch (which) {
     case COMPAMS_STATE_THETA: p = c.theta; cnt = d; break;
     case COMPAMS_STATE_M: p = c.m; cnt = d; break;
@@ -385,13 +572,13 @@ int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* co
       p = ctx->tk.val; cnt = n * c.k; break;
     case COMPAMS_STATE_LAST_THRESHOLD:
       if (!tk) return COMPAMS_BAD_STATE;
-      p = ctx->tk.tau; cnt = n; break;
+      p = ctx->tk.tau; cnt = problems; break;
     case COMPAMS_STATE_LAST_COUNT_GT:
       if (!tk) return COMPAMS_BAD_STATE;
-      p = ctx->tk.count_gt; cnt = n; break;
+      p = ctx->tk.count_gt; cnt = problems; break;
     case COMPAMS_STATE_COUNTERS:
       if (!tk) return COMPAMS_BAD_STATE;
-      p = ctx->tk.counters; cnt = n * COMPAMS_COUNTERS_PER_ROW; break;
+      p = ctx->tk.counters; cnt = problems * COMPAMS_COUNTERS_PER_ROW; break;
     case COMPAMS_STATE_LAST_SIGNBITS:
       if (!bs) return COMPAMS_BAD_STATE;
       p = ctx->bs.bits; cnt = n * static_cast<int64_t>(ctx->geo.words); break;
@@ -407,7 +594,7 @@ int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* co
 
 int compams_set_option(compams_ctx* ctx, int option, int64_t value) {
   if (!ctx) return COMPAMS_INVALID_ARG;
-  if (ctx->cfg.compressor != COMPAMS_TOPK) return COMPAMS_BAD_STATE;
+  if (!is_topk(ctx->cfg.compressor)) return COMPAMS_BAD_STATE;
   switch (option) {
     case COMPAMS_OPT_CANDIDATE_CAP:
       if (value < 0 || value > static_cast<int64_t>(ctx->lay.cap_alloc)) return COMPAMS_INVALID_ARG;
@@ -487,27 +674,26 @@ const char* compams_strerror(int status) {
 
 size_t compams_wire_capacity(const compams_config* cfg) {
   if (!basic_valid(cfg)) return 0;
-  if (cfg->compressor == COMPAMS_TOPK) {  // header, a width byte per tile of 256 gaps, at most 31 bits per gap
-    const size_t k = static_cast<size_t>(cfg->k), tiles = (k + kWireTile - 1) / kWireTile;
-    return 3 + (tiles + 3) / 4 + 2 * k;
+  size_t k = static_cast<size_t>(cfg->k);
+  if (cfg->compressor == COMPAMS_TOPK_BLOCKS) {
+    k = 0;
+    for (int64_t b = 0; b < cfg->num_blocks; ++b) k += static_cast<size_t>(cfg->block_k[b]);
   }
-  if (cfg->compressor == COMPAMS_BLOCKSIGN)
-    return 3 + (static_cast<size_t>(cfg->d) + 31) / 32 + static_cast<size_t>(cfg->num_blocks);
-  return 0;
+  return wire_capacity_words(cfg->compressor, k, static_cast<size_t>(cfg->d), static_cast<size_t>(cfg->num_blocks));
 }
 
 int compams_encode(compams_ctx* ctx, uint32_t* messages, int64_t stride_words, uint32_t* words_out, void* hip_stream) {
   if (!ctx || !messages || !words_out) return COMPAMS_INVALID_ARG;
   const compams_config& c = ctx->cfg;
   if (c.compressor == COMPAMS_NONE || ctx->steps == 0) return COMPAMS_BAD_STATE;
-  if (stride_words < static_cast<int64_t>(compams_wire_capacity(&c))) return COMPAMS_INVALID_ARG;
+  if (stride_words < static_cast<int64_t>(ctx_wire_capacity(c))) return COMPAMS_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(messages) % 4 != 0 || reinterpret_cast<uintptr_t>(words_out) % 4 != 0)
     return COMPAMS_BAD_ALIGNMENT;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
   try {
-    err = c.compressor == COMPAMS_TOPK
+    err = is_topk(c.compressor)
               ? wire_encode_topk(ctx->geo, ctx->tk, messages, stride_words, words_out, stream, L)
               : wire_encode_blocksign(ctx->geo, ctx->bs, messages, stride_words, words_out, stream, L);
   } catch (...) {
@@ -521,7 +707,7 @@ int compams_decode(compams_ctx* ctx, const uint32_t* messages, int64_t stride_wo
   if (!ctx || !messages || !out_a || !out_b || !status_out) return COMPAMS_INVALID_ARG;
   const compams_config& c = ctx->cfg;
   if (c.compressor == COMPAMS_NONE) return COMPAMS_BAD_STATE;
-  if (stride_words < static_cast<int64_t>(compams_wire_capacity(&c))) return COMPAMS_INVALID_ARG;
+  if (stride_words < static_cast<int64_t>(ctx_wire_capacity(c))) return COMPAMS_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(messages) % 4 != 0 || reinterpret_cast<uintptr_t>(out_a) % 4 != 0 ||
       reinterpret_cast<uintptr_t>(out_b) % 4 != 0 || reinterpret_cast<uintptr_t>(status_out) % 4 != 0 ||
       reinterpret_cast<uintptr_t>(words) % 4 != 0)
@@ -530,7 +716,7 @@ int compams_decode(compams_ctx* ctx, const uint32_t* messages, int64_t stride_wo
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
   try {
-    err = c.compressor == COMPAMS_TOPK
+    err = is_topk(c.compressor)
               ? wire_decode_topk(ctx->geo, ctx->tk, messages, stride_words, words, static_cast<int32_t*>(out_a),
                                  static_cast<float*>(out_b), status_out, stream, L)
               : wire_decode_blocksign(ctx->geo, messages, stride_words, words, static_cast<uint32_t*>(out_a),

@@ -124,6 +124,7 @@ struct TopkWorkspace {
   const WgSlot* map_sweep;
   const WgSlot* map_count;
   const WgSlot* map_emit;   // .group = first chunk of the four that the workgroup's wavefronts take
+  const WgSlot* map_final;  // .seg = block (worker 0's segment of it), .group = chunk of the block
   uint32_t* sel_off_srv;    // n * (chunks of a whole row + 1) : list offsets per chunk of coordinates, for the
                             //                                   server's lines run from lists
 };
@@ -171,7 +172,7 @@ struct Geometry {
 
 // Kernel slots for optional timing.
 enum KernelSlot {
-  kSlotPassA = 0, kSlotLevel1, kSlotLevel2, kSlotCount, kSlotTopkFinal,
+  kSlotPassA = 0, kSlotLevel1, kSlotLevel2, kSlotCount, kSlotTopkFinal, kSlotTopkEmit, kSlotTopkOffsets,
   kSlotBsPass1, kSlotBsFinal, kSlotBsPass2, kSlotBsAms,
   kSlotNoneAms, kSlotWireEncode, kSlotWireDecode, kNumSlots
 };
@@ -183,6 +184,17 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
                      const float* g, float* e, float* theta, float* m, float* v, float* vhat,
                      bool first_pass_may_predict, bool clear_pending, bool workers_only, hipStream_t stream,
                      Launcher* L);
+// Sizes of the flat launches of top-k inside every block.
+struct TopkFlat {
+  uint32_t wg_first, wg_sweep, wg_count, wg_emit, wg_final;
+  // from worker i's segment of a block to worker i + 1's: segment index, chunk tables, list offsets, candidates
+  uint32_t blocks, chunk_stride, seloff_stride;
+  uint64_t cand_stride;
+};
+hipError_t topk_blocks_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
+                            const TopkFlat& flat, const float* g, float* e, float* theta, float* m, float* v,
+                            float* vhat, bool first_pass_may_predict, bool clear_pending, bool workers_only,
+                            hipStream_t stream, Launcher* L);
 hipError_t topk_server_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
                             float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L);
 hipError_t topk_apply_clear(const Geometry& geo, const TopkWorkspace& ws, float* e, hipStream_t stream);

@@ -933,6 +933,56 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
 //            one worker's coordinates are distinct, so no atomics are needed.
 //   Phase 3: gbar = sum / n and the AMSGrad moment and parameter update (server lines of Algorithm 2).
 // ---------------------------------------------------------------------------------------------
+// One wavefront writes the selected entries of chunk c of one selection problem to their places in the list:
+// `at` is where the chunk's slice starts, eq_seen how many keys equal to tau lie in earlier chunks (ties are
+// taken in coordinate order until r are in).  Coordinates are written relative to the worker's row
+// (coord_base = the problem's first coordinate there).
+__device__ __forceinline__ void emit_chunk(uint32_t mode, const float* __restrict__ er, uint32_t d, uint32_t c,
+                                           const uint2* __restrict__ candr, const uint2* __restrict__ descr,
+                                           uint32_t cap, uint32_t tau, uint32_t r, bool all_ties, uint32_t eq_seen,
+                                           uint32_t at, int32_t* __restrict__ idx, float* __restrict__ val, uint32_t k,
+                                           uint32_t coord_base) {
+  for_each_round(mode, er, d, c, candr, descr, cap, [&](const Entry4& en, int slots) {
+    bool sel[4] = {false, false, false, false};
+    if (all_ties) {
+      for (int s = 0; s < slots; ++s) sel[s] = en.ok[s] && key_of_bits(en.bits[s]) >= tau;
+    } else {
+      uint64_t be[4];
+      uint32_t below = 0, total = 0;
+      for (int s = 0; s < slots; ++s) {
+        be[s] = ballot64(en.ok[s] && key_of_bits(en.bits[s]) == tau);
+        below += count_below(be[s]);
+        total += popc64(be[s]);
+      }
+      uint32_t rank = eq_seen + below;  // ties before this lane's first slot, in coordinate order
+      for (int s = 0; s < slots; ++s) {
+        const uint32_t key = key_of_bits(en.bits[s]);
+        const bool is_eq = en.ok[s] && key == tau;
+        sel[s] = en.ok[s] && (key > tau || (is_eq && rank < r));
+        rank += is_eq;
+      }
+      eq_seen += total;
+    }
+    uint64_t bs[4];
+    uint32_t below = 0, total = 0;
+    for (int s = 0; s < slots; ++s) {
+      bs[s] = ballot64(sel[s]);
+      below += count_below(bs[s]);
+      total += popc64(bs[s]);
+    }
+    uint32_t pos = at + below;
+    for (int s = 0; s < slots; ++s)
+      if (sel[s]) {
+        if (pos < k) {  // always true when the counts are consistent
+          idx[pos] = static_cast<int32_t>(coord_base + en.j[s]);
+          val[pos] = __uint_as_float(en.bits[s]);
+        }
+        ++pos;
+      }
+    at += total;
+  });
+}
+
 constexpr int kPerWave = 4;                       // workers per wavefront and tile
 constexpr int kTileWorkers = kWaves * kPerWave;
 
@@ -948,25 +998,70 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
 // (eight wavefronts per SIMD: the streaming phase needs the occupancy more than phase 1 needs registers)
 enum : int { kWholeStep = 0, kWorkerHalf = 1, kServerHalf = 2 };
 
-template <int ROLE>
+// UNI: one selection problem per worker over its whole row, one workgroup per chunk of the row.  !UNI (whole step
+// only): top-k inside every block; a workgroup takes one chunk of one block (flat launch over map_final) and goes
+// through the workers' segments of that block, which lie a fixed stride apart in every table.
+struct FinalCtx {
+  uint32_t c;                     // chunk of the problem
+  uint32_t base;                  // first coordinate of the chunk, in coordinates of the worker's row
+  uint32_t coord_base, d_loc;     // the problem covers coordinates coord_base .. coord_base + d_loc of the row
+  uint32_t k_loc, num_chunks, count_cpw, cap;
+  uint32_t row0, row_stride;      // control block of worker i: row0 + i * row_stride
+  size_t chunk0, chunk_stride, seloff0, seloff_stride, cand0, cand_stride, list0, list_stride;
+};
+
+template <bool UNI>
+__device__ __forceinline__ FinalCtx final_ctx(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt,
+                                              const TopkFlat& flat) {
+  FinalCtx f;
+  if (UNI) {
+    f.c = blockIdx.x;
+    f.base = f.c * kChunk;
+    f.coord_base = 0; f.d_loc = geo.d; f.k_loc = geo.k; f.num_chunks = geo.num_chunks; f.count_cpw = geo.count_cpw;
+    f.cap = opt.cap;
+    f.row0 = 0; f.row_stride = 1;
+    f.chunk0 = 0; f.chunk_stride = geo.num_chunks;
+    f.seloff0 = 0; f.seloff_stride = geo.num_chunks + 1;
+    f.cand0 = 0; f.cand_stride = opt.cap;
+    f.list0 = 0; f.list_stride = geo.k;
+  } else {
+    const WgSlot slot = ws.map_final[blockIdx.x];
+    const Seg sg = ws.segs[slot.seg];  // worker 0's segment of the block
+    f.c = slot.group;
+    f.coord_base = sg.coord_base;
+    f.base = sg.coord_base + f.c * kChunk;
+    f.d_loc = sg.d; f.k_loc = sg.k; f.num_chunks = sg.num_chunks; f.count_cpw = sg.count_cpw;
+    f.cap = opt.cap < sg.cap ? opt.cap : sg.cap;
+    f.row0 = slot.seg; f.row_stride = flat.blocks;
+    f.chunk0 = sg.chunk_base; f.chunk_stride = flat.chunk_stride;
+    f.seloff0 = sg.seloff_base; f.seloff_stride = flat.seloff_stride;
+    f.cand0 = sg.cand_base; f.cand_stride = flat.cand_stride;
+    f.list0 = sg.list_base; f.list_stride = geo.k;  // a worker's list holds the lists of all its blocks
+  }
+  return f;
+}
+
+template <int ROLE, bool UNI>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_topk_final(
     float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v, float* __restrict__ vhat,
-    const float* __restrict__ e, Geometry geo, TopkWorkspace ws, TopkOptions opt, AmsParams p) {
+    const float* __restrict__ e, Geometry geo, TopkWorkspace ws, TopkOptions opt, AmsParams p, TopkFlat flat) {
+  static_assert(UNI || ROLE == kWholeStep, "the halves of a step work on whole rows");
   __shared__ float gs[kChunk];
   __shared__ uint32_t sh_lo[kTileWorkers], sh_hi[kTileWorkers], sh_eqb[kTileWorkers];
-  const uint32_t c = blockIdx.x;
-  const uint32_t base = c * kChunk;
+  const FinalCtx f = final_ctx<UNI>(geo, ws, opt, flat);
+  const uint32_t c = f.c;
+  const uint32_t base = f.base;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   if (ROLE != kWorkerHalf)
     for (int t = threadIdx.x; t < kChunk; t += kWG) gs[t] = 0.0f;
   if (ROLE != kServerHalf && c == 0)  // the next step's first pass allocates its candidate lists from the start
-    for (uint32_t i = threadIdx.x; i < geo.n; i += kWG) ws.rows[i].cursor = 0;
-  const uint32_t my_block = c / geo.count_cpw;  // count blocks before this chunk's
+    for (uint32_t i = threadIdx.x; i < geo.n; i += kWG) ws.rows[f.row0 + i * f.row_stride].cursor = 0;
+  const uint32_t my_block = c / f.count_cpw;  // count blocks before this chunk's
 
   for (uint32_t i0 = 0; i0 < geo.n; i0 += kTileWorkers) {
     if (ROLE == kServerHalf) {
       if (threadIdx.x < kTileWorkers && i0 + threadIdx.x < geo.n) {
-        const uint32_t* so = ws.sel_off + static_cast<size_t>(i0 + threadIdx.x) * (geo.num_chunks + 1) + c;
+        const uint32_t* so = ws.sel_off_srv + static_cast<size_t>(i0 + threadIdx.x) * (geo.num_chunks + 1) + c;
         sh_lo[threadIdx.x] = so[0];
         sh_hi[threadIdx.x] = so[1];
       }
@@ -983,14 +1078,14 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         part[u] = make_uint2(0, 0);
         r_[u] = 0;
         if (i < geo.n) {  // wave-uniform
-          rec[u] = ws.chunk_rec[static_cast<size_t>(i) * geo.num_chunks + c];
-          const uint2* blk = ws.blk + static_cast<size_t>(i) * kMaxCountBlocks;
+          rec[u] = ws.chunk_rec[f.chunk0 + i * f.chunk_stride + c];
+          const uint2* blk = ws.blk + static_cast<size_t>(f.row0 + i * f.row_stride) * kMaxCountBlocks;
           for (uint32_t b = lane; b < my_block; b += 64) {
             const uint2 t = blk[b];
             part[u].x += t.x;
             part[u].y += t.y;
           }
-          r_[u] = ws.rows[i].r;
+          r_[u] = ws.rows[f.row0 + i * f.row_stride].r;
         }
       }
 #pragma unroll
@@ -1006,9 +1101,9 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         const uint32_t at = gt_before + taken_before;
         const uint32_t hi = at + rec[u].x + take_here;
         if (lane == 0) {
-          uint32_t* so = ws.sel_off + static_cast<size_t>(i) * (geo.num_chunks + 1);
+          uint32_t* so = ws.sel_off + f.seloff0 + i * f.seloff_stride;
           so[c] = at;  // the next step's first pass finds this chunk's slice of the list here
-          if (c + 1 == geo.num_chunks) so[c + 1] = hi;
+          if (c + 1 == f.num_chunks) so[c + 1] = hi;
           sh_lo[i - i0] = at;
           sh_hi[i - i0] = hi;
           sh_eqb[i - i0] = eq_before;
@@ -1021,54 +1116,16 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       uint32_t at = sh_lo[i - i0];
       const uint32_t hi = sh_hi[i - i0];
       if (hi == at) continue;  // nothing of this worker in the chunk (wave-uniform)
-      const float* er = e + static_cast<int64_t>(i) * geo.ld;
-      const uint2* candr = ws.cand + static_cast<size_t>(i) * opt.cap;
-      const uint2* descr = ws.desc + static_cast<size_t>(i) * geo.num_chunks;
-      int32_t* idx = ws.idx + static_cast<size_t>(i) * geo.k;
-      float* val = ws.val + static_cast<size_t>(i) * geo.k;
-      const TopkRow* rowp = ws.rows + i;
+      const float* er = e + static_cast<int64_t>(i) * geo.ld + f.coord_base;
+      const uint2* candr = ws.cand + f.cand0 + i * f.cand_stride;
+      const uint2* descr = ws.desc + f.chunk0 + i * f.chunk_stride;
+      int32_t* idx = ws.idx + f.list0 + i * f.list_stride;
+      float* val = ws.val + f.list0 + i * f.list_stride;
+      const TopkRow* rowp = ws.rows + f.row0 + i * f.row_stride;
       const uint32_t mode = rowp->mode, tau = rowp->tau, r = rowp->r;
       const bool all_ties = rowp->take_all_ties != 0;
-      uint32_t eq_seen = sh_eqb[i - i0];
-      for_each_round(mode, er, geo.d, c, candr, descr, opt.cap, [&](const Entry4& en, int slots) {
-        bool sel[4] = {false, false, false, false};
-        if (all_ties) {
-          for (int s = 0; s < slots; ++s) sel[s] = en.ok[s] && key_of_bits(en.bits[s]) >= tau;
-        } else {
-          uint64_t be[4];
-          uint32_t below = 0, total = 0;
-          for (int s = 0; s < slots; ++s) {
-            be[s] = ballot64(en.ok[s] && key_of_bits(en.bits[s]) == tau);
-            below += count_below(be[s]);
-            total += popc64(be[s]);
-          }
-          uint32_t rank = eq_seen + below;  // ties before this lane's first slot, in coordinate order
-          for (int s = 0; s < slots; ++s) {
-            const uint32_t key = key_of_bits(en.bits[s]);
-            const bool is_eq = en.ok[s] && key == tau;
-            sel[s] = en.ok[s] && (key > tau || (is_eq && rank < r));
-            rank += is_eq;
-          }
-          eq_seen += total;
-        }
-        uint64_t bs[4];
-        uint32_t below = 0, total = 0;
-        for (int s = 0; s < slots; ++s) {
-          bs[s] = ballot64(sel[s]);
-          below += count_below(bs[s]);
-          total += popc64(bs[s]);
-        }
-        uint32_t pos = at + below;
-        for (int s = 0; s < slots; ++s)
-          if (sel[s]) {
-            if (pos < geo.k) {  // always true when the counts are consistent
-              idx[pos] = static_cast<int32_t>(en.j[s]);
-              val[pos] = __uint_as_float(en.bits[s]);
-            }
-            ++pos;
-          }
-        at += total;
-      });
+      emit_chunk(mode, er, f.d_loc, c, candr, descr, f.cap, tau, r, all_ties, sh_eqb[i - i0], at, idx, val, f.k_loc,
+                 f.coord_base);
     }
     }  // ROLE != kServerHalf
     if (ROLE == kWorkerHalf) continue;
@@ -1091,11 +1148,11 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         vl[u] = 0.0f;
         if (i < i_end) {
           lo[u] = sh_lo[i - i0];
-          hi[u] = sh_hi[i - i0] < geo.k ? sh_hi[i - i0] : geo.k;
+          hi[u] = sh_hi[i - i0] < f.k_loc ? sh_hi[i - i0] : f.k_loc;
           const uint32_t q = lo[u] + threadIdx.x;
           if (q < hi[u]) {
-            jl[u] = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + q]) - base;
-            vl[u] = ws.val[static_cast<size_t>(i) * geo.k + q];
+            jl[u] = static_cast<uint32_t>(ws.idx[f.list0 + i * f.list_stride + q]) - base;
+            vl[u] = ws.val[f.list0 + i * f.list_stride + q];
           }
         }
       }
@@ -1114,8 +1171,8 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
               jj[w] = 0xffffffffu;
               vv[w] = 0.0f;
               if (qq < hi[u]) {
-                jj[w] = static_cast<uint32_t>(ws.idx[static_cast<size_t>(i) * geo.k + qq]) - base;
-                vv[w] = ws.val[static_cast<size_t>(i) * geo.k + qq];
+                jj[w] = static_cast<uint32_t>(ws.idx[f.list0 + i * f.list_stride + qq]) - base;
+                vv[w] = ws.val[f.list0 + i * f.list_stride + qq];
               }
             }
 #pragma unroll
@@ -1129,11 +1186,12 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   }
 
   if (ROLE == kWorkerHalf) return;
+  const uint32_t d_end = f.coord_base + f.d_loc;  // the chunk's coordinates end here at the latest
 #pragma unroll
   for (int r = 0; r < kChunk / (kWG * 4); ++r) {
     const uint32_t t = r * kWG * 4 + threadIdx.x * 4;
     const uint32_t j = base + t;
-    if (j + 3 < geo.d) {
+    if (j + 3 < d_end) {
       float4 th = *reinterpret_cast<float4*>(theta + j), mm = *reinterpret_cast<float4*>(m + j);
       float4 vv = *reinterpret_cast<float4*>(v + j), vh = *reinterpret_cast<float4*>(vhat + j);
       const float4 s = *reinterpret_cast<const float4*>(gs + t);
@@ -1146,7 +1204,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       *reinterpret_cast<float4*>(v + j) = vv;
       *reinterpret_cast<float4*>(vhat + j) = vh;
     } else {
-      for (uint32_t s = 0; s < 4 && j + s < geo.d; ++s) {
+      for (uint32_t s = 0; s < 4 && j + s < d_end; ++s) {
         float th = theta[j + s], mm = m[j + s], vv = v[j + s], vh = vhat[j + s];
         ams_update(gs[t + s] / p.nf, th, mm, vv, vh, p);
         theta[j + s] = th; m[j + s] = mm; v[j + s] = vv; vhat[j + s] = vh;
@@ -1155,13 +1213,55 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   }
 }
 
+// Top-k inside every block: the workers' last lines on their own.  A wavefront takes one chunk of one segment,
+// finds where its slice of the list starts (as phase 1 of the kernel above does for a worker's row) and writes
+// the selected entries there, with coordinates of the worker's whole row.  Flat launch over map_emit.
+__global__ __launch_bounds__(kWG) void k_topk_emit(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
+                                                    TopkOptions opt) {
+  const WgSlot slot = ws.map_emit[blockIdx.x];
+  const Seg sg = ws.segs[slot.seg];
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t c = slot.group + wave;
+  if (c >= sg.num_chunks) return;  // wave-uniform; no barrier in this kernel
+  TopkRow* rowp = ws.rows + slot.seg;
+  if (c == 0 && lane == 0) rowp->cursor = 0;  // the next step's first pass allocates its list from the start
+  const uint4 rec = ws.chunk_rec[sg.chunk_base + c];
+  const uint2* blk = ws.blk + static_cast<size_t>(slot.seg) * kMaxCountBlocks;
+  const uint32_t my_block = c / sg.count_cpw;
+  uint2 part = make_uint2(0, 0);
+  for (uint32_t b = lane; b < my_block; b += 64) {
+    const uint2 t = blk[b];
+    part.x += t.x;
+    part.y += t.y;
+  }
+  const uint32_t r = rowp->r, tau = rowp->tau, mode = rowp->mode;
+  const bool all_ties = rowp->take_all_ties != 0;
+  const uint32_t gt_before = wave_sum(part.x) + rec.z;
+  const uint32_t eq_before = wave_sum(part.y) + rec.w;
+  const uint32_t taken_before = eq_before < r ? eq_before : r;
+  const uint32_t quota = r - taken_before;
+  const uint32_t take_here = rec.y < quota ? rec.y : quota;
+  const uint32_t at = gt_before + taken_before;
+  const uint32_t hi = at + rec.x + take_here;
+  if (lane == 0) {
+    uint32_t* so = ws.sel_off + sg.seloff_base;
+    so[c] = at;
+    if (c + 1 == sg.num_chunks) so[c + 1] = hi;
+  }
+  if (hi == at) return;
+  const uint32_t cap = opt.cap < sg.cap ? opt.cap : sg.cap;
+  emit_chunk(mode, e + sg.elem_off, sg.d, c, ws.cand + sg.cand_base, ws.desc + sg.chunk_base, cap, tau, r, all_ties,
+             eq_before, at, ws.idx + sg.list_base, ws.val + sg.list_base, sg.k, sg.coord_base);
+  (void)geo;
+}
+
 // Where each chunk's slice of a worker's ascending coordinate list starts: sel_off[c] = number of listed
 // coordinates below c * kChunk, for c = 0 .. num_chunks.  The thread of entry q fills the chunks between its
 // predecessor's chunk (exclusive) and its own (inclusive); the last entry also fills the rest up to num_chunks.
 __global__ __launch_bounds__(kWG) void k_topk_list_offsets(Geometry geo, TopkWorkspace ws) {
   const uint32_t row = blockIdx.y;
   const int32_t* idx = ws.idx + static_cast<size_t>(row) * geo.k;
-  uint32_t* so = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
+  uint32_t* so = ws.sel_off_srv + static_cast<size_t>(row) * (geo.num_chunks + 1);
   const uint32_t step = gridDim.x * kWG;
   for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < geo.k; q += step) {
     uint32_t cur = static_cast<uint32_t>(idx[q]) / kChunk;
@@ -1223,11 +1323,43 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   launch(L, kSlotCount, k_topk_count<true>, dim3(count_blocks, geo.n), wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
   if (role == kWorkerHalf)
-    launch(L, kSlotTopkFinal, k_topk_final<kWorkerHalf>, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws,
-           opt, ap);
+    launch(L, kSlotTopkFinal, k_topk_final<kWorkerHalf, true>, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws,
+           opt, ap, TopkFlat{});
   else
-    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep>, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws,
-           opt, ap);
+    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, true>, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws,
+           opt, ap, TopkFlat{});
+  COMPAMS_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+// Top-k inside every block: the same kernels over segments (flat launches), then the lists are complete and
+// the server's lines run from them.
+hipError_t topk_blocks_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
+                            const TopkFlat& flat, const float* g, float* e, float* theta, float* m, float* v,
+                            float* vhat, bool first_pass_may_predict, bool clear_pending, bool workers_only,
+                            hipStream_t stream, Launcher* L) {
+  const dim3 wg(kWG), wga(kWGA), grid_a(flat.wg_first);
+  if (first_pass_may_predict) {
+    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<true, true, false>, grid_a, wga, stream, g, e, geo, ws, opt);
+    else launch(L, kSlotPassA, k_topk_pass_a<true, false, false>, grid_a, wga, stream, g, e, geo, ws, opt);
+  } else {
+    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<false, true, false>, grid_a, wga, stream, g, e, geo, ws, opt);
+    else launch(L, kSlotPassA, k_topk_pass_a<false, false, false>, grid_a, wga, stream, g, e, geo, ws, opt);
+  }
+  COMPAMS_CHECK_LAUNCH();
+  launch(L, kSlotLevel1, k_topk_level1<false>, dim3(flat.wg_sweep), wg, stream, e, geo, ws, opt);
+  COMPAMS_CHECK_LAUNCH();
+  launch(L, kSlotLevel2, k_topk_level2<false>, dim3(flat.wg_sweep), wg, stream, e, geo, ws, opt);
+  COMPAMS_CHECK_LAUNCH();
+  launch(L, kSlotCount, k_topk_count<false>, dim3(flat.wg_count), wg, stream, e, geo, ws, opt);
+  COMPAMS_CHECK_LAUNCH();
+  if (workers_only) {
+    launch(L, kSlotTopkEmit, k_topk_emit, dim3(flat.wg_emit), wg, stream, e, geo, ws, opt);
+  } else {
+    const float* residuals = e;
+    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, false>, dim3(flat.wg_final), wg, stream, theta, m, v, vhat,
+           residuals, geo, ws, opt, ap, flat);
+  }
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -1237,11 +1369,11 @@ hipError_t topk_server_step(const Geometry& geo, const TopkWorkspace& ws, const 
                             float* theta, float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
   uint32_t groups = (geo.k + kWG * 4 - 1) / (kWG * 4);
   if (groups > 256) groups = 256;
-  launch(L, kSlotTopkFinal, k_topk_list_offsets, dim3(groups, geo.n), dim3(kWG), stream, geo, ws);
+  launch(L, kSlotTopkOffsets, k_topk_list_offsets, dim3(groups, geo.n), dim3(kWG), stream, geo, ws);
   COMPAMS_CHECK_LAUNCH();
   const float* no_e = nullptr;
-  launch(L, kSlotTopkFinal, k_topk_final<kServerHalf>, dim3(geo.num_chunks), dim3(kWG), stream, theta, m, v, vhat, no_e,
-         geo, ws, opt, ap);
+  launch(L, kSlotTopkFinal, k_topk_final<kServerHalf, true>, dim3(geo.num_chunks), dim3(kWG), stream, theta, m, v, vhat, no_e,
+         geo, ws, opt, ap, TopkFlat{});
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }

@@ -86,13 +86,18 @@ def test_full_size_resnet18_blocksign_layers():
     run_full("r18_blocksign", 3)
 
 
-def test_full_size_resnet18_topk_per_layer():
-    """Top-k inside every layer tensor (62 contexts over slices of shared buffers) against the oracle's per-block
-    compressor, ResNet-18 shape, 1 % of every tensor."""
+@pytest.mark.parametrize("form", ["one context", "a context per tensor"])
+def test_full_size_resnet18_topk_per_layer(form):
+    """Top-k inside every layer tensor against the oracle's per-block compressor, ResNet-18 shape, 1 % of every
+    tensor: as one context whose launches cover all 16 x 62 selection problems (what bench.py times), and as 62
+    contexts over slices of shared buffers."""
     w = W.get("r18_topk1_layers")
     dev = torch.device("cuda:0")
     th0 = W.theta0(w, dev)
-    gpu = B.CompamsBlockTopk(w.n, w.d, th0, w.block_offsets(), w.block_k())
+    if form == "one context":
+        gpu = B.Compams(w.n, w.d, th0, compressor=B.TOPK_BLOCKS, block_offsets=w.block_offsets(), block_k=w.block_k())
+    else:
+        gpu = B.CompamsBlockTopk(w.n, w.d, th0, w.block_offsets(), w.block_k())
     cpu = O.Oracle(w.n, w.d, th0.cpu().numpy(), compressor=O.TOPK_BLOCKS, block_offsets=w.block_offsets(),
                    block_k=w.block_k())
     scale = W.coordinate_scale(w, dev)
