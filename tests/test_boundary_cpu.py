@@ -35,6 +35,26 @@ def test_header_compiles_as_plain_c(tmp_path):
                     "-o", str(tmp_path / "t.o")], check=True)
 
 
+def test_binding_struct_matches_the_header(tmp_path):
+    """Size of compams_config and the offset of every field, as a C compiler lays out the header's struct."""
+    fields = [f[0] for f in B.compams_config._fields_]
+    src = tmp_path / "layout.c"
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "compams.h"', 'int main(void){',
+             'printf("%zu\\n", sizeof(compams_config));']
+    lines += [f'printf("%zu\\n", offsetof(compams_config, {f}));' for f in fields]
+    lines += ['return 0;}']
+    src.write_text("\n".join(lines))
+    import subprocess
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert out[0] == ctypes.sizeof(B.compams_config)
+    assert out[1:] == [getattr(B.compams_config, f).offset for f in fields]
+    text = open(os.path.join(ROOT, "include", "compams.h")).read()
+    for name, value in (("NONE", B.NONE), ("TOPK", B.TOPK), ("BLOCKSIGN", B.BLOCKSIGN), ("TOPK_BLOCKS", B.TOPK_BLOCKS)):
+        assert re.search(rf"COMPAMS_{name}\s*=\s*{value}\b", text), name
+
+
 def cfg(**kw):
     c = B.compams_config()
     c.n, c.d, c.ld, c.compressor, c.k = 4, 1000, 1000, B.TOPK, 10
@@ -83,6 +103,42 @@ def test_init_rejects_bad_block_offsets():
         c.block_offsets = a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
         h = ctypes.c_void_p()
         assert B.lib().compams_init(ctypes.byref(c), ctypes.byref(h)) == -1
+
+
+def blocks_cfg(off, kb, **kw):
+    a = np.array(off, dtype=np.int64)
+    b = np.array(kb, dtype=np.int64)
+    c = cfg(compressor=B.TOPK_BLOCKS, k=0, num_blocks=len(off) - 1, **kw)
+    c.block_offsets = a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+    if kb is not None and len(kb):
+        c.block_k = b.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+    c._keep = (a, b)
+    return c
+
+
+def test_topk_inside_blocks_is_validated_on_the_host():
+    L = B.lib()
+    good = blocks_cfg([0, 400, 1000], [4, 6])
+    size = L.compams_workspace_size(ctypes.byref(good))
+    assert size > 0 and size % 256 == 0
+    k = 10
+    assert L.compams_wire_capacity(ctypes.byref(good)) == 3 + ((k + 255) // 256 + 3) // 4 + 2 * k
+    assert L.compams_workspace_size(ctypes.byref(blocks_cfg([0, 400, 1000], [40, 60]))) > size
+    for off, kb in (([0, 400, 1000], [401, 1]), ([0, 400, 1000], [0, 1]), ([0, 400, 999], [1, 1]),
+                    ([0, 400, 400, 1000], [1, 1, 1]), ([4, 400, 1000], [1, 1]), ([0, 400, 1000], [])):
+        c = blocks_cfg(off, kb)
+        assert L.compams_workspace_size(ctypes.byref(c)) == 0, (off, kb)
+        assert L.compams_wire_capacity(ctypes.byref(c)) == 0
+        h = ctypes.c_void_p()
+        assert L.compams_init(ctypes.byref(c), ctypes.byref(h)) == -1 and not h.value
+    h = ctypes.c_void_p()
+    assert L.compams_init(ctypes.byref(blocks_cfg([0, 402, 1000], [1, 1])), ctypes.byref(h)) == -2  # 402 % 4 != 0
+    assert L.compams_init(ctypes.byref(blocks_cfg([0, 400, 1000], [4, 6], workspace_bytes=256)), ctypes.byref(h)) == -3
+    assert not h.value
+    # the per-layer workload: scratch stays well under a GiB
+    w = W.get("r18_topk1_layers")
+    c = blocks_cfg(w.block_offsets(), w.block_k(), n=w.n, d=w.d, ld=B.padded_ld(w.d))
+    assert 0 < L.compams_workspace_size(ctypes.byref(c)) < (1 << 30)
 
 
 def test_null_context_is_rejected_everywhere():
