@@ -111,7 +111,13 @@ int compams_init(const compams_config* cfg, compams_ctx** out);
  * coordinates; block-sign with blocks other than aligned 4096-coordinate chunks: everywhere), and the next
  * step applies it while it reads e.  compams_state(COMPAMS_STATE_E) and compams_destroy() apply what is
  * pending first (one kernel on the last step's stream); do not read or write the e buffer between steps by
- * any other route.  Every other result of the step is final when the stream has passed it. */
+ * any other route.  Every other result of the step is final when the stream has passed it.
+ * Stream capture: the call only enqueues kernel launches on hip_stream (no allocation, no synchronisation, no
+ * memset or copy node; profiling must be off), so it may be recorded into a HIP graph.  Which kernels are
+ * enqueued depends on the context's state at that moment (the first step of a context differs from the later
+ * ones; a pending error line is applied by the step that follows): record a step after at least one step has
+ * run, replay it with new gradients copied into the same g, and record it again after a call that applies
+ * the pending error line (compams_state(COMPAMS_STATE_E), compams_server_step) if replays are to follow. */
 int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream);
 
 /* What compams_state() can hand out.  Counts are in elements of the listed type. */
