@@ -165,7 +165,8 @@ def main():
                         "candidates_per_row_last_step": c[:, 1].tolist()}
         else:   # one selection problem per (worker, block): totals
             counters = {"selection_problems": int(c.shape[0]),
-                        "problems_with_dense_rereads_last_step": int((c[:, 0] > 0).sum()),
+                        "problems_without_candidate_list_last_step": int((c[:, 0] == 4).sum()),
+                        "problems_with_one_reread_last_step": int((c[:, 0] == 1).sum()),
                         "candidates_last_step": int(c[:, 1].sum())}
     if args.kernels:
         for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):

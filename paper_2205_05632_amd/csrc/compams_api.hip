@@ -57,12 +57,13 @@ struct Layout {
   size_t total;
   // top-k
   size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_total,
-      wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_sweep, map_count, map_emit, map_final;
+      wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_sweep, map_count, map_emit, map_final, micro_list;
   // block-sign
   size_t offsets, chunk_block, acc, special, done, scales, bits;
   uint32_t cap_alloc, num_chunks, words;
   // top-k inside every block
   uint64_t k_total;
+  size_t num_micro;  // selection problems taken by single wavefronts (top-k per block)
   TopkFlat flat;
 };
 
@@ -92,7 +93,7 @@ bool basic_valid(const compams_config* c) {
 
 // Top-k inside every block: the shape of one block's selection problem and how many workgroups it gets.
 struct BlockShape {
-  uint32_t off, d, k, nc, cap, cpw, groups_first, groups_sweep, count_blocks, emit_slots;
+  uint32_t off, d, k, nc, cap, cpw, groups_first, groups_sweep, count_blocks, emit_slots, micro;
 };
 
 std::vector<BlockShape> block_shapes(const compams_config* c) {
@@ -110,6 +111,7 @@ std::vector<BlockShape> block_shapes(const compams_config* c) {
     s.cpw = count_chunks_per_block(s.nc);
     s.count_blocks = (s.nc + s.cpw - 1) / s.cpw;
     s.emit_slots = (s.nc + kWaves - 1) / kWaves;
+    s.micro = s.d <= kMicroCoords ? 1u : 0u;
     chunks_per_worker += s.nc;
   }
   // about 2048 workgroups in the first pass (blocks differ in size by orders of magnitude: small pieces, handed
@@ -122,6 +124,7 @@ std::vector<BlockShape> block_shapes(const compams_config* c) {
     const uint32_t most = (s.nc + kWaves - 1) / kWaves;  // one chunk per wavefront at least
     s.groups_first = std::max<uint32_t>(1, std::min<uint32_t>(most, (s.nc + per_first / 2) / per_first));
     s.groups_sweep = std::max<uint32_t>(1, std::min<uint32_t>(most, (s.nc + per_sweep / 2) / per_sweep));
+    if (s.micro) s.groups_first = s.groups_sweep = s.count_blocks = 0;  // a wavefront of a shared workgroup instead
   }
   return v;
 }
@@ -162,15 +165,17 @@ Layout make_layout(const compams_config* c) {
   } else if (c->compressor == COMPAMS_TOPK_BLOCKS) {
     const std::vector<BlockShape> shapes = block_shapes(c);
     const size_t M = shapes.size(), S = n * M;
-    size_t k = 0, chunks = 0, caps = 0, wg_first = 0, wg_sweep = 0, wg_count = 0, wg_emit = 0;
+    size_t k = 0, chunks = 0, caps = 0, wg_first = 0, wg_sweep = 0, wg_count = 0, wg_emit = 0, micro = 0;
     uint32_t cap_max = 0;
     for (const BlockShape& b : shapes) {
       k += b.k; chunks += b.nc; caps += b.cap; cap_max = std::max(cap_max, b.cap);
       wg_first += b.groups_first; wg_sweep += b.groups_sweep; wg_count += b.count_blocks; wg_emit += b.emit_slots;
+      micro += b.micro;
     }
     L.k_total = k;
     L.cap_alloc = cap_max;
-    L.flat.wg_first = static_cast<uint32_t>(n * wg_first);
+    L.num_micro = n * micro;
+    L.flat.wg_first = static_cast<uint32_t>(n * wg_first + (n * micro + kWaves - 1) / kWaves);
     L.flat.wg_sweep = static_cast<uint32_t>(n * wg_sweep);
     L.flat.wg_count = static_cast<uint32_t>(n * wg_count);
     L.flat.wg_emit = static_cast<uint32_t>(n * wg_emit);
@@ -204,6 +209,7 @@ Layout make_layout(const compams_config* c) {
     L.map_count = take(L.flat.wg_count * sizeof(WgSlot));
     L.map_emit = take(L.flat.wg_emit * sizeof(WgSlot));
     L.map_final = take(L.flat.wg_final * sizeof(WgSlot));
+    L.micro_list = take(L.num_micro * 4);
   } else if (c->compressor == COMPAMS_BLOCKSIGN) {
     const size_t M = static_cast<size_t>(c->num_blocks);
     L.offsets = take((M + 1) * 4);
@@ -353,7 +359,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     ctx->tkopt.predict = 1;
     ctx->tkopt.force_dense = 0;
     t.sel_off_srv = reinterpret_cast<uint32_t*>(w + lay.sel_off_srv);
-    t.segs = nullptr; t.map_first = t.map_sweep = t.map_count = t.map_emit = t.map_final = nullptr;
+    t.segs = nullptr; t.map_first = t.map_sweep = t.map_count = t.map_emit = t.map_final = nullptr; t.micro_list = nullptr;
     // control blocks, counters, histograms and chunk tables start at zero; lists need no initial value
     ok(fill_u32(reinterpret_cast<uint32_t*>(w), lay.cand / 4, 0u, s0));
     ok(fill_u32(reinterpret_cast<uint32_t*>(w + lay.idx), (lay.total - lay.idx) / 4, 0u, s0));
@@ -361,6 +367,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
       // the segments (worker-major: worker i, block b is segment i * M + b) and the workgroups of the flat launches
       std::vector<Seg> segs;
       std::vector<WgSlot> m_first, m_sweep, m_count, m_emit, m_final;
+      std::vector<uint32_t> micro;
       try {
         const std::vector<BlockShape> shapes = block_shapes(cfg);
         const size_t M = shapes.size();
@@ -382,6 +389,8 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
             sg.d = sh.d; sg.k = sh.k; sg.num_chunks = sh.nc; sg.cap = sh.cap; sg.coord_base = sh.off;
             sg.count_cpw = sh.cpw;
             sg.groups_first = sh.groups_first; sg.groups_sweep = sh.groups_sweep; sg.count_blocks = sh.count_blocks;
+            sg.micro = sh.micro;
+            if (sh.micro) micro.push_back(si);
             for (uint32_t q = 0; q < sh.groups_first; ++q) m_first.push_back(WgSlot{si, q});
             for (uint32_t q = 0; q < sh.groups_sweep; ++q) m_sweep.push_back(WgSlot{si, q});
             for (uint32_t q = 0; q < sh.count_blocks; ++q) m_count.push_back(WgSlot{si, q});
@@ -396,6 +405,10 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
           return (segs[a.seg].num_chunks + segs[a.seg].groups_first - 1) / segs[a.seg].groups_first;
         };
         std::stable_sort(m_first.begin(), m_first.end(), [&](const WgSlot& a, const WgSlot& b) { return work(a) > work(b); });
+        // and last of all the workgroups whose wavefronts take one micro problem each
+        for (size_t q = 0; q < micro.size(); q += kWaves)
+          m_first.push_back(WgSlot{kMicroFlag | static_cast<uint32_t>(q),
+                                   static_cast<uint32_t>(std::min<size_t>(kWaves, micro.size() - q))});
       } catch (...) { delete ctx; return COMPAMS_HIP_ERROR; }
       ok(hipStreamSynchronize(s0));
       ok(hipMemcpy(w + lay.segs, segs.data(), segs.size() * sizeof(Seg), hipMemcpyHostToDevice));
@@ -404,12 +417,17 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
       ok(hipMemcpy(w + lay.map_count, m_count.data(), m_count.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
       ok(hipMemcpy(w + lay.map_emit, m_emit.data(), m_emit.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
       ok(hipMemcpy(w + lay.map_final, m_final.data(), m_final.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
+      if (!micro.empty()) ok(hipMemcpy(w + lay.micro_list, micro.data(), micro.size() * 4, hipMemcpyHostToDevice));
+      if (m_first.size() != lay.flat.wg_first || m_sweep.size() != lay.flat.wg_sweep || m_count.size() != lay.flat.wg_count ||
+          m_emit.size() != lay.flat.wg_emit || m_final.size() != lay.flat.wg_final || micro.size() != lay.num_micro)
+        ok(hipErrorInvalidValue);  // the tables and the launch sizes come from the same shapes
       t.segs = reinterpret_cast<const Seg*>(w + lay.segs);
       t.map_first = reinterpret_cast<const WgSlot*>(w + lay.map_first);
       t.map_sweep = reinterpret_cast<const WgSlot*>(w + lay.map_sweep);
       t.map_count = reinterpret_cast<const WgSlot*>(w + lay.map_count);
       t.map_emit = reinterpret_cast<const WgSlot*>(w + lay.map_emit);
       t.map_final = reinterpret_cast<const WgSlot*>(w + lay.map_final);
+      t.micro_list = reinterpret_cast<const uint32_t*>(w + lay.micro_list);
     }
   } else if (cfg->compressor == COMPAMS_BLOCKSIGN) {
     BlocksignWorkspace& b = ctx->bs;

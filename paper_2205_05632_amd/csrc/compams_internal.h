@@ -30,6 +30,10 @@ constexpr int kNB2 = 1 << 9;
 // The first pass keeps level-1 histograms of this many buckets, starting at the guessed one: the guess is one
 // below the last threshold bucket, so a threshold that moved by one bucket either way still resolves there.
 constexpr uint32_t kTracked = 3;
+// Top-k inside every block: a block of at most this many coordinates (a bias, a norm weight) is one wavefront's
+// work from reading g to writing its part of the list; it takes no part in histograms, sweeps or counting.
+constexpr uint32_t kMicroCoords = 1024;
+constexpr uint32_t kMicroFlag = 0x80000000u;  // WgSlot.seg of a first-pass workgroup that takes micro problems
 
 // The counting kernel splits a row's chunks into at most kMaxCountBlocks contiguous blocks of count_cpw chunks
 // (a multiple of 32: four wavefronts, eight chunks at a time).  d < 2^31 gives at most 2^19 chunks.
@@ -83,7 +87,8 @@ struct Seg {
   uint32_t coord_base;   // coordinate of the first element within the worker's row
   uint32_t count_cpw;    // chunks per block of the counting kernel
   uint32_t groups_first, groups_sweep, count_blocks;  // workgroups the three kernel classes give this segment
-  uint32_t pad[3];
+  uint32_t micro;        // at most kMicroCoords coordinates: one wavefront of the first pass does the whole selection
+  uint32_t pad[2];
 };
 static_assert(sizeof(Seg) == 88 || sizeof(Seg) == 96, "Seg layout");
 
@@ -124,6 +129,8 @@ struct TopkWorkspace {
   const WgSlot* map_sweep;
   const WgSlot* map_count;
   const WgSlot* map_emit;   // .group = first chunk of the four that the workgroup's wavefronts take
+  const uint32_t* micro_list;  // segments that are micro problems; a first-pass workgroup with kMicroFlag takes
+                               // .group (<= 4) of them, from entry (.seg without the flag) on, one per wavefront
   const WgSlot* map_final;  // .seg = block (worker 0's segment of it), .group = chunk of the block
   uint32_t* sel_off_srv;    // n * (chunks of a whole row + 1) : list offsets per chunk of coordinates, for the
                             //                                   server's lines run from lists

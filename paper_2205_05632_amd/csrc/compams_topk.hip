@@ -262,6 +262,123 @@ __device__ __forceinline__ void resolve_level1(TopkRow* rp, uint32_t bstar, uint
   }
 }
 
+__device__ __forceinline__ void emit_chunk(uint32_t mode, const float* __restrict__ er, uint32_t d, uint32_t c,
+                                           const uint2* __restrict__ candr, const uint2* __restrict__ descr,
+                                           uint32_t cap, uint32_t tau, uint32_t r, bool all_ties, uint32_t eq_seen,
+                                           uint32_t at, int32_t* __restrict__ idx, float* __restrict__ val, uint32_t k,
+                                           uint32_t coord_base);
+
+// A micro problem (top-k inside a block of at most kMicroCoords coordinates) from end to end by one wavefront:
+// x = e + g with the pending zeros honoured, stored in place of e; the k-th largest key by a bit-by-bit search
+// over the keys, which stay in registers (31 steps of ballots: the largest t with at least k keys >= t); the
+// selected entries in coordinate order into the problem's part of the worker's list (ties as everywhere: in
+// coordinate order until r are in); and the records the last kernel reads (it finds the list written).
+// bm: 32 words of LDS of this wavefront (PEND only).  No barrier: other wavefronts of the workgroup do other
+// problems.
+constexpr int kMicroRounds = static_cast<int>(kMicroCoords / 256);
+
+template <bool PEND>
+__device__ __forceinline__ void micro_problem(const float* __restrict__ g, float* __restrict__ e, const Seg& sg,
+                                              uint32_t seg, const TopkWorkspace& ws, uint32_t* bm) {
+  const uint32_t lane = lane_id();
+  const float* gr = g + sg.elem_off;
+  float* er = e + sg.elem_off;
+  const uint32_t d = sg.d, k = sg.k;
+  int32_t* idx = ws.idx + sg.list_base;
+  float* val = ws.val + sg.list_base;
+  if constexpr (PEND) {
+    if (lane < kMicroCoords / 32) bm[lane] = 0;
+    const uint32_t* so = ws.sel_off + sg.seloff_base;
+    const uint32_t lo = so[0];
+    const uint32_t hi = so[1] < k ? so[1] : k;
+    for (uint32_t q = lo + lane; q < hi; q += 64) {
+      const uint32_t jl = static_cast<uint32_t>(idx[q]) - sg.coord_base;
+      if (jl < kMicroCoords) atomicOr(&bm[jl >> 5], 1u << (jl & 31u));
+    }
+  }
+  uint32_t key[kMicroRounds * 4];
+  uint32_t okm = 0;  // bit 4r + s: this lane's slot s of round r is a coordinate of the problem
+#pragma unroll
+  for (int r = 0; r < kMicroRounds; ++r) {
+    const uint32_t j = r * 256 + lane * 4;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) key[4 * r + s] = 0;
+    if (j < d) {
+      const float4 gv = *reinterpret_cast<const float4*>(gr + j);
+      const float4 e_in = *reinterpret_cast<const float4*>(er + j);
+      float4 ev = e_in;
+      if constexpr (PEND) {
+        const uint32_t nib = (bm[r * 8 + (lane >> 3)] >> ((lane & 7u) * 4u)) & 15u;
+        if (nib & 1u) ev.x = 0.0f;
+        if (nib & 2u) ev.y = 0.0f;
+        if (nib & 4u) ev.z = 0.0f;
+        if (nib & 8u) ev.w = 0.0f;
+      }
+      float4 x = make_float4(ev.x + gv.x, ev.y + gv.y, ev.z + gv.z, ev.w + gv.w);
+      const bool ok1 = j + 1 < d, ok2 = j + 2 < d, ok3 = j + 3 < d;
+      if (!ok1) x.y = e_in.y;  // columns >= d keep what they held
+      if (!ok2) x.z = e_in.z;
+      if (!ok3) x.w = e_in.w;
+      *reinterpret_cast<float4*>(er + j) = x;
+      key[4 * r + 0] = key_of_bits(__float_as_uint(x.x));
+      key[4 * r + 1] = ok1 ? key_of_bits(__float_as_uint(x.y)) : 0u;
+      key[4 * r + 2] = ok2 ? key_of_bits(__float_as_uint(x.z)) : 0u;
+      key[4 * r + 3] = ok3 ? key_of_bits(__float_as_uint(x.w)) : 0u;
+      okm |= (1u | (ok1 ? 2u : 0u) | (ok2 ? 4u : 0u) | (ok3 ? 8u : 0u)) << (4 * r);
+    }
+  }
+  const int rounds = static_cast<int>((d + 255) / 256);  // wave-uniform; keys of later rounds are 0 and not looked at
+  uint32_t tau = 0;
+  for (int bit = 30; bit >= 0; --bit) {
+    const uint32_t t = tau | (1u << bit);  // t >= 1: a slot outside the problem (key 0) never counts
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int r = 0; r < kMicroRounds; ++r)
+      if (r < rounds) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) cnt += popc64(ballot64(key[4 * r + s] >= t));
+      }
+    if (cnt >= k) tau = t;
+  }
+  uint32_t gt = 0, ties = 0;
+#pragma unroll
+  for (int r = 0; r < kMicroRounds; ++r)
+    if (r < rounds) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const bool ok = (okm >> (4 * r + s)) & 1u;
+        gt += popc64(ballot64(ok && key[4 * r + s] > tau));
+        ties += popc64(ballot64(ok && key[4 * r + s] == tau));
+      }
+    }
+  const uint32_t r_take = k - gt;  // 1 <= r_take <= ties
+  if (lane == 0) {
+    TopkRow* rowp = ws.rows + seg;
+    rowp->mode = kModeDense;
+    rowp->n_src = 0;
+    rowp->cursor = 0;
+    rowp->pred_valid = 0;
+    rowp->b_guess = 0;
+    rowp->level1_done = 1;
+    rowp->tau = tau;
+    rowp->r = r_take;
+    rowp->ties = ties;
+    rowp->take_all_ties = (r_take == ties);
+    ws.tau[seg] = tau;
+    ws.count_gt[seg] = gt;
+    uint32_t* cn = ws.counters + seg * 4;
+    cn[0] = 0;
+    cn[1] = 0;
+    cn[2] = ties;
+    cn[3] = r_take;
+    ws.chunk_rec[sg.chunk_base] = make_uint4(gt, ties, 0u, 0u);  // one chunk, nothing before it
+    ws.blk[static_cast<size_t>(seg) * kMaxCountBlocks] = make_uint2(gt, ties);
+  }
+  // the values come back from where this wavefront has just stored them
+  emit_chunk(kModeDense, er, d, 0u, nullptr, nullptr, 0u, tau, r_take, r_take == ties, 0u, 0u, idx, val, k,
+             sg.coord_base);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Kernel 1: first pass.  Grid (groups, n); each wavefront walks chunks wave, wave + stride, ...
 //   PRED: rows with a valid guess also emit candidates and level-1 histograms of buckets guess, guess+1.
@@ -531,6 +648,18 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
   __shared__ uint32_t suf[kWGA + 1];
   __shared__ uint32_t out2[2];
   __shared__ uint32_t sh_flag, sh_l1, sh_bstar, sh_need;
+  if constexpr (!UNI) {
+    const WgSlot slot = ws.map_first[blockIdx.x];
+    if (slot.seg & kMicroFlag) {  // workgroup-uniform: up to four micro problems, one per wavefront
+      const uint32_t w = threadIdx.x >> 6;
+      if (w < slot.group) {
+        const uint32_t seg = ws.micro_list[(slot.seg & ~kMicroFlag) + w];
+        const Seg sg = ws.segs[seg];
+        micro_problem<PEND>(g, e, sg, seg, ws, bm_all + (PEND ? w * 128 : 0));
+      }
+      return;
+    }
+  }
   const SegCtx sc = seg_ctx<UNI, kClassFirst>(geo, opt, ws);
   const uint32_t row = sc.seg;
   for (int b = threadIdx.x; b < kNB0; b += kWGA) lh[b] = 0;
@@ -1006,6 +1135,7 @@ struct FinalCtx {
   uint32_t base;                  // first coordinate of the chunk, in coordinates of the worker's row
   uint32_t coord_base, d_loc;     // the problem covers coordinates coord_base .. coord_base + d_loc of the row
   uint32_t k_loc, num_chunks, count_cpw, cap;
+  bool micro;                     // the list entries are there already (written by the first pass)
   uint32_t row0, row_stride;      // control block of worker i: row0 + i * row_stride
   size_t chunk0, chunk_stride, seloff0, seloff_stride, cand0, cand_stride, list0, list_stride;
 };
@@ -1019,6 +1149,7 @@ __device__ __forceinline__ FinalCtx final_ctx(const Geometry& geo, const TopkWor
     f.base = f.c * kChunk;
     f.coord_base = 0; f.d_loc = geo.d; f.k_loc = geo.k; f.num_chunks = geo.num_chunks; f.count_cpw = geo.count_cpw;
     f.cap = opt.cap;
+    f.micro = false;
     f.row0 = 0; f.row_stride = 1;
     f.chunk0 = 0; f.chunk_stride = geo.num_chunks;
     f.seloff0 = 0; f.seloff_stride = geo.num_chunks + 1;
@@ -1032,6 +1163,7 @@ __device__ __forceinline__ FinalCtx final_ctx(const Geometry& geo, const TopkWor
     f.base = sg.coord_base + f.c * kChunk;
     f.d_loc = sg.d; f.k_loc = sg.k; f.num_chunks = sg.num_chunks; f.count_cpw = sg.count_cpw;
     f.cap = opt.cap < sg.cap ? opt.cap : sg.cap;
+    f.micro = sg.micro != 0;
     f.row0 = slot.seg; f.row_stride = flat.blocks;
     f.chunk0 = sg.chunk_base; f.chunk_stride = flat.chunk_stride;
     f.seloff0 = sg.seloff_base; f.seloff_stride = flat.seloff_stride;
@@ -1115,7 +1247,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     for (uint32_t i = i0 + wave; i < geo.n && i < i0 + kTileWorkers; i += kWaves) {
       uint32_t at = sh_lo[i - i0];
       const uint32_t hi = sh_hi[i - i0];
-      if (hi == at) continue;  // nothing of this worker in the chunk (wave-uniform)
+      if (hi == at || f.micro) continue;  // nothing of this worker in the chunk, or written already (wave-uniform)
       const float* er = e + static_cast<int64_t>(i) * geo.ld + f.coord_base;
       const uint2* candr = ws.cand + f.cand0 + i * f.cand_stride;
       const uint2* descr = ws.desc + f.chunk0 + i * f.chunk_stride;
@@ -1248,7 +1380,7 @@ __global__ __launch_bounds__(kWG) void k_topk_emit(const float* __restrict__ e, 
     so[c] = at;
     if (c + 1 == sg.num_chunks) so[c + 1] = hi;
   }
-  if (hi == at) return;
+  if (hi == at || sg.micro) return;  // a micro problem's entries were written by the first pass
   const uint32_t cap = opt.cap < sg.cap ? opt.cap : sg.cap;
   emit_chunk(mode, e + sg.elem_off, sg.d, c, ws.cand + sg.cand_base, ws.desc + sg.chunk_base, cap, tau, r, all_ties,
              eq_before, at, ws.idx + sg.list_base, ws.val + sg.list_base, sg.k, sg.coord_base);
@@ -1347,12 +1479,14 @@ hipError_t topk_blocks_step(const Geometry& geo, const TopkWorkspace& ws, const 
     else launch(L, kSlotPassA, k_topk_pass_a<false, false, false>, grid_a, wga, stream, g, e, geo, ws, opt);
   }
   COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotLevel1, k_topk_level1<false>, dim3(flat.wg_sweep), wg, stream, e, geo, ws, opt);
-  COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotLevel2, k_topk_level2<false>, dim3(flat.wg_sweep), wg, stream, e, geo, ws, opt);
-  COMPAMS_CHECK_LAUNCH();
-  launch(L, kSlotCount, k_topk_count<false>, dim3(flat.wg_count), wg, stream, e, geo, ws, opt);
-  COMPAMS_CHECK_LAUNCH();
+  if (flat.wg_sweep) {  // none if every block is a micro problem
+    launch(L, kSlotLevel1, k_topk_level1<false>, dim3(flat.wg_sweep), wg, stream, e, geo, ws, opt);
+    COMPAMS_CHECK_LAUNCH();
+    launch(L, kSlotLevel2, k_topk_level2<false>, dim3(flat.wg_sweep), wg, stream, e, geo, ws, opt);
+    COMPAMS_CHECK_LAUNCH();
+    launch(L, kSlotCount, k_topk_count<false>, dim3(flat.wg_count), wg, stream, e, geo, ws, opt);
+    COMPAMS_CHECK_LAUNCH();
+  }
   if (workers_only) {
     launch(L, kSlotTopkEmit, k_topk_emit, dim3(flat.wg_emit), wg, stream, e, geo, ws, opt);
   } else {

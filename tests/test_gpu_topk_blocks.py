@@ -63,7 +63,10 @@ class BlockPair:
             f"{label}: counts above the threshold"
         for name in ("theta", "m", "v", "vhat") + (("e",) if with_e else ()):
             got = np.ascontiguousarray(gpu.compams_state(name).cpu().numpy())
-            assert np.array_equal(got.view(np.uint32), cpu.get(name).view(np.uint32)), f"{label}: {name}"
+            want = cpu.get(name)
+            nan = np.isnan(want)    # a NaN is a NaN: its sign and payload are not part of the bar
+            assert np.array_equal(np.isnan(got), nan), f"{label}: {name}: NaN pattern"
+            assert np.array_equal(got.view(np.uint32)[~nan], want.view(np.uint32)[~nan]), f"{label}: {name}"
 
     def close(self):
         self.gpu.close(); self.cpu.close()
@@ -116,6 +119,40 @@ def test_ties_and_zero_blocks():
     p.close()
 
 
+def test_blocks_that_one_wavefront_selects_from():
+    """Blocks of at most 1024 coordinates never meet the histogram kernels: sizes around the round and size limits,
+    everything kept, one kept, equal magnitudes, zeros only, non-finite entries, a ragged last block."""
+    rng = np.random.default_rng(77)
+    sizes = [4, 252, 256, 260, 508, 512, 516, 1020, 1024, 1028, 64, 64, 128, 1000, 4096, 8, 1023]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    kb = np.array([4, 1, 256, 3, 5, 512, 1, 1020, 7, 10, 1, 64, 2, 999, 40, 8, 11], dtype=np.int64)
+    n, d = 5, int(off[-1])
+    p = BlockPair(n, d, off, kb, (rng.standard_normal(d) * 0.1).astype(np.float32))
+    for t in range(6):
+        g = grads(rng, n, d)
+        g[:, off[10]:off[11]] = np.where(rng.random((n, 64)) < 0.5, 3.0, -3.0)            # 64 equal magnitudes, one kept
+        g[:, off[11]:off[12]] = 0.0                                                        # zeros only, all kept
+        g[:, off[12]:off[13]] = np.round(g[:, off[12]:off[13]] * 2) / 2                    # many ties
+        if t == 2:
+            g[0, off[13] + 5] = np.inf; g[1, off[13] + 6] = -np.inf; g[2, off[13] + 7] = np.nan
+        p.step(g)
+        p.compare(f"step {t}", with_e=(t % 2 == 1) and t < 2)
+    p.close()
+
+
+def test_only_small_blocks():
+    """Every block is one wavefront's: the sweep and counting kernels have nothing to do."""
+    rng = np.random.default_rng(78)
+    n, d = 7, 40 * 300
+    off = np.arange(0, d + 1, 300, dtype=np.int64)
+    kb = rng.integers(1, 300, size=40).astype(np.int64)
+    p = BlockPair(n, d, off, kb, np.zeros(d, dtype=np.float32))
+    for t in range(4):
+        p.step(grads(rng, n, d))
+        p.compare(f"step {t}", with_e=t == 3)
+    p.close()
+
+
 @pytest.mark.parametrize("route", ["dense", "no guess", "small candidate list"])
 def test_routes(route):
     rng = np.random.default_rng(3)
@@ -151,6 +188,9 @@ def test_messages_and_the_two_halves():
     rng = np.random.default_rng(21)
     n, d = 4, 150000
     off, kb = make_blocks(d, 11, rng)
+    off = np.concatenate([off[:-1], [d, d + 64, d + 576, d + 1600]]).astype(np.int64)   # and three small blocks
+    kb = np.concatenate([kb, [1, 5, 100]]).astype(np.int64)
+    d = int(off[-1])
     theta0 = rng.standard_normal(d).astype(np.float32) * 0.1
     whole = BlockPair(n, d, off, kb, theta0)
     halves = B.Compams(n, d, torch.from_numpy(theta0), compressor=B.TOPK_BLOCKS, block_offsets=off, block_k=kb)
