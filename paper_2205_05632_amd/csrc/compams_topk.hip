@@ -1005,28 +1005,39 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
         a[u] = lane < cnt[u] ? candr[off[u] + lane] : make_uint2(0, 0);
         b[u] = lane + 64 < cnt[u] ? candr[off[u] + lane + 64] : make_uint2(0, 0);
       }
-      uint32_t my_gt = 0, my_eq = 0;
+      uint32_t gt[kGroup], eq[kGroup];  // wave-uniform
+      uint32_t longest = 0;
 #pragma unroll
       for (int u = 0; u < kGroup; ++u) {
         const uint32_t ka = key_of_bits(a[u].y), kb = key_of_bits(b[u].y);
-        uint32_t gt = popc64(ballot64(lane < cnt[u] && ka > tau)) + popc64(ballot64(lane + 64 < cnt[u] && kb > tau));
-        uint32_t eq = popc64(ballot64(lane < cnt[u] && ka == tau)) + popc64(ballot64(lane + 64 < cnt[u] && kb == tau));
-        for (uint32_t t = 128; t < cnt[u]; t += 256) {  // long segments: four independent loads per trip
-          uint32_t kk[4];
-          bool okk[4];
+        gt[u] = popc64(ballot64(lane < cnt[u] && ka > tau)) + popc64(ballot64(lane + 64 < cnt[u] && kb > tau));
+        eq[u] = popc64(ballot64(lane < cnt[u] && ka == tau)) + popc64(ballot64(lane + 64 < cnt[u] && kb == tau));
+        longest = cnt[u] > longest ? cnt[u] : longest;
+      }
+      // long segments: the next 128 entries of every segment of the group per trip, all loads in flight together
+      // (a trip per segment instead would make a group of long segments a chain of several dozen round trips)
+      for (uint32_t t = 128; t < longest; t += 128) {
+        uint32_t ka[kGroup], kb[kGroup];
 #pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            okk[w] = t + w * 64 + lane < cnt[u];
-            kk[w] = okk[w] ? key_of_bits(candr[off[u] + t + w * 64 + lane].y) : 0;
-          }
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            gt += popc64(ballot64(okk[w] && kk[w] > tau));
-            eq += popc64(ballot64(okk[w] && kk[w] == tau));
+        for (int u = 0; u < kGroup; ++u) {
+          ka[u] = kb[u] = 0;
+          if (t < cnt[u]) {  // wave-uniform
+            if (t + lane < cnt[u]) ka[u] = key_of_bits(candr[off[u] + t + lane].y);
+            if (t + 64 + lane < cnt[u]) kb[u] = key_of_bits(candr[off[u] + t + 64 + lane].y);
           }
         }
-        if (lane == static_cast<uint32_t>(u)) { my_gt = gt; my_eq = eq; }
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u)
+          if (t < cnt[u]) {
+            const bool oa = t + lane < cnt[u], ob = t + 64 + lane < cnt[u];
+            gt[u] += popc64(ballot64(oa && ka[u] > tau)) + popc64(ballot64(ob && kb[u] > tau));
+            eq[u] += popc64(ballot64(oa && ka[u] == tau)) + popc64(ballot64(ob && kb[u] == tau));
+          }
       }
+      uint32_t my_gt = 0, my_eq = 0;
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u)
+        if (lane == static_cast<uint32_t>(u)) { my_gt = gt[u]; my_eq = eq[u]; }
       if (lane < kGroup && c0 + lane < end) { l_gt[c0 - start + lane] = my_gt; l_eq[c0 - start + lane] = my_eq; }
     }
   }
