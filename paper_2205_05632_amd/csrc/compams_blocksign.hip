@@ -62,45 +62,52 @@ __device__ __forceinline__ void atomic_add_u64(uint64_t* p, uint64_t v) {
   atomicAdd(reinterpret_cast<unsigned long long*>(p), static_cast<unsigned long long>(v));
 }
 
-// Register accumulators of a lane: two fp64 sums, one per window of kWinSpan binary exponents, placed by the
-// wavefront (wave-uniform) where the magnitudes are expected.  Every |x| in a window is an integer below
-// 2^(24 + kWinSpan - 1) = 2^40 times the window's quantum 2^(lowest exponent - 150), so the fp64 sum of up to
-// 2^13 of them is below 2^53 quanta: every addition is exact and their order does not matter.  A lane flushes
-// after kWinAdds additions, far inside that bound (a wavefront rarely stays in one block for longer, and the
-// longest rows of the tests then reach the limit).  At a flush the sums become integers again, are added over
-// the wavefront and go to the global digits.  Entries
-// outside both windows (rare) and non-finite ones go straight to the global digits and flags.
+// Register accumulator of a lane: an fp64 sum over a window of kWinSpan binary exponents, placed by the
+// wavefront (wave-uniform) where the magnitudes are expected.  Every |x| in the window is an integer below
+// 2^(24 + kWinSpan - 1) = 2^45 times the window's quantum 2^(lowest exponent - 150), so the fp64 sum of up to
+// kWinAdds = 2^8 of them is below 2^53 quanta: every addition is exact and their order does not matter.  A lane
+// flushes after kWinAdds additions (or when its wavefront leaves the block): the sum becomes an integer
+// again, is added over the wavefront and goes to the global digits.  Entries outside the window (more than
+// 2^20 below the largest magnitude the wavefront met when it placed the window: rare) and non-finite ones go
+// straight to the global digits and flags.
 // "Exponent" here is the effective one: max(biased exponent, 1), so that subnormals share the quantum of
 // the smallest normal numbers; |x| = mantissa * 2^(exponent - 150).
-constexpr uint32_t kWinSpan = 17;
+// (One window of 22 exponents replaced two of 17: per entry one compare, one select, one conversion and one
+// addition instead of twice that and a second range test.)
+constexpr uint32_t kWinSpan = 22;
 constexpr uint32_t kWinAdds = 256;
+static_assert(24 + kWinSpan - 1 + 8 <= 53, "a window's sum must stay an exact integer in fp64");
 
 struct WaveAcc {
-  double hi, lo;    // sums of the upper and the lower window
-  uint32_t eh;      // upper window: exponents eh .. eh + kWinSpan - 1
-  uint32_t el;      // lower window: exponents el .. eh - 1 (empty when el == eh)
+  double sum;       // sum of the window
+  uint32_t eh;      // window: exponents eh .. eh + kWinSpan - 1
+  uint32_t klo;     // magnitude keys klo .. klo + kspan - 1 lie in the window (eh == 1: from key 0, the
+  uint32_t kspan;   // subnormals and zero included)
   uint32_t adds;    // additions per lane since the last flush (wave-uniform)
   bool live;
 };
 
 __device__ __forceinline__ void acc_reset(WaveAcc& A) {
-  A.hi = 0.0; A.lo = 0.0; A.eh = 1; A.el = 1; A.adds = 0; A.live = false;
+  A.sum = 0.0; A.eh = 1; A.klo = 0; A.kspan = 0; A.adds = 0; A.live = false;
 }
 
-// Places the windows so that the upper one ends `headroom` exponents above the largest finite magnitude key
-// kmax_key seen so far (wave-uniform).
+// Places the window so that it ends `headroom` exponents above the largest finite magnitude key kmax_key
+// seen so far (wave-uniform).  Its top exponent is at most 254: infinities and NaNs are never inside.
 __device__ __forceinline__ void acc_place(WaveAcc& A, uint32_t kmax_key, uint32_t headroom) {
   uint32_t top = kmax_key >> 23;
   top = top ? top : 1u;
   top = top + headroom > 254u ? 254u : top + headroom;
   A.eh = top >= kWinSpan ? top - (kWinSpan - 1u) : 1u;
-  A.el = A.eh > kWinSpan ? A.eh - kWinSpan : 1u;
+  A.klo = A.eh == 1u ? 0u : A.eh << 23;
+  A.kspan = ((A.eh + kWinSpan) << 23) - A.klo;
   A.live = true;
 }
 
-// One window's sum as an integer number of quanta 2^(e_low - 150), added over the wavefront and then, by
+// The window's sum as an integer number of quanta 2^(e_low - 150), added over the wavefront and then, by
 // lane 0, into the digits: bit position e_low - 1 above 2^-149, i.e. digit (e_low - 1) / 32 and up.
-__device__ __forceinline__ void window_to_digits(double sum, uint32_t e_low, uint64_t* digits) {
+// Out of line: flushes are rare (a wavefront leaves a block, or the window has taken kWinAdds additions), and
+// the streaming loops stay small enough for the instruction cache.
+__device__ __noinline__ void window_to_digits(double sum, uint32_t e_low, uint64_t* digits) {
   const uint64_t mine = static_cast<uint64_t>(ldexp(sum, 150 - static_cast<int>(e_low)));  // exact, below 2^53
   const uint64_t all = wave_sum_u64(mine);                                                 // below 2^59
   if (lane_id() == 0 && all) {
@@ -113,16 +120,9 @@ __device__ __forceinline__ void window_to_digits(double sum, uint32_t e_low, uin
   }
 }
 
-// Out of line: flushes are rare (a wavefront leaves a block, or a window has taken kWinAdds additions), and the
-// streaming loops stay small enough for the instruction cache.
-__device__ __noinline__ void flush_windows(double hi, double lo, uint32_t eh, uint32_t el, uint64_t* digits) {
-  window_to_digits(hi, eh, digits);
-  if (el != eh) window_to_digits(lo, el, digits);
-}
-
 __device__ __forceinline__ void acc_flush(WaveAcc& A, uint64_t* digits /* kLimbs of the (row, block) */) {
   if (!A.live) return;
-  flush_windows(A.hi, A.lo, A.eh, A.el, digits);
+  window_to_digits(A.sum, A.eh, digits);
   acc_reset(A);
 }
 
@@ -136,21 +136,7 @@ __device__ __noinline__ void add_direct(uint32_t bits, uint64_t* digits, uint32_
   }
 }
 
-// Which window an entry with magnitude key `key` belongs to.
-struct WinClass {
-  bool in_hi, in_lo, finite;
-};
-__device__ __forceinline__ WinClass classify(const WaveAcc& A, uint32_t key) {
-  const uint32_t ex = key >> 23;
-  const uint32_t ee = ex ? ex : 1u;
-  WinClass c;
-  c.finite = ex != 255u;
-  c.in_hi = c.finite && ee - A.eh < kWinSpan;            // unsigned: false below the window
-  c.in_lo = c.finite && ee - A.el < A.eh - A.el;         // el <= ee < eh
-  return c;
-}
-
-// Adds the four entries of a lane's quad.  Branch-free for entries inside the windows; everything else
+// Adds the four entries of a lane's quad.  Branch-free for entries inside the window; everything else
 // leaves through one wave-uniform branch.
 __device__ __forceinline__ void acc_add4(WaveAcc& A, const uint32_t bits[4], const bool ok[4], uint64_t* digits,
                                          uint32_t* special) {
@@ -159,11 +145,11 @@ __device__ __forceinline__ void acc_add4(WaveAcc& A, const uint32_t bits[4], con
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     const uint32_t key = bits[s] & 0x7fffffffu;
-    const WinClass c = classify(A, key);
-    const double v = static_cast<double>(__uint_as_float(key));  // |x|, exactly
-    A.hi += (ok[s] && c.in_hi) ? v : 0.0;
-    A.lo += (ok[s] && c.in_lo) ? v : 0.0;
-    rare[s] = ok[s] && (!c.finite || (key != 0u && !c.in_hi && !c.in_lo));
+    const bool in = ok[s] && key - A.klo < A.kspan;  // unsigned: false below the window
+    uint32_t ksel = in ? key : 0u;
+    asm volatile("" : "+v"(ksel));  // select the 32-bit key, then convert (not: convert, then select both halves)
+    A.sum += static_cast<double>(__uint_as_float(ksel));  // |x|, exactly
+    rare[s] = ok[s] && !in && key != 0u;
     any |= rare[s];
   }
   A.adds += 4;
@@ -229,22 +215,99 @@ __device__ __forceinline__ void digits3_to_192(uint64_t s0, uint64_t s1, uint64_
 // ---------------------------------------------------------------------------------------------
 constexpr int kBsBatch = 4;
 
+// A value that is the same in every lane, moved to a scalar register: conditions on it become scalar branches
+// and it can be an operand of every lane's arithmetic without a register per lane.
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// A table entry at a wave-uniform index, read through the scalar path: the tables read this way (block offsets,
+// chunk-to-block map, the previous step's means) are not written by the kernel that reads them, and a scalar
+// load has its own counter, so waiting for it does not mean waiting for the vector loads of the next batch that
+// are in flight (a vector load here stalled the stream once per chunk).
+typedef const __attribute__((address_space(4))) uint32_t* ScalarTable;
+__device__ __forceinline__ uint32_t table_u32(const uint32_t* p, uint32_t i) {
+  return reinterpret_cast<ScalarTable>(reinterpret_cast<uintptr_t>(p))[i];
+}
+__device__ __forceinline__ float table_f32(const float* p, uint32_t i) {
+  return __uint_as_float(table_u32(reinterpret_cast<const uint32_t*>(p), i));
+}
+
 struct BsBatch {
   float4 g[kBsBatch], e[kBsBatch];
 };
 
-__device__ __forceinline__ void bs_load_batch(BsBatch& B, const float* __restrict__ gr, const float* __restrict__ er,
-                                              uint32_t c, int r0, uint32_t d) {
+template <bool FULL>
+__device__ __forceinline__ void bs_load_batch_t(BsBatch& B, const float* __restrict__ gr, const float* __restrict__ er,
+                                                uint32_t c, int r0, uint32_t d) {
   const uint32_t lane = lane_id();
 #pragma unroll
   for (int u = 0; u < kBsBatch; ++u) {
     const uint32_t j = c * kChunk + (r0 + u) * 256 + lane * 4;
-    B.g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-    B.e[u] = B.g[u];
-    if (j < d) {
+    if (FULL) {
       B.g[u] = load_stream4(gr + j);
       B.e[u] = load_stream4(er + j);
+    } else {
+      B.g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      B.e[u] = B.g[u];
+      if (j < d) {
+        B.g[u] = load_stream4(gr + j);
+        B.e[u] = load_stream4(er + j);
+      }
     }
+  }
+}
+
+__device__ __forceinline__ void bs_load_batch(BsBatch& B, const float* __restrict__ gr, const float* __restrict__ er,
+                                              uint32_t c, int r0, uint32_t d) {
+  bs_load_batch_t<false>(B, gr, er, c, r0, d);
+}
+
+// One round (256 coordinates from j0 on) that straddles block boundaries: every coordinate looks up its own
+// block (walking on from block b, the block of the round's first coordinate), takes that block's previous mean
+// (PEND) and adds its magnitude to that block's digits.  Rare (a few rounds per row) and out of line, so that
+// the common round keeps no register that a path through here may have loaded a moment ago: the compiler would
+// otherwise make every round wait for all loads in flight, the next batch's included.
+template <bool PEND>
+__device__ __noinline__ void straddling_round(float4 g4, float4 e4, uint32_t j0, uint32_t d, uint32_t b,
+                                              const uint32_t* __restrict__ off, const float* __restrict__ mur,
+                                              float* __restrict__ er, uint32_t* __restrict__ bitr, uint32_t words,
+                                              uint64_t* accr, uint32_t* specr) {
+  const uint32_t lane = lane_id();
+  const uint32_t j = j0 + lane * 4;
+  const bool ok[4] = {j < d, j + 1 < d, j + 2 < d, j + 3 < d};
+  float ev[4] = {e4.x, e4.y, e4.z, e4.w};
+  const float gv[4] = {g4.x, g4.y, g4.z, g4.w};
+  uint32_t bb[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    bb[s] = ok[s] ? block_of(off, b, j + s) : b;
+    if (PEND && ok[s]) {
+      const float mu = mur[bb[s]];
+      ev[s] = ev[s] - (ev[s] < 0.0f ? -mu : mu);
+    }
+  }
+  float xv[4];
+  uint32_t nib = 0;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    xv[s] = ok[s] ? ev[s] + gv[s] : ev[s];  // columns at and beyond d keep their contents
+    nib |= (ok[s] && xv[s] < 0.0f ? 1u : 0u) << s;
+  }
+  if (ok[0]) store_stream4(er + j, make_float4(xv[0], xv[1], xv[2], xv[3]));
+  const uint32_t word = or_over_8_lanes(nib << ((lane & 7u) * 4u));
+  const uint32_t widx = (j0 >> 5) + (lane >> 3);
+  if ((lane & 7u) == 0 && widx < words) bitr[widx] = word;
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+    if (ok[s]) add_direct(__float_as_uint(xv[s]), accr + static_cast<size_t>(bb[s]) * kLimbs, specr + bb[s]);
+}
+
+// Makes the registers of a batch inputs of an (empty) instruction sequence: whatever loads they are waiting
+// for have completed afterwards, as far as the compiler's bookkeeping is concerned too.
+__device__ __forceinline__ void settle_batch(BsBatch& B) {
+#pragma unroll
+  for (int u = 0; u < kBsBatch; ++u) {
+    asm volatile("" : "+v"(B.g[u].x), "+v"(B.g[u].y), "+v"(B.g[u].z), "+v"(B.g[u].w));
+    asm volatile("" : "+v"(B.e[u].x), "+v"(B.e[u].y), "+v"(B.e[u].z), "+v"(B.e[u].w));
   }
 }
 
@@ -271,19 +334,28 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const uint32_t stride = gridDim.x * kWaves;
   const uint32_t d = geo.d;
-  uint32_t c = blockIdx.x * kWaves + wave;
+  uint32_t c = uniform_u32(blockIdx.x * kWaves + wave);  // the wavefront's chunk: a scalar, like all that follows from it
   if (c >= geo.num_chunks) return;
   int r0 = 0;
   BsBatch cur, nxt;
-  bs_load_batch(cur, gr, er, c, 0, d);
+  // (a chunk that lies entirely below d, as every chunk of a row but the last does: plain loads, all in flight
+  // together; with per-lane predicates the compiler waits for each pair of loads before it issues the next)
+  if ((c + 1) * static_cast<uint64_t>(kChunk) <= d) bs_load_batch_t<true>(cur, gr, er, c, 0, d);
+  else bs_load_batch_t<false>(cur, gr, er, c, 0, d);
   // b: block of the round being summed; blk_end = off[b + 1] and mu_b = the block's previous mean are kept in
   // registers (the tables are only read when the walk enters another block); b_next: block of the next
   // chunk's first coordinate, requested together with that chunk's first batch.
-  uint32_t b = ws.chunk_block[c], b_next = b;
-  uint32_t blk_end = off[b + 1];
-  float mu_b = PEND ? mur[b] : 0.0f;
+  uint32_t b = table_u32(ws.chunk_block, c), b_next = b;
+  uint32_t blk_end = table_u32(off, b + 1);
+  float mu_b = PEND ? table_f32(mur, b) : 0.0f;
   WaveAcc A;
   acc_reset(A);
+  // The first batch has to have arrived before the loop is entered: inside the loop the batch being summed was
+  // copied from registers that had been waited for, and only if that holds on every way into the loop does the
+  // compiler leave the next batch's loads in flight while the current one is summed (otherwise it waits for all
+  // outstanding loads at the first use of the current batch, in every iteration).
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // one wait for the whole batch (its loads stay above this line)
+  settle_batch(cur);
   for (;;) {
     // where the walk goes next (wave-uniform)
     uint32_t cn = c;
@@ -292,7 +364,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
     const bool more = cn < geo.num_chunks;
     if (more) {
       bs_load_batch(nxt, gr, er, cn, rn, d);
-      if (rn == 0) b_next = ws.chunk_block[cn];
+      if (rn == 0) b_next = table_u32(ws.chunk_block, cn);
     }
     // One batch of rounds.  FULL: the chunk lies entirely below d (every chunk of a row but the last): no
     // per-coordinate bounds predicates are needed.
@@ -309,24 +381,22 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
       while (blk_end <= j0) {
         acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
         ++b;
-        blk_end = off[b + 1];
-        if (PEND) mu_b = mur[b];
+        blk_end = table_u32(off, b + 1);
+        if (PEND) mu_b = table_f32(mur, b);
       }
       const uint32_t j_end = (FULL || j0 + 256 < d) ? j0 + 256 : d;
-      const bool whole = blk_end >= j_end;  // the whole round lies in block b (wave-uniform)
-      uint32_t bb[4] = {b, b, b, b};
-      if (!whole) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) bb[s] = ok[s] ? block_of(off, b, j + s) : b;
+      if (blk_end < j_end) {  // the round straddles block boundaries (a scalar condition): out of line
+        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+        straddling_round<PEND>(cur.g[u], cur.e[u], j0, d, b, off, mur, er, bitr, geo.words, accr, specr);
+        continue;
       }
+      // the whole round lies in block b
       float ev[4] = {cur.e[u].x, cur.e[u].y, cur.e[u].z, cur.e[u].w};
       const float gv[4] = {cur.g[u].x, cur.g[u].y, cur.g[u].z, cur.g[u].w};
       if (PEND) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const float mu = whole ? mu_b : (ok[s] ? mur[bb[s]] : 0.0f);
-          if (ok[s]) ev[s] = ev[s] - (ev[s] < 0.0f ? -mu : mu);
-        }
+        for (int s = 0; s < 4; ++s)
+          if (ok[s]) ev[s] = ev[s] - (ev[s] < 0.0f ? -mu_b : mu_b);
       }
       float xv[4];
       uint32_t nib = 0;
@@ -341,33 +411,23 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
       if ((lane & 7u) == 0 && (FULL || widx < geo.words)) bitr[widx] = word;
       const uint32_t bits[4] = {__float_as_uint(xv[0]), __float_as_uint(xv[1]), __float_as_uint(xv[2]),
                                 __float_as_uint(xv[3])};
-      if (whole) {
-        if (A.adds + 4 > kWinAdds) acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
-        if (!A.live) {
-          // place the windows by the largest magnitude of this round, with room for entries 4 times larger
-          uint32_t kmax = 0;
-#pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            const uint32_t key = bits[s] & 0x7fffffffu;
-            if (ok[s] && key < 0x7f800000u && key > kmax) kmax = key;
-          }
-#pragma unroll
-          for (int s = 32; s >= 1; s >>= 1) {
-            const uint32_t o = __shfl_xor(kmax, s, 64);
-            kmax = o > kmax ? o : kmax;
-          }
-          acc_place(A, kmax, 2);
-        }
-        acc_add4(A, bits, ok, accr + static_cast<size_t>(b) * kLimbs, specr + b);
-      } else {
-        // the round straddles block boundaries: every coordinate goes to its own block's digits
-        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+      if (A.adds + 4 > kWinAdds) acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
+      if (!A.live) {
+        // place the window by the largest magnitude of this round, with room for entries 4 times larger
+        uint32_t kmax = 0;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          if (!ok[s]) continue;
-          add_direct(bits[s], accr + static_cast<size_t>(bb[s]) * kLimbs, specr + bb[s]);
+          const uint32_t key = bits[s] & 0x7fffffffu;
+          if (ok[s] && key < 0x7f800000u && key > kmax) kmax = key;
         }
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+          const uint32_t o = __shfl_xor(kmax, s, 64);
+          kmax = o > kmax ? o : kmax;
+        }
+        acc_place(A, uniform_u32(kmax), 2);
       }
+      acc_add4(A, bits, ok, accr + static_cast<size_t>(b) * kLimbs, specr + b);
     }
     };
     if ((c + 1) * static_cast<uint64_t>(kChunk) <= d) batch(std::true_type{});
@@ -381,8 +441,8 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
     if (rn == 0 && b_next != b) {
       acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
       b = b_next;
-      blk_end = off[b + 1];
-      if (PEND) mu_b = mur[b];
+      blk_end = table_u32(off, b + 1);
+      if (PEND) mu_b = table_f32(mur, b);
     }
     cur = nxt;
     c = cn;
