@@ -451,11 +451,15 @@ __global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, f
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fused single pass for the layout "block b = coordinates [4096 b, 4096 (b+1))" (block = chunk): the
-// wavefront keeps the chunk's x in registers, sums it exactly, derives the scale itself and writes sign
-// bits and residuals: 12 bytes per coordinate instead of 20.  A block with an entry more than 2^32 below
-// its largest one, or with a non-finite entry, takes the general route instead (x is stored, the digits
-// go to memory, done = 0) and is finished by the kernels below.
+// Fused single pass for the layout "block b = coordinates [4096 b, 4096 (b+1))" (block = chunk): a workgroup
+// takes a block, each of its four wavefronts a quarter of it (4 rounds, kept in 16 registers per lane); the
+// quarters' largest magnitudes and then their exact partial sums meet in LDS (two barriers per block), every
+// wavefront derives the same scale and writes the sign bits and residuals of its quarter: 12 bytes per
+// coordinate instead of 20.  (A wavefront per block, with the
+// block's 16 rounds in 64 registers per lane, spilled: the spill stores alone were 2.8 GB of HBM writes per
+// launch on the GPT-2 workload, two thirds as much again as the residuals.)
+// A block with an entry more than 2^32 below its largest one, or with a non-finite entry, takes the general
+// route instead (x is stored, the digits go to memory, done = 0) and is finished by the kernels below.
 // ---------------------------------------------------------------------------------------------
 // Store the entries of a lane's quad that lie below d (columns >= d are never written).
 __device__ __forceinline__ void store_valid4(float* er, uint32_t j, uint32_t d, const float xv[4]) {
@@ -467,8 +471,13 @@ __device__ __forceinline__ void store_valid4(float* er, uint32_t j, uint32_t d, 
   }
 }
 
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_bs_fused4096(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
+constexpr int kQuarter = kRounds / kWaves;  // rounds of a block per wavefront
+static_assert(kQuarter == kBsBatch, "a wavefront's quarter of a block is one batch of loads");
+
+__global__ __launch_bounds__(kWG) void k_bs_fused4096(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
                                                        BlocksignWorkspace ws) {
+  __shared__ uint32_t sh_kmax[1][kWaves], sh_odd[1][kWaves];
+  __shared__ uint64_t sh_sum[1][kWaves][3];
   const uint32_t row = blockIdx.y;
   const float* gr = g + static_cast<int64_t>(row) * geo.ld;
   float* er = e + static_cast<int64_t>(row) * geo.ld;
@@ -477,41 +486,33 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
   float* mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;
   uint32_t* doner = ws.done + static_cast<size_t>(row) * geo.num_blocks;
   uint32_t* bitr = ws.bits + static_cast<size_t>(row) * geo.words;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint32_t stride = gridDim.x * kWaves;
+  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
   const uint32_t d = geo.d;
-  for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
-    const uint32_t base = c * kChunk + lane * 4;
+  const uint32_t c = blockIdx.x;  // one block per workgroup: the dispatcher overlaps blocks better than a loop
+  if (c >= geo.num_chunks) return;  // with two barriers per trip does (workgroup-uniform)
+  BsBatch cur;
+  // this wavefront's rounds of block c: wave * kQuarter ..
+  if ((c + 1) * static_cast<uint64_t>(kChunk) <= d) bs_load_batch_t<true>(cur, gr, er, c, wave * kQuarter, d);
+  else bs_load_batch_t<false>(cur, gr, er, c, wave * kQuarter, d);
+  {
+    constexpr uint32_t buf = 0;
+    const uint32_t base = c * kChunk + wave * kQuarter * 256 + lane * 4;
     const uint32_t len = (c + 1) * static_cast<uint64_t>(kChunk) <= d ? kChunk : d - c * kChunk;
-    float4 x[kRounds];
+    float4 x[kQuarter];
     uint32_t kmax = 0;
     bool odd = false;  // a non-finite entry
 #pragma unroll
-    for (int r0 = 0; r0 < kRounds; r0 += kBsBatch) {
-      float4 gv[kBsBatch], ev[kBsBatch];
+    for (int u = 0; u < kQuarter; ++u) {
+      const uint32_t j = base + u * 256;
+      x[u] = make_float4(cur.e[u].x + cur.g[u].x, cur.e[u].y + cur.g[u].y, cur.e[u].z + cur.g[u].z,
+                         cur.e[u].w + cur.g[u].w);
+      const float xv[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
 #pragma unroll
-      for (int u = 0; u < kBsBatch; ++u) {
-        const uint32_t j = base + (r0 + u) * 256;
-        gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        ev[u] = gv[u];
-        if (j < d) {
-          gv[u] = load_stream4(gr + j);
-          ev[u] = load_stream4(er + j);
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < kBsBatch; ++u) {
-        const int r = r0 + u;
-        const uint32_t j = base + r * 256;
-        x[r] = make_float4(ev[u].x + gv[u].x, ev[u].y + gv[u].y, ev[u].z + gv[u].z, ev[u].w + gv[u].w);
-        const float xv[4] = {x[r].x, x[r].y, x[r].z, x[r].w};
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const uint32_t key = __float_as_uint(xv[s]) & 0x7fffffffu;
-          if (j + s < d) {
-            if (key >= 0x7f800000u) odd = true;
-            else if (key > kmax) kmax = key;
-          }
+      for (int s = 0; s < 4; ++s) {
+        const uint32_t key = __float_as_uint(xv[s]) & 0x7fffffffu;
+        if (j + s < d) {
+          if (key >= 0x7f800000u) odd = true;
+          else if (key > kmax) kmax = key;
         }
       }
     }
@@ -520,13 +521,26 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
       const uint32_t o = __shfl_xor(kmax, s, 64);
       kmax = o > kmax ? o : kmax;
     }
+    if (lane == 0) {
+      sh_kmax[buf][wave] = kmax;
+      sh_odd[buf][wave] = ballot64(odd) != 0 ? 1u : 0u;
+    }
+    __syncthreads();
+    uint32_t any_odd = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const uint32_t o = sh_kmax[buf][w];
+      kmax = o > kmax ? o : kmax;
+      any_odd |= sh_odd[buf][w];
+    }
     const uint32_t exm = kmax >> 23;
     const uint32_t centre = (exm ? exm - 1 : 0) >> 5;  // digit of the largest entry: nothing lies above it
     uint64_t a0 = 0, a1 = 0, a2 = 0;
+    bool far = false;  // an entry more than 2^32 below the largest one
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-      const uint32_t j = base + r * 256;
-      const float xv[4] = {x[r].x, x[r].y, x[r].z, x[r].w};
+    for (int u = 0; u < kQuarter; ++u) {
+      const uint32_t j = base + u * 256;
+      const float xv[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         if (j + s >= d) continue;
@@ -534,28 +548,47 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         if (f.special || (f.lo | f.hi) == 0) continue;
         if (f.w == centre) { a1 += f.lo; a2 += f.hi; }
         else if (f.w + 1 == centre) { a0 += f.lo; a1 += f.hi; }
-        else odd = true;  // more than 2^32 below the largest entry
+        else far = true;
       }
     }
-    if (ballot64(odd) == 0) {
+    {
       const uint64_t s0 = wave_sum_u64(a0), s1 = wave_sum_u64(a1), s2 = wave_sum_u64(a2);
+      const bool wave_far = ballot64(far) != 0;
+      if (lane == 0) {
+        sh_sum[buf][wave][0] = s0;
+        sh_sum[buf][wave][1] = s1;
+        sh_sum[buf][wave][2] = s2;
+        if (wave_far) sh_odd[buf][wave] = 1u;  // read again after the barrier
+      }
+    }
+    __syncthreads();
+    uint64_t t0 = 0, t1 = 0, t2 = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      t0 += sh_sum[buf][w][0];
+      t1 += sh_sum[buf][w][1];
+      t2 += sh_sum[buf][w][2];
+      any_odd |= sh_odd[buf][w];
+    }
+    any_odd = uniform_u32(any_odd);
+    if (any_odd == 0) {
       uint64_t w0, w1, w2;
-      // lowest digit held: centre - 1 (or 0 when the centre is digit 0; a0 is then empty)
+      // lowest digit held: centre - 1 (or 0 when the centre is digit 0; the lowest accumulator is then empty)
       const uint32_t low = centre ? centre - 1 : 0;
-      if (centre) digits3_to_192(s0, s1, s2, w0, w1, w2);
-      else digits3_to_192(s1, s2, 0, w0, w1, w2);
+      if (centre) digits3_to_192(t0, t1, t2, w0, w1, w2);
+      else digits3_to_192(t1, t2, 0, w0, w1, w2);
       const double sum = fixed192_to_double(w0, w1, w2, 32 * static_cast<int>(low) - 149, false);
       const float mu = static_cast<float>(sum / static_cast<double>(len));
-      if (lane == 0) {
+      if (threadIdx.x == 0) {
         mur[c] = mu;
         doner[c] = 1;
       }
 #pragma unroll
-      for (int r = 0; r < kRounds; ++r) {
-        const uint32_t j0 = c * kChunk + r * 256;
+      for (int u = 0; u < kQuarter; ++u) {
+        const uint32_t j0 = c * kChunk + (wave * kQuarter + u) * 256;
         if (j0 >= d) break;  // wave-uniform
         const uint32_t j = j0 + lane * 4;
-        float xv[4] = {x[r].x, x[r].y, x[r].z, x[r].w};
+        float xv[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
         uint32_t nib = 0;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
@@ -569,12 +602,12 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
       }
     } else {
-      if (lane == 0) doner[c] = 0;
+      if (threadIdx.x == 0) doner[c] = 0;
       uint64_t* dg = accr + static_cast<size_t>(c) * kLimbs;
-#pragma unroll
-      for (int r = 0; r < kRounds; ++r) {
-        const uint32_t j = base + r * 256;
-        const float xv[4] = {x[r].x, x[r].y, x[r].z, x[r].w};
+#pragma unroll 1
+      for (int u = 0; u < kQuarter; ++u) {
+        const uint32_t j = base + u * 256;
+        const float xv[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
 #pragma unroll
         for (int s = 0; s < 4; ++s)
           if (j + s < d) add_direct(__float_as_uint(xv[s]), dg, specr + c);
@@ -863,7 +896,7 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
   // these passes hide their latencies through occupancy: many workgroups per row
   const dim3 grid_rows(G, geo.n), grid_2(G * 2, geo.n), grid_4(G * 4, geo.n), wg(kWG);
   const int fused = ws.uniform4096 ? 1 : 0;
-  if (fused) launch(L, kSlotBsPass1, k_bs_fused4096, grid_2, wg, stream, g, e, geo, ws);
+  if (fused) launch(L, kSlotBsPass1, k_bs_fused4096, dim3(geo.num_chunks, geo.n), wg, stream, g, e, geo, ws);
   else if (residual_pending) launch(L, kSlotBsPass1, k_bs_pass1<true>, grid_4, wg, stream, g, e, geo, ws);
   else launch(L, kSlotBsPass1, k_bs_pass1<false>, grid_4, wg, stream, g, e, geo, ws);
   COMPAMS_CHECK_LAUNCH();
