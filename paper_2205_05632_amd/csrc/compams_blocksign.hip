@@ -743,10 +743,12 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
   const uint32_t d = geo.d;
   // a wavefront takes a quarter of a chunk: four times as many wavefronts hide the latency of the per-round
   // chain (state, sign words, scales -> update -> store) better than one wavefront per chunk does
-  const uint32_t gw = blockIdx.x * kWaves + wave;
+  // (chunk, block and block end are scalars and come through scalar loads: a look-up through the vector path
+  // would wait for the state loads issued just before it, a second round trip per round)
+  const uint32_t gw = uniform_u32(blockIdx.x * kWaves + wave);
   const uint32_t c = gw / kBsSplit, part = gw % kBsSplit;
   if (c >= geo.num_chunks) return;
-  uint32_t b = ws.chunk_block[c];
+  uint32_t b = table_u32(ws.chunk_block, c);
   for (int r = part * (kRounds / kBsSplit); r < static_cast<int>(part + 1) * (kRounds / kBsSplit); ++r) {
     const uint32_t j0 = c * kChunk + r * 256;
     if (j0 >= d) break;
@@ -760,9 +762,9 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
       vv = *reinterpret_cast<const float4*>(v + j);
       vh = *reinterpret_cast<const float4*>(vhat + j);
     }
-    while (off[b + 1] <= j0) ++b;
+    while (table_u32(off, b + 1) <= j0) ++b;
     const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
-    const bool uniform = off[b + 1] >= j_end;
+    const bool uniform = table_u32(off, b + 1) >= j_end;
     uint32_t bb[4] = {b, b, b, b};
     if (!uniform) {
 #pragma unroll
@@ -781,7 +783,7 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
           mu[u] = 0.0f;
           if (i < geo.n) {
             if (ok[0]) word[u] = ws.bits[static_cast<size_t>(i) * geo.words + widx];
-            mu[u] = ws.scales[static_cast<size_t>(i) * geo.num_blocks + b];
+            mu[u] = table_f32(ws.scales + static_cast<size_t>(i) * geo.num_blocks, b);
           }
         }
 #pragma unroll
