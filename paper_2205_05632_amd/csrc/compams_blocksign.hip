@@ -835,16 +835,31 @@ __global__ __launch_bounds__(kWG) void k_none_amsgrad(const float* __restrict__ 
                                                        float* __restrict__ vhat, Geometry geo, AmsParams p) {
   const uint32_t j = (blockIdx.x * kWG + threadIdx.x) * 4;
   if (j >= geo.d) return;
-  float sum[4] = {0.f, 0.f, 0.f, 0.f};
-  for (uint32_t i = 0; i < geo.n; ++i) {
-    // x = e + g with e identically zero
-    const float4 gv = *reinterpret_cast<const float4*>(g + static_cast<int64_t>(i) * geo.ld + j);
-    sum[0] = sum[0] + (0.0f + gv.x); sum[1] = sum[1] + (0.0f + gv.y);
-    sum[2] = sum[2] + (0.0f + gv.z); sum[3] = sum[3] + (0.0f + gv.w);
+  const bool whole = j + 3 < geo.d;
+  // the optimizer state is requested first; the workers' gradients follow eight rows at a time, loads together
+  float4 th = make_float4(0.f, 0.f, 0.f, 0.f), mm = th, vv = th, vh = th;
+  if (whole) {
+    th = *reinterpret_cast<float4*>(theta + j); mm = *reinterpret_cast<float4*>(m + j);
+    vv = *reinterpret_cast<float4*>(v + j); vh = *reinterpret_cast<float4*>(vhat + j);
   }
-  if (j + 3 < geo.d) {
-    float4 th = *reinterpret_cast<float4*>(theta + j), mm = *reinterpret_cast<float4*>(m + j);
-    float4 vv = *reinterpret_cast<float4*>(v + j), vh = *reinterpret_cast<float4*>(vhat + j);
+  float sum[4] = {0.f, 0.f, 0.f, 0.f};
+  constexpr int kRows = 8;
+  for (uint32_t i0 = 0; i0 < geo.n; i0 += kRows) {
+    float4 gv[kRows];
+#pragma unroll
+    for (int u = 0; u < kRows; ++u) {
+      gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i0 + u < geo.n) gv[u] = load_stream4(g + static_cast<int64_t>(i0 + u) * geo.ld + j);  // uniform condition
+    }
+#pragma unroll
+    for (int u = 0; u < kRows; ++u)
+      if (i0 + u < geo.n) {
+        // x = e + g with e identically zero
+        sum[0] = sum[0] + (0.0f + gv[u].x); sum[1] = sum[1] + (0.0f + gv[u].y);
+        sum[2] = sum[2] + (0.0f + gv[u].z); sum[3] = sum[3] + (0.0f + gv[u].w);
+      }
+  }
+  if (whole) {
     ams_update(sum[0] / p.nf, th.x, mm.x, vv.x, vh.x, p);
     ams_update(sum[1] / p.nf, th.y, mm.y, vv.y, vh.y, p);
     ams_update(sum[2] / p.nf, th.z, mm.z, vv.z, vh.z, p);
