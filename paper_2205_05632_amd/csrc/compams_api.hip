@@ -480,6 +480,7 @@ static AmsParams ams_params(const compams_config& c, float lr) {
   ap.lr = lr;
   ap.nf = static_cast<float>(c.n);
   ap.eps_out = c.eps_mode == COMPAMS_EPS_OUT_SQRT;
+  ap.stream_state = static_cast<int64_t>(c.d) * 16 > (int64_t(192) << 20);  // against 256 MB of memory-side cache
   return ap;
 }
 

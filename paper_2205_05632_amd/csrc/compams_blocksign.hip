@@ -735,6 +735,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometr
 constexpr int kBsWorkers = 8;  // workers whose sign words and scales are requested together
 constexpr int kBsSplit = 4;    // wavefronts per chunk in the server kernel
 
+template <bool STREAM>  // streaming accesses for theta, m, v, vhat (see the top-k final kernel)
 __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, float* __restrict__ m,
                                                      float* __restrict__ v, float* __restrict__ vhat, Geometry geo,
                                                      BlocksignWorkspace ws, AmsParams p) {
@@ -757,10 +758,14 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
     // the optimizer state of this round is requested first; the sign/scale loop runs while it travels
     float4 th = make_float4(0.f, 0.f, 0.f, 0.f), mm = th, vv = th, vh = th;
     if (ok[3]) {
-      th = *reinterpret_cast<const float4*>(theta + j);
-      mm = *reinterpret_cast<const float4*>(m + j);
-      vv = *reinterpret_cast<const float4*>(v + j);
-      vh = *reinterpret_cast<const float4*>(vhat + j);
+      if (STREAM) {
+        th = load_stream4(theta + j); mm = load_stream4(m + j); vv = load_stream4(v + j); vh = load_stream4(vhat + j);
+      } else {
+        th = *reinterpret_cast<const float4*>(theta + j);
+        mm = *reinterpret_cast<const float4*>(m + j);
+        vv = *reinterpret_cast<const float4*>(v + j);
+        vh = *reinterpret_cast<const float4*>(vhat + j);
+      }
     }
     while (table_u32(off, b + 1) <= j0) ++b;
     const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
@@ -812,10 +817,14 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
       ams_update(sum[1] / p.nf, th.y, mm.y, vv.y, vh.y, p);
       ams_update(sum[2] / p.nf, th.z, mm.z, vv.z, vh.z, p);
       ams_update(sum[3] / p.nf, th.w, mm.w, vv.w, vh.w, p);
-      *reinterpret_cast<float4*>(theta + j) = th;
-      *reinterpret_cast<float4*>(m + j) = mm;
-      *reinterpret_cast<float4*>(v + j) = vv;
-      *reinterpret_cast<float4*>(vhat + j) = vh;
+      if (STREAM) {
+        store_stream4(theta + j, th); store_stream4(m + j, mm); store_stream4(v + j, vv); store_stream4(vhat + j, vh);
+      } else {
+        *reinterpret_cast<float4*>(theta + j) = th;
+        *reinterpret_cast<float4*>(m + j) = mm;
+        *reinterpret_cast<float4*>(v + j) = vv;
+        *reinterpret_cast<float4*>(vhat + j) = vh;
+      }
     } else {
       for (int s = 0; s < 4; ++s)
         if (ok[s]) {
@@ -830,6 +839,7 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
 // ---------------------------------------------------------------------------------------------
 // C = identity (full-precision distributed AMSGrad): gbar = mean of the n gradients in worker order.
 // ---------------------------------------------------------------------------------------------
+template <bool STREAM>
 __global__ __launch_bounds__(kWG) void k_none_amsgrad(const float* __restrict__ g, float* __restrict__ theta,
                                                        float* __restrict__ m, float* __restrict__ v,
                                                        float* __restrict__ vhat, Geometry geo, AmsParams p) {
@@ -839,8 +849,12 @@ __global__ __launch_bounds__(kWG) void k_none_amsgrad(const float* __restrict__ 
   // the optimizer state is requested first; the workers' gradients follow eight rows at a time, loads together
   float4 th = make_float4(0.f, 0.f, 0.f, 0.f), mm = th, vv = th, vh = th;
   if (whole) {
-    th = *reinterpret_cast<float4*>(theta + j); mm = *reinterpret_cast<float4*>(m + j);
-    vv = *reinterpret_cast<float4*>(v + j); vh = *reinterpret_cast<float4*>(vhat + j);
+    if (STREAM) {
+      th = load_stream4(theta + j); mm = load_stream4(m + j); vv = load_stream4(v + j); vh = load_stream4(vhat + j);
+    } else {
+      th = *reinterpret_cast<float4*>(theta + j); mm = *reinterpret_cast<float4*>(m + j);
+      vv = *reinterpret_cast<float4*>(v + j); vh = *reinterpret_cast<float4*>(vhat + j);
+    }
   }
   float sum[4] = {0.f, 0.f, 0.f, 0.f};
   constexpr int kRows = 8;
@@ -864,10 +878,14 @@ __global__ __launch_bounds__(kWG) void k_none_amsgrad(const float* __restrict__ 
     ams_update(sum[1] / p.nf, th.y, mm.y, vv.y, vh.y, p);
     ams_update(sum[2] / p.nf, th.z, mm.z, vv.z, vh.z, p);
     ams_update(sum[3] / p.nf, th.w, mm.w, vv.w, vh.w, p);
-    *reinterpret_cast<float4*>(theta + j) = th;
-    *reinterpret_cast<float4*>(m + j) = mm;
-    *reinterpret_cast<float4*>(v + j) = vv;
-    *reinterpret_cast<float4*>(vhat + j) = vh;
+    if (STREAM) {
+      store_stream4(theta + j, th); store_stream4(m + j, mm); store_stream4(v + j, vv); store_stream4(vhat + j, vh);
+    } else {
+      *reinterpret_cast<float4*>(theta + j) = th;
+      *reinterpret_cast<float4*>(m + j) = mm;
+      *reinterpret_cast<float4*>(v + j) = vv;
+      *reinterpret_cast<float4*>(vhat + j) = vh;
+    }
   } else {
     for (uint32_t s = 0; s < 4 && j + s < geo.d; ++s) {
       float th = theta[j + s], mm = m[j + s], vv = v[j + s], vh = vhat[j + s];
@@ -935,8 +953,9 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
 // The server's lines from the sign words and scales that sit in the workspace.
 hipError_t blocksign_server_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, float* theta,
                                  float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
-  launch(L, kSlotBsAms, k_bs_amsgrad, dim3((geo.num_chunks * kBsSplit + kWaves - 1) / kWaves), dim3(kWG), stream, theta,
-         m, v, vhat, geo, ws, ap);
+  const dim3 grid((geo.num_chunks * kBsSplit + kWaves - 1) / kWaves), wg(kWG);
+  if (ap.stream_state) launch(L, kSlotBsAms, k_bs_amsgrad<true>, grid, wg, stream, theta, m, v, vhat, geo, ws, ap);
+  else launch(L, kSlotBsAms, k_bs_amsgrad<false>, grid, wg, stream, theta, m, v, vhat, geo, ws, ap);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -950,8 +969,9 @@ hipError_t blocksign_apply_residual(const Geometry& geo, const BlocksignWorkspac
 hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, float* theta, float* m, float* v,
                      float* vhat, hipStream_t stream, Launcher* L) {
   const uint32_t quads = (geo.d + 3) / 4;
-  launch(L, kSlotNoneAms, k_none_amsgrad, dim3((quads + kWG - 1) / kWG), dim3(kWG), stream, g, theta, m, v, vhat, geo,
-         ap);
+  const dim3 grid((quads + kWG - 1) / kWG), wg(kWG);
+  if (ap.stream_state) launch(L, kSlotNoneAms, k_none_amsgrad<true>, grid, wg, stream, g, theta, m, v, vhat, geo, ap);
+  else launch(L, kSlotNoneAms, k_none_amsgrad<false>, grid, wg, stream, g, theta, m, v, vhat, geo, ap);
   return hipGetLastError();
 }
 

@@ -151,6 +151,8 @@ constexpr int kLimbs = 10;  // 10 digits of 32 bits cover 2^-149 .. 2^171
 struct AmsParams {
   float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, lr, nf;
   int eps_out;  // 1: epsilon outside the square root
+  int stream_state;  // 1: theta, m, v, vhat do not fit the memory-side cache from one step to the next: streaming
+                     // accesses for them (measured: 4-5 % faster then; 25 % slower when they do fit)
 };
 
 // Moment and parameter lines of Algorithm 2 for one coordinate: every product, sum, square root and

@@ -1184,7 +1184,9 @@ __device__ __forceinline__ FinalCtx final_ctx(const Geometry& geo, const TopkWor
   return f;
 }
 
-template <int ROLE, bool UNI>
+// STREAM: streaming accesses for theta, m, v, vhat (a template parameter: as a run-time choice between two
+// otherwise identical branches the compiler merges them and drops the hint).
+template <int ROLE, bool UNI, bool STREAM>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_topk_final(
     float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v, float* __restrict__ vhat,
     const float* __restrict__ e, Geometry geo, TopkWorkspace ws, TopkOptions opt, AmsParams p, TopkFlat flat) {
@@ -1335,17 +1337,26 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
     const uint32_t t = r * kWG * 4 + threadIdx.x * 4;
     const uint32_t j = base + t;
     if (j + 3 < d_end) {
-      float4 th = *reinterpret_cast<float4*>(theta + j), mm = *reinterpret_cast<float4*>(m + j);
-      float4 vv = *reinterpret_cast<float4*>(v + j), vh = *reinterpret_cast<float4*>(vhat + j);
+      float4 th, mm, vv, vh;
+      if (STREAM) {
+        th = load_stream4(theta + j); mm = load_stream4(m + j); vv = load_stream4(v + j); vh = load_stream4(vhat + j);
+      } else {
+        th = *reinterpret_cast<float4*>(theta + j); mm = *reinterpret_cast<float4*>(m + j);
+        vv = *reinterpret_cast<float4*>(v + j); vh = *reinterpret_cast<float4*>(vhat + j);
+      }
       const float4 s = *reinterpret_cast<const float4*>(gs + t);
       ams_update(s.x / p.nf, th.x, mm.x, vv.x, vh.x, p);
       ams_update(s.y / p.nf, th.y, mm.y, vv.y, vh.y, p);
       ams_update(s.z / p.nf, th.z, mm.z, vv.z, vh.z, p);
       ams_update(s.w / p.nf, th.w, mm.w, vv.w, vh.w, p);
-      *reinterpret_cast<float4*>(theta + j) = th;
-      *reinterpret_cast<float4*>(m + j) = mm;
-      *reinterpret_cast<float4*>(v + j) = vv;
-      *reinterpret_cast<float4*>(vhat + j) = vh;
+      if (STREAM) {
+        store_stream4(theta + j, th); store_stream4(m + j, mm); store_stream4(v + j, vv); store_stream4(vhat + j, vh);
+      } else {
+        *reinterpret_cast<float4*>(theta + j) = th;
+        *reinterpret_cast<float4*>(m + j) = mm;
+        *reinterpret_cast<float4*>(v + j) = vv;
+        *reinterpret_cast<float4*>(vhat + j) = vh;
+      }
     } else {
       for (uint32_t s = 0; s < 4 && j + s < d_end; ++s) {
         float th = theta[j + s], mm = m[j + s], vv = v[j + s], vh = vhat[j + s];
@@ -1465,12 +1476,17 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   const uint32_t count_blocks = (geo.num_chunks + geo.count_cpw - 1) / geo.count_cpw;  // <= kMaxCountBlocks
   launch(L, kSlotCount, k_topk_count<true>, dim3(count_blocks, geo.n), wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
+  const dim3 grid_f(geo.num_chunks);
+  const TopkFlat none{};
   if (role == kWorkerHalf)
-    launch(L, kSlotTopkFinal, k_topk_final<kWorkerHalf, true>, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws,
-           opt, ap, TopkFlat{});
+    launch(L, kSlotTopkFinal, k_topk_final<kWorkerHalf, true, false>, grid_f, wg, stream, theta, m, v, vhat, e, geo, ws, opt,
+           ap, none);
+  else if (ap.stream_state)
+    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, true, true>, grid_f, wg, stream, theta, m, v, vhat, e, geo, ws, opt,
+           ap, none);
   else
-    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, true>, dim3(geo.num_chunks), wg, stream, theta, m, v, vhat, e, geo, ws,
-           opt, ap, TopkFlat{});
+    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, true, false>, grid_f, wg, stream, theta, m, v, vhat, e, geo, ws, opt,
+           ap, none);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -1502,8 +1518,13 @@ hipError_t topk_blocks_step(const Geometry& geo, const TopkWorkspace& ws, const 
     launch(L, kSlotTopkEmit, k_topk_emit, dim3(flat.wg_emit), wg, stream, e, geo, ws, opt);
   } else {
     const float* residuals = e;
-    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, false>, dim3(flat.wg_final), wg, stream, theta, m, v, vhat,
-           residuals, geo, ws, opt, ap, flat);
+    const dim3 grid_f(flat.wg_final);
+    if (ap.stream_state)
+      launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, false, true>, grid_f, wg, stream, theta, m, v, vhat, residuals, geo,
+             ws, opt, ap, flat);
+    else
+      launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, false, false>, grid_f, wg, stream, theta, m, v, vhat, residuals, geo,
+             ws, opt, ap, flat);
   }
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
@@ -1517,8 +1538,14 @@ hipError_t topk_server_step(const Geometry& geo, const TopkWorkspace& ws, const 
   launch(L, kSlotTopkOffsets, k_topk_list_offsets, dim3(groups, geo.n), dim3(kWG), stream, geo, ws);
   COMPAMS_CHECK_LAUNCH();
   const float* no_e = nullptr;
-  launch(L, kSlotTopkFinal, k_topk_final<kServerHalf, true>, dim3(geo.num_chunks), dim3(kWG), stream, theta, m, v, vhat, no_e,
-         geo, ws, opt, ap, TopkFlat{});
+  const dim3 grid_f(geo.num_chunks), wg(kWG);
+  const TopkFlat none{};
+  if (ap.stream_state)
+    launch(L, kSlotTopkFinal, k_topk_final<kServerHalf, true, true>, grid_f, wg, stream, theta, m, v, vhat, no_e, geo, ws, opt,
+           ap, none);
+  else
+    launch(L, kSlotTopkFinal, k_topk_final<kServerHalf, true, false>, grid_f, wg, stream, theta, m, v, vhat, no_e, geo, ws,
+           opt, ap, none);
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
