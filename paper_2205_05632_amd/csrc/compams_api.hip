@@ -48,7 +48,7 @@ void launcher_end(Launcher* L, int slot, hipStream_t stream) {
 namespace {
 
 const char* const kSlotNames[kNumSlots] = {
-    "topk_pass_a", "topk_level1", "topk_level2", "topk_count", "topk_final", "topk_emit", "topk_offsets",
+    "topk_pass_a", "topk_level0", "topk_level1", "topk_level2", "topk_count", "topk_final", "topk_emit", "topk_offsets",
     "bs_pass1", "bs_finalize", "bs_pass2", "bs_amsgrad", "none_amsgrad", "wire_encode", "wire_decode"};
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

@@ -181,7 +181,7 @@ struct Geometry {
 
 // Kernel slots for optional timing.
 enum KernelSlot {
-  kSlotPassA = 0, kSlotLevel1, kSlotLevel2, kSlotCount, kSlotTopkFinal, kSlotTopkEmit, kSlotTopkOffsets,
+  kSlotPassA = 0, kSlotLevel0, kSlotLevel1, kSlotLevel2, kSlotCount, kSlotTopkFinal, kSlotTopkEmit, kSlotTopkOffsets,
   kSlotBsPass1, kSlotBsFinal, kSlotBsPass2, kSlotBsAms,
   kSlotNoneAms, kSlotWireEncode, kSlotWireDecode, kNumSlots
 };

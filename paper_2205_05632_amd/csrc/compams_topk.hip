@@ -756,6 +756,267 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
+// One selection per row, first pass without histograms.  A workgroup takes ONE chunk and ends; wavefront w takes
+// rounds 4w .. 4w+3 of it.  Measured on MI355X with plain streaming kernels of the same traffic (read g, read e,
+// write e, 2.1 GB): a grid of such short workgroups, handed out in order, streams at 6.1-6.4 TB/s, while
+// workgroups that each walk many chunks stay at 5.4-5.7 TB/s whatever their number, occupancy or prefetch depth.
+// A short-lived workgroup cannot afford a 4096-bin histogram in LDS (to clear and to flush), so this pass has
+// none: x = e + g (pending zeros honoured) is stored, and when the row carries a guess for the threshold bucket
+// the entries at or above it are staged per wavefront in coordinate order, the chunk's segment of the candidate
+// list is allocated with one atomic for the whole workgroup, and the four quarters are written behind one
+// another.  The level-0 histogram is taken afterwards, from the candidate list (k_topk_level0).
+// ---------------------------------------------------------------------------------------------
+constexpr int kLeanRounds = kRounds / kWaves;  // rounds of a chunk per wavefront
+constexpr int kStageQ = 512;                   // staged candidates per wavefront (of at most 1024 coordinates)
+
+template <bool PEND>
+__global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
+                                                    TopkWorkspace ws, TopkOptions opt, uint32_t use_guess) {
+  __shared__ uint2 stage_all[kWaves * kStageQ];
+  __shared__ uint32_t bm_all[PEND ? kWaves * 32 : 1];
+  __shared__ uint32_t sh_cnt[kWaves], sh_off;
+  const uint32_t c = blockIdx.x, row = blockIdx.y;
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const float* gr = g + static_cast<int64_t>(row) * geo.ld;
+  float* er = e + static_cast<int64_t>(row) * geo.ld;
+  TopkRow* rowp = ws.rows + row;
+  const bool pred = use_guess && rowp->pred_valid != 0;  // workgroup-uniform
+  const uint32_t bg = rowp->b_guess;
+  const uint32_t d = geo.d;
+  const uint32_t q0 = c * kChunk + wave * (kLeanRounds * 256);  // first coordinate of this wavefront's quarter
+  const bool full = (c + 1) * static_cast<uint64_t>(kChunk) <= d;
+  float4 gv[kLeanRounds], ev[kLeanRounds];
+#pragma unroll
+  for (int u = 0; u < kLeanRounds; ++u) {
+    const uint32_t j = q0 + u * 256 + lane * 4;
+    gv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    ev[u] = gv[u];
+    if (full || j < d) {
+      gv[u] = load_stream4(gr + j);
+      ev[u] = load_stream4(er + j);
+    }
+  }
+  uint32_t* bm = bm_all + (PEND ? wave * 32 : 0);
+  if constexpr (PEND) {
+    // the quarter's coordinates that were selected in the previous step: their residual counts as zero
+    if (lane < 32) bm[lane] = 0;
+    const uint32_t* prev_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
+    const int32_t* prev_idx = ws.idx + static_cast<size_t>(row) * geo.k;
+    const uint32_t lo = prev_off[c];
+    const uint32_t hi = prev_off[c + 1] < geo.k ? prev_off[c + 1] : geo.k;
+    for (uint32_t q = lo + lane; q < hi; q += 64) {
+      const uint32_t jl = static_cast<uint32_t>(prev_idx[q]) - q0;
+      if (jl < static_cast<uint32_t>(kLeanRounds * 256)) atomicOr(&bm[jl >> 5], 1u << (jl & 31u));
+    }
+  }
+  uint2* stage = stage_all + wave * kStageQ;
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int u = 0; u < kLeanRounds; ++u) {
+    const uint32_t j = q0 + u * 256 + lane * 4;
+    const bool ok[4] = {full || j < d, full || j + 1 < d, full || j + 2 < d, full || j + 3 < d};
+    float4 en = ev[u];
+    if constexpr (PEND) {
+      const uint32_t nib = (bm[u * 8 + (lane >> 3)] >> ((lane & 7u) * 4u)) & 15u;
+      if (nib & 1u) en.x = 0.0f;
+      if (nib & 2u) en.y = 0.0f;
+      if (nib & 4u) en.z = 0.0f;
+      if (nib & 8u) en.w = 0.0f;
+    }
+    float4 x = make_float4(en.x + gv[u].x, en.y + gv[u].y, en.z + gv[u].z, en.w + gv[u].w);
+    if (!full) {  // columns >= d keep what they held
+      if (!ok[1]) x.y = ev[u].y;
+      if (!ok[2]) x.z = ev[u].z;
+      if (!ok[3]) x.w = ev[u].w;
+    }
+    if (ok[0]) store_stream4(er + j, x);
+    if (pred) {
+      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)};
+      bool flag[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) flag[s] = ok[s] && (key_of_bits(bits[s]) >> kL0Shift) >= bg;
+      const RoundRank rr = rank_round(flag);
+      if (rr.total) {
+        uint32_t pos = cnt + rr.below;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          if (flag[s]) {
+            if (pos < static_cast<uint32_t>(kStageQ)) stage[pos] = make_uint2(j + s, bits[s]);
+            ++pos;
+          }
+        cnt += rr.total;
+      }
+    }
+  }
+  if (!pred) return;  // workgroup-uniform
+  // the chunk's segment: one allocation for the four quarters
+  if (lane == 0) sh_cnt[wave] = cnt;
+  __syncthreads();
+  uint32_t before = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const uint32_t t = sh_cnt[w];
+    before += static_cast<uint32_t>(w) < wave ? t : 0u;
+    total += t;
+  }
+  if (threadIdx.x == 0) {
+    const uint32_t off = total ? atomicAdd(&rowp->cursor, total) : 0u;
+    sh_off = off;
+    ws.desc[static_cast<size_t>(row) * geo.num_chunks + c] = make_uint2(off, total);
+  }
+  __syncthreads();
+  const uint32_t off = sh_off;
+  if (cnt == 0 || off + total > opt.cap) return;  // otherwise the row's list has overflowed and will not be used
+  uint2* dst = ws.cand + static_cast<size_t>(row) * opt.cap + off + before;
+  if (cnt <= static_cast<uint32_t>(kStageQ)) {
+    for (uint32_t q = lane; q < cnt; q += 64) dst[q] = stage[q];
+  } else {
+    // more candidates than the staging area holds: the quarter's (already stored) values are read again
+    uint32_t at = 0;
+    for (int u = 0; u < kLeanRounds; ++u) {
+      const uint32_t j = q0 + u * 256 + lane * 4;
+      float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j < d) x = *reinterpret_cast<const float4*>(er + j);
+      const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)};
+      bool flag[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) flag[s] = j + s < d && (key_of_bits(bits[s]) >> kL0Shift) >= bg;
+      const RoundRank rr = rank_round(flag);
+      uint32_t pos = at + rr.below;
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        if (flag[s]) {
+          if (pos < cnt) dst[pos] = make_uint2(j + s, bits[s]);
+          ++pos;
+        }
+      at += rr.total;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Level 0 after the lean first pass.  A row whose guess held (its candidate list holds at least k entries and
+// did not overflow) gets the histogram of threshold buckets from the list -- every key at or above the guessed
+// bucket is in it, so the k-th largest key of the list is the row's -- together with the level-1 histograms of
+// the three buckets from the guess upwards.  Any other row (no guess yet, the guess was too high, the list
+// overflowed) gets its histogram from the stored values themselves, one more read of the row.  The last
+// workgroup of the row finds the threshold bucket, decides the route of the remaining kernels and leaves the
+// guess for the next step.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
+                                                      TopkOptions opt, uint32_t use_guess) {
+  __shared__ uint32_t lh[kNB0];
+  __shared__ uint32_t lh1[kTracked * kNB1];
+  __shared__ uint32_t suf[kWG + 1];
+  __shared__ uint32_t out2[2];
+  __shared__ uint32_t sh_flag, sh_l1, sh_bstar, sh_need;
+  const uint32_t row = blockIdx.y;
+  TopkRow* rowp = ws.rows + row;
+  const uint32_t bg = rowp->b_guess;
+  const uint32_t cursor = rowp->cursor;  // written by the previous launch
+  const bool listed = use_guess && rowp->pred_valid != 0 && cursor >= geo.k && cursor <= opt.cap && !opt.force_dense;
+  for (int b = threadIdx.x; b < kNB0; b += kWG) lh[b] = 0;
+  for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWG) lh1[b] = 0;
+  __syncthreads();
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  if (listed) {
+    const uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
+    const uint32_t step = gridDim.x * kWG;
+    for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < cursor; q += step) {
+      const uint32_t key = key_of_bits(candr[q].y);
+      const uint32_t bucket = key >> kL0Shift;
+      atomicAdd(&lh[bucket], 1u);
+      const uint32_t rel = bucket - bg;
+      if (rel < kTracked) atomicAdd(&lh1[rel * kNB1 + ((key >> kL1Shift) & (kNB1 - 1))], 1u);
+    }
+  } else {
+    const float* er = e + static_cast<int64_t>(row) * geo.ld;
+    uint32_t zeros = 0;
+    const uint32_t stride = gridDim.x * kWaves;
+    for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+      const uint32_t base = c * kChunk + lane * 4;
+#pragma unroll 4
+      for (int r = 0; r < kRounds; ++r) {
+        const uint32_t j = base + r * 256;
+        if (c * kChunk + r * 256 >= geo.d) break;  // wave-uniform
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j < geo.d) x = *reinterpret_cast<const float4*>(er + j);
+        Quad q;
+        q.key[0] = key_of_bits(__float_as_uint(x.x)); q.key[1] = key_of_bits(__float_as_uint(x.y));
+        q.key[2] = key_of_bits(__float_as_uint(x.z)); q.key[3] = key_of_bits(__float_as_uint(x.w));
+#pragma unroll
+        for (int s = 0; s < 4; ++s) q.ok[s] = j + s < geo.d;
+        hist4<false>(lh, q, zeros);
+      }
+    }
+    if (zeros && lane == 0) atomicAdd(&lh[0], zeros);
+  }
+  __syncthreads();
+  uint32_t* gh = ws.hist0 + static_cast<size_t>(row) * kNB0;
+  for (int b = threadIdx.x; b < kNB0; b += kWG) {
+    const uint32_t h = lh[b];
+    if (h) atomicAdd(&gh[b], h);
+  }
+  uint32_t* gh1 = ws.hist1x + static_cast<size_t>(row) * kTracked * kNB1;
+  if (listed)
+    for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWG) {
+      const uint32_t h = lh1[b];
+      if (h) atomicAdd(&gh1[b], h);
+    }
+  // ---- row-wide part, by whichever workgroup of the row finishes last ----
+  if (!last_group_of_row(&rowp->ticket[0], gridDim.x, &sh_flag)) return;
+  take_hist<kNB0>(gh, lh);
+  find_crossing<kNB0>(lh, geo.k, suf, out2);
+  if (threadIdx.x == 0) {
+    const uint32_t bstar = out2[0], above = out2[1];
+    const uint32_t total = above + lh[bstar];  // entries with bucket >= bstar
+    uint32_t mode, n_src, reads;
+    if (listed) { mode = kModeCand; n_src = cursor; reads = 0; }  // bstar >= bg: the list holds the k largest keys
+    else if (total <= opt.cap && !opt.force_dense) { mode = kModeNeedB; n_src = total; reads = 1; }
+    else { mode = kModeDense; n_src = 0; reads = 4; }
+    rowp->mode = mode;
+    rowp->n_src = n_src;
+    rowp->cursor = 0;
+    rowp->bstar = bstar;
+    rowp->need = geo.k - above;
+    rowp->level1_done = 0;
+    // Guess for the next step: one bucket below this step's threshold bucket if the list that guess would
+    // have produced now fits with room to spare, else the bucket itself, else no guess.  From a list, nothing
+    // is known about the buckets below the guess it was made with: the bucket below is then taken to hold at
+    // most as many entries as all the buckets above it together.
+    uint32_t valid = 0, guess = 0;
+    if (opt.predict && !opt.force_dense) {
+      const uint32_t below = bstar ? ((listed && bstar == bg) ? total : lh[bstar - 1]) : 0;
+      if (bstar && total + below <= opt.cap / 2) { valid = 1; guess = bstar - 1; }
+      else if (total <= opt.cap / 2) { valid = 1; guess = bstar; }
+    }
+    rowp->pred_valid = valid;
+    rowp->b_guess = guess;
+    uint32_t* cn = ws.counters + row * 4;
+    cn[0] = reads;
+    cn[1] = n_src;
+    sh_l1 = (listed && bstar - bg < kTracked) ? 1u + (bstar - bg) : 0u;
+    sh_bstar = bstar;
+    sh_need = geo.k - above;
+  }
+  __syncthreads();
+  if (listed) {
+    const uint32_t which = sh_l1;  // 0: level 1 not available; 1 + t: histogram of bucket guess + t
+    if (which) {
+      const AgentView view = agent_view(gh1 + (which - 1) * kNB1, kNB1);
+      uint32_t x[kNB1 / kWG];
+#pragma unroll
+      for (int i = 0; i < kNB1 / kWG; ++i) x[i] = load_agent(view, i * kWG + threadIdx.x);
+#pragma unroll
+      for (int i = 0; i < kNB1 / kWG; ++i) lh[i * kWG + threadIdx.x] = x[i];
+    }
+    for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWG) gh1[b] = 0;
+    __syncthreads();
+    if (which) resolve_level1(rowp, sh_bstar, sh_need, lh, suf, out2);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Kernel 2: level 1 for rows that could not resolve it in the first pass.
 //   kModeNeedB: one more read of the row; writes the candidate list (bucket >= bstar) and the histogram.
 //   kModeCand : the list exists (the threshold bucket was above the tracked ones): sweep it.
@@ -1459,15 +1720,13 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
                      Launcher* L) {
   const int role = workers_only ? kWorkerHalf : kWholeStep;
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
-  const uint32_t GA = groups_first_pass(geo.n, geo.num_chunks, kWavesA);
-  const dim3 grid_rows(G, geo.n), wg(kWG), grid_a(GA, geo.n), wga(kWGA);
-  if (first_pass_may_predict) {
-    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<true, true, true>, grid_a, wga, stream, g, e, geo, ws, opt);
-    else launch(L, kSlotPassA, k_topk_pass_a<true, false, true>, grid_a, wga, stream, g, e, geo, ws, opt);
-  } else {
-    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<false, true, true>, grid_a, wga, stream, g, e, geo, ws, opt);
-    else launch(L, kSlotPassA, k_topk_pass_a<false, false, true>, grid_a, wga, stream, g, e, geo, ws, opt);
-  }
+  const dim3 grid_rows(G, geo.n), wg(kWG);
+  const uint32_t use_guess = first_pass_may_predict ? 1u : 0u;
+  const dim3 grid_chunks(geo.num_chunks, geo.n);
+  if (clear_pending) launch(L, kSlotPassA, k_topk_lean<true>, grid_chunks, wg, stream, g, e, geo, ws, opt, use_guess);
+  else launch(L, kSlotPassA, k_topk_lean<false>, grid_chunks, wg, stream, g, e, geo, ws, opt, use_guess);
+  COMPAMS_CHECK_LAUNCH();
+  launch(L, kSlotLevel0, k_topk_level0, grid_rows, wg, stream, e, geo, ws, opt, use_guess);
   COMPAMS_CHECK_LAUNCH();
   launch(L, kSlotLevel1, k_topk_level1<true>, grid_rows, wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
