@@ -60,6 +60,7 @@ struct Layout {
       wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_sweep, map_count, map_emit, map_final, micro_list;
   // block-sign
   size_t offsets, chunk_block, acc, special, done, scales, bits;
+  uint32_t acc_replicas;
   uint32_t cap_alloc, num_chunks, words;
   // top-k inside every block
   uint64_t k_total;
@@ -214,7 +215,10 @@ Layout make_layout(const compams_config* c) {
     const size_t M = static_cast<size_t>(c->num_blocks);
     L.offsets = take((M + 1) * 4);
     L.chunk_block = take(nc * 4);
-    L.acc = take(n * M * kLimbs * 8);
+    // sets of digits per (row, block): as many as a block has chunks on average, at most 32 (one for the layout
+    // "block = chunk")
+    L.acc_replicas = static_cast<uint32_t>(std::min<size_t>(32, std::max<size_t>(1, nc / M)));
+    L.acc = take(n * M * L.acc_replicas * kLimbs * 8);
     L.special = take(n * M * 4);
     L.done = take(n * M * 4);
     L.scales = take(n * M * 4);
@@ -434,6 +438,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     b.offsets = reinterpret_cast<uint32_t*>(w + lay.offsets);
     b.chunk_block = reinterpret_cast<uint32_t*>(w + lay.chunk_block);
     b.acc = reinterpret_cast<uint64_t*>(w + lay.acc);
+    b.acc_replicas = lay.acc_replicas;
     b.special = reinterpret_cast<uint32_t*>(w + lay.special);
     b.done = reinterpret_cast<uint32_t*>(w + lay.done);
     b.scales = reinterpret_cast<float*>(w + lay.scales);

@@ -107,7 +107,7 @@ __device__ __forceinline__ void acc_place(WaveAcc& A, uint32_t kmax_key, uint32_
 // lane 0, into the digits: bit position e_low - 1 above 2^-149, i.e. digit (e_low - 1) / 32 and up.
 // Out of line: flushes are rare (a wavefront leaves a block, or the window has taken kWinAdds additions), and
 // the streaming loops stay small enough for the instruction cache.
-__device__ __noinline__ void window_to_digits(double sum, uint32_t e_low, uint64_t* digits) {
+__device__ __forceinline__ void window_to_digits_inline(double sum, uint32_t e_low, uint64_t* digits) {
   const uint64_t mine = static_cast<uint64_t>(ldexp(sum, 150 - static_cast<int>(e_low)));  // exact, below 2^53
   const uint64_t all = wave_sum_u64(mine);                                                 // below 2^59
   if (lane_id() == 0 && all) {
@@ -118,6 +118,10 @@ __device__ __noinline__ void window_to_digits(double sum, uint32_t e_low, uint64
     if (d1) atomic_add_u64(digits + w + 1, d1);
     if (high) atomic_add_u64(digits + w + 2, high);  // w <= 7: still inside the kLimbs digits
   }
+}
+
+__device__ __noinline__ void window_to_digits(double sum, uint32_t e_low, uint64_t* digits) {
+  window_to_digits_inline(sum, e_low, digits);
 }
 
 __device__ __forceinline__ void acc_flush(WaveAcc& A, uint64_t* digits /* kLimbs of the (row, block) */) {
@@ -161,7 +165,7 @@ __device__ __forceinline__ void acc_add4(WaveAcc& A, const uint32_t bits[4], con
 }
 
 // Largest b with off[b] <= j, starting the walk at hint (off[hint] <= j must hold).
-__device__ __noinline__ uint32_t block_of(const uint32_t* __restrict__ off, uint32_t hint, uint32_t j) {
+__device__ __forceinline__ uint32_t block_of(const uint32_t* __restrict__ off, uint32_t hint, uint32_t j) {
   uint32_t b = hint;
   while (off[b + 1] <= j) ++b;
   return b;
@@ -214,6 +218,8 @@ __device__ __forceinline__ void digits3_to_192(uint64_t s0, uint64_t s1, uint64_
 // takes a chunk at a time and loads one batch of rounds ahead.
 // ---------------------------------------------------------------------------------------------
 constexpr int kBsBatch = 4;
+constexpr int kQuarter = kRounds / kWaves;  // rounds of a chunk per wavefront when a workgroup takes one chunk
+static_assert(kQuarter == kBsBatch, "a wavefront's quarter of a chunk is one batch of loads");
 
 // A value that is the same in every lane, moved to a scalar register: conditions on it become scalar branches
 // and it can be an operand of every lane's arithmetic without a register per lane.
@@ -261,28 +267,31 @@ __device__ __forceinline__ void bs_load_batch(BsBatch& B, const float* __restric
   bs_load_batch_t<false>(B, gr, er, c, r0, d);
 }
 
-// One round (256 coordinates from j0 on) that straddles block boundaries: every coordinate looks up its own
-// block (walking on from block b, the block of the round's first coordinate), takes that block's previous mean
-// (PEND) and adds its magnitude to that block's digits.  Rare (a few rounds per row) and out of line, so that
-// the common round keeps no register that a path through here may have loaded a moment ago: the compiler would
-// otherwise make every round wait for all loads in flight, the next batch's included.
+// One round (256 coordinates from j0 on) that straddles block boundaries.  The blocks that meet the round are
+// the same for every lane, so they are gone through one after the other (from block b, the block of the round's
+// first coordinate, on): the block's previous mean is taken off the residuals of its coordinates (PEND), and
+// after x has been formed and stored the magnitudes of its coordinates are summed in a register window and go
+// to its digits like any other partial sum.  A block with at most 8 coordinates in the round adds them one by
+// one instead (a layout of one-coordinate blocks would otherwise make 256 trips through the wavefront-wide
+// sum).  Rare -- a few rounds per row in layouts worth the name -- and out of line.
 template <bool PEND>
 __device__ __noinline__ void straddling_round(float4 g4, float4 e4, uint32_t j0, uint32_t d, uint32_t b,
                                               const uint32_t* __restrict__ off, const float* __restrict__ mur,
                                               float* __restrict__ er, uint32_t* __restrict__ bitr, uint32_t words,
-                                              uint64_t* accr, uint32_t* specr) {
+                                              uint64_t* accr, size_t blk_digits, uint32_t replica, uint32_t* specr) {
   const uint32_t lane = lane_id();
   const uint32_t j = j0 + lane * 4;
+  const uint32_t j_end = j0 + 256 < d ? j0 + 256 : d;
   const bool ok[4] = {j < d, j + 1 < d, j + 2 < d, j + 3 < d};
   float ev[4] = {e4.x, e4.y, e4.z, e4.w};
   const float gv[4] = {g4.x, g4.y, g4.z, g4.w};
-  uint32_t bb[4];
+  if (PEND) {
+    for (uint32_t bb = b; table_u32(off, bb) < j_end; ++bb) {  // wave-uniform
+      const uint32_t lo = table_u32(off, bb), hi = table_u32(off, bb + 1);
+      const float mu = table_f32(mur, bb);
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    bb[s] = ok[s] ? block_of(off, b, j + s) : b;
-    if (PEND && ok[s]) {
-      const float mu = mur[bb[s]];
-      ev[s] = ev[s] - (ev[s] < 0.0f ? -mu : mu);
+      for (int s = 0; s < 4; ++s)
+        if (ok[s] && j + s >= lo && j + s < hi) ev[s] = ev[s] - (ev[s] < 0.0f ? -mu : mu);
     }
   }
   float xv[4];
@@ -296,9 +305,38 @@ __device__ __noinline__ void straddling_round(float4 g4, float4 e4, uint32_t j0,
   const uint32_t word = or_over_8_lanes(nib << ((lane & 7u) * 4u));
   const uint32_t widx = (j0 >> 5) + (lane >> 3);
   if ((lane & 7u) == 0 && widx < words) bitr[widx] = word;
+  const uint32_t bits[4] = {__float_as_uint(xv[0]), __float_as_uint(xv[1]), __float_as_uint(xv[2]),
+                            __float_as_uint(xv[3])};
+  for (uint32_t bb = b; table_u32(off, bb) < j_end; ++bb) {  // wave-uniform
+    const uint32_t lo = table_u32(off, bb), hi = table_u32(off, bb + 1);
+    bool in[4];
 #pragma unroll
-  for (int s = 0; s < 4; ++s)
-    if (ok[s]) add_direct(__float_as_uint(xv[s]), accr + static_cast<size_t>(bb[s]) * kLimbs, specr + bb[s]);
+    for (int s = 0; s < 4; ++s) in[s] = ok[s] && j + s >= lo && j + s < hi;
+    uint64_t* dg = accr + static_cast<size_t>(bb) * blk_digits;
+    const uint32_t first = lo > j0 ? lo : j0, last = hi < j_end ? hi : j_end;
+    if (last - first <= 8) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        if (in[s]) add_direct(bits[s], dg, specr + bb);
+    } else {
+      uint32_t kmax = 0;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const uint32_t key = bits[s] & 0x7fffffffu;
+        if (in[s] && key < 0x7f800000u && key > kmax) kmax = key;
+      }
+#pragma unroll
+      for (int s = 32; s >= 1; s >>= 1) {
+        const uint32_t o = __shfl_xor(kmax, s, 64);
+        kmax = o > kmax ? o : kmax;
+      }
+      WaveAcc A;
+      acc_reset(A);
+      acc_place(A, uniform_u32(kmax), 0);
+      acc_add4(A, bits, in, dg + static_cast<size_t>(replica) * kLimbs, specr + bb);
+      window_to_digits_inline(A.sum, A.eh, dg + static_cast<size_t>(replica) * kLimbs);
+    }
+  }
 }
 
 // Makes the registers of a batch inputs of an (empty) instruction sequence: whatever loads they are waiting
@@ -311,143 +349,100 @@ __device__ __forceinline__ void settle_batch(BsBatch& B) {
   }
 }
 
-// A wavefront walks chunks c, c + stride, ... in batches of kBsBatch rounds; the loads of the next batch
-// (of the same or of the next chunk) are in flight while the current one is summed.
-//
-// PEND: the residual update of the previous step has not been applied yet: e still holds that step's x,
-// and ws.scales that step's block means.  The pass then forms e = x_prev - sign(x_prev) * mu_prev on the
-// fly (the very expression, in fp32, that the stand-alone residual kernel applies) before it adds g.  In
-// this way a step with layer-sized blocks reads g and e once and writes e once; the mean of a block is
-// needed before its residual can be written, but not before the *next* step reads it.
-// The pass also writes the sign words of x (eight lanes, 32 coordinates, share a word).
+// ---------------------------------------------------------------------------------------------
+// First pass for general block layouts as a grid of short workgroups: a workgroup takes ONE chunk and ends,
+// wavefront w takes rounds 4w .. 4w+3 of it (plain streaming kernels of this shape move the same traffic at
+// 6.1-6.4 TB/s on MI355X, workgroups that walk many chunks at 5.4-5.7 TB/s).  A quarter that lies inside one
+// block -- all but a few per row -- is summed in a register window placed by the quarter's own largest
+// magnitude and goes to the block's digits with at most three atomics per wavefront; a quarter that straddles
+// block boundaries takes the out-of-line per-coordinate route.  The pending residual update is applied on
+// the fly as before.
+// ---------------------------------------------------------------------------------------------
 template <bool PEND>
-__global__ __launch_bounds__(kWG) void k_bs_pass1(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
-                                                   BlocksignWorkspace ws) {
-  const uint32_t row = blockIdx.y;
+__global__ __launch_bounds__(kWG) void k_bs_lean(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
+                                                  BlocksignWorkspace ws) {
+  const uint32_t c = blockIdx.x, row = blockIdx.y;
+  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
   const float* gr = g + static_cast<int64_t>(row) * geo.ld;
   float* er = e + static_cast<int64_t>(row) * geo.ld;
   const uint32_t* __restrict__ off = ws.offsets;
   const float* mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;  // previous step's means (PEND)
   uint32_t* bitr = ws.bits + static_cast<size_t>(row) * geo.words;
-  uint64_t* accr = ws.acc + static_cast<size_t>(row) * geo.num_blocks * kLimbs;
+  const size_t blk_digits = static_cast<size_t>(ws.acc_replicas) * kLimbs;  // digits of one (row, block): all replicas
+  uint64_t* accr = ws.acc + static_cast<size_t>(row) * geo.num_blocks * blk_digits;
   uint32_t* specr = ws.special + static_cast<size_t>(row) * geo.num_blocks;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint32_t stride = gridDim.x * kWaves;
   const uint32_t d = geo.d;
-  uint32_t c = uniform_u32(blockIdx.x * kWaves + wave);  // the wavefront's chunk: a scalar, like all that follows from it
-  if (c >= geo.num_chunks) return;
-  int r0 = 0;
-  BsBatch cur, nxt;
-  // (a chunk that lies entirely below d, as every chunk of a row but the last does: plain loads, all in flight
-  // together; with per-lane predicates the compiler waits for each pair of loads before it issues the next)
-  if ((c + 1) * static_cast<uint64_t>(kChunk) <= d) bs_load_batch_t<true>(cur, gr, er, c, 0, d);
-  else bs_load_batch_t<false>(cur, gr, er, c, 0, d);
-  // b: block of the round being summed; blk_end = off[b + 1] and mu_b = the block's previous mean are kept in
-  // registers (the tables are only read when the walk enters another block); b_next: block of the next
-  // chunk's first coordinate, requested together with that chunk's first batch.
-  uint32_t b = table_u32(ws.chunk_block, c), b_next = b;
-  uint32_t blk_end = table_u32(off, b + 1);
-  float mu_b = PEND ? table_f32(mur, b) : 0.0f;
-  WaveAcc A;
-  acc_reset(A);
-  // The first batch has to have arrived before the loop is entered: inside the loop the batch being summed was
-  // copied from registers that had been waited for, and only if that holds on every way into the loop does the
-  // compiler leave the next batch's loads in flight while the current one is summed (otherwise it waits for all
-  // outstanding loads at the first use of the current batch, in every iteration).
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // one wait for the whole batch (its loads stay above this line)
-  settle_batch(cur);
-  for (;;) {
-    // where the walk goes next (wave-uniform)
-    uint32_t cn = c;
-    int rn = r0 + kBsBatch;
-    if (rn >= kRounds || c * kChunk + rn * 256 >= d) { cn = c + stride; rn = 0; }
-    const bool more = cn < geo.num_chunks;
-    if (more) {
-      bs_load_batch(nxt, gr, er, cn, rn, d);
-      if (rn == 0) b_next = table_u32(ws.chunk_block, cn);
+  const uint32_t q0 = c * kChunk + wave * (kQuarter * 256);  // first coordinate of this wavefront's quarter
+  if (q0 >= d) return;                                       // wave-uniform; no barrier in this kernel
+  const bool full = (c + 1) * static_cast<uint64_t>(kChunk) <= d;
+  BsBatch cur;
+  if (full) bs_load_batch_t<true>(cur, gr, er, c, wave * kQuarter, d);
+  else bs_load_batch_t<false>(cur, gr, er, c, wave * kQuarter, d);
+  uint32_t b = table_u32(ws.chunk_block, c);
+  while (table_u32(off, b + 1) <= q0) ++b;  // block of the quarter's first coordinate
+  const uint32_t q_end = q0 + kQuarter * 256 < d ? q0 + kQuarter * 256 : d;
+  if (table_u32(off, b + 1) < q_end) {  // the quarter straddles block boundaries (a scalar condition)
+#pragma unroll  // (a run-time index into the batch would put it into scratch memory)
+    for (int u = 0; u < kQuarter; ++u) {
+      const uint32_t j0 = q0 + u * 256;
+      if (j0 >= d) break;
+      while (table_u32(off, b + 1) <= j0) ++b;
+      straddling_round<PEND>(cur.g[u], cur.e[u], j0, d, b, off, mur, er, bitr, geo.words, accr, blk_digits,
+                             c % ws.acc_replicas, specr);
     }
-    // One batch of rounds.  FULL: the chunk lies entirely below d (every chunk of a row but the last): no
-    // per-coordinate bounds predicates are needed.
-    auto batch = [&](auto full_tag) {
-    constexpr bool FULL = decltype(full_tag)::value;
+    return;
+  }
+  const float mu_b = PEND ? table_f32(mur, b) : 0.0f;
+  uint32_t bits[kQuarter][4];
+  uint32_t kmax = 0;
 #pragma unroll
-    for (int u = 0; u < kBsBatch; ++u) {
-      const uint32_t j0 = c * kChunk + (r0 + u) * 256;  // wave-uniform
-      if (!FULL && j0 >= d) break;
-      const uint32_t j = j0 + lane * 4;
-      const bool in = FULL || j < d;
-      const bool ok[4] = {in, FULL || j + 1 < d, FULL || j + 2 < d, FULL || j + 3 < d};
-      // leave blocks that end at or before this round
-      while (blk_end <= j0) {
-        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
-        ++b;
-        blk_end = table_u32(off, b + 1);
-        if (PEND) mu_b = table_f32(mur, b);
-      }
-      const uint32_t j_end = (FULL || j0 + 256 < d) ? j0 + 256 : d;
-      if (blk_end < j_end) {  // the round straddles block boundaries (a scalar condition): out of line
-        acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
-        straddling_round<PEND>(cur.g[u], cur.e[u], j0, d, b, off, mur, er, bitr, geo.words, accr, specr);
-        continue;
-      }
-      // the whole round lies in block b
-      float ev[4] = {cur.e[u].x, cur.e[u].y, cur.e[u].z, cur.e[u].w};
-      const float gv[4] = {cur.g[u].x, cur.g[u].y, cur.g[u].z, cur.g[u].w};
-      if (PEND) {
+  for (int u = 0; u < kQuarter; ++u) {
+    const uint32_t j0 = q0 + u * 256;
+    const uint32_t j = j0 + lane * 4;
+    const bool ok[4] = {full || j < d, full || j + 1 < d, full || j + 2 < d, full || j + 3 < d};
+    float ev[4] = {cur.e[u].x, cur.e[u].y, cur.e[u].z, cur.e[u].w};
+    const float gv[4] = {cur.g[u].x, cur.g[u].y, cur.g[u].z, cur.g[u].w};
+    if (PEND) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-          if (ok[s]) ev[s] = ev[s] - (ev[s] < 0.0f ? -mu_b : mu_b);
-      }
-      float xv[4];
-      uint32_t nib = 0;
+      for (int s = 0; s < 4; ++s)
+        if (ok[s]) ev[s] = ev[s] - (ev[s] < 0.0f ? -mu_b : mu_b);
+    }
+    float xv[4];
+    uint32_t nib = 0;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        xv[s] = ok[s] ? ev[s] + gv[s] : ev[s];  // columns at and beyond d keep their contents
-        nib |= (ok[s] && xv[s] < 0.0f ? 1u : 0u) << s;
-      }
-      if (in) store_stream4(er + j, make_float4(xv[0], xv[1], xv[2], xv[3]));
+    for (int s = 0; s < 4; ++s) {
+      xv[s] = ok[s] ? ev[s] + gv[s] : ev[s];  // columns at and beyond d keep their contents
+      nib |= (ok[s] && xv[s] < 0.0f ? 1u : 0u) << s;
+    }
+    if (ok[0]) store_stream4(er + j, make_float4(xv[0], xv[1], xv[2], xv[3]));
+    if (full || j0 < d) {  // wave-uniform
       const uint32_t word = or_over_8_lanes(nib << ((lane & 7u) * 4u));
       const uint32_t widx = (j0 >> 5) + (lane >> 3);
-      if ((lane & 7u) == 0 && (FULL || widx < geo.words)) bitr[widx] = word;
-      const uint32_t bits[4] = {__float_as_uint(xv[0]), __float_as_uint(xv[1]), __float_as_uint(xv[2]),
-                                __float_as_uint(xv[3])};
-      if (A.adds + 4 > kWinAdds) acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
-      if (!A.live) {
-        // place the window by the largest magnitude of this round, with room for entries 4 times larger
-        uint32_t kmax = 0;
+      if ((lane & 7u) == 0 && (full || widx < geo.words)) bitr[widx] = word;
+    }
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const uint32_t key = bits[s] & 0x7fffffffu;
-          if (ok[s] && key < 0x7f800000u && key > kmax) kmax = key;
-        }
-#pragma unroll
-        for (int s = 32; s >= 1; s >>= 1) {
-          const uint32_t o = __shfl_xor(kmax, s, 64);
-          kmax = o > kmax ? o : kmax;
-        }
-        acc_place(A, uniform_u32(kmax), 2);
-      }
-      acc_add4(A, bits, ok, accr + static_cast<size_t>(b) * kLimbs, specr + b);
+    for (int s = 0; s < 4; ++s) {
+      bits[u][s] = ok[s] ? __float_as_uint(xv[s]) : 0u;  // a coordinate beyond d adds nothing
+      const uint32_t key = bits[u][s] & 0x7fffffffu;
+      if (key < 0x7f800000u && key > kmax) kmax = key;
     }
-    };
-    if ((c + 1) * static_cast<uint64_t>(kChunk) <= d) batch(std::true_type{});
-    else batch(std::false_type{});
-    // b is wave-uniform.  The register digits stay live across the wavefront's chunks as long as these lie in
-    // one block; they are flushed when the walk moves to another block and at the end.
-    if (!more) {
-      acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
-      break;
-    }
-    if (rn == 0 && b_next != b) {
-      acc_flush(A, accr + static_cast<size_t>(b) * kLimbs);
-      b = b_next;
-      blk_end = table_u32(off, b + 1);
-      if (PEND) mu_b = table_f32(mur, b);
-    }
-    cur = nxt;
-    c = cn;
-    r0 = rn;
   }
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) {
+    const uint32_t o = __shfl_xor(kmax, s, 64);
+    kmax = o > kmax ? o : kmax;
+  }
+  // the window ends at the quarter's largest magnitude: 16 additions per lane, exact
+  WaveAcc A;
+  acc_reset(A);
+  acc_place(A, uniform_u32(kmax), 0);
+  // a large block receives the sums of thousands of wavefronts: they go to one of several sets of digits, chosen
+  // by the chunk (atomics to one address are performed one after the other), which the finalize kernel adds up
+  uint64_t* dg = accr + static_cast<size_t>(b) * blk_digits + static_cast<size_t>(c % ws.acc_replicas) * kLimbs;
+  const bool all[4] = {true, true, true, true};
+#pragma unroll
+  for (int u = 0; u < kQuarter; ++u) acc_add4(A, bits[u], all, dg, specr + b);
+  window_to_digits_inline(A.sum, A.eh, dg);  // once per wavefront: in line (a call would go through scratch)
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -471,8 +466,6 @@ __device__ __forceinline__ void store_valid4(float* er, uint32_t j, uint32_t d, 
   }
 }
 
-constexpr int kQuarter = kRounds / kWaves;  // rounds of a block per wavefront
-static_assert(kQuarter == kBsBatch, "a wavefront's quarter of a block is one batch of loads");
 
 __global__ __launch_bounds__(kWG) void k_bs_fused4096(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
                                                        BlocksignWorkspace ws) {
@@ -481,7 +474,8 @@ __global__ __launch_bounds__(kWG) void k_bs_fused4096(const float* __restrict__ 
   const uint32_t row = blockIdx.y;
   const float* gr = g + static_cast<int64_t>(row) * geo.ld;
   float* er = e + static_cast<int64_t>(row) * geo.ld;
-  uint64_t* accr = ws.acc + static_cast<size_t>(row) * geo.num_blocks * kLimbs;
+  const size_t blk_digits = static_cast<size_t>(ws.acc_replicas) * kLimbs;  // digits of one (row, block): all replicas
+  uint64_t* accr = ws.acc + static_cast<size_t>(row) * geo.num_blocks * blk_digits;
   uint32_t* specr = ws.special + static_cast<size_t>(row) * geo.num_blocks;
   float* mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;
   uint32_t* doner = ws.done + static_cast<size_t>(row) * geo.num_blocks;
@@ -603,7 +597,7 @@ __global__ __launch_bounds__(kWG) void k_bs_fused4096(const float* __restrict__ 
       }
     } else {
       if (threadIdx.x == 0) doner[c] = 0;
-      uint64_t* dg = accr + static_cast<size_t>(c) * kLimbs;
+      uint64_t* dg = accr + static_cast<size_t>(c) * blk_digits;
 #pragma unroll 1
       for (int u = 0; u < kQuarter; ++u) {
         const uint32_t j = base + u * 256;
@@ -622,20 +616,45 @@ __global__ __launch_bounds__(kWG) void k_bs_fused4096(const float* __restrict__ 
 // to even), divide by the block length, round to fp32.  Clears the digits for the next step.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWorkspace ws, int skip_done) {
-  const size_t t = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x;
   const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
-  if (t >= total) return;
-  if (skip_done && ws.done[t]) return;
+  const uint32_t R = ws.acc_replicas;  // sets of digits per (row, block)
+  size_t t;
+  uint64_t word[kLimbs];
+  if (R == 1) {  // a thread per (row, block)
+    t = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x;
+    if (t >= total) return;
+    if (skip_done && ws.done[t]) return;
+    uint64_t* dg = ws.acc + t * kLimbs;
+#pragma unroll
+    for (int i = 0; i < kLimbs; ++i) {
+      word[i] = dg[i];
+      dg[i] = 0;
+    }
+  } else {  // a wavefront per (row, block): lane r brings replica r, the sums are taken over the wavefront
+    t = static_cast<size_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
+    if (t >= total) return;
+    if (skip_done && ws.done[t]) return;
+    const uint32_t lane = lane_id();
+    uint64_t* dg = ws.acc + (t * R + lane) * kLimbs;
+#pragma unroll
+    for (int i = 0; i < kLimbs; ++i) {
+      uint64_t mine = 0;
+      if (lane < R) {
+        mine = dg[i];
+        dg[i] = 0;
+      }
+      word[i] = wave_sum_u64(mine);  // every digit word is far below 2^53 (see window_to_digits): no wrap
+    }
+    if (lane != 0) return;
+  }
   const uint32_t b = static_cast<uint32_t>(t % geo.num_blocks);
-  uint64_t* dg = ws.acc + t * kLimbs;
   uint32_t digit[kLimbs + 1];
   uint64_t carry = 0;
 #pragma unroll
   for (int i = 0; i < kLimbs; ++i) {
-    const uint64_t v = dg[i] + carry;
+    const uint64_t v = word[i] + carry;
     digit[i] = static_cast<uint32_t>(v);
     carry = v >> 32;
-    dg[i] = 0;
   }
   digit[kLimbs] = static_cast<uint32_t>(carry);
   const uint32_t sp = ws.special[t];
@@ -932,12 +951,13 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
   const dim3 grid_rows(G, geo.n), grid_2(G * 2, geo.n), grid_4(G * 4, geo.n), wg(kWG);
   const int fused = ws.uniform4096 ? 1 : 0;
   if (fused) launch(L, kSlotBsPass1, k_bs_fused4096, dim3(geo.num_chunks, geo.n), wg, stream, g, e, geo, ws);
-  else if (residual_pending) launch(L, kSlotBsPass1, k_bs_pass1<true>, grid_4, wg, stream, g, e, geo, ws);
-  else launch(L, kSlotBsPass1, k_bs_pass1<false>, grid_4, wg, stream, g, e, geo, ws);
+  else if (residual_pending) launch(L, kSlotBsPass1, k_bs_lean<true>, dim3(geo.num_chunks, geo.n), wg, stream, g, e, geo, ws);
+  else launch(L, kSlotBsPass1, k_bs_lean<false>, dim3(geo.num_chunks, geo.n), wg, stream, g, e, geo, ws);
   COMPAMS_CHECK_LAUNCH();
   const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
-  launch(L, kSlotBsFinal, k_bs_finalize, dim3(static_cast<uint32_t>((total + kWG - 1) / kWG)), wg, stream, geo, ws,
-         fused);
+  const size_t per_group = ws.acc_replicas == 1 ? kWG : kWaves;  // (row, block) pairs per workgroup
+  launch(L, kSlotBsFinal, k_bs_finalize, dim3(static_cast<uint32_t>((total + per_group - 1) / per_group)), wg, stream,
+         geo, ws, fused);
   COMPAMS_CHECK_LAUNCH();
   // General layouts: the residual e = x - sign(x) * mu is left to the next step's first pass (or to
   // blocksign_apply_residual when e is asked for).  Block = chunk layout: only the blocks that the single pass

@@ -139,7 +139,9 @@ struct TopkWorkspace {
 struct BlocksignWorkspace {
   uint32_t* offsets;    // M + 1 block offsets
   uint32_t* chunk_block; // num_chunks : index of the block that holds the chunk's first coordinate
-  uint64_t* acc;        // n * M * kLimbs : exact sums of |x| (32-bit digits carried in 64-bit words)
+  uint64_t* acc;        // n * M * acc_replicas * kLimbs : exact sums of |x| (32-bit digits carried in 64-bit words);
+                        // the sum of a (row, block) is the sum of its replicas
+  uint32_t acc_replicas;
   uint32_t* special;    // n * M : bit 0 = an infinity was seen, bit 1 = a NaN was seen
   uint32_t* done;       // n * M : the fused single pass has finished this block (block = chunk layouts only)
   uint32_t uniform4096; // block b is exactly coordinates [4096 b, 4096 (b + 1))
