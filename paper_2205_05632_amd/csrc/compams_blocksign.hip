@@ -928,7 +928,8 @@ __global__ __launch_bounds__(kWG) void k_fill_rows(float* p, int64_t ld, uint32_
   for (uint32_t j = blockIdx.x * kWG + threadIdx.x; j < d; j += step) r[j] = value;
 }
 
-// Streaming (non-temporal) accesses, as in the step's dense kernels.
+// Streaming (non-temporal) accesses and short workgroups (4 KiB each, handed out in order), as in the step's dense
+// kernels: the shape that streams fastest on this part.
 __global__ __launch_bounds__(kWG) void k_copy16(float* __restrict__ dst, const float* __restrict__ src, size_t count) {
   const size_t step = static_cast<size_t>(gridDim.x) * kWG;
   for (size_t i = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x; i < count; i += step)
@@ -1013,8 +1014,8 @@ hipError_t fill_rows_f32(float* p, uint32_t n, int64_t ld, uint32_t d, float val
 hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream) {
   const size_t count = bytes / 16;
   if (!count) return hipSuccess;
-  size_t blocks = (count + kWG - 1) / kWG;
-  if (blocks > 256 * 16) blocks = 256 * 16;
+  size_t blocks = (count + kWG - 1) / kWG;  // one quad per thread up to 32 GiB, a stride loop beyond
+  if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;
   hipLaunchKernelGGL(k_copy16, dim3(static_cast<uint32_t>(blocks)), dim3(kWG), 0, stream,
                      static_cast<float*>(dst), static_cast<const float*>(src), count);
   return hipGetLastError();
