@@ -262,10 +262,6 @@ __device__ __forceinline__ void bs_load_batch_t(BsBatch& B, const float* __restr
   }
 }
 
-__device__ __forceinline__ void bs_load_batch(BsBatch& B, const float* __restrict__ gr, const float* __restrict__ er,
-                                              uint32_t c, int r0, uint32_t d) {
-  bs_load_batch_t<false>(B, gr, er, c, r0, d);
-}
 
 // One round (256 coordinates from j0 on) that straddles block boundaries.  The blocks that meet the round are
 // the same for every lane, so they are gone through one after the other (from block b, the block of the round's
@@ -336,16 +332,6 @@ __device__ __noinline__ void straddling_round(float4 g4, float4 e4, uint32_t j0,
       acc_add4(A, bits, in, dg + static_cast<size_t>(replica) * kLimbs, specr + bb);
       window_to_digits_inline(A.sum, A.eh, dg + static_cast<size_t>(replica) * kLimbs);
     }
-  }
-}
-
-// Makes the registers of a batch inputs of an (empty) instruction sequence: whatever loads they are waiting
-// for have completed afterwards, as far as the compiler's bookkeeping is concerned too.
-__device__ __forceinline__ void settle_batch(BsBatch& B) {
-#pragma unroll
-  for (int u = 0; u < kBsBatch; ++u) {
-    asm volatile("" : "+v"(B.g[u].x), "+v"(B.g[u].y), "+v"(B.g[u].z), "+v"(B.g[u].w));
-    asm volatile("" : "+v"(B.e[u].x), "+v"(B.e[u].y), "+v"(B.e[u].z), "+v"(B.e[u].w));
   }
 }
 

@@ -256,14 +256,5 @@ inline uint32_t groups_per_row(uint32_t n, uint32_t num_chunks) {
   return g;
 }
 
-// The first pass streams best with about one workgroup per compute unit (fewer concurrent address
-// streams keep DRAM pages open longer); measured on MI355X.
-inline uint32_t groups_first_pass(uint32_t n, uint32_t num_chunks, uint32_t waves_per_group) {
-  uint32_t g = (256 + n - 1) / n;
-  const uint32_t max_g = (num_chunks + waves_per_group - 1) / waves_per_group;
-  if (g > max_g) g = max_g;
-  if (g < 1) g = 1;
-  return g;
-}
 
 }  // namespace compams
