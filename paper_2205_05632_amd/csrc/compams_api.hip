@@ -57,7 +57,7 @@ struct Layout {
   size_t total;
   // top-k
   size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_total,
-      wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_sweep, map_count, map_emit, map_final, micro_list;
+      wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_level0, map_sweep, map_count, map_emit, map_final, micro_list;
   // block-sign
   size_t offsets, chunk_block, acc, special, done, scales, bits;
   uint32_t acc_replicas;
@@ -94,7 +94,7 @@ bool basic_valid(const compams_config* c) {
 
 // Top-k inside every block: the shape of one block's selection problem and how many workgroups it gets.
 struct BlockShape {
-  uint32_t off, d, k, nc, cap, cpw, groups_first, groups_sweep, count_blocks, emit_slots, micro;
+  uint32_t off, d, k, nc, cap, cpw, groups_first, groups_level0, groups_sweep, count_blocks, emit_slots, micro;
 };
 
 std::vector<BlockShape> block_shapes(const compams_config* c) {
@@ -115,17 +115,18 @@ std::vector<BlockShape> block_shapes(const compams_config* c) {
     s.micro = s.d <= kMicroCoords ? 1u : 0u;
     chunks_per_worker += s.nc;
   }
-  // about 2048 workgroups in the first pass (blocks differ in size by orders of magnitude: small pieces, handed
-  // out largest first, are what keeps the compute units evenly busy; measured on MI355X) and in the sweeps over
-  // all workers, at least one per problem
+  // the first pass takes a workgroup per chunk; about 512 workgroups find the threshold buckets and 2048 make the
+  // sweeps over all workers, at least one per problem
   const uint64_t all = chunks_per_worker * static_cast<uint64_t>(c->n);
-  const uint32_t per_first = static_cast<uint32_t>(std::max<uint64_t>(8, (all + 2047) / 2048));
+  const uint32_t per_level0 = static_cast<uint32_t>(std::max<uint64_t>(8, (all + 511) / 512));
   const uint32_t per_sweep = static_cast<uint32_t>(std::max<uint64_t>(4, (all + 2047) / 2048));
   for (BlockShape& s : v) {
     const uint32_t most = (s.nc + kWaves - 1) / kWaves;  // one chunk per wavefront at least
-    s.groups_first = std::max<uint32_t>(1, std::min<uint32_t>(most, (s.nc + per_first / 2) / per_first));
+    s.groups_first = s.nc;
+    s.groups_level0 = std::max<uint32_t>(1, std::min<uint32_t>(most, (s.nc + per_level0 / 2) / per_level0));
     s.groups_sweep = std::max<uint32_t>(1, std::min<uint32_t>(most, (s.nc + per_sweep / 2) / per_sweep));
-    if (s.micro) s.groups_first = s.groups_sweep = s.count_blocks = 0;  // a wavefront of a shared workgroup instead
+    // a micro problem is a wavefront of a shared workgroup of the first pass instead
+    if (s.micro) s.groups_first = s.groups_level0 = s.groups_sweep = s.count_blocks = 0;
   }
   return v;
 }
@@ -166,17 +167,18 @@ Layout make_layout(const compams_config* c) {
   } else if (c->compressor == COMPAMS_TOPK_BLOCKS) {
     const std::vector<BlockShape> shapes = block_shapes(c);
     const size_t M = shapes.size(), S = n * M;
-    size_t k = 0, chunks = 0, caps = 0, wg_first = 0, wg_sweep = 0, wg_count = 0, wg_emit = 0, micro = 0;
+    size_t k = 0, chunks = 0, caps = 0, wg_first = 0, wg_level0 = 0, wg_sweep = 0, wg_count = 0, wg_emit = 0, micro = 0;
     uint32_t cap_max = 0;
     for (const BlockShape& b : shapes) {
       k += b.k; chunks += b.nc; caps += b.cap; cap_max = std::max(cap_max, b.cap);
-      wg_first += b.groups_first; wg_sweep += b.groups_sweep; wg_count += b.count_blocks; wg_emit += b.emit_slots;
+      wg_first += b.groups_first; wg_level0 += b.groups_level0; wg_sweep += b.groups_sweep; wg_count += b.count_blocks; wg_emit += b.emit_slots;
       micro += b.micro;
     }
     L.k_total = k;
     L.cap_alloc = cap_max;
     L.num_micro = n * micro;
     L.flat.wg_first = static_cast<uint32_t>(n * wg_first + (n * micro + kWaves - 1) / kWaves);
+    L.flat.wg_level0 = static_cast<uint32_t>(n * wg_level0);
     L.flat.wg_sweep = static_cast<uint32_t>(n * wg_sweep);
     L.flat.wg_count = static_cast<uint32_t>(n * wg_count);
     L.flat.wg_emit = static_cast<uint32_t>(n * wg_emit);
@@ -206,6 +208,7 @@ Layout make_layout(const compams_config* c) {
     L.sel_off_srv = take(n * (nc + 1) * 4);
     L.segs = take(S * sizeof(Seg));
     L.map_first = take(L.flat.wg_first * sizeof(WgSlot));
+    L.map_level0 = take(L.flat.wg_level0 * sizeof(WgSlot));
     L.map_sweep = take(L.flat.wg_sweep * sizeof(WgSlot));
     L.map_count = take(L.flat.wg_count * sizeof(WgSlot));
     L.map_emit = take(L.flat.wg_emit * sizeof(WgSlot));
@@ -363,14 +366,14 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     ctx->tkopt.predict = 1;
     ctx->tkopt.force_dense = 0;
     t.sel_off_srv = reinterpret_cast<uint32_t*>(w + lay.sel_off_srv);
-    t.segs = nullptr; t.map_first = t.map_sweep = t.map_count = t.map_emit = t.map_final = nullptr; t.micro_list = nullptr;
+    t.segs = nullptr; t.map_first = t.map_level0 = t.map_sweep = t.map_count = t.map_emit = t.map_final = nullptr; t.micro_list = nullptr;
     // control blocks, counters, histograms and chunk tables start at zero; lists need no initial value
     ok(fill_u32(reinterpret_cast<uint32_t*>(w), lay.cand / 4, 0u, s0));
     ok(fill_u32(reinterpret_cast<uint32_t*>(w + lay.idx), (lay.total - lay.idx) / 4, 0u, s0));
     if (cfg->compressor == COMPAMS_TOPK_BLOCKS) {
       // the segments (worker-major: worker i, block b is segment i * M + b) and the workgroups of the flat launches
       std::vector<Seg> segs;
-      std::vector<WgSlot> m_first, m_sweep, m_count, m_emit, m_final;
+      std::vector<WgSlot> m_first, m_level0, m_sweep, m_count, m_emit, m_final;
       std::vector<uint32_t> micro;
       try {
         const std::vector<BlockShape> shapes = block_shapes(cfg);
@@ -394,8 +397,10 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
             sg.count_cpw = sh.cpw;
             sg.groups_first = sh.groups_first; sg.groups_sweep = sh.groups_sweep; sg.count_blocks = sh.count_blocks;
             sg.micro = sh.micro;
+            sg.groups_level0 = sh.groups_level0;
             if (sh.micro) micro.push_back(si);
-            for (uint32_t q = 0; q < sh.groups_first; ++q) m_first.push_back(WgSlot{si, q});
+            for (uint32_t q = 0; q < sh.groups_first; ++q) m_first.push_back(WgSlot{si, q});  // in address order
+            for (uint32_t q = 0; q < sh.groups_level0; ++q) m_level0.push_back(WgSlot{si, q});
             for (uint32_t q = 0; q < sh.groups_sweep; ++q) m_sweep.push_back(WgSlot{si, q});
             for (uint32_t q = 0; q < sh.count_blocks; ++q) m_count.push_back(WgSlot{si, q});
             for (uint32_t q = 0; q < sh.emit_slots; ++q) m_emit.push_back(WgSlot{si, q * static_cast<uint32_t>(kWaves)});
@@ -404,11 +409,6 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
             c_at += sh.nc; cap_at += sh.cap; k_at += sh.k;
           }
         }
-        // the first pass hands out its workgroups in launch order: the longest ones first
-        auto work = [&](const WgSlot& a) {
-          return (segs[a.seg].num_chunks + segs[a.seg].groups_first - 1) / segs[a.seg].groups_first;
-        };
-        std::stable_sort(m_first.begin(), m_first.end(), [&](const WgSlot& a, const WgSlot& b) { return work(a) > work(b); });
         // and last of all the workgroups whose wavefronts take one micro problem each
         for (size_t q = 0; q < micro.size(); q += kWaves)
           m_first.push_back(WgSlot{kMicroFlag | static_cast<uint32_t>(q),
@@ -417,16 +417,19 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
       ok(hipStreamSynchronize(s0));
       ok(hipMemcpy(w + lay.segs, segs.data(), segs.size() * sizeof(Seg), hipMemcpyHostToDevice));
       ok(hipMemcpy(w + lay.map_first, m_first.data(), m_first.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
+      if (!m_level0.empty())
+        ok(hipMemcpy(w + lay.map_level0, m_level0.data(), m_level0.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
       ok(hipMemcpy(w + lay.map_sweep, m_sweep.data(), m_sweep.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
       ok(hipMemcpy(w + lay.map_count, m_count.data(), m_count.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
       ok(hipMemcpy(w + lay.map_emit, m_emit.data(), m_emit.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
       ok(hipMemcpy(w + lay.map_final, m_final.data(), m_final.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
       if (!micro.empty()) ok(hipMemcpy(w + lay.micro_list, micro.data(), micro.size() * 4, hipMemcpyHostToDevice));
-      if (m_first.size() != lay.flat.wg_first || m_sweep.size() != lay.flat.wg_sweep || m_count.size() != lay.flat.wg_count ||
+      if (m_first.size() != lay.flat.wg_first || m_level0.size() != lay.flat.wg_level0 || m_sweep.size() != lay.flat.wg_sweep || m_count.size() != lay.flat.wg_count ||
           m_emit.size() != lay.flat.wg_emit || m_final.size() != lay.flat.wg_final || micro.size() != lay.num_micro)
         ok(hipErrorInvalidValue);  // the tables and the launch sizes come from the same shapes
       t.segs = reinterpret_cast<const Seg*>(w + lay.segs);
       t.map_first = reinterpret_cast<const WgSlot*>(w + lay.map_first);
+      t.map_level0 = reinterpret_cast<const WgSlot*>(w + lay.map_level0);
       t.map_sweep = reinterpret_cast<const WgSlot*>(w + lay.map_sweep);
       t.map_count = reinterpret_cast<const WgSlot*>(w + lay.map_count);
       t.map_emit = reinterpret_cast<const WgSlot*>(w + lay.map_emit);

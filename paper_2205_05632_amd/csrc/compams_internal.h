@@ -86,9 +86,11 @@ struct Seg {
   uint32_t cap;          // capacity of the candidate list
   uint32_t coord_base;   // coordinate of the first element within the worker's row
   uint32_t count_cpw;    // chunks per block of the counting kernel
-  uint32_t groups_first, groups_sweep, count_blocks;  // workgroups the three kernel classes give this segment
+  uint32_t groups_first, groups_sweep, count_blocks;  // workgroups the kernel classes give this segment (first pass:
+                                                      // one per chunk)
   uint32_t micro;        // at most kMicroCoords coordinates: one wavefront of the first pass does the whole selection
-  uint32_t pad[2];
+  uint32_t groups_level0;
+  uint32_t pad[1];
 };
 static_assert(sizeof(Seg) == 88 || sizeof(Seg) == 96, "Seg layout");
 
@@ -125,7 +127,8 @@ struct TopkWorkspace {
   uint32_t* tau;        // n
   // top-k inside every block only: the segments and, per kernel class, the workgroups of a flat launch
   const Seg* segs;
-  const WgSlot* map_first;
+  const WgSlot* map_first;   // first pass: .group = chunk of the segment (or a workgroup of micro problems, see below)
+  const WgSlot* map_level0;
   const WgSlot* map_sweep;
   const WgSlot* map_count;
   const WgSlot* map_emit;   // .group = first chunk of the four that the workgroup's wavefronts take
@@ -197,7 +200,7 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
                      Launcher* L);
 // Sizes of the flat launches of top-k inside every block.
 struct TopkFlat {
-  uint32_t wg_first, wg_sweep, wg_count, wg_emit, wg_final;
+  uint32_t wg_first, wg_level0, wg_sweep, wg_count, wg_emit, wg_final;
   // from worker i's segment of a block to worker i + 1's: segment index, chunk tables, list offsets, candidates
   uint32_t blocks, chunk_stride, seloff_stride;
   uint64_t cand_stride;

@@ -388,220 +388,12 @@ __device__ __forceinline__ void micro_problem(const float* __restrict__ g, float
 }
 
 // ---------------------------------------------------------------------------------------------
-// Kernel 1: first pass.  Grid (groups, n); each wavefront walks chunks wave, wave + stride, ...
-//   PRED: rows with a valid guess also emit candidates and level-1 histograms of buckets guess, guess+1.
-//   PEND: coordinates selected in the previous step still hold their old value in e and count as zero.
-// ---------------------------------------------------------------------------------------------
-constexpr int kBatch = 4;  // rounds whose loads are in flight together
-constexpr int kWGA = 256;  // threads per workgroup of the first pass
-constexpr int kWavesA = kWGA / 64;
-
-struct Batch {
-  float4 g[kBatch], e[kBatch];
-};
-
-template <bool FULL>
-__device__ __forceinline__ void load_batch(Batch& b, const float* __restrict__ gr, const float* __restrict__ er,
-                                           uint32_t base, int r0, uint32_t d) {
-#pragma unroll
-  for (int u = 0; u < kBatch; ++u) {
-    const uint32_t j = base + (r0 + u) * 256;
-    b.g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-    b.e[u] = b.g[u];
-    if (FULL || j < d) {
-      b.g[u] = load_stream4(gr + j);
-      b.e[u] = load_stream4(er + j);
-    }
-  }
-}
-
-// What one wavefront carries through its walk over chunks.
-struct PassA {
-  const float* gr;
-  float* er;
-  uint32_t d;
-  uint32_t* lh;          // level-0 histogram of the workgroup (LDS)
-  uint32_t* lh1;         // level-1 histograms of the tracked buckets (LDS)
-  uint2* stage;          // this wavefront's staging area (LDS)
-  uint32_t* bm;          // this wavefront's bit map of pending zeros (LDS, 128 words)
-  bool pred;
-  uint32_t bg;
-  TopkRow* rowp;
-  uint2* candr;
-  uint32_t cap;
-  uint2* descr;
-  const uint32_t* prev_off;
-  const int32_t* prev_idx;  // coordinates within the worker's row
-  uint32_t coord_base;      // the row coordinate of this problem's first element
-  uint32_t k;
-  uint32_t zeros;        // zero keys seen (added to bin 0 at the end)
-};
-
-// The first 128 entries of a chunk's slice of the previous step's list, requested ahead of time.
-struct PendAhead {
-  uint32_t lo, hi;
-  uint32_t j0, j1;
-};
-
-__device__ __forceinline__ void pend_request(PendAhead& pa, const PassA& A, uint32_t c) {
-  const uint32_t lane = lane_id();
-  pa.lo = A.prev_off[c];
-  pa.hi = A.prev_off[c + 1] < A.k ? A.prev_off[c + 1] : A.k;
-  pa.j0 = pa.lo + lane < pa.hi ? static_cast<uint32_t>(A.prev_idx[pa.lo + lane]) : 0xffffffffu;
-  pa.j1 = pa.lo + 64 + lane < pa.hi ? static_cast<uint32_t>(A.prev_idx[pa.lo + 64 + lane]) : 0xffffffffu;
-}
-
-// Bit map of the chunk's coordinates that were selected in the previous step (their residual is zero).
-__device__ __forceinline__ void pend_build(const PendAhead& pa, const PassA& A, uint32_t c) {
-  const uint32_t lane = lane_id();
-  A.bm[lane] = 0;
-  A.bm[lane + 64] = 0;
-  const uint32_t a = pa.j0 - A.coord_base - c * kChunk, b = pa.j1 - A.coord_base - c * kChunk;
-  if (a < static_cast<uint32_t>(kChunk)) atomicOr(&A.bm[a >> 5], 1u << (a & 31u));
-  if (b < static_cast<uint32_t>(kChunk)) atomicOr(&A.bm[b >> 5], 1u << (b & 31u));
-  for (uint32_t q = pa.lo + 128 + lane; q < pa.hi; q += 64) {  // dense chunks only
-    const uint32_t jl = static_cast<uint32_t>(A.prev_idx[q]) - A.coord_base - c * kChunk;
-    if (jl < static_cast<uint32_t>(kChunk)) atomicOr(&A.bm[jl >> 5], 1u << (jl & 31u));
-  }
-}
-
-// One round (256 coordinates) of the first pass: x = e + g (pending zeros honoured), store, histogram,
-// candidate staging.  cnt is the running number of staged candidates of the chunk.
-template <bool PRED, bool PEND, bool FULL>
-__device__ __forceinline__ void pass_a_round(PassA& A, uint32_t j, int r, const float4& gv, const float4& e_in,
-                                             uint32_t& cnt) {
-  const uint32_t lane = lane_id();
-  const bool in = FULL || j < A.d;
-  float4 ev = e_in;
-  if constexpr (PEND) {
-    const uint32_t nib = (A.bm[r * 8 + (lane >> 3)] >> ((lane & 7u) * 4u)) & 15u;
-    if (nib & 1u) ev.x = 0.0f;
-    if (nib & 2u) ev.y = 0.0f;
-    if (nib & 4u) ev.z = 0.0f;
-    if (nib & 8u) ev.w = 0.0f;
-  }
-  float4 x = make_float4(ev.x + gv.x, ev.y + gv.y, ev.z + gv.z, ev.w + gv.w);
-  Quad q;
-  q.ok[0] = in; q.ok[1] = FULL || j + 1 < A.d; q.ok[2] = FULL || j + 2 < A.d; q.ok[3] = FULL || j + 3 < A.d;
-  if (!FULL) {  // columns >= d keep what they held
-    if (!q.ok[1]) x.y = e_in.y;
-    if (!q.ok[2]) x.z = e_in.z;
-    if (!q.ok[3]) x.w = e_in.w;
-  }
-  if (in) store_stream4(A.er + j, x);
-  const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)};
-#pragma unroll
-  for (int s = 0; s < 4; ++s) q.key[s] = key_of_bits(bits[s]);
-  hist4<FULL>(A.lh, q, A.zeros);
-  if constexpr (PRED) {
-    if (A.pred) {
-      // candidates (bucket >= guess): staged in coordinate order; those in the tracked buckets also go
-      // into the level-1 histograms
-      bool flag[4];
-      uint64_t mk[4];
-      uint32_t total = 0;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        flag[s] = q.ok[s] && (q.key[s] >> kL0Shift) >= A.bg;
-        mk[s] = ballot64(flag[s]);
-        total += popc64(mk[s]);
-      }
-      if (total) {
-        uint32_t pos = cnt + count_below(mk[0]) + count_below(mk[1]) + count_below(mk[2]) + count_below(mk[3]);
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-          if (flag[s]) {
-            if (pos < static_cast<uint32_t>(kStage)) A.stage[pos] = make_uint2(j + s, bits[s]);
-            ++pos;
-            const uint32_t rel = (q.key[s] >> kL0Shift) - A.bg;
-            if (rel < kTracked) atomicAdd(&A.lh1[rel * kNB1 + ((q.key[s] >> kL1Shift) & (kNB1 - 1))], 1u);
-          }
-        cnt += total;
-      }
-    }
-  }
-}
-
-// A wavefront's walk over its chunks (c = first, first + stride, ...).  Loads run one batch of kBatch
-// rounds ahead of the arithmetic, across chunk boundaries too, so that the round trip of a chunk's
-// segment allocation (an atomic with return) and of the look-up of pending zeros never leaves the
-// wavefront without loads in flight.
-template <bool PRED, bool PEND>
-__device__ __forceinline__ void pass_a_walk(PassA& A, uint32_t first, uint32_t stride, uint32_t num_chunks) {
-  const uint32_t lane = lane_id();
-  const uint32_t nfull = A.d / kChunk;  // whole chunks
-  uint32_t c = first;
-  Batch cur;
-  PendAhead pa;
-  // the previous chunk's segment: requested, not yet written (its staging buffer is the other one)
-  bool p_have = false;
-  uint32_t p_raw = 0, p_cnt = 0, p_c = 0;
-  uint2* const stage0 = A.stage;
-  uint32_t buf = 0;
-  if (c < nfull) {
-    load_batch<true>(cur, A.gr, A.er, c * kChunk + lane * 4, 0, A.d);
-    if constexpr (PEND) pend_request(pa, A, c);
-  }
-  while (c < nfull) {
-    const uint32_t cn = c + stride;
-    const bool more = cn < nfull;
-    const uint32_t base = c * kChunk + lane * 4;
-    if constexpr (PEND) pend_build(pa, A, c);
-    A.stage = stage0 + buf * kStage;
-    uint32_t cnt = 0;
-#pragma unroll 1
-    for (int r0 = 0; r0 < kRounds; r0 += kBatch) {
-      Batch nxt;
-      if (r0 + kBatch < kRounds) load_batch<true>(nxt, A.gr, A.er, base, r0 + kBatch, A.d);
-      else if (more) load_batch<true>(nxt, A.gr, A.er, cn * kChunk + lane * 4, 0, A.d);
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u)
-        pass_a_round<PRED, PEND, true>(A, base + (r0 + u) * 256, r0 + u, cur.g[u], cur.e[u], cnt);
-      cur = nxt;
-    }
-    if constexpr (PEND)
-      if (more) pend_request(pa, A, cn);
-    if constexpr (PRED) {
-      if (A.pred) {
-        // request this chunk's segment now, write the previous chunk's (whose request returned long ago)
-        const uint32_t raw = segment_request(A.rowp, cnt);
-        if (p_have)
-          segment_write(p_raw, stage0 + (buf ^ 1u) * kStage, p_cnt, A.er, A.d, p_c, A.bg, A.candr, A.cap, A.descr);
-        p_have = true; p_raw = raw; p_cnt = cnt; p_c = c;
-        buf ^= 1u;
-      }
-    }
-    c = cn;
-  }
-  if constexpr (PRED)
-    if (p_have) segment_write(p_raw, stage0 + (buf ^ 1u) * kStage, p_cnt, A.er, A.d, p_c, A.bg, A.candr, A.cap, A.descr);
-  A.stage = stage0;
-  if (c == nfull && nfull < num_chunks) {  // the row's last, partial chunk
-    const uint32_t base = c * kChunk + lane * 4;
-    if constexpr (PEND) {
-      pend_request(pa, A, c);
-      pend_build(pa, A, c);
-    }
-    uint32_t cnt = 0;
-#pragma unroll 1
-    for (int r0 = 0; r0 < kRounds; r0 += kBatch) {
-      load_batch<false>(cur, A.gr, A.er, base, r0, A.d);
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u)
-        pass_a_round<PRED, PEND, false>(A, base + (r0 + u) * 256, r0 + u, cur.g[u], cur.e[u], cnt);
-    }
-    if constexpr (PRED)
-      if (A.pred) flush_chunk(A.stage, cnt, A.er, A.d, c, A.bg, A.rowp, A.candr, A.cap, A.descr);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
 // Which selection problem a workgroup works on.  UNI: one problem per worker row, all of one shape, grid
 // (groups, rows): everything follows from the block indices.  Otherwise the launch is flat and tables say
 // which segment (a block of a worker's row) and which of its workgroups this is; geo and opt are then
 // narrowed to the segment's own shape.
 // ---------------------------------------------------------------------------------------------
-enum : int { kClassFirst = 0, kClassSweep = 1, kClassCount = 2 };
+enum : int { kClassFirst = 0, kClassSweep = 1, kClassCount = 2, kClassLevel0 = 3 };
 
 struct SegCtx {
   uint32_t seg;     // index into the per-problem tables (control blocks, histograms, thresholds)
@@ -626,11 +418,15 @@ __device__ __forceinline__ SegCtx seg_ctx(Geometry& geo, TopkOptions& opt, const
     c.cand_base = static_cast<size_t>(c.seg) * opt.cap;
     c.list_base = static_cast<size_t>(c.seg) * geo.k;
   } else {
-    const WgSlot slot = (CLASS == kClassFirst ? ws.map_first : (CLASS == kClassSweep ? ws.map_sweep : ws.map_count))[blockIdx.x];
+    const WgSlot slot = (CLASS == kClassFirst ? ws.map_first
+                         : CLASS == kClassLevel0 ? ws.map_level0
+                         : CLASS == kClassSweep ? ws.map_sweep : ws.map_count)[blockIdx.x];
     const Seg sg = ws.segs[slot.seg];
     c.seg = slot.seg;
     c.group = slot.group;
-    c.groups = CLASS == kClassFirst ? sg.groups_first : (CLASS == kClassSweep ? sg.groups_sweep : sg.count_blocks);
+    c.groups = CLASS == kClassFirst ? sg.groups_first
+               : CLASS == kClassLevel0 ? sg.groups_level0
+               : CLASS == kClassSweep ? sg.groups_sweep : sg.count_blocks;
     c.elem_off = sg.elem_off;
     c.coord_base = sg.coord_base;
     c.chunk_base = sg.chunk_base;
@@ -644,123 +440,6 @@ __device__ __forceinline__ SegCtx seg_ctx(Geometry& geo, TopkOptions& opt, const
     opt.cap = opt.cap < sg.cap ? opt.cap : sg.cap;
   }
   return c;
-}
-
-template <bool PRED, bool PEND, bool UNI>
-__global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ g, float* __restrict__ e,
-                                                      Geometry geo, TopkWorkspace ws, TopkOptions opt) {
-  __shared__ uint32_t lh[kNB0];
-  __shared__ uint32_t lh1[PRED ? kTracked * kNB1 : 1];
-  __shared__ uint2 stage_all[PRED ? kWavesA * 2 * kStage : 1];
-  __shared__ uint32_t bm_all[PEND ? kWavesA * 128 : 1];
-  __shared__ uint32_t suf[kWGA + 1];
-  __shared__ uint32_t out2[2];
-  __shared__ uint32_t sh_flag, sh_l1, sh_bstar, sh_need;
-  if constexpr (!UNI) {
-    const WgSlot slot = ws.map_first[blockIdx.x];
-    if (slot.seg & kMicroFlag) {  // workgroup-uniform: up to four micro problems, one per wavefront
-      const uint32_t w = threadIdx.x >> 6;
-      if (w < slot.group) {
-        const uint32_t seg = ws.micro_list[(slot.seg & ~kMicroFlag) + w];
-        const Seg sg = ws.segs[seg];
-        micro_problem<PEND>(g, e, sg, seg, ws, bm_all + (PEND ? w * 128 : 0));
-      }
-      return;
-    }
-  }
-  const SegCtx sc = seg_ctx<UNI, kClassFirst>(geo, opt, ws);
-  const uint32_t row = sc.seg;
-  for (int b = threadIdx.x; b < kNB0; b += kWGA) lh[b] = 0;
-  if (PRED)
-    for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWGA) lh1[b] = 0;
-  __syncthreads();
-  const float* gr = g + sc.elem_off;
-  float* er = e + sc.elem_off;
-  TopkRow* rowp = ws.rows + row;
-  bool pred = false;
-  uint32_t bg = 0;
-  if (PRED) {
-    pred = rowp->pred_valid != 0;
-    bg = rowp->b_guess;
-  }
-  uint2* candr = ws.cand + sc.cand_base;
-  uint2* descr = ws.desc + sc.chunk_base;
-  const uint32_t* prev_off = ws.sel_off + sc.seloff_base;
-  const int32_t* prev_idx = ws.idx + sc.list_base;
-  const uint32_t wave = threadIdx.x >> 6;
-  uint2* stage = stage_all + (PRED ? wave * 2 * kStage : 0);
-  uint32_t* bm = bm_all + (PEND ? wave * 128 : 0);
-  PassA A;
-  A.gr = gr; A.er = er; A.d = geo.d; A.lh = lh; A.lh1 = lh1; A.stage = stage; A.bm = bm; A.pred = pred; A.bg = bg;
-  A.rowp = rowp; A.candr = candr; A.cap = opt.cap; A.descr = descr; A.prev_off = prev_off; A.prev_idx = prev_idx;
-  A.k = geo.k; A.zeros = 0; A.coord_base = sc.coord_base;
-  pass_a_walk<PRED, PEND>(A, sc.group * kWavesA + wave, sc.groups * kWavesA, geo.num_chunks);
-  const uint32_t zeros = A.zeros;
-  if (zeros && lane_id() == 0) atomicAdd(&lh[0], zeros);
-  __syncthreads();
-  uint32_t* gh = ws.hist0 + static_cast<size_t>(row) * kNB0;
-  for (int b = threadIdx.x; b < kNB0; b += kWGA) {
-    const uint32_t h = lh[b];
-    if (h) atomicAdd(&gh[b], h);
-  }
-  uint32_t* gh1 = ws.hist1x + static_cast<size_t>(row) * kTracked * kNB1;
-  if (PRED && pred)
-    for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWGA) {
-      const uint32_t h = lh1[b];
-      if (h) atomicAdd(&gh1[b], h);
-    }
-
-  // ---- row-wide part, by whichever workgroup of the row finishes last ----
-  if (!last_group_of_row(&rowp->ticket[0], sc.groups, &sh_flag)) return;
-  take_hist<kNB0, kWGA>(gh, lh);
-  find_crossing<kNB0, kWGA>(lh, geo.k, suf, out2);
-  if (threadIdx.x == 0) {
-    const uint32_t bstar = out2[0], above = out2[1];
-    const uint32_t total = above + lh[bstar];  // entries with bucket >= bstar
-    const uint32_t cursor = load_agent(&rowp->cursor);
-    const bool pred_ok = PRED && pred && bstar >= bg && cursor <= opt.cap && !opt.force_dense;
-    uint32_t mode, n_src, reads;
-    if (pred_ok) { mode = kModeCand; n_src = cursor; reads = 0; }
-    else if (total <= opt.cap && !opt.force_dense) { mode = kModeNeedB; n_src = total; reads = 1; }
-    else { mode = kModeDense; n_src = 0; reads = 4; }
-    rowp->mode = mode;
-    rowp->n_src = n_src;
-    rowp->cursor = 0;
-    rowp->bstar = bstar;
-    rowp->need = geo.k - above;
-    rowp->level1_done = 0;
-    // Guess for the next step: one bucket below this step's threshold bucket if the list that guess would
-    // have produced now fits with room to spare, else the bucket itself, else no guess.
-    uint32_t valid = 0, guess = 0;
-    if (opt.predict && !opt.force_dense) {
-      const uint32_t below = bstar ? lh[bstar - 1] : 0;
-      if (bstar && total + below <= opt.cap / 2) { valid = 1; guess = bstar - 1; }
-      else if (total <= opt.cap / 2) { valid = 1; guess = bstar; }
-    }
-    rowp->pred_valid = valid;
-    rowp->b_guess = guess;
-    uint32_t* cn = ws.counters + row * 4;
-    cn[0] = reads;
-    cn[1] = n_src;
-    sh_l1 = (pred_ok && bstar - bg < kTracked) ? 1u + (bstar - bg) : 0u;
-    sh_bstar = bstar;
-    sh_need = geo.k - above;
-  }
-  __syncthreads();
-  if (PRED && pred) {
-    const uint32_t which = sh_l1;  // 0: level 1 not available; 1 + t: histogram of bucket guess + t
-    if (which) {
-      const AgentView view = agent_view(gh1 + (which - 1) * kNB1, kNB1);
-      uint32_t x[kNB1 / kWGA];
-#pragma unroll
-      for (int i = 0; i < kNB1 / kWGA; ++i) x[i] = load_agent(view, i * kWGA + threadIdx.x);
-#pragma unroll
-      for (int i = 0; i < kNB1 / kWGA; ++i) lh[i * kWGA + threadIdx.x] = x[i];
-    }
-    for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWGA) gh1[b] = 0;
-    __syncthreads();
-    if (which) resolve_level1<kWGA>(rowp, sh_bstar, sh_need, lh, suf, out2);
-  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -777,16 +456,31 @@ __global__ __launch_bounds__(kWGA) void k_topk_pass_a(const float* __restrict__ 
 constexpr int kLeanRounds = kRounds / kWaves;  // rounds of a chunk per wavefront
 constexpr int kStageQ = 512;                   // staged candidates per wavefront (of at most 1024 coordinates)
 
-template <bool PEND>
+// UNI: grid (chunks, rows).  Otherwise (top-k inside every block) the launch is flat over map_first: a workgroup
+// per chunk of every segment in address order, and at the end the workgroups whose wavefronts take one micro
+// problem each; coordinates below are the segment's own, the lists hold coordinates of the worker's row.
+template <bool PEND, bool UNI>
 __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
                                                     TopkWorkspace ws, TopkOptions opt, uint32_t use_guess) {
   __shared__ uint2 stage_all[kWaves * kStageQ];
   __shared__ uint32_t bm_all[PEND ? kWaves * 32 : 1];
   __shared__ uint32_t sh_cnt[kWaves], sh_off;
-  const uint32_t c = blockIdx.x, row = blockIdx.y;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const float* gr = g + static_cast<int64_t>(row) * geo.ld;
-  float* er = e + static_cast<int64_t>(row) * geo.ld;
+  if constexpr (!UNI) {
+    const WgSlot slot = ws.map_first[blockIdx.x];
+    if (slot.seg & kMicroFlag) {  // workgroup-uniform: up to four micro problems, one per wavefront
+      if (wave < slot.group) {
+        const uint32_t seg = ws.micro_list[(slot.seg & ~kMicroFlag) + wave];
+        const Seg sg = ws.segs[seg];
+        micro_problem<PEND>(g, e, sg, seg, ws, bm_all + (PEND ? wave * 32 : 0));
+      }
+      return;
+    }
+  }
+  const SegCtx sc = seg_ctx<UNI, kClassFirst>(geo, opt, ws);
+  const uint32_t c = sc.group, row = sc.seg;
+  const float* gr = g + sc.elem_off;
+  float* er = e + sc.elem_off;
   TopkRow* rowp = ws.rows + row;
   const bool pred = use_guess && rowp->pred_valid != 0;  // workgroup-uniform
   const uint32_t bg = rowp->b_guess;
@@ -808,12 +502,12 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   if constexpr (PEND) {
     // the quarter's coordinates that were selected in the previous step: their residual counts as zero
     if (lane < 32) bm[lane] = 0;
-    const uint32_t* prev_off = ws.sel_off + static_cast<size_t>(row) * (geo.num_chunks + 1);
-    const int32_t* prev_idx = ws.idx + static_cast<size_t>(row) * geo.k;
+    const uint32_t* prev_off = ws.sel_off + sc.seloff_base;
+    const int32_t* prev_idx = ws.idx + sc.list_base;
     const uint32_t lo = prev_off[c];
     const uint32_t hi = prev_off[c + 1] < geo.k ? prev_off[c + 1] : geo.k;
     for (uint32_t q = lo + lane; q < hi; q += 64) {
-      const uint32_t jl = static_cast<uint32_t>(prev_idx[q]) - q0;
+      const uint32_t jl = static_cast<uint32_t>(prev_idx[q]) - sc.coord_base - q0;
       if (jl < static_cast<uint32_t>(kLeanRounds * 256)) atomicOr(&bm[jl >> 5], 1u << (jl & 31u));
     }
   }
@@ -870,12 +564,12 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   if (threadIdx.x == 0) {
     const uint32_t off = total ? atomicAdd(&rowp->cursor, total) : 0u;
     sh_off = off;
-    ws.desc[static_cast<size_t>(row) * geo.num_chunks + c] = make_uint2(off, total);
+    ws.desc[sc.chunk_base + c] = make_uint2(off, total);
   }
   __syncthreads();
   const uint32_t off = sh_off;
   if (cnt == 0 || off + total > opt.cap) return;  // otherwise the row's list has overflowed and will not be used
-  uint2* dst = ws.cand + static_cast<size_t>(row) * opt.cap + off + before;
+  uint2* dst = ws.cand + sc.cand_base + off + before;
   if (cnt <= static_cast<uint32_t>(kStageQ)) {
     for (uint32_t q = lane; q < cnt; q += 64) dst[q] = stage[q];
   } else {
@@ -911,6 +605,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
 // workgroup of the row finds the threshold bucket, decides the route of the remaining kernels and leaves the
 // guess for the next step.
 // ---------------------------------------------------------------------------------------------
+template <bool UNI>
 __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                       TopkOptions opt, uint32_t use_guess) {
   __shared__ uint32_t lh[kNB0];
@@ -918,7 +613,8 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
   __shared__ uint32_t suf[kWG + 1];
   __shared__ uint32_t out2[2];
   __shared__ uint32_t sh_flag, sh_l1, sh_bstar, sh_need;
-  const uint32_t row = blockIdx.y;
+  const SegCtx sc = seg_ctx<UNI, kClassLevel0>(geo, opt, ws);
+  const uint32_t row = sc.seg;
   TopkRow* rowp = ws.rows + row;
   const uint32_t bg = rowp->b_guess;
   const uint32_t cursor = rowp->cursor;  // written by the previous launch
@@ -928,9 +624,9 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
   __syncthreads();
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   if (listed) {
-    const uint2* candr = ws.cand + static_cast<size_t>(row) * opt.cap;
-    const uint32_t step = gridDim.x * kWG;
-    for (uint32_t q = blockIdx.x * kWG + threadIdx.x; q < cursor; q += 4 * step) {  // four loads in flight
+    const uint2* candr = ws.cand + sc.cand_base;
+    const uint32_t step = sc.groups * kWG;
+    for (uint32_t q = sc.group * kWG + threadIdx.x; q < cursor; q += 4 * step) {  // four loads in flight
       uint32_t key[4];
       bool ok[4];
 #pragma unroll
@@ -948,10 +644,10 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
         }
     }
   } else {
-    const float* er = e + static_cast<int64_t>(row) * geo.ld;
+    const float* er = e + sc.elem_off;
     uint32_t zeros = 0;
-    const uint32_t stride = gridDim.x * kWaves;
-    for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
+    const uint32_t stride = sc.groups * kWaves;
+    for (uint32_t c = sc.group * kWaves + wave; c < geo.num_chunks; c += stride) {
       const uint32_t base = c * kChunk + lane * 4;
 #pragma unroll 4
       for (int r = 0; r < kRounds; ++r) {
@@ -982,7 +678,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
       if (h) atomicAdd(&gh1[b], h);
     }
   // ---- row-wide part, by whichever workgroup of the row finishes last ----
-  if (!last_group_of_row(&rowp->ticket[0], gridDim.x, &sh_flag)) return;
+  if (!last_group_of_row(&rowp->ticket[0], sc.groups, &sh_flag)) return;
   take_hist<kNB0>(gh, lh);
   find_crossing<kNB0>(lh, geo.k, suf, out2);
   if (threadIdx.x == 0) {
@@ -1741,15 +1437,17 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   const dim3 grid_rows(G, geo.n), wg(kWG);
   const uint32_t use_guess = first_pass_may_predict ? 1u : 0u;
   const dim3 grid_chunks(geo.num_chunks, geo.n);
-  if (clear_pending) launch(L, kSlotPassA, k_topk_lean<true>, grid_chunks, wg, stream, g, e, geo, ws, opt, use_guess);
-  else launch(L, kSlotPassA, k_topk_lean<false>, grid_chunks, wg, stream, g, e, geo, ws, opt, use_guess);
+  if (clear_pending)
+    launch(L, kSlotPassA, k_topk_lean<true, true>, grid_chunks, wg, stream, g, e, geo, ws, opt, use_guess);
+  else
+    launch(L, kSlotPassA, k_topk_lean<false, true>, grid_chunks, wg, stream, g, e, geo, ws, opt, use_guess);
   COMPAMS_CHECK_LAUNCH();
   {
     // about two workgroups per compute unit over all rows: each clears and flushes a whole histogram, and the
     // lists are short (measured on the headline workload: 37 us with 128 workgroups per row, 23 us with 32)
     uint32_t g0 = (512 + geo.n - 1) / geo.n;
     g0 = g0 > G ? G : g0;
-    launch(L, kSlotLevel0, k_topk_level0, dim3(g0, geo.n), wg, stream, e, geo, ws, opt, use_guess);
+    launch(L, kSlotLevel0, k_topk_level0<true>, dim3(g0, geo.n), wg, stream, e, geo, ws, opt, use_guess);
   }
   COMPAMS_CHECK_LAUNCH();
   launch(L, kSlotLevel1, k_topk_level1<true>, grid_rows, wg, stream, e, geo, ws, opt);
@@ -1780,15 +1478,17 @@ hipError_t topk_blocks_step(const Geometry& geo, const TopkWorkspace& ws, const 
                             const TopkFlat& flat, const float* g, float* e, float* theta, float* m, float* v,
                             float* vhat, bool first_pass_may_predict, bool clear_pending, bool workers_only,
                             hipStream_t stream, Launcher* L) {
-  const dim3 wg(kWG), wga(kWGA), grid_a(flat.wg_first);
-  if (first_pass_may_predict) {
-    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<true, true, false>, grid_a, wga, stream, g, e, geo, ws, opt);
-    else launch(L, kSlotPassA, k_topk_pass_a<true, false, false>, grid_a, wga, stream, g, e, geo, ws, opt);
-  } else {
-    if (clear_pending) launch(L, kSlotPassA, k_topk_pass_a<false, true, false>, grid_a, wga, stream, g, e, geo, ws, opt);
-    else launch(L, kSlotPassA, k_topk_pass_a<false, false, false>, grid_a, wga, stream, g, e, geo, ws, opt);
-  }
+  const dim3 wg(kWG);
+  const uint32_t use_guess = first_pass_may_predict ? 1u : 0u;
+  if (clear_pending)
+    launch(L, kSlotPassA, k_topk_lean<true, false>, dim3(flat.wg_first), wg, stream, g, e, geo, ws, opt, use_guess);
+  else
+    launch(L, kSlotPassA, k_topk_lean<false, false>, dim3(flat.wg_first), wg, stream, g, e, geo, ws, opt, use_guess);
   COMPAMS_CHECK_LAUNCH();
+  if (flat.wg_level0) {
+    launch(L, kSlotLevel0, k_topk_level0<false>, dim3(flat.wg_level0), wg, stream, e, geo, ws, opt, use_guess);
+    COMPAMS_CHECK_LAUNCH();
+  }
   if (flat.wg_sweep) {  // none if every block is a micro problem
     launch(L, kSlotLevel1, k_topk_level1<false>, dim3(flat.wg_sweep), wg, stream, e, geo, ws, opt);
     COMPAMS_CHECK_LAUNCH();
