@@ -141,7 +141,8 @@ enum {
 /* Per-worker counters of the last step (top-k), for tests and profiling reports. */
 enum {
   COMPAMS_CNT_DENSE_READS = 0, /* how many times the step read the whole row of corrected gradients back
-                                  (0: candidates came out of the first pass; 1: one re-read; 4: no candidate list) */
+                                  (0: candidates came out of the first pass; 1: the candidate list had to be made
+                                  from the stored row; 4: no candidate list) */
   COMPAMS_CNT_CANDIDATES = 1,  /* entries in the candidate list, 0 if none was used */
   COMPAMS_CNT_TIES = 2,        /* coordinates whose key equals the threshold key */
   COMPAMS_CNT_TIES_TAKEN = 3,  /* how many of those were selected */
