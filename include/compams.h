@@ -108,7 +108,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out);
  * compressed gradients in the order 0..n-1 in fp32 and divides by n. *
  * The error line of Algorithm 2 (e <- x - C(x)) may be left pending when the step returns: e then still
  * holds the corrected gradient x where the update has not been applied (top-k: at the selected
- * coordinates; block-sign with blocks other than aligned 4096-coordinate chunks: everywhere), and the next
+ * coordinates; block-sign: everywhere), and the next
  * step applies it while it reads e.  compams_state(COMPAMS_STATE_E) and compams_destroy() apply what is
  * pending first (one kernel on the last step's stream); do not read or write the e buffer between steps by
  * any other route.  Every other result of the step is final when the stream has passed it.

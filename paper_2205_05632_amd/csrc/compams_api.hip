@@ -59,7 +59,7 @@ struct Layout {
   size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_total,
       wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_level0, map_sweep, map_count, map_emit, map_final, micro_list;
   // block-sign
-  size_t offsets, chunk_block, acc, special, done, scales, bits;
+  size_t offsets, chunk_block, acc, special, scales, bits;
   uint32_t acc_replicas;
   uint32_t cap_alloc, num_chunks, words;
   // top-k inside every block
@@ -223,7 +223,6 @@ Layout make_layout(const compams_config* c) {
     L.acc_replicas = static_cast<uint32_t>(std::min<size_t>(32, std::max<size_t>(1, nc / M)));
     L.acc = take(n * M * L.acc_replicas * kLimbs * 8);
     L.special = take(n * M * 4);
-    L.done = take(n * M * 4);
     L.scales = take(n * M * 4);
     L.bits = take(n * static_cast<size_t>(L.words) * 4);
   }
@@ -443,7 +442,6 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     b.acc = reinterpret_cast<uint64_t*>(w + lay.acc);
     b.acc_replicas = lay.acc_replicas;
     b.special = reinterpret_cast<uint32_t*>(w + lay.special);
-    b.done = reinterpret_cast<uint32_t*>(w + lay.done);
     b.scales = reinterpret_cast<float*>(w + lay.scales);
     b.bits = reinterpret_cast<uint32_t*>(w + lay.bits);
     std::vector<uint32_t> off32, cb;
@@ -452,9 +450,6 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
       cb.resize(lay.num_chunks);
     } catch (...) { delete ctx; return COMPAMS_HIP_ERROR; }
     for (int64_t i = 0; i <= cfg->num_blocks; ++i) off32[static_cast<size_t>(i)] = static_cast<uint32_t>(cfg->block_offsets[i]);
-    bool uniform = static_cast<uint32_t>(cfg->num_blocks) == lay.num_chunks;
-    for (int64_t i = 0; uniform && i < cfg->num_blocks; ++i) uniform = cfg->block_offsets[i] == i * kChunk;
-    b.uniform4096 = uniform ? 1u : 0u;
     uint32_t blk = 0;
     for (uint32_t c = 0; c < lay.num_chunks; ++c) {
       const uint32_t j = c * static_cast<uint32_t>(kChunk);
@@ -515,7 +510,7 @@ static int step_impl(compams_ctx* ctx, const float* g, float lr, bool workers_on
     } else if (c.compressor == COMPAMS_BLOCKSIGN) {
       err = blocksign_step(ctx->geo, ctx->bs, ap, g, c.e, c.theta, c.m, c.v, c.vhat, ctx->clear_pending, workers_only,
                            stream, L);
-      ctx->clear_pending = ctx->bs.uniform4096 == 0;  // the single-pass layout writes its residuals itself
+      ctx->clear_pending = true;
     } else {
       err = none_step(ctx->geo, ap, g, c.theta, c.m, c.v, c.vhat, stream, L);
     }

@@ -14,7 +14,7 @@
 // Pass 1 forms x (stored in place of e), its sign words and the sums, a small kernel turns sums into
 // scales, and the server kernel adds the n workers' +-mu in worker order before the AMSGrad update.  The
 // residual e = x - sign(x) * mu is applied by the next step's pass 1 as it reads e (or by the stand-alone
-// residual kernel when e is asked for).  Layouts with block = 4096-coordinate chunk do all of it in one pass.
+// residual kernel when e is asked for).
 
 #include <type_traits>
 
@@ -432,176 +432,10 @@ __global__ __launch_bounds__(kWG) void k_bs_lean(const float* __restrict__ g, fl
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fused single pass for the layout "block b = coordinates [4096 b, 4096 (b+1))" (block = chunk): a workgroup
-// takes a block, each of its four wavefronts a quarter of it (4 rounds, kept in 16 registers per lane); the
-// quarters' largest magnitudes and then their exact partial sums meet in LDS (two barriers per block), every
-// wavefront derives the same scale and writes the sign bits and residuals of its quarter: 12 bytes per
-// coordinate instead of 20.  (A wavefront per block, with the
-// block's 16 rounds in 64 registers per lane, spilled: the spill stores alone were 2.8 GB of HBM writes per
-// launch on the GPT-2 workload, two thirds as much again as the residuals.)
-// A block with an entry more than 2^32 below its largest one, or with a non-finite entry, takes the general
-// route instead (x is stored, the digits go to memory, done = 0) and is finished by the kernels below.
-// ---------------------------------------------------------------------------------------------
-// Store the entries of a lane's quad that lie below d (columns >= d are never written).
-__device__ __forceinline__ void store_valid4(float* er, uint32_t j, uint32_t d, const float xv[4]) {
-  if (j + 3 < d) store_stream4(er + j, make_float4(xv[0], xv[1], xv[2], xv[3]));
-  else {
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-      if (j + s < d) er[j + s] = xv[s];
-  }
-}
-
-
-__global__ __launch_bounds__(kWG) void k_bs_fused4096(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
-                                                       BlocksignWorkspace ws) {
-  __shared__ uint32_t sh_kmax[1][kWaves], sh_odd[1][kWaves];
-  __shared__ uint64_t sh_sum[1][kWaves][3];
-  const uint32_t row = blockIdx.y;
-  const float* gr = g + static_cast<int64_t>(row) * geo.ld;
-  float* er = e + static_cast<int64_t>(row) * geo.ld;
-  const size_t blk_digits = static_cast<size_t>(ws.acc_replicas) * kLimbs;  // digits of one (row, block): all replicas
-  uint64_t* accr = ws.acc + static_cast<size_t>(row) * geo.num_blocks * blk_digits;
-  uint32_t* specr = ws.special + static_cast<size_t>(row) * geo.num_blocks;
-  float* mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;
-  uint32_t* doner = ws.done + static_cast<size_t>(row) * geo.num_blocks;
-  uint32_t* bitr = ws.bits + static_cast<size_t>(row) * geo.words;
-  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
-  const uint32_t d = geo.d;
-  const uint32_t c = blockIdx.x;  // one block per workgroup: the dispatcher overlaps blocks better than a loop
-  if (c >= geo.num_chunks) return;  // with two barriers per trip does (workgroup-uniform)
-  BsBatch cur;
-  // this wavefront's rounds of block c: wave * kQuarter ..
-  if ((c + 1) * static_cast<uint64_t>(kChunk) <= d) bs_load_batch_t<true>(cur, gr, er, c, wave * kQuarter, d);
-  else bs_load_batch_t<false>(cur, gr, er, c, wave * kQuarter, d);
-  {
-    constexpr uint32_t buf = 0;
-    const uint32_t base = c * kChunk + wave * kQuarter * 256 + lane * 4;
-    const uint32_t len = (c + 1) * static_cast<uint64_t>(kChunk) <= d ? kChunk : d - c * kChunk;
-    float4 x[kQuarter];
-    uint32_t kmax = 0;
-    bool odd = false;  // a non-finite entry
-#pragma unroll
-    for (int u = 0; u < kQuarter; ++u) {
-      const uint32_t j = base + u * 256;
-      x[u] = make_float4(cur.e[u].x + cur.g[u].x, cur.e[u].y + cur.g[u].y, cur.e[u].z + cur.g[u].z,
-                         cur.e[u].w + cur.g[u].w);
-      const float xv[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const uint32_t key = __float_as_uint(xv[s]) & 0x7fffffffu;
-        if (j + s < d) {
-          if (key >= 0x7f800000u) odd = true;
-          else if (key > kmax) kmax = key;
-        }
-      }
-    }
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) {
-      const uint32_t o = __shfl_xor(kmax, s, 64);
-      kmax = o > kmax ? o : kmax;
-    }
-    if (lane == 0) {
-      sh_kmax[buf][wave] = kmax;
-      sh_odd[buf][wave] = ballot64(odd) != 0 ? 1u : 0u;
-    }
-    __syncthreads();
-    uint32_t any_odd = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const uint32_t o = sh_kmax[buf][w];
-      kmax = o > kmax ? o : kmax;
-      any_odd |= sh_odd[buf][w];
-    }
-    const uint32_t exm = kmax >> 23;
-    const uint32_t centre = (exm ? exm - 1 : 0) >> 5;  // digit of the largest entry: nothing lies above it
-    uint64_t a0 = 0, a1 = 0, a2 = 0;
-    bool far = false;  // an entry more than 2^32 below the largest one
-#pragma unroll
-    for (int u = 0; u < kQuarter; ++u) {
-      const uint32_t j = base + u * 256;
-      const float xv[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        if (j + s >= d) continue;
-        const Fixed f = to_fixed(__float_as_uint(xv[s]));
-        if (f.special || (f.lo | f.hi) == 0) continue;
-        if (f.w == centre) { a1 += f.lo; a2 += f.hi; }
-        else if (f.w + 1 == centre) { a0 += f.lo; a1 += f.hi; }
-        else far = true;
-      }
-    }
-    {
-      const uint64_t s0 = wave_sum_u64(a0), s1 = wave_sum_u64(a1), s2 = wave_sum_u64(a2);
-      const bool wave_far = ballot64(far) != 0;
-      if (lane == 0) {
-        sh_sum[buf][wave][0] = s0;
-        sh_sum[buf][wave][1] = s1;
-        sh_sum[buf][wave][2] = s2;
-        if (wave_far) sh_odd[buf][wave] = 1u;  // read again after the barrier
-      }
-    }
-    __syncthreads();
-    uint64_t t0 = 0, t1 = 0, t2 = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      t0 += sh_sum[buf][w][0];
-      t1 += sh_sum[buf][w][1];
-      t2 += sh_sum[buf][w][2];
-      any_odd |= sh_odd[buf][w];
-    }
-    any_odd = uniform_u32(any_odd);
-    if (any_odd == 0) {
-      uint64_t w0, w1, w2;
-      // lowest digit held: centre - 1 (or 0 when the centre is digit 0; the lowest accumulator is then empty)
-      const uint32_t low = centre ? centre - 1 : 0;
-      if (centre) digits3_to_192(t0, t1, t2, w0, w1, w2);
-      else digits3_to_192(t1, t2, 0, w0, w1, w2);
-      const double sum = fixed192_to_double(w0, w1, w2, 32 * static_cast<int>(low) - 149, false);
-      const float mu = static_cast<float>(sum / static_cast<double>(len));
-      if (threadIdx.x == 0) {
-        mur[c] = mu;
-        doner[c] = 1;
-      }
-#pragma unroll
-      for (int u = 0; u < kQuarter; ++u) {
-        const uint32_t j0 = c * kChunk + (wave * kQuarter + u) * 256;
-        if (j0 >= d) break;  // wave-uniform
-        const uint32_t j = j0 + lane * 4;
-        float xv[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
-        uint32_t nib = 0;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const bool neg = j + s < d && xv[s] < 0.0f;
-          nib |= (neg ? 1u : 0u) << s;
-          xv[s] = xv[s] - (neg ? -mu : mu);
-        }
-        store_valid4(er, j, d, xv);
-        const uint32_t word = or_over_8_lanes(nib << ((lane & 7u) * 4u));
-        const uint32_t widx = (j0 >> 5) + (lane >> 3);
-        if ((lane & 7u) == 0 && widx < geo.words) bitr[widx] = word;
-      }
-    } else {
-      if (threadIdx.x == 0) doner[c] = 0;
-      uint64_t* dg = accr + static_cast<size_t>(c) * blk_digits;
-#pragma unroll 1
-      for (int u = 0; u < kQuarter; ++u) {
-        const uint32_t j = base + u * 256;
-        const float xv[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-          if (j + s < d) add_direct(__float_as_uint(xv[s]), dg, specr + c);
-        store_valid4(er, j, d, xv);
-      }
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
 // Scales: one thread per (row, block).  Normalise the digits, round the sum to double (nearest, ties
 // to even), divide by the block length, round to fp32.  Clears the digits for the next step.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWorkspace ws, int skip_done) {
+__global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWorkspace ws) {
   const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
   const uint32_t R = ws.acc_replicas;  // sets of digits per (row, block)
   size_t t;
@@ -609,7 +443,6 @@ __global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWork
   if (R == 1) {  // a thread per (row, block)
     t = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x;
     if (t >= total) return;
-    if (skip_done && ws.done[t]) return;
     uint64_t* dg = ws.acc + t * kLimbs;
 #pragma unroll
     for (int i = 0; i < kLimbs; ++i) {
@@ -619,7 +452,6 @@ __global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWork
   } else {  // a wavefront per (row, block): lane r brings replica r, the sums are taken over the wavefront
     t = static_cast<size_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
     if (t >= total) return;
-    if (skip_done && ws.done[t]) return;
     const uint32_t lane = lane_id();
     uint64_t* dg = ws.acc + (t * R + lane) * kLimbs;
 #pragma unroll
@@ -675,19 +507,16 @@ __global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWork
 // layout is still pending.  One wavefront per chunk.  Eight lanes
 // (32 coordinates) share one word of the bit map.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometry geo, BlocksignWorkspace ws,
-                                                   int skip_done) {
+__global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometry geo, BlocksignWorkspace ws) {
   const uint32_t row = blockIdx.y;
   float* er = e + static_cast<int64_t>(row) * geo.ld;
   const uint32_t* __restrict__ off = ws.offsets;
   const float* __restrict__ mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;
-  const uint32_t* doner = ws.done + static_cast<size_t>(row) * geo.num_blocks;
   uint32_t* bitr = ws.bits + static_cast<size_t>(row) * geo.words;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const uint32_t stride = gridDim.x * kWaves;
   const uint32_t d = geo.d;
   for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
-    if (skip_done && doner[c]) continue;  // block = chunk, finished by the fused pass (wave-uniform)
     uint32_t b = ws.chunk_block[c];
 #pragma unroll 1
     for (int r0 = 0; r0 < kRounds; r0 += kBsBatch) {
@@ -933,26 +762,17 @@ __global__ __launch_bounds__(kWG) void k_copy16(float* __restrict__ dst, const f
 hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, const float* g,
                           float* e, float* theta, float* m, float* v, float* vhat, bool residual_pending,
                           bool workers_only, hipStream_t stream, Launcher* L) {
-  const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
-  // these passes hide their latencies through occupancy: many workgroups per row
-  const dim3 grid_rows(G, geo.n), grid_2(G * 2, geo.n), grid_4(G * 4, geo.n), wg(kWG);
-  const int fused = ws.uniform4096 ? 1 : 0;
-  if (fused) launch(L, kSlotBsPass1, k_bs_fused4096, dim3(geo.num_chunks, geo.n), wg, stream, g, e, geo, ws);
-  else if (residual_pending) launch(L, kSlotBsPass1, k_bs_lean<true>, dim3(geo.num_chunks, geo.n), wg, stream, g, e, geo, ws);
-  else launch(L, kSlotBsPass1, k_bs_lean<false>, dim3(geo.num_chunks, geo.n), wg, stream, g, e, geo, ws);
+  const dim3 grid_chunks(geo.num_chunks, geo.n), wg(kWG);
+  if (residual_pending) launch(L, kSlotBsPass1, k_bs_lean<true>, grid_chunks, wg, stream, g, e, geo, ws);
+  else launch(L, kSlotBsPass1, k_bs_lean<false>, grid_chunks, wg, stream, g, e, geo, ws);
   COMPAMS_CHECK_LAUNCH();
   const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
   const size_t per_group = ws.acc_replicas == 1 ? kWG : kWaves;  // (row, block) pairs per workgroup
   launch(L, kSlotBsFinal, k_bs_finalize, dim3(static_cast<uint32_t>((total + per_group - 1) / per_group)), wg, stream,
-         geo, ws, fused);
+         geo, ws);
   COMPAMS_CHECK_LAUNCH();
-  // General layouts: the residual e = x - sign(x) * mu is left to the next step's first pass (or to
-  // blocksign_apply_residual when e is asked for).  Block = chunk layout: only the blocks that the single pass
-  // could not finish are completed here.
-  if (fused) {
-    launch(L, kSlotBsPass2, k_bs_pass2, grid_rows, wg, stream, e, geo, ws, 1);
-    COMPAMS_CHECK_LAUNCH();
-  }
+  // The residual e = x - sign(x) * mu is left to the next step's first pass (or to blocksign_apply_residual when
+  // e is asked for).
   if (workers_only) return hipSuccess;
   return blocksign_server_step(geo, ws, ap, theta, m, v, vhat, stream, L);
 }
@@ -969,7 +789,7 @@ hipError_t blocksign_server_step(const Geometry& geo, const BlocksignWorkspace& 
 
 hipError_t blocksign_apply_residual(const Geometry& geo, const BlocksignWorkspace& ws, float* e, hipStream_t stream) {
   const uint32_t G = groups_per_row(geo.n, geo.num_chunks);
-  hipLaunchKernelGGL(k_bs_pass2, dim3(G * 2, geo.n), dim3(kWG), 0, stream, e, geo, ws, 0);
+  hipLaunchKernelGGL(k_bs_pass2, dim3(G * 2, geo.n), dim3(kWG), 0, stream, e, geo, ws);
   return hipGetLastError();
 }
 

@@ -146,8 +146,6 @@ struct BlocksignWorkspace {
                         // the sum of a (row, block) is the sum of its replicas
   uint32_t acc_replicas;
   uint32_t* special;    // n * M : bit 0 = an infinity was seen, bit 1 = a NaN was seen
-  uint32_t* done;       // n * M : the fused single pass has finished this block (block = chunk layouts only)
-  uint32_t uniform4096; // block b is exactly coordinates [4096 b, 4096 (b + 1))
   float* scales;        // n * M
   uint32_t* bits;       // n * words
 };
