@@ -63,13 +63,12 @@ __device__ __forceinline__ void atomic_add_u64(uint64_t* p, uint64_t v) {
 }
 
 // Register accumulator of a lane: an fp64 sum over a window of kWinSpan binary exponents, placed by the
-// wavefront (wave-uniform) where the magnitudes are expected.  Every |x| in the window is an integer below
-// 2^(24 + kWinSpan - 1) = 2^45 times the window's quantum 2^(lowest exponent - 150), so the fp64 sum of up to
-// kWinAdds = 2^8 of them is below 2^53 quanta: every addition is exact and their order does not matter.  A lane
-// flushes after kWinAdds additions (or when its wavefront leaves the block): the sum becomes an integer
-// again, is added over the wavefront and goes to the global digits.  Entries outside the window (more than
-// 2^20 below the largest magnitude the wavefront met when it placed the window: rare) and non-finite ones go
-// straight to the global digits and flags.
+// wavefront (wave-uniform) so that it ends at the largest magnitude of the coordinates it is about to add.
+// Every |x| in the window is an integer below 2^(24 + kWinSpan - 1) = 2^45 times the window's quantum
+// 2^(lowest exponent - 150), so the fp64 sum of up to kWinAdds = 2^8 of them (a lane adds 16) is below 2^53
+// quanta: every addition is exact and their order does not matter.  The sum then becomes an integer again, is
+// added over the wavefront and goes to the global digits.  Entries below the window (more than 2^21 below the
+// largest magnitude: rare) and non-finite ones go straight to the global digits and flags.
 // "Exponent" here is the effective one: max(biased exponent, 1), so that subnormals share the quantum of
 // the smallest normal numbers; |x| = mantissa * 2^(exponent - 150).
 // (One window of 22 exponents replaced two of 17: per entry one compare, one select, one conversion and one
@@ -83,12 +82,10 @@ struct WaveAcc {
   uint32_t eh;      // window: exponents eh .. eh + kWinSpan - 1
   uint32_t klo;     // magnitude keys klo .. klo + kspan - 1 lie in the window (eh == 1: from key 0, the
   uint32_t kspan;   // subnormals and zero included)
-  uint32_t adds;    // additions per lane since the last flush (wave-uniform)
-  bool live;
 };
 
 __device__ __forceinline__ void acc_reset(WaveAcc& A) {
-  A.sum = 0.0; A.eh = 1; A.klo = 0; A.kspan = 0; A.adds = 0; A.live = false;
+  A.sum = 0.0; A.eh = 1; A.klo = 0; A.kspan = 0;
 }
 
 // Places the window so that it ends `headroom` exponents above the largest finite magnitude key kmax_key
@@ -100,14 +97,12 @@ __device__ __forceinline__ void acc_place(WaveAcc& A, uint32_t kmax_key, uint32_
   A.eh = top >= kWinSpan ? top - (kWinSpan - 1u) : 1u;
   A.klo = A.eh == 1u ? 0u : A.eh << 23;
   A.kspan = ((A.eh + kWinSpan) << 23) - A.klo;
-  A.live = true;
 }
 
 // The window's sum as an integer number of quanta 2^(e_low - 150), added over the wavefront and then, by
 // lane 0, into the digits: bit position e_low - 1 above 2^-149, i.e. digit (e_low - 1) / 32 and up.
-// Out of line: flushes are rare (a wavefront leaves a block, or the window has taken kWinAdds additions), and
-// the streaming loops stay small enough for the instruction cache.
-__device__ __forceinline__ void window_to_digits_inline(double sum, uint32_t e_low, uint64_t* digits) {
+// In line: once per wavefront, and a call would pass its arguments through scratch memory.
+__device__ __forceinline__ void window_to_digits(double sum, uint32_t e_low, uint64_t* digits) {
   const uint64_t mine = static_cast<uint64_t>(ldexp(sum, 150 - static_cast<int>(e_low)));  // exact, below 2^53
   const uint64_t all = wave_sum_u64(mine);                                                 // below 2^59
   if (lane_id() == 0 && all) {
@@ -118,16 +113,6 @@ __device__ __forceinline__ void window_to_digits_inline(double sum, uint32_t e_l
     if (d1) atomic_add_u64(digits + w + 1, d1);
     if (high) atomic_add_u64(digits + w + 2, high);  // w <= 7: still inside the kLimbs digits
   }
-}
-
-__device__ __noinline__ void window_to_digits(double sum, uint32_t e_low, uint64_t* digits) {
-  window_to_digits_inline(sum, e_low, digits);
-}
-
-__device__ __forceinline__ void acc_flush(WaveAcc& A, uint64_t* digits /* kLimbs of the (row, block) */) {
-  if (!A.live) return;
-  window_to_digits(A.sum, A.eh, digits);
-  acc_reset(A);
 }
 
 // One entry straight into the global digits (or the flags for non-finite values).  Out of line: rare.
@@ -156,7 +141,6 @@ __device__ __forceinline__ void acc_add4(WaveAcc& A, const uint32_t bits[4], con
     rare[s] = ok[s] && !in && key != 0u;
     any |= rare[s];
   }
-  A.adds += 4;
   if (ballot64(any) != 0) {
 #pragma unroll
     for (int s = 0; s < 4; ++s)
@@ -197,29 +181,13 @@ __device__ __forceinline__ double fixed192_to_double(uint64_t w0, uint64_t w1, u
   return ldexp(static_cast<double>(kept), lsb_exp + sh);
 }
 
-// Sum of three 64-bit digit accumulators that sit 32 bits apart (s0 lowest) as a 192-bit integer.
-__device__ __forceinline__ void digits3_to_192(uint64_t s0, uint64_t s1, uint64_t s2, uint64_t& w0, uint64_t& w1,
-                                               uint64_t& w2) {
-  // value = s0 + s1 * 2^32 + s2 * 2^64
-  w0 = s0;
-  w1 = 0;
-  w2 = 0;
-  const uint64_t a = s1 << 32, ah = s1 >> 32;
-  w0 += a;
-  uint64_t c = w0 < a ? 1ull : 0ull;
-  w1 = ah + c;  // ah < 2^32: no wrap
-  const uint64_t t = w1 + s2;
-  w2 = t < s2 ? 1ull : 0ull;
-  w1 = t;
-}
-
 // ---------------------------------------------------------------------------------------------
-// Pass 1: x = e + g -> e, the sign words of x and the exact block sums.  Grid (groups, n); a wavefront
-// takes a chunk at a time and loads one batch of rounds ahead.
+// Pass 1: x = e + g -> e, the sign words of x and the exact block sums.
 // ---------------------------------------------------------------------------------------------
 constexpr int kBsBatch = 4;
 constexpr int kQuarter = kRounds / kWaves;  // rounds of a chunk per wavefront when a workgroup takes one chunk
 static_assert(kQuarter == kBsBatch, "a wavefront's quarter of a chunk is one batch of loads");
+static_assert(kQuarter * 4 <= static_cast<int>(kWinAdds), "additions per lane into one window");
 
 // A value that is the same in every lane, moved to a scalar register: conditions on it become scalar branches
 // and it can be an operand of every lane's arithmetic without a register per lane.
@@ -330,7 +298,7 @@ __device__ __noinline__ void straddling_round(float4 g4, float4 e4, uint32_t j0,
       acc_reset(A);
       acc_place(A, uniform_u32(kmax), 0);
       acc_add4(A, bits, in, dg + static_cast<size_t>(replica) * kLimbs, specr + bb);
-      window_to_digits_inline(A.sum, A.eh, dg + static_cast<size_t>(replica) * kLimbs);
+      window_to_digits(A.sum, A.eh, dg + static_cast<size_t>(replica) * kLimbs);
     }
   }
 }
@@ -341,8 +309,8 @@ __device__ __noinline__ void straddling_round(float4 g4, float4 e4, uint32_t j0,
 // 6.1-6.4 TB/s on MI355X, workgroups that walk many chunks at 5.4-5.7 TB/s).  A quarter that lies inside one
 // block -- all but a few per row -- is summed in a register window placed by the quarter's own largest
 // magnitude and goes to the block's digits with at most three atomics per wavefront; a quarter that straddles
-// block boundaries takes the out-of-line per-coordinate route.  The pending residual update is applied on
-// the fly as before.
+// block boundaries goes out of line through the blocks it meets.  The pending residual update of the previous
+// step is applied to e as it is read.
 // ---------------------------------------------------------------------------------------------
 template <bool PEND>
 __global__ __launch_bounds__(kWG) void k_bs_lean(const float* __restrict__ g, float* __restrict__ e, Geometry geo,
@@ -428,12 +396,13 @@ __global__ __launch_bounds__(kWG) void k_bs_lean(const float* __restrict__ g, fl
   const bool all[4] = {true, true, true, true};
 #pragma unroll
   for (int u = 0; u < kQuarter; ++u) acc_add4(A, bits[u], all, dg, specr + b);
-  window_to_digits_inline(A.sum, A.eh, dg);  // once per wavefront: in line (a call would go through scratch)
+  window_to_digits(A.sum, A.eh, dg);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Scales: one thread per (row, block).  Normalise the digits, round the sum to double (nearest, ties
-// to even), divide by the block length, round to fp32.  Clears the digits for the next step.
+// Scales: per (row, block) add up the sets of digits (a thread when there is one set, else a wavefront with a
+// lane per set), normalise them, round the sum to double (nearest, ties to even), divide by the block length,
+// round to fp32.  Clears the digits for the next step.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWorkspace ws) {
   const size_t total = static_cast<size_t>(geo.n) * geo.num_blocks;
@@ -502,10 +471,9 @@ __global__ __launch_bounds__(kWG) void k_bs_finalize(Geometry geo, BlocksignWork
 }
 
 // ---------------------------------------------------------------------------------------------
-// The residual  e = x - sign(x) * mu  on its own (and the sign words once more): for blocks that the
-// single-pass kernel left unfinished, and when the caller asks for e while the update of a general
-// layout is still pending.  One wavefront per chunk.  Eight lanes
-// (32 coordinates) share one word of the bit map.
+// The residual  e = x - sign(x) * mu  on its own (and the sign words once more): when the caller asks for e
+// while the update is still pending.  One wavefront per chunk.  Eight lanes (32 coordinates) share one word
+// of the bit map.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometry geo, BlocksignWorkspace ws) {
   const uint32_t row = blockIdx.y;

@@ -10,15 +10,16 @@ namespace compams {
 // ---------------------------------------------------------------------------------------------
 // Geometry shared by all kernels.
 //
-// A row (one worker's d coordinates) is cut into chunks of kChunk consecutive coordinates.  One
-// wavefront (64 lanes) owns a chunk at a time and walks it in kRounds rounds; in a round lane l
-// holds the four coordinates base + 256*round + 4*l + {0,1,2,3}, so that a wave's 128-bit accesses
-// cover 1 KiB of contiguous memory and (round, lane, slot) order is ascending coordinate order.
+// A row (one worker's d coordinates) is cut into chunks of kChunk consecutive coordinates, a chunk into
+// kRounds rounds of 256 coordinates; in a round lane l of a wavefront holds the four coordinates
+// base + 256*round + 4*l + {0,1,2,3}, so that a wave's 128-bit accesses cover 1 KiB of contiguous memory and
+// (round, lane, slot) order is ascending coordinate order.  The dense passes give a chunk to a workgroup
+// (a quarter of its rounds to each wavefront), the sweeps over stored rows and lists a chunk to a wavefront.
 // ---------------------------------------------------------------------------------------------
 constexpr int kWG = 256;                 // threads per workgroup = 4 wavefronts
 constexpr int kWaves = kWG / 64;
 constexpr int kChunk = 4096;             // coordinates per chunk
-constexpr int kRounds = kChunk / 256;    // rounds per chunk and wavefront
+constexpr int kRounds = kChunk / 256;    // rounds per chunk
 
 // Radix levels over the 31-bit magnitude key (fp32 bit pattern without the sign):
 // level 0 = bits 30..19 (the exponent and 4 mantissa bits), level 1 = bits 18..9, level 2 = bits 8..0.
@@ -27,7 +28,7 @@ constexpr int kNB0 = 1 << 12;
 constexpr int kL1Shift = 9;
 constexpr int kNB1 = 1 << 10;
 constexpr int kNB2 = 1 << 9;
-// The first pass keeps level-1 histograms of this many buckets, starting at the guessed one: the guess is one
+// The level-0 kernel keeps level-1 histograms of this many buckets, starting at the guessed one: the guess is one
 // below the last threshold bucket, so a threshold that moved by one bucket either way still resolves there.
 constexpr uint32_t kTracked = 3;
 // Top-k inside every block: a block of at most this many coordinates (a bias, a norm weight) is one wavefront's
@@ -46,7 +47,7 @@ inline uint32_t count_chunks_per_block(uint32_t num_chunks) {
 
 constexpr int kWireTile = 256;  // coordinate gaps per tile of a top-k message (one width per tile)
 
-// Where a row's selection reads its elements from after the first pass.
+// Where a row's selection reads its elements from after level 0.
 enum : uint32_t {
   kModeCand = 0,   // candidate list written by the first pass (threshold bucket was predicted)
   kModeNeedB = 1,  // candidate list written by a second dense pass that knows the exact level-0 bucket
@@ -110,7 +111,7 @@ struct TopkWorkspace {
   uint32_t* counters;   // n * COMPAMS_COUNTERS_PER_ROW
   uint32_t* hist0;      // n * kNB0
   uint32_t* hist1;      // n * kNB1
-  uint32_t* hist1x;     // n * kTracked * kNB1 : level-1 histograms of the buckets tracked by the first pass
+  uint32_t* hist1x;     // n * kTracked * kNB1 : level-1 histograms of the tracked buckets
   uint32_t* hist2;      // n * kNB2
   uint4* chunk_rec;     // n * num_chunks : keys above tau, keys equal to tau, and the exclusive prefixes of both
                         //                  within the chunk's count block

@@ -5,22 +5,28 @@
 // (fp32 pattern without the sign; ties to the lower coordinate) are written out as ascending
 // (coordinate, value) lists, and the residual at those coordinates becomes zero.
 //
-// Five kernels per step:
-//   1 first pass   x = e + g -> e, level-0 histogram of the keys (12 bits); when the previous step's
-//                  threshold bucket is carried over as a guess, the same pass also writes the candidate
-//                  list (entries at or above the guessed bucket) and the level-1 histograms of the three
-//                  buckets from the guess upwards, among which the threshold is expected.  The last workgroup of a row to finish finds
-//                  the threshold bucket, checks the guess, and resolves level 1 if it can.
-//   2 level 1      only for rows whose guess failed (or had none): one more read of the row that writes
-//                  the candidate list with the exact bucket and builds the level-1 histogram (10 bits);
-//                  rows that would not fit a list are histogrammed from the row itself.
-//   3 level 2      histogram of the last 9 key bits over the matching candidates; yields the k-th largest
+// Six kernels per step (the key's 32 bits are resolved as 12 + 10 + 9 bits and a zero sign bit):
+//   1 first pass   x = e + g -> e as a grid of short workgroups, one chunk each.  When the previous step's
+//                  threshold bucket is carried over as a guess, the same pass writes the candidate list: the
+//                  entries at or above the guessed bucket, a segment per chunk.
+//   2 level 0      histogram of the 12-bit threshold buckets, from the candidate list when the guess held (the
+//                  list then holds at least k entries), else from the row itself; for a listed row also the
+//                  level-1 histograms of the three buckets from the guess upwards, among which the threshold
+//                  is expected.  The last workgroup of a row to finish finds the threshold bucket, checks the
+//                  guess, resolves level 1 if it can, and sets the next step's guess.
+//   3 level 1      only for rows that level 0 could not resolve: one more read of the row that writes the
+//                  candidate list with the exact bucket and builds the level-1 histogram (10 bits), or a
+//                  sweep of the list; rows that would not fit a list are histogrammed from the row itself.
+//   4 level 2      histogram of the last 9 key bits over the matching candidates; yields the k-th largest
 //                  key tau and how many keys equal to tau are taken.
-//   4 count        per chunk: keys above tau and keys equal to tau, with prefixes inside contiguous blocks of
+//   5 count        per chunk: keys above tau and keys equal to tau, with prefixes inside contiguous blocks of
 //                  chunks and the totals of every block.
-//   5 final        per chunk of coordinates: the position of each worker's entries in its list follows from
+//   6 final        per chunk of coordinates: the position of each worker's entries in its list follows from
 //                  the block totals and prefixes; the selected entries are written there, then added in
 //                  worker order into an LDS tile of the averaged gradient, then AMSGrad.
+// With top-k inside every block (one selection problem per worker and block) the same six launches go over all
+// problems at once through tables of workgroup slots; problems of at most 1024 coordinates are solved by one
+// wavefront inside the first pass.
 // Zeroing the residual at the selected coordinates is not done by scattered stores: the next step's
 // first pass treats the coordinates in the previous lists as zero while it forms x (and a small kernel
 // applies the zeros when the caller asks for e).
