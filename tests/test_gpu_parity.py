@@ -336,9 +336,9 @@ def test_blocksign_sums_around_the_register_windows(late_exp):
     p.close()
 
 
-def test_blocksign_4096_blocks_take_the_general_route_when_a_block_is_too_wide():
-    """Blocks of exactly 4096 coordinates are normally finished in one pass; a block whose entries span more than
-    2^32 (or hold an infinity) is handed to the general kernels.  Both kinds in one run."""
+def test_blocksign_4096_blocks_of_every_kind():
+    """Blocks of exactly one chunk: ordinary ones beside a block whose entries span 74 decades (far outside any
+    register window), an empty block, a block with one tiny entry and a block of denormals."""
     n, d = 3, 10 * 4096 + 1000
     rng = np.random.default_rng(6)
     off = np.concatenate([np.arange(0, d, 4096), [d]]).astype(np.int64)
