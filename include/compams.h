@@ -63,7 +63,7 @@ enum {
 };
 
 typedef struct compams_config {
-  int32_t n;          /* number of workers (rows), >= 1 */
+  int32_t n;          /* number of workers (rows), 1 <= n <= 65535 */
   int64_t d;          /* coordinates per worker, 1 <= d < 2^31 */
   int64_t ld;         /* row stride of g and e in elements: ld >= d and ld % 4 == 0; a multiple of 1024 (rows that
                          start on 4 KiB boundaries) streams about 8 % faster than an odd stride */

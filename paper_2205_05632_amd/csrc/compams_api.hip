@@ -78,7 +78,7 @@ bool blocks_valid(const compams_config* c) {
 
 bool basic_valid(const compams_config* c) {
   if (!c) return false;
-  if (c->n < 1 || c->d < 1 || c->d >= (int64_t(1) << 31)) return false;
+  if (c->n < 1 || c->n > 65535 || c->d < 1 || c->d >= (int64_t(1) << 31)) return false;  // n is a grid dimension
   if (c->compressor != COMPAMS_NONE && c->compressor != COMPAMS_TOPK && c->compressor != COMPAMS_BLOCKSIGN &&
       c->compressor != COMPAMS_TOPK_BLOCKS)
     return false;

@@ -85,7 +85,7 @@ def test_workspace_size_is_host_only_and_monotone():
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(n=0), -1), (dict(d=0), -1), (dict(k=0), -1), (dict(k=1001), -1), (dict(ld=996), -1),
+    (dict(n=0), -1), (dict(n=65536), -1), (dict(d=0), -1), (dict(k=0), -1), (dict(k=1001), -1), (dict(ld=996), -1),
     (dict(ld=1002), -2), (dict(eps_mode=5), -1), (dict(theta=None), -1), (dict(workspace=None), -1),
     (dict(theta=0x1004), -2), (dict(workspace=0x1010), -2), (dict(workspace_bytes=16), -3),
     (dict(compressor=B.BLOCKSIGN, num_blocks=2), -1),      # no offsets given

@@ -45,7 +45,8 @@ def test_topk_tiny_config_10_steps(eps_mode):
 
 @pytest.mark.parametrize("n,d,k,ld", [(3, 100003, 1000, None), (2, 4097, 5, 4100), (1, 1, 1, None), (5, 8191, 8191, 8200),
                                       (2, 12288, 1, None), (4, 300001, 150000, None), (17, 20000, 200, None),
-                                      (40, 30000, 300, None), (33, 9000, 9000, None), (64, 4097, 40, None)])
+                                      (40, 30000, 300, None), (33, 9000, 9000, None), (64, 4097, 40, None),
+                                      (300, 5000, 50, None)])
 def test_topk_ragged_shapes(n, d, k, ld):
     rng = np.random.default_rng(d + k)
     p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, B.TOPK, k=k, ld=ld)
@@ -217,6 +218,7 @@ def ragged_offsets(d, rng, m):
     (3, 33000, "ragged2000"),
     (21, 20000, "ragged40"),
     (40, 8192, "fixed4096"),
+    (300, 6000, "ragged40"),
 ])
 def test_blocksign_block_layouts(n, d, offsets):
     rng = np.random.default_rng(d)

@@ -73,7 +73,7 @@ class BlockPair:
 
 
 SHAPES = [(3, 40000, 7), (2, 100000, 30), (5, 8192, 2), (2, 4 * 4096, 4096), (1, 300000, 5), (4, 70001 * 4, 1),
-          (17, 12288, 3)]
+          (17, 12288, 3), (150, 6000, 9)]
 
 
 @pytest.mark.parametrize("n,d,blocks", SHAPES)
