@@ -78,4 +78,20 @@ __device__ __forceinline__ void store_stream4(float* p, const float4& x) {
   __builtin_nontemporal_store(v, reinterpret_cast<f4v*>(p));
 }
 
+// A value that is the same in every lane, moved to a scalar register: conditions on it become scalar branches
+// and it can be an operand of every lane's arithmetic without a register per lane.
+__device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// A table entry at a wave-uniform index, read through the scalar path: the tables read this way (block offsets,
+// chunk-to-block map, the previous step's means and list offsets, a row's carried-over guess) are not
+// written by the kernel that reads them, and a scalar load has its own counter, so waiting for it does not mean
+// waiting for the vector loads that are in flight (a vector load here stalled the stream once per chunk); what
+// it returns sits in scalar registers.
+typedef const __attribute__((address_space(4))) uint32_t* ScalarTable;
+__device__ __forceinline__ uint32_t table_u32(const uint32_t* p, uint32_t i) {
+  return reinterpret_cast<ScalarTable>(reinterpret_cast<uintptr_t>(p))[i];
+}
+__device__ __forceinline__ float table_f32(const float* p, uint32_t i) {
+  return __uint_as_float(table_u32(reinterpret_cast<const uint32_t*>(p), i));
+}
 }  // namespace compams

@@ -410,10 +410,31 @@ struct SegCtx {
   size_t chunk_base, seloff_base, cand_base, list_base;
 };
 
+// The context of workgroup `group` of segment `seg` in a flat launch.
+__device__ __forceinline__ SegCtx seg_ctx_of(uint32_t seg, uint32_t group, uint32_t groups, const Seg& sg, Geometry& geo,
+                                             TopkOptions& opt) {
+  SegCtx c;
+  c.seg = seg;
+  c.group = group;
+  c.groups = groups;
+  c.elem_off = sg.elem_off;
+  c.coord_base = sg.coord_base;
+  c.chunk_base = sg.chunk_base;
+  c.seloff_base = sg.seloff_base;
+  c.cand_base = sg.cand_base;
+  c.list_base = sg.list_base;
+  geo.d = sg.d;
+  geo.k = sg.k;
+  geo.num_chunks = sg.num_chunks;
+  geo.count_cpw = sg.count_cpw;
+  opt.cap = opt.cap < sg.cap ? opt.cap : sg.cap;
+  return c;
+}
+
 template <bool UNI, int CLASS>
 __device__ __forceinline__ SegCtx seg_ctx(Geometry& geo, TopkOptions& opt, const TopkWorkspace& ws) {
-  SegCtx c;
   if (UNI) {
+    SegCtx c;
     c.seg = blockIdx.y;
     c.group = blockIdx.x;
     c.groups = gridDim.x;
@@ -423,29 +444,18 @@ __device__ __forceinline__ SegCtx seg_ctx(Geometry& geo, TopkOptions& opt, const
     c.seloff_base = static_cast<size_t>(c.seg) * (geo.num_chunks + 1);
     c.cand_base = static_cast<size_t>(c.seg) * opt.cap;
     c.list_base = static_cast<size_t>(c.seg) * geo.k;
-  } else {
-    const WgSlot slot = (CLASS == kClassFirst ? ws.map_first
-                         : CLASS == kClassLevel0 ? ws.map_level0
-                         : CLASS == kClassSweep ? ws.map_sweep : ws.map_count)[blockIdx.x];
-    const Seg sg = ws.segs[slot.seg];
-    c.seg = slot.seg;
-    c.group = slot.group;
-    c.groups = CLASS == kClassFirst ? sg.groups_first
-               : CLASS == kClassLevel0 ? sg.groups_level0
-               : CLASS == kClassSweep ? sg.groups_sweep : sg.count_blocks;
-    c.elem_off = sg.elem_off;
-    c.coord_base = sg.coord_base;
-    c.chunk_base = sg.chunk_base;
-    c.seloff_base = sg.seloff_base;
-    c.cand_base = sg.cand_base;
-    c.list_base = sg.list_base;
-    geo.d = sg.d;
-    geo.k = sg.k;
-    geo.num_chunks = sg.num_chunks;
-    geo.count_cpw = sg.count_cpw;
-    opt.cap = opt.cap < sg.cap ? opt.cap : sg.cap;
+    return c;
   }
-  return c;
+  // (the records come through the vector path: through the scalar one the first pass was 1-2 % slower)
+  const WgSlot slot = (CLASS == kClassFirst ? ws.map_first
+                       : CLASS == kClassLevel0 ? ws.map_level0
+                       : CLASS == kClassSweep ? ws.map_sweep : ws.map_count)[blockIdx.x];
+  const Seg sg = ws.segs[slot.seg];
+  return seg_ctx_of(slot.seg, slot.group,
+                    CLASS == kClassFirst ? sg.groups_first
+                    : CLASS == kClassLevel0 ? sg.groups_level0
+                    : CLASS == kClassSweep ? sg.groups_sweep : sg.count_blocks,
+                    sg, geo, opt);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -488,8 +498,13 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   const float* gr = g + sc.elem_off;
   float* er = e + sc.elem_off;
   TopkRow* rowp = ws.rows + row;
-  const bool pred = use_guess && rowp->pred_valid != 0;  // workgroup-uniform
-  const uint32_t bg = rowp->b_guess;
+  // What this pass reads of the row's control block and of the previous step's list offsets was written by earlier
+  // launches and is the same for the whole workgroup: it comes through the scalar path, whose answers do not
+  // queue behind the chunk's loads (vector loads return in order).
+  const uint32_t* row_words = reinterpret_cast<const uint32_t*>(rowp);
+  static_assert(offsetof(TopkRow, pred_valid) == 0 && offsetof(TopkRow, b_guess) == 4, "words read below");
+  const bool pred = use_guess && table_u32(row_words, 0) != 0;  // workgroup-uniform
+  const uint32_t bg = table_u32(row_words, 1);
   const uint32_t d = geo.d;
   const uint32_t q0 = c * kChunk + wave * (kLeanRounds * 256);  // first coordinate of this wavefront's quarter
   const bool full = (c + 1) * static_cast<uint64_t>(kChunk) <= d;
@@ -510,8 +525,8 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
     if (lane < 32) bm[lane] = 0;
     const uint32_t* prev_off = ws.sel_off + sc.seloff_base;
     const int32_t* prev_idx = ws.idx + sc.list_base;
-    const uint32_t lo = prev_off[c];
-    const uint32_t hi = prev_off[c + 1] < geo.k ? prev_off[c + 1] : geo.k;
+    const uint32_t lo = table_u32(prev_off, c), hi_raw = table_u32(prev_off, c + 1);
+    const uint32_t hi = hi_raw < geo.k ? hi_raw : geo.k;
     for (uint32_t q = lo + lane; q < hi; q += 64) {
       const uint32_t jl = static_cast<uint32_t>(prev_idx[q]) - sc.coord_base - q0;
       if (jl < static_cast<uint32_t>(kLeanRounds * 256)) atomicOr(&bm[jl >> 5], 1u << (jl & 31u));
