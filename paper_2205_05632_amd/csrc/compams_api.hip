@@ -56,7 +56,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t total;
   // top-k
-  size_t rows, counters, hist0, hist1, hist1x, hist2, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_total,
+  size_t rows, counters, hist0, hist1, hist1x, hist2, xcur, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_total,
       wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_level0, map_sweep, map_count, map_emit, map_final, micro_list;
   // block-sign
   size_t offsets, chunk_block, acc, special, scales, bits;
@@ -151,6 +151,7 @@ Layout make_layout(const compams_config* c) {
     L.hist1 = take(n * kNB1 * 4);
     L.hist1x = take(n * kTracked * kNB1 * 4);
     L.hist2 = take(n * kNB2 * 4);
+    L.xcur = take(n * kSubLists * kCursorPitch * 4);
     L.chunk_rec = take(n * nc * 16);
     L.blk = take(n * kMaxCountBlocks * 8);
     L.sel_off = take(n * (nc + 1) * 4);
@@ -349,6 +350,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     t.hist1 = reinterpret_cast<uint32_t*>(w + lay.hist1);
     t.hist1x = reinterpret_cast<uint32_t*>(w + lay.hist1x);
     t.hist2 = reinterpret_cast<uint32_t*>(w + lay.hist2);
+    t.xcur = cfg->compressor == COMPAMS_TOPK ? reinterpret_cast<uint32_t*>(w + lay.xcur) : nullptr;
     t.chunk_rec = reinterpret_cast<uint4*>(w + lay.chunk_rec);
     t.blk = reinterpret_cast<uint2*>(w + lay.blk);
     t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);

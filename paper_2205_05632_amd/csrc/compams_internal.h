@@ -45,6 +45,13 @@ inline uint32_t count_chunks_per_block(uint32_t num_chunks) {
   return 32 * (m ? m : 1);
 }
 
+// One selection per row: the candidate list of a row is kept as kSubLists runs, chunk c of the row appending to run
+// c % kSubLists, each run with a cursor in a 128-byte line of its own.  Atomics to one address are performed one
+// after the other (about 3 ns apart on MI355X); a chunk's allocation every 8 ns through a single cursor queued long
+// enough to cost the first pass 9 of 352 us, and cursors that share a line were little better.
+constexpr uint32_t kSubLists = 8;
+constexpr uint32_t kCursorPitch = 32;  // words between the cursors of a row
+
 constexpr int kWireTile = 256;  // coordinate gaps per tile of a top-k message (one width per tile)
 
 // Where a row's selection reads its elements from after level 0.
@@ -58,7 +65,7 @@ enum : uint32_t {
 struct TopkRow {
   uint32_t pred_valid;  // the next first pass may emit candidates with level-0 bucket >= b_guess
   uint32_t b_guess;
-  uint32_t cursor;      // candidate entries allocated so far in this step
+  uint32_t cursor;      // candidate entries allocated so far in this step (a list kept as one run)
   uint32_t mode;        // kMode*
   uint32_t n_src;       // entries in the candidate list (kModeCand / kModeNeedB)
   uint32_t bstar;       // level-0 bucket that holds the k-th largest key
@@ -70,7 +77,9 @@ struct TopkRow {
   uint32_t take_all_ties;  // r == ties: no tie ranking needed
   uint32_t level1_done;    // bits 30..9 of the threshold key are known (prefix1 / need are valid)
   uint32_t ticket[4];      // "last workgroup of the row" counters of kernels 1..4; zero between launches
-  uint32_t pad[15];
+  uint32_t n_lists;        // runs of the candidate list: kSubLists (run s from entry s * (capacity / kSubLists) on), or 1
+  uint32_t n_sub[kSubLists];  // entries of each run (n_src in all)
+  uint32_t pad[6];
 };
 static_assert(sizeof(TopkRow) == 128, "TopkRow layout");
 
@@ -113,6 +122,7 @@ struct TopkWorkspace {
   uint32_t* hist1;      // n * kNB1
   uint32_t* hist1x;     // n * kTracked * kNB1 : level-1 histograms of the tracked buckets
   uint32_t* hist2;      // n * kNB2
+  uint32_t* xcur;       // n * kSubLists * kCursorPitch : the cursors of a row's runs (one selection per row only)
   uint4* chunk_rec;     // n * num_chunks : keys above tau, keys equal to tau, and the exclusive prefixes of both
                         //                  within the chunk's count block
   uint2* blk;           // n * kMaxCountBlocks : the two totals of every count block

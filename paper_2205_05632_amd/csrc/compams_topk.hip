@@ -32,9 +32,10 @@
 // applies the zeros when the caller asks for e).
 //
 // All routes give the same result; the guess only decides how many bytes move.  A candidate list is a
-// set of per-chunk segments, each in ascending coordinate order, placed by an integer atomic cursor:
-// their physical order varies from run to run but nothing that is output depends on it.  No
-// floating-point atomics are used anywhere.
+// set of per-chunk segments, each in ascending coordinate order, placed by integer atomic cursors (a row's
+// list is kept as eight runs with a cursor each, chunk c appending to run c % 8): their physical order
+// varies from run to run but nothing that is output depends on it.  No floating-point atomics are used
+// anywhere.
 
 #include "compams_device.h"
 #include "compams_internal.h"
@@ -458,6 +459,58 @@ __device__ __forceinline__ SegCtx seg_ctx(Geometry& geo, TopkOptions& opt, const
                     sg, geo, opt);
 }
 
+// The runs of a problem's candidate list (one, or kSubLists for a row of the one-selection-per-row form).
+struct ListRuns {
+  uint32_t lists, pitch;  // run s starts at entry s * pitch
+  uint32_t n[kSubLists];
+  uint32_t total;
+  bool fits;              // no run has outgrown its share of the capacity
+};
+
+// As the first pass left them: from the cursors.
+template <bool UNI>
+__device__ __forceinline__ ListRuns runs_from_cursors(const TopkWorkspace& ws, const TopkRow* rowp, uint32_t row,
+                                                      uint32_t cap) {
+  ListRuns L;
+  L.total = 0;
+  L.fits = true;
+  if (UNI) {
+    L.lists = kSubLists;
+    L.pitch = cap / kSubLists;
+    const uint32_t* cur = ws.xcur + static_cast<size_t>(row) * kSubLists * kCursorPitch;
+#pragma unroll
+    for (uint32_t s = 0; s < kSubLists; ++s) {
+      L.n[s] = cur[s * kCursorPitch];
+      L.total += L.n[s];
+      L.fits = L.fits && L.n[s] <= L.pitch;
+    }
+  } else {
+    L.lists = 1;
+    L.pitch = 0;
+    L.n[0] = rowp->cursor;
+#pragma unroll
+    for (uint32_t s = 1; s < kSubLists; ++s) L.n[s] = 0;
+    L.total = L.n[0];
+    L.fits = L.n[0] <= cap;
+  }
+  return L;
+}
+
+// As level 0 recorded them for the later sweeps.
+__device__ __forceinline__ ListRuns runs_of_row(const TopkRow* rowp, uint32_t cap) {
+  ListRuns L;
+  L.lists = rowp->n_lists;
+  L.pitch = cap / kSubLists;
+  L.total = 0;
+  L.fits = true;
+#pragma unroll
+  for (uint32_t s = 0; s < kSubLists; ++s) {
+    L.n[s] = s < L.lists ? rowp->n_sub[s] : 0u;
+    L.total += L.n[s];
+  }
+  return L;
+}
+
 // ---------------------------------------------------------------------------------------------
 // One selection per row, first pass without histograms.  A workgroup takes ONE chunk and ends; wavefront w takes
 // rounds 4w .. 4w+3 of it.  Measured on MI355X with plain streaming kernels of the same traffic (read g, read e,
@@ -582,15 +635,20 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
     before += static_cast<uint32_t>(w) < wave ? t : 0u;
     total += t;
   }
+  // the run this chunk appends to, its share of the capacity and its cursor
+  const uint32_t run = UNI ? c % kSubLists : 0u;
+  const uint32_t run_cap = UNI ? opt.cap / kSubLists : opt.cap;
+  const uint32_t run_base = run * run_cap;
   if (threadIdx.x == 0) {
-    const uint32_t off = total ? atomicAdd(&rowp->cursor, total) : 0u;
+    uint32_t* cur = UNI ? ws.xcur + (static_cast<size_t>(row) * kSubLists + run) * kCursorPitch : &rowp->cursor;
+    const uint32_t off = total ? atomicAdd(cur, total) : 0u;
     sh_off = off;
-    ws.desc[sc.chunk_base + c] = make_uint2(off, total);
+    ws.desc[sc.chunk_base + c] = make_uint2(run_base + off, total);
   }
   __syncthreads();
   const uint32_t off = sh_off;
-  if (cnt == 0 || off + total > opt.cap) return;  // otherwise the row's list has overflowed and will not be used
-  uint2* dst = ws.cand + sc.cand_base + off + before;
+  if (cnt == 0 || off + total > run_cap) return;  // otherwise the list has overflowed and will not be used
+  uint2* dst = ws.cand + sc.cand_base + run_base + off + before;
   if (cnt <= static_cast<uint32_t>(kStageQ)) {
     for (uint32_t q = lane; q < cnt; q += 64) dst[q] = stage[q];
   } else {
@@ -638,31 +696,36 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
   const uint32_t row = sc.seg;
   TopkRow* rowp = ws.rows + row;
   const uint32_t bg = rowp->b_guess;
-  const uint32_t cursor = rowp->cursor;  // written by the previous launch
-  const bool listed = use_guess && rowp->pred_valid != 0 && cursor >= geo.k && cursor <= opt.cap && !opt.force_dense;
+  const ListRuns runs = runs_from_cursors<UNI>(ws, rowp, row, opt.cap);  // written by the previous launch
+  const bool listed = use_guess && rowp->pred_valid != 0 && runs.total >= geo.k && runs.fits && !opt.force_dense;
   for (int b = threadIdx.x; b < kNB0; b += kWG) lh[b] = 0;
   for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWG) lh1[b] = 0;
   __syncthreads();
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   if (listed) {
-    const uint2* candr = ws.cand + sc.cand_base;
     const uint32_t step = sc.groups * kWG;
-    for (uint32_t q = sc.group * kWG + threadIdx.x; q < cursor; q += 4 * step) {  // four loads in flight
-      uint32_t key[4];
-      bool ok[4];
+#pragma unroll  // (a run-time index into the runs would put them into scratch memory)
+    for (uint32_t s = 0; s < kSubLists; ++s) {
+      if (s >= runs.lists) break;
+      const uint2* candr = ws.cand + sc.cand_base + static_cast<size_t>(s) * runs.pitch;
+      const uint32_t len = runs.n[s];
+      for (uint32_t q = sc.group * kWG + threadIdx.x; q < len; q += 4 * step) {  // four loads in flight
+        uint32_t key[4];
+        bool ok[4];
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        ok[w] = q + w * step < cursor;
-        key[w] = ok[w] ? key_of_bits(candr[q + w * step].y) : 0u;
-      }
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-        if (ok[w]) {
-          const uint32_t bucket = key[w] >> kL0Shift;
-          atomicAdd(&lh[bucket], 1u);
-          const uint32_t rel = bucket - bg;
-          if (rel < kTracked) atomicAdd(&lh1[rel * kNB1 + ((key[w] >> kL1Shift) & (kNB1 - 1))], 1u);
+        for (int w = 0; w < 4; ++w) {
+          ok[w] = q + w * step < len;
+          key[w] = ok[w] ? key_of_bits(candr[q + w * step].y) : 0u;
         }
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          if (ok[w]) {
+            const uint32_t bucket = key[w] >> kL0Shift;
+            atomicAdd(&lh[bucket], 1u);
+            const uint32_t rel = bucket - bg;
+            if (rel < kTracked) atomicAdd(&lh1[rel * kNB1 + ((key[w] >> kL1Shift) & (kNB1 - 1))], 1u);
+          }
+      }
     }
   } else {
     const float* er = e + sc.elem_off;
@@ -706,12 +769,22 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
     const uint32_t bstar = out2[0], above = out2[1];
     const uint32_t total = above + lh[bstar];  // entries with bucket >= bstar
     uint32_t mode, n_src, reads;
-    if (listed) { mode = kModeCand; n_src = cursor; reads = 0; }  // bstar >= bg: the list holds the k largest keys
+    if (listed) { mode = kModeCand; n_src = runs.total; reads = 0; }  // bstar >= bg: the list holds the k largest keys
     else if (total <= opt.cap && !opt.force_dense) { mode = kModeNeedB; n_src = total; reads = 1; }
     else { mode = kModeDense; n_src = 0; reads = 4; }
     rowp->mode = mode;
     rowp->n_src = n_src;
+    // the list's runs for the sweeps that follow: as the first pass left them, or the one run that the second
+    // read of the row is about to write; the cursors go back to zero for that read and for the next step
+    rowp->n_lists = listed ? runs.lists : 1u;
+#pragma unroll
+    for (uint32_t s = 0; s < kSubLists; ++s) rowp->n_sub[s] = listed ? runs.n[s] : (s == 0 ? n_src : 0u);
     rowp->cursor = 0;
+    if (UNI) {
+#pragma unroll
+      for (uint32_t s = 0; s < kSubLists; ++s)
+        ws.xcur[(static_cast<size_t>(row) * kSubLists + s) * kCursorPitch] = 0;
+    }
     rowp->bstar = bstar;
     rowp->need = geo.k - above;
     rowp->level1_done = 0;
@@ -805,9 +878,14 @@ __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e
       flush_chunk(stage, cnt, er, geo.d, c, bstar, rowp, candr, opt.cap, descr);
     }
   } else if (mode == kModeCand) {
-    const uint32_t n_src = rowp->n_src;
+    const ListRuns runs = runs_of_row(rowp, opt.cap);
     const uint32_t step = sc.groups * kWG;
-    for (uint32_t q = sc.group * kWG + threadIdx.x; q < n_src; q += step) visit(candr[q].y, true);
+#pragma unroll  // (a run-time index into the runs would put them into scratch memory)
+    for (uint32_t s = 0; s < kSubLists; ++s) {
+      if (s >= runs.lists) break;
+      const uint2* run = candr + static_cast<size_t>(s) * runs.pitch;
+      for (uint32_t q = sc.group * kWG + threadIdx.x; q < runs.n[s]; q += step) visit(run[q].y, true);
+    }
   } else {
     const uint32_t step = sc.groups * kWG * 4;
     for (uint32_t j = (sc.group * kWG + threadIdx.x) * 4; j < geo.d; j += step) {
@@ -861,9 +939,14 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
     }
   } else {
     const uint2* candr = ws.cand + sc.cand_base;
-    const uint32_t n_src = rowp->n_src;
+    const ListRuns runs = runs_of_row(rowp, opt.cap);
     const uint32_t step = sc.groups * kWG;
-    for (uint32_t q = sc.group * kWG + threadIdx.x; q < n_src; q += step) visit(candr[q].y, true);
+#pragma unroll  // (a run-time index into the runs would put them into scratch memory)
+    for (uint32_t s = 0; s < kSubLists; ++s) {
+      if (s >= runs.lists) break;
+      const uint2* run = candr + static_cast<size_t>(s) * runs.pitch;
+      for (uint32_t q = sc.group * kWG + threadIdx.x; q < runs.n[s]; q += step) visit(run[q].y, true);
+    }
   }
   __syncthreads();
   uint32_t* gh = ws.hist2 + static_cast<size_t>(row) * kNB2;

@@ -144,6 +144,35 @@ def test_topk_routes_agree_and_are_counted():
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
+@pytest.mark.parametrize("where", ["every eighth chunk", "every chunk"])
+def test_topk_candidates_all_in_one_run_of_the_list(where):
+    """The candidate list of a row is kept as eight runs, chunk c appending to run c % 8, each with an eighth of the
+    capacity.  With every large entry in chunks 0, 8, 16, ... that run outgrows its share although the list as a
+    whole would fit: the step has to notice and read the row once more, and the result is the same.  The same
+    entries spread over all chunks fit, and the steady-state steps take their candidates from the first pass."""
+    n, d, k = 2, 64 * 4096, 6000
+    rng = np.random.default_rng(8)
+    p = Pair(n, d, np.zeros(d, np.float32), B.TOPK, k=k)
+    p.gpu.set_option(B.OPT_CANDIDATE_CAP, 16000)      # an eighth: 2000 entries
+    chunks, per_chunk = (range(0, 64, 8), 1496) if where == "every eighth chunk" else (range(64), 187)
+    reads = []
+    for t in range(5):
+        g = (rng.standard_normal((n, d)) * 1e-3).astype(np.float32)
+        for c in chunks:
+            big = rng.standard_normal((n, per_chunk)) + 3.0 * np.sign(rng.standard_normal((n, per_chunk)))
+            g[:, c * 4096:c * 4096 + per_chunk] = big.astype(np.float32)
+        p.gpu.e.zero_()                                # keep the large entries where they are from step to step
+        p.cpu.set_state(e=np.zeros((n, d), np.float32))
+        p.step(g, 1e-3, label=f"{where} step {t}")
+        reads.append(p.gpu.compams_state("counters").cpu().numpy()[:, 0].copy())
+    reads = np.array(reads)
+    if where == "every eighth chunk":
+        assert (reads[1:] >= 1).all(), reads           # never from the first pass's list
+    else:
+        assert (reads[2:] == 0).all(), reads
+    p.close()
+
+
 def test_topk_guess_that_is_too_high_falls_back():
     """Gradients that shrink by 100x make the carried-over bucket too high: the step must notice and re-read."""
     n, d, k = 2, 100000, 1000
