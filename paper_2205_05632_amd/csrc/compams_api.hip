@@ -168,12 +168,13 @@ Layout make_layout(const compams_config* c) {
   } else if (c->compressor == COMPAMS_TOPK_BLOCKS) {
     const std::vector<BlockShape> shapes = block_shapes(c);
     const size_t M = shapes.size(), S = n * M;
-    size_t k = 0, chunks = 0, caps = 0, wg_first = 0, wg_level0 = 0, wg_sweep = 0, wg_count = 0, wg_emit = 0, micro = 0;
+    size_t k = 0, chunks = 0, caps = 0, wg_first = 0, wg_level0 = 0, wg_sweep = 0, wg_count = 0, wg_emit = 0, micro = 0, big = 0;
     uint32_t cap_max = 0;
     for (const BlockShape& b : shapes) {
       k += b.k; chunks += b.nc; caps += b.cap; cap_max = std::max(cap_max, b.cap);
       wg_first += b.groups_first; wg_level0 += b.groups_level0; wg_sweep += b.groups_sweep; wg_count += b.count_blocks; wg_emit += b.emit_slots;
       micro += b.micro;
+      big += b.nc >= kSubListMinChunks ? 1 : 0;  // blocks whose candidate lists are kept as several runs
     }
     L.k_total = k;
     L.cap_alloc = cap_max;
@@ -194,6 +195,7 @@ Layout make_layout(const compams_config* c) {
     L.hist1 = take(S * kNB1 * 4);
     L.hist1x = take(S * kTracked * kNB1 * 4);
     L.hist2 = take(S * kNB2 * 4);
+    L.xcur = take(n * big * kSubLists * kCursorPitch * 4);
     L.chunk_rec = take(n * chunks * 16);
     L.blk = take(S * kMaxCountBlocks * 8);
     L.sel_off = take(n * (chunks + M) * 4);
@@ -350,7 +352,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     t.hist1 = reinterpret_cast<uint32_t*>(w + lay.hist1);
     t.hist1x = reinterpret_cast<uint32_t*>(w + lay.hist1x);
     t.hist2 = reinterpret_cast<uint32_t*>(w + lay.hist2);
-    t.xcur = cfg->compressor == COMPAMS_TOPK ? reinterpret_cast<uint32_t*>(w + lay.xcur) : nullptr;
+    t.xcur = reinterpret_cast<uint32_t*>(w + lay.xcur);
     t.chunk_rec = reinterpret_cast<uint4*>(w + lay.chunk_rec);
     t.blk = reinterpret_cast<uint2*>(w + lay.blk);
     t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);
@@ -381,6 +383,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
         const size_t M = shapes.size();
         uint64_t chunks = 0, caps = 0;
         for (const BlockShape& b : shapes) { chunks += b.nc; caps += b.cap; }
+        uint32_t cursor_sets = 0;
         segs.resize(static_cast<size_t>(cfg->n) * M);
         for (int64_t i = 0; i < cfg->n; ++i) {
           uint64_t c_at = 0, cap_at = 0, k_at = 0;
@@ -399,6 +402,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
             sg.groups_first = sh.groups_first; sg.groups_sweep = sh.groups_sweep; sg.count_blocks = sh.count_blocks;
             sg.micro = sh.micro;
             sg.groups_level0 = sh.groups_level0;
+            sg.cursor_set = sh.nc >= kSubListMinChunks ? cursor_sets++ : kNoCursorSet;
             if (sh.micro) micro.push_back(si);
             for (uint32_t q = 0; q < sh.groups_first; ++q) m_first.push_back(WgSlot{si, q});  // in address order
             for (uint32_t q = 0; q < sh.groups_level0; ++q) m_level0.push_back(WgSlot{si, q});

@@ -45,12 +45,16 @@ inline uint32_t count_chunks_per_block(uint32_t num_chunks) {
   return 32 * (m ? m : 1);
 }
 
-// One selection per row: the candidate list of a row is kept as kSubLists runs, chunk c of the row appending to run
+// The candidate list of a selection problem is kept as kSubLists runs, chunk c of the problem appending to run
 // c % kSubLists, each run with a cursor in a 128-byte line of its own.  Atomics to one address are performed one
 // after the other (about 3 ns apart on MI355X); a chunk's allocation every 8 ns through a single cursor queued long
 // enough to cost the first pass 9 of 352 us, and cursors that share a line were little better.
 constexpr uint32_t kSubLists = 8;
-constexpr uint32_t kCursorPitch = 32;  // words between the cursors of a row
+constexpr uint32_t kCursorPitch = 32;  // words between the cursors of a problem
+// Top-k inside every block: a block of fewer chunks than this keeps its list as one run (its share of the
+// allocations is small, and an eighth of a small capacity would overflow for nothing).
+constexpr uint32_t kSubListMinChunks = 64;
+constexpr uint32_t kNoCursorSet = 0xffffffffu;
 
 constexpr int kWireTile = 256;  // coordinate gaps per tile of a top-k message (one width per tile)
 
@@ -100,7 +104,7 @@ struct Seg {
                                                       // one per chunk)
   uint32_t micro;        // at most kMicroCoords coordinates: one wavefront of the first pass does the whole selection
   uint32_t groups_level0;
-  uint32_t pad[1];
+  uint32_t cursor_set;   // which set of kSubLists cursors the problem's list uses, or kNoCursorSet: one run, rowp->cursor
 };
 static_assert(sizeof(Seg) == 88 || sizeof(Seg) == 96, "Seg layout");
 
@@ -122,7 +126,8 @@ struct TopkWorkspace {
   uint32_t* hist1;      // n * kNB1
   uint32_t* hist1x;     // n * kTracked * kNB1 : level-1 histograms of the tracked buckets
   uint32_t* hist2;      // n * kNB2
-  uint32_t* xcur;       // n * kSubLists * kCursorPitch : the cursors of a row's runs (one selection per row only)
+  uint32_t* xcur;       // sets of kSubLists cursors, kCursorPitch words apart: one set per row, or per segment of at
+                        // least kSubListMinChunks chunks
   uint4* chunk_rec;     // n * num_chunks : keys above tau, keys equal to tau, and the exclusive prefixes of both
                         //                  within the chunk's count block
   uint2* blk;           // n * kMaxCountBlocks : the two totals of every count block

@@ -409,6 +409,7 @@ struct SegCtx {
   int64_t elem_off;
   uint32_t coord_base;
   size_t chunk_base, seloff_base, cand_base, list_base;
+  uint32_t cursor_set;  // see Seg
 };
 
 // The context of workgroup `group` of segment `seg` in a flat launch.
@@ -424,6 +425,7 @@ __device__ __forceinline__ SegCtx seg_ctx_of(uint32_t seg, uint32_t group, uint3
   c.seloff_base = sg.seloff_base;
   c.cand_base = sg.cand_base;
   c.list_base = sg.list_base;
+  c.cursor_set = sg.cursor_set;
   geo.d = sg.d;
   geo.k = sg.k;
   geo.num_chunks = sg.num_chunks;
@@ -445,6 +447,7 @@ __device__ __forceinline__ SegCtx seg_ctx(Geometry& geo, TopkOptions& opt, const
     c.seloff_base = static_cast<size_t>(c.seg) * (geo.num_chunks + 1);
     c.cand_base = static_cast<size_t>(c.seg) * opt.cap;
     c.list_base = static_cast<size_t>(c.seg) * geo.k;
+    c.cursor_set = c.seg;
     return c;
   }
   // (the records come through the vector path: through the scalar one the first pass was 1-2 % slower)
@@ -468,16 +471,15 @@ struct ListRuns {
 };
 
 // As the first pass left them: from the cursors.
-template <bool UNI>
-__device__ __forceinline__ ListRuns runs_from_cursors(const TopkWorkspace& ws, const TopkRow* rowp, uint32_t row,
+__device__ __forceinline__ ListRuns runs_from_cursors(const TopkWorkspace& ws, const TopkRow* rowp, uint32_t cursor_set,
                                                       uint32_t cap) {
   ListRuns L;
   L.total = 0;
   L.fits = true;
-  if (UNI) {
+  if (cursor_set != kNoCursorSet) {  // uniform
     L.lists = kSubLists;
     L.pitch = cap / kSubLists;
-    const uint32_t* cur = ws.xcur + static_cast<size_t>(row) * kSubLists * kCursorPitch;
+    const uint32_t* cur = ws.xcur + static_cast<size_t>(cursor_set) * kSubLists * kCursorPitch;
 #pragma unroll
     for (uint32_t s = 0; s < kSubLists; ++s) {
       L.n[s] = cur[s * kCursorPitch];
@@ -636,11 +638,13 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
     total += t;
   }
   // the run this chunk appends to, its share of the capacity and its cursor
-  const uint32_t run = UNI ? c % kSubLists : 0u;
-  const uint32_t run_cap = UNI ? opt.cap / kSubLists : opt.cap;
+  const bool runs = sc.cursor_set != kNoCursorSet;  // workgroup-uniform
+  const uint32_t run = runs ? c % kSubLists : 0u;
+  const uint32_t run_cap = runs ? opt.cap / kSubLists : opt.cap;
   const uint32_t run_base = run * run_cap;
   if (threadIdx.x == 0) {
-    uint32_t* cur = UNI ? ws.xcur + (static_cast<size_t>(row) * kSubLists + run) * kCursorPitch : &rowp->cursor;
+    uint32_t* cur =
+        runs ? ws.xcur + (static_cast<size_t>(sc.cursor_set) * kSubLists + run) * kCursorPitch : &rowp->cursor;
     const uint32_t off = total ? atomicAdd(cur, total) : 0u;
     sh_off = off;
     ws.desc[sc.chunk_base + c] = make_uint2(run_base + off, total);
@@ -696,7 +700,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
   const uint32_t row = sc.seg;
   TopkRow* rowp = ws.rows + row;
   const uint32_t bg = rowp->b_guess;
-  const ListRuns runs = runs_from_cursors<UNI>(ws, rowp, row, opt.cap);  // written by the previous launch
+  const ListRuns runs = runs_from_cursors(ws, rowp, sc.cursor_set, opt.cap);  // written by the previous launch
   const bool listed = use_guess && rowp->pred_valid != 0 && runs.total >= geo.k && runs.fits && !opt.force_dense;
   for (int b = threadIdx.x; b < kNB0; b += kWG) lh[b] = 0;
   for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWG) lh1[b] = 0;
@@ -780,10 +784,10 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
 #pragma unroll
     for (uint32_t s = 0; s < kSubLists; ++s) rowp->n_sub[s] = listed ? runs.n[s] : (s == 0 ? n_src : 0u);
     rowp->cursor = 0;
-    if (UNI) {
+    if (sc.cursor_set != kNoCursorSet) {
 #pragma unroll
       for (uint32_t s = 0; s < kSubLists; ++s)
-        ws.xcur[(static_cast<size_t>(row) * kSubLists + s) * kCursorPitch] = 0;
+        ws.xcur[(static_cast<size_t>(sc.cursor_set) * kSubLists + s) * kCursorPitch] = 0;
     }
     rowp->bstar = bstar;
     rowp->need = geo.k - above;
