@@ -515,3 +515,46 @@ def test_keep_state_resumes_bit_exactly():
     for s in ("theta", "m", "v", "vhat", "e", "last_idx"):
         assert torch.equal(a.compams_state(s), b.compams_state(s)), s
     a.close(); b.close()
+
+
+# ------------------------------------------------------------------------------------------- long runs
+@pytest.mark.parametrize("compressor", ["topk", "blocksign", "topk_blocks"])
+def test_hundred_steps_with_a_drifting_gradient_scale(compressor):
+    """A long run whose gradient scale decays, now and then jumps by a decade either way, and whose rows differ in
+    scale: the carried-over threshold guesses go stale again and again, the pending residual updates are applied a
+    hundred times, and everything still has to agree with the oracle after every tenth step (the lists and sign
+    words at every step they are looked at, the state bit for bit at the end)."""
+    n, d = 4, 3 * 4096 * 5 + 8
+    rng = np.random.default_rng(77)
+    theta0 = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    off = np.array([0, 4096 * 4, 4096 * 4 + 1000, 4096 * 11, d], dtype=np.int64)
+    if compressor == "topk_blocks":
+        from test_gpu_topk_blocks import BlockPair
+        p = BlockPair(n, d, off, np.array([160, 10, 290, 200], dtype=np.int64), theta0)
+    elif compressor == "topk":
+        p = Pair(n, d, theta0, B.TOPK, k=600)
+    else:
+        p = Pair(n, d, theta0, B.BLOCKSIGN, block_offsets=off)
+    scale = 1.0
+    rows = (10.0 ** rng.uniform(-1, 1, (n, 1)))
+    rereads = 0
+    for t in range(100):
+        scale *= 0.97
+        if t % 13 == 12:
+            scale *= 10.0 ** rng.choice([-1.0, 1.0])
+        g = (rng.standard_normal((n, d)) * scale * rows).astype(np.float32)
+        look = t % 10 == 9
+        if compressor == "topk_blocks":
+            p.step(g)
+            if look:
+                p.compare(f"step {t}", with_e=(t == 99))
+        else:
+            p.step(g, 1e-3, check=look, label=f"{compressor} step {t}", with_e=(t == 99))
+        if compressor != "blocksign":
+            torch.cuda.synchronize()
+            rereads += int((p.gpu.compams_state("counters").cpu().numpy().reshape(-1, 4)[:, 0] > 0).sum())
+    if compressor == "topk":
+        assert all(p.exact.values()), p.exact
+    if compressor != "blocksign":
+        assert rereads > 0, "the jumps in scale should have made some guesses fail"
+    p.close()
