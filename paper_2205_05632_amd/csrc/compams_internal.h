@@ -51,8 +51,9 @@ inline uint32_t count_chunks_per_block(uint32_t num_chunks) {
 // enough to cost the first pass 9 of 352 us, and cursors that share a line were little better.
 constexpr uint32_t kSubLists = 8;
 constexpr uint32_t kCursorPitch = 32;  // words between the cursors of a problem
-// Top-k inside every block: a block of fewer chunks than this keeps its list as one run (its share of the
-// allocations is small, and an eighth of a small capacity would overflow for nothing).
+// A problem (row or block) of fewer chunks than this keeps its list as one run: its allocations are few, and
+// with a handful of chunks the runs would be of very different lengths and an eighth of the capacity each
+// would overflow for nothing.
 constexpr uint32_t kSubListMinChunks = 64;
 constexpr uint32_t kNoCursorSet = 0xffffffffu;
 

@@ -447,7 +447,7 @@ __device__ __forceinline__ SegCtx seg_ctx(Geometry& geo, TopkOptions& opt, const
     c.seloff_base = static_cast<size_t>(c.seg) * (geo.num_chunks + 1);
     c.cand_base = static_cast<size_t>(c.seg) * opt.cap;
     c.list_base = static_cast<size_t>(c.seg) * geo.k;
-    c.cursor_set = c.seg;
+    c.cursor_set = geo.num_chunks >= kSubListMinChunks ? c.seg : kNoCursorSet;  // short rows keep one run
     return c;
   }
   // (the records come through the vector path: through the scalar one the first pass was 1-2 % slower)
