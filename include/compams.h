@@ -105,13 +105,13 @@ int compams_init(const compams_config* cfg, compams_ctx** out);
  * Top-k ties are broken towards the larger |x| and then the lower index, with |x| ordered by the fp32
  * bit pattern without its sign bit; the selected indices come out ascending per worker.  Block-sign
  * uses sign(x) = -1 iff x < 0 and the exactly summed block L1 norm.  The average adds the workers'
- * compressed gradients in the order 0..n-1 in fp32 and divides by n. *
+ * compressed gradients in the order 0..n-1 in fp32 and divides by n.
  * The error line of Algorithm 2 (e <- x - C(x)) may be left pending when the step returns: e then still
  * holds the corrected gradient x where the update has not been applied (top-k: at the selected
- * coordinates; block-sign: everywhere), and the next
- * step applies it while it reads e.  compams_state(COMPAMS_STATE_E) and compams_destroy() apply what is
- * pending first (one kernel on the last step's stream); do not read or write the e buffer between steps by
- * any other route.  Every other result of the step is final when the stream has passed it.
+ * coordinates; block-sign: everywhere), and the next step applies it while it reads e.
+ * compams_state(COMPAMS_STATE_E) and compams_destroy() apply what is pending first (one kernel on the last
+ * step's stream); do not read or write the e buffer between steps by any other route.  Every other result
+ * of the step is final when the stream has passed it.
  * Stream capture: the call only enqueues kernel launches on hip_stream (no allocation, no synchronisation, no
  * memset or copy node; profiling must be off), so it may be recorded into a HIP graph.  Which kernels are
  * enqueued depends on the context's state at that moment (the first step of a context differs from the later
@@ -158,7 +158,10 @@ int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* co
  * selection takes and exist for tests of the rarely taken routes and for ablation measurements. */
 enum {
   COMPAMS_OPT_CANDIDATE_CAP = 0, /* candidate-list capacity per worker, 0 .. the capacity the workspace was sized
-                                    for (min(d, 8k + 65536)); a list that would not fit is not built */
+                                    for (min(d, 8k + 65536)); a list that would not fit is not built.  Rows of 64
+                                    chunks (262144 coordinates) and more keep the list as eight runs of an eighth
+                                    of the capacity each, filled by every eighth chunk of the row: a run that would
+                                    not fit counts as a list that would not fit */
   COMPAMS_OPT_PREDICT = 1,       /* 1 (default): the first pass of a step already writes the candidate list, using
                                     the previous step's threshold bucket as a guess that is verified afterwards */
   COMPAMS_OPT_FORCE_DENSE = 2    /* 1: never build a candidate list; every selection pass reads the whole row */
@@ -167,9 +170,9 @@ int compams_set_option(compams_ctx* ctx, int option, int64_t value);
 
 /* Optional per-kernel timing.  enable = 1: compams_step() brackets every kernel with HIP events on the
  * step's stream (about 3 us per kernel of extra time); enable = 2: only the kernel that moves most of the
- * step's bytes is bracketed; enable = 0: off.  compams_profile_read() waits for the recorded events, then fills names[i] (static
- * strings) and ms[i] (total milliseconds since the last reset) and launches[i] for up to cap kernels,
- * returns how many kernels there are through *count, and resets the totals. */
+ * step's bytes is bracketed; enable = 0: off.  compams_profile_read() waits for the recorded events, then
+ * fills names[i] (static strings), ms[i] (total milliseconds since the last reset) and launches[i] for up to
+ * cap kernels, returns how many kernels there are through *count, and resets the totals. */
 int compams_profile_enable(compams_ctx* ctx, int enable);
 int compams_profile_read(compams_ctx* ctx, int cap, const char** names, double* ms, int64_t* launches, int* count);
 
@@ -213,9 +216,8 @@ const char* compams_strerror(int status);
  *   status_out: DEVICE, n words: 0 if message i was well formed, else bit 0 = not a message of this kind and
  *   size or a tile width outside 1..31, bit 1 = length differs from `words`, bit 2 = a coordinate at or
  *   beyond d.  Malformed input never makes the library read outside [message, message + stride_words); the
- *   outputs for such a message are
- *   unspecified.  Uses the context's workspace: not concurrent with compams_step or another decode on the
- *   same context. */
+ *   outputs for such a message are unspecified.  Uses the context's workspace: not concurrent with
+ *   compams_step or another decode on the same context. */
 size_t compams_wire_capacity(const compams_config* cfg);
 int compams_encode(compams_ctx* ctx, uint32_t* messages, int64_t stride_words, uint32_t* words_out, void* hip_stream);
 int compams_decode(compams_ctx* ctx, const uint32_t* messages, int64_t stride_words, const uint32_t* words,
