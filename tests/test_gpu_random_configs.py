@@ -2,6 +2,8 @@
 gradient values are all drawn from the seed, and every step of the HIP library (through the C ABI) is compared
 with the oracle to the bar of the other parity tests -- index sets, values, sign words and scales bit for bit,
 floats within 1e-5.  The fixed cases elsewhere aim at known corners; this sweep is for the ones nobody thought of."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -65,7 +67,8 @@ def draw_config(seed):
     return cfg, rng
 
 
-@pytest.mark.parametrize("seed", range(120))
+# COMPAMS_RANDOM_CONFIGS=<count> widens the sweep for an occasional longer run
+@pytest.mark.parametrize("seed", range(int(os.environ.get("COMPAMS_RANDOM_CONFIGS", "120"))))
 def test_random_configuration(seed):
     cfg, rng = draw_config(seed)
     n, d = cfg["n"], cfg["d"]
