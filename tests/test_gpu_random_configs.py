@@ -39,6 +39,9 @@ def draw_config(seed):
     n = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 16, 33]))
     d = int(10.0 ** (rng.uniform(0.0, 5.3) if rng.random() < 0.35 else rng.uniform(3.6, 5.3)))  # most span chunks
     d = max(1, min(d, 200000 // n * 4))
+    if rng.random() < 0.15:     # long rows: 64 chunks and more, where the candidate list is kept as eight runs
+        n = int(rng.choice([1, 2, 3, 4]))
+        d = int(rng.integers(64 * 4096, 150 * 4096))
     compressor = ["topk", "blocksign", "topk_blocks", "none"][int(rng.choice(4, p=[0.35, 0.3, 0.3, 0.05]))]
     if compressor == "topk_blocks" and d < 8:
         d = 8 + 4 * int(rng.integers(0, 8))
