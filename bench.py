@@ -9,6 +9,10 @@ average and the AMSGrad update, on gradients that already sit in HBM.  Prints ON
 The default workload is the one the headline metric is quoted on: n = 16 workers, d = 11 181 642
 (ResNet-18-shaped), top-k with k/d = 1 %.  Gradients are seeded synthetic data (a distinct pre-generated
 buffer per step, so the residuals evolve as they would in training).
+
+`value` is the headline workload's.  The line also carries, under "workloads", a short run (10 timed steps, two
+gradient buffers) of every other workload of the build and, under "eps_out", the headline workload with epsilon
+outside the square root: figures for the record, none of them enters `value`.
 """
 import argparse
 import json
@@ -21,6 +25,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+OTHER_WORKLOADS = ["r18_topk01", "r18_blocksign", "r18_none", "r18_topk1_layers", "r50_topk1", "gpt2s_topk01",
+                   "gpt2s_blocksign"]
 
 
 def algorithmic_bytes(w, comp):
@@ -38,7 +44,7 @@ def algorithmic_bytes(w, comp):
 
 def dominant_kernel(comp):
     """(kernel slot name, algorithmic bytes per launch as a function of n, d)."""
-    if comp == "topk":
+    if comp in ("topk", "topk_blocks"):
         return "topk_pass_a", lambda n, d: 12 * n * d      # read g, read e, write x in place of e
     if comp == "blocksign":
         return "bs_pass1", lambda n, d: 12 * n * d
@@ -57,6 +63,112 @@ def load_traffic(workload, kernel):
     return None
 
 
+class Run:
+    """One workload set up on the GPU: context, pre-generated gradients, and the timed loop."""
+
+    def __init__(self, name, steps, warmup, grad_buffers=0, eps_mode=None, predict=True, force_dense=False):
+        import torch
+        from paper_2205_05632_amd import binding as B
+        from paper_2205_05632_amd import workloads as W
+        self.torch, self.B, self.W = torch, B, W
+        self.dev = torch.device("cuda:0")
+        self.w = w = W.get(name)
+        self.steps, self.warmup = steps, warmup
+        self.blocks_topk = w.compressor == "topk_blocks"
+        self.comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE, "topk_blocks": B.TOPK_BLOCKS}[w.compressor]
+        self.eps_mode = B.EPS_IN_SQRT if eps_mode is None else eps_mode
+        self.ctx = B.Compams(w.n, w.d, W.theta0(w, self.dev), compressor=self.comp, k=w.k,
+                             block_offsets=w.block_offsets(), block_k=w.block_k() if self.blocks_topk else None,
+                             eps_mode=self.eps_mode, device=self.dev)
+        if not predict:
+            self.ctx.set_option(B.OPT_PREDICT, 0)
+        if force_dense:
+            self.ctx.set_option(B.OPT_FORCE_DENSE, 1)
+        total = warmup + steps
+        scale = W.coordinate_scale(w, self.dev)
+        nbuf = total if grad_buffers <= 0 else min(total, grad_buffers)
+        pool = [W.gradients(w, t, device=self.dev, ld=self.ctx.ld, scale=scale) for t in range(nbuf)]
+        self.grads = [pool[t % nbuf] for t in range(total)]
+        del scale
+        torch.cuda.synchronize()
+
+    def timed(self, event_mode=2, stride=4, settle_each_step=False):
+        """Warm-up, then the timed steps between two synchronisations.  event_mode 2 brackets the dominant kernel
+        with HIP events on the step's stream on every `stride`-th step (their cost is part of the measured time),
+        1 brackets every kernel of every step, 0 none."""
+        torch, ctx, w = self.torch, self.ctx, self.w
+        for t in range(self.warmup):
+            ctx.compams_step(self.grads[t], w.lr)
+        stride = 1 if event_mode == 1 else max(1, stride)
+        ctx.profile_enable(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(self.warmup, self.warmup + self.steps):
+            if event_mode:
+                ctx.profile_enable(event_mode if (t - self.warmup) % stride == 0 else 0)  # host-side switch only
+            ctx.compams_step(self.grads[t], w.lr)
+            if settle_each_step:
+                ctx.compams_state("e")
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        prof = ctx.profile_read()
+        ctx.profile_enable(0)
+        sec = t1 - t0
+        bmin = algorithmic_bytes(w, w.compressor)
+        res = {"ms_per_step": sec / self.steps * 1e3, "steps_per_s": self.steps / sec, "prof": prof,
+               "algorithmic_bytes_per_step": bmin, "hbm_gbps": bmin / (sec / self.steps) / 1e9}
+        res["hbm_frac_of_peak"] = res["hbm_gbps"] / HBM_PEAK_GBPS
+        kname, kbytes = dominant_kernel(w.compressor)
+        res["roofline"] = None
+        if prof and kname in prof:
+            k_ms, k_launches = prof[kname]
+            k_avg_s = k_ms / k_launches * 1e-3
+            k_gbps = kbytes(w.n, w.d) / k_avg_s / 1e9
+            res["roofline"] = {"bound": "hbm", "kernel": kname, "achieved": k_gbps, "peak": HBM_PEAK_GBPS,
+                               "unit": "GB/s", "frac": k_gbps / HBM_PEAK_GBPS, "traffic": load_traffic(w.name, kname),
+                               "traffic_source": f"profiles/traffic_{w.name}.txt (rocprofv3 --pmc FETCH_SIZE / "
+                                                 "WRITE_SIZE runs of this command, committed; not measured in this run)",
+                               "avg_launch_us": k_avg_s * 1e6, "launches_timed": k_launches,
+                               "algorithmic_bytes_per_launch": kbytes(w.n, w.d)}
+        return res
+
+    def counters(self):
+        B = self.B
+        if self.comp not in (B.TOPK, B.TOPK_BLOCKS):
+            return None
+        c = self.ctx.compams_state("counters").cpu()
+        if self.comp == B.TOPK:
+            return {"dense_rereads_per_row_last_step": c[:, 0].tolist(),
+                    "candidates_per_row_last_step": c[:, 1].tolist()}
+        return {"selection_problems": int(c.shape[0]),   # one selection problem per (worker, block): totals
+                "problems_without_candidate_list_last_step": int((c[:, 0] == 4).sum()),
+                "problems_with_one_reread_last_step": int((c[:, 0] == 1).sum()),
+                "candidates_last_step": int(c[:, 1].sum())}
+
+    def close(self):
+        self.ctx.close()
+        self.grads = None
+        self.torch.cuda.empty_cache()
+
+
+def brief(name, eps_mode=None, stride=4):
+    """The short run of a workload for the record: 10 timed steps after 5, two gradient buffers."""
+    r = Run(name, steps=10, warmup=5, grad_buffers=2, eps_mode=eps_mode)
+    m = r.timed(event_mode=2, stride=stride)
+    c = r.counters()
+    out = {"ms_per_step": m["ms_per_step"], "steps_per_s": m["steps_per_s"], "hbm_frac_of_peak": m["hbm_frac_of_peak"],
+           "algorithmic_bytes_per_step": m["algorithmic_bytes_per_step"], "n": r.w.n, "d": r.w.d,
+           "compressor": r.w.compressor, "steps": 10, "warmup": 5, "grad_buffers": 2}
+    if m["roofline"]:
+        out["dominant_kernel"] = m["roofline"]["kernel"]
+        out["dominant_kernel_us"] = m["roofline"]["avg_launch_us"]
+        out["dominant_kernel_frac"] = m["roofline"]["frac"]
+    if c and "dense_rereads_per_row_last_step" in c:
+        out["dense_rereads_last_step"] = int(sum(c["dense_rereads_per_row_last_step"]))
+    r.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,13 +176,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="r18_topk1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="leave out the short runs of the other workloads and of the other epsilon form")
+    ap.add_argument("--eps-out", action="store_true", help="epsilon outside the square root for the main run")
     ap.add_argument("--cpu-steps", type=int, default=10, help="oracle steps timed for the cpu_baseline leg")
     ap.add_argument("--kernels", action="store_true",
                     help="bracket every kernel with events and print the per-kernel table to stderr")
     ap.add_argument("--no-predict", action="store_true", help="ablation: re-read the row instead of guessing")
     ap.add_argument("--force-dense", action="store_true", help="ablation: no candidate lists at all")
-    ap.add_argument("--compose-blocks", action="store_true",
-                    help="top-k per layer tensor as one context per tensor, stepped one after the other")
     ap.add_argument("--grad-buffers", type=int, default=0,
                     help="how many distinct gradient buffers to cycle through (0: one per step)")
     ap.add_argument("--settle-each-step", action="store_true",
@@ -92,82 +205,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    w = W.get(args.workload)
-    blocks_topk = w.compressor == "topk_blocks"
-    # --compose-blocks: one context per layer tensor stepped one after the other (no per-kernel events, no codec)
-    per_block = blocks_topk and args.compose_blocks
-    if per_block:
-        comp = None
-        ctx = B.CompamsBlockTopk(w.n, w.d, W.theta0(w, dev), w.block_offsets(), w.block_k(), device=dev)
-        args.no_kernel_events = True
-    else:
-        comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE, "topk_blocks": B.TOPK_BLOCKS}[w.compressor]
-        ctx = B.Compams(w.n, w.d, W.theta0(w, dev), compressor=comp, k=w.k, block_offsets=w.block_offsets(),
-                        block_k=w.block_k() if blocks_topk else None, device=dev)
-    if args.no_predict and not per_block:
-        ctx.set_option(B.OPT_PREDICT, 0)
-    if args.force_dense and not per_block:
-        ctx.set_option(B.OPT_FORCE_DENSE, 1)
-
-    total = args.warmup + args.steps
-    scale = W.coordinate_scale(w, dev)
-    nbuf = total if args.grad_buffers <= 0 else min(total, args.grad_buffers)
-    pool = [W.gradients(w, t, device=dev, ld=ctx.ld, scale=scale) for t in range(nbuf)]
-    grads = [pool[t % nbuf] for t in range(total)]
-    torch.cuda.synchronize()
-
-    for t in range(args.warmup):
-        ctx.compams_step(grads[t], w.lr)
-    # timed region: the dominant kernel is bracketed by HIP events on the step's stream (their cost is part of
-    # the measured time); --kernels brackets every kernel instead, which costs a few microseconds per kernel
+    run = Run(args.workload, args.steps, args.warmup, grad_buffers=args.grad_buffers,
+              eps_mode=B.EPS_OUT_SQRT if args.eps_out else B.EPS_IN_SQRT, predict=not args.no_predict,
+              force_dense=args.force_dense)
+    w, ctx, comp, grads = run.w, run.ctx, run.comp, run.grads
     event_mode = 0 if args.no_kernel_events else (1 if args.kernels else 2)
-    stride = 1 if args.kernels else max(1, args.event_stride)
-    if not per_block:
-        ctx.profile_enable(0)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(args.warmup, total):
-        if event_mode and stride > 1:
-            ctx.profile_enable(event_mode if (t - args.warmup) % stride == 0 else 0)  # host-side switch only
-        elif t == args.warmup and not per_block:
-            ctx.profile_enable(event_mode)
-        ctx.compams_step(grads[t], w.lr)
-        if args.settle_each_step:
-            ctx.compams_state("e")
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    prof = {} if per_block else ctx.profile_read()
-    if not per_block:
-        ctx.profile_enable(0)
-    sec = t1 - t0
-    ms_per_step = sec / args.steps * 1e3
-    steps_per_s = args.steps / sec
-
-    bmin = algorithmic_bytes(w, w.compressor)
-    kname, kbytes = dominant_kernel("topk" if blocks_topk else w.compressor)
-    roofline = None
-    kernel_sum_ms = None
-    if prof:
-        k_ms, k_launches = prof[kname]
-        k_avg_s = k_ms / k_launches * 1e-3
-        k_gbps = kbytes(w.n, w.d) / k_avg_s / 1e9
-        kernel_sum_ms = sum(ms / cnt for ms, cnt in prof.values())
-        roofline = {"bound": "hbm", "kernel": kname, "achieved": k_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": k_gbps / HBM_PEAK_GBPS, "traffic": load_traffic(w.name, kname),
-                    "avg_launch_us": k_avg_s * 1e6, "launches_timed": k_launches,
-                    "algorithmic_bytes_per_launch": kbytes(w.n, w.d)}
-
-    counters = None
-    if comp in (B.TOPK, B.TOPK_BLOCKS):
-        c = ctx.compams_state("counters").cpu()
-        if comp == B.TOPK:
-            counters = {"dense_rereads_per_row_last_step": c[:, 0].tolist(),
-                        "candidates_per_row_last_step": c[:, 1].tolist()}
-        else:   # one selection problem per (worker, block): totals
-            counters = {"selection_problems": int(c.shape[0]),
-                        "problems_without_candidate_list_last_step": int((c[:, 0] == 4).sum()),
-                        "problems_with_one_reread_last_step": int((c[:, 0] == 1).sum()),
-                        "candidates_last_step": int(c[:, 1].sum())}
+    main_res = run.timed(event_mode=event_mode, stride=args.event_stride, settle_each_step=args.settle_each_step)
+    prof = main_res["prof"]
+    kernel_sum_ms = sum(ms / cnt for ms, cnt in prof.values()) if prof else None
+    counters = run.counters()
     if args.kernels:
         for name, (ms, cnt) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
             print(f"  {name:16s} {ms / cnt * 1e3:9.1f} us/launch  x{cnt}", file=sys.stderr)
@@ -200,7 +246,7 @@ def main():
     # the last step's messages on the wire: sizes (32 bits per word, the accounting of the paper's experiments
     # section) and the time to pack and unpack them; not part of `value`
     wire = None
-    if comp is not None and comp != B.NONE:
+    if comp != B.NONE:
         reps = 20
         msgs, words = ctx.compams_encode()      # warm-up: first launches load the kernels
         ctx.compams_decode(msgs, words)
@@ -228,7 +274,8 @@ def main():
         from oracle import compams_oracle as O
         ocomp = {"topk": O.TOPK, "blocksign": O.BLOCKSIGN, "none": O.NONE, "topk_blocks": O.TOPK_BLOCKS}[w.compressor]
         orc = O.Oracle(w.n, w.d, W.theta0(w, dev).cpu().numpy(), compressor=ocomp, k=w.k,
-                       block_offsets=w.block_offsets(), block_k=w.block_k() if blocks_topk else None)
+                       block_offsets=w.block_offsets(), block_k=w.block_k() if run.blocks_topk else None,
+                       eps_mode=run.eps_mode)
         host = [grads[t][:, : w.d].cpu().contiguous().numpy() for t in range(args.cpu_steps)]
         c0 = time.perf_counter()
         for g in host:
@@ -237,29 +284,44 @@ def main():
         cpu = {"value": args.cpu_steps / (c1 - c0), "unit": "steps/s", "cores": 1, "kind": "oracle",
                "sample": f"first {args.cpu_steps} steps of the same workload and inputs, single thread"}
         orc.close()
+        del host
+    run.close()
+    del grads
+
+    others, eps_out = None, None
+    if not args.no_others:
+        eps_out = brief(args.workload, eps_mode=B.EPS_IN_SQRT if args.eps_out else B.EPS_OUT_SQRT,
+                        stride=args.event_stride)
+        eps_out["eps_mode"] = "in_sqrt" if args.eps_out else "out_sqrt"
+        others = {}
+        for name in OTHER_WORKLOADS:
+            if name != args.workload:
+                others[name] = brief(name, stride=args.event_stride)
 
     out = {
         "metric": "compressed-AMSGrad steps/sec and HBM GB/s (% of peak), n=16, d=11.2M, top-k 1%",
-        "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": main_res["steps_per_s"], "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "d": w.d, "compressor": w.compressor, "k": w.k,
                    "num_blocks": (len(w.block_offsets()) - 1) if w.compressor == "blocksign" else 0,
+                   "eps_mode": "out_sqrt" if args.eps_out else "in_sqrt",
                    "predict": not args.no_predict, "force_dense": args.force_dense},
-        "hbm_gbps": bmin / (sec / args.steps) / 1e9,
-        "hbm_frac_of_peak": bmin / (sec / args.steps) / 1e9 / HBM_PEAK_GBPS,
-        "algorithmic_bytes_per_step": bmin,
+        "hbm_gbps": main_res["hbm_gbps"],
+        "hbm_frac_of_peak": main_res["hbm_frac_of_peak"],
+        "algorithmic_bytes_per_step": main_res["algorithmic_bytes_per_step"],
         "step_ms_median": step_ms_median, "step_ms_min": step_ms_min,
-        "copy_kernel_gbps": copy_gbps, "hbm_frac_of_copy_kernel": bmin / (sec / args.steps) / 1e9 / copy_gbps,
+        "copy_kernel_gbps": copy_gbps, "hbm_frac_of_copy_kernel": main_res["hbm_gbps"] / copy_gbps,
         "kernel_ms_per_step": kernel_sum_ms,
-        "roofline": roofline,
+        "roofline": main_res["roofline"],
         "kernels_us_per_launch": {k_: v_[0] / v_[1] * 1e3 for k_, v_ in prof.items()},
         "topk_counters": counters,
         "wire": wire,
         "cpu_baseline": cpu,
+        "eps_out": eps_out,
+        "workloads": others,
     }
     print(json.dumps(out))
-    ctx.close()
 
 
 if __name__ == "__main__":

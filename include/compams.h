@@ -1,7 +1,7 @@
 /* compams.h -- C ABI of the COMP-AMS optimizer step for MI355X (gfx950).
  *
  * One call of compams_step() is one iteration of the paper's Algorithm 2
- * ("Distributed COMP-AMS with error feedback"): every one of n workers adds its
+ * (the distributed method with error feedback): every one of n workers adds its
  * error accumulator to its gradient, compresses the sum, keeps what the
  * compressor dropped as the new error, and the server averages the n compressed
  * gradients and applies an AMSGrad update (Algorithm 1's moment and parameter
@@ -19,6 +19,16 @@
  *   - compams_step() only enqueues work on the given stream; it does not
  *     synchronise with the host and takes no data-dependent decision on the
  *     host.  One context may be driven by one host thread at a time.
+ *   - A context is one sequence of steps.  Calls that enqueue work (the step
+ *     calls, compams_encode, compams_decode) may come on different streams: a
+ *     call on another stream than the previous one first makes its stream wait,
+ *     on the device, for everything the context has enqueued so far (an event
+ *     made at compams_init; the host does not wait).  Ordering the caller's own
+ *     work (filling g, reading state) against those streams stays the caller's,
+ *     and so does the order of graph replays: a stream under capture runs
+ *     nothing and takes no part in this.
+ *   - The device that was current at compams_init() must be current at every
+ *     later call on the context (COMPAMS_BAD_STATE otherwise).
  */
 #ifndef COMPAMS_H
 #define COMPAMS_H
@@ -59,7 +69,9 @@ enum {
   COMPAMS_BAD_ALIGNMENT = -2,       /* a device pointer is not 16-byte aligned, or ld is not a multiple of 4 */
   COMPAMS_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < compams_workspace_size() */
   COMPAMS_HIP_ERROR = -4,           /* a HIP runtime call failed */
-  COMPAMS_BAD_STATE = -5            /* query does not apply to this context's compressor */
+  COMPAMS_BAD_STATE = -5            /* the call does not apply to this context: wrong compressor for the query,
+                                       another device is current, or an earlier step failed with COMPAMS_HIP_ERROR
+                                       half-way (the context can then only be destroyed) */
 };
 
 typedef struct compams_config {
@@ -90,7 +102,10 @@ typedef struct compams_config {
 } compams_config;
 
 /* Bytes of device workspace this configuration needs (0 on an invalid configuration).
- * Host-only; reads n, d, compressor, k, num_blocks (and block_offsets, block_k for top-k per block). */
+ * Host-only; reads n, d, compressor, k, num_blocks (and block_offsets, block_k for top-k per block).
+ * The workspace holds what the workers "send" in Algorithm 2 (the kept coordinates and values of Definition 1,
+ * the sign words and block means of Definition 2) and the tables of the selection; the paper's own state
+ * (theta, m, v, vhat, e_i: Algorithm 2's input and initialisation lines) is never kept there. */
 size_t compams_workspace_size(const compams_config* cfg);
 
 /* Validates cfg, copies it, lays out the workspace, uploads the block offsets and, unless
@@ -120,7 +135,11 @@ int compams_init(const compams_config* cfg, compams_ctx** out);
  * the pending error line (compams_state(COMPAMS_STATE_E), compams_server_step) if replays are to follow. */
 int compams_step(compams_ctx* ctx, const float* g, float lr, void* hip_stream);
 
-/* What compams_state() can hand out.  Counts are in elements of the listed type. */
+/* What compams_state() can hand out.  Counts are in elements of the listed type.
+ * 0..4 are the state of Algorithm 2: its parameter theta_t, the moments m_t, v_t and the running maximum vhat_t
+ * of its server lines, and the workers' error accumulators e_{t,i} (all zero after the initialisation line,
+ * theta_1 the caller's).  5..8 are what the workers sent in the last step (the send line of Algorithm 2, in the
+ * form of Definition 1 or Definition 2).  The rest describes how the last selection went. */
 enum {
   COMPAMS_STATE_THETA = 0,          /* float[d] */
   COMPAMS_STATE_M = 1,              /* float[d] */
@@ -134,8 +153,12 @@ enum {
   COMPAMS_STATE_LAST_THRESHOLD = 9, /* top-k: uint32[n], magnitude key of the k-th largest entry (top-k per block:
                                        uint32[n*M], worker-major; likewise the count and the counters below) */
   COMPAMS_STATE_COUNTERS = 10,      /* uint32[n*COMPAMS_COUNTERS_PER_ROW], see below */
-  COMPAMS_STATE_LAST_COUNT_GT = 11  /* top-k: uint32[n], selected entries strictly above the threshold key (the
+  COMPAMS_STATE_LAST_COUNT_GT = 11, /* top-k: uint32[n], selected entries strictly above the threshold key (the
                                        other k - that many are ties, taken in coordinate order) */
+  COMPAMS_STATE_PENDING = 12        /* a host-side answer, no pointer: *dev_ptr = NULL and *count = 1 if the error
+                                       line of the last step is still pending (see compams_step), else 0.  A step
+                                       recorded into a HIP graph while the answer was 1 must be replayed only while
+                                       it is 1 (and the other way round) */
 };
 
 /* Per-worker counters of the last step (top-k), for tests and profiling reports. */
@@ -176,14 +199,16 @@ int compams_set_option(compams_ctx* ctx, int option, int64_t value);
 int compams_profile_enable(compams_ctx* ctx, int enable);
 int compams_profile_read(compams_ctx* ctx, int cap, const char** names, double* ms, int64_t* launches, int* count);
 
-/* Frees the context (host memory and HIP events only; device buffers stay the caller's). */
+/* Ends the sequence of steps: applies a pending error line (so that e holds e_{t+1,i} of Algorithm 2, as
+ * compams_state(COMPAMS_STATE_E) would), waits for it, and frees the context (host memory and HIP events only;
+ * device buffers stay the caller's). */
 int compams_destroy(compams_ctx* ctx);
 
 /* Static description of a status code. */
 const char* compams_strerror(int status);
 
 /* ---- The workers' messages on the wire ------------------------------------------------------------------
- * What a worker sends to the server in its "send" line of Algorithm 2, as one contiguous sequence of 32-bit
+ * What a worker sends to the server in its send line of Algorithm 2, as one contiguous sequence of 32-bit
  * little-endian words per worker.  The paper fixes only the accounting (experiments section: 32 bits per
  * transmitted float); the layout below is this library's.
  *
@@ -234,7 +259,8 @@ int compams_decode(compams_ctx* ctx, const uint32_t* messages, int64_t stride_wo
  * compams_server_step: the server's lines from n packed messages (laid out as for compams_decode; message i
  *   is worker i in the fixed order of the average): unpacks them into the workspace, adds them in that order,
  *   divides by n and applies the AMSGrad lines with learning rate lr.  Reads no gradient; touches e only to
- *   apply a residual update of this same context that is still pending.  status_out: as for compams_decode; a
+ *   apply a residual update of this same context that is still pending (on the stream of the step that left
+ *   it; this call's stream then waits for that one on the device).  status_out: as for compams_decode; a
  *   message that is not well formed still contributes whatever it unpacks to (never read out of bounds), so
  *   check status_out.
  * compams_worker_step + compams_encode on one context followed by compams_server_step on a context of the

@@ -20,7 +20,8 @@ def build(force: bool = False, sanitize: bool = False) -> str:
     if (not force and os.path.exists(lib)
             and os.path.getmtime(lib) >= os.path.getmtime(SRC)):
         return lib
-    cmd = ["g++"] + FLAGS + (["-fsanitize=address,undefined", "-g"] if sanitize else []) \
+    # the sanitizer build stops at the first finding (no recovery), so that a test run under it fails loudly
+    cmd = ["g++"] + FLAGS + (["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-g"] if sanitize else []) \
         + [SRC, "-o", lib]
     subprocess.run(cmd, check=True)
     return lib

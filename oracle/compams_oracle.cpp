@@ -390,8 +390,8 @@ double oracle_exact_abs_sum(const float* x, int64_t len) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Wire format of one worker's message (what "send the compressed gradient to the server" in the worker
-// lines of Algorithm 2 puts on the wire), as a sequence of 32-bit words.  The paper fixes only the
+// Wire format of one worker's message (what the send line among the worker lines of Algorithm 2 puts on the
+// wire), as a sequence of 32-bit words.  The paper fixes only the
 // accounting (32 bits per transmitted float, experiments section); the layout is this library's own and
 // is stated in full in the public header.  Written here bit by bit, straight from that statement.
 //

@@ -23,7 +23,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = build_oracle.build()
+        # COMPAMS_ORACLE_SANITIZE=1: the AddressSanitizer / UBSan build of the same source (the process must have
+        # been started with the sanitizer runtime preloaded)
+        path = build_oracle.build(sanitize=os.environ.get("COMPAMS_ORACLE_SANITIZE") == "1")
         L = ctypes.CDLL(path)
         f32p = ctypes.POINTER(ctypes.c_float)
         i64p = ctypes.POINTER(ctypes.c_int64)

@@ -21,7 +21,7 @@ OPT_CANDIDATE_CAP, OPT_PREDICT, OPT_FORCE_DENSE = 0, 1, 2
 COUNTERS_PER_ROW = 4
 
 STATE = {"theta": 0, "m": 1, "v": 2, "vhat": 3, "e": 4, "last_idx": 5, "last_val": 6, "last_signbits": 7,
-         "last_scales": 8, "last_threshold": 9, "counters": 10, "last_count_gt": 11}
+         "last_scales": 8, "last_threshold": 9, "counters": 10, "last_count_gt": 11, "pending": 12}
 _STATE_DTYPE = {"last_idx": torch.int32, "last_signbits": torch.int32, "last_threshold": torch.int32,
                 "counters": torch.int32, "last_count_gt": torch.int32}
 
@@ -186,11 +186,13 @@ class Compams:
         with torch.cuda.device(self.device):
             _check(lib().compams_step(self._h, g.data_ptr(), lr, _current_stream_handle()), "compams_step")
 
-    def compams_state(self, name: str) -> torch.Tensor:
-        """A torch view (no copy) of a state tensor or of the last step's messages."""
+    def compams_state(self, name: str):
+        """A torch view (no copy) of a state tensor or of the last step's messages ("pending": a bool)."""
         p = ctypes.c_void_p()
         cnt = ctypes.c_int64()
         _check(lib().compams_state(self._h, STATE[name], ctypes.byref(p), ctypes.byref(cnt)), "compams_state")
+        if name == "pending":   # a host-side answer: is the last step's error line still to be applied?
+            return bool(cnt.value)
         dt = _STATE_DTYPE.get(name, torch.float32)
         t = _tensor_from_ptr(p.value, cnt.value, dt, self.device, keepalive=self)
         if name == "e":
@@ -280,75 +282,6 @@ class Compams:
             torch.cuda.synchronize(self.device)
             lib().compams_destroy(self._h)
             self._h = None
-
-    def __del__(self):
-        try:
-            self.close()
-        except Exception:
-            pass
-
-
-class CompamsBlockTopk:
-    """Top-k applied to every block (layer tensor) on its own: block b keeps block_k[b] coordinates per worker.
-
-    The average and the AMSGrad lines act coordinate by coordinate, so the step falls apart into one
-    independent top-k step per block on the block's slice of g, e, theta, m, v, vhat.  This class lays one
-    context over every slice of shared buffers and steps them one after the other on the same stream (five
-    launches per block: not fused across blocks).  Block offsets must be multiples of 4 (16-byte aligned
-    slices)."""
-
-    def __init__(self, n: int, d: int, theta0: torch.Tensor, block_offsets, block_k, beta1: float = 0.9,
-                 beta2: float = 0.999, eps: float = 1e-8, eps_mode: int = EPS_IN_SQRT, ld: Optional[int] = None,
-                 device="cuda:0"):
-        self.n, self.d = int(n), int(d)
-        self.off = np.ascontiguousarray(block_offsets, dtype=np.int64)
-        self.kb = np.ascontiguousarray(block_k, dtype=np.int64)
-        if self.off[0] != 0 or self.off[-1] != d or self.kb.size != self.off.size - 1:
-            raise CompamsError("block offsets must run from 0 to d, with one count per block")
-        if (self.off[:-1] % 4).any():
-            raise CompamsError("block offsets must be multiples of 4 (16-byte aligned slices)")
-        self.k = int(self.kb.sum())
-        self.ld = padded_ld(d) if ld is None else int(ld)
-        self.device = torch.device(device)
-        f32 = dict(dtype=torch.float32, device=self.device)
-        self.theta = theta0.detach().to(**f32).clone().contiguous()
-        self.m = torch.empty(self.d, **f32)
-        self.v = torch.empty(self.d, **f32)
-        self.vhat = torch.empty(self.d, **f32)
-        self.e = torch.zeros((self.n, self.ld), **f32)
-        self.blocks = []
-        for b in range(self.kb.size):
-            lo, hi = int(self.off[b]), int(self.off[b + 1])
-            views = {"theta": self.theta[lo:hi], "m": self.m[lo:hi], "v": self.v[lo:hi], "vhat": self.vhat[lo:hi],
-                     "e": self.e[:, lo:hi]}
-            self.blocks.append(Compams(n, hi - lo, None, compressor=TOPK, k=int(self.kb[b]), beta1=beta1, beta2=beta2,
-                                       eps=eps, eps_mode=eps_mode, ld=self.ld, device=device, views=views))
-
-    def compams_step(self, g: torch.Tensor, lr: float):
-        assert g.dtype == torch.float32 and g.is_cuda and g.is_contiguous() and g.shape == (self.n, self.ld)
-        with torch.cuda.device(self.device):
-            stream = _current_stream_handle()
-            for b, c in enumerate(self.blocks):
-                _check(lib().compams_step(c._h, g.data_ptr() + 4 * int(self.off[b]), lr, stream), "compams_step")
-
-    def compams_state(self, name: str) -> torch.Tensor:
-        if name in ("theta", "m", "v", "vhat"):
-            return getattr(self, name)
-        if name == "e":
-            for c in self.blocks:     # asking a block for its residuals applies what is pending there
-                p, cnt = ctypes.c_void_p(), ctypes.c_int64()
-                _check(lib().compams_state(c._h, STATE["e"], ctypes.byref(p), ctypes.byref(cnt)), "compams_state")
-            return self.e[:, : self.d]
-        if name == "last_idx":
-            return torch.cat([c.compams_state("last_idx") + int(self.off[b]) for b, c in enumerate(self.blocks)], dim=1)
-        if name == "last_val":
-            return torch.cat([c.compams_state("last_val") for c in self.blocks], dim=1)
-        raise CompamsError(f"no such state for per-block top-k: {name}")
-
-    def close(self):
-        for c in self.blocks:
-            c.close()
-        self.blocks = []
 
     def __del__(self):
         try:

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -266,21 +267,127 @@ struct compams_ctx {
   int64_t steps;
   bool clear_pending;      // the last step's residual update is still to be applied: top-k: e holds x at the
                            // selected coordinates; block-sign (general layouts): e holds x everywhere
-  hipStream_t last_stream; // stream of the last step
+  hipStream_t last_stream; // stream of the last call that enqueued work of this context
+  bool enqueued;           // last_stream is meaningful: some call has enqueued work there
+  hipEvent_t order_event;  // made at init (no timing): orders a new stream behind last_stream, device-side
+  bool failed;             // a step's launches failed half-way: e and the workspace are in no defined state
   bool profiling;
   Launcher launcher;
 };
+
+// One context is a single sequence of steps: each reads what the one before left in theta, m, v, vhat, e and the
+// workspace.  When a call arrives on another stream than the previous one, the new stream is made to wait (on the
+// device; the host does not) for everything the context has enqueued so far.
+static bool is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &st) != hipSuccess) {
+    (void)hipGetLastError();  // e.g. the null stream while another stream is being captured: not capturing itself
+    return false;
+  }
+  return st == hipStreamCaptureStatusActive;
+}
+
+// A stream that is being captured into a graph runs nothing now: no event is recorded for it and it does not
+// become the context's last stream (whoever replays the graph orders the replays).
+static hipError_t order_after_last(compams_ctx* ctx, hipStream_t stream) {
+  if (!ctx->enqueued || ctx->last_stream == stream || is_capturing(stream)) return hipSuccess;
+  hipError_t err = hipEventRecord(ctx->order_event, ctx->last_stream);
+  if (err == hipSuccess) err = hipStreamWaitEvent(stream, ctx->order_event, 0);
+  return err;
+}
+
+static void free_ctx(compams_ctx* ctx) {
+  if (ctx->order_event) (void)hipEventDestroy(ctx->order_event);
+  Launcher& L = ctx->launcher;
+  for (int s = 0; s < kNumSlots; ++s)
+    for (const Launcher::Pair& p : L.pending[s]) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  for (const Launcher::Pair& p : L.pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+  delete ctx;
+}
+
+static void note_enqueued(compams_ctx* ctx, hipStream_t stream) {
+  if (is_capturing(stream)) return;
+  ctx->last_stream = stream;
+  ctx->enqueued = true;
+}
 
 // Top-k leaves the zeroing of the residual at the selected coordinates to the next step's first pass.
 // Before anybody else looks at e, the zeros are written for real (on the stream of the last step).
 static hipError_t settle_residuals(compams_ctx* ctx) {
   if (!ctx->clear_pending) return hipSuccess;
+  if (ctx->failed) return hipErrorInvalidValue;  // the lists or scales it would apply were never completed
   hipError_t err = hipSuccess;
   if (is_topk(ctx->cfg.compressor)) err = topk_apply_clear(ctx->geo, ctx->tk, ctx->cfg.e, ctx->last_stream);
   else if (ctx->cfg.compressor == COMPAMS_BLOCKSIGN)
     err = blocksign_apply_residual(ctx->geo, ctx->bs, ctx->cfg.e, ctx->last_stream);
   if (err == hipSuccess) ctx->clear_pending = false;
   return err;
+}
+
+// Points a context's top-k tables into a workspace laid out by make_layout (one selection per row: no segment
+// tables), with the default options.
+static void bind_topk_workspace(compams_ctx* ctx, char* w) {
+  const Layout& lay = ctx->lay;
+  TopkWorkspace& t = ctx->tk;
+  t.rows = reinterpret_cast<TopkRow*>(w + lay.rows);
+  t.counters = reinterpret_cast<uint32_t*>(w + lay.counters);
+  t.hist0 = reinterpret_cast<uint32_t*>(w + lay.hist0);
+  t.hist1 = reinterpret_cast<uint32_t*>(w + lay.hist1);
+  t.hist1x = reinterpret_cast<uint32_t*>(w + lay.hist1x);
+  t.hist2 = reinterpret_cast<uint32_t*>(w + lay.hist2);
+  t.xcur = reinterpret_cast<uint32_t*>(w + lay.xcur);
+  t.chunk_rec = reinterpret_cast<uint4*>(w + lay.chunk_rec);
+  t.blk = reinterpret_cast<uint2*>(w + lay.blk);
+  t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);
+  t.count_gt = reinterpret_cast<uint32_t*>(w + lay.count_gt);
+  t.wire_total = reinterpret_cast<uint32_t*>(w + lay.wire_total);
+  t.wire_tile_off = reinterpret_cast<uint32_t*>(w + lay.wire_tile_off);
+  t.wire_tile_sum = reinterpret_cast<uint32_t*>(w + lay.wire_tile_sum);
+  t.desc = reinterpret_cast<uint2*>(w + lay.desc);
+  t.cand = reinterpret_cast<uint2*>(w + lay.cand);
+  t.idx = reinterpret_cast<int32_t*>(w + lay.idx);
+  t.val = reinterpret_cast<float*>(w + lay.val);
+  t.tau = reinterpret_cast<uint32_t*>(w + lay.tau);
+  t.sel_off_srv = reinterpret_cast<uint32_t*>(w + lay.sel_off_srv);
+  t.segs = nullptr;
+  t.map_first = t.map_level0 = t.map_sweep = t.map_count = t.map_emit = t.map_final = nullptr;
+  t.micro_list = nullptr;
+  ctx->tkopt.cap = lay.cap_alloc;
+  ctx->tkopt.predict = 1;
+  ctx->tkopt.force_dense = 0;
+}
+
+// The shape of the launches, from a validated configuration and its layout.
+static void set_geometry(compams_ctx* ctx) {
+  const compams_config& c = ctx->cfg;
+  Geometry& geo = ctx->geo;
+  geo.n = static_cast<uint32_t>(c.n);
+  geo.d = static_cast<uint32_t>(c.d);
+  geo.ld = c.ld;
+  geo.num_chunks = ctx->lay.num_chunks;
+  geo.k = is_topk(c.compressor) ? static_cast<uint32_t>(c.k) : 0;
+  geo.num_blocks = c.compressor == COMPAMS_BLOCKSIGN ? static_cast<uint32_t>(c.num_blocks) : 0;
+  geo.words = ctx->lay.words;
+  geo.count_cpw = count_chunks_per_block(ctx->lay.num_chunks);
+}
+
+// What compams_init checks of a configuration before it looks at the workspace.
+static int check_config(const compams_config* cfg) {
+  if (!basic_valid(cfg)) return COMPAMS_INVALID_ARG;
+  if (cfg->ld < cfg->d) return COMPAMS_INVALID_ARG;
+  if (cfg->ld % 4 != 0) return COMPAMS_BAD_ALIGNMENT;
+  if (cfg->eps_mode != COMPAMS_EPS_IN_SQRT && cfg->eps_mode != COMPAMS_EPS_OUT_SQRT) return COMPAMS_INVALID_ARG;
+  if (!cfg->theta || !cfg->m || !cfg->v || !cfg->vhat) return COMPAMS_INVALID_ARG;
+  if (cfg->compressor != COMPAMS_NONE && !cfg->e) return COMPAMS_INVALID_ARG;
+  auto misaligned = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; };
+  if (misaligned(cfg->theta, 16) || misaligned(cfg->m, 16) || misaligned(cfg->v, 16) || misaligned(cfg->vhat, 16) ||
+      (cfg->e && misaligned(cfg->e, 16)))
+    return COMPAMS_BAD_ALIGNMENT;
+  if (cfg->compressor == COMPAMS_BLOCKSIGN && !blocks_valid(cfg)) return COMPAMS_INVALID_ARG;
+  if (cfg->compressor == COMPAMS_TOPK_BLOCKS)
+    for (int64_t b = 0; b < cfg->num_blocks; ++b)
+      if (cfg->block_offsets[b] % 4 != 0) return COMPAMS_BAD_ALIGNMENT;  // every block starts on 16 bytes
+  return COMPAMS_OK;
 }
 
 extern "C" {
@@ -295,21 +402,10 @@ size_t compams_workspace_size(const compams_config* cfg) {
 }
 
 int compams_init(const compams_config* cfg, compams_ctx** out) {
-  if (!out || !basic_valid(cfg)) return COMPAMS_INVALID_ARG;
-  if (cfg->ld < cfg->d) return COMPAMS_INVALID_ARG;
-  if (cfg->ld % 4 != 0) return COMPAMS_BAD_ALIGNMENT;
-  if (cfg->eps_mode != COMPAMS_EPS_IN_SQRT && cfg->eps_mode != COMPAMS_EPS_OUT_SQRT) return COMPAMS_INVALID_ARG;
-  if (!cfg->theta || !cfg->m || !cfg->v || !cfg->vhat) return COMPAMS_INVALID_ARG;
-  if (cfg->compressor != COMPAMS_NONE && !cfg->e) return COMPAMS_INVALID_ARG;
+  if (!out) return COMPAMS_INVALID_ARG;
+  if (const int bad = check_config(cfg)) return bad;
   if (!cfg->workspace) return COMPAMS_INVALID_ARG;
-  auto misaligned = [](const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; };
-  if (misaligned(cfg->theta, 16) || misaligned(cfg->m, 16) || misaligned(cfg->v, 16) || misaligned(cfg->vhat, 16) ||
-      (cfg->e && misaligned(cfg->e, 16)) || misaligned(cfg->workspace, 256))
-    return COMPAMS_BAD_ALIGNMENT;
-  if (cfg->compressor == COMPAMS_BLOCKSIGN && !blocks_valid(cfg)) return COMPAMS_INVALID_ARG;
-  if (cfg->compressor == COMPAMS_TOPK_BLOCKS)
-    for (int64_t b = 0; b < cfg->num_blocks; ++b)
-      if (cfg->block_offsets[b] % 4 != 0) return COMPAMS_BAD_ALIGNMENT;  // every block starts on 16 bytes
+  if (reinterpret_cast<uintptr_t>(cfg->workspace) % 256 != 0) return COMPAMS_BAD_ALIGNMENT;
   Layout lay;
   try {
     lay = make_layout(cfg);
@@ -328,48 +424,25 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
   ctx->steps = 0;
   ctx->clear_pending = false;
   ctx->last_stream = nullptr;
+  ctx->enqueued = false;
+  ctx->failed = false;
   ctx->profiling = false;
-  if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return COMPAMS_HIP_ERROR; }
-  Geometry& geo = ctx->geo;
-  geo.n = static_cast<uint32_t>(cfg->n);
-  geo.d = static_cast<uint32_t>(cfg->d);
-  geo.ld = cfg->ld;
-  geo.num_chunks = lay.num_chunks;
-  geo.k = is_topk(cfg->compressor) ? static_cast<uint32_t>(ctx->cfg.k) : 0;
-  geo.num_blocks = cfg->compressor == COMPAMS_BLOCKSIGN ? static_cast<uint32_t>(cfg->num_blocks) : 0;
-  geo.words = lay.words;
-  geo.count_cpw = count_chunks_per_block(lay.num_chunks);
+  ctx->order_event = nullptr;
+  if (hipGetDevice(&ctx->device) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->order_event, hipEventDisableTiming) != hipSuccess) {
+    free_ctx(ctx);
+    return COMPAMS_HIP_ERROR;
+  }
+  set_geometry(ctx);
+  const Geometry& geo = ctx->geo;
   char* w = static_cast<char*>(cfg->workspace);
   hipStream_t s0 = nullptr;
   hipError_t err = hipSuccess;
   auto ok = [&](hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; };
 
   if (is_topk(cfg->compressor)) {
+    bind_topk_workspace(ctx, w);
     TopkWorkspace& t = ctx->tk;
-    t.rows = reinterpret_cast<TopkRow*>(w + lay.rows);
-    t.counters = reinterpret_cast<uint32_t*>(w + lay.counters);
-    t.hist0 = reinterpret_cast<uint32_t*>(w + lay.hist0);
-    t.hist1 = reinterpret_cast<uint32_t*>(w + lay.hist1);
-    t.hist1x = reinterpret_cast<uint32_t*>(w + lay.hist1x);
-    t.hist2 = reinterpret_cast<uint32_t*>(w + lay.hist2);
-    t.xcur = reinterpret_cast<uint32_t*>(w + lay.xcur);
-    t.chunk_rec = reinterpret_cast<uint4*>(w + lay.chunk_rec);
-    t.blk = reinterpret_cast<uint2*>(w + lay.blk);
-    t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);
-    t.count_gt = reinterpret_cast<uint32_t*>(w + lay.count_gt);
-    t.wire_total = reinterpret_cast<uint32_t*>(w + lay.wire_total);
-    t.wire_tile_off = reinterpret_cast<uint32_t*>(w + lay.wire_tile_off);
-    t.wire_tile_sum = reinterpret_cast<uint32_t*>(w + lay.wire_tile_sum);
-    t.desc = reinterpret_cast<uint2*>(w + lay.desc);
-    t.cand = reinterpret_cast<uint2*>(w + lay.cand);
-    t.idx = reinterpret_cast<int32_t*>(w + lay.idx);
-    t.val = reinterpret_cast<float*>(w + lay.val);
-    t.tau = reinterpret_cast<uint32_t*>(w + lay.tau);
-    ctx->tkopt.cap = lay.cap_alloc;
-    ctx->tkopt.predict = 1;
-    ctx->tkopt.force_dense = 0;
-    t.sel_off_srv = reinterpret_cast<uint32_t*>(w + lay.sel_off_srv);
-    t.segs = nullptr; t.map_first = t.map_level0 = t.map_sweep = t.map_count = t.map_emit = t.map_final = nullptr; t.micro_list = nullptr;
     // control blocks, counters, histograms and chunk tables start at zero; lists need no initial value
     ok(fill_u32(reinterpret_cast<uint32_t*>(w), lay.cand / 4, 0u, s0));
     ok(fill_u32(reinterpret_cast<uint32_t*>(w + lay.idx), (lay.total - lay.idx) / 4, 0u, s0));
@@ -418,7 +491,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
         for (size_t q = 0; q < micro.size(); q += kWaves)
           m_first.push_back(WgSlot{kMicroFlag | static_cast<uint32_t>(q),
                                    static_cast<uint32_t>(std::min<size_t>(kWaves, micro.size() - q))});
-      } catch (...) { delete ctx; return COMPAMS_HIP_ERROR; }
+      } catch (...) { free_ctx(ctx); return COMPAMS_HIP_ERROR; }
       ok(hipStreamSynchronize(s0));
       ok(hipMemcpy(w + lay.segs, segs.data(), segs.size() * sizeof(Seg), hipMemcpyHostToDevice));
       ok(hipMemcpy(w + lay.map_first, m_first.data(), m_first.size() * sizeof(WgSlot), hipMemcpyHostToDevice));
@@ -454,7 +527,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     try {
       off32.resize(static_cast<size_t>(cfg->num_blocks) + 1);
       cb.resize(lay.num_chunks);
-    } catch (...) { delete ctx; return COMPAMS_HIP_ERROR; }
+    } catch (...) { free_ctx(ctx); return COMPAMS_HIP_ERROR; }
     for (int64_t i = 0; i <= cfg->num_blocks; ++i) off32[static_cast<size_t>(i)] = static_cast<uint32_t>(cfg->block_offsets[i]);
     uint32_t blk = 0;
     for (uint32_t c = 0; c < lay.num_chunks; ++c) {
@@ -474,7 +547,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
     ok(fill_rows_f32(cfg->vhat, 1, 0, geo.d, 0.0f, s0));
   }
   ok(hipStreamSynchronize(s0));
-  if (err != hipSuccess) { delete ctx; return COMPAMS_HIP_ERROR; }
+  if (err != hipSuccess) { free_ctx(ctx); return COMPAMS_HIP_ERROR; }
   *out = ctx;
   return COMPAMS_OK;
 }
@@ -493,6 +566,14 @@ static AmsParams ams_params(const compams_config& c, float lr) {
   return ap;
 }
 
+// A call that enqueues work of the context: not after a failed step, and on the device the context was made on.
+static int usable(const compams_ctx* ctx) {
+  if (ctx->failed) return COMPAMS_BAD_STATE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return COMPAMS_HIP_ERROR;
+  return dev == ctx->device ? COMPAMS_OK : COMPAMS_BAD_STATE;
+}
+
 // The whole step, or only the workers' lines of it.
 static int step_impl(compams_ctx* ctx, const float* g, float lr, bool workers_only, void* hip_stream) {
   if (!ctx || !g) return COMPAMS_INVALID_ARG;
@@ -500,6 +581,8 @@ static int step_impl(compams_ctx* ctx, const float* g, float lr, bool workers_on
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const compams_config& c = ctx->cfg;
   if (workers_only && c.compressor == COMPAMS_NONE) return COMPAMS_BAD_STATE;  // the message is g itself
+  if (const int bad = usable(ctx)) return bad;
+  if (order_after_last(ctx, stream) != hipSuccess) return COMPAMS_HIP_ERROR;  // nothing of the step is enqueued yet
   const AmsParams ap = ams_params(c, lr);
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
@@ -512,19 +595,23 @@ static int step_impl(compams_ctx* ctx, const float* g, float lr, bool workers_on
       else
         err = topk_blocks_step(ctx->geo, ctx->tk, ctx->tkopt, ap, ctx->lay.flat, g, c.e, c.theta, c.m, c.v, c.vhat,
                                may_predict, ctx->clear_pending, workers_only, stream, L);
-      ctx->clear_pending = true;
     } else if (c.compressor == COMPAMS_BLOCKSIGN) {
       err = blocksign_step(ctx->geo, ctx->bs, ap, g, c.e, c.theta, c.m, c.v, c.vhat, ctx->clear_pending, workers_only,
                            stream, L);
-      ctx->clear_pending = true;
     } else {
       err = none_step(ctx->geo, ap, g, c.theta, c.m, c.v, c.vhat, stream, L);
     }
   } catch (...) {
+    err = hipErrorUnknown;
+  }
+  note_enqueued(ctx, stream);  // whatever was launched before a failure sits on this stream
+  if (err != hipSuccess || (L && L->failed)) {
+    // some of the step's kernels may run, others not: nothing that later calls could build on
+    if (err != hipSuccess) ctx->failed = true;
     return COMPAMS_HIP_ERROR;
   }
-  ctx->last_stream = stream;
-  if (err != hipSuccess || (L && L->failed)) return COMPAMS_HIP_ERROR;
+  // every kernel of the step is enqueued: the error line it leaves to the next first pass is pending from now on
+  if (c.compressor != COMPAMS_NONE) ctx->clear_pending = true;
   ++ctx->steps;
   return COMPAMS_OK;
 }
@@ -547,13 +634,12 @@ int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stri
       reinterpret_cast<uintptr_t>(words) % 4 != 0)
     return COMPAMS_BAD_ALIGNMENT;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (const int bad = usable(ctx)) return bad;
   // The messages are unpacked into the workspace arrays that a pending residual update of this context still
-  // needs (the last lists, the last scales): apply it first.
-  if (ctx->clear_pending) {
-    if (ctx->last_stream != stream && hipStreamSynchronize(ctx->last_stream) != hipSuccess) return COMPAMS_HIP_ERROR;
-    ctx->last_stream = stream;
-    if (settle_residuals(ctx) != hipSuccess) return COMPAMS_HIP_ERROR;
-  }
+  // needs (the last lists, the last scales): apply it first, on the stream of the step that left it; then this
+  // call's stream is ordered behind that one on the device.
+  if (settle_residuals(ctx) != hipSuccess) return COMPAMS_HIP_ERROR;
+  if (order_after_last(ctx, stream) != hipSuccess) return COMPAMS_HIP_ERROR;
   const AmsParams ap = ams_params(c, lr);
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
@@ -569,9 +655,10 @@ int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stri
       if (err == hipSuccess) err = blocksign_server_step(ctx->geo, ctx->bs, ap, c.theta, c.m, c.v, c.vhat, stream, L);
     }
   } catch (...) {
-    return COMPAMS_HIP_ERROR;
+    err = hipErrorUnknown;
   }
-  ctx->last_stream = stream;
+  note_enqueued(ctx, stream);
+  if (err != hipSuccess) ctx->failed = true;  // theta, m, v, vhat may be half updated
   return err == hipSuccess && !(L && L->failed) ? COMPAMS_OK : COMPAMS_HIP_ERROR;
 }
 
@@ -613,6 +700,8 @@ int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* co
     case COMPAMS_STATE_LAST_SCALES:
       if (!bs) return COMPAMS_BAD_STATE;
       p = ctx->bs.scales; cnt = n * c.num_blocks; break;
+    case COMPAMS_STATE_PENDING:  // no pointer: the answer is the count
+      p = nullptr; cnt = ctx->clear_pending ? 1 : 0; break;
     default: return COMPAMS_INVALID_ARG;
   }
   *dev_ptr = p;
@@ -676,15 +765,11 @@ int compams_profile_read(compams_ctx* ctx, int cap, const char** names, double* 
 int compams_destroy(compams_ctx* ctx) {
   if (!ctx) return COMPAMS_INVALID_ARG;
   int status = COMPAMS_OK;
-  if (ctx->clear_pending) {  // hand e back to the caller in its settled form
+  if (ctx->clear_pending && !ctx->failed) {  // hand e back to the caller in its settled form
     if (settle_residuals(ctx) != hipSuccess || hipStreamSynchronize(ctx->last_stream) != hipSuccess)
       status = COMPAMS_HIP_ERROR;
   }
-  Launcher& L = ctx->launcher;
-  for (int s = 0; s < kNumSlots; ++s)
-    for (const Launcher::Pair& p : L.pending[s]) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
-  for (const Launcher::Pair& p : L.pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
-  delete ctx;
+  free_ctx(ctx);
   return status;
 }
 
@@ -695,7 +780,7 @@ const char* compams_strerror(int status) {
     case COMPAMS_BAD_ALIGNMENT: return "pointer or row stride not aligned";
     case COMPAMS_WORKSPACE_TOO_SMALL: return "workspace too small";
     case COMPAMS_HIP_ERROR: return "HIP runtime error";
-    case COMPAMS_BAD_STATE: return "query or option does not apply to this compressor";
+    case COMPAMS_BAD_STATE: return "call does not apply to this context (compressor, device, or a step that failed)";
     default: return "unknown status";
   }
 }
@@ -718,6 +803,8 @@ int compams_encode(compams_ctx* ctx, uint32_t* messages, int64_t stride_words, u
   if (reinterpret_cast<uintptr_t>(messages) % 4 != 0 || reinterpret_cast<uintptr_t>(words_out) % 4 != 0)
     return COMPAMS_BAD_ALIGNMENT;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (const int bad = usable(ctx)) return bad;
+  if (order_after_last(ctx, stream) != hipSuccess) return COMPAMS_HIP_ERROR;
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
   try {
@@ -725,8 +812,9 @@ int compams_encode(compams_ctx* ctx, uint32_t* messages, int64_t stride_words, u
               ? wire_encode_topk(ctx->geo, ctx->tk, messages, stride_words, words_out, stream, L)
               : wire_encode_blocksign(ctx->geo, ctx->bs, messages, stride_words, words_out, stream, L);
   } catch (...) {
-    return COMPAMS_HIP_ERROR;
+    err = hipErrorUnknown;
   }
+  note_enqueued(ctx, stream);
   return err == hipSuccess && !(L && L->failed) ? COMPAMS_OK : COMPAMS_HIP_ERROR;
 }
 
@@ -741,6 +829,8 @@ int compams_decode(compams_ctx* ctx, const uint32_t* messages, int64_t stride_wo
       reinterpret_cast<uintptr_t>(words) % 4 != 0)
     return COMPAMS_BAD_ALIGNMENT;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (const int bad = usable(ctx)) return bad;
+  if (order_after_last(ctx, stream) != hipSuccess) return COMPAMS_HIP_ERROR;
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
   try {
@@ -750,8 +840,9 @@ int compams_decode(compams_ctx* ctx, const uint32_t* messages, int64_t stride_wo
               : wire_decode_blocksign(ctx->geo, messages, stride_words, words, static_cast<uint32_t*>(out_a),
                                       static_cast<float*>(out_b), status_out, stream, L);
   } catch (...) {
-    return COMPAMS_HIP_ERROR;
+    err = hipErrorUnknown;
   }
+  note_enqueued(ctx, stream);
   return err == hipSuccess && !(L && L->failed) ? COMPAMS_OK : COMPAMS_HIP_ERROR;
 }
 

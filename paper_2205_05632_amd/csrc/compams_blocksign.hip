@@ -689,6 +689,11 @@ __global__ __launch_bounds__(kWG) void k_fill_u32(uint32_t* p, size_t count, uin
   for (size_t i = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x; i < count; i += step) p[i] = value;
 }
 
+__global__ __launch_bounds__(kWG) void k_copy_u32(uint32_t* __restrict__ dst, const uint32_t* __restrict__ src, size_t count) {
+  const size_t step = static_cast<size_t>(gridDim.x) * kWG;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kWG + threadIdx.x; i < count; i += step) dst[i] = src[i];
+}
+
 __global__ __launch_bounds__(kWG) void k_fill_rows(float* p, int64_t ld, uint32_t d, float value) {
   float* r = p + static_cast<int64_t>(blockIdx.y) * ld;
   const uint32_t step = gridDim.x * kWG;
@@ -759,6 +764,14 @@ hipError_t fill_u32(uint32_t* p, size_t count, uint32_t value, hipStream_t strea
   size_t blocks = (count + kWG - 1) / kWG;
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(k_fill_u32, dim3(static_cast<uint32_t>(blocks)), dim3(kWG), 0, stream, p, count, value);
+  return hipGetLastError();
+}
+
+hipError_t copy_u32(uint32_t* dst, const uint32_t* src, size_t count, hipStream_t stream) {
+  if (!count) return hipSuccess;
+  size_t blocks = (count + kWG - 1) / kWG;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(k_copy_u32, dim3(static_cast<uint32_t>(blocks)), dim3(kWG), 0, stream, dst, src, count);
   return hipGetLastError();
 }
 

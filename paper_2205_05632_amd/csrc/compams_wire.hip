@@ -1,5 +1,5 @@
-// The workers' messages as they would go on the wire ("send the compressed gradient to the server" in the
-// worker lines of Algorithm 2), and back.  One message per worker, a sequence of 32-bit words:
+// The workers' messages as they would go on the wire (the send line among the worker lines of Algorithm 2),
+// and back.  One message per worker, a sequence of 32-bit words:
 //
 //   top-k      [1, k, 256,  width words,  gap stream,  k value words]
 //              gap_0 = idx_0, gap_q = idx_q - idx_{q-1} - 1.  The gaps are taken in tiles of 256 (the last one

@@ -53,6 +53,8 @@ def test_binding_struct_matches_the_header(tmp_path):
     text = open(os.path.join(ROOT, "include", "compams.h")).read()
     for name, value in (("NONE", B.NONE), ("TOPK", B.TOPK), ("BLOCKSIGN", B.BLOCKSIGN), ("TOPK_BLOCKS", B.TOPK_BLOCKS)):
         assert re.search(rf"COMPAMS_{name}\s*=\s*{value}\b", text), name
+    for name, value in B.STATE.items():       # the queries of compams_state
+        assert re.search(rf"COMPAMS_STATE_{name.upper()}\s*=\s*{value}\b", text), name
 
 
 def cfg(**kw):

@@ -12,6 +12,7 @@ import torch
 
 from oracle import compams_oracle as O
 from paper_2205_05632_amd import binding as B
+from composed_blocks import CompamsBlockTopk
 from paper_2205_05632_amd import workloads as W
 
 from parity import Pair
@@ -413,7 +414,7 @@ def test_topk_per_block_composition(n, d, blocks):
     off = np.concatenate([[0], cuts, [d]]).astype(np.int64)
     kb = np.maximum(1, ((off[1:] - off[:-1]) * 0.03).astype(np.int64))
     theta0 = rng.standard_normal(d).astype(np.float32) * 0.1
-    gpu = B.CompamsBlockTopk(n, d, torch.from_numpy(theta0), off, kb)
+    gpu = CompamsBlockTopk(n, d, torch.from_numpy(theta0), off, kb)
     cpu = O.Oracle(n, d, theta0, compressor=O.TOPK_BLOCKS, block_offsets=off, block_k=kb)
     for t in range(5):
         g = (rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-3, 0, (1, d))).astype(np.float32)
@@ -433,7 +434,7 @@ def test_topk_per_block_composition(n, d, blocks):
 
 def test_topk_per_block_needs_aligned_blocks():
     with pytest.raises(B.CompamsError):
-        B.CompamsBlockTopk(2, 100, torch.zeros(100), [0, 50, 100], [1, 1])     # 50 is not a multiple of 4
+        CompamsBlockTopk(2, 100, torch.zeros(100), [0, 50, 100], [1, 1])     # 50 is not a multiple of 4
 
 
 # ------------------------------------------------------------------------------------------- identity

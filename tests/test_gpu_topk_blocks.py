@@ -7,6 +7,7 @@ import torch
 
 from oracle import compams_oracle as O
 from paper_2205_05632_amd import binding as B
+from composed_blocks import CompamsBlockTopk
 
 pytestmark = pytest.mark.gpu
 
@@ -231,7 +232,7 @@ def test_fused_equals_composition_and_is_deterministic():
     outs = []
     for make in (lambda: B.Compams(n, d, torch.from_numpy(theta0), compressor=B.TOPK_BLOCKS, block_offsets=off, block_k=kb),
                  lambda: B.Compams(n, d, torch.from_numpy(theta0), compressor=B.TOPK_BLOCKS, block_offsets=off, block_k=kb),
-                 lambda: B.CompamsBlockTopk(n, d, torch.from_numpy(theta0), off, kb)):
+                 lambda: CompamsBlockTopk(n, d, torch.from_numpy(theta0), off, kb)):
         c = make()
         for g in gs:
             gp = torch.zeros((n, c.ld), dtype=torch.float32); gp[:, :d] = torch.from_numpy(g)
