@@ -274,6 +274,31 @@ int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stri
  * beside the step's figures, and the known-size kernel that hardware counters are calibrated against. */
 int compams_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/* ---- One whole step for callers that cannot allocate ------------------------------------------------------
+ * For code that runs where no device memory can be allocated or handed over as a workspace (under HIP graph
+ * capture, in a tight serving loop, in a harness that forbids it): compams_init + compams_step +
+ * compams_state(COMPAMS_STATE_E) + compams_destroy in one call that allocates nothing, on the device or through
+ * any library.  The tables of the selection live in a device array inside the library, COMPAMS_STATIC_SCRATCH_BYTES
+ * large, that every device the library has run this call on holds until the process ends.
+ *   cfg: as for compams_init (same checks, same status codes), with compressor = COMPAMS_TOPK (else
+ *        COMPAMS_BAD_STATE: the other compressors need tables copied from the host) and with workspace and
+ *        workspace_bytes ignored.  A configuration whose compams_workspace_size() exceeds
+ *        COMPAMS_STATIC_SCRATCH_BYTES is rejected with COMPAMS_WORKSPACE_TOO_SMALL before anything is enqueued.
+ *        Without COMPAMS_KEEP_STATE the call first zeroes e, m, v, vhat (a first step); with it, e must hold the
+ *        error accumulators in their settled form (as compams_state(COMPAMS_STATE_E) or this call left them).
+ *   g, lr: as for compams_step.
+ *   idx_out, val_out: DEVICE, n * k entries each, or NULL: receive what the workers sent (COMPAMS_STATE_LAST_IDX,
+ *        COMPAMS_STATE_LAST_VAL).
+ * Only enqueues kernels on hip_stream (no copy or memset node, no synchronisation).  When the stream has passed
+ * the call, theta, m, v, vhat and e hold the result of one iteration of Algorithm 2 with nothing left pending:
+ * bit for bit what the four calls above give.  Nothing is carried from one call to the next (no threshold guess:
+ * every call reads the rows of corrected gradients a second time), so it is the slower way to step.
+ * All calls on one device share that device's array: calls that overlap in time on one device (two streams, two
+ * threads) race; calls on one stream, or otherwise ordered, do not. */
+#define COMPAMS_STATIC_SCRATCH_BYTES (32u << 20)
+int compams_step_static(const compams_config* cfg, const float* g, float lr, int32_t* idx_out, float* val_out,
+                        void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

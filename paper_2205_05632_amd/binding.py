@@ -27,7 +27,9 @@ _STATE_DTYPE = {"last_idx": torch.int32, "last_signbits": torch.int32, "last_thr
 
 EXPORTS = ["compams_workspace_size", "compams_init", "compams_step", "compams_state", "compams_set_option",
            "compams_profile_enable", "compams_profile_read", "compams_destroy", "compams_strerror", "compams_copy",
-           "compams_wire_capacity", "compams_encode", "compams_decode", "compams_worker_step", "compams_server_step"]
+           "compams_wire_capacity", "compams_encode", "compams_decode", "compams_worker_step", "compams_server_step",
+           "compams_step_static"]
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class compams_config(ctypes.Structure):
@@ -80,6 +82,8 @@ def lib():
         L.compams_worker_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.compams_server_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                           ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p]
+        L.compams_step_static.argtypes = [cfgp, ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -307,6 +311,24 @@ def _tensor_from_ptr(ptr: int, count: int, dtype: torch.dtype, device, keepalive
     t = torch.as_tensor(hld, device=device)
     assert t.element_size() == itemsize
     return t
+
+
+def compams_step_static(n: int, d: int, k: int, theta, m, v, vhat, e, g, lr: float, idx_out=None, val_out=None,
+                        beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, eps_mode: int = EPS_IN_SQRT,
+                        keep_state: bool = True) -> int:
+    """One whole top-k step on the caller's tensors with the library's built-in scratch array: marshals the
+    arguments of the C entry point of the same name and returns its status (no exception: callers test for the
+    rejection codes).  e and g are n x ld (ld = their common row stride)."""
+    cfg = compams_config()
+    cfg.n, cfg.d, cfg.ld, cfg.compressor, cfg.k = int(n), int(d), int(e.stride(0)), TOPK, int(k)
+    cfg.beta1, cfg.beta2, cfg.eps, cfg.eps_mode = beta1, beta2, eps, eps_mode
+    cfg.flags = KEEP_STATE if keep_state else 0
+    cfg.theta, cfg.m, cfg.v, cfg.vhat, cfg.e = theta.data_ptr(), m.data_ptr(), v.data_ptr(), vhat.data_ptr(), e.data_ptr()
+    assert g.stride(0) == e.stride(0) and g.is_cuda and g.dtype == torch.float32
+    with torch.cuda.device(e.device):
+        return lib().compams_step_static(ctypes.byref(cfg), g.data_ptr(), lr,
+                                         None if idx_out is None else idx_out.data_ptr(),
+                                         None if val_out is None else val_out.data_ptr(), _current_stream_handle())
 
 
 def compams_copy(dst: torch.Tensor, src: torch.Tensor):

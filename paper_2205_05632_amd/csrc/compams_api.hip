@@ -854,4 +854,89 @@ int compams_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
                                                                                             : COMPAMS_HIP_ERROR;
 }
 
+// ---- One whole step without a workspace argument -----------------------------------------------------------
+// For callers that cannot hand over (or allocate) a workspace: the tables of the top-k selection live in a
+// device array that is part of the library's code object.  Every device the library runs on holds its own copy
+// at its own address until the process ends; the host-side name below is only a handle for hipGetSymbolAddress.
+__attribute__((used)) static __device__ __align__(256) unsigned char scratch[COMPAMS_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device, once looked up
+
+// The address of this device's copy of the array (the device must be current).
+hipError_t scratch_of_current_device(char** out) {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return err;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> hold(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess) return err;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = static_cast<char*>(g_scratch_ptr[dev]);
+  return hipSuccess;
+}
+}  // namespace
+
+int compams_step_static(const compams_config* cfg, const float* g, float lr, int32_t* idx_out, float* val_out,
+                        void* hip_stream) {
+  if (!cfg || !g) return COMPAMS_INVALID_ARG;
+  if (const int bad = check_config(cfg)) return bad;
+  if (cfg->compressor != COMPAMS_TOPK) return COMPAMS_BAD_STATE;  // the other compressors' tables come from the host
+  if (reinterpret_cast<uintptr_t>(g) % 16 != 0 || reinterpret_cast<uintptr_t>(idx_out) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(val_out) % 4 != 0)
+    return COMPAMS_BAD_ALIGNMENT;
+  compams_ctx ctx;  // lives for this call only; nothing in it owns memory
+  try {
+    ctx.lay = make_layout(cfg);
+  } catch (...) {
+    return COMPAMS_HIP_ERROR;
+  }
+  if (ctx.lay.total > static_cast<size_t>(COMPAMS_STATIC_SCRATCH_BYTES)) return COMPAMS_WORKSPACE_TOO_SMALL;
+  char* w = nullptr;
+  if (scratch_of_current_device(&w) != hipSuccess) return COMPAMS_HIP_ERROR;
+  ctx.cfg = *cfg;
+  ctx.cfg.workspace = w;
+  ctx.cfg.workspace_bytes = COMPAMS_STATIC_SCRATCH_BYTES;
+  set_geometry(&ctx);
+  bind_topk_workspace(&ctx, w);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const Layout& lay = ctx.lay;
+  const AmsParams ap = ams_params(ctx.cfg, lr);
+  hipError_t err = hipSuccess;
+  auto ok = [&](hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; };
+  // the array keeps what the last call left: control blocks, counters, histograms and chunk tables start at zero
+  // (fill kernels, so that the call can be recorded into a graph); lists need no initial value
+  ok(fill_u32(reinterpret_cast<uint32_t*>(w), lay.cand / 4, 0u, stream));
+  ok(fill_u32(reinterpret_cast<uint32_t*>(w + lay.idx), (lay.total - lay.idx) / 4, 0u, stream));
+  if (!(cfg->flags & COMPAMS_KEEP_STATE)) {
+    ok(fill_rows_f32(cfg->e, ctx.geo.n, ctx.geo.ld, ctx.geo.d, 0.0f, stream));
+    ok(fill_rows_f32(cfg->m, 1, 0, ctx.geo.d, 0.0f, stream));
+    ok(fill_rows_f32(cfg->v, 1, 0, ctx.geo.d, 0.0f, stream));
+    ok(fill_rows_f32(cfg->vhat, 1, 0, ctx.geo.d, 0.0f, stream));
+  }
+  if (err == hipSuccess) {
+    try {
+      // no guess is carried over and no error line is pending on entry; the one this step leaves is applied at once
+      err = topk_step(ctx.geo, ctx.tk, ctx.tkopt, ap, g, cfg->e, cfg->theta, cfg->m, cfg->v, cfg->vhat, false, false,
+                      false, stream, nullptr);
+    } catch (...) {
+      err = hipErrorUnknown;
+    }
+  }
+  if (err == hipSuccess) err = topk_apply_clear(ctx.geo, ctx.tk, cfg->e, stream);
+  const size_t nk = static_cast<size_t>(cfg->n) * static_cast<size_t>(cfg->k);
+  if (err == hipSuccess && idx_out)
+    err = copy_u32(reinterpret_cast<uint32_t*>(idx_out), reinterpret_cast<const uint32_t*>(ctx.tk.idx), nk, stream);
+  if (err == hipSuccess && val_out)
+    err = copy_u32(reinterpret_cast<uint32_t*>(val_out), reinterpret_cast<const uint32_t*>(ctx.tk.val), nk, stream);
+  return err == hipSuccess ? COMPAMS_OK : COMPAMS_HIP_ERROR;
+}
+
 }  // extern "C"
