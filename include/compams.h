@@ -169,7 +169,9 @@ enum {
   COMPAMS_CNT_CANDIDATES = 1,  /* entries in the candidate list, 0 if none was used */
   COMPAMS_CNT_TIES = 2,        /* coordinates whose key equals the threshold key */
   COMPAMS_CNT_TIES_TAKEN = 3,  /* how many of those were selected */
-  COMPAMS_COUNTERS_PER_ROW = 4
+  COMPAMS_CNT_BAND = 4,        /* entries in the band list if the threshold key was found there (the selection then
+                                  took a single launch), else 0 */
+  COMPAMS_COUNTERS_PER_ROW = 8 /* 5..7 are reserved and read 0 */
 };
 
 /* Borrowed DEVICE pointer to a state tensor or to what the workers "sent" in the last step, valid until
@@ -187,7 +189,11 @@ enum {
                                     not fit counts as a list that would not fit */
   COMPAMS_OPT_PREDICT = 1,       /* 1 (default): the first pass of a step already writes the candidate list, using
                                     the previous step's threshold bucket as a guess that is verified afterwards */
-  COMPAMS_OPT_FORCE_DENSE = 2    /* 1: never build a candidate list; every selection pass reads the whole row */
+  COMPAMS_OPT_FORCE_DENSE = 2,   /* 1: never build a candidate list; every selection pass reads the whole row */
+  COMPAMS_OPT_BAND = 3           /* 1 (default): the first pass also gets a window of keys around the threshold
+                                    expected from the last two steps, counts what lies above it and lists what lies
+                                    inside; when the threshold does fall inside (verified exactly), one launch
+                                    finishes the selection from that short list */
 };
 int compams_set_option(compams_ctx* ctx, int option, int64_t value);
 

@@ -49,20 +49,23 @@ void launcher_end(Launcher* L, int slot, hipStream_t stream) {
 namespace {
 
 const char* const kSlotNames[kNumSlots] = {
-    "topk_pass_a", "topk_level0", "topk_level1", "topk_level2", "topk_count", "topk_final", "topk_emit", "topk_offsets",
+    "topk_pass_a", "topk_band", "topk_level0", "topk_level1", "topk_level2", "topk_count", "topk_final", "topk_emit", "topk_offsets",
     "bs_pass1", "bs_finalize", "bs_pass2", "bs_amsgrad", "none_amsgrad", "wire_encode", "wire_decode"};
+
+static_assert(kCountersPerRow == COMPAMS_COUNTERS_PER_ROW, "the kernels' stride of the counters is the header's");
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Layout {
   size_t total;
   // top-k
-  size_t rows, counters, hist0, hist1, hist1x, hist2, xcur, chunk_rec, blk, sel_off, desc, cand, idx, val, tau, count_gt, wire_total,
-      wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_level0, map_sweep, map_count, map_emit, map_final, micro_list;
+  size_t rows, counters, hist0, hist1, hist1x, hist2, bhist, xcur, chunk_rec, blk, sel_off, desc, desc2, bnd, bnd_sel, cand, band,
+      idx, val, tau, count_gt, wire_total, wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_level0, map_sweep,
+      map_count, map_emit, map_final, micro_list;
   // block-sign
   size_t offsets, chunk_block, acc, special, scales, bits;
   uint32_t acc_replicas;
-  uint32_t cap_alloc, num_chunks, words;
+  uint32_t cap_alloc, band_alloc, num_chunks, words;
   // top-k inside every block
   uint64_t k_total;
   size_t num_micro;  // selection problems taken by single wavefronts (top-k per block)
@@ -95,8 +98,15 @@ bool basic_valid(const compams_config* c) {
 
 // Top-k inside every block: the shape of one block's selection problem and how many workgroups it gets.
 struct BlockShape {
-  uint32_t off, d, k, nc, cap, cpw, groups_first, groups_level0, groups_sweep, count_blocks, emit_slots, micro;
+  uint32_t off, d, k, nc, cap, band_cap, cpw, groups_first, groups_level0, groups_sweep, count_blocks, emit_slots, micro;
 };
+
+// Entries of a problem's band list: the window around the expected threshold holds a fraction of k.
+uint32_t band_capacity(uint64_t k, uint32_t cap) {
+  uint64_t want = k / 3 + 4096;
+  if (want > kBandMaxEntries) want = kBandMaxEntries;
+  return want > cap ? cap : static_cast<uint32_t>(want);
+}
 
 std::vector<BlockShape> block_shapes(const compams_config* c) {
   const size_t M = static_cast<size_t>(c->num_blocks);
@@ -111,9 +121,10 @@ std::vector<BlockShape> block_shapes(const compams_config* c) {
     const uint64_t cap = 8ull * s.k + 8192;
     s.cap = cap > s.d ? s.d : static_cast<uint32_t>(cap);
     s.cpw = count_chunks_per_block(s.nc);
+    s.micro = s.d <= kMicroCoords ? 1u : 0u;
+    s.band_cap = s.micro ? 0u : band_capacity(s.k, s.cap);
     s.count_blocks = (s.nc + s.cpw - 1) / s.cpw;
     s.emit_slots = (s.nc + kWaves - 1) / kWaves;
-    s.micro = s.d <= kMicroCoords ? 1u : 0u;
     chunks_per_worker += s.nc;
   }
   // the first pass takes a workgroup per chunk; about 512 workgroups find the threshold buckets and 2048 make the
@@ -146,18 +157,24 @@ Layout make_layout(const compams_config* c) {
     size_t cap = 8 * k + 65536;
     if (cap > d) cap = d;
     L.cap_alloc = static_cast<uint32_t>(cap);
+    L.band_alloc = band_capacity(k, L.cap_alloc);
     L.rows = take(n * sizeof(TopkRow));
     L.counters = take(n * COMPAMS_COUNTERS_PER_ROW * 4);
     L.hist0 = take(n * kNB0 * 4);
     L.hist1 = take(n * kNB1 * 4);
     L.hist1x = take(n * kTracked * kNB1 * 4);
     L.hist2 = take(n * kNB2 * 4);
+    L.bhist = take(n * kBandBuckets * 4);
     L.xcur = take(n * kSubLists * kCursorPitch * 4);
     L.chunk_rec = take(n * nc * 16);
     L.blk = take(n * kMaxCountBlocks * 8);
     L.sel_off = take(n * (nc + 1) * 4);
     L.desc = take(n * nc * 8);
+    L.desc2 = take(n * nc * 8);
+    L.bnd = take(n * kBoundaryCap * 8);
+    L.bnd_sel = take(n * kBoundaryCap * 4);
     L.cand = take(n * cap * 8);
+    L.band = take(n * static_cast<size_t>(L.band_alloc) * 8);
     L.idx = take(n * k * 4);
     L.val = take(n * k * 4);
     L.tau = take(n * 4);
@@ -169,16 +186,19 @@ Layout make_layout(const compams_config* c) {
   } else if (c->compressor == COMPAMS_TOPK_BLOCKS) {
     const std::vector<BlockShape> shapes = block_shapes(c);
     const size_t M = shapes.size(), S = n * M;
-    size_t k = 0, chunks = 0, caps = 0, wg_first = 0, wg_level0 = 0, wg_sweep = 0, wg_count = 0, wg_emit = 0, micro = 0, big = 0;
-    uint32_t cap_max = 0;
+    size_t k = 0, chunks = 0, caps = 0, bcaps = 0, wg_first = 0, wg_level0 = 0, wg_sweep = 0, wg_count = 0, wg_emit = 0, micro = 0,
+           big = 0;
+    uint32_t cap_max = 0, band_max = 0;
     for (const BlockShape& b : shapes) {
       k += b.k; chunks += b.nc; caps += b.cap; cap_max = std::max(cap_max, b.cap);
+      bcaps += b.band_cap; band_max = std::max(band_max, b.band_cap);
       wg_first += b.groups_first; wg_level0 += b.groups_level0; wg_sweep += b.groups_sweep; wg_count += b.count_blocks; wg_emit += b.emit_slots;
       micro += b.micro;
       big += b.nc >= kSubListMinChunks ? 1 : 0;  // blocks whose candidate lists are kept as several runs
     }
     L.k_total = k;
     L.cap_alloc = cap_max;
+    L.band_alloc = band_max;
     L.num_micro = n * micro;
     L.flat.wg_first = static_cast<uint32_t>(n * wg_first + (n * micro + kWaves - 1) / kWaves);
     L.flat.wg_level0 = static_cast<uint32_t>(n * wg_level0);
@@ -186,6 +206,7 @@ Layout make_layout(const compams_config* c) {
     L.flat.wg_count = static_cast<uint32_t>(n * wg_count);
     L.flat.wg_emit = static_cast<uint32_t>(n * wg_emit);
     L.flat.wg_final = static_cast<uint32_t>(chunks);
+    L.flat.band_stride = bcaps;
     L.flat.blocks = static_cast<uint32_t>(M);
     L.flat.chunk_stride = static_cast<uint32_t>(chunks);
     L.flat.seloff_stride = static_cast<uint32_t>(chunks + M);
@@ -196,12 +217,17 @@ Layout make_layout(const compams_config* c) {
     L.hist1 = take(S * kNB1 * 4);
     L.hist1x = take(S * kTracked * kNB1 * 4);
     L.hist2 = take(S * kNB2 * 4);
+    L.bhist = take(S * kBandBuckets * 4);
     L.xcur = take(n * big * kSubLists * kCursorPitch * 4);
     L.chunk_rec = take(n * chunks * 16);
     L.blk = take(S * kMaxCountBlocks * 8);
     L.sel_off = take(n * (chunks + M) * 4);
     L.desc = take(n * chunks * 8);
+    L.desc2 = take(n * chunks * 8);
+    L.bnd = take(S * kBoundaryCap * 8);
+    L.bnd_sel = take(S * kBoundaryCap * 4);
     L.cand = take(n * caps * 8);
+    L.band = take(n * bcaps * 8);
     L.idx = take(n * k * 4);
     L.val = take(n * k * 4);
     L.tau = take(S * 4);
@@ -344,7 +370,12 @@ static void bind_topk_workspace(compams_ctx* ctx, char* w) {
   t.wire_tile_off = reinterpret_cast<uint32_t*>(w + lay.wire_tile_off);
   t.wire_tile_sum = reinterpret_cast<uint32_t*>(w + lay.wire_tile_sum);
   t.desc = reinterpret_cast<uint2*>(w + lay.desc);
+  t.desc2 = reinterpret_cast<uint2*>(w + lay.desc2);
   t.cand = reinterpret_cast<uint2*>(w + lay.cand);
+  t.band = reinterpret_cast<uint2*>(w + lay.band);
+  t.bhist = reinterpret_cast<uint32_t*>(w + lay.bhist);
+  t.bnd = reinterpret_cast<uint2*>(w + lay.bnd);
+  t.bnd_sel = reinterpret_cast<uint32_t*>(w + lay.bnd_sel);
   t.idx = reinterpret_cast<int32_t*>(w + lay.idx);
   t.val = reinterpret_cast<float*>(w + lay.val);
   t.tau = reinterpret_cast<uint32_t*>(w + lay.tau);
@@ -355,6 +386,8 @@ static void bind_topk_workspace(compams_ctx* ctx, char* w) {
   ctx->tkopt.cap = lay.cap_alloc;
   ctx->tkopt.predict = 1;
   ctx->tkopt.force_dense = 0;
+  ctx->tkopt.band = 1;
+  ctx->tkopt.band_cap = lay.band_alloc;
 }
 
 // The shape of the launches, from a validated configuration and its layout.
@@ -454,12 +487,12 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
       try {
         const std::vector<BlockShape> shapes = block_shapes(cfg);
         const size_t M = shapes.size();
-        uint64_t chunks = 0, caps = 0;
-        for (const BlockShape& b : shapes) { chunks += b.nc; caps += b.cap; }
+        uint64_t chunks = 0, caps = 0, bcaps = 0;
+        for (const BlockShape& b : shapes) { chunks += b.nc; caps += b.cap; bcaps += b.band_cap; }
         uint32_t cursor_sets = 0;
         segs.resize(static_cast<size_t>(cfg->n) * M);
         for (int64_t i = 0; i < cfg->n; ++i) {
-          uint64_t c_at = 0, cap_at = 0, k_at = 0;
+          uint64_t c_at = 0, cap_at = 0, k_at = 0, band_at = 0;
           for (size_t b = 0; b < M; ++b) {
             const BlockShape& sh = shapes[b];
             const uint32_t si = static_cast<uint32_t>(static_cast<size_t>(i) * M + b);
@@ -470,7 +503,9 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
             sg.seloff_base = static_cast<uint64_t>(i) * (chunks + M) + c_at + b;
             sg.cand_base = static_cast<uint64_t>(i) * caps + cap_at;
             sg.list_base = static_cast<uint64_t>(i) * lay.k_total + k_at;
+            sg.band_base = static_cast<uint64_t>(i) * bcaps + band_at;
             sg.d = sh.d; sg.k = sh.k; sg.num_chunks = sh.nc; sg.cap = sh.cap; sg.coord_base = sh.off;
+            sg.band_cap = sh.band_cap;
             sg.count_cpw = sh.cpw;
             sg.groups_first = sh.groups_first; sg.groups_sweep = sh.groups_sweep; sg.count_blocks = sh.count_blocks;
             sg.micro = sh.micro;
@@ -484,7 +519,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
             for (uint32_t q = 0; q < sh.emit_slots; ++q) m_emit.push_back(WgSlot{si, q * static_cast<uint32_t>(kWaves)});
             if (i == 0)
               for (uint32_t q = 0; q < sh.nc; ++q) m_final.push_back(WgSlot{si, q});
-            c_at += sh.nc; cap_at += sh.cap; k_at += sh.k;
+            c_at += sh.nc; cap_at += sh.cap; k_at += sh.k; band_at += sh.band_cap;
           }
         }
         // and last of all the workgroups whose wavefronts take one micro problem each
@@ -722,6 +757,9 @@ int compams_set_option(compams_ctx* ctx, int option, int64_t value) {
       return COMPAMS_OK;
     case COMPAMS_OPT_FORCE_DENSE:
       ctx->tkopt.force_dense = value ? 1u : 0u;
+      return COMPAMS_OK;
+    case COMPAMS_OPT_BAND:
+      ctx->tkopt.band = value ? 1u : 0u;
       return COMPAMS_OK;
     default: return COMPAMS_INVALID_ARG;
   }

@@ -57,6 +57,8 @@ constexpr uint32_t kCursorPitch = 32;  // words between the cursors of a problem
 constexpr uint32_t kSubListMinChunks = 64;
 constexpr uint32_t kNoCursorSet = 0xffffffffu;
 
+constexpr uint32_t kCountersPerRow = 8;  // == COMPAMS_COUNTERS_PER_ROW of the public header
+
 constexpr int kWireTile = 256;  // coordinate gaps per tile of a top-k message (one width per tile)
 
 // Where a row's selection reads its elements from after level 0.
@@ -66,11 +68,26 @@ enum : uint32_t {
   kModeDense = 2   // no candidate list (it would not fit): every later pass reads the whole row
 };
 
+// The band: a window of magnitude keys [band_lo, band_hi) in which the next step's threshold key is expected,
+// set from the last two thresholds, cut into kBandBuckets buckets of 2^band_shift keys.  The first pass counts, per
+// chunk, the entries at or above band_hi, copies the entries inside the window to a short list of their own (a
+// segment per chunk) and adds them to the row's bucket histogram.  If the threshold does fall inside (checked
+// exactly), one launch finishes the selection from the short list alone (k_topk_band).
+constexpr uint32_t kBandBuckets = 1024;
+constexpr uint32_t kBandMaxEntries = 1u << 20;  // capacity of a band list at most
+constexpr uint32_t kBoundaryCap = 64;      // entries in the bucket that holds the threshold key; more: general route
+constexpr uint32_t kCursorAboveWord = 2;   // word of a run's cursor line that counts the run's entries above the band
+
 // Per-row control block of the top-k selection (device memory, written by single workgroups).
 struct TopkRow {
   uint32_t pred_valid;  // the next first pass may emit candidates with level-0 bucket >= b_guess
   uint32_t b_guess;
-  uint32_t cursor;      // candidate entries allocated so far in this step (a list kept as one run)
+  uint32_t cursor;      // candidate entries allocated so far in this step (a list kept as one run) ...
+  uint32_t cursor_band; // ... and band entries: the two are advanced together as one 64-bit word
+  uint32_t band_valid;  // the next first pass may also fill the band list and the bucket histogram
+  uint32_t band_lo, band_hi;  // keys; band_lo >= b_guess << kL0Shift, band_hi > band_lo
+  uint32_t band_shift;  // bucket of a key inside the band: (key - band_lo) >> band_shift  (< kBandBuckets)
+  uint32_t fast;        // this step's threshold was found in the band: the general kernels skip the problem
   uint32_t mode;        // kMode*
   uint32_t n_src;       // entries in the candidate list (kModeCand / kModeNeedB)
   uint32_t bstar;       // level-0 bucket that holds the k-th largest key
@@ -79,14 +96,19 @@ struct TopkRow {
   uint32_t tau;         // the k-th largest key
   uint32_t r;           // how many keys equal to tau are selected
   uint32_t ties;        // how many keys equal tau
-  uint32_t take_all_ties;  // r == ties: no tie ranking needed
   uint32_t level1_done;    // bits 30..9 of the threshold key are known (prefix1 / need are valid)
   uint32_t ticket[4];      // "last workgroup of the row" counters of kernels 1..4; zero between launches
   uint32_t n_lists;        // runs of the candidate list: kSubLists (run s from entry s * (capacity / kSubLists) on), or 1
   uint32_t n_sub[kSubLists];  // entries of each run (n_src in all)
-  uint32_t pad[6];
+  uint32_t tie_last;       // fast: ties are taken up to and including this coordinate (of the problem)
+  uint32_t tau_prev;       // the threshold key of the step before (0: none)
+  uint32_t above;          // entries at or above band_hi (a list kept as one run; else in the runs' cursor lines)
+  uint32_t bnd_n;          // entries of the threshold's bucket gathered so far (k_topk_band); zero between launches
+  uint32_t bnd_kept;       // fast: how many of them are kept; their coordinates, ascending, are in bnd_sel
+  uint32_t ticket_band;    // "last workgroup" counter of k_topk_band; zero between launches
+  uint32_t pad[27];
 };
-static_assert(sizeof(TopkRow) == 128, "TopkRow layout");
+static_assert(sizeof(TopkRow) == 256, "TopkRow layout");
 
 // One selection problem: a worker's whole row (top-k over the flattened gradient) or one block of a worker's
 // row (top-k inside every block).  Index fields count entries of the respective workspace tables.
@@ -96,9 +118,11 @@ struct Seg {
   uint64_t seloff_base;  // first entry in sel_off (a segment has one entry more than it has chunks)
   uint64_t cand_base;    // first entry of the segment's candidate list
   uint64_t list_base;    // first entry of the segment's slice of the worker's (coordinate, value) list
+  uint64_t band_base;    // first entry of the segment's band list
   uint32_t d, k;         // length, and how many coordinates are kept
   uint32_t num_chunks;
   uint32_t cap;          // capacity of the candidate list
+  uint32_t band_cap;     // capacity of the band list
   uint32_t coord_base;   // coordinate of the first element within the worker's row
   uint32_t count_cpw;    // chunks per block of the counting kernel
   uint32_t groups_first, groups_sweep, count_blocks;  // workgroups the kernel classes give this segment (first pass:
@@ -107,7 +131,7 @@ struct Seg {
   uint32_t groups_level0;
   uint32_t cursor_set;   // which set of kSubLists cursors the problem's list uses, or kNoCursorSet: one run, rowp->cursor
 };
-static_assert(sizeof(Seg) == 88 || sizeof(Seg) == 96, "Seg layout");
+static_assert(sizeof(Seg) % 8 == 0, "Seg layout");
 
 // Which segment, and which of its workgroups, a workgroup of a flat launch is.
 struct WgSlot {
@@ -118,6 +142,8 @@ struct TopkOptions {
   uint32_t cap;            // candidate entries per row
   uint32_t predict;        // 1: carry the threshold bucket over to the next step's first pass
   uint32_t force_dense;    // 1: never build a candidate list (test / ablation)
+  uint32_t band;           // 1: also carry a window for the threshold key itself over (k_topk_band)
+  uint32_t band_cap;       // band entries per row
 };
 
 struct TopkWorkspace {
@@ -138,6 +164,12 @@ struct TopkWorkspace {
   uint32_t* wire_tile_off; // n * ceil(k / kWireTile) : where each tile of gaps starts in its stream
   uint32_t* wire_tile_sum; // n * ceil(k / kWireTile) : coordinates before each tile, while unpacking
   uint2* desc;          // n * num_chunks : (offset, count) of the chunk's segment in the candidate list
+  uint2* desc2;         // n * num_chunks : offset of the chunk's segment in the band list; entries at or above the
+                        //                  band | entries in the band << 13 | kBandChunkOverflow
+  uint2* band;          // n * band_cap   : (coordinate, fp32 bits) of the entries inside the band
+  uint32_t* bhist;      // n * kBandBuckets : how many band entries fall into each bucket; zero between steps
+  uint2* bnd;           // n * kBoundaryCap : the entries of the bucket that holds the threshold key
+  uint32_t* bnd_sel;    // n * kBoundaryCap : coordinates of the kept ones among them, ascending
   uint2* cand;          // n * cap_alloc  : (coordinate, fp32 bits)
   int32_t* idx;         // n * k
   float* val;           // n * k
@@ -201,7 +233,7 @@ struct Geometry {
 
 // Kernel slots for optional timing.
 enum KernelSlot {
-  kSlotPassA = 0, kSlotLevel0, kSlotLevel1, kSlotLevel2, kSlotCount, kSlotTopkFinal, kSlotTopkEmit, kSlotTopkOffsets,
+  kSlotPassA = 0, kSlotBand, kSlotLevel0, kSlotLevel1, kSlotLevel2, kSlotCount, kSlotTopkFinal, kSlotTopkEmit, kSlotTopkOffsets,
   kSlotBsPass1, kSlotBsFinal, kSlotBsPass2, kSlotBsAms,
   kSlotNoneAms, kSlotWireEncode, kSlotWireDecode, kNumSlots
 };
@@ -218,7 +250,7 @@ struct TopkFlat {
   uint32_t wg_first, wg_level0, wg_sweep, wg_count, wg_emit, wg_final;
   // from worker i's segment of a block to worker i + 1's: segment index, chunk tables, list offsets, candidates
   uint32_t blocks, chunk_stride, seloff_stride;
-  uint64_t cand_stride;
+  uint64_t cand_stride, band_stride;
 };
 hipError_t topk_blocks_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOptions& opt, const AmsParams& ap,
                             const TopkFlat& flat, const float* g, float* e, float* theta, float* m, float* v,

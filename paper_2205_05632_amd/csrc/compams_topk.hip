@@ -5,26 +5,35 @@
 // (fp32 pattern without the sign; ties to the lower coordinate) are written out as ascending
 // (coordinate, value) lists, and the residual at those coordinates becomes zero.
 //
-// Six kernels per step (the key's 32 bits are resolved as 12 + 10 + 9 bits and a zero sign bit):
-//   1 first pass   x = e + g -> e as a grid of short workgroups, one chunk each.  When the previous step's
+// Kernels of a step.  In the steady state three of them do the work (first pass, band, final); the four
+// general ones in between return at once for every row whose threshold the band kernel has found:
+//   first pass     x = e + g -> e as a grid of short workgroups, one chunk each.  When the previous step's
 //                  threshold bucket is carried over as a guess, the same pass writes the candidate list: the
-//                  entries at or above the guessed bucket, a segment per chunk.
-//   2 level 0      histogram of the 12-bit threshold buckets, from the candidate list when the guess held (the
+//                  entries at or above the guessed bucket, a segment per chunk.  When the last two thresholds
+//                  also give a band of keys in which this step's threshold is expected, it counts per chunk the
+//                  entries above the band, lists the entries inside it (a segment per chunk again) and adds
+//                  them to the row's histogram of 1024 buckets across the band.
+//   band           if the threshold key does lie in the band (decided exactly from the counts): per chunk the
+//                  entries kept for certain, their prefixes inside blocks of chunks and the block totals; the
+//                  few entries of the threshold's bucket are ranked by the last workgroup of the row, which
+//                  gives tau, the ties to keep (by coordinate) and the next step's guess and band.
+//   The general route (12 + 10 + 9 key bits and a zero sign bit), for every other row:
+//   level 0        histogram of the 12-bit threshold buckets, from the candidate list when the guess held (the
 //                  list then holds at least k entries), else from the row itself; for a listed row also the
 //                  level-1 histograms of the three buckets from the guess upwards, among which the threshold
 //                  is expected.  The last workgroup of a row to finish finds the threshold bucket, checks the
 //                  guess, resolves level 1 if it can, and sets the next step's guess.
-//   3 level 1      only for rows that level 0 could not resolve: one more read of the row that writes the
+//   level 1        only for rows that level 0 could not resolve: one more read of the row that writes the
 //                  candidate list with the exact bucket and builds the level-1 histogram (10 bits), or a
 //                  sweep of the list; rows that would not fit a list are histogrammed from the row itself.
-//   4 level 2      histogram of the last 9 key bits over the matching candidates; yields the k-th largest
-//                  key tau and how many keys equal to tau are taken.
-//   5 count        per chunk: keys above tau and keys equal to tau, with prefixes inside contiguous blocks of
+//   level 2        histogram of the last 9 key bits over the matching candidates; yields the k-th largest
+//                  key tau and how many keys equal to tau are taken; sets the next step's band.
+//   count          per chunk: keys above tau and keys equal to tau, with prefixes inside contiguous blocks of
 //                  chunks and the totals of every block.
-//   6 final        per chunk of coordinates: the position of each worker's entries in its list follows from
+//   final          per chunk of coordinates: the position of each worker's entries in its list follows from
 //                  the block totals and prefixes; the selected entries are written there, then added in
 //                  worker order into an LDS tile of the averaged gradient, then AMSGrad.
-// With top-k inside every block (one selection problem per worker and block) the same six launches go over all
+// With top-k inside every block (one selection problem per worker and block) the same launches go over all
 // problems at once through tables of workgroup slots; problems of at most 1024 coordinates are solved by one
 // wavefront inside the first pass.
 // Zeroing the residual at the selected coordinates is not done by scattered stores: the next step's
@@ -69,6 +78,12 @@ __device__ __forceinline__ void hist4(uint32_t* lh, const Quad& q, uint32_t& zer
     if (q.ok[s] && q.key[s] != 0) atomicAdd(&lh[q.key[s] >> kL0Shift], 1u);
   }
   zeros += z;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+  return v;
 }
 
 // Number of flagged entries of one round, and this lane's position among them in (lane, slot) order.
@@ -281,7 +296,7 @@ __device__ __forceinline__ void emit_chunk(uint32_t mode, const float* __restric
                                            const uint2* __restrict__ candr, const uint2* __restrict__ descr,
                                            uint32_t cap, uint32_t tau, uint32_t r, bool all_ties, uint32_t eq_seen,
                                            uint32_t at, int32_t* __restrict__ idx, float* __restrict__ val, uint32_t k,
-                                           uint32_t coord_base);
+                                           uint32_t coord_base, bool by_coord = false, uint32_t tie_last = 0);
 
 // A micro problem (top-k inside a block of at most kMicroCoords coordinates) from end to end by one wavefront:
 // x = e + g with the pending zeros honoured, stored in place of e; the k-th largest key by a bit-by-bit search
@@ -372,20 +387,23 @@ __device__ __forceinline__ void micro_problem(const float* __restrict__ g, float
     rowp->mode = kModeDense;
     rowp->n_src = 0;
     rowp->cursor = 0;
+    rowp->cursor_band = 0;
     rowp->pred_valid = 0;
+    rowp->band_valid = 0;
+    rowp->fast = 0;
     rowp->b_guess = 0;
     rowp->level1_done = 1;
     rowp->tau = tau;
     rowp->r = r_take;
     rowp->ties = ties;
-    rowp->take_all_ties = (r_take == ties);
     ws.tau[seg] = tau;
     ws.count_gt[seg] = gt;
-    uint32_t* cn = ws.counters + seg * 4;
+    uint32_t* cn = ws.counters + seg * kCountersPerRow;
     cn[0] = 0;
     cn[1] = 0;
     cn[2] = ties;
     cn[3] = r_take;
+    cn[4] = 0;
     ws.chunk_rec[sg.chunk_base] = make_uint4(gt, ties, 0u, 0u);  // one chunk, nothing before it
     ws.blk[static_cast<size_t>(seg) * kMaxCountBlocks] = make_uint2(gt, ties);
   }
@@ -408,7 +426,7 @@ struct SegCtx {
   uint32_t groups;
   int64_t elem_off;
   uint32_t coord_base;
-  size_t chunk_base, seloff_base, cand_base, list_base;
+  size_t chunk_base, seloff_base, cand_base, list_base, band_base;
   uint32_t cursor_set;  // see Seg
 };
 
@@ -425,12 +443,14 @@ __device__ __forceinline__ SegCtx seg_ctx_of(uint32_t seg, uint32_t group, uint3
   c.seloff_base = sg.seloff_base;
   c.cand_base = sg.cand_base;
   c.list_base = sg.list_base;
+  c.band_base = sg.band_base;
   c.cursor_set = sg.cursor_set;
   geo.d = sg.d;
   geo.k = sg.k;
   geo.num_chunks = sg.num_chunks;
   geo.count_cpw = sg.count_cpw;
   opt.cap = opt.cap < sg.cap ? opt.cap : sg.cap;
+  opt.band_cap = opt.band_cap < sg.band_cap ? opt.band_cap : sg.band_cap;
   return c;
 }
 
@@ -447,6 +467,7 @@ __device__ __forceinline__ SegCtx seg_ctx(Geometry& geo, TopkOptions& opt, const
     c.seloff_base = static_cast<size_t>(c.seg) * (geo.num_chunks + 1);
     c.cand_base = static_cast<size_t>(c.seg) * opt.cap;
     c.list_base = static_cast<size_t>(c.seg) * geo.k;
+    c.band_base = static_cast<size_t>(c.seg) * opt.band_cap;
     c.cursor_set = geo.num_chunks >= kSubListMinChunks ? c.seg : kNoCursorSet;  // short rows keep one run
     return c;
   }
@@ -575,7 +596,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
                                                     TopkWorkspace ws, TopkOptions opt, uint32_t use_guess) {
   __shared__ uint2 stage_all[kWaves * kStageQ];
   __shared__ uint32_t bm_all[PEND ? kWaves * 32 : 1];
-  __shared__ uint32_t sh_cnt[kWaves], sh_off;
+  __shared__ uint32_t sh_cnt[kWaves], sh_above[kWaves], sh_from[kWaves], sh_off, sh_boff;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   if constexpr (!UNI) {
     const WgSlot slot = ws.map_first[blockIdx.x];
@@ -597,9 +618,19 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   // launches and is the same for the whole workgroup: it comes through the scalar path, whose answers do not
   // queue behind the chunk's loads (vector loads return in order).
   const uint32_t* row_words = reinterpret_cast<const uint32_t*>(rowp);
-  static_assert(offsetof(TopkRow, pred_valid) == 0 && offsetof(TopkRow, b_guess) == 4, "words read below");
+  static_assert(offsetof(TopkRow, pred_valid) == 0 && offsetof(TopkRow, b_guess) == 4 &&
+                offsetof(TopkRow, band_valid) == 16 && offsetof(TopkRow, band_lo) == 20 &&
+                offsetof(TopkRow, band_hi) == 24 && offsetof(TopkRow, band_shift) == 28 &&
+                offsetof(TopkRow, cursor) == 8 && offsetof(TopkRow, cursor_band) == 12,
+                "words read below; the two cursors form one 64-bit word");
   const bool pred = use_guess && table_u32(row_words, 0) != 0;  // workgroup-uniform
   const uint32_t bg = table_u32(row_words, 1);
+  // the band [blo, bhi) of keys: empty (no key is >= 0xffffffff) unless the row carries one
+  const bool banded = pred && opt.band && table_u32(row_words, 4) != 0;
+  const uint32_t blo = banded ? table_u32(row_words, 5) : 0xffffffffu;
+  const uint32_t bhi = banded ? table_u32(row_words, 6) : 0xffffffffu;
+  const uint32_t bsh = banded ? table_u32(row_words, 7) : 31u;
+  uint32_t* bh = ws.bhist + static_cast<size_t>(row) * kBandBuckets;
   const uint32_t d = geo.d;
   const uint32_t q0 = c * kChunk + wave * (kLeanRounds * 256);  // first coordinate of this wavefront's quarter
   const bool full = (c + 1) * static_cast<uint64_t>(kChunk) <= d;
@@ -629,6 +660,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   }
   uint2* stage = stage_all + wave * kStageQ;
   uint32_t cnt = 0;
+  uint32_t n_above = 0, n_from = 0;  // this lane's entries at or above the band's upper end / its lower end
 #pragma unroll
   for (int u = 0; u < kLeanRounds; ++u) {
     const uint32_t j = q0 + u * 256 + lane * 4;
@@ -652,7 +684,12 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
       const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)};
       bool flag[4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) flag[s] = ok[s] && (key_of_bits(bits[s]) >> kL0Shift) >= bg;
+      for (int s = 0; s < 4; ++s) {
+        const uint32_t key = key_of_bits(bits[s]);
+        flag[s] = ok[s] && (key >> kL0Shift) >= bg;
+        n_above += (ok[s] && key >= bhi) ? 1u : 0u;
+        n_from += (ok[s] && key >= blo) ? 1u : 0u;
+      }
       const RoundRank rr = rank_round(flag);
       if (rr.total) {
         uint32_t pos = cnt + rr.below;
@@ -667,34 +704,67 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
     }
   }
   if (!pred) return;  // workgroup-uniform
-  // the chunk's segment: one allocation for the four quarters
-  if (lane == 0) sh_cnt[wave] = cnt;
+  // the chunk's segments of the candidate list and of the band list: one allocation for the four quarters
+  const uint32_t above_w = banded ? wave_sum(n_above) : 0u;
+  const uint32_t band_w = banded ? wave_sum(n_from) - above_w : 0u;  // this quarter's entries inside the band
+  if (lane == 0) { sh_cnt[wave] = cnt; sh_above[wave] = above_w; sh_from[wave] = band_w; }
   __syncthreads();
-  uint32_t before = 0, total = 0;
+  uint32_t before = 0, total = 0, bbefore = 0, btotal = 0, atotal = 0;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
-    const uint32_t t = sh_cnt[w];
+    const uint32_t t = sh_cnt[w], tb = sh_from[w];
     before += static_cast<uint32_t>(w) < wave ? t : 0u;
+    bbefore += static_cast<uint32_t>(w) < wave ? tb : 0u;
     total += t;
+    btotal += tb;
+    atotal += sh_above[w];
   }
-  // the run this chunk appends to, its share of the capacity and its cursor
+  // the run this chunk appends to, its share of the capacities and its cursors (candidates in the low half of a
+  // 64-bit word, band entries in the high half: one atomic advances both)
   const bool runs = sc.cursor_set != kNoCursorSet;  // workgroup-uniform
   const uint32_t run = runs ? c % kSubLists : 0u;
   const uint32_t run_cap = runs ? opt.cap / kSubLists : opt.cap;
   const uint32_t run_base = run * run_cap;
+  const uint32_t brun_cap = runs ? opt.band_cap / kSubLists : opt.band_cap;
+  const uint32_t brun_base = run * brun_cap;
   if (threadIdx.x == 0) {
     uint32_t* cur =
         runs ? ws.xcur + (static_cast<size_t>(sc.cursor_set) * kSubLists + run) * kCursorPitch : &rowp->cursor;
-    const uint32_t off = total ? atomicAdd(cur, total) : 0u;
+    const unsigned long long add = static_cast<unsigned long long>(total) | (static_cast<unsigned long long>(btotal) << 32);
+    const unsigned long long old = add ? atomicAdd(reinterpret_cast<unsigned long long*>(cur), add) : 0ull;
+    const uint32_t off = static_cast<uint32_t>(old), boff = static_cast<uint32_t>(old >> 32);
     sh_off = off;
+    sh_boff = boff;
     ws.desc[sc.chunk_base + c] = make_uint2(run_base + off, total);
+    ws.desc2[sc.chunk_base + c] = make_uint2(brun_base + boff, atotal | (btotal << 13));
+    if (atotal) atomicAdd(runs ? cur + kCursorAboveWord : &rowp->above, atotal);  // nobody waits for it
   }
   __syncthreads();
-  const uint32_t off = sh_off;
-  if (cnt == 0 || off + total > run_cap) return;  // otherwise the list has overflowed and will not be used
+  const uint32_t off = sh_off, boff = sh_boff;
+  if (off + total > run_cap) return;  // the list has overflowed and will not be used (nor will the band)
+  const bool band_fits = boff + btotal <= brun_cap;  // else the band has overflowed and will not be used
   uint2* dst = ws.cand + sc.cand_base + run_base + off + before;
+  uint2* bdst = ws.band + sc.band_base + brun_base + boff + bbefore;
+  uint32_t bat = 0;  // band entries of this quarter written so far
   if (cnt <= static_cast<uint32_t>(kStageQ)) {
-    for (uint32_t q = lane; q < cnt; q += 64) dst[q] = stage[q];
+    for (uint32_t q0s = 0; q0s < cnt; q0s += 64) {
+      const uint32_t q = q0s + lane;
+      uint2 en = make_uint2(0u, 0u);
+      if (q < cnt) {
+        en = stage[q];
+        dst[q] = en;
+      }
+      if (band_w && band_fits) {  // wave-uniform
+        const uint32_t key = key_of_bits(en.y);
+        const bool inb = q < cnt && key >= blo && key < bhi;
+        const uint64_t bb = ballot64(inb);
+        if (inb) {
+          bdst[bat + count_below(bb)] = en;
+          atomicAdd(&bh[(key - blo) >> bsh], 1u);  // the row's bucket histogram; nobody waits for it
+        }
+        bat += popc64(bb);
+      }
+    }
   } else {
     // more candidates than the staging area holds: the quarter's (already stored) values are read again
     uint32_t at = 0;
@@ -703,9 +773,13 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
       float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
       if (j < d) x = *reinterpret_cast<const float4*>(er + j);
       const uint32_t bits[4] = {__float_as_uint(x.x), __float_as_uint(x.y), __float_as_uint(x.z), __float_as_uint(x.w)};
-      bool flag[4];
+      bool flag[4], inb[4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) flag[s] = j + s < d && (key_of_bits(bits[s]) >> kL0Shift) >= bg;
+      for (int s = 0; s < 4; ++s) {
+        const uint32_t key = key_of_bits(bits[s]);
+        flag[s] = j + s < d && (key >> kL0Shift) >= bg;
+        inb[s] = j + s < d && key >= blo && key < bhi;
+      }
       const RoundRank rr = rank_round(flag);
       uint32_t pos = at + rr.below;
 #pragma unroll
@@ -715,6 +789,355 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
           ++pos;
         }
       at += rr.total;
+      if (band_w && band_fits) {  // wave-uniform
+        const RoundRank br = rank_round(inb);
+        uint32_t bpos = bat + br.below;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          if (inb[s]) {
+            if (bpos < band_w) {
+              bdst[bpos] = make_uint2(j + s, bits[s]);
+              atomicAdd(&bh[(key_of_bits(bits[s]) - blo) >> bsh], 1u);
+            }
+            ++bpos;
+          }
+        bat += br.total;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The window of keys in which the next step's threshold is expected, from this step's threshold key `tau` and the
+// one before (0: none).  The keys of positive floats order as the floats do, so the window is set in float
+// arithmetic: the centre extrapolates the last ratio, the half-width is 0.4 % plus 0.4 of the last relative change
+// (training thresholds drift smoothly: the residuals build up over the first dozens of steps) plus 1.5 / sqrt(k)
+// (the k-th largest of a sample scatters by about 1 / (7 sqrt(k)) of its value from step to step, and the
+// extrapolation more than doubles that).  It only decides which route the next step takes, never a result.  guess_valid / guess: the bucket guess the next first pass
+// will use; the window must lie at or above it so that every band entry is also a candidate.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void set_next_band(TopkRow* rowp, uint32_t tau, uint32_t tau_prev, uint32_t guess_valid,
+                                              uint32_t guess, uint32_t k, const TopkOptions& opt) {
+  uint32_t valid = 0, lo = 0, hi = 0, shift = 0;
+  if (guess_valid && opt.band && opt.band_cap && tau >= 0x00800000u && tau < 0x7f000000u) {  // a normal number
+    const float t1 = __uint_as_float(tau);
+    float ratio = 1.0f;
+    if (tau_prev >= 0x00800000u && tau_prev < 0x7f000000u) ratio = t1 / __uint_as_float(tau_prev);
+    ratio = fminf(fmaxf(ratio, 0.5f), 2.0f);
+    const float drift = fabsf(ratio - 1.0f);
+    const float delta = fminf(0.004f + 0.4f * drift + 1.5f / sqrtf(static_cast<float>(k)), 0.25f);
+    const float centre = t1 * ratio;
+    const float flo = centre * (1.0f - delta), fhi = centre * (1.0f + delta);
+    lo = __float_as_uint(flo);
+    hi = __float_as_uint(fhi);
+    const uint32_t floor_key = guess << kL0Shift;
+    if (lo < floor_key) lo = floor_key;
+    valid = (hi < 0x7f800000u && hi > lo && lo >= 0x00800000u) ? 1u : 0u;
+    if (valid)
+      while (((hi - lo - 1u) >> shift) >= kBandBuckets) ++shift;
+  }
+  rowp->band_valid = valid;
+  rowp->band_lo = lo;
+  rowp->band_hi = hi;
+  rowp->band_shift = shift;
+}
+
+// The runs of a problem's band list, from the high halves of the cursors the first pass advanced.
+__device__ __forceinline__ ListRuns band_runs_from_cursors(const TopkWorkspace& ws, const TopkRow* rowp,
+                                                           uint32_t cursor_set, uint32_t cap) {
+  ListRuns L;
+  L.total = 0;
+  L.fits = true;
+  if (cursor_set != kNoCursorSet) {  // uniform
+    L.lists = kSubLists;
+    L.pitch = cap / kSubLists;
+    const uint32_t* cur = ws.xcur + static_cast<size_t>(cursor_set) * kSubLists * kCursorPitch;
+#pragma unroll
+    for (uint32_t s = 0; s < kSubLists; ++s) {
+      L.n[s] = cur[s * kCursorPitch + 1];
+      L.total += L.n[s];
+      L.fits = L.fits && L.n[s] <= L.pitch;
+    }
+  } else {
+    L.lists = 1;
+    L.pitch = 0;
+    L.n[0] = rowp->cursor_band;
+#pragma unroll
+    for (uint32_t s = 1; s < kSubLists; ++s) L.n[s] = 0;
+    L.total = L.n[0];
+    L.fits = L.n[0] <= cap;
+  }
+  return L;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The selection in one launch, for problems whose threshold key falls inside the band the first pass was given.
+// Same geometry as the counting kernel: a workgroup owns a contiguous block of geo.count_cpw chunks.
+//   1. Every workgroup of a problem reads the problem's bucket histogram of band entries (kBandBuckets counts,
+//      added up by the first pass) and the count A of entries at or above the band, and finds by itself the
+//      bucket that holds the k-th largest key: it exists iff A < k <= A + (entries in the band); both lists must
+//      have fitted and the bucket must hold at most kBoundaryCap entries.  Otherwise the problem is left to the
+//      general kernels that follow.  All workgroups of a problem read the same data and decide alike.
+//   2. Per chunk: kept for certain = entries at or above the band + band entries in a bucket above the threshold's;
+//      the workgroup leaves these counts with their prefixes inside the block, and the block's total, in the
+//      tables the last kernel reads (the "equal to tau" columns stay 0).  Band entries in the threshold's bucket
+//      are gathered in a small array of the problem.
+//   3. The last workgroup of the problem to finish ranks the gathered entries by (key descending, coordinate
+//      ascending): the first k - (entries above the bucket) of them are kept, the last of those holds tau;
+//      an entry anywhere is kept iff key > tau, or key == tau and coordinate <= tie_last.  The coordinates of
+//      the kept ones, ascending, let the last kernel add them to the positions of the chunks after them.
+//      It also sets the guess and the band for the next step and clears the histogram.
+// ---------------------------------------------------------------------------------------------
+template <bool UNI>
+__global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace ws, TopkOptions opt, uint32_t use_guess) {
+  __shared__ uint32_t lh[kBandBuckets];
+  __shared__ uint32_t suf[kWG + 1];
+  __shared__ uint32_t out2[2];
+  __shared__ uint32_t l_gt[kMaxCountCpw];
+  __shared__ uint32_t scratch[kWG / 64 + 1];
+  __shared__ uint32_t sh_flag;
+  __shared__ uint2 b_en[kBoundaryCap];
+  __shared__ uint32_t b_rank[kBoundaryCap];
+  const SegCtx sc = seg_ctx<UNI, kClassCount>(geo, opt, ws);
+  const uint32_t row = sc.seg, t = threadIdx.x;
+  const uint32_t cpw = geo.count_cpw, nc = geo.num_chunks, k = geo.k;
+  const uint32_t start = sc.group * cpw;
+  if (start >= nc) return;  // uniform; the grid has exactly the blocks that exist
+  const uint32_t end = start + cpw < nc ? start + cpw : nc;
+  TopkRow* rowp = ws.rows + row;
+  uint32_t* bh = ws.bhist + static_cast<size_t>(row) * kBandBuckets;
+  const uint32_t wave = t >> 6, lane = lane_id();
+  constexpr int kGroup = 8;  // chunks a wavefront takes at a time: descriptors with one load, entries together
+  // Everything that can be asked for before anything is known goes out together (a workgroup's work is a chain
+  // of round trips otherwise): the control block and the cursors, the bucket histogram, the counts above the
+  // band, the first descriptors.
+  const uint2* d2 = ws.desc2 + sc.chunk_base;
+  const uint32_t c_first = start + wave * kGroup;
+  uint2 ds = make_uint2(0, 0);
+  if (lane < kGroup && c_first + lane < end) ds = d2[c_first + lane];
+  uint32_t x[kBandBuckets / kWG];
+#pragma unroll
+  for (uint32_t i = 0; i < kBandBuckets / kWG; ++i) x[i] = bh[i * kWG + t];
+  uint32_t total_above = rowp->above;
+  if (sc.cursor_set != kNoCursorSet) {
+    total_above = 0;
+#pragma unroll
+    for (uint32_t s = 0; s < kSubLists; ++s)
+      total_above += ws.xcur[(static_cast<size_t>(sc.cursor_set) * kSubLists + s) * kCursorPitch + kCursorAboveWord];
+  }
+  const uint32_t blo = rowp->band_lo, bhi = rowp->band_hi, bsh = rowp->band_shift, bg = rowp->b_guess;
+  const uint32_t tau_before = rowp->tau;  // last step's threshold key (asked for here: the last workgroup needs it)
+  const ListRuns cand = runs_from_cursors(ws, rowp, sc.cursor_set, opt.cap);
+  const ListRuns band = band_runs_from_cursors(ws, rowp, sc.cursor_set, opt.band_cap);
+  // all of it was written by earlier launches: the same for every workgroup of the problem
+  const bool banded = use_guess && opt.band && !opt.force_dense && rowp->pred_valid != 0 && rowp->band_valid != 0;
+  if (!(banded && cand.fits && band.fits && bhi > blo)) {
+    // Not this route.  The first pass may still have counted (lists that did not fit): one workgroup clears the
+    // problem's histogram and counters; nobody of this launch makes use of them.
+    if (sc.group == 0) {
+      if (banded)
+        for (uint32_t b = t; b < kBandBuckets; b += kWG) bh[b] = 0;
+      if (t == 0) {
+        rowp->fast = 0;
+        rowp->above = 0;
+        if (sc.cursor_set != kNoCursorSet)
+          for (uint32_t s = 0; s < kSubLists; ++s)
+            ws.xcur[(static_cast<size_t>(sc.cursor_set) * kSubLists + s) * kCursorPitch + kCursorAboveWord] = 0;
+      }
+    }
+    return;
+  }
+  // the band entries of this wavefront's first chunks: requested before the histogram is looked at
+  const uint2* bandr = ws.band + sc.band_base;
+  uint32_t off[kGroup], cnt[kGroup];
+  uint2 a[kGroup];
+  auto request = [&](const uint2& d) {
+    uint32_t cnt_l = (d.y >> 13) & 0x1fffu;
+    if (d.x > opt.band_cap) cnt_l = 0;  // segments always lie inside the list; never read outside it
+    else if (cnt_l > opt.band_cap - d.x) cnt_l = opt.band_cap - d.x;
+#pragma unroll
+    for (int u = 0; u < kGroup; ++u) {
+      off[u] = __builtin_amdgcn_readlane(d.x, u);
+      cnt[u] = __builtin_amdgcn_readlane(cnt_l, u);
+      a[u] = lane < cnt[u] ? bandr[off[u] + lane] : make_uint2(0, 0);
+    }
+  };
+  request(ds);
+  // ---- 1. the bucket of the threshold key ----
+#pragma unroll
+  for (uint32_t i = 0; i < kBandBuckets / kWG; ++i) lh[i * kWG + t] = x[i];
+  __syncthreads();
+  bool inside = total_above < k && k - total_above <= band.total;  // uniform
+  uint32_t bstar = 0, need = 0;
+  if (inside) {
+    find_crossing<kBandBuckets>(lh, k - total_above, suf, out2);
+    bstar = out2[0];
+    need = k - total_above - out2[1];       // how many entries of bucket bstar are kept: 1 <= need <= lh[bstar]
+    inside = lh[bstar] <= kBoundaryCap;
+  }
+  const uint32_t n_boundary = inside ? lh[bstar] : 0u;
+  // ---- 2. per chunk: entries kept for certain; the threshold bucket's entries are gathered ----
+  if (inside) {
+    uint2* bnd = ws.bnd + static_cast<size_t>(row) * kBoundaryCap;
+    for (uint32_t c0 = c_first; c0 < end; c0 += kWaves * kGroup) {
+      if (c0 != c_first) {  // wave-uniform
+        ds = make_uint2(0, 0);
+        if (lane < kGroup && c0 + lane < end) ds = d2[c0 + lane];
+        request(ds);
+      }
+      uint32_t gt[kGroup];  // wave-uniform
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u) {
+        gt[u] = 0;
+        for (uint32_t q = 0; q < cnt[u]; q += 64) {  // one trip unless the chunk holds more than 64 band entries
+          const uint2 en = q == 0 ? a[u] : (q + lane < cnt[u] ? bandr[off[u] + q + lane] : make_uint2(0, 0));
+          const bool ok = q + lane < cnt[u];
+          const uint32_t bucket = (key_of_bits(en.y) - blo) >> bsh;
+          gt[u] += popc64(ballot64(ok && bucket > bstar));
+          if (ok && bucket == bstar) {
+            const uint32_t slot = atomicAdd(&rowp->bnd_n, 1u);
+            if (slot < kBoundaryCap) {  // always: the histogram counted these entries
+              __hip_atomic_store(&bnd[slot].x, en.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              __hip_atomic_store(&bnd[slot].y, en.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+          }
+        }
+      }
+      uint32_t mine = 0;
+#pragma unroll
+      for (int u = 0; u < kGroup; ++u)
+        if (lane == static_cast<uint32_t>(u)) mine = gt[u];
+      if (lane < kGroup && c0 + lane < end) l_gt[c0 - start + lane] = (ds.y & 0x1fffu) + mine;
+    }
+    __syncthreads();
+    // exclusive prefixes within the block: thread t takes `per` consecutive chunks
+    const uint32_t len = end - start;
+    const uint32_t per = (cpw + kWG - 1) / kWG;  // <= kMaxCountCpw / kWG
+    const uint32_t first = t * per;
+    uint32_t sum_gt = 0;
+    for (uint32_t i = 0; i < per; ++i)
+      if (first + i < len) sum_gt += l_gt[first + i];
+    uint32_t tot_gt;
+    uint32_t pre_gt = block_excl_scan<kWG>(sum_gt, scratch, &tot_gt);
+    uint4* rec = ws.chunk_rec + sc.chunk_base + start;
+    for (uint32_t i = 0; i < per; ++i)
+      if (first + i < len) {
+        const uint32_t g = l_gt[first + i];
+        rec[first + i] = make_uint4(g, 0u, pre_gt, 0u);
+        pre_gt += g;
+      }
+    if (t == 0) ws.blk[static_cast<size_t>(row) * kMaxCountBlocks + sc.group] = make_uint2(tot_gt, 0u);
+  }
+  // ---- 3. the problem-wide part, by whichever of its workgroups finishes last ----
+  if (!last_group_of_row(&rowp->ticket_band, sc.groups, &sh_flag)) return;
+  for (uint32_t b = t; b < kBandBuckets; b += kWG) bh[b] = 0;  // every workgroup has read it
+  uint32_t n_kept = 0;
+  if (inside) {
+    // the gathered entries (written by other workgroups with device-scope stores: read at that scope)
+    const uint2* bnd = ws.bnd + static_cast<size_t>(row) * kBoundaryCap;
+    const AgentView view = agent_view(reinterpret_cast<const uint32_t*>(bnd), 2 * kBoundaryCap);
+    if (t < kBoundaryCap) {
+      uint2 en = make_uint2(0xffffffffu, 0u);
+      if (t < n_boundary) en = make_uint2(load_agent(view, 2 * t), load_agent(view, 2 * t + 1));
+      b_en[t] = en;
+    }
+    __syncthreads();
+    // rank by (key descending, coordinate ascending): coordinates are distinct, so ranks are
+    bool kept = false;
+    uint32_t my_key = 0, my_coord = 0xffffffffu;
+    if (t < n_boundary) {
+      my_key = key_of_bits(b_en[t].y);
+      my_coord = b_en[t].x;
+      uint32_t rank = 0;
+      for (uint32_t q = 0; q < n_boundary; ++q) {
+        const uint32_t kq = key_of_bits(b_en[q].y), cq = b_en[q].x;
+        rank += (kq > my_key || (kq == my_key && cq < my_coord)) ? 1u : 0u;
+      }
+      kept = rank < need;
+      if (rank == need - 1) { out2[0] = my_key; out2[1] = my_coord; }  // the last kept one: tau and the last tie taken
+    }
+    __syncthreads();
+    const uint32_t tau = out2[0], last_coord = out2[1];
+    // ties, and the kept entries' coordinates in ascending order
+    if (t < kBoundaryCap) b_rank[t] = 0xffffffffu;
+    __syncthreads();
+    uint32_t is_tie = 0;
+    if (t < n_boundary) {
+      is_tie = my_key == tau ? 1u : 0u;
+      if (kept) {
+        uint32_t pos = 0;
+        for (uint32_t q = 0; q < n_boundary; ++q) {
+          const uint32_t kq = key_of_bits(b_en[q].y), cq = b_en[q].x;
+          const bool kept_q = kq > tau || (kq == tau && cq <= last_coord);
+          pos += (kept_q && cq < my_coord) ? 1u : 0u;
+        }
+        b_rank[pos] = my_coord;
+      }
+    }
+    __syncthreads();
+    static_assert(kBoundaryCap <= 64, "the first wavefront holds all of it");
+    if (wave == 0) {
+      const uint32_t ties = popc64(ballot64(is_tie != 0));
+      const uint32_t ties_in = popc64(ballot64(is_tie != 0 && my_coord <= last_coord));
+      if (lane == 0) { suf[0] = ties; suf[1] = ties_in; }
+    }
+    __syncthreads();
+    const uint32_t n_ties = suf[0];
+    n_kept = need;
+    uint32_t* sel = ws.bnd_sel + static_cast<size_t>(row) * kBoundaryCap;
+    if (t < kBoundaryCap) sel[t] = b_rank[t];
+    if (t == 0) {
+      // ties kept: those at coordinates <= last_coord; all of them if the last tie is kept
+      const uint32_t ties_kept = suf[1], ties_after = n_ties - ties_kept;
+      const uint32_t tau_prev = tau_before;
+      rowp->fast = 1;
+      rowp->level1_done = 1;
+      rowp->mode = kModeCand;
+      rowp->n_src = cand.total;
+      rowp->tau_prev = tau_prev;
+      rowp->tau = tau;
+      rowp->r = ties_kept;
+      rowp->ties = n_ties;
+      rowp->tie_last = ties_after ? last_coord : 0xffffffffu;
+      rowp->bnd_kept = n_kept;
+      ws.tau[row] = tau;
+      ws.count_gt[row] = k - ties_kept;
+      uint32_t* cn = ws.counters + row * kCountersPerRow;
+      cn[0] = 0;
+      cn[1] = cand.total;
+      cn[2] = n_ties;
+      cn[3] = ties_kept;
+      cn[4] = band.total;
+      // Guess for the next step, as the general route sets it but from what is known here: the candidate list held
+      // cand.total entries at or above bucket bg, so that many bound the entries from any bucket >= bg upwards;
+      // of the bucket below bg nothing is known, and it is taken to hold at most as many again.
+      const uint32_t b0 = tau >> kL0Shift;  // >= bg
+      uint32_t valid = 0, guess = 0;
+      if (opt.predict) {
+        const uint32_t bound = b0 > bg ? cand.total : 2u * cand.total;  // entries from bucket b0 - 1 upwards
+        if (b0 && bound <= opt.cap / 2) { valid = 1; guess = b0 - 1; }
+        else if (cand.total <= opt.cap / 2) { valid = 1; guess = b0; }
+      }
+      rowp->pred_valid = valid;
+      rowp->b_guess = guess;
+      set_next_band(rowp, tau, tau_prev, valid, guess, k, opt);
+    }
+  } else if (t == 0) {
+    rowp->fast = 0;
+  }
+  if (t == 0) {
+    rowp->above = 0;
+    rowp->bnd_n = 0;
+    if (inside) {  // the cursors go back to zero for the next step (else the general kernels still read them)
+      rowp->cursor = 0;
+      rowp->cursor_band = 0;
+    }
+    if (sc.cursor_set != kNoCursorSet) {
+      for (uint32_t s = 0; s < kSubLists; ++s) {
+        uint32_t* cur = ws.xcur + (static_cast<size_t>(sc.cursor_set) * kSubLists + s) * kCursorPitch;
+        if (inside) { cur[0] = 0; cur[1] = 0; }
+        cur[kCursorAboveWord] = 0;
+      }
     }
   }
 }
@@ -739,6 +1162,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
   const SegCtx sc = seg_ctx<UNI, kClassLevel0>(geo, opt, ws);
   const uint32_t row = sc.seg;
   TopkRow* rowp = ws.rows + row;
+  if (rowp->fast) return;  // the threshold was found in the band (k_topk_band); same for the whole row
   const uint32_t bg = rowp->b_guess;
   const ListRuns runs = runs_from_cursors(ws, rowp, sc.cursor_set, opt.cap);  // written by the previous launch
   const bool listed = use_guess && rowp->pred_valid != 0 && runs.total >= geo.k && runs.fits && !opt.force_dense;
@@ -807,10 +1231,14 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
 #pragma unroll
     for (uint32_t s = 0; s < kSubLists; ++s) rowp->n_sub[s] = listed ? runs.n[s] : (s == 0 ? n_src : 0u);
     rowp->cursor = 0;
+    rowp->cursor_band = 0;
     if (sc.cursor_set != kNoCursorSet) {
 #pragma unroll
-      for (uint32_t s = 0; s < kSubLists; ++s)
-        ws.xcur[(static_cast<size_t>(sc.cursor_set) * kSubLists + s) * kCursorPitch] = 0;
+      for (uint32_t s = 0; s < kSubLists; ++s) {
+        uint32_t* cur = ws.xcur + (static_cast<size_t>(sc.cursor_set) * kSubLists + s) * kCursorPitch;
+        cur[0] = 0;
+        cur[1] = 0;
+      }
     }
     rowp->bstar = bstar;
     rowp->need = geo.k - above;
@@ -827,7 +1255,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
     }
     rowp->pred_valid = valid;
     rowp->b_guess = guess;
-    uint32_t* cn = ws.counters + row * 4;
+    uint32_t* cn = ws.counters + row * kCountersPerRow;
     cn[0] = reads;
     cn[1] = n_src;
     sh_l1 = (listed && bstar - bg < kTracked) ? 1u + (bstar - bg) : 0u;
@@ -868,7 +1296,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e
   const SegCtx sc = seg_ctx<UNI, kClassSweep>(geo, opt, ws);
   const uint32_t row = sc.seg;
   TopkRow* rowp = ws.rows + row;
-  if (rowp->level1_done) return;
+  if (rowp->fast || rowp->level1_done) return;
   const uint32_t mode = rowp->mode, bstar = rowp->bstar, need = rowp->need;
   for (int b = threadIdx.x; b < kNB1; b += kWG) lh[b] = 0;
   __syncthreads();
@@ -941,6 +1369,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
   const SegCtx sc = seg_ctx<UNI, kClassSweep>(geo, opt, ws);
   const uint32_t row = sc.seg;
   TopkRow* rowp = ws.rows + row;
+  if (rowp->fast) return;
   const uint32_t mode = rowp->mode, want = rowp->prefix1, need = rowp->need;
   for (int b = threadIdx.x; b < kNB2; b += kWG) lh[b] = 0;
   __syncthreads();
@@ -976,15 +1405,19 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
     const uint32_t s = out2[0], above = out2[1];
     const uint32_t tau = (want << kL1Shift) | s;
     const uint32_t r = need - above, ties = lh[s];
+    const uint32_t tau_prev = rowp->tau;
+    rowp->tau_prev = tau_prev;
     rowp->tau = tau;
     rowp->r = r;
     rowp->ties = ties;
-    rowp->take_all_ties = (r == ties);
     ws.tau[row] = tau;
     ws.count_gt[row] = geo.k - r;
-    uint32_t* cn = ws.counters + row * 4;
+    uint32_t* cn = ws.counters + row * kCountersPerRow;
     cn[2] = ties;
     cn[3] = r;
+    cn[4] = 0;
+    // the guess was set when the threshold bucket was found (first kernel of this route, an earlier launch)
+    set_next_band(rowp, tau, tau_prev, rowp->pred_valid, rowp->b_guess, geo.k, opt);
   }
 }
 
@@ -1064,6 +1497,7 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
   if (start >= geo.num_chunks) return;  // uniform; the grid has exactly the blocks that exist
   const uint32_t end = start + cpw < geo.num_chunks ? start + cpw : geo.num_chunks;
   const TopkRow* rowp = ws.rows + row;
+  if (rowp->fast) return;
   const uint32_t mode = rowp->mode, tau = rowp->tau;
   const float* er = e + sc.elem_off;
   const uint2* candr = ws.cand + sc.cand_base;
@@ -1170,15 +1604,21 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
 // One wavefront writes the selected entries of chunk c of one selection problem to their places in the list:
 // `at` is where the chunk's slice starts, eq_seen how many keys equal to tau lie in earlier chunks (ties are
 // taken in coordinate order until r are in).  Coordinates are written relative to the worker's row
-// (coord_base = the problem's first coordinate there).
+// (coord_base = the problem's first coordinate there).  by_coord: the ties to keep are given as "up to and
+// including coordinate tie_last of the problem" (k_topk_band) instead of through r and eq_seen.
 __device__ __forceinline__ void emit_chunk(uint32_t mode, const float* __restrict__ er, uint32_t d, uint32_t c,
                                            const uint2* __restrict__ candr, const uint2* __restrict__ descr,
                                            uint32_t cap, uint32_t tau, uint32_t r, bool all_ties, uint32_t eq_seen,
                                            uint32_t at, int32_t* __restrict__ idx, float* __restrict__ val, uint32_t k,
-                                           uint32_t coord_base) {
+                                           uint32_t coord_base, bool by_coord, uint32_t tie_last) {
   for_each_round(mode, er, d, c, candr, descr, cap, [&](const Entry4& en, int slots) {
     bool sel[4] = {false, false, false, false};
-    if (all_ties) {
+    if (by_coord) {
+      for (int s = 0; s < slots; ++s) {
+        const uint32_t key = key_of_bits(en.bits[s]);
+        sel[s] = en.ok[s] && (key > tau || (key == tau && en.j[s] <= tie_last));
+      }
+    } else if (all_ties) {
       for (int s = 0; s < slots; ++s) sel[s] = en.ok[s] && key_of_bits(en.bits[s]) >= tau;
     } else {
       uint64_t be[4];
@@ -1219,12 +1659,6 @@ __device__ __forceinline__ void emit_chunk(uint32_t mode, const float* __restric
 
 constexpr int kPerWave = 4;                       // workers per wavefront and tile
 constexpr int kTileWorkers = kWaves * kPerWave;
-
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
-  return v;
-}
 
 // ROLE: kWholeStep runs all phases; kWorkerHalf stops after phase 1 (the workers' lines of Algorithm 2: the
 // lists are the messages); kServerHalf starts at phase 2 from lists that were put into the workspace (the
@@ -1281,7 +1715,7 @@ __device__ __forceinline__ FinalCtx final_ctx(const Geometry& geo, const TopkWor
 // STREAM: streaming accesses for theta, m, v, vhat (a template parameter: as a run-time choice between two
 // otherwise identical branches the compiler merges them and drops the hint).
 template <int ROLE, bool UNI, bool STREAM>
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_topk_final(
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7, 8))) void k_topk_final(
     float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v, float* __restrict__ vhat,
     const float* __restrict__ e, Geometry geo, TopkWorkspace ws, TopkOptions opt, AmsParams p, TopkFlat flat) {
   static_assert(UNI || ROLE == kWholeStep, "the halves of a step work on whole rows");
@@ -1294,7 +1728,10 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
   if (ROLE != kWorkerHalf)
     for (int t = threadIdx.x; t < kChunk; t += kWG) gs[t] = 0.0f;
   if (ROLE != kServerHalf && c == 0)  // the next step's first pass allocates its candidate lists from the start
-    for (uint32_t i = threadIdx.x; i < geo.n; i += kWG) ws.rows[f.row0 + i * f.row_stride].cursor = 0;
+    for (uint32_t i = threadIdx.x; i < geo.n; i += kWG) {
+      ws.rows[f.row0 + i * f.row_stride].cursor = 0;
+      ws.rows[f.row0 + i * f.row_stride].cursor_band = 0;
+    }
   const uint32_t my_block = c / f.count_cpw;  // count blocks before this chunk's
 
   for (uint32_t i0 = 0; i0 < geo.n; i0 += kTileWorkers) {
@@ -1310,6 +1747,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       uint4 rec[kPerWave];
       uint2 part[kPerWave];
       uint32_t r_[kPerWave];
+      uint32_t fast_mask = 0;  // wave-uniform: bit u = worker u of this wavefront was selected by k_topk_band
 #pragma unroll
       for (int u = 0; u < kPerWave; ++u) {
         const uint32_t i = i0 + wave + u * kWaves;
@@ -1317,14 +1755,16 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         part[u] = make_uint2(0, 0);
         r_[u] = 0;
         if (i < geo.n) {  // wave-uniform
+          const uint32_t rowi = f.row0 + i * f.row_stride;
           rec[u] = ws.chunk_rec[f.chunk0 + i * f.chunk_stride + c];
-          const uint2* blk = ws.blk + static_cast<size_t>(f.row0 + i * f.row_stride) * kMaxCountBlocks;
+          const uint2* blk = ws.blk + static_cast<size_t>(rowi) * kMaxCountBlocks;
           for (uint32_t b = lane; b < my_block; b += 64) {
             const uint2 t = blk[b];
             part[u].x += t.x;
             part[u].y += t.y;
           }
-          r_[u] = ws.rows[f.row0 + i * f.row_stride].r;
+          r_[u] = ws.rows[rowi].r;
+          fast_mask |= (uniform_u32(ws.rows[rowi].fast) ? 1u : 0u) << u;
         }
       }
 #pragma unroll
@@ -1333,19 +1773,52 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
         if (i >= geo.n) continue;  // wave-uniform
         const uint32_t gt_before = wave_sum(part[u].x) + rec[u].z;
         const uint32_t eq_before = wave_sum(part[u].y) + rec[u].w;
-        const uint32_t r = r_[u];
+        const uint32_t r = ((fast_mask >> u) & 1u) ? 0u : r_[u];  // that route does not use the "equal to tau" columns
         const uint32_t taken_before = eq_before < r ? eq_before : r;  // ties go in coordinate order until r are in
         const uint32_t quota = r - taken_before;
         const uint32_t take_here = rec[u].y < quota ? rec[u].y : quota;
         const uint32_t at = gt_before + taken_before;
         const uint32_t hi = at + rec[u].x + take_here;
         if (lane == 0) {
-          uint32_t* so = ws.sel_off + f.seloff0 + i * f.seloff_stride;
-          so[c] = at;  // the next step's first pass finds this chunk's slice of the list here
-          if (c + 1 == f.num_chunks) so[c + 1] = hi;
           sh_lo[i - i0] = at;
           sh_hi[i - i0] = hi;
           sh_eqb[i - i0] = eq_before;
+        }
+      }
+      // A row selected by k_topk_band: the kept entries of the threshold's bucket are not in the tables above.
+      // Their coordinates (ascending, 0xffffffff beyond the last) come with one load per lane; those before the
+      // chunk move its slice of the list up, those inside lengthen it.
+      if (fast_mask) {  // wave-uniform
+        static_assert(kBoundaryCap == 64, "one entry per lane");
+        uint32_t a[kPerWave];
+#pragma unroll
+        for (int u = 0; u < kPerWave; ++u) {
+          const uint32_t i = i0 + wave + u * kWaves;
+          a[u] = 0xffffffffu;
+          if ((fast_mask >> u) & 1u)
+            a[u] = ws.bnd_sel[static_cast<size_t>(f.row0 + i * f.row_stride) * kBoundaryCap + lane];
+        }
+        const uint32_t lo_c = c * kChunk, hi_c = lo_c + kChunk;  // coordinates of the problem
+#pragma unroll
+        for (int u = 0; u < kPerWave; ++u) {
+          const uint32_t i = i0 + wave + u * kWaves;
+          if (!((fast_mask >> u) & 1u)) continue;
+          const uint32_t before = popc64(ballot64(a[u] < lo_c));
+          const uint32_t here = popc64(ballot64(a[u] >= lo_c && a[u] < hi_c));
+          if (lane == 0) {
+            sh_lo[i - i0] += before;
+            sh_hi[i - i0] += before + here;
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kPerWave; ++u) {
+        const uint32_t i = i0 + wave + u * kWaves;
+        if (i >= geo.n) continue;  // wave-uniform
+        if (lane == 0) {
+          uint32_t* so = ws.sel_off + f.seloff0 + i * f.seloff_stride;
+          so[c] = sh_lo[i - i0];  // the next step's first pass finds this chunk's slice of the list here
+          if (c + 1 == f.num_chunks) so[c + 1] = sh_hi[i - i0];
         }
       }
     }
@@ -1362,9 +1835,9 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8, 8))) voi
       float* val = ws.val + f.list0 + i * f.list_stride;
       const TopkRow* rowp = ws.rows + f.row0 + i * f.row_stride;
       const uint32_t mode = rowp->mode, tau = rowp->tau, r = rowp->r;
-      const bool all_ties = rowp->take_all_ties != 0;
+      const bool all_ties = rowp->r == rowp->ties;
       emit_chunk(mode, er, f.d_loc, c, candr, descr, f.cap, tau, r, all_ties, sh_eqb[i - i0], at, idx, val, f.k_loc,
-                 f.coord_base);
+                 f.coord_base, rowp->fast != 0, rowp->tie_last);
     }
     }  // ROLE != kServerHalf
     if (ROLE == kWorkerHalf) continue;
@@ -1472,7 +1945,12 @@ __global__ __launch_bounds__(kWG) void k_topk_emit(const float* __restrict__ e, 
   const uint32_t c = slot.group + wave;
   if (c >= sg.num_chunks) return;  // wave-uniform; no barrier in this kernel
   TopkRow* rowp = ws.rows + slot.seg;
-  if (c == 0 && lane == 0) rowp->cursor = 0;  // the next step's first pass allocates its list from the start
+  if (c == 0 && lane == 0) {  // the next step's first pass allocates its list from the start
+    rowp->cursor = 0;
+    rowp->cursor_band = 0;
+  }
+  const uint32_t cap = opt.cap < sg.cap ? opt.cap : sg.cap;
+  const uint32_t r = rowp->r, tau = rowp->tau, mode = rowp->mode;
   const uint4 rec = ws.chunk_rec[sg.chunk_base + c];
   const uint2* blk = ws.blk + static_cast<size_t>(slot.seg) * kMaxCountBlocks;
   const uint32_t my_block = c / sg.count_cpw;
@@ -1482,24 +1960,32 @@ __global__ __launch_bounds__(kWG) void k_topk_emit(const float* __restrict__ e, 
     part.x += t.x;
     part.y += t.y;
   }
-  const uint32_t r = rowp->r, tau = rowp->tau, mode = rowp->mode;
-  const bool all_ties = rowp->take_all_ties != 0;
-  const uint32_t gt_before = wave_sum(part.x) + rec.z;
+  const bool all_ties = rowp->r == rowp->ties;
+  const bool fast = uniform_u32(rowp->fast) != 0;
+  uint32_t gt_before = wave_sum(part.x) + rec.z;
   const uint32_t eq_before = wave_sum(part.y) + rec.w;
-  const uint32_t taken_before = eq_before < r ? eq_before : r;
-  const uint32_t quota = r - taken_before;
+  uint32_t gt_here = rec.x;
+  uint32_t r_pos = r;
+  if (fast) {  // selected by k_topk_band: see the last kernel
+    const uint32_t a = ws.bnd_sel[static_cast<size_t>(slot.seg) * kBoundaryCap + lane];
+    const uint32_t lo_c = c * kChunk, hi_c = lo_c + kChunk;
+    gt_before += popc64(ballot64(a < lo_c));
+    gt_here += popc64(ballot64(a >= lo_c && a < hi_c));
+    r_pos = 0;
+  }
+  const uint32_t taken_before = eq_before < r_pos ? eq_before : r_pos;
+  const uint32_t quota = r_pos - taken_before;
   const uint32_t take_here = rec.y < quota ? rec.y : quota;
   const uint32_t at = gt_before + taken_before;
-  const uint32_t hi = at + rec.x + take_here;
+  const uint32_t hi = at + gt_here + take_here;
   if (lane == 0) {
     uint32_t* so = ws.sel_off + sg.seloff_base;
     so[c] = at;
     if (c + 1 == sg.num_chunks) so[c + 1] = hi;
   }
   if (hi == at || sg.micro) return;  // a micro problem's entries were written by the first pass
-  const uint32_t cap = opt.cap < sg.cap ? opt.cap : sg.cap;
   emit_chunk(mode, e + sg.elem_off, sg.d, c, ws.cand + sg.cand_base, ws.desc + sg.chunk_base, cap, tau, r, all_ties,
-             eq_before, at, ws.idx + sg.list_base, ws.val + sg.list_base, sg.k, sg.coord_base);
+             eq_before, at, ws.idx + sg.list_base, ws.val + sg.list_base, sg.k, sg.coord_base, fast, rowp->tie_last);
   (void)geo;
 }
 
@@ -1561,6 +2047,11 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   else
     launch(L, kSlotPassA, k_topk_lean<false, true>, grid_chunks, wg, stream, g, e, geo, ws, opt, use_guess);
   COMPAMS_CHECK_LAUNCH();
+  // the selection in one launch for the rows whose threshold lies in the band; it clears the rows' "fast" mark
+  // otherwise, so it runs in every step (about a microsecond when it has nothing to do)
+  const uint32_t count_blocks = (geo.num_chunks + geo.count_cpw - 1) / geo.count_cpw;  // <= kMaxCountBlocks
+  launch(L, kSlotBand, k_topk_band<true>, dim3(count_blocks, geo.n), wg, stream, geo, ws, opt, use_guess);
+  COMPAMS_CHECK_LAUNCH();
   {
     // about two workgroups per compute unit over all rows: each clears and flushes a whole histogram, and the
     // lists are short (measured on the headline workload: 37 us with 128 workgroups per row, 23 us with 32)
@@ -1573,7 +2064,6 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   COMPAMS_CHECK_LAUNCH();
   launch(L, kSlotLevel2, k_topk_level2<true>, grid_rows, wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
-  const uint32_t count_blocks = (geo.num_chunks + geo.count_cpw - 1) / geo.count_cpw;  // <= kMaxCountBlocks
   launch(L, kSlotCount, k_topk_count<true>, dim3(count_blocks, geo.n), wg, stream, e, geo, ws, opt);
   COMPAMS_CHECK_LAUNCH();
   const dim3 grid_f(geo.num_chunks);
@@ -1604,6 +2094,10 @@ hipError_t topk_blocks_step(const Geometry& geo, const TopkWorkspace& ws, const 
   else
     launch(L, kSlotPassA, k_topk_lean<false, false>, dim3(flat.wg_first), wg, stream, g, e, geo, ws, opt, use_guess);
   COMPAMS_CHECK_LAUNCH();
+  if (flat.wg_count) {
+    launch(L, kSlotBand, k_topk_band<false>, dim3(flat.wg_count), wg, stream, geo, ws, opt, use_guess);
+    COMPAMS_CHECK_LAUNCH();
+  }
   if (flat.wg_level0) {
     launch(L, kSlotLevel0, k_topk_level0<false>, dim3(flat.wg_level0), wg, stream, e, geo, ws, opt, use_guess);
     COMPAMS_CHECK_LAUNCH();

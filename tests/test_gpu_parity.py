@@ -553,7 +553,7 @@ def test_hundred_steps_with_a_drifting_gradient_scale(compressor):
             p.step(g, 1e-3, check=look, label=f"{compressor} step {t}", with_e=(t == 99))
         if compressor != "blocksign":
             torch.cuda.synchronize()
-            rereads += int((p.gpu.compams_state("counters").cpu().numpy().reshape(-1, 4)[:, 0] > 0).sum())
+            rereads += int((p.gpu.compams_state("counters").cpu().numpy().reshape(-1, B.COUNTERS_PER_ROW)[:, 0] > 0).sum())
     if compressor == "topk":
         assert all(p.exact.values()), p.exact
     if compressor != "blocksign":
