@@ -171,7 +171,11 @@ enum {
   COMPAMS_CNT_TIES_TAKEN = 3,  /* how many of those were selected */
   COMPAMS_CNT_BAND = 4,        /* entries in the band list if the threshold key was found there (the selection then
                                   took a single launch), else 0 */
-  COMPAMS_COUNTERS_PER_ROW = 8 /* 5..7 are reserved and read 0 */
+  COMPAMS_CNT_BAND_MISS = 5,   /* why not: 0 = it was; 1 = the step had no window to offer (first steps, options, blocks of
+                                  at most 1024 coordinates); 2 = the candidate list did not fit; 3 = the band list did
+                                  not fit; 4 / 5 = the threshold key lay above / below the window; 6 = its bucket held
+                                  more than 64 entries (many equal or nearly equal magnitudes) */
+  COMPAMS_COUNTERS_PER_ROW = 8 /* 6, 7 are reserved and read 0 */
 };
 
 /* Borrowed DEVICE pointer to a state tensor or to what the workers "sent" in the last step, valid until

@@ -59,7 +59,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t total;
   // top-k
-  size_t rows, counters, hist0, hist1, hist1x, hist2, bhist, xcur, chunk_rec, blk, sel_off, desc, desc2, bnd, bnd_sel, cand, band,
+  size_t rows, flags, counters, hist0, hist1, hist1x, hist2, bhist, xcur, chunk_rec, blk, sel_off, desc, desc2, bnd, bnd_sel, cand, band,
       idx, val, tau, count_gt, wire_total, wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_level0, map_sweep,
       map_count, map_emit, map_final, micro_list;
   // block-sign
@@ -103,7 +103,7 @@ struct BlockShape {
 
 // Entries of a problem's band list: the window around the expected threshold holds a fraction of k.
 uint32_t band_capacity(uint64_t k, uint32_t cap) {
-  uint64_t want = k / 3 + 4096;
+  uint64_t want = k / 2 + 4096;
   if (want > kBandMaxEntries) want = kBandMaxEntries;
   return want > cap ? cap : static_cast<uint32_t>(want);
 }
@@ -159,6 +159,7 @@ Layout make_layout(const compams_config* c) {
     L.cap_alloc = static_cast<uint32_t>(cap);
     L.band_alloc = band_capacity(k, L.cap_alloc);
     L.rows = take(n * sizeof(TopkRow));
+    L.flags = take(64);
     L.counters = take(n * COMPAMS_COUNTERS_PER_ROW * 4);
     L.hist0 = take(n * kNB0 * 4);
     L.hist1 = take(n * kNB1 * 4);
@@ -212,6 +213,7 @@ Layout make_layout(const compams_config* c) {
     L.flat.seloff_stride = static_cast<uint32_t>(chunks + M);
     L.flat.cand_stride = caps;
     L.rows = take(S * sizeof(TopkRow));
+    L.flags = take(64);
     L.counters = take(S * COMPAMS_COUNTERS_PER_ROW * 4);
     L.hist0 = take(S * kNB0 * 4);
     L.hist1 = take(S * kNB1 * 4);
@@ -376,6 +378,7 @@ static void bind_topk_workspace(compams_ctx* ctx, char* w) {
   t.bhist = reinterpret_cast<uint32_t*>(w + lay.bhist);
   t.bnd = reinterpret_cast<uint2*>(w + lay.bnd);
   t.bnd_sel = reinterpret_cast<uint32_t*>(w + lay.bnd_sel);
+  t.flags = reinterpret_cast<uint32_t*>(w + lay.flags);
   t.idx = reinterpret_cast<int32_t*>(w + lay.idx);
   t.val = reinterpret_cast<float*>(w + lay.val);
   t.tau = reinterpret_cast<uint32_t*>(w + lay.tau);

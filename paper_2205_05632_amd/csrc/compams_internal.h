@@ -69,11 +69,11 @@ enum : uint32_t {
 };
 
 // The band: a window of magnitude keys [band_lo, band_hi) in which the next step's threshold key is expected,
-// set from the last two thresholds, cut into kBandBuckets buckets of 2^band_shift keys.  The first pass counts, per
+// set from the last two thresholds, cut into kBandBuckets buckets of equal width (band_bucket below).  The first pass counts, per
 // chunk, the entries at or above band_hi, copies the entries inside the window to a short list of their own (a
 // segment per chunk) and adds them to the row's bucket histogram.  If the threshold does fall inside (checked
 // exactly), one launch finishes the selection from the short list alone (k_topk_band).
-constexpr uint32_t kBandBuckets = 1024;
+constexpr uint32_t kBandBuckets = 2048;
 constexpr uint32_t kBandMaxEntries = 1u << 20;  // capacity of a band list at most
 constexpr uint32_t kBoundaryCap = 64;      // entries in the bucket that holds the threshold key; more: general route
 constexpr uint32_t kCursorAboveWord = 2;   // word of a run's cursor line that counts the run's entries above the band
@@ -86,7 +86,7 @@ struct TopkRow {
   uint32_t cursor_band; // ... and band entries: the two are advanced together as one 64-bit word
   uint32_t band_valid;  // the next first pass may also fill the band list and the bucket histogram
   uint32_t band_lo, band_hi;  // keys; band_lo >= b_guess << kL0Shift, band_hi > band_lo
-  uint32_t band_shift;  // bucket of a key inside the band: (key - band_lo) >> band_shift  (< kBandBuckets)
+  uint32_t band_mul;    // bucket of a key inside the band: see band_bucket()
   uint32_t fast;        // this step's threshold was found in the band: the general kernels skip the problem
   uint32_t mode;        // kMode*
   uint32_t n_src;       // entries in the candidate list (kModeCand / kModeNeedB)
@@ -109,6 +109,17 @@ struct TopkRow {
   uint32_t pad[27];
 };
 static_assert(sizeof(TopkRow) == 256, "TopkRow layout");
+
+// Bucket of a key inside a band of `span` keys starting at lo: floor(rel * kBandBuckets / span) for rel = key - lo,
+// computed as the high word of rel * mul with mul = floor(2^32 * kBandBuckets / span); a band of at most kBandBuckets
+// keys (mul = 0) has a bucket per key.  Non-decreasing in the key and always below kBandBuckets.
+inline uint32_t band_multiplier(uint32_t span) {
+  return span > kBandBuckets ? static_cast<uint32_t>((static_cast<uint64_t>(kBandBuckets) << 32) / span) : 0u;
+}
+__device__ __forceinline__ uint32_t band_multiplier_dev(uint32_t span) {
+  return span > kBandBuckets ? static_cast<uint32_t>((static_cast<uint64_t>(kBandBuckets) << 32) / span) : 0u;
+}
+__device__ __forceinline__ uint32_t band_bucket(uint32_t rel, uint32_t mul) { return mul ? __umulhi(rel, mul) : rel; }
 
 // One selection problem: a worker's whole row (top-k over the flattened gradient) or one block of a worker's
 // row (top-k inside every block).  Index fields count entries of the respective workspace tables.
@@ -170,6 +181,8 @@ struct TopkWorkspace {
   uint32_t* bhist;      // n * kBandBuckets : how many band entries fall into each bucket; zero between steps
   uint2* bnd;           // n * kBoundaryCap : the entries of the bucket that holds the threshold key
   uint32_t* bnd_sel;    // n * kBoundaryCap : coordinates of the kept ones among them, ascending
+  uint32_t* flags;      // [0]: some problem of this step was left to the general kernels (set by k_topk_band, cleared
+                        //      by the step's last kernel): the general kernels return at once otherwise
   uint2* cand;          // n * cap_alloc  : (coordinate, fp32 bits)
   int32_t* idx;         // n * k
   float* val;           // n * k

@@ -12,7 +12,7 @@
 //                  entries at or above the guessed bucket, a segment per chunk.  When the last two thresholds
 //                  also give a band of keys in which this step's threshold is expected, it counts per chunk the
 //                  entries above the band, lists the entries inside it (a segment per chunk again) and adds
-//                  them to the row's histogram of 1024 buckets across the band.
+//                  them to the row's histogram of 2048 buckets across the band.
 //   band           if the threshold key does lie in the band (decided exactly from the counts): per chunk the
 //                  entries kept for certain, their prefixes inside blocks of chunks and the block totals; the
 //                  few entries of the threshold's bucket are ranked by the last workgroup of the row, which
@@ -404,6 +404,7 @@ __device__ __forceinline__ void micro_problem(const float* __restrict__ g, float
     cn[2] = ties;
     cn[3] = r_take;
     cn[4] = 0;
+    cn[5] = 1;
     ws.chunk_rec[sg.chunk_base] = make_uint4(gt, ties, 0u, 0u);  // one chunk, nothing before it
     ws.blk[static_cast<size_t>(seg) * kMaxCountBlocks] = make_uint2(gt, ties);
   }
@@ -620,7 +621,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   const uint32_t* row_words = reinterpret_cast<const uint32_t*>(rowp);
   static_assert(offsetof(TopkRow, pred_valid) == 0 && offsetof(TopkRow, b_guess) == 4 &&
                 offsetof(TopkRow, band_valid) == 16 && offsetof(TopkRow, band_lo) == 20 &&
-                offsetof(TopkRow, band_hi) == 24 && offsetof(TopkRow, band_shift) == 28 &&
+                offsetof(TopkRow, band_hi) == 24 && offsetof(TopkRow, band_mul) == 28 &&
                 offsetof(TopkRow, cursor) == 8 && offsetof(TopkRow, cursor_band) == 12,
                 "words read below; the two cursors form one 64-bit word");
   const bool pred = use_guess && table_u32(row_words, 0) != 0;  // workgroup-uniform
@@ -629,7 +630,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   const bool banded = pred && opt.band && table_u32(row_words, 4) != 0;
   const uint32_t blo = banded ? table_u32(row_words, 5) : 0xffffffffu;
   const uint32_t bhi = banded ? table_u32(row_words, 6) : 0xffffffffu;
-  const uint32_t bsh = banded ? table_u32(row_words, 7) : 31u;
+  const uint32_t bmul = banded ? table_u32(row_words, 7) : 0u;
   uint32_t* bh = ws.bhist + static_cast<size_t>(row) * kBandBuckets;
   const uint32_t d = geo.d;
   const uint32_t q0 = c * kChunk + wave * (kLeanRounds * 256);  // first coordinate of this wavefront's quarter
@@ -760,7 +761,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
         const uint64_t bb = ballot64(inb);
         if (inb) {
           bdst[bat + count_below(bb)] = en;
-          atomicAdd(&bh[(key - blo) >> bsh], 1u);  // the row's bucket histogram; nobody waits for it
+          atomicAdd(&bh[band_bucket(key - blo, bmul)], 1u);  // the row's bucket histogram; nobody waits for it
         }
         bat += popc64(bb);
       }
@@ -797,7 +798,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
           if (inb[s]) {
             if (bpos < band_w) {
               bdst[bpos] = make_uint2(j + s, bits[s]);
-              atomicAdd(&bh[(key_of_bits(bits[s]) - blo) >> bsh], 1u);
+              atomicAdd(&bh[band_bucket(key_of_bits(bits[s]) - blo, bmul)], 1u);
             }
             ++bpos;
           }
@@ -810,22 +811,29 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
 // ---------------------------------------------------------------------------------------------
 // The window of keys in which the next step's threshold is expected, from this step's threshold key `tau` and the
 // one before (0: none).  The keys of positive floats order as the floats do, so the window is set in float
-// arithmetic: the centre extrapolates the last ratio, the half-width is 0.4 % plus 0.4 of the last relative change
-// (training thresholds drift smoothly: the residuals build up over the first dozens of steps) plus 1.5 / sqrt(k)
-// (the k-th largest of a sample scatters by about 1 / (7 sqrt(k)) of its value from step to step, and the
-// extrapolation more than doubles that).  It only decides which route the next step takes, never a result.  guess_valid / guess: the bucket guess the next first pass
-// will use; the window must lie at or above it so that every band entry is also a candidate.
+// arithmetic: the centre extrapolates the last ratio; the half-width is 0.4 % plus 0.4 of the last relative change
+// (training thresholds drift smoothly: the residuals build up over the first dozens of steps) plus `noise`, an
+// allowance for the scatter of the k-th largest of a sample from step to step.  With B entries found in a window
+// of relative width w around the threshold, one entry more or fewer above a level moves the k-th largest key by
+// w / B of its value and the count above a level scatters by about sqrt(k): k_topk_band passes 8 w sqrt(k) / B
+// (the extrapolation more than doubles the scatter, and three times the result is allowed for); where no window
+// has been looked at yet, 1.5 / sqrt(k) stands in (as if a fourteenth of the kept entries lay within one per
+// cent of the threshold).  It only decides which route the next step takes, never a result.  guess_valid / guess:
+// the bucket guess the next first pass will use; the window must lie at or above it so that every band entry is
+// also a candidate.
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float default_band_noise(uint32_t k) { return 1.5f / sqrtf(static_cast<float>(k)); }
+
 __device__ __forceinline__ void set_next_band(TopkRow* rowp, uint32_t tau, uint32_t tau_prev, uint32_t guess_valid,
-                                              uint32_t guess, uint32_t k, const TopkOptions& opt) {
-  uint32_t valid = 0, lo = 0, hi = 0, shift = 0;
+                                              uint32_t guess, float noise, const TopkOptions& opt) {
+  uint32_t valid = 0, lo = 0, hi = 0;
   if (guess_valid && opt.band && opt.band_cap && tau >= 0x00800000u && tau < 0x7f000000u) {  // a normal number
     const float t1 = __uint_as_float(tau);
     float ratio = 1.0f;
     if (tau_prev >= 0x00800000u && tau_prev < 0x7f000000u) ratio = t1 / __uint_as_float(tau_prev);
     ratio = fminf(fmaxf(ratio, 0.5f), 2.0f);
     const float drift = fabsf(ratio - 1.0f);
-    const float delta = fminf(0.004f + 0.4f * drift + 1.5f / sqrtf(static_cast<float>(k)), 0.25f);
+    const float delta = fminf(0.004f + 0.4f * drift + fminf(fmaxf(noise, 0.0005f), 0.25f), 0.25f);
     const float centre = t1 * ratio;
     const float flo = centre * (1.0f - delta), fhi = centre * (1.0f + delta);
     lo = __float_as_uint(flo);
@@ -833,13 +841,11 @@ __device__ __forceinline__ void set_next_band(TopkRow* rowp, uint32_t tau, uint3
     const uint32_t floor_key = guess << kL0Shift;
     if (lo < floor_key) lo = floor_key;
     valid = (hi < 0x7f800000u && hi > lo && lo >= 0x00800000u) ? 1u : 0u;
-    if (valid)
-      while (((hi - lo - 1u) >> shift) >= kBandBuckets) ++shift;
   }
   rowp->band_valid = valid;
   rowp->band_lo = lo;
   rowp->band_hi = hi;
-  rowp->band_shift = shift;
+  rowp->band_mul = valid ? band_multiplier_dev(hi - lo) : 0u;
 }
 
 // The runs of a problem's band list, from the high halves of the cursors the first pass advanced.
@@ -925,7 +931,7 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
     for (uint32_t s = 0; s < kSubLists; ++s)
       total_above += ws.xcur[(static_cast<size_t>(sc.cursor_set) * kSubLists + s) * kCursorPitch + kCursorAboveWord];
   }
-  const uint32_t blo = rowp->band_lo, bhi = rowp->band_hi, bsh = rowp->band_shift, bg = rowp->b_guess;
+  const uint32_t blo = rowp->band_lo, bhi = rowp->band_hi, bmul = rowp->band_mul, bg = rowp->b_guess;
   const uint32_t tau_before = rowp->tau;  // last step's threshold key (asked for here: the last workgroup needs it)
   const ListRuns cand = runs_from_cursors(ws, rowp, sc.cursor_set, opt.cap);
   const ListRuns band = band_runs_from_cursors(ws, rowp, sc.cursor_set, opt.band_cap);
@@ -943,6 +949,10 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
         if (sc.cursor_set != kNoCursorSet)
           for (uint32_t s = 0; s < kSubLists; ++s)
             ws.xcur[(static_cast<size_t>(sc.cursor_set) * kSubLists + s) * kCursorPitch + kCursorAboveWord] = 0;
+        uint32_t* cn = ws.counters + row * kCountersPerRow;
+        cn[4] = 0;
+        cn[5] = !banded ? 1u : (!cand.fits ? 2u : 3u);  // no band was set; the candidate list / the band list overflowed
+        ws.flags[0] = 1;  // work for the general kernels
       }
     }
     return;
@@ -968,6 +978,7 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
   for (uint32_t i = 0; i < kBandBuckets / kWG; ++i) lh[i * kWG + t] = x[i];
   __syncthreads();
   bool inside = total_above < k && k - total_above <= band.total;  // uniform
+  const uint32_t miss = total_above >= k ? 4u : (inside ? 6u : 5u);  // the threshold lies above / below the band; or (6) ...
   uint32_t bstar = 0, need = 0;
   if (inside) {
     find_crossing<kBandBuckets>(lh, k - total_above, suf, out2);
@@ -992,7 +1003,7 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
         for (uint32_t q = 0; q < cnt[u]; q += 64) {  // one trip unless the chunk holds more than 64 band entries
           const uint2 en = q == 0 ? a[u] : (q + lane < cnt[u] ? bandr[off[u] + q + lane] : make_uint2(0, 0));
           const bool ok = q + lane < cnt[u];
-          const uint32_t bucket = (key_of_bits(en.y) - blo) >> bsh;
+          const uint32_t bucket = band_bucket(key_of_bits(en.y) - blo, bmul);
           gt[u] += popc64(ballot64(ok && bucket > bstar));
           if (ok && bucket == bstar) {
             const uint32_t slot = atomicAdd(&rowp->bnd_n, 1u);
@@ -1108,6 +1119,7 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
       cn[2] = n_ties;
       cn[3] = ties_kept;
       cn[4] = band.total;
+      cn[5] = 0;
       // Guess for the next step, as the general route sets it but from what is known here: the candidate list held
       // cand.total entries at or above bucket bg, so that many bound the entries from any bucket >= bg upwards;
       // of the bucket below bg nothing is known, and it is taken to hold at most as many again.
@@ -1120,10 +1132,16 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
       }
       rowp->pred_valid = valid;
       rowp->b_guess = guess;
-      set_next_band(rowp, tau, tau_prev, valid, guess, k, opt);
+      const float width = (__uint_as_float(bhi) - __uint_as_float(blo)) / __uint_as_float(tau);  // band keys are normal floats
+      const float noise = 8.0f * width * sqrtf(static_cast<float>(k)) / static_cast<float>(band.total);
+      set_next_band(rowp, tau, tau_prev, valid, guess, noise, opt);
     }
   } else if (t == 0) {
     rowp->fast = 0;
+    uint32_t* cn = ws.counters + row * kCountersPerRow;
+    cn[4] = 0;
+    cn[5] = miss;  // (6): ... its bucket holds more entries than are ranked here
+    ws.flags[0] = 1;  // work for the general kernels
   }
   if (t == 0) {
     rowp->above = 0;
@@ -1154,6 +1172,7 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
 template <bool UNI>
 __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                       TopkOptions opt, uint32_t use_guess) {
+  if (table_u32(ws.flags, 0) == 0) return;  // every problem of this step was selected by k_topk_band
   __shared__ uint32_t lh[kNB0];
   __shared__ uint32_t lh1[kTracked * kNB1];
   __shared__ uint32_t suf[kWG + 1];
@@ -1288,6 +1307,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
 template <bool UNI>
 __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                       TopkOptions opt) {
+  if (table_u32(ws.flags, 0) == 0) return;  // every problem of this step was selected by k_topk_band
   __shared__ uint32_t lh[kNB1];
   __shared__ uint2 stage_all[kWaves * kStage];
   __shared__ uint32_t suf[kWG + 1];
@@ -1362,6 +1382,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e
 template <bool UNI>
 __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                       TopkOptions opt) {
+  if (table_u32(ws.flags, 0) == 0) return;  // every problem of this step was selected by k_topk_band
   __shared__ uint32_t lh[kNB2];
   __shared__ uint32_t suf[kWG + 1];
   __shared__ uint32_t out2[2];
@@ -1417,7 +1438,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
     cn[3] = r;
     cn[4] = 0;
     // the guess was set when the threshold bucket was found (first kernel of this route, an earlier launch)
-    set_next_band(rowp, tau, tau_prev, rowp->pred_valid, rowp->b_guess, geo.k, opt);
+    set_next_band(rowp, tau, tau_prev, rowp->pred_valid, rowp->b_guess, default_band_noise(geo.k), opt);
   }
 }
 
@@ -1488,6 +1509,7 @@ __device__ __forceinline__ void for_each_round(uint32_t mode, const float* __res
 template <bool UNI>
 __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                      TopkOptions opt) {
+  if (table_u32(ws.flags, 0) == 0) return;  // every problem of this step was selected by k_topk_band
   __shared__ uint32_t l_gt[kMaxCountCpw], l_eq[kMaxCountCpw];
   __shared__ uint32_t scratch[kWG / 64 + 1];
   const SegCtx sc = seg_ctx<UNI, kClassCount>(geo, opt, ws);
@@ -1727,6 +1749,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   if (ROLE != kWorkerHalf)
     for (int t = threadIdx.x; t < kChunk; t += kWG) gs[t] = 0.0f;
+  if (ROLE != kServerHalf && blockIdx.x == 0 && threadIdx.x == 0) ws.flags[0] = 0;  // the general kernels have run
   if (ROLE != kServerHalf && c == 0)  // the next step's first pass allocates its candidate lists from the start
     for (uint32_t i = threadIdx.x; i < geo.n; i += kWG) {
       ws.rows[f.row0 + i * f.row_stride].cursor = 0;
@@ -1939,6 +1962,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7
 // the selected entries there, with coordinates of the worker's whole row.  Flat launch over map_emit.
 __global__ __launch_bounds__(kWG) void k_topk_emit(const float* __restrict__ e, Geometry geo, TopkWorkspace ws,
                                                     TopkOptions opt) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) ws.flags[0] = 0;  // the general kernels have run
   const WgSlot slot = ws.map_emit[blockIdx.x];
   const Seg sg = ws.segs[slot.seg];
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
