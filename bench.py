@@ -66,7 +66,7 @@ def load_traffic(workload, kernel):
 class Run:
     """One workload set up on the GPU: context, pre-generated gradients, and the timed loop."""
 
-    def __init__(self, name, steps, warmup, grad_buffers=0, eps_mode=None, predict=True, force_dense=False):
+    def __init__(self, name, steps, warmup, grad_buffers=0, eps_mode=None, predict=True, force_dense=False, band=True):
         import torch
         from paper_2205_05632_amd import binding as B
         from paper_2205_05632_amd import workloads as W
@@ -84,6 +84,8 @@ class Run:
             self.ctx.set_option(B.OPT_PREDICT, 0)
         if force_dense:
             self.ctx.set_option(B.OPT_FORCE_DENSE, 1)
+        if not band and self.comp in (B.TOPK, B.TOPK_BLOCKS):
+            self.ctx.set_option(B.OPT_BAND, 0)
         total = warmup + steps
         scale = W.coordinate_scale(w, self.dev)
         nbuf = total if grad_buffers <= 0 else min(total, grad_buffers)
@@ -196,6 +198,8 @@ def main():
                     help="bracket every kernel with events and print the per-kernel table to stderr")
     ap.add_argument("--no-predict", action="store_true", help="ablation: re-read the row instead of guessing")
     ap.add_argument("--force-dense", action="store_true", help="ablation: no candidate lists at all")
+    ap.add_argument("--no-band", action="store_true",
+                    help="ablation: every selection by the general kernels (no window carried over for the threshold key)")
     ap.add_argument("--grad-buffers", type=int, default=0,
                     help="how many distinct gradient buffers to cycle through (0: one per step)")
     ap.add_argument("--settle-each-step", action="store_true",
@@ -219,7 +223,7 @@ def main():
     dev = torch.device("cuda:0")
     run = Run(args.workload, args.steps, args.warmup, grad_buffers=args.grad_buffers,
               eps_mode=B.EPS_OUT_SQRT if args.eps_out else B.EPS_IN_SQRT, predict=not args.no_predict,
-              force_dense=args.force_dense)
+              force_dense=args.force_dense, band=not args.no_band)
     w, ctx, comp, grads = run.w, run.ctx, run.comp, run.grads
     event_mode = 0 if args.no_kernel_events else (1 if args.kernels else 2)
     main_res = run.timed(event_mode=event_mode, stride=args.event_stride, settle_each_step=args.settle_each_step)
@@ -325,7 +329,7 @@ def main():
         "config": {"workload": w.name, "n": w.n, "d": w.d, "compressor": w.compressor, "k": w.k,
                    "num_blocks": (len(w.block_offsets()) - 1) if w.compressor == "blocksign" else 0,
                    "eps_mode": "out_sqrt" if args.eps_out else "in_sqrt",
-                   "predict": not args.no_predict, "force_dense": args.force_dense},
+                   "predict": not args.no_predict, "force_dense": args.force_dense, "band": not args.no_band},
         "hbm_gbps": main_res["hbm_gbps"],
         "hbm_frac_of_peak": main_res["hbm_frac_of_peak"],
         "algorithmic_bytes_per_step": main_res["algorithmic_bytes_per_step"],

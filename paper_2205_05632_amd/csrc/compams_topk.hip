@@ -293,7 +293,7 @@ __device__ __forceinline__ void resolve_level1(TopkRow* rp, uint32_t bstar, uint
 }
 
 __device__ __forceinline__ void emit_chunk(uint32_t mode, const float* __restrict__ er, uint32_t d, uint32_t c,
-                                           const uint2* __restrict__ candr, const uint2* __restrict__ descr,
+                                           const uint2* __restrict__ candr, uint2 ds,
                                            uint32_t cap, uint32_t tau, uint32_t r, bool all_ties, uint32_t eq_seen,
                                            uint32_t at, int32_t* __restrict__ idx, float* __restrict__ val, uint32_t k,
                                            uint32_t coord_base, bool by_coord = false, uint32_t tie_last = 0);
@@ -409,7 +409,7 @@ __device__ __forceinline__ void micro_problem(const float* __restrict__ g, float
     ws.blk[static_cast<size_t>(seg) * kMaxCountBlocks] = make_uint2(gt, ties);
   }
   // the values come back from where this wavefront has just stored them
-  emit_chunk(kModeDense, er, d, 0u, nullptr, nullptr, 0u, tau, r_take, r_take == ties, 0u, 0u, idx, val, k,
+  emit_chunk(kModeDense, er, d, 0u, nullptr, make_uint2(0u, 0u), 0u, tau, r_take, r_take == ties, 0u, 0u, idx, val, k,
              sg.coord_base);
 }
 
@@ -1455,8 +1455,8 @@ struct Entry4 {
 // f(const Entry4&, int slots) is called wave-uniformly once per round.
 template <typename F>
 __device__ __forceinline__ void for_each_round(uint32_t mode, const float* __restrict__ er, uint32_t d, uint32_t c,
-                                               const uint2* __restrict__ candr, const uint2* __restrict__ descr,
-                                               uint32_t cap, F&& f) {
+                                               const uint2* __restrict__ candr, uint2 ds, uint32_t cap, F&& f) {
+  // ds: the chunk's segment of the candidate list (offset, count), the same in every lane; not looked at without a list
   const uint32_t lane = lane_id();
   if (mode == kModeDense) {
     const uint32_t base = c * kChunk + lane * 4;
@@ -1473,7 +1473,6 @@ __device__ __forceinline__ void for_each_round(uint32_t mode, const float* __res
       f(en, 4);
     }
   } else {
-    const uint2 ds = descr[c];
     const uint32_t off = first_lane(ds.x);
     uint32_t cnt = first_lane(ds.y);
     if (off > cap) cnt = 0;                      // segments always lie inside the list; never read outside it
@@ -1528,7 +1527,7 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
   if (mode == kModeDense) {
     for (uint32_t c = start + wave; c < end; c += kWaves) {
       uint32_t gt = 0, eq = 0;
-      for_each_round(mode, er, geo.d, c, candr, descr, opt.cap, [&](const Entry4& en, int slots) {
+      for_each_round(mode, er, geo.d, c, candr, make_uint2(0u, 0u), opt.cap, [&](const Entry4& en, int slots) {
         for (int s = 0; s < slots; ++s) {
           const uint32_t key = key_of_bits(en.bits[s]);
           gt += popc64(ballot64(en.ok[s] && key > tau));
@@ -1629,11 +1628,11 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
 // (coord_base = the problem's first coordinate there).  by_coord: the ties to keep are given as "up to and
 // including coordinate tie_last of the problem" (k_topk_band) instead of through r and eq_seen.
 __device__ __forceinline__ void emit_chunk(uint32_t mode, const float* __restrict__ er, uint32_t d, uint32_t c,
-                                           const uint2* __restrict__ candr, const uint2* __restrict__ descr,
+                                           const uint2* __restrict__ candr, uint2 ds,
                                            uint32_t cap, uint32_t tau, uint32_t r, bool all_ties, uint32_t eq_seen,
                                            uint32_t at, int32_t* __restrict__ idx, float* __restrict__ val, uint32_t k,
                                            uint32_t coord_base, bool by_coord, uint32_t tie_last) {
-  for_each_round(mode, er, d, c, candr, descr, cap, [&](const Entry4& en, int slots) {
+  for_each_round(mode, er, d, c, candr, ds, cap, [&](const Entry4& en, int slots) {
     bool sel[4] = {false, false, false, false};
     if (by_coord) {
       for (int s = 0; s < slots; ++s) {
@@ -1846,21 +1845,42 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7
       }
     }
     // ---- phase 1b: write the selected entries (positions come back from LDS: written by this wavefront) ----
+    // What a worker's turn needs of its control block and the chunk's segment descriptor is the same in every lane
+    // and was written by earlier launches: it comes through the scalar path, all of it with one round trip, and the
+    // next worker's is asked for before this worker's entries are (a turn was a chain of three round trips).
+    {
+      struct Turn { uint32_t mode, tau, r, ties, fast, tie_last, off, cnt; };
+      auto fetch = [&](uint32_t i) {
+        Turn w{kModeDense, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+        if (i < geo.n && i < i0 + kTileWorkers) {  // wave-uniform
+          const uint32_t* rw = reinterpret_cast<const uint32_t*>(ws.rows + f.row0 + i * f.row_stride);
+          w.mode = table_u32(rw, offsetof(TopkRow, mode) / 4);
+          w.tau = table_u32(rw, offsetof(TopkRow, tau) / 4);
+          w.r = table_u32(rw, offsetof(TopkRow, r) / 4);
+          w.ties = table_u32(rw, offsetof(TopkRow, ties) / 4);
+          w.fast = table_u32(rw, offsetof(TopkRow, fast) / 4);
+          w.tie_last = table_u32(rw, offsetof(TopkRow, tie_last) / 4);
+          const uint32_t* dw = reinterpret_cast<const uint32_t*>(ws.desc + f.chunk0 + i * f.chunk_stride + c);
+          w.off = table_u32(dw, 0);
+          w.cnt = table_u32(dw, 1);
+        }
+        return w;
+      };
+      Turn next = fetch(i0 + wave);
 #pragma unroll 1
-    for (uint32_t i = i0 + wave; i < geo.n && i < i0 + kTileWorkers; i += kWaves) {
-      uint32_t at = sh_lo[i - i0];
-      const uint32_t hi = sh_hi[i - i0];
-      if (hi == at || f.micro) continue;  // nothing of this worker in the chunk, or written already (wave-uniform)
-      const float* er = e + static_cast<int64_t>(i) * geo.ld + f.coord_base;
-      const uint2* candr = ws.cand + f.cand0 + i * f.cand_stride;
-      const uint2* descr = ws.desc + f.chunk0 + i * f.chunk_stride;
-      int32_t* idx = ws.idx + f.list0 + i * f.list_stride;
-      float* val = ws.val + f.list0 + i * f.list_stride;
-      const TopkRow* rowp = ws.rows + f.row0 + i * f.row_stride;
-      const uint32_t mode = rowp->mode, tau = rowp->tau, r = rowp->r;
-      const bool all_ties = rowp->r == rowp->ties;
-      emit_chunk(mode, er, f.d_loc, c, candr, descr, f.cap, tau, r, all_ties, sh_eqb[i - i0], at, idx, val, f.k_loc,
-                 f.coord_base, rowp->fast != 0, rowp->tie_last);
+      for (uint32_t i = i0 + wave; i < geo.n && i < i0 + kTileWorkers; i += kWaves) {
+        const Turn w = next;
+        next = fetch(i + kWaves);
+        const uint32_t at = sh_lo[i - i0];
+        const uint32_t hi = sh_hi[i - i0];
+        if (hi == at || f.micro) continue;  // nothing of this worker in the chunk, or written already (wave-uniform)
+        const float* er = e + static_cast<int64_t>(i) * geo.ld + f.coord_base;
+        const uint2* candr = ws.cand + f.cand0 + i * f.cand_stride;
+        int32_t* idx = ws.idx + f.list0 + i * f.list_stride;
+        float* val = ws.val + f.list0 + i * f.list_stride;
+        emit_chunk(w.mode, er, f.d_loc, c, candr, make_uint2(w.off, w.cnt), f.cap, w.tau, w.r, w.r == w.ties,
+                   sh_eqb[i - i0], at, idx, val, f.k_loc, f.coord_base, w.fast != 0, w.tie_last);
+      }
     }
     }  // ROLE != kServerHalf
     if (ROLE == kWorkerHalf) continue;
@@ -2008,7 +2028,7 @@ __global__ __launch_bounds__(kWG) void k_topk_emit(const float* __restrict__ e, 
     if (c + 1 == sg.num_chunks) so[c + 1] = hi;
   }
   if (hi == at || sg.micro) return;  // a micro problem's entries were written by the first pass
-  emit_chunk(mode, e + sg.elem_off, sg.d, c, ws.cand + sg.cand_base, ws.desc + sg.chunk_base, cap, tau, r, all_ties,
+  emit_chunk(mode, e + sg.elem_off, sg.d, c, ws.cand + sg.cand_base, ws.desc[sg.chunk_base + c], cap, tau, r, all_ties,
              eq_before, at, ws.idx + sg.list_base, ws.val + sg.list_base, sg.k, sg.coord_base, fast, rowp->tie_last);
   (void)geo;
 }
