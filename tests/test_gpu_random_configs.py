@@ -16,6 +16,18 @@ from test_gpu_topk_blocks import BlockPair
 
 pytestmark = pytest.mark.gpu
 
+ROUTES = {"band": 0, "general": 0, "reread": 0}   # selection problems per route over the whole sweep (steps after the first)
+
+
+def tally(gpu, t):
+    if t == 0:
+        return
+    torch.cuda.synchronize()
+    c = gpu.compams_state("counters").cpu().numpy()
+    ROUTES["band"] += int((c[:, 4] > 0).sum())
+    ROUTES["general"] += int(((c[:, 4] == 0) & (c[:, 5] > 1)).sum())
+    ROUTES["reread"] += int((c[:, 0] > 0).sum())
+
 
 def draw_gradients(rng, kind, n, d):
     if kind == "scaled":        # per-coordinate scales over eight decades
@@ -78,15 +90,25 @@ def test_random_configuration(seed):
     label = " ".join(f"{k}={v}" for k, v in cfg.items() if k not in ("off", "kb"))
     print(label, flush=True)
     theta0 = (rng.standard_normal(d) * 0.1).astype(np.float32)
-    steps = 4
+    steps = 9 if seed % 3 == 0 else 4      # the longer ones give the one-launch selection time to settle in
     if cfg["compressor"] == "topk_blocks":
         p = BlockPair(n, d, cfg["off"], cfg["kb"], theta0)
         for t in range(steps):
             p.step(draw_gradients(rng, cfg["kind"], n, d))
             p.compare(f"{label} step {t}", with_e=(t % 2 == 1))
+            tally(p.gpu, t)
     else:
         comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE}[cfg["compressor"]]
         p = Pair(n, d, theta0, comp, k=cfg.get("k", 0), block_offsets=cfg.get("off"), ld=cfg["ld"])
         for t in range(steps):
             p.step(draw_gradients(rng, cfg["kind"], n, d), 1e-3, label=f"{label} step {t}", with_e=(t % 2 == 1))
+            if comp == B.TOPK:
+                tally(p.gpu, t)
     p.close()
+
+
+def test_the_sweep_took_every_route():
+    """The configurations above must have exercised the one-launch selection, the general kernels with a usable
+    candidate list, and the re-read of a row, many times each (else the sweep no longer tests what it is for)."""
+    print(ROUTES, flush=True)
+    assert ROUTES["band"] > 200 and ROUTES["general"] > 200 and ROUTES["reread"] > 100, ROUTES
