@@ -103,7 +103,7 @@ struct BlockShape {
 
 // Entries of a problem's band list: the window around the expected threshold holds a fraction of k.
 uint32_t band_capacity(uint64_t k, uint32_t cap) {
-  uint64_t want = k / 2 + 4096;
+  uint64_t want = k + 4096;
   if (want > kBandMaxEntries) want = kBandMaxEntries;
   return want > cap ? cap : static_cast<uint32_t>(want);
 }

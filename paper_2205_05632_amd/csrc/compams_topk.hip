@@ -811,9 +811,12 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
 // ---------------------------------------------------------------------------------------------
 // The window of keys in which the next step's threshold is expected, from this step's threshold key `tau` and the
 // one before (0: none).  The keys of positive floats order as the floats do, so the window is set in float
-// arithmetic: the centre extrapolates the last ratio; the half-width is 0.4 % plus 0.4 of the last relative change
-// (training thresholds drift smoothly: the residuals build up over the first dozens of steps) plus `noise`, an
-// allowance for the scatter of the k-th largest of a sample from step to step.  With B entries found in a window
+// arithmetic.  Training thresholds drift smoothly while the residuals build up (+34 %, +17 %, +10 %, +7.5 % ... over
+// the first steps of the ResNet-18-shaped workload, +2 % at step ten): with d1 the last relative change and d0 the
+// one before, a drift that is dying down (same sign, |d1| < |d0|) is taken to go on doing so, next = d1 * d1 / d0
+// (not below d1 / 4), and to be off by at most half of what that took away from d1; any other pair of changes is
+// extrapolated flat, next = d1, unsure by 0.4 |d1| + |d1 - d0|.  The centre is tau (1 + next), the half-width
+// 0.4 % + unsure + `noise`, an allowance for the scatter of the k-th largest of a sample from step to step.  With B entries found in a window
 // of relative width w around the threshold, one entry more or fewer above a level moves the k-th largest key by
 // w / B of its value and the count above a level scatters by about sqrt(k): k_topk_band passes 8 w sqrt(k) / B
 // (the extrapolation more than doubles the scatter, and three times the result is allowed for); where no window
@@ -824,17 +827,28 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ float default_band_noise(uint32_t k) { return 1.5f / sqrtf(static_cast<float>(k)); }
 
-__device__ __forceinline__ void set_next_band(TopkRow* rowp, uint32_t tau, uint32_t tau_prev, uint32_t guess_valid,
-                                              uint32_t guess, float noise, const TopkOptions& opt) {
+__device__ __forceinline__ bool normal_key(uint32_t key) { return key >= 0x00800000u && key < 0x7f000000u; }
+
+__device__ __forceinline__ void set_next_band(TopkRow* rowp, uint32_t tau, uint32_t tau_prev, uint32_t tau_prev2,
+                                              uint32_t guess_valid, uint32_t guess, float noise,
+                                              const TopkOptions& opt) {
   uint32_t valid = 0, lo = 0, hi = 0;
-  if (guess_valid && opt.band && opt.band_cap && tau >= 0x00800000u && tau < 0x7f000000u) {  // a normal number
+  if (guess_valid && opt.band && opt.band_cap && normal_key(tau)) {
     const float t1 = __uint_as_float(tau);
-    float ratio = 1.0f;
-    if (tau_prev >= 0x00800000u && tau_prev < 0x7f000000u) ratio = t1 / __uint_as_float(tau_prev);
-    ratio = fminf(fmaxf(ratio, 0.5f), 2.0f);
-    const float drift = fabsf(ratio - 1.0f);
-    const float delta = fminf(0.004f + 0.4f * drift + fminf(fmaxf(noise, 0.0005f), 0.25f), 0.25f);
-    const float centre = t1 * ratio;
+    float d1 = 0.0f;  // the last relative change of the threshold
+    if (normal_key(tau_prev)) d1 = fminf(fmaxf(t1 / __uint_as_float(tau_prev), 0.5f), 2.0f) - 1.0f;
+    float next = d1, unsure = 0.4f * fabsf(d1);  // the change expected next, and how far off that may be
+    if (normal_key(tau_prev) && normal_key(tau_prev2)) {
+      const float d0 = fminf(fmaxf(__uint_as_float(tau_prev) / __uint_as_float(tau_prev2), 0.5f), 2.0f) - 1.0f;
+      if (d0 * d1 > 0.0f && fabsf(d1) < fabsf(d0)) {  // a drift that is dying down: let it go on doing so
+        next = d1 * fmaxf(d1 / d0, 0.25f);
+        unsure = 0.5f * fabsf(d1 - next);
+      } else {
+        unsure += fabsf(d1 - d0);
+      }
+    }
+    const float delta = fminf(0.004f + unsure + fminf(fmaxf(noise, 0.0005f), 0.25f), 0.25f);
+    const float centre = t1 * (1.0f + next);
     const float flo = centre * (1.0f - delta), fhi = centre * (1.0f + delta);
     lo = __float_as_uint(flo);
     hi = __float_as_uint(fhi);
@@ -932,7 +946,8 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
       total_above += ws.xcur[(static_cast<size_t>(sc.cursor_set) * kSubLists + s) * kCursorPitch + kCursorAboveWord];
   }
   const uint32_t blo = rowp->band_lo, bhi = rowp->band_hi, bmul = rowp->band_mul, bg = rowp->b_guess;
-  const uint32_t tau_before = rowp->tau;  // last step's threshold key (asked for here: the last workgroup needs it)
+  const uint32_t tau_before = rowp->tau, tau_before2 = rowp->tau_prev;  // the last two threshold keys (asked for
+                                                                       // here: the last workgroup needs them)
   const ListRuns cand = runs_from_cursors(ws, rowp, sc.cursor_set, opt.cap);
   const ListRuns band = band_runs_from_cursors(ws, rowp, sc.cursor_set, opt.band_cap);
   // all of it was written by earlier launches: the same for every workgroup of the problem
@@ -1134,7 +1149,7 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
       rowp->b_guess = guess;
       const float width = (__uint_as_float(bhi) - __uint_as_float(blo)) / __uint_as_float(tau);  // band keys are normal floats
       const float noise = 8.0f * width * sqrtf(static_cast<float>(k)) / static_cast<float>(band.total);
-      set_next_band(rowp, tau, tau_prev, valid, guess, noise, opt);
+      set_next_band(rowp, tau, tau_prev, tau_before2, valid, guess, noise, opt);
     }
   } else if (t == 0) {
     rowp->fast = 0;
@@ -1426,7 +1441,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
     const uint32_t s = out2[0], above = out2[1];
     const uint32_t tau = (want << kL1Shift) | s;
     const uint32_t r = need - above, ties = lh[s];
-    const uint32_t tau_prev = rowp->tau;
+    const uint32_t tau_prev = rowp->tau, tau_prev2 = rowp->tau_prev;
     rowp->tau_prev = tau_prev;
     rowp->tau = tau;
     rowp->r = r;
@@ -1438,7 +1453,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level2(const float* __restrict__ e
     cn[3] = r;
     cn[4] = 0;
     // the guess was set when the threshold bucket was found (first kernel of this route, an earlier launch)
-    set_next_band(rowp, tau, tau_prev, rowp->pred_valid, rowp->b_guess, default_band_noise(geo.k), opt);
+    set_next_band(rowp, tau, tau_prev, tau_prev2, rowp->pred_valid, rowp->b_guess, default_band_noise(geo.k), opt);
   }
 }
 
