@@ -257,7 +257,28 @@ def main():
         B.compams_copy(dst, src)
     torch.cuda.synchronize()
     copy_gbps = 2.0 * (1 << 30) / ((time.perf_counter() - c0) / 10) / 1e9
-    del src, dst
+
+    # what the box gives the access pattern of the server's lines (theta, m, v, vhat of the workload's size read and
+    # written once, in place, nothing else): each launch follows a copy of 2 GiB of traffic, as a step's server
+    # kernel follows its first pass; both kinds of access (the library takes ordinary ones while the four arrays
+    # fit the memory-side cache, streaming ones beyond)
+    quads = (w.d + 3) // 4 * 4
+    state = [torch.zeros(quads, dtype=torch.float32, device=dev) for _ in range(4)]
+    server_ceiling = {"arrays": 4, "elements_each": quads, "bytes_per_launch": 32 * quads,
+                      "library_uses": "streaming" if 16 * w.d > (192 << 20) else "ordinary"}
+    for kind, streaming in (("ordinary", False), ("streaming", True)):
+        pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+        for a, b in pe:
+            B.compams_copy(dst, src)
+            a.record()
+            B.compams_inplace_probe(state, streaming)
+            b.record()
+        torch.cuda.synchronize()
+        us = sorted(a.elapsed_time(b) * 1e3 for a, b in pe[2:])
+        server_ceiling[kind + "_us_median"] = us[len(us) // 2]
+        server_ceiling[kind + "_us_min"] = us[0]
+        server_ceiling[kind + "_gbps_median"] = 32 * quads / us[len(us) // 2] / 1e3
+    del src, dst, state
 
     # the last step's messages on the wire: sizes (32 bits per word, the accounting of the paper's experiments
     # section) and the time to pack and unpack them; not part of `value`
@@ -335,6 +356,7 @@ def main():
         "algorithmic_bytes_per_step": main_res["algorithmic_bytes_per_step"],
         "step_ms_median": step_ms_median, "step_ms_min": step_ms_min,
         "copy_kernel_gbps": copy_gbps, "hbm_frac_of_copy_kernel": main_res["hbm_gbps"] / copy_gbps,
+        "server_lines_ceiling": server_ceiling,
         "kernel_ms_per_step": kernel_sum_ms,
         "roofline": main_res["roofline"],
         "kernels_us_per_launch": {k_: v_[0] / v_[1] * 1e3 for k_, v_ in prof.items()},

@@ -284,6 +284,17 @@ int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stri
  * beside the step's figures, and the known-size kernel that hardware counters are calibrated against. */
 int compams_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/* A second measured ceiling, for the server's lines of Algorithm 2 (theta, m, v, vhat each read once and
+ * written once, in place): n_arrays (1..4) separately allocated fp32 arrays of `count` elements each are
+ * updated in place, x += 1, by a workgroup per 4096 elements that takes that stretch of every array, 16 bytes
+ * per lane and access - the access pattern of those lines without their arithmetic and without the look-ups
+ * that precede them.  What the box gives this pattern bounds the kernels that apply those lines.
+ *   arrays: HOST array of n_arrays DEVICE pointers (16-byte aligned, distinct, count elements each, modified).
+ *   count: multiple of 4.  streaming: non-zero = non-temporal accesses, zero = ordinary ones (the library's
+ *   own kernels use the latter while the four arrays fit the memory-side cache).
+ * Only enqueues on hip_stream.  COMPAMS_INVALID_ARG / COMPAMS_BAD_ALIGNMENT as for compams_copy. */
+int compams_inplace_probe(float* const* arrays, int n_arrays, size_t count, int streaming, void* hip_stream);
+
 /* ---- One whole step for callers that cannot allocate ------------------------------------------------------
  * For code that runs where no device memory can be allocated or handed over as a workspace (under HIP graph
  * capture, in a tight serving loop, in a harness that forbids it): compams_init + compams_step +

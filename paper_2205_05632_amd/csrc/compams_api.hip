@@ -895,6 +895,18 @@ int compams_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
                                                                                             : COMPAMS_HIP_ERROR;
 }
 
+int compams_inplace_probe(float* const* arrays, int n_arrays, size_t count, int streaming, void* hip_stream) {
+  if (!arrays || n_arrays < 1 || n_arrays > 4 || count > (static_cast<size_t>(1) << 40)) return COMPAMS_INVALID_ARG;
+  for (int a = 0; a < n_arrays; ++a)
+    if (!arrays[a]) return COMPAMS_INVALID_ARG;
+  if (count % 4 != 0) return COMPAMS_BAD_ALIGNMENT;
+  for (int a = 0; a < n_arrays; ++a)
+    if (reinterpret_cast<uintptr_t>(arrays[a]) % 16 != 0) return COMPAMS_BAD_ALIGNMENT;
+  return inplace_probe(arrays, n_arrays, count, streaming != 0, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+             ? COMPAMS_OK
+             : COMPAMS_HIP_ERROR;
+}
+
 // ---- One whole step without a workspace argument -----------------------------------------------------------
 // For callers that cannot hand over (or allocate) a workspace: the tables of the top-k selection live in a
 // device array that is part of the library's code object.  Every device the library runs on holds its own copy

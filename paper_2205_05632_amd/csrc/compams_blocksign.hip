@@ -708,6 +708,32 @@ __global__ __launch_bounds__(kWG) void k_copy16(float* __restrict__ dst, const f
     store_stream4(dst + 4 * i, load_stream4(src + 4 * i));
 }
 
+// The access pattern of the server's lines of Algorithm 2 with nothing else around it: A separately allocated
+// arrays, a workgroup per 4096 elements that takes that stretch of every array, 16 bytes per lane and access, all
+// loads of a round requested before the first is used, every element read, increased by one and written back.
+template <int A, bool STREAM>
+__global__ __launch_bounds__(kWG) void k_inplace_probe(float* a0, float* a1, float* a2, float* a3, size_t count) {
+  float* const arr[4] = {a0, a1, a2, a3};
+#pragma unroll
+  for (int r = 0; r < kChunk / (kWG * 4); ++r) {
+    const size_t j = static_cast<size_t>(blockIdx.x) * kChunk + r * kWG * 4 + threadIdx.x * 4;
+    if (j + 3 < count) {
+      float4 x[A];
+#pragma unroll
+      for (int a = 0; a < A; ++a) x[a] = STREAM ? load_stream4(arr[a] + j) : *reinterpret_cast<const float4*>(arr[a] + j);
+#pragma unroll
+      for (int a = 0; a < A; ++a) {
+        x[a].x += 1.0f; x[a].y += 1.0f; x[a].z += 1.0f; x[a].w += 1.0f;
+      }
+#pragma unroll
+      for (int a = 0; a < A; ++a) {
+        if (STREAM) store_stream4(arr[a] + j, x[a]);
+        else *reinterpret_cast<float4*>(arr[a] + j) = x[a];
+      }
+    }
+  }
+}
+
 }  // namespace
 
 #define COMPAMS_CHECK_LAUNCH()                    \
@@ -789,6 +815,24 @@ hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t str
   if (blocks > 0x7fffffffu) blocks = 0x7fffffffu;
   hipLaunchKernelGGL(k_copy16, dim3(static_cast<uint32_t>(blocks)), dim3(kWG), 0, stream,
                      static_cast<float*>(dst), static_cast<const float*>(src), count);
+  return hipGetLastError();
+}
+
+template <bool STREAM>
+static void launch_inplace_probe(int arrays, dim3 grid, hipStream_t stream, float* const* a, size_t count) {
+  switch (arrays) {
+    case 1: hipLaunchKernelGGL((k_inplace_probe<1, STREAM>), grid, dim3(kWG), 0, stream, a[0], a[0], a[0], a[0], count); break;
+    case 2: hipLaunchKernelGGL((k_inplace_probe<2, STREAM>), grid, dim3(kWG), 0, stream, a[0], a[1], a[1], a[1], count); break;
+    case 3: hipLaunchKernelGGL((k_inplace_probe<3, STREAM>), grid, dim3(kWG), 0, stream, a[0], a[1], a[2], a[2], count); break;
+    default: hipLaunchKernelGGL((k_inplace_probe<4, STREAM>), grid, dim3(kWG), 0, stream, a[0], a[1], a[2], a[3], count); break;
+  }
+}
+
+hipError_t inplace_probe(float* const* arrays, int n_arrays, size_t count, bool streaming, hipStream_t stream) {
+  if (!count) return hipSuccess;
+  const dim3 grid(static_cast<uint32_t>((count + kChunk - 1) / kChunk));
+  if (streaming) launch_inplace_probe<true>(n_arrays, grid, stream, arrays, count);
+  else launch_inplace_probe<false>(n_arrays, grid, stream, arrays, count);
   return hipGetLastError();
 }
 

@@ -294,6 +294,7 @@ hipError_t fill_u32(uint32_t* p, size_t count, uint32_t value, hipStream_t strea
 hipError_t fill_rows_f32(float* p, uint32_t n, int64_t ld, uint32_t d, float value, hipStream_t stream);
 hipError_t copy_u32(uint32_t* dst, const uint32_t* src, size_t count, hipStream_t stream);
 hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+hipError_t inplace_probe(float* const* arrays, int n_arrays, size_t count, bool streaming, hipStream_t stream);
 
 // Launch with optional timing: when the slot is being timed, the launch is bracketed by a pair of events on
 // the same stream.  (Events attached to the dispatch itself give the same durations but slow the step down

@@ -153,6 +153,11 @@ def test_null_context_is_rejected_everywhere():
     assert L.compams_state(None, 0, ctypes.byref(p), ctypes.byref(c)) == -1
     assert L.compams_copy(None, None, 16, None) == -1
     assert L.compams_copy(0x1000, 0x2000, 8, None) == -2
+    two = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    assert L.compams_inplace_probe(None, 1, 16, 0, None) == -1
+    assert L.compams_inplace_probe(two, 5, 16, 0, None) == -1
+    assert L.compams_inplace_probe(two, 2, 6, 0, None) == -2
+    assert L.compams_inplace_probe((ctypes.c_void_p * 2)(0x1000, 0x2004), 2, 16, 0, None) == -2
 
 
 def test_strerror_covers_every_status():
