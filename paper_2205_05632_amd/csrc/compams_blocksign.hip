@@ -465,7 +465,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometr
   const uint32_t* __restrict__ off = ws.offsets;
   const float* __restrict__ mur = ws.scales + static_cast<size_t>(row) * geo.num_blocks;
   uint32_t* bitr = ws.bits + static_cast<size_t>(row) * geo.words;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
   const uint32_t stride = gridDim.x * kWaves;
   const uint32_t d = geo.d;
   for (uint32_t c = blockIdx.x * kWaves + wave; c < geo.num_chunks; c += stride) {
@@ -526,7 +526,7 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
                                                      float* __restrict__ v, float* __restrict__ vhat, Geometry geo,
                                                      BlocksignWorkspace ws, AmsParams p) {
   const uint32_t* __restrict__ off = ws.offsets;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
   const uint32_t d = geo.d;
   // a wavefront takes a quarter of a chunk: four times as many wavefronts hide the latency of the per-round
   // chain (state, sign words, scales -> update -> store) better than one wavefront per chunk does

@@ -598,7 +598,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   __shared__ uint2 stage_all[kWaves * kStageQ];
   __shared__ uint32_t bm_all[PEND ? kWaves * 32 : 1];
   __shared__ uint32_t sh_cnt[kWaves], sh_above[kWaves], sh_from[kWaves], sh_off, sh_boff;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
   if constexpr (!UNI) {
     const WgSlot slot = ws.map_first[blockIdx.x];
     if (slot.seg & kMicroFlag) {  // workgroup-uniform: up to four micro problems, one per wavefront
@@ -926,7 +926,7 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
   const uint32_t end = start + cpw < nc ? start + cpw : nc;
   TopkRow* rowp = ws.rows + row;
   uint32_t* bh = ws.bhist + static_cast<size_t>(row) * kBandBuckets;
-  const uint32_t wave = t >> 6, lane = lane_id();
+  const uint32_t wave = uniform_u32(t >> 6), lane = lane_id();
   constexpr int kGroup = 8;  // chunks a wavefront takes at a time: descriptors with one load, entries together
   // Everything that can be asked for before anything is known goes out together (a workgroup's work is a chain
   // of round trips otherwise): the control block and the cursors, the bucket histogram, the counts above the
@@ -1203,7 +1203,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level0(const float* __restrict__ e
   for (int b = threadIdx.x; b < kNB0; b += kWG) lh[b] = 0;
   for (uint32_t b = threadIdx.x; b < kTracked * kNB1; b += kWG) lh1[b] = 0;
   __syncthreads();
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
   if (listed) {
     sweep_list(ws.cand + sc.cand_base, runs, sc.group * kWG + threadIdx.x, sc.groups * kWG, [&](uint32_t bits) {
       const uint32_t key = key_of_bits(bits);
@@ -1343,7 +1343,7 @@ __global__ __launch_bounds__(kWG) void k_topk_level1(const float* __restrict__ e
   };
   if (mode == kModeNeedB) {
     uint2* descr = ws.desc + sc.chunk_base;
-    const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+    const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
     uint2* stage = stage_all + wave * kStage;
     const uint32_t stride = sc.groups * kWaves;
     for (uint32_t c = sc.group * kWaves + wave; c < geo.num_chunks; c += stride) {
@@ -1538,7 +1538,7 @@ __global__ __launch_bounds__(kWG) void k_topk_count(const float* __restrict__ e,
   const float* er = e + sc.elem_off;
   const uint2* candr = ws.cand + sc.cand_base;
   const uint2* descr = ws.desc + sc.chunk_base;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
   if (mode == kModeDense) {
     for (uint32_t c = start + wave; c < end; c += kWaves) {
       uint32_t gt = 0, eq = 0;
@@ -1760,7 +1760,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7
   const FinalCtx f = final_ctx<UNI>(geo, ws, opt, flat);
   const uint32_t c = f.c;
   const uint32_t base = f.base;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();  // the wavefront's number: a scalar
   if (ROLE != kWorkerHalf)
     for (int t = threadIdx.x; t < kChunk; t += kWG) gs[t] = 0.0f;
   if (ROLE != kServerHalf && blockIdx.x == 0 && threadIdx.x == 0) ws.flags[0] = 0;  // the general kernels have run
@@ -2000,7 +2000,7 @@ __global__ __launch_bounds__(kWG) void k_topk_emit(const float* __restrict__ e, 
   if (blockIdx.x == 0 && threadIdx.x == 0) ws.flags[0] = 0;  // the general kernels have run
   const WgSlot slot = ws.map_emit[blockIdx.x];
   const Seg sg = ws.segs[slot.seg];
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
   const uint32_t c = slot.group + wave;
   if (c >= sg.num_chunks) return;  // wave-uniform; no barrier in this kernel
   TopkRow* rowp = ws.rows + slot.seg;
