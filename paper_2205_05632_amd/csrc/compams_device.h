@@ -91,6 +91,11 @@ typedef const __attribute__((address_space(4))) uint32_t* ScalarTable;
 __device__ __forceinline__ uint32_t table_u32(const uint32_t* p, uint32_t i) {
   return reinterpret_cast<ScalarTable>(reinterpret_cast<uintptr_t>(p))[i];
 }
+// Eight consecutive words of such a table (32-byte aligned) with one scalar load.
+typedef uint32_t U32x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ U32x8 table_u32x8(const uint32_t* p) {
+  return *reinterpret_cast<const __attribute__((address_space(4))) U32x8*>(reinterpret_cast<uintptr_t>(p));
+}
 __device__ __forceinline__ float table_f32(const float* p, uint32_t i) {
   return __uint_as_float(table_u32(reinterpret_cast<const uint32_t*>(p), i));
 }

@@ -615,26 +615,10 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   const float* gr = g + sc.elem_off;
   float* er = e + sc.elem_off;
   TopkRow* rowp = ws.rows + row;
-  // What this pass reads of the row's control block and of the previous step's list offsets was written by earlier
-  // launches and is the same for the whole workgroup: it comes through the scalar path, whose answers do not
-  // queue behind the chunk's loads (vector loads return in order).
-  const uint32_t* row_words = reinterpret_cast<const uint32_t*>(rowp);
-  static_assert(offsetof(TopkRow, pred_valid) == 0 && offsetof(TopkRow, b_guess) == 4 &&
-                offsetof(TopkRow, band_valid) == 16 && offsetof(TopkRow, band_lo) == 20 &&
-                offsetof(TopkRow, band_hi) == 24 && offsetof(TopkRow, band_mul) == 28 &&
-                offsetof(TopkRow, cursor) == 8 && offsetof(TopkRow, cursor_band) == 12,
-                "words read below; the two cursors form one 64-bit word");
-  const bool pred = use_guess && table_u32(row_words, 0) != 0;  // workgroup-uniform
-  const uint32_t bg = table_u32(row_words, 1);
-  // the band [blo, bhi) of keys: empty (no key is >= 0xffffffff) unless the row carries one
-  const bool banded = pred && opt.band && table_u32(row_words, 4) != 0;
-  const uint32_t blo = banded ? table_u32(row_words, 5) : 0xffffffffu;
-  const uint32_t bhi = banded ? table_u32(row_words, 6) : 0xffffffffu;
-  const uint32_t bmul = banded ? table_u32(row_words, 7) : 0u;
-  uint32_t* bh = ws.bhist + static_cast<size_t>(row) * kBandBuckets;
   const uint32_t d = geo.d;
   const uint32_t q0 = c * kChunk + wave * (kLeanRounds * 256);  // first coordinate of this wavefront's quarter
   const bool full = (c + 1) * static_cast<uint64_t>(kChunk) <= d;
+  // The chunk's loads go out before anything else is asked for: nothing below decides their addresses.
   float4 gv[kLeanRounds], ev[kLeanRounds];
 #pragma unroll
   for (int u = 0; u < kLeanRounds; ++u) {
@@ -646,17 +630,49 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
       ev[u] = load_stream4(er + j);
     }
   }
+  // What this pass reads of the row's control block and of the previous step's list offsets was written by earlier
+  // launches and is the same for the whole workgroup: it comes through the scalar path, whose answers do not
+  // queue behind the chunk's loads (vector loads return in order) - the first eight words of the control block
+  // with one load, the list offsets with it, and only then is any of it looked at (one round trip, not one per
+  // condition).
+  static_assert(offsetof(TopkRow, pred_valid) == 0 && offsetof(TopkRow, b_guess) == 4 &&
+                offsetof(TopkRow, band_valid) == 16 && offsetof(TopkRow, band_lo) == 20 &&
+                offsetof(TopkRow, band_hi) == 24 && offsetof(TopkRow, band_mul) == 28 &&
+                offsetof(TopkRow, cursor) == 8 && offsetof(TopkRow, cursor_band) == 12,
+                "words read below; the two cursors form one 64-bit word");
+  const U32x8 rw = table_u32x8(reinterpret_cast<const uint32_t*>(rowp));
+  uint32_t prev_lo = 0, prev_hi = 0;
+  if constexpr (PEND) {
+    const uint32_t* prev_off = ws.sel_off + sc.seloff_base;
+    prev_lo = table_u32(prev_off, c);
+    prev_hi = table_u32(prev_off, c + 1);
+  }
+  const bool pred = use_guess && rw[0] != 0;  // workgroup-uniform
+  const uint32_t bg = rw[1];
+  // the band [blo, bhi) of keys: empty (no key is >= 0xffffffff) unless the row carries one
+  const bool banded = pred && opt.band && rw[4] != 0;
+  const uint32_t blo = banded ? rw[5] : 0xffffffffu;
+  const uint32_t bhi = banded ? rw[6] : 0xffffffffu;
+  const uint32_t bmul = banded ? rw[7] : 0u;
+  uint32_t* bh = ws.bhist + static_cast<size_t>(row) * kBandBuckets;
   uint32_t* bm = bm_all + (PEND ? wave * 32 : 0);
   if constexpr (PEND) {
     // the quarter's coordinates that were selected in the previous step: their residual counts as zero
     if (lane < 32) bm[lane] = 0;
-    const uint32_t* prev_off = ws.sel_off + sc.seloff_base;
     const int32_t* prev_idx = ws.idx + sc.list_base;
-    const uint32_t lo = table_u32(prev_off, c), hi_raw = table_u32(prev_off, c + 1);
-    const uint32_t hi = hi_raw < geo.k ? hi_raw : geo.k;
-    for (uint32_t q = lo + lane; q < hi; q += 64) {
-      const uint32_t jl = static_cast<uint32_t>(prev_idx[q]) - sc.coord_base - q0;
-      if (jl < static_cast<uint32_t>(kLeanRounds * 256)) atomicOr(&bm[jl >> 5], 1u << (jl & 31u));
+    const uint32_t lo = prev_lo;
+    const uint32_t hi = prev_hi < geo.k ? prev_hi : geo.k;
+    // 256 entries of the chunk's slice per trip, requested together (a chunk that holds entries at all holds
+    // 80 to 150 of a worker's: one round trip instead of two or three in a row)
+    for (uint32_t q = lo + lane; q < hi; q += 256) {
+      uint32_t jv[4];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) jv[w] = q + 64 * w < hi ? static_cast<uint32_t>(prev_idx[q + 64 * w]) : 0xffffffffu;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t jl = jv[w] - sc.coord_base - q0;
+        if (q + 64 * w < hi && jl < static_cast<uint32_t>(kLeanRounds * 256)) atomicOr(&bm[jl >> 5], 1u << (jl & 31u));
+      }
     }
   }
   uint2* stage = stage_all + wave * kStageQ;
@@ -1785,23 +1801,51 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7
       uint2 part[kPerWave];
       uint32_t r_[kPerWave];
       uint32_t fast_mask = 0;  // wave-uniform: bit u = worker u of this wavefront was selected by k_topk_band
+      // Nothing is looked at before everything has been asked for (a sum inside the loop that loads, a value moved
+      // to a scalar register where it is loaded, or a branch around a worker's loads makes every worker a round
+      // trip of its own): the chunk's record and the first 128 block totals of each worker as vector loads, r and
+      // the route through the scalar path.  A worker beyond the last reads worker i0's tables and is ignored.
+      uint2 pa[kPerWave], pb[kPerWave];
+      uint32_t fast_[kPerWave];
 #pragma unroll
       for (int u = 0; u < kPerWave; ++u) {
         const uint32_t i = i0 + wave + u * kWaves;
-        rec[u] = make_uint4(0, 0, 0, 0);
-        part[u] = make_uint2(0, 0);
-        r_[u] = 0;
-        if (i < geo.n) {  // wave-uniform
-          const uint32_t rowi = f.row0 + i * f.row_stride;
-          rec[u] = ws.chunk_rec[f.chunk0 + i * f.chunk_stride + c];
-          const uint2* blk = ws.blk + static_cast<size_t>(rowi) * kMaxCountBlocks;
-          for (uint32_t b = lane; b < my_block; b += 64) {
-            const uint2 t = blk[b];
-            part[u].x += t.x;
-            part[u].y += t.y;
+        const uint32_t is = i < geo.n ? i : i0;
+        const uint32_t rowi = f.row0 + is * f.row_stride;
+        rec[u] = ws.chunk_rec[f.chunk0 + is * f.chunk_stride + c];
+        const uint2* blk = ws.blk + static_cast<size_t>(rowi) * kMaxCountBlocks;
+        pa[u] = make_uint2(0, 0);
+        pb[u] = make_uint2(0, 0);
+        if (lane < my_block) pa[u] = blk[lane];
+        if (lane + 64 < my_block) pb[u] = blk[lane + 64];
+        const uint32_t* rw = reinterpret_cast<const uint32_t*>(ws.rows + rowi);
+        r_[u] = table_u32(rw, offsetof(TopkRow, r) / 4);
+        fast_[u] = table_u32(rw, offsetof(TopkRow, fast) / 4);
+      }
+#pragma unroll
+      for (int u = 0; u < kPerWave; ++u) {
+        const bool there = i0 + wave + u * kWaves < geo.n;  // wave-uniform
+        part[u] = make_uint2(pa[u].x + pb[u].x, pa[u].y + pb[u].y);
+        fast_mask |= (there && fast_[u] ? 1u : 0u) << u;
+        if (!there) { rec[u] = make_uint4(0, 0, 0, 0); part[u] = make_uint2(0, 0); r_[u] = 0; }
+      }
+      if (my_block > 128) {  // uniform: rows of more than 128 count blocks
+        static_assert(kMaxCountBlocks <= 256, "four block totals per lane at most");
+#pragma unroll
+        for (int u = 0; u < kPerWave; ++u) {
+          const uint32_t i = i0 + wave + u * kWaves;
+          pa[u] = make_uint2(0, 0);
+          pb[u] = make_uint2(0, 0);
+          if (i < geo.n) {  // wave-uniform
+            const uint2* blk = ws.blk + static_cast<size_t>(f.row0 + i * f.row_stride) * kMaxCountBlocks;
+            if (lane + 128 < my_block) pa[u] = blk[lane + 128];
+            if (lane + 192 < my_block) pb[u] = blk[lane + 192];
           }
-          r_[u] = ws.rows[rowi].r;
-          fast_mask |= (uniform_u32(ws.rows[rowi].fast) ? 1u : 0u) << u;
+        }
+#pragma unroll
+        for (int u = 0; u < kPerWave; ++u) {
+          part[u].x += pa[u].x + pb[u].x;
+          part[u].y += pa[u].y + pb[u].y;
         }
       }
 #pragma unroll
@@ -1929,7 +1973,9 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7
 #pragma unroll
       for (int u = 0; u < kGroup; ++u) {
         const uint32_t i = g0 + u;
-        if (i < i_end) {  // uniform
+        if (i < i_end && hi[u] > lo[u]) {  // the same in every thread of the workgroup: a worker without entries in
+                                           // the chunk (every worker, in more than half of the chunks) adds nothing
+                                           // and needs no barrier
           if (jl[u] < static_cast<uint32_t>(kChunk)) gs[jl[u]] = gs[jl[u]] + vl[u];
           // segments longer than a workgroup: four entries per thread and trip, loads in flight together
           for (uint32_t q = lo[u] + kWG + threadIdx.x; q < hi[u]; q += 4 * kWG) {
