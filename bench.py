@@ -260,24 +260,23 @@ def main():
 
     # what the box gives the access pattern of the server's lines (theta, m, v, vhat of the workload's size read and
     # written once, in place, nothing else): each launch follows a copy of 2 GiB of traffic, as a step's server
-    # kernel follows its first pass; both kinds of access (the library takes ordinary ones while the four arrays
-    # fit the memory-side cache, streaming ones beyond)
+    # kernel follows its first pass; with as many of the four arrays kept in the memory-side cache as the library
+    # keeps for this size, and with none and all four beside it
     quads = (w.d + 3) // 4 * 4
     state = [torch.zeros(quads, dtype=torch.float32, device=dev) for _ in range(4)]
-    server_ceiling = {"arrays": 4, "elements_each": quads, "bytes_per_launch": 32 * quads,
-                      "library_uses": "streaming" if 16 * w.d > (192 << 20) else "ordinary"}
-    for kind, streaming in (("ordinary", False), ("streaming", True)):
+    kept = B.compams_cached_state_arrays(w.d)
+    server_ceiling = {"arrays": 4, "elements_each": quads, "bytes_per_launch": 32 * quads, "library_caches": kept}
+    for cached in sorted({0, kept, 4}):
         pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
         for a, b in pe:
             B.compams_copy(dst, src)
             a.record()
-            B.compams_inplace_probe(state, streaming)
+            B.compams_inplace_probe(state, cached)
             b.record()
         torch.cuda.synchronize()
         us = sorted(a.elapsed_time(b) * 1e3 for a, b in pe[2:])
-        server_ceiling[kind + "_us_median"] = us[len(us) // 2]
-        server_ceiling[kind + "_us_min"] = us[0]
-        server_ceiling[kind + "_gbps_median"] = 32 * quads / us[len(us) // 2] / 1e3
+        server_ceiling[f"cached_{cached}"] = {"us_median": us[len(us) // 2], "us_min": us[0],
+                                              "gbps_median": 32 * quads / us[len(us) // 2] / 1e3}
     del src, dst, state
 
     # the last step's messages on the wire: sizes (32 bits per word, the accounting of the paper's experiments

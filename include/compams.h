@@ -284,16 +284,22 @@ int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stri
  * beside the step's figures, and the known-size kernel that hardware counters are calibrated against. */
 int compams_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
+/* How many of theta, m, v, vhat (in that order) the kernels that apply the server's lines of Algorithm 2 read and
+ * write with ordinary accesses for a problem of d coordinates, so that they stay in the memory-side cache from
+ * one step to the next; the others are streamed past it.  As many as fit a fixed share of that cache together:
+ * 0..4 (4 for every small d).  Pure, host-only; COMPAMS_INVALID_ARG for d < 1. */
+int compams_cached_state_arrays(int64_t d);
+
 /* A second measured ceiling, for the server's lines of Algorithm 2 (theta, m, v, vhat each read once and
  * written once, in place): n_arrays (1..4) separately allocated fp32 arrays of `count` elements each are
  * updated in place, x += 1, by a workgroup per 4096 elements that takes that stretch of every array, 16 bytes
  * per lane and access - the access pattern of those lines without their arithmetic and without the look-ups
  * that precede them.  What the box gives this pattern bounds the kernels that apply those lines.
  *   arrays: HOST array of n_arrays DEVICE pointers (16-byte aligned, distinct, count elements each, modified).
- *   count: multiple of 4.  streaming: non-zero = non-temporal accesses, zero = ordinary ones (the library's
- *   own kernels use the latter while the four arrays fit the memory-side cache).
+ *   count: multiple of 4.  cached_arrays (0..4): the first that many arrays are accessed with ordinary loads
+ *   and stores, the others with non-temporal ones (see compams_cached_state_arrays).
  * Only enqueues on hip_stream.  COMPAMS_INVALID_ARG / COMPAMS_BAD_ALIGNMENT as for compams_copy. */
-int compams_inplace_probe(float* const* arrays, int n_arrays, size_t count, int streaming, void* hip_stream);
+int compams_inplace_probe(float* const* arrays, int n_arrays, size_t count, int cached_arrays, void* hip_stream);
 
 /* ---- One whole step for callers that cannot allocate ------------------------------------------------------
  * For code that runs where no device memory can be allocated or handed over as a workspace (under HIP graph

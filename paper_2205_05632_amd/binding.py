@@ -26,7 +26,7 @@ _STATE_DTYPE = {"last_idx": torch.int32, "last_signbits": torch.int32, "last_thr
                 "counters": torch.int32, "last_count_gt": torch.int32}
 
 EXPORTS = ["compams_workspace_size", "compams_init", "compams_step", "compams_state", "compams_set_option",
-           "compams_profile_enable", "compams_profile_read", "compams_destroy", "compams_strerror", "compams_copy", "compams_inplace_probe",
+           "compams_profile_enable", "compams_profile_read", "compams_destroy", "compams_strerror", "compams_copy", "compams_inplace_probe", "compams_cached_state_arrays",
            "compams_wire_capacity", "compams_encode", "compams_decode", "compams_worker_step", "compams_server_step",
            "compams_step_static"]
 STATIC_SCRATCH_BYTES = 32 << 20
@@ -74,6 +74,7 @@ def lib():
         L.compams_strerror.restype = ctypes.c_char_p
         L.compams_strerror.argtypes = [ctypes.c_int]
         L.compams_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.compams_cached_state_arrays.argtypes = [ctypes.c_int64]
         L.compams_inplace_probe.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_size_t,
                                             ctypes.c_int, ctypes.c_void_p]
         L.compams_wire_capacity.restype = ctypes.c_size_t
@@ -333,13 +334,22 @@ def compams_step_static(n: int, d: int, k: int, theta, m, v, vhat, e, g, lr: flo
                                          None if val_out is None else val_out.data_ptr(), _current_stream_handle())
 
 
-def compams_inplace_probe(arrays, streaming: bool):
+def compams_cached_state_arrays(d: int) -> int:
+    """How many of theta, m, v, vhat the server kernels keep in the memory-side cache for a problem of d coordinates."""
+    count = lib().compams_cached_state_arrays(d)
+    if count < 0:
+        _check(count, "compams_cached_state_arrays")
+    return count
+
+
+def compams_inplace_probe(arrays, cached_arrays: int):
     """x += 1 on up to four separately allocated fp32 arrays of one size, in the access pattern of the server's
-    lines of Algorithm 2 (the measured ceiling for the kernels that apply them)."""
+    lines of Algorithm 2 (the measured ceiling for the kernels that apply them); the first cached_arrays of them
+    with ordinary accesses, the others with streaming ones."""
     count = arrays[0].numel()
     assert all(a.numel() == count and a.dtype == torch.float32 and a.is_cuda and a.is_contiguous() for a in arrays)
     ptrs = (ctypes.c_void_p * len(arrays))(*[a.data_ptr() for a in arrays])
-    _check(lib().compams_inplace_probe(ptrs, len(arrays), count, 1 if streaming else 0, _current_stream_handle()),
+    _check(lib().compams_inplace_probe(ptrs, len(arrays), count, int(cached_arrays), _current_stream_handle()),
            "compams_inplace_probe")
 
 

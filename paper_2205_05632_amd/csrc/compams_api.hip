@@ -600,7 +600,7 @@ static AmsParams ams_params(const compams_config& c, float lr) {
   ap.lr = lr;
   ap.nf = static_cast<float>(c.n);
   ap.eps_out = c.eps_mode == COMPAMS_EPS_OUT_SQRT;
-  ap.stream_state = static_cast<int64_t>(c.d) * 16 > (int64_t(192) << 20);  // against 256 MB of memory-side cache
+  ap.cached_arrays = cached_state_arrays(c.d);
   return ap;
 }
 
@@ -895,14 +895,18 @@ int compams_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
                                                                                             : COMPAMS_HIP_ERROR;
 }
 
-int compams_inplace_probe(float* const* arrays, int n_arrays, size_t count, int streaming, void* hip_stream) {
-  if (!arrays || n_arrays < 1 || n_arrays > 4 || count > (static_cast<size_t>(1) << 40)) return COMPAMS_INVALID_ARG;
+int compams_cached_state_arrays(int64_t d) { return d < 1 ? COMPAMS_INVALID_ARG : cached_state_arrays(d); }
+
+int compams_inplace_probe(float* const* arrays, int n_arrays, size_t count, int cached_arrays, void* hip_stream) {
+  if (!arrays || n_arrays < 1 || n_arrays > 4 || count > (static_cast<size_t>(1) << 40) || cached_arrays < 0 ||
+      cached_arrays > 4)
+    return COMPAMS_INVALID_ARG;
   for (int a = 0; a < n_arrays; ++a)
     if (!arrays[a]) return COMPAMS_INVALID_ARG;
   if (count % 4 != 0) return COMPAMS_BAD_ALIGNMENT;
   for (int a = 0; a < n_arrays; ++a)
     if (reinterpret_cast<uintptr_t>(arrays[a]) % 16 != 0) return COMPAMS_BAD_ALIGNMENT;
-  return inplace_probe(arrays, n_arrays, count, streaming != 0, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+  return inplace_probe(arrays, n_arrays, count, cached_arrays, static_cast<hipStream_t>(hip_stream)) == hipSuccess
              ? COMPAMS_OK
              : COMPAMS_HIP_ERROR;
 }

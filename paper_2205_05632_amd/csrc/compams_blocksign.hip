@@ -521,7 +521,7 @@ __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometr
 constexpr int kBsWorkers = 8;  // workers whose sign words and scales are requested together
 constexpr int kBsSplit = 4;    // wavefronts per chunk in the server kernel
 
-template <bool STREAM>  // streaming accesses for theta, m, v, vhat (see the top-k final kernel)
+template <int NC>  // how many of theta, m, v, vhat are cached, the others streamed (see the top-k final kernel)
 __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, float* __restrict__ m,
                                                      float* __restrict__ v, float* __restrict__ vhat, Geometry geo,
                                                      BlocksignWorkspace ws, AmsParams p) {
@@ -544,14 +544,8 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
     // the optimizer state of this round is requested first; the sign/scale loop runs while it travels
     float4 th = make_float4(0.f, 0.f, 0.f, 0.f), mm = th, vv = th, vh = th;
     if (ok[3]) {
-      if (STREAM) {
-        th = load_stream4(theta + j); mm = load_stream4(m + j); vv = load_stream4(v + j); vh = load_stream4(vhat + j);
-      } else {
-        th = *reinterpret_cast<const float4*>(theta + j);
-        mm = *reinterpret_cast<const float4*>(m + j);
-        vv = *reinterpret_cast<const float4*>(v + j);
-        vh = *reinterpret_cast<const float4*>(vhat + j);
-      }
+      th = load_state4<(NC > 0)>(theta + j); mm = load_state4<(NC > 1)>(m + j);
+      vv = load_state4<(NC > 2)>(v + j); vh = load_state4<(NC > 3)>(vhat + j);
     }
     while (table_u32(off, b + 1) <= j0) ++b;
     const uint32_t j_end = (j0 + 256 < d) ? j0 + 256 : d;
@@ -603,14 +597,10 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
       ams_update(sum[1] / p.nf, th.y, mm.y, vv.y, vh.y, p);
       ams_update(sum[2] / p.nf, th.z, mm.z, vv.z, vh.z, p);
       ams_update(sum[3] / p.nf, th.w, mm.w, vv.w, vh.w, p);
-      if (STREAM) {
-        store_stream4(theta + j, th); store_stream4(m + j, mm); store_stream4(v + j, vv); store_stream4(vhat + j, vh);
-      } else {
-        *reinterpret_cast<float4*>(theta + j) = th;
-        *reinterpret_cast<float4*>(m + j) = mm;
-        *reinterpret_cast<float4*>(v + j) = vv;
-        *reinterpret_cast<float4*>(vhat + j) = vh;
-      }
+      store_state4<(NC > 0)>(theta + j, th);
+      store_state4<(NC > 1)>(m + j, mm);
+      store_state4<(NC > 2)>(v + j, vv);
+      store_state4<(NC > 3)>(vhat + j, vh);
     } else {
       for (int s = 0; s < 4; ++s)
         if (ok[s]) {
@@ -625,7 +615,7 @@ __global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, f
 // ---------------------------------------------------------------------------------------------
 // C = identity (full-precision distributed AMSGrad): gbar = mean of the n gradients in worker order.
 // ---------------------------------------------------------------------------------------------
-template <bool STREAM>
+template <int NC>  // how many of theta, m, v, vhat are cached (the others are streamed)
 __global__ __launch_bounds__(kWG) void k_none_amsgrad(const float* __restrict__ g, float* __restrict__ theta,
                                                        float* __restrict__ m, float* __restrict__ v,
                                                        float* __restrict__ vhat, Geometry geo, AmsParams p) {
@@ -635,12 +625,8 @@ __global__ __launch_bounds__(kWG) void k_none_amsgrad(const float* __restrict__ 
   // the optimizer state is requested first; the workers' gradients follow eight rows at a time, loads together
   float4 th = make_float4(0.f, 0.f, 0.f, 0.f), mm = th, vv = th, vh = th;
   if (whole) {
-    if (STREAM) {
-      th = load_stream4(theta + j); mm = load_stream4(m + j); vv = load_stream4(v + j); vh = load_stream4(vhat + j);
-    } else {
-      th = *reinterpret_cast<float4*>(theta + j); mm = *reinterpret_cast<float4*>(m + j);
-      vv = *reinterpret_cast<float4*>(v + j); vh = *reinterpret_cast<float4*>(vhat + j);
-    }
+    th = load_state4<(NC > 0)>(theta + j); mm = load_state4<(NC > 1)>(m + j);
+    vv = load_state4<(NC > 2)>(v + j); vh = load_state4<(NC > 3)>(vhat + j);
   }
   float sum[4] = {0.f, 0.f, 0.f, 0.f};
   constexpr int kRows = 8;
@@ -664,14 +650,10 @@ __global__ __launch_bounds__(kWG) void k_none_amsgrad(const float* __restrict__ 
     ams_update(sum[1] / p.nf, th.y, mm.y, vv.y, vh.y, p);
     ams_update(sum[2] / p.nf, th.z, mm.z, vv.z, vh.z, p);
     ams_update(sum[3] / p.nf, th.w, mm.w, vv.w, vh.w, p);
-    if (STREAM) {
-      store_stream4(theta + j, th); store_stream4(m + j, mm); store_stream4(v + j, vv); store_stream4(vhat + j, vh);
-    } else {
-      *reinterpret_cast<float4*>(theta + j) = th;
-      *reinterpret_cast<float4*>(m + j) = mm;
-      *reinterpret_cast<float4*>(v + j) = vv;
-      *reinterpret_cast<float4*>(vhat + j) = vh;
-    }
+    store_state4<(NC > 0)>(theta + j, th);
+    store_state4<(NC > 1)>(m + j, mm);
+    store_state4<(NC > 2)>(v + j, vv);
+    store_state4<(NC > 3)>(vhat + j, vh);
   } else {
     for (uint32_t s = 0; s < 4 && j + s < geo.d; ++s) {
       float th = theta[j + s], mm = m[j + s], vv = v[j + s], vh = vhat[j + s];
@@ -709,27 +691,28 @@ __global__ __launch_bounds__(kWG) void k_copy16(float* __restrict__ dst, const f
 }
 
 // The access pattern of the server's lines of Algorithm 2 with nothing else around it: A separately allocated
-// arrays, a workgroup per 4096 elements that takes that stretch of every array, 16 bytes per lane and access, all
-// loads of a round requested before the first is used, every element read, increased by one and written back.
-template <int A, bool STREAM>
+// arrays (the pointers beyond the A-th are not looked at), a workgroup per 4096 elements that
+// takes that stretch of every array, 16 bytes per lane and access, all loads of a round requested before the first is
+// used, every element read, increased by one and written back.  NC as in the kernels that apply those lines.
+template <int A, int NC>
 __global__ __launch_bounds__(kWG) void k_inplace_probe(float* a0, float* a1, float* a2, float* a3, size_t count) {
-  float* const arr[4] = {a0, a1, a2, a3};
 #pragma unroll
   for (int r = 0; r < kChunk / (kWG * 4); ++r) {
     const size_t j = static_cast<size_t>(blockIdx.x) * kChunk + r * kWG * 4 + threadIdx.x * 4;
     if (j + 3 < count) {
-      float4 x[A];
-#pragma unroll
-      for (int a = 0; a < A; ++a) x[a] = STREAM ? load_stream4(arr[a] + j) : *reinterpret_cast<const float4*>(arr[a] + j);
+      float4 x[4];
+      x[0] = load_state4<(NC > 0)>(a0 + j);
+      if (A > 1) x[1] = load_state4<(NC > 1)>(a1 + j);
+      if (A > 2) x[2] = load_state4<(NC > 2)>(a2 + j);
+      if (A > 3) x[3] = load_state4<(NC > 3)>(a3 + j);
 #pragma unroll
       for (int a = 0; a < A; ++a) {
         x[a].x += 1.0f; x[a].y += 1.0f; x[a].z += 1.0f; x[a].w += 1.0f;
       }
-#pragma unroll
-      for (int a = 0; a < A; ++a) {
-        if (STREAM) store_stream4(arr[a] + j, x[a]);
-        else *reinterpret_cast<float4*>(arr[a] + j) = x[a];
-      }
+      store_state4<(NC > 0)>(a0 + j, x[0]);
+      if (A > 1) store_state4<(NC > 1)>(a1 + j, x[1]);
+      if (A > 2) store_state4<(NC > 2)>(a2 + j, x[2]);
+      if (A > 3) store_state4<(NC > 3)>(a3 + j, x[3]);
     }
   }
 }
@@ -764,8 +747,10 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
 hipError_t blocksign_server_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, float* theta,
                                  float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
   const dim3 grid((geo.num_chunks * kBsSplit + kWaves - 1) / kWaves), wg(kWG);
-  if (ap.stream_state) launch(L, kSlotBsAms, k_bs_amsgrad<true>, grid, wg, stream, theta, m, v, vhat, geo, ws, ap);
-  else launch(L, kSlotBsAms, k_bs_amsgrad<false>, grid, wg, stream, theta, m, v, vhat, geo, ws, ap);
+#define COMPAMS_BS_AMSGRAD(NC) k_bs_amsgrad<NC>
+  COMPAMS_LAUNCH_BY_CACHED(ap.cached_arrays, L, kSlotBsAms, COMPAMS_BS_AMSGRAD, grid, wg, stream, theta, m, v, vhat, geo, ws,
+                           ap);
+#undef COMPAMS_BS_AMSGRAD
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -780,8 +765,10 @@ hipError_t none_step(const Geometry& geo, const AmsParams& ap, const float* g, f
                      float* vhat, hipStream_t stream, Launcher* L) {
   const uint32_t quads = (geo.d + 3) / 4;
   const dim3 grid((quads + kWG - 1) / kWG), wg(kWG);
-  if (ap.stream_state) launch(L, kSlotNoneAms, k_none_amsgrad<true>, grid, wg, stream, g, theta, m, v, vhat, geo, ap);
-  else launch(L, kSlotNoneAms, k_none_amsgrad<false>, grid, wg, stream, g, theta, m, v, vhat, geo, ap);
+#define COMPAMS_NONE_AMSGRAD(NC) k_none_amsgrad<NC>
+  COMPAMS_LAUNCH_BY_CACHED(ap.cached_arrays, L, kSlotNoneAms, COMPAMS_NONE_AMSGRAD, grid, wg, stream, g, theta, m, v, vhat,
+                           geo, ap);
+#undef COMPAMS_NONE_AMSGRAD
   return hipGetLastError();
 }
 
@@ -818,21 +805,30 @@ hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t str
   return hipGetLastError();
 }
 
-template <bool STREAM>
-static void launch_inplace_probe(int arrays, dim3 grid, hipStream_t stream, float* const* a, size_t count) {
-  switch (arrays) {
-    case 1: hipLaunchKernelGGL((k_inplace_probe<1, STREAM>), grid, dim3(kWG), 0, stream, a[0], a[0], a[0], a[0], count); break;
-    case 2: hipLaunchKernelGGL((k_inplace_probe<2, STREAM>), grid, dim3(kWG), 0, stream, a[0], a[1], a[1], a[1], count); break;
-    case 3: hipLaunchKernelGGL((k_inplace_probe<3, STREAM>), grid, dim3(kWG), 0, stream, a[0], a[1], a[2], a[2], count); break;
-    default: hipLaunchKernelGGL((k_inplace_probe<4, STREAM>), grid, dim3(kWG), 0, stream, a[0], a[1], a[2], a[3], count); break;
+template <int A>
+static void launch_inplace_probe(int cached, dim3 grid, hipStream_t stream, float* const* a, size_t count) {
+  float* const last = a[A - 1];
+  float* const a1 = A > 1 ? a[1] : last;
+  float* const a2 = A > 2 ? a[2] : last;
+  float* const a3 = A > 3 ? a[3] : last;
+  switch (cached) {
+    case 0: hipLaunchKernelGGL((k_inplace_probe<A, 0>), grid, dim3(kWG), 0, stream, a[0], a1, a2, a3, count); break;
+    case 1: hipLaunchKernelGGL((k_inplace_probe<A, 1>), grid, dim3(kWG), 0, stream, a[0], a1, a2, a3, count); break;
+    case 2: hipLaunchKernelGGL((k_inplace_probe<A, 2>), grid, dim3(kWG), 0, stream, a[0], a1, a2, a3, count); break;
+    case 3: hipLaunchKernelGGL((k_inplace_probe<A, 3>), grid, dim3(kWG), 0, stream, a[0], a1, a2, a3, count); break;
+    default: hipLaunchKernelGGL((k_inplace_probe<A, 4>), grid, dim3(kWG), 0, stream, a[0], a1, a2, a3, count); break;
   }
 }
 
-hipError_t inplace_probe(float* const* arrays, int n_arrays, size_t count, bool streaming, hipStream_t stream) {
+hipError_t inplace_probe(float* const* arrays, int n_arrays, size_t count, int cached_arrays, hipStream_t stream) {
   if (!count) return hipSuccess;
   const dim3 grid(static_cast<uint32_t>((count + kChunk - 1) / kChunk));
-  if (streaming) launch_inplace_probe<true>(n_arrays, grid, stream, arrays, count);
-  else launch_inplace_probe<false>(n_arrays, grid, stream, arrays, count);
+  switch (n_arrays) {
+    case 1: launch_inplace_probe<1>(cached_arrays, grid, stream, arrays, count); break;
+    case 2: launch_inplace_probe<2>(cached_arrays, grid, stream, arrays, count); break;
+    case 3: launch_inplace_probe<3>(cached_arrays, grid, stream, arrays, count); break;
+    default: launch_inplace_probe<4>(cached_arrays, grid, stream, arrays, count); break;
+  }
   return hipGetLastError();
 }
 

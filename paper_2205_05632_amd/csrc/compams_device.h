@@ -78,6 +78,19 @@ __device__ __forceinline__ void store_stream4(float* p, const float4& x) {
   __builtin_nontemporal_store(v, reinterpret_cast<f4v*>(p));
 }
 
+// theta, m, v, vhat are touched once per step.  CACHED: an ordinary access, which leaves the line in the memory-side
+// cache for the next step; else a streaming one.
+template <bool CACHED>
+__device__ __forceinline__ float4 load_state4(const float* p) {
+  if constexpr (CACHED) return *reinterpret_cast<const float4*>(p);
+  else return load_stream4(p);
+}
+template <bool CACHED>
+__device__ __forceinline__ void store_state4(float* p, const float4& x) {
+  if constexpr (CACHED) *reinterpret_cast<float4*>(p) = x;
+  else store_stream4(p, x);
+}
+
 // A value that is the same in every lane, moved to a scalar register: conditions on it become scalar branches
 // and it can be an operand of every lane's arithmetic without a register per lane.
 __device__ __forceinline__ uint32_t uniform_u32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }

@@ -216,9 +216,19 @@ constexpr int kLimbs = 10;  // 10 digits of 32 bits cover 2^-149 .. 2^171
 struct AmsParams {
   float beta1, beta2, one_minus_beta1, one_minus_beta2, eps, lr, nf;
   int eps_out;  // 1: epsilon outside the square root
-  int stream_state;  // 1: theta, m, v, vhat do not fit the memory-side cache from one step to the next: streaming
-                     // accesses for them (measured: 4-5 % faster then; 25 % slower when they do fit)
+  int cached_arrays;  // how many of theta, m, v, vhat (in that order) fit the memory-side cache together from one
+                      // step to the next: those are read and written with ordinary accesses, the others with
+                      // streaming ones (measured, final kernel of the top-k step: ResNet-18, 4 x 45 MB, all four
+                      // cached 70 against 87 us; ResNet-50, 4 x 102 MB, none 174, one 147, two 144, three 175 us;
+                      // GPT-2, 4 x 498 MB, none is best)
 };
+
+// The memory-side cache holds 256 MB; what the first pass streams through in between costs some of it.
+inline int cached_state_arrays(int64_t d) {
+  const int64_t budget = int64_t(212) << 20, each = d * 4;
+  const int64_t fit = budget / each;
+  return fit > 4 ? 4 : static_cast<int>(fit);
+}
 
 // Moment and parameter lines of Algorithm 2 for one coordinate: every product, sum, square root and
 // quotient is a separately rounded fp32 operation (the library is built without contraction).
@@ -294,7 +304,7 @@ hipError_t fill_u32(uint32_t* p, size_t count, uint32_t value, hipStream_t strea
 hipError_t fill_rows_f32(float* p, uint32_t n, int64_t ld, uint32_t d, float value, hipStream_t stream);
 hipError_t copy_u32(uint32_t* dst, const uint32_t* src, size_t count, hipStream_t stream);
 hipError_t stream_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
-hipError_t inplace_probe(float* const* arrays, int n_arrays, size_t count, bool streaming, hipStream_t stream);
+hipError_t inplace_probe(float* const* arrays, int n_arrays, size_t count, int cached_arrays, hipStream_t stream);
 
 // Launch with optional timing: when the slot is being timed, the launch is bracketed by a pair of events on
 // the same stream.  (Events attached to the dispatch itself give the same durations but slow the step down
@@ -309,6 +319,18 @@ inline void launch(Launcher* L, int slot, void (*kernel)(KArgs...), const dim3& 
   hipLaunchKernelGGL(kernel, grid, block, 0, stream, static_cast<KArgs>(args)...);
   if (L) launcher_end(L, slot, stream);
 }
+
+// A kernel template over the number of cached state arrays (0..4), picked at run time.
+#define COMPAMS_LAUNCH_BY_CACHED(nc, L, slot, KERNEL, ...)                      \
+  do {                                                                          \
+    switch (nc) {                                                               \
+      case 0: launch(L, slot, KERNEL(0), __VA_ARGS__); break;                   \
+      case 1: launch(L, slot, KERNEL(1), __VA_ARGS__); break;                   \
+      case 2: launch(L, slot, KERNEL(2), __VA_ARGS__); break;                   \
+      case 3: launch(L, slot, KERNEL(3), __VA_ARGS__); break;                   \
+      default: launch(L, slot, KERNEL(4), __VA_ARGS__); break;                  \
+    }                                                                           \
+  } while (0)
 
 // How many workgroups per row the streaming kernels use: enough to keep 256 compute units busy
 // with several workgroups each, whatever n is.

@@ -1764,9 +1764,10 @@ __device__ __forceinline__ FinalCtx final_ctx(const Geometry& geo, const TopkWor
   return f;
 }
 
-// STREAM: streaming accesses for theta, m, v, vhat (a template parameter: as a run-time choice between two
-// otherwise identical branches the compiler merges them and drops the hint).
-template <int ROLE, bool UNI, bool STREAM>
+// NC: how many of theta, m, v, vhat (in that order) are read and written with ordinary accesses, the others with
+// streaming ones (a template parameter: as a run-time choice between otherwise identical branches the compiler
+// merges them and drops the hint).
+template <int ROLE, bool UNI, int NC>
 __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7, 8))) void k_topk_final(
     float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v, float* __restrict__ vhat,
     const float* __restrict__ e, Geometry geo, TopkWorkspace ws, TopkOptions opt, AmsParams p, TopkFlat flat) {
@@ -2008,26 +2009,17 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7
     const uint32_t t = r * kWG * 4 + threadIdx.x * 4;
     const uint32_t j = base + t;
     if (j + 3 < d_end) {
-      float4 th, mm, vv, vh;
-      if (STREAM) {
-        th = load_stream4(theta + j); mm = load_stream4(m + j); vv = load_stream4(v + j); vh = load_stream4(vhat + j);
-      } else {
-        th = *reinterpret_cast<float4*>(theta + j); mm = *reinterpret_cast<float4*>(m + j);
-        vv = *reinterpret_cast<float4*>(v + j); vh = *reinterpret_cast<float4*>(vhat + j);
-      }
+      float4 th = load_state4<(NC > 0)>(theta + j), mm = load_state4<(NC > 1)>(m + j);
+      float4 vv = load_state4<(NC > 2)>(v + j), vh = load_state4<(NC > 3)>(vhat + j);
       const float4 s = *reinterpret_cast<const float4*>(gs + t);
       ams_update(s.x / p.nf, th.x, mm.x, vv.x, vh.x, p);
       ams_update(s.y / p.nf, th.y, mm.y, vv.y, vh.y, p);
       ams_update(s.z / p.nf, th.z, mm.z, vv.z, vh.z, p);
       ams_update(s.w / p.nf, th.w, mm.w, vv.w, vh.w, p);
-      if (STREAM) {
-        store_stream4(theta + j, th); store_stream4(m + j, mm); store_stream4(v + j, vv); store_stream4(vhat + j, vh);
-      } else {
-        *reinterpret_cast<float4*>(theta + j) = th;
-        *reinterpret_cast<float4*>(m + j) = mm;
-        *reinterpret_cast<float4*>(v + j) = vv;
-        *reinterpret_cast<float4*>(vhat + j) = vh;
-      }
+      store_state4<(NC > 0)>(theta + j, th);
+      store_state4<(NC > 1)>(m + j, mm);
+      store_state4<(NC > 2)>(v + j, vv);
+      store_state4<(NC > 3)>(vhat + j, vh);
     } else {
       for (uint32_t s = 0; s < 4 && j + s < d_end; ++s) {
         float th = theta[j + s], mm = m[j + s], vv = v[j + s], vh = vhat[j + s];
@@ -2173,15 +2165,14 @@ hipError_t topk_step(const Geometry& geo, const TopkWorkspace& ws, const TopkOpt
   COMPAMS_CHECK_LAUNCH();
   const dim3 grid_f(geo.num_chunks);
   const TopkFlat none{};
+#define COMPAMS_FINAL_WHOLE_ROW(NC) k_topk_final<kWholeStep, true, NC>
   if (role == kWorkerHalf)
-    launch(L, kSlotTopkFinal, k_topk_final<kWorkerHalf, true, false>, grid_f, wg, stream, theta, m, v, vhat, e, geo, ws, opt,
-           ap, none);
-  else if (ap.stream_state)
-    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, true, true>, grid_f, wg, stream, theta, m, v, vhat, e, geo, ws, opt,
+    launch(L, kSlotTopkFinal, k_topk_final<kWorkerHalf, true, 0>, grid_f, wg, stream, theta, m, v, vhat, e, geo, ws, opt,
            ap, none);
   else
-    launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, true, false>, grid_f, wg, stream, theta, m, v, vhat, e, geo, ws, opt,
-           ap, none);
+    COMPAMS_LAUNCH_BY_CACHED(ap.cached_arrays, L, kSlotTopkFinal, COMPAMS_FINAL_WHOLE_ROW, grid_f, wg, stream, theta, m, v,
+                             vhat, e, geo, ws, opt, ap, none);
+#undef COMPAMS_FINAL_WHOLE_ROW
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -2220,12 +2211,10 @@ hipError_t topk_blocks_step(const Geometry& geo, const TopkWorkspace& ws, const 
   } else {
     const float* residuals = e;
     const dim3 grid_f(flat.wg_final);
-    if (ap.stream_state)
-      launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, false, true>, grid_f, wg, stream, theta, m, v, vhat, residuals, geo,
-             ws, opt, ap, flat);
-    else
-      launch(L, kSlotTopkFinal, k_topk_final<kWholeStep, false, false>, grid_f, wg, stream, theta, m, v, vhat, residuals, geo,
-             ws, opt, ap, flat);
+#define COMPAMS_FINAL_BLOCKS(NC) k_topk_final<kWholeStep, false, NC>
+    COMPAMS_LAUNCH_BY_CACHED(ap.cached_arrays, L, kSlotTopkFinal, COMPAMS_FINAL_BLOCKS, grid_f, wg, stream, theta, m, v, vhat,
+                             residuals, geo, ws, opt, ap, flat);
+#undef COMPAMS_FINAL_BLOCKS
   }
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
@@ -2241,12 +2230,10 @@ hipError_t topk_server_step(const Geometry& geo, const TopkWorkspace& ws, const 
   const float* no_e = nullptr;
   const dim3 grid_f(geo.num_chunks), wg(kWG);
   const TopkFlat none{};
-  if (ap.stream_state)
-    launch(L, kSlotTopkFinal, k_topk_final<kServerHalf, true, true>, grid_f, wg, stream, theta, m, v, vhat, no_e, geo, ws, opt,
-           ap, none);
-  else
-    launch(L, kSlotTopkFinal, k_topk_final<kServerHalf, true, false>, grid_f, wg, stream, theta, m, v, vhat, no_e, geo, ws,
-           opt, ap, none);
+#define COMPAMS_FINAL_SERVER(NC) k_topk_final<kServerHalf, true, NC>
+  COMPAMS_LAUNCH_BY_CACHED(ap.cached_arrays, L, kSlotTopkFinal, COMPAMS_FINAL_SERVER, grid_f, wg, stream, theta, m, v, vhat,
+                           no_e, geo, ws, opt, ap, none);
+#undef COMPAMS_FINAL_SERVER
   COMPAMS_CHECK_LAUNCH();
   return hipSuccess;
 }

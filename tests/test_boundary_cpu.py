@@ -153,6 +153,10 @@ def test_null_context_is_rejected_everywhere():
     assert L.compams_state(None, 0, ctypes.byref(p), ctypes.byref(c)) == -1
     assert L.compams_copy(None, None, 16, None) == -1
     assert L.compams_copy(0x1000, 0x2000, 8, None) == -2
+    assert L.compams_inplace_probe((ctypes.c_void_p * 2)(0x1000, 0x2000), 2, 16, 5, None) == -1
+    assert L.compams_cached_state_arrays(0) == -1
+    # the workloads' sizes: four arrays of 45 MB all fit, of 102 MB two, of 498 MB none
+    assert [B.compams_cached_state_arrays(d) for d in (1, 11181642, 25557032, 124439808)] == [4, 4, 2, 0]
     two = (ctypes.c_void_p * 2)(0x1000, 0x2000)
     assert L.compams_inplace_probe(None, 1, 16, 0, None) == -1
     assert L.compams_inplace_probe(two, 5, 16, 0, None) == -1

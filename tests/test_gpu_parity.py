@@ -564,11 +564,11 @@ def test_hundred_steps_with_a_drifting_gradient_scale(compressor):
 def test_inplace_probe_adds_one_to_every_element_and_nothing_else():
     """The measurement aid for the server's lines: values are exact, the ragged last workgroup stops at count."""
     for count, arrays in ((4096 * 3 + 20, 4), (8, 1), (4096, 3), (70000, 2)):
-        for streaming in (False, True):
+        for cached in range(5):
             bufs = [torch.arange(count + 8, dtype=torch.float32, device="cuda") * (a + 1) for a in range(arrays)]
-            B.compams_inplace_probe([b[:count] for b in bufs], streaming)
+            B.compams_inplace_probe([b[:count] for b in bufs], cached)
             torch.cuda.synchronize()
             for a, b in enumerate(bufs):
                 want = torch.arange(count + 8, dtype=torch.float32) * (a + 1)
                 want[:count] += 1.0
-                assert torch.equal(b.cpu(), want), (count, arrays, streaming, a)
+                assert torch.equal(b.cpu(), want), (count, arrays, cached, a)
