@@ -654,6 +654,11 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
   const uint32_t blo = banded ? rw[5] : 0xffffffffu;
   const uint32_t bhi = banded ? rw[6] : 0xffffffffu;
   const uint32_t bmul = banded ? rw[7] : 0u;
+  // Candidates: every key at or above cand_lo - the guessed bucket's first key, or, with a band (which starts at or
+  // above that), the band's first key: the threshold is expected inside the band, so that nothing below it is needed
+  // (a list of at least k entries that holds every key from some key upwards holds the k largest, wherever that
+  // key lies inside a bucket; a shorter one sends the row to the kernels that read it again).
+  const uint32_t cand_lo = banded ? blo : bg << kL0Shift;
   uint32_t* bh = ws.bhist + static_cast<size_t>(row) * kBandBuckets;
   uint32_t* bm = bm_all + (PEND ? wave * 32 : 0);
   if constexpr (PEND) {
@@ -703,7 +708,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         const uint32_t key = key_of_bits(bits[s]);
-        flag[s] = ok[s] && (key >> kL0Shift) >= bg;
+        flag[s] = ok[s] && key >= cand_lo;
         n_above += (ok[s] && key >= bhi) ? 1u : 0u;
         n_from += (ok[s] && key >= blo) ? 1u : 0u;
       }
@@ -794,7 +799,7 @@ __global__ __launch_bounds__(kWG) void k_topk_lean(const float* __restrict__ g, 
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         const uint32_t key = key_of_bits(bits[s]);
-        flag[s] = j + s < d && (key >> kL0Shift) >= bg;
+        flag[s] = j + s < d && key >= cand_lo;
         inb[s] = j + s < d && key >= blo && key < bhi;
       }
       const RoundRank rr = rank_round(flag);
