@@ -10,9 +10,10 @@
 //   first pass     x = e + g -> e as a grid of short workgroups, one chunk each.  When the previous step's
 //                  threshold bucket is carried over as a guess, the same pass writes the candidate list: the
 //                  entries at or above the guessed bucket, a segment per chunk.  When the last two thresholds
-//                  also give a band of keys in which this step's threshold is expected, it counts per chunk the
-//                  entries above the band, lists the entries inside it (a segment per chunk again) and adds
-//                  them to the row's histogram of 2048 buckets across the band.
+//                  also give a band of keys in which this step's threshold is expected, the candidates are the
+//                  entries from the band's first key upwards (it lies at or above the guessed bucket), and the
+//                  pass counts per chunk the entries above the band, lists the entries inside it (a segment per
+//                  chunk again) and adds them to the row's histogram of 2048 buckets across the band.
 //   band           if the threshold key does lie in the band (decided exactly from the counts): per chunk the
 //                  entries kept for certain, their prefixes inside blocks of chunks and the block totals; the
 //                  few entries of the threshold's bucket are ranked by the last workgroup of the row, which
