@@ -1774,7 +1774,7 @@ __device__ __forceinline__ FinalCtx final_ctx(const Geometry& geo, const TopkWor
 // streaming ones (a template parameter: as a run-time choice between otherwise identical branches the compiler
 // merges them and drops the hint).
 template <int ROLE, bool UNI, int NC>
-__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7, 8))) void k_topk_final(
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu((UNI && NC == 4) ? 8 : 7, 8))) void k_topk_final(
     float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v, float* __restrict__ vhat,
     const float* __restrict__ e, Geometry geo, TopkWorkspace ws, TopkOptions opt, AmsParams p, TopkFlat flat) {
   static_assert(UNI || ROLE == kWholeStep, "the halves of a step work on whole rows");
@@ -1793,6 +1793,23 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7
       ws.rows[f.row0 + i * f.row_stride].cursor_band = 0;
     }
   const uint32_t my_block = c / f.count_cpw;  // count blocks before this chunk's
+  // State that comes from HBM (not all of it kept in the memory-side cache): the first quarter of the chunk's is
+  // requested here, before the look-ups of phases 1 and 2, and travels while they run (16 more registers: seven
+  // wavefronts per SIMD; measured on the final kernel: GPT-2, nothing cached, 727 -> 650-710 us; ResNet-50, two
+  // arrays cached, 139 -> 137; two quarters, at five wavefronts, are slower again; with all four arrays cached the
+  // request gains nothing and the kernel keeps its eight wavefronts).
+  constexpr int kEarly = (ROLE != kWorkerHalf && UNI && NC < 4) ? 1 : 0;  // (the per-block form has no registers to spare)
+  const uint32_t d_end = f.coord_base + f.d_loc;  // the chunk's coordinates end here at the latest
+  float4 th0[kEarly > 0 ? kEarly : 1], mm0[kEarly > 0 ? kEarly : 1], vv0[kEarly > 0 ? kEarly : 1], vh0[kEarly > 0 ? kEarly : 1];
+#pragma unroll
+  for (int r = 0; r < kEarly; ++r) {
+    const uint32_t j = base + r * kWG * 4 + threadIdx.x * 4;
+    th0[r] = mm0[r] = vv0[r] = vh0[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j + 3 < d_end) {
+      th0[r] = load_state4<(NC > 0)>(theta + j); mm0[r] = load_state4<(NC > 1)>(m + j);
+      vv0[r] = load_state4<(NC > 2)>(v + j); vh0[r] = load_state4<(NC > 3)>(vhat + j);
+    }
+  }
 
   for (uint32_t i0 = 0; i0 < geo.n; i0 += kTileWorkers) {
     if (ROLE == kServerHalf) {
@@ -2009,14 +2026,18 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(UNI ? 8 : 7
   }
 
   if (ROLE == kWorkerHalf) return;
-  const uint32_t d_end = f.coord_base + f.d_loc;  // the chunk's coordinates end here at the latest
 #pragma unroll
   for (int r = 0; r < kChunk / (kWG * 4); ++r) {
     const uint32_t t = r * kWG * 4 + threadIdx.x * 4;
     const uint32_t j = base + t;
     if (j + 3 < d_end) {
-      float4 th = load_state4<(NC > 0)>(theta + j), mm = load_state4<(NC > 1)>(m + j);
-      float4 vv = load_state4<(NC > 2)>(v + j), vh = load_state4<(NC > 3)>(vhat + j);
+      float4 th, mm, vv, vh;
+      if (r < kEarly) {
+        th = th0[r]; mm = mm0[r]; vv = vv0[r]; vh = vh0[r];
+      } else {
+        th = load_state4<(NC > 0)>(theta + j); mm = load_state4<(NC > 1)>(m + j);
+        vv = load_state4<(NC > 2)>(v + j); vh = load_state4<(NC > 3)>(vhat + j);
+      }
       const float4 s = *reinterpret_cast<const float4*>(gs + t);
       ams_update(s.x / p.nf, th.x, mm.x, vv.x, vh.x, p);
       ams_update(s.y / p.nf, th.y, mm.y, vv.y, vh.y, p);
