@@ -691,28 +691,37 @@ __global__ __launch_bounds__(kWG) void k_copy16(float* __restrict__ dst, const f
 }
 
 // The access pattern of the server's lines of Algorithm 2 with nothing else around it: A separately allocated
-// arrays (the pointers beyond the A-th are not looked at), a workgroup per 4096 elements that
-// takes that stretch of every array, 16 bytes per lane and access, all loads of a round requested before the first is
-// used, every element read, increased by one and written back.  NC as in the kernels that apply those lines.
+// arrays (the pointers beyond the A-th are not looked at), a workgroup per 4096 elements that takes that stretch of
+// every array, 16 bytes per lane and access, every element read, increased by one and written back.  All of a
+// lane's loads are requested before the first is used (nothing else needs the registers here: the most this
+// pattern can have in flight).  NC as in the kernels that apply those lines.
 template <int A, int NC>
 __global__ __launch_bounds__(kWG) void k_inplace_probe(float* a0, float* a1, float* a2, float* a3, size_t count) {
+  constexpr int kR = kChunk / (kWG * 4);
+  float4 x[kR][4];
+  const size_t j0 = static_cast<size_t>(blockIdx.x) * kChunk + threadIdx.x * 4;
 #pragma unroll
-  for (int r = 0; r < kChunk / (kWG * 4); ++r) {
-    const size_t j = static_cast<size_t>(blockIdx.x) * kChunk + r * kWG * 4 + threadIdx.x * 4;
+  for (int r = 0; r < kR; ++r) {
+    const size_t j = j0 + r * kWG * 4;
     if (j + 3 < count) {
-      float4 x[4];
-      x[0] = load_state4<(NC > 0)>(a0 + j);
-      if (A > 1) x[1] = load_state4<(NC > 1)>(a1 + j);
-      if (A > 2) x[2] = load_state4<(NC > 2)>(a2 + j);
-      if (A > 3) x[3] = load_state4<(NC > 3)>(a3 + j);
+      x[r][0] = load_state4<(NC > 0)>(a0 + j);
+      if (A > 1) x[r][1] = load_state4<(NC > 1)>(a1 + j);
+      if (A > 2) x[r][2] = load_state4<(NC > 2)>(a2 + j);
+      if (A > 3) x[r][3] = load_state4<(NC > 3)>(a3 + j);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < kR; ++r) {
+    const size_t j = j0 + r * kWG * 4;
+    if (j + 3 < count) {
 #pragma unroll
       for (int a = 0; a < A; ++a) {
-        x[a].x += 1.0f; x[a].y += 1.0f; x[a].z += 1.0f; x[a].w += 1.0f;
+        x[r][a].x += 1.0f; x[r][a].y += 1.0f; x[r][a].z += 1.0f; x[r][a].w += 1.0f;
       }
-      store_state4<(NC > 0)>(a0 + j, x[0]);
-      if (A > 1) store_state4<(NC > 1)>(a1 + j, x[1]);
-      if (A > 2) store_state4<(NC > 2)>(a2 + j, x[2]);
-      if (A > 3) store_state4<(NC > 3)>(a3 + j, x[3]);
+      store_state4<(NC > 0)>(a0 + j, x[r][0]);
+      if (A > 1) store_state4<(NC > 1)>(a1 + j, x[r][1]);
+      if (A > 2) store_state4<(NC > 2)>(a2 + j, x[r][2]);
+      if (A > 3) store_state4<(NC > 3)>(a3 + j, x[r][3]);
     }
   }
 }
