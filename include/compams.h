@@ -183,8 +183,9 @@ enum {
  * the step on the step's stream). */
 int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* count);
 
-/* Knobs of the top-k selection.  None of them changes any result; they decide which route the
- * selection takes and exist for tests of the rarely taken routes and for ablation measurements. */
+/* Knobs.  None of them changes any result; they decide which route the top-k selection takes, or how memory is
+ * accessed, and exist for tests of the rarely taken routes and for ablation measurements.  Options 0..3 are for the
+ * top-k compressors only (COMPAMS_BAD_STATE otherwise). */
 enum {
   COMPAMS_OPT_CANDIDATE_CAP = 0, /* candidate-list capacity per worker, 0 .. the capacity the workspace was sized
                                     for (min(d, 8k + 65536)); a list that would not fit is not built.  Rows of 64
@@ -194,10 +195,13 @@ enum {
   COMPAMS_OPT_PREDICT = 1,       /* 1 (default): the first pass of a step already writes the candidate list, using
                                     the previous step's threshold bucket as a guess that is verified afterwards */
   COMPAMS_OPT_FORCE_DENSE = 2,   /* 1: never build a candidate list; every selection pass reads the whole row */
-  COMPAMS_OPT_BAND = 3           /* 1 (default): the first pass also gets a window of keys around the threshold
+  COMPAMS_OPT_BAND = 3,          /* 1 (default): the first pass also gets a window of keys around the threshold
                                     expected from the last two steps, counts what lies above it and lists what lies
                                     inside; when the threshold does fall inside (verified exactly), one launch
                                     finishes the selection from that short list */
+  COMPAMS_OPT_CACHED_ARRAYS = 4  /* every compressor: how many of theta, m, v, vhat (in that order) the server's
+                                    lines read and write with ordinary accesses, the others with streaming ones:
+                                    0..4, or -1 (default) for compams_cached_state_arrays(d) */
 };
 int compams_set_option(compams_ctx* ctx, int option, int64_t value);
 

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libcompams.so")
 NONE, TOPK, BLOCKSIGN, TOPK_BLOCKS = 0, 1, 2, 3
 EPS_IN_SQRT, EPS_OUT_SQRT = 0, 1
 KEEP_STATE = 1
-OPT_CANDIDATE_CAP, OPT_PREDICT, OPT_FORCE_DENSE, OPT_BAND = 0, 1, 2, 3
+OPT_CANDIDATE_CAP, OPT_PREDICT, OPT_FORCE_DENSE, OPT_BAND, OPT_CACHED_ARRAYS = 0, 1, 2, 3, 4
 COUNTERS_PER_ROW = 8
 
 STATE = {"theta": 0, "m": 1, "v": 2, "vhat": 3, "e": 4, "last_idx": 5, "last_val": 6, "last_signbits": 7,

@@ -286,6 +286,7 @@ static bool is_topk(int compressor) { return compressor == COMPAMS_TOPK || compr
 
 struct compams_ctx {
   compams_config cfg;
+  int cached_override = -1;  // COMPAMS_OPT_CACHED_ARRAYS: -1 = the library picks by size
   Layout lay;
   Geometry geo;
   TopkWorkspace tk;
@@ -590,7 +591,7 @@ int compams_init(const compams_config* cfg, compams_ctx** out) {
   return COMPAMS_OK;
 }
 
-static AmsParams ams_params(const compams_config& c, float lr) {
+static AmsParams ams_params(const compams_config& c, float lr, int cached_override) {
   AmsParams ap;
   ap.beta1 = c.beta1;
   ap.beta2 = c.beta2;
@@ -600,7 +601,7 @@ static AmsParams ams_params(const compams_config& c, float lr) {
   ap.lr = lr;
   ap.nf = static_cast<float>(c.n);
   ap.eps_out = c.eps_mode == COMPAMS_EPS_OUT_SQRT;
-  ap.cached_arrays = cached_state_arrays(c.d);
+  ap.cached_arrays = cached_override >= 0 ? cached_override : cached_state_arrays(c.d);
   return ap;
 }
 
@@ -621,7 +622,7 @@ static int step_impl(compams_ctx* ctx, const float* g, float lr, bool workers_on
   if (workers_only && c.compressor == COMPAMS_NONE) return COMPAMS_BAD_STATE;  // the message is g itself
   if (const int bad = usable(ctx)) return bad;
   if (order_after_last(ctx, stream) != hipSuccess) return COMPAMS_HIP_ERROR;  // nothing of the step is enqueued yet
-  const AmsParams ap = ams_params(c, lr);
+  const AmsParams ap = ams_params(c, lr, ctx->cached_override);
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
   try {
@@ -678,7 +679,7 @@ int compams_server_step(compams_ctx* ctx, const uint32_t* messages, int64_t stri
   // call's stream is ordered behind that one on the device.
   if (settle_residuals(ctx) != hipSuccess) return COMPAMS_HIP_ERROR;
   if (order_after_last(ctx, stream) != hipSuccess) return COMPAMS_HIP_ERROR;
-  const AmsParams ap = ams_params(c, lr);
+  const AmsParams ap = ams_params(c, lr, ctx->cached_override);
   Launcher* L = ctx->profiling ? &ctx->launcher : nullptr;
   hipError_t err;
   try {
@@ -749,6 +750,11 @@ int compams_state(compams_ctx* ctx, int which, const void** dev_ptr, int64_t* co
 
 int compams_set_option(compams_ctx* ctx, int option, int64_t value) {
   if (!ctx) return COMPAMS_INVALID_ARG;
+  if (option == COMPAMS_OPT_CACHED_ARRAYS) {  // every compressor
+    if (value < -1 || value > 4) return COMPAMS_INVALID_ARG;
+    ctx->cached_override = static_cast<int>(value);
+    return COMPAMS_OK;
+  }
   if (!is_topk(ctx->cfg.compressor)) return COMPAMS_BAD_STATE;
   switch (option) {
     case COMPAMS_OPT_CANDIDATE_CAP:
@@ -965,7 +971,7 @@ int compams_step_static(const compams_config* cfg, const float* g, float lr, int
   bind_topk_workspace(&ctx, w);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const Layout& lay = ctx.lay;
-  const AmsParams ap = ams_params(ctx.cfg, lr);
+  const AmsParams ap = ams_params(ctx.cfg, lr, -1);
   hipError_t err = hipSuccess;
   auto ok = [&](hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; };
   // the array keeps what the last call left: control blocks, counters, histograms and chunk tables start at zero

@@ -148,6 +148,7 @@ def test_null_context_is_rejected_everywhere():
     assert L.compams_step(None, 0x1000, 1e-3, None) == -1
     assert L.compams_destroy(None) == -1
     assert L.compams_set_option(None, 0, 0) == -1
+    assert L.compams_set_option(None, B.OPT_CACHED_ARRAYS, 2) == -1
     assert L.compams_profile_enable(None, 1) == -1
     p, c = ctypes.c_void_p(), ctypes.c_int64()
     assert L.compams_state(None, 0, ctypes.byref(p), ctypes.byref(c)) == -1

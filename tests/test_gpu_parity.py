@@ -15,7 +15,7 @@ from paper_2205_05632_amd import binding as B
 from composed_blocks import CompamsBlockTopk
 from paper_2205_05632_amd import workloads as W
 
-from parity import Pair
+from parity import Pair, bits_equal
 
 pytestmark = pytest.mark.gpu
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -572,3 +572,55 @@ def test_inplace_probe_adds_one_to_every_element_and_nothing_else():
                 want = torch.arange(count + 8, dtype=torch.float32) * (a + 1)
                 want[:count] += 1.0
                 assert torch.equal(b.cpu(), want), (count, arrays, cached, a)
+
+
+@pytest.mark.parametrize("cached", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("case", ["topk", "topk_blocks", "blocksign", "none", "split"])
+def test_every_count_of_cached_state_arrays_gives_the_same_bytes(case, cached):
+    """The server kernels exist in five forms (0..4 of theta, m, v, vhat kept in the memory-side cache, the others
+    streamed); the library picks one by size, so small problems would only ever run one of them.  Forced here:
+    each form against the oracle, for every compressor and for the server half of a split step."""
+    n, d = 5, 3 * 4096 + 1234
+    rng = np.random.default_rng(100 + cached)
+    theta0 = (rng.standard_normal(d) * 0.1).astype(np.float32)
+    off = np.array([0, 400, 4096 + 8, 2 * 4096 + 100, d], dtype=np.int64)
+    gs = rand_grads(7, n, d, 5, scale=0.3)
+    if case == "split":
+        k = d // 50
+        wk = B.Compams(n, d, torch.from_numpy(theta0), compressor=B.TOPK, k=k)
+        sv = B.Compams(n, d, torch.from_numpy(theta0), compressor=B.TOPK, k=k)
+        sv.set_option(B.OPT_CACHED_ARRAYS, cached)
+        cpu = O.Oracle(n, d, theta0, compressor=O.TOPK, k=k)
+        for t, g in enumerate(gs):
+            gp = torch.zeros((n, wk.ld), dtype=torch.float32)
+            gp[:, :d] = torch.from_numpy(g)
+            wk.compams_worker_step(gp.to(wk.device))
+            msgs, words = wk.compams_encode()
+            sv.compams_server_step(msgs, words, 1e-3)
+            cpu.step(g, 1e-3)
+            torch.cuda.synchronize()
+            for name in ("theta", "m", "v", "vhat"):
+                assert bits_equal(sv.compams_state(name).cpu().numpy(), cpu.get(name)), f"{name} after step {t}"
+        wk.close(); sv.close(); cpu.close()
+        return
+    if case == "topk_blocks":
+        from test_gpu_topk_blocks import BlockPair
+        kb = np.maximum(1, (off[1:] - off[:-1]) // 40)
+        p = BlockPair(n, d, off, kb, theta0)
+        p.gpu.set_option(B.OPT_CACHED_ARRAYS, cached)
+        for t, g in enumerate(gs):
+            p.step(g)
+            p.compare(f"blocks, {cached} cached, step {t}", with_e=(t == len(gs) - 1))
+        p.gpu.close(); p.cpu.close()
+        return
+    kw = {"topk": dict(k=d // 50), "blocksign": dict(block_offsets=off), "none": {}}[case]
+    comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE}[case]
+    p = Pair(n, d, theta0, comp, **kw)
+    for bad in (-2, 5):
+        with pytest.raises(B.CompamsError):
+            p.gpu.set_option(B.OPT_CACHED_ARRAYS, bad)
+    p.gpu.set_option(B.OPT_CACHED_ARRAYS, -1)   # the library's own choice: allowed for every compressor
+    p.gpu.set_option(B.OPT_CACHED_ARRAYS, cached)
+    run_pair(p, gs, label=f"{case}, {cached} cached")
+    assert all(p.exact[s] for s in ("theta", "m", "v", "vhat"))
+    p.close()
