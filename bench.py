@@ -66,7 +66,8 @@ def load_traffic(workload, kernel):
 class Run:
     """One workload set up on the GPU: context, pre-generated gradients, and the timed loop."""
 
-    def __init__(self, name, steps, warmup, grad_buffers=0, eps_mode=None, predict=True, force_dense=False, band=True):
+    def __init__(self, name, steps, warmup, grad_buffers=0, eps_mode=None, predict=True, force_dense=False, band=True,
+                 cached_arrays=-1):
         import torch
         from paper_2205_05632_amd import binding as B
         from paper_2205_05632_amd import workloads as W
@@ -86,6 +87,8 @@ class Run:
             self.ctx.set_option(B.OPT_FORCE_DENSE, 1)
         if not band and self.comp in (B.TOPK, B.TOPK_BLOCKS):
             self.ctx.set_option(B.OPT_BAND, 0)
+        if cached_arrays >= 0:
+            self.ctx.set_option(B.OPT_CACHED_ARRAYS, cached_arrays)
         total = warmup + steps
         scale = W.coordinate_scale(w, self.dev)
         nbuf = total if grad_buffers <= 0 else min(total, grad_buffers)
@@ -200,6 +203,9 @@ def main():
     ap.add_argument("--force-dense", action="store_true", help="ablation: no candidate lists at all")
     ap.add_argument("--no-band", action="store_true",
                     help="ablation: every selection by the general kernels (no window carried over for the threshold key)")
+    ap.add_argument("--cached-arrays", type=int, default=-1,
+                    help="ablation: how many of theta, m, v, vhat the server kernels keep in the memory-side cache "
+                         "(0..4; default: the library's choice by size)")
     ap.add_argument("--grad-buffers", type=int, default=0,
                     help="how many distinct gradient buffers to cycle through (0: one per step)")
     ap.add_argument("--settle-each-step", action="store_true",
@@ -223,7 +229,7 @@ def main():
     dev = torch.device("cuda:0")
     run = Run(args.workload, args.steps, args.warmup, grad_buffers=args.grad_buffers,
               eps_mode=B.EPS_OUT_SQRT if args.eps_out else B.EPS_IN_SQRT, predict=not args.no_predict,
-              force_dense=args.force_dense, band=not args.no_band)
+              force_dense=args.force_dense, band=not args.no_band, cached_arrays=args.cached_arrays)
     w, ctx, comp, grads = run.w, run.ctx, run.comp, run.grads
     event_mode = 0 if args.no_kernel_events else (1 if args.kernels else 2)
     main_res = run.timed(event_mode=event_mode, stride=args.event_stride, settle_each_step=args.settle_each_step)
@@ -349,7 +355,9 @@ def main():
         "config": {"workload": w.name, "n": w.n, "d": w.d, "compressor": w.compressor, "k": w.k,
                    "num_blocks": (len(w.block_offsets()) - 1) if w.compressor == "blocksign" else 0,
                    "eps_mode": "out_sqrt" if args.eps_out else "in_sqrt",
-                   "predict": not args.no_predict, "force_dense": args.force_dense, "band": not args.no_band},
+                   "predict": not args.no_predict, "force_dense": args.force_dense, "band": not args.no_band,
+                   "cached_state_arrays": args.cached_arrays if args.cached_arrays >= 0
+                   else B.compams_cached_state_arrays(w.d)},
         "hbm_gbps": main_res["hbm_gbps"],
         "hbm_frac_of_peak": main_res["hbm_frac_of_peak"],
         "algorithmic_bytes_per_step": main_res["algorithmic_bytes_per_step"],
