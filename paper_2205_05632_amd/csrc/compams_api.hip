@@ -59,7 +59,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Layout {
   size_t total;
   // top-k
-  size_t rows, flags, counters, hist0, hist1, hist1x, hist2, bhist, xcur, chunk_rec, blk, sel_off, desc, desc2, bnd, bnd_sel, cand, band,
+  size_t rows, flags, counters, hist0, hist1, hist1x, hist2, bhist, xcur, chunk_rec, blk, blk_prefix, sel_off, desc, desc2, bnd, bnd_sel, cand, band,
       idx, val, tau, count_gt, wire_total, wire_tile_off, wire_tile_sum, sel_off_srv, segs, map_first, map_level0, map_sweep,
       map_count, map_emit, map_final, micro_list;
   // block-sign
@@ -169,6 +169,7 @@ Layout make_layout(const compams_config* c) {
     L.xcur = take(n * kSubLists * kCursorPitch * 4);
     L.chunk_rec = take(n * nc * 16);
     L.blk = take(n * kMaxCountBlocks * 8);
+    L.blk_prefix = take(n * kMaxCountBlocks * 8);
     L.sel_off = take(n * (nc + 1) * 4);
     L.desc = take(n * nc * 8);
     L.desc2 = take(n * nc * 8);
@@ -223,6 +224,7 @@ Layout make_layout(const compams_config* c) {
     L.xcur = take(n * big * kSubLists * kCursorPitch * 4);
     L.chunk_rec = take(n * chunks * 16);
     L.blk = take(S * kMaxCountBlocks * 8);
+    L.blk_prefix = take(S * kMaxCountBlocks * 8);
     L.sel_off = take(n * (chunks + M) * 4);
     L.desc = take(n * chunks * 8);
     L.desc2 = take(n * chunks * 8);
@@ -367,6 +369,7 @@ static void bind_topk_workspace(compams_ctx* ctx, char* w) {
   t.xcur = reinterpret_cast<uint32_t*>(w + lay.xcur);
   t.chunk_rec = reinterpret_cast<uint4*>(w + lay.chunk_rec);
   t.blk = reinterpret_cast<uint2*>(w + lay.blk);
+  t.blk_prefix = reinterpret_cast<uint2*>(w + lay.blk_prefix);
   t.sel_off = reinterpret_cast<uint32_t*>(w + lay.sel_off);
   t.count_gt = reinterpret_cast<uint32_t*>(w + lay.count_gt);
   t.wire_total = reinterpret_cast<uint32_t*>(w + lay.wire_total);

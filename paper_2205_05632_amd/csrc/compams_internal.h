@@ -169,6 +169,8 @@ struct TopkWorkspace {
   uint4* chunk_rec;     // n * num_chunks : keys above tau, keys equal to tau, and the exclusive prefixes of both
                         //                  within the chunk's count block
   uint2* blk;           // n * kMaxCountBlocks : the two totals of every count block
+  uint2* blk_prefix;    // n * kMaxCountBlocks : for a problem selected by k_topk_band, the totals of the blocks
+                        // before each block (the sums the last kernel would otherwise form per chunk)
   uint32_t* sel_off;    // n * (num_chunks + 1) : where each chunk's slice of the worker's list starts
   uint32_t* count_gt;   // n : selected entries whose key lies strictly above the threshold key
   uint32_t* wire_total;    // n : words of the gap stream of the message being packed or unpacked

@@ -1074,7 +1074,11 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
         rec[first + i] = make_uint4(g, 0u, pre_gt, 0u);
         pre_gt += g;
       }
-    if (t == 0) ws.blk[static_cast<size_t>(row) * kMaxCountBlocks + sc.group] = make_uint2(tot_gt, 0u);
+    if (t == 0) {  // (device-scope stores: the problem's last workgroup adds the blocks' totals up)
+      uint2* tot = ws.blk + static_cast<size_t>(row) * kMaxCountBlocks + sc.group;
+      __hip_atomic_store(&tot->x, tot_gt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&tot->y, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
   // ---- 3. the problem-wide part, by whichever of its workgroups finishes last ----
   if (!last_group_of_row(&rowp->ticket_band, sc.groups, &sh_flag)) return;
@@ -1084,10 +1088,21 @@ __global__ __launch_bounds__(kWG) void k_topk_band(Geometry geo, TopkWorkspace w
     // the gathered entries (written by other workgroups with device-scope stores: read at that scope)
     const uint2* bnd = ws.bnd + static_cast<size_t>(row) * kBoundaryCap;
     const AgentView view = agent_view(reinterpret_cast<const uint32_t*>(bnd), 2 * kBoundaryCap);
+    // ... and with the same round trip the blocks' totals, for their prefix sums: the last kernel then needs one
+    // number per worker and chunk instead of a sum over all the blocks before the chunk's
+    static_assert(kMaxCountBlocks <= kWG, "a thread per count block");
+    const AgentView totals = agent_view(reinterpret_cast<const uint32_t*>(ws.blk + static_cast<size_t>(row) * kMaxCountBlocks),
+                                        2 * kMaxCountBlocks);
+    const uint32_t my_total = t < sc.groups ? load_agent(totals, 2 * t) : 0u;
     if (t < kBoundaryCap) {
       uint2 en = make_uint2(0xffffffffu, 0u);
       if (t < n_boundary) en = make_uint2(load_agent(view, 2 * t), load_agent(view, 2 * t + 1));
       b_en[t] = en;
+    }
+    {
+      uint32_t all;
+      const uint32_t before = block_excl_scan<kWG>(my_total, scratch, &all);  // (ends with a barrier of its own)
+      if (t < sc.groups) ws.blk_prefix[static_cast<size_t>(row) * kMaxCountBlocks + t] = make_uint2(before, 0u);
     }
     __syncthreads();
     // rank by (key descending, coordinate ascending): coordinates are distinct, so ranks are
@@ -1800,14 +1815,14 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu((UNI && NC 
   // request gains nothing and the kernel keeps its eight wavefronts).
   constexpr int kEarly = (ROLE != kWorkerHalf && UNI && NC < 4) ? 1 : 0;  // (the per-block form has no registers to spare)
   const uint32_t d_end = f.coord_base + f.d_loc;  // the chunk's coordinates end here at the latest
-  float4 th0[kEarly > 0 ? kEarly : 1], mm0[kEarly > 0 ? kEarly : 1], vv0[kEarly > 0 ? kEarly : 1], vh0[kEarly > 0 ? kEarly : 1];
+  float4 th0[kEarly > 0 ? kEarly : 1], mm0[kEarly > 0 ? kEarly : 1], vv0[kEarly > 0 ? kEarly : 1];
 #pragma unroll
   for (int r = 0; r < kEarly; ++r) {
     const uint32_t j = base + r * kWG * 4 + threadIdx.x * 4;
-    th0[r] = mm0[r] = vv0[r] = vh0[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+    th0[r] = mm0[r] = vv0[r] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (j + 3 < d_end) {
       th0[r] = load_state4<(NC > 0)>(theta + j); mm0[r] = load_state4<(NC > 1)>(m + j);
-      vv0[r] = load_state4<(NC > 2)>(v + j); vh0[r] = load_state4<(NC > 3)>(vhat + j);
+      vv0[r] = load_state4<(NC > 2)>(v + j);  // (vhat follows in phase 3: a fourth early load would be spilled)
     }
   }
 
@@ -1829,7 +1844,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu((UNI && NC 
       // to a scalar register where it is loaded, or a branch around a worker's loads makes every worker a round
       // trip of its own): the chunk's record and the first 128 block totals of each worker as vector loads, r and
       // the route through the scalar path.  A worker beyond the last reads worker i0's tables and is ignored.
-      uint2 pa[kPerWave], pb[kPerWave];
+      uint2 pre[kPerWave];
       uint32_t fast_[kPerWave];
 #pragma unroll
       for (int u = 0; u < kPerWave; ++u) {
@@ -1837,47 +1852,45 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu((UNI && NC 
         const uint32_t is = i < geo.n ? i : i0;
         const uint32_t rowi = f.row0 + is * f.row_stride;
         rec[u] = ws.chunk_rec[f.chunk0 + is * f.chunk_stride + c];
-        const uint2* blk = ws.blk + static_cast<size_t>(rowi) * kMaxCountBlocks;
-        pa[u] = make_uint2(0, 0);
-        pb[u] = make_uint2(0, 0);
-        if (lane < my_block) pa[u] = blk[lane];
-        if (lane + 64 < my_block) pb[u] = blk[lane + 64];
+        // a problem selected by k_topk_band has the sum over the blocks before the chunk's ready (the same in
+        // every lane); for any other the blocks' totals are added up below
+        pre[u] = make_uint2(0, 0);
+        if (my_block) pre[u] = ws.blk_prefix[static_cast<size_t>(rowi) * kMaxCountBlocks + my_block];
         const uint32_t* rw = reinterpret_cast<const uint32_t*>(ws.rows + rowi);
         r_[u] = table_u32(rw, offsetof(TopkRow, r) / 4);
         fast_[u] = table_u32(rw, offsetof(TopkRow, fast) / 4);
       }
+      bool sums = false;  // wave-uniform: some worker of this wavefront needs its totals added up
 #pragma unroll
       for (int u = 0; u < kPerWave; ++u) {
         const bool there = i0 + wave + u * kWaves < geo.n;  // wave-uniform
-        part[u] = make_uint2(pa[u].x + pb[u].x, pa[u].y + pb[u].y);
         fast_mask |= (there && fast_[u] ? 1u : 0u) << u;
+        sums = sums || (there && !fast_[u] && my_block != 0);
+        part[u] = pre[u];
         if (!there) { rec[u] = make_uint4(0, 0, 0, 0); part[u] = make_uint2(0, 0); r_[u] = 0; }
       }
-      if (my_block > 128) {  // uniform: rows of more than 128 count blocks
-        static_assert(kMaxCountBlocks <= 256, "four block totals per lane at most");
+      if (sums) {  // the general kernels' problems (the rare route: worker after worker, few registers)
 #pragma unroll
         for (int u = 0; u < kPerWave; ++u) {
           const uint32_t i = i0 + wave + u * kWaves;
-          pa[u] = make_uint2(0, 0);
-          pb[u] = make_uint2(0, 0);
-          if (i < geo.n) {  // wave-uniform
+          if (i < geo.n && !((fast_mask >> u) & 1u)) {  // wave-uniform
             const uint2* blk = ws.blk + static_cast<size_t>(f.row0 + i * f.row_stride) * kMaxCountBlocks;
-            if (lane + 128 < my_block) pa[u] = blk[lane + 128];
-            if (lane + 192 < my_block) pb[u] = blk[lane + 192];
+            uint2 sum = make_uint2(0, 0);
+            for (uint32_t b = lane; b < my_block; b += 64) {
+              const uint2 t = blk[b];
+              sum.x += t.x;
+              sum.y += t.y;
+            }
+            part[u] = make_uint2(wave_sum(sum.x), wave_sum(sum.y));
           }
-        }
-#pragma unroll
-        for (int u = 0; u < kPerWave; ++u) {
-          part[u].x += pa[u].x + pb[u].x;
-          part[u].y += pa[u].y + pb[u].y;
         }
       }
 #pragma unroll
       for (int u = 0; u < kPerWave; ++u) {
         const uint32_t i = i0 + wave + u * kWaves;
         if (i >= geo.n) continue;  // wave-uniform
-        const uint32_t gt_before = wave_sum(part[u].x) + rec[u].z;
-        const uint32_t eq_before = wave_sum(part[u].y) + rec[u].w;
+        const uint32_t gt_before = part[u].x + rec[u].z;
+        const uint32_t eq_before = part[u].y + rec[u].w;
         const uint32_t r = ((fast_mask >> u) & 1u) ? 0u : r_[u];  // that route does not use the "equal to tau" columns
         const uint32_t taken_before = eq_before < r ? eq_before : r;  // ties go in coordinate order until r are in
         const uint32_t quota = r - taken_before;
@@ -2033,7 +2046,8 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu((UNI && NC 
     if (j + 3 < d_end) {
       float4 th, mm, vv, vh;
       if (r < kEarly) {
-        th = th0[r]; mm = mm0[r]; vv = vv0[r]; vh = vh0[r];
+        th = th0[r]; mm = mm0[r]; vv = vv0[r];
+        vh = load_state4<(NC > 3)>(vhat + j);
       } else {
         th = load_state4<(NC > 0)>(theta + j); mm = load_state4<(NC > 1)>(m + j);
         vv = load_state4<(NC > 2)>(v + j); vh = load_state4<(NC > 3)>(vhat + j);
