@@ -111,6 +111,35 @@ def test_ties_at_the_threshold(levels, expect_band):
     p.close()
 
 
+def test_special_values_arriving_on_the_band_route():
+    """Once every row is selected in one launch, a step brings infinities, NaNs (the largest keys of all), values
+    near the largest finite one and negative zeros: they lie far above the window, are kept like any other entry,
+    and the rows stay on the route; the state then holds Inf and NaN at those coordinates on both sides."""
+    n, d, k = 3, 33 * 4096 + 77, 1400
+    rng = np.random.default_rng(77)
+    p = Pair(n, d, np.zeros(d, np.float32), B.TOPK, k=k)
+    where = {"inf": [5, 4096 * 7 + 63, d - 1], "ninf": [4096, 4097], "nan": [64, 4096 * 20 + 1], "huge": [9, 70000],
+             "nzero": [0, 1, 2, 3, 8191]}
+    for t in range(12):
+        g = rng.standard_normal((n, d)).astype(np.float32)
+        if t == 7:
+            g[:, where["inf"]] = np.inf
+            g[1:, where["ninf"]] = -np.inf
+            g[0, where["nan"]] = np.nan
+            g[2, where["huge"]] = np.float32(-3.0e38)
+            g[:, where["nzero"]] = np.float32(-0.0)
+        with np.errstate(invalid="ignore", over="ignore"):
+            p.step(g, 1e-3, label=f"special values step {t}", with_e=(t in (7, 11)))
+        used = band_counter(p)
+        if t >= 6:
+            assert (used > 0).all(), (t, used)
+        if t == 7:
+            idx = p.gpu.compams_state("last_idx").cpu().numpy()
+            assert all(np.isin(where["inf"], idx[i]).all() for i in range(n))
+            assert np.isin(where["nan"], idx[0]).all() and np.isin(where["huge"], idx[2]).all()
+    p.close()
+
+
 def test_window_that_overflows_is_left_to_the_general_kernels():
     """Almost all magnitudes within a fraction of a per cent of each other: the window holds far more entries
     than the band list, in every step."""
