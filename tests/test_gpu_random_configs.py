@@ -82,8 +82,11 @@ def draw_config(seed):
     return cfg, rng
 
 
-# COMPAMS_RANDOM_CONFIGS=<count> widens the sweep for an occasional longer run
-@pytest.mark.parametrize("seed", range(int(os.environ.get("COMPAMS_RANDOM_CONFIGS", "120"))))
+# COMPAMS_RANDOM_CONFIGS=<count> widens the sweep for an occasional longer run, COMPAMS_RANDOM_FIRST=<seed> moves it
+FIRST = int(os.environ.get("COMPAMS_RANDOM_FIRST", "0"))
+
+
+@pytest.mark.parametrize("seed", range(FIRST, FIRST + int(os.environ.get("COMPAMS_RANDOM_CONFIGS", "120"))))
 def test_random_configuration(seed):
     cfg, rng = draw_config(seed)
     n, d = cfg["n"], cfg["d"]
