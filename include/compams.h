@@ -44,7 +44,9 @@ typedef struct compams_ctx compams_ctx; /* opaque; host memory owned by the libr
 
 /* The compressor C of Assumption 1. */
 enum {
-  COMPAMS_NONE = 0,     /* C(x) = x (q = 0): full-precision distributed AMSGrad; e is neither read nor written */
+  COMPAMS_NONE = 0,     /* C(x) = x (q = 0): full-precision distributed AMSGrad (Algorithm 1, which has no residual);
+                           e is neither read nor written and stays zero, also for an infinite gradient entry,
+                           where the error line of Algorithm 2 taken literally (Inf - Inf) would leave a NaN */
   COMPAMS_TOPK = 1,     /* Definition 1: keep the k coordinates of largest magnitude per worker */
   COMPAMS_BLOCKSIGN = 2, /* Definition 2: per block, sign(x) times the block's mean absolute value */
   COMPAMS_TOPK_BLOCKS = 3 /* Definition 1 applied to every block on its own: block b keeps its block_k[b] coordinates

@@ -327,6 +327,28 @@ def test_blocksign_deferred_residual_with_a_block_that_is_not_finite():
     p.close()
 
 
+def test_blocksign_with_nans_in_the_gradients():
+    """A NaN makes its block's mean a NaN (whatever else the block holds, an infinity included) and codes as +1;
+    the block's residuals and parameters are NaNs from then on, on both sides, and the other blocks go on bit
+    for bit.  NaNs of either sign and with a payload, in one-coordinate, small and large blocks."""
+    n, d = 3, 50000
+    rng = np.random.default_rng(41)
+    off = np.array([0, 1000, 1004, 20000, 20001, 40960, d], dtype=np.int64)
+    p = Pair(n, d, np.zeros(d, np.float32), B.BLOCKSIGN, block_offsets=off)
+    for t in range(7):
+        g = rng.standard_normal((n, d)).astype(np.float32)
+        if t in (2, 4):
+            g[0, 1001] = np.nan
+            g[1, 20000] = -np.nan
+            g[0, 45000] = np.uint32(0xFFC12345).view(np.float32)
+            g[2, 45001] = np.inf
+        with np.errstate(invalid="ignore"):
+            p.step(g, 1e-3, label=f"NaN blocks step {t}", with_e=(t in (3, 6)))
+    mu = p.cpu.get("mu")
+    assert np.isnan(mu[0, [1, 5]]).all() and np.isnan(mu[1, 3]) and np.isfinite(mu[:, [0, 2, 4]]).all()
+    p.close()
+
+
 def test_blocksign_wide_dynamic_range_is_summed_exactly():
     """Magnitudes from denormal to 1e30 in one block: any accumulation that is not exact gets the scale wrong."""
     n, d = 2, 40000
@@ -444,6 +466,39 @@ def test_identity_compressor(n, d):
     p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, B.NONE)
     run_pair(p, rand_grads(d, n, d, 10, scale=0.3), label="none")
     assert all(p.exact[s] for s in ("theta", "m", "v", "vhat"))
+    p.close()
+
+
+def test_identity_compressor_with_infinite_gradients():
+    """Algorithm 1 has no residual: an infinite entry of one worker's gradient makes that coordinate's average,
+    m and v infinite and its parameter a NaN, and they stay so (beta * Inf + finite); the library keeps e at
+    zero.  The oracle's literal error line of Algorithm 2 (x - x in fp32) leaves a NaN there instead, which the
+    next step carries into m and v, so those coordinates are checked against the closed form and all the others
+    against the oracle, bit for bit."""
+    n, d = 3, 30000
+    rng = np.random.default_rng(15)
+    p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, B.NONE)
+    pos, neg, nan = [7, 4096, d - 1], [8, 20000], [100, 9000]
+    special = np.array(pos + neg + nan)
+    rest = np.setdiff1d(np.arange(d), special)
+    for t in range(6):
+        g = (rng.standard_normal((n, d)) * 0.3).astype(np.float32)
+        if t == 2:
+            g[1, pos] = np.inf
+            g[2, neg] = -np.inf
+            g[0, nan] = np.nan
+        with np.errstate(invalid="ignore", over="ignore"):
+            p.step(g, 1e-3, check=False)
+        torch.cuda.synchronize()
+        got = {s: p.gpu.compams_state(s).cpu().numpy() for s in ("theta", "m", "v", "vhat")}
+        for s, a in got.items():
+            assert bits_equal(a[rest], p.cpu.get(s)[rest]), f"step {t}: {s} away from the special entries"
+        if t >= 2:
+            assert (got["m"][pos] == np.inf).all() and (got["m"][neg] == -np.inf).all(), got["m"][special]
+            assert (got["v"][pos + neg] == np.inf).all() and (got["vhat"][pos + neg] == np.inf).all()
+            assert np.isnan(got["theta"][special]).all()
+            assert np.isnan(got["m"][nan]).all() and np.isnan(got["v"][nan]).all()
+    assert p.gpu.e is None            # no residual array exists for this compressor
     p.close()
 
 

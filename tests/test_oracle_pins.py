@@ -167,6 +167,47 @@ def test_blocksign_l1_mass_sign_bits_and_bound():
     assert abs(float(O.block_l1_mean(z)) - math.sqrt(2 / math.pi)) < 5e-3
 
 
+def test_non_finite_entries_follow_ieee_arithmetic():
+    """What IEEE arithmetic fixes for entries that are not finite.  Block-sign (Definition 2): a block's sum of
+    magnitudes is +Inf with an infinity in it and NaN with a NaN in it (NaN wins over Inf), whatever the sign or
+    payload; a NaN is not below zero, so its sign codes as +1; the other blocks are untouched.  Top-k
+    (Definition 1, keys as magnitude bits): the residual at a kept coordinate is zero, an infinite one included.
+    Identity: the error line of Algorithm 2 is x - x, which is zero for finite x and NaN for an infinite one."""
+    d = 64
+    offsets = np.array([0, 8, 16, 24, 32, d], dtype=np.int64)
+    x = np.linspace(-1.0, 1.0, d).astype(np.float32)
+    x[3] = np.inf; x[7] = 0.5                                   # block 0: Inf, beside entries of both signs
+    x[9] = np.uint32(0xFFC12345).view(np.float32)               # block 1: negative NaN with a payload
+    x[17] = np.nan; x[18] = -np.inf                             # block 2: NaN and Inf
+    o = _blocksign_once(x, offsets)
+    mu, bits, c, e = o.get("mu")[0], o.get("bits")[0], o.get("ctil")[0], o.get("e")[0]
+    assert mu[0] == np.inf and np.isnan(mu[1]) and np.isnan(mu[2])
+    assert math.isinf(O.exact_abs_sum(x[0:8])) and math.isnan(O.exact_abs_sum(x[8:16])) and math.isnan(O.exact_abs_sum(x[16:24]))
+    for b in (3, 4):
+        lo, hi = offsets[b], offsets[b + 1]
+        assert mu[b] == np.float32(math.fsum(abs(float(v)) for v in x[lo:hi]) / float(hi - lo))
+    neg = [(int(bits[j // 32]) >> (j % 32)) & 1 for j in range(d)]
+    with np.errstate(invalid="ignore"):
+        assert neg == [int(v < 0) for v in x]                   # NaNs of either sign: 0; -Inf: 1
+    assert c[3] == np.inf and e[3] != e[3]                      # Inf - Inf
+    assert e[0] == np.inf and e[7] == -np.inf                   # the block's finite entries: x - (-Inf), x - (+Inf)
+    assert np.isnan(c[8:24]).all() and np.isnan(e[8:24]).all()
+    o.close()
+    ot = O.Oracle(1, d, np.zeros(d, np.float32), compressor=O.TOPK, k=4)
+    ot.step(x.reshape(1, d), 1e-3)
+    assert list(ot.get("idx")[0]) == [3, 9, 17, 18]             # two NaNs, two infinities: the four largest keys
+    et = ot.get("e")[0]
+    assert (et[[3, 9, 17, 18]] == 0).all() and np.signbit(et[[3, 9, 17, 18]]).sum() == 0
+    rest = np.setdiff1d(np.arange(d), [3, 9, 17, 18])
+    assert np.array_equal(et[rest], x[rest])
+    ot.close()
+    oi = O.Oracle(1, d, np.zeros(d, np.float32), compressor=O.NONE)
+    oi.step(x.reshape(1, d), 1e-3)
+    ei = oi.get("e")[0]
+    assert np.isnan(ei[[3, 9, 17, 18]]).all() and (ei[rest] == 0).all()
+    oi.close()
+
+
 def test_blocksign_unit_blocks_is_identity():
     # d_i = 1 for all i gives q = 0 in Remark 1: C(x) = x and the residual stays zero
     rng = np.random.default_rng(2)
