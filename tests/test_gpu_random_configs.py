@@ -40,9 +40,15 @@ def draw_gradients(rng, kind, n, d):
     elif kind == "ties":        # few distinct magnitudes, both signs and both zeros
         g = rng.integers(-3, 4, (n, d)).astype(np.float64) * 0.25
         g[:, ::5] *= -1.0
-    else:                       # denormals beside ordinary numbers
+    elif kind == "denormal":    # denormals beside ordinary numbers
         g = rng.standard_normal((n, d))
         g[:, ::3] *= 1e-41
+    else:                       # every other call brings a few entries that are not finite, or nearly so
+        g = rng.standard_normal((n, d))
+        if rng.random() < 0.5:
+            pool = [np.nan, -np.nan] if kind == "nans" else [np.inf, -np.inf, np.nan, -np.nan, 3.0e38, -3.0e38]
+            m = int(rng.integers(1, 7))
+            g[rng.integers(0, n, m), rng.integers(0, d, m)] = rng.choice(pool, m)
     return g.astype(np.float32)
 
 
@@ -60,7 +66,10 @@ def draw_config(seed):
     ld = None
     if rng.random() < 0.5:
         ld = (d + 3) // 4 * 4 + 4 * int(rng.integers(0, 6))
-    kind = ["scaled", "sparse", "heavy", "ties", "denormal"][int(rng.integers(0, 5))]
+    kind = ["scaled", "sparse", "heavy", "ties", "denormal", "specials"][int(rng.integers(0, 6))]
+    if kind == "specials" and compressor == "none":
+        kind = "nans"           # an infinite entry is where the library follows Algorithm 1 and the oracle the literal
+                                # error line of Algorithm 2 (a test of its own covers that)
     cfg = dict(seed=seed, n=n, d=d, ld=ld, compressor=compressor, kind=kind)
     if compressor == "topk":
         cfg["k"] = int(rng.choice([1, d, max(1, d // 100), int(rng.integers(1, d + 1))]))
@@ -97,14 +106,16 @@ def test_random_configuration(seed):
     if cfg["compressor"] == "topk_blocks":
         p = BlockPair(n, d, cfg["off"], cfg["kb"], theta0)
         for t in range(steps):
-            p.step(draw_gradients(rng, cfg["kind"], n, d))
+            with np.errstate(invalid="ignore", over="ignore"):
+                p.step(draw_gradients(rng, cfg["kind"], n, d))
             p.compare(f"{label} step {t}", with_e=(t % 2 == 1))
             tally(p.gpu, t)
     else:
         comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE}[cfg["compressor"]]
         p = Pair(n, d, theta0, comp, k=cfg.get("k", 0), block_offsets=cfg.get("off"), ld=cfg["ld"])
         for t in range(steps):
-            p.step(draw_gradients(rng, cfg["kind"], n, d), 1e-3, label=f"{label} step {t}", with_e=(t % 2 == 1))
+            with np.errstate(invalid="ignore", over="ignore"):
+                p.step(draw_gradients(rng, cfg["kind"], n, d), 1e-3, label=f"{label} step {t}", with_e=(t % 2 == 1))
             if comp == B.TOPK:
                 tally(p.gpu, t)
     p.close()
