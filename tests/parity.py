@@ -95,7 +95,8 @@ class Pair:
             a = gpu.compams_state(name).cpu().numpy()
             b = cpu.get(name)
             close(a, b, f"{label}: {name}")
-            if not bits_equal(np.ascontiguousarray(a), b):
+            ok = ~np.isnan(b)       # a NaN is a NaN (close() has compared where they are): sign and payload are not part of the bar
+            if not bits_equal(np.ascontiguousarray(a)[ok], b[ok]):
                 self.exact[name] = False
 
     def close(self):

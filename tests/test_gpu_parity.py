@@ -469,6 +469,30 @@ def test_identity_compressor(n, d):
     p.close()
 
 
+@pytest.mark.parametrize("compressor", ["topk", "blocksign", "none"])
+@pytest.mark.parametrize("beta1,beta2,eps,eps_mode", [
+    (0.0, 0.0, 1e-3, B.EPS_IN_SQRT),          # no memory at all: m is the average, v its square
+    (0.5, 0.9, 0.0, B.EPS_OUT_SQRT),          # no epsilon: the quotient alone
+    (0.99, 0.9999, 1e-12, B.EPS_IN_SQRT),
+    (0.9, 0.999, 0.5, B.EPS_OUT_SQRT),        # an epsilon that dominates the root
+])
+def test_hyper_parameters_away_from_the_defaults_and_a_learning_rate_that_changes(compressor, beta1, beta2, eps, eps_mode):
+    """The moment and parameter lines of Algorithm 2 with other constants than the experiments' (Section 5.1),
+    and a learning rate that differs from step to step (zero, negative and large ones among them): it is an
+    argument of each step, not part of the context."""
+    n, d = 3, 3 * 4096 + 99
+    rng = np.random.default_rng(int(beta1 * 100) + 7)
+    kw = {"topk": dict(k=300), "blocksign": dict(block_offsets=np.array([0, 5, 4096, 9000, d], np.int64)), "none": {}}[compressor]
+    comp = {"topk": B.TOPK, "blocksign": B.BLOCKSIGN, "none": B.NONE}[compressor]
+    p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, comp, beta1=beta1, beta2=beta2, eps=eps,
+             eps_mode=eps_mode, **kw)
+    for t, lr in enumerate([1e-3, 0.0, 0.25, -1e-2, 3e-5, 10.0, 1e-3]):
+        g = (rng.standard_normal((n, d)) * 0.3 + 0.01).astype(np.float32)
+        p.step(g, lr, label=f"{compressor} b1={beta1} b2={beta2} eps={eps} lr={lr} step {t}")
+    assert all(p.exact[s] for s in ("theta", "m", "v", "vhat"))
+    p.close()
+
+
 def test_identity_compressor_with_infinite_gradients():
     """Algorithm 1 has no residual: an infinite entry of one worker's gradient makes that coordinate's average,
     m and v infinite and its parameter a NaN, and they stay so (beta * Inf + finite); the library keeps e at
