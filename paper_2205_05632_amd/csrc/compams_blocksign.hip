@@ -516,27 +516,130 @@ __global__ __launch_bounds__(kWG) void k_bs_pass2(float* __restrict__ e, Geometr
 
 // ---------------------------------------------------------------------------------------------
 // Server lines for sign/scale messages: gbar_j = (sum_i s_ij * mu_i,b(j)) / n in worker order, then
-// AMSGrad.  One wavefront per chunk of coordinates.
+// AMSGrad.  A workgroup per chunk of coordinates, each of its wavefronts a share of KQ rounds.
 // ---------------------------------------------------------------------------------------------
-constexpr int kBsWorkers = 8;  // workers whose sign words and scales are requested together
-constexpr int kBsSplit = 4;    // wavefronts per chunk in the server kernel
+constexpr int kBsWorkers = 8;  // workers whose sign words and scales are requested together (rounds that meet block ends)
+
+// Wavefronts per chunk.  With the whole state cached a wavefront takes two rounds and asks for everything it
+// needs at once; with state that streams from HBM four rounds, the next one's state requested while one is
+// updated (ResNet-18 shape, all cached: 61 against 66 us; GPT-2 shape, all streamed: 666 against 685 us).
+constexpr int bs_server_split(int cached_arrays) { return cached_arrays == 4 ? 8 : 4; }
+
+// Sums of a share of KQ rounds that lies inside block b and inside the row: sum[r][s] for the lane's four
+// coordinates of round r.  A worker's sign words of the share are KQ * 8 consecutive words, which a group of
+// lanes requests once, several workers per load; a round then takes its word out of the holder's register.
+// (Asked for round by round, 32 bytes at a time with the state's traffic in between, the lines were fetched
+// 3.4 times over.)  One scale per worker serves all rounds.  Worker order, as everywhere.
+template <int KQ>
+__device__ __forceinline__ void bs_share_sums(float (&sum)[KQ][4], const Geometry& geo, const BlocksignWorkspace& ws,
+                                              uint32_t b, uint32_t q0, uint32_t lane) {
+  constexpr int kShareWords = KQ * 8;           // sign words of one worker for the share
+  constexpr int kPerLoad = 64 / kShareWords;    // workers whose words one load of the wavefront brings in
+  constexpr int kTrip = KQ == 2 ? 16 : 8;       // workers per trip: kTrip / kPerLoad loads, kTrip scales
+  static_assert(kShareWords * kPerLoad == 64 && kTrip % kPerLoad == 0, "lanes of a load: worker by word");
+#pragma unroll
+  for (int r = 0; r < KQ; ++r)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) sum[r][s] = 0.0f;
+  const uint32_t qw = (q0 >> 5) + (lane % kShareWords), sub = lane / kShareWords;
+  const uint32_t sh = (lane & 7u) * 4u, src = lane >> 3;
+  for (uint32_t i0 = 0; i0 < geo.n; i0 += kTrip) {
+    uint32_t w[kTrip / kPerLoad];
+#pragma unroll
+    for (int u = 0; u < kTrip / kPerLoad; ++u) {
+      const uint32_t i = i0 + kPerLoad * u + sub;
+      w[u] = i < geo.n ? ws.bits[static_cast<size_t>(i) * geo.words + qw] : 0u;
+    }
+    float mu[kTrip];
+#pragma unroll
+    for (int u = 0; u < kTrip; ++u)
+      mu[u] = i0 + u < geo.n ? table_f32(ws.scales + static_cast<size_t>(i0 + u) * geo.num_blocks, b) : 0.0f;
+#pragma unroll
+    for (int u = 0; u < kTrip; ++u) {
+      if (i0 + u < geo.n) {  // wave-uniform
+        if ((u & 1) == 0) __builtin_amdgcn_sched_barrier(0);  // (else the words of all workers are taken at once: 82 registers)
+#pragma unroll
+        for (int r = 0; r < KQ; ++r) {
+          const uint32_t word =
+              __shfl(w[u / kPerLoad], static_cast<int>((u % kPerLoad) * kShareWords + r * 8 + src), 64);
+          const uint32_t nib = (word >> sh) & 15u;
+#pragma unroll
+          for (int s = 0; s < 4; ++s) sum[r][s] = sum[r][s] + (((nib >> s) & 1u) ? -mu[u] : mu[u]);
+        }
+      }
+    }
+  }
+}
 
 template <int NC>  // how many of theta, m, v, vhat are cached, the others streamed (see the top-k final kernel)
-__global__ __launch_bounds__(kWG) void k_bs_amsgrad(float* __restrict__ theta, float* __restrict__ m,
-                                                     float* __restrict__ v, float* __restrict__ vhat, Geometry geo,
-                                                     BlocksignWorkspace ws, AmsParams p) {
+__global__ __launch_bounds__(bs_server_split(NC) * 64) __attribute__((amdgpu_waves_per_eu(7, 8))) void k_bs_amsgrad(
+    float* __restrict__ theta, float* __restrict__ m, float* __restrict__ v, float* __restrict__ vhat, Geometry geo,
+    BlocksignWorkspace ws, AmsParams p) {
   const uint32_t* __restrict__ off = ws.offsets;
   const uint32_t wave = uniform_u32(threadIdx.x >> 6), lane = lane_id();
   const uint32_t d = geo.d;
-  // a wavefront takes a quarter of a chunk: four times as many wavefronts hide the latency of the per-round
-  // chain (state, sign words, scales -> update -> store) better than one wavefront per chunk does
   // (chunk, block and block end are scalars and come through scalar loads: a look-up through the vector path
   // would wait for the state loads issued just before it, a second round trip per round)
-  const uint32_t gw = uniform_u32(blockIdx.x * kWaves + wave);
-  const uint32_t c = gw / kBsSplit, part = gw % kBsSplit;
+  const uint32_t c = blockIdx.x, part = wave;
   if (c >= geo.num_chunks) return;
   uint32_t b = table_u32(ws.chunk_block, c);
-  for (int r = part * (kRounds / kBsSplit); r < static_cast<int>(part + 1) * (kRounds / kBsSplit); ++r) {
+  constexpr int kQ = kRounds / bs_server_split(NC);  // rounds of a wavefront's share of the chunk
+  const uint32_t q0 = c * kChunk + part * (kQ * 256);
+  if (q0 >= d) return;
+  while (table_u32(off, b + 1) <= q0) ++b;  // block of the share's first coordinate
+  if (q0 + kQ * 256 <= d && table_u32(off, b + 1) >= q0 + kQ * 256) {
+    // the whole share lies inside one block (all but a few per row in layouts worth the name)
+    const uint32_t j = q0 + lane * 4;
+    float sum[kQ][4];
+    if constexpr (kQ == 2) {  // the state of both rounds and the sign words are requested together
+      float4 th[kQ], mm[kQ], vv[kQ], vh[kQ];
+#pragma unroll
+      for (int r = 0; r < kQ; ++r) {
+        th[r] = load_state4<(NC > 0)>(theta + j + r * 256); mm[r] = load_state4<(NC > 1)>(m + j + r * 256);
+        vv[r] = load_state4<(NC > 2)>(v + j + r * 256); vh[r] = load_state4<(NC > 3)>(vhat + j + r * 256);
+      }
+      bs_share_sums<kQ>(sum, geo, ws, b, q0, lane);
+#pragma unroll
+      for (int r = 0; r < kQ; ++r) {
+        const uint32_t jr = j + r * 256;
+        ams_update(sum[r][0] / p.nf, th[r].x, mm[r].x, vv[r].x, vh[r].x, p);
+        ams_update(sum[r][1] / p.nf, th[r].y, mm[r].y, vv[r].y, vh[r].y, p);
+        ams_update(sum[r][2] / p.nf, th[r].z, mm[r].z, vv[r].z, vh[r].z, p);
+        ams_update(sum[r][3] / p.nf, th[r].w, mm[r].w, vv[r].w, vh[r].w, p);
+        store_state4<(NC > 0)>(theta + jr, th[r]);
+        store_state4<(NC > 1)>(m + jr, mm[r]);
+        store_state4<(NC > 2)>(v + jr, vv[r]);
+        store_state4<(NC > 3)>(vhat + jr, vh[r]);
+      }
+    } else {  // the first round's state with the sign words, each next round's while one is updated
+      float4 th = load_state4<(NC > 0)>(theta + j), mm = load_state4<(NC > 1)>(m + j);
+      float4 vv = load_state4<(NC > 2)>(v + j), vh = load_state4<(NC > 3)>(vhat + j);
+      bs_share_sums<kQ>(sum, geo, ws, b, q0, lane);
+#pragma unroll
+      for (int r = 0; r < kQ; ++r) {
+        __builtin_amdgcn_sched_barrier(0);  // (else all rounds' loads are moved up front: 82 registers)
+        const uint32_t jr = j + r * 256;
+        float4 th2 = th, mm2 = mm, vv2 = vv, vh2 = vh;
+        if (r + 1 < kQ) {
+          th2 = load_state4<(NC > 0)>(theta + jr + 256); mm2 = load_state4<(NC > 1)>(m + jr + 256);
+          vv2 = load_state4<(NC > 2)>(v + jr + 256); vh2 = load_state4<(NC > 3)>(vhat + jr + 256);
+        }
+        ams_update(sum[r][0] / p.nf, th.x, mm.x, vv.x, vh.x, p);
+        ams_update(sum[r][1] / p.nf, th.y, mm.y, vv.y, vh.y, p);
+        ams_update(sum[r][2] / p.nf, th.z, mm.z, vv.z, vh.z, p);
+        ams_update(sum[r][3] / p.nf, th.w, mm.w, vv.w, vh.w, p);
+        store_state4<(NC > 0)>(theta + jr, th);
+        store_state4<(NC > 1)>(m + jr, mm);
+        store_state4<(NC > 2)>(v + jr, vv);
+        store_state4<(NC > 3)>(vhat + jr, vh);
+        th = th2; mm = mm2; vv = vv2; vh = vh2;
+      }
+    }
+    return;
+  }
+  // a share that meets block ends or the row's end: round by round, the sign words and scales of a round
+  // requested after its state
+  for (int r = part * kQ; r < static_cast<int>(part + 1) * kQ; ++r) {
     const uint32_t j0 = c * kChunk + r * 256;
     if (j0 >= d) break;
     const uint32_t j = j0 + lane * 4;
@@ -755,7 +858,7 @@ hipError_t blocksign_step(const Geometry& geo, const BlocksignWorkspace& ws, con
 // The server's lines from the sign words and scales that sit in the workspace.
 hipError_t blocksign_server_step(const Geometry& geo, const BlocksignWorkspace& ws, const AmsParams& ap, float* theta,
                                  float* m, float* v, float* vhat, hipStream_t stream, Launcher* L) {
-  const dim3 grid((geo.num_chunks * kBsSplit + kWaves - 1) / kWaves), wg(kWG);
+  const dim3 grid(geo.num_chunks), wg(bs_server_split(ap.cached_arrays) * 64);  // a workgroup per chunk
 #define COMPAMS_BS_AMSGRAD(NC) k_bs_amsgrad<NC>
   COMPAMS_LAUNCH_BY_CACHED(ap.cached_arrays, L, kSlotBsAms, COMPAMS_BS_AMSGRAD, grid, wg, stream, theta, m, v, vhat, geo, ws,
                            ap);
