@@ -311,6 +311,25 @@ def test_blocksign_deferred_residual(n, d, offsets):
     p.close()
 
 
+@pytest.mark.parametrize("cached", [0, 3, 4])
+@pytest.mark.parametrize("n", [1, 8, 9, 17, 40])
+def test_blocksign_server_kernel_shares(n, cached):
+    """The server kernel gives a wavefront a share of a chunk's rounds (two with the whole state cached, else
+    four) and fetches each worker's sign words of the share once, eight or sixteen workers per trip; shares that
+    meet a block's or the row's end go round by round.  Worker counts around the trip sizes, block ends on and
+    off the shares' and the sign words' boundaries, a last chunk that is partial, both share sizes."""
+    d = 5 * 4096 + 777
+    rng = np.random.default_rng(n * 10 + cached)
+    off = np.array([0, 512, 1024 + 32, 4096, 2 * 4096 + 1, 3 * 4096 + 1024, 4 * 4096 + 2048 - 5, d], dtype=np.int64)
+    p = Pair(n, d, rng.standard_normal(d).astype(np.float32) * 0.1, B.BLOCKSIGN, block_offsets=off)
+    p.gpu.set_option(B.OPT_CACHED_ARRAYS, cached)
+    for t in range(4):
+        g = (rng.standard_normal((n, d)) * 10.0 ** rng.uniform(-3, 0, (n, 1))).astype(np.float32)
+        p.step(g, 1e-3, label=f"shares n={n} cached={cached} step {t}", with_e=(t == 3))
+    assert all(p.exact[s] for s in ("theta", "m", "v", "vhat"))
+    p.close()
+
+
 def test_blocksign_deferred_residual_with_a_block_that_is_not_finite():
     """An infinite entry makes its block's mean infinite; the residual of that block (x - sign(x) * inf) is then
     -inf, +inf or NaN, and the deferred form must produce the same pattern as the oracle's immediate one."""
